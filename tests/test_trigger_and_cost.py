@@ -1,0 +1,79 @@
+"""Trigger-scan oracle against a brute-force loop, and the work counters against Appendix A."""
+import numpy as np
+import pytest
+
+from paper_2504_12329_amd import cost, synth
+
+
+def _brute(tokens, lo, hi, kwset, delimset, window):
+    out = []
+    for p in range(lo, hi):
+        if tokens[p] in kwset and (window == 1 or (p >= 1 and tokens[p - 1] in delimset)):
+            out.append(p)
+    return out
+
+
+def test_modulo_bitmap():
+    bm = synth.modulo_bitmap(1024, 16)
+    ids = [i for i in range(1024) if (bm[i >> 5] >> (i & 31)) & 1]
+    assert ids == list(range(0, 1024, 16))
+    bm = synth.modulo_bitmap(151936, 97)
+    assert sum(bin(int(x)).count("1") for x in bm) == len(range(0, 151936, 97))
+
+
+@pytest.mark.parametrize("window", [1, 2])
+def test_trigger_scan_bruteforce(oracle_lib, window):
+    rng = np.random.default_rng(window)
+    V = 300
+    kw, dl = synth.modulo_bitmap(V, 7), synth.modulo_bitmap(V, 3)
+    kwset, dlset = set(range(0, V, 7)), set(range(0, V, 3))
+    for trial in range(30):
+        n = int(rng.integers(0, 200))
+        toks = rng.integers(0, V, n).astype(np.int32)
+        if n > 3:
+            toks[0] = 0                       # id 0 is divisible by everything; p = 0 has no predecessor
+            toks[rng.integers(0, n)] = 21
+        lo = int(rng.integers(0, n + 1))
+        hi = int(rng.integers(lo, n + 1))
+        want = _brute(toks, lo, hi, kwset, dlset, window)
+        cnt, pos = oracle_lib.trigger_scan(toks, lo, hi, V, kw, dl, window, cap=1000)
+        assert cnt == len(want) and pos.tolist() == want
+        cnt, pos = oracle_lib.trigger_scan(toks, lo, hi, V, kw, dl, window, cap=2)
+        assert cnt == len(want) and pos.tolist() == want[:2]
+
+
+def test_trigger_scan_hand_cases(oracle_lib):
+    V = 64
+    kw, dl = synth.modulo_bitmap(V, 5), synth.modulo_bitmap(V, 3)
+    toks = np.array([5, 3, 5, 10, 9, 4, 15, 6, 20], np.int32)
+    assert oracle_lib.trigger_scan(toks, 0, 9, V, kw, dl, 2, 9)[1].tolist() == [2, 8]
+    assert oracle_lib.trigger_scan(toks, 0, 9, V, kw, dl, 1, 9)[1].tolist() == [0, 2, 3, 6, 8]
+    assert oracle_lib.trigger_scan(toks, 2, 3, V, kw, dl, 2, 9)[1].tolist() == [2]   # looks back before lo
+    assert oracle_lib.trigger_scan(toks, 4, 4, V, kw, dl, 1, 9)[0] == 0              # empty range
+    with pytest.raises(ValueError):
+        oracle_lib.trigger_scan(np.array([64], np.int32), 0, 1, V, kw, dl, 1, 4)
+
+
+def test_cost_reduces_to_appendix_a_for_mha():
+    # Appendix A, per layer, h = n*d:  decode(s) = 8h^2 + 16h + 4sh + 4sn + 6hh' + 2h'
+    #                                  prefill(s) = 8sh^2 + 16sh + 4s^2h + 4s^2n + 6shh' + 2sh'
+    # the 16h, 4sn, 2h' terms are element-wise work; the counter keeps the matmul terms.
+    n, d, hp = 12, 128, 8960
+    h = n * d
+    cfg = dict(hidden=h, head_dim=d, n_q_heads=n, n_kv_heads=n, intermediate=hp, n_layers=1, vocab=1000)
+    for s in (1, 17, 4096):
+        assert cost.decode_flops_layer(cfg, s) == 8 * h * h + 4 * s * h + 6 * h * hp
+        assert cost.prefill_flops_layer(cfg, s, 0, causal=False) == 8 * s * h * h + 4 * s * s * h + 6 * s * h * hp
+    # a prefix pass of m tokens on a cache of kv0 costs what m decode steps at growing lengths cost
+    m, kv0 = 9, 100
+    assert cost.prefill_flops_layer(cfg, m, kv0) == sum(cost.decode_flops_layer(cfg, kv0 + i + 1) for i in range(m))
+
+
+def test_cost_bytes_of_the_paper_models():
+    c15 = synth.model_config("qwen1p5b", 4608)
+    c32 = synth.model_config("qwen32b", 8192)
+    assert cost.layer_matmul_params(c15) == 46792704
+    assert cost.layer_matmul_params(c32) == 487587840
+    assert abs(cost.weight_bytes(c15) / 1e9 - 3.087) < 1e-3
+    assert abs(cost.weight_bytes(c32) / 1e9 - 63.97) < 1e-2
+    assert cost.kv_bytes_per_position(c15) == 28672 and cost.kv_bytes_per_position(c32) == 262144
