@@ -1,0 +1,182 @@
+/*
+ * st.h -- C ABI of the Speculative Thinking hot path on one AMD MI355X (gfx950).
+ *
+ * Speculative Thinking (arXiv 2504.12329, Section 3) lets a small "speculative" model write
+ * most of a reasoning trace and hands fixed-length segments to a large "target" model at
+ * delimiter + keyword trigger points.  Both models condition on the same token sequence, so
+ * at every hand-over the model that was idle first runs a "prefix" pass over the tokens it
+ * has not seen (Section 4, Table 3, Eq. 1) and then decodes.  This library is that hot path
+ * for Qwen-2.5-architecture decoders: the catch-up prefill onto an existing KV cache, the
+ * single-token decode step, the integer trigger scan and the hand-over itself.
+ *
+ * Conventions
+ *  - Every call returns ST_OK (0) or a negative st_status; st_last_error() gives a
+ *    thread-local message for the last failure.  All arguments are validated before any
+ *    kernel is launched; a failed call leaves the model's KV length unchanged.
+ *  - The library never allocates device memory.  Weights, the KV cache and the workspace
+ *    are device buffers owned by the caller and must outlive the model; st_query_sizes
+ *    tells how large the KV cache and workspace must be.  Handles are host memory owned by
+ *    the library (st_model_create / st_model_destroy).
+ *  - All work of a model is enqueued on the hipStream_t given at creation (passed as
+ *    void*; NULL is the default stream).  A call that returns data through a host pointer
+ *    synchronises that stream before returning; with ST_OUT_DEVICE it does not.
+ *  - Weights are bf16, row-major [out_features][in_features].  The KV cache is bf16 laid
+ *    out [K|V][layer][kv_head][max_seq][head_dim].  Logits are fp32[vocab].
+ *  - One model handle must not be used from two threads at once.
+ */
+#ifndef ST_H
+#define ST_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    ST_OK = 0,
+    ST_EINVAL = -1, /* null pointer, bad configuration or flag combination */
+    ST_ENOMEM = -2, /* KV cache or workspace buffer smaller than st_query_sizes reports */
+    ST_ERANGE = -3, /* KV cache overflow, token id outside the vocabulary, bad range */
+    ST_EHIP = -4    /* the HIP runtime reported an error (message has its text) */
+} st_status;
+
+enum {
+    ST_TOKENS_DEVICE = 1u, /* `tokens` / `seq` points to device memory (default: host) */
+    ST_OUT_DEVICE = 2u,    /* output pointers are device memory; the call does not synchronise */
+    ST_TOKEN_CHAINED = 4u  /* st_decode_step: ignore `token`, feed the model's own last greedy token
+                              (kept on the device), so steps can be queued without a host round trip */
+};
+
+/* Shape of a Qwen-2.5-architecture decoder (pre-norm, RMSNorm, rotate-half RoPE, GQA, SwiGLU). */
+typedef struct {
+    int32_t n_layers, hidden, n_q_heads, n_kv_heads, head_dim, intermediate, vocab;
+    float rms_eps, rope_theta;
+    int32_t tie_embeddings; /* 1: lm_head is the embedding matrix */
+    int32_t qkv_bias;       /* 1: q/k/v projections have a bias (o and MLP never do) */
+    int32_t max_seq;        /* KV cache capacity in positions */
+    int32_t max_chunk;      /* most rows one prefill pass processes; st_prefill splits longer inputs */
+} st_config;
+/* Supported: head_dim 64 or 128; hidden, n_q_heads*head_dim, intermediate multiples of 8;
+ * hidden <= 8192; n_q_heads a multiple of n_kv_heads with n_q_heads/n_kv_heads <= 8. */
+
+/* Device pointers to bf16 weights.  The per-layer members are HOST arrays of n_layers device
+ * pointers (copied at creation).  Row order inside the fused matrices:
+ *   wqkv      [(n_q_heads + 2 n_kv_heads) * head_dim][hidden] : all q heads, then k heads, then v heads
+ *   bqkv      [(n_q_heads + 2 n_kv_heads) * head_dim]          (may be NULL when qkv_bias == 0)
+ *   wo        [hidden][n_q_heads * head_dim]
+ *   w_gate_up [2 * intermediate][hidden]                       : gate rows [0,I), up rows [I,2I)
+ *   w_down    [hidden][intermediate]
+ *   norm_attn, norm_mlp, final_norm [hidden]
+ *   embed, lm_head [vocab][hidden]                             (lm_head ignored when tied) */
+typedef struct {
+    const void *embed, *lm_head, *final_norm;
+    const void *const *wqkv, *const *bqkv, *const *wo, *const *w_gate_up, *const *w_down;
+    const void *const *norm_attn, *const *norm_mlp;
+} st_weights;
+
+typedef struct st_model st_model;
+
+/* Bytes the caller must provide for the KV cache and the workspace of a model of this shape.
+ * Either output may be NULL.  ST_EINVAL on an unsupported shape. */
+int st_query_sizes(const st_config *cfg, size_t *kv_bytes, size_t *workspace_bytes);
+
+/* Creates a model over caller-owned device buffers (both 256-byte aligned).  Initialises the
+ * workspace (RoPE table, counters) on `stream`; the KV length starts at 0.  The weights,
+ * `kv` and `workspace` are borrowed until st_model_destroy.  Two models must not share a
+ * workspace or KV buffer. */
+int st_model_create(const st_config *cfg, const st_weights *w, void *kv, size_t kv_bytes,
+                    void *workspace, size_t workspace_bytes, void *stream, st_model **out);
+void st_model_destroy(st_model *m);
+
+/* Number of positions whose keys/values are cached. */
+int st_kv_len(const st_model *m, int32_t *out);
+/* O(1) rollback to a shorter context (0 <= new_len <= kv_len), ST_ERANGE otherwise. */
+int st_kv_truncate(st_model *m, int32_t new_len);
+
+/* The prefix / catch-up pass (paper Section 4, "prefix" stage of Table 3 and Eq. 1): feeds
+ * tokens[0,n) at positions [kv_len, kv_len+n), appends their keys and values to the cache,
+ * kv_len += n.  logits (fp32[vocab]) and next_tok (the greedy arg-max, lowest index on ties)
+ * of the LAST fed position are written when the pointers are non-NULL.
+ * ST_ERANGE if n <= 0, kv_len + n > max_seq, or (host tokens only) an id is outside the vocabulary;
+ * ids in device memory that are out of range are clamped into the vocabulary by the kernel. */
+int st_prefill(st_model *m, const int32_t *tokens, int32_t n, float *logits, int32_t *next_tok,
+               uint32_t flags);
+
+/* One decode step (paper Section 4, "decode" stage): feeds one token at position kv_len,
+ * kv_len += 1, same outputs as st_prefill. */
+int st_decode_step(st_model *m, int32_t token, float *logits, int32_t *next_tok, uint32_t flags);
+
+/* n chained greedy decode steps: feeds first_token (or the model's own last greedy token when
+ * ST_TOKEN_CHAINED is set), then each step's arg-max, writing the n produced tokens to
+ * out_tokens (host, or device with ST_OUT_DEVICE).  kv_len += n.  Nothing returns to the
+ * host between steps. */
+int st_decode_greedy(st_model *m, int32_t first_token, int32_t n, int32_t *out_tokens, uint32_t flags);
+
+/* Token-level form of the takeover trigger (Section 3 (1); keyword sets of Appendix C become
+ * sets of token ids): a position p fires when tokens[p] is in the keyword set and, for
+ * window == 2, p >= 1 and tokens[p-1] is in the delimiter set.  Sets are bitmaps over the
+ * vocabulary (bit id&31 of 32-bit word id>>5) in device memory. */
+typedef struct {
+    const uint32_t *kw_bitmap, *delim_bitmap; /* device; delim may be NULL when window == 1 */
+    int32_t window;                           /* 1 or 2 */
+    int32_t vocab;
+} st_trigger_rule;
+
+/* Scans tokens[lo,hi) (device memory, int32): writes the first min(count, cap) firing
+ * positions in ascending order to positions[] and the total count to *n_found.  positions and
+ * n_found are host pointers (the call synchronises `stream`) unless ST_OUT_DEVICE is set;
+ * `scratch` is cap+1 int32 of device memory used for the result in the host-output case (may be
+ * NULL with ST_OUT_DEVICE).  Ids outside the vocabulary never fire.  ST_ERANGE if lo < 0 or hi < lo. */
+int st_trigger_scan(const st_trigger_rule *rule, const int32_t *tokens, int32_t lo, int32_t hi,
+                    int32_t *positions, int32_t cap, int32_t *n_found, int32_t *scratch,
+                    void *stream, uint32_t flags);
+
+/* Half-open absolute position spans touched by one hand-over. */
+typedef struct {
+    int32_t large_prefill_lo, large_prefill_hi; /* tokens the target caught up on */
+    int32_t large_decode_lo, large_decode_hi;   /* positions the target wrote */
+    int32_t small_prefill_lo, small_prefill_hi; /* tokens the speculative model caught up on (empty if the
+                                                   budget ended inside the segment) */
+} st_spans;
+
+/* One takeover (Section 3 (1)): seq[0,*T) is the shared sequence in HOST memory (capacity at
+ * least *T + min(n_large, budget)); seq[*T-1] is the trigger token, already written but not yet
+ * fed to `small`.  The target catches up on seq[kv_len(large), *T), greedily writes
+ * min(n_large, budget) tokens to seq (feeding itself all but the last), then, unless the
+ * budget ended the segment early (budget <= n_large), the speculative model catches up on
+ * seq[kv_len(small), *T').  On return *T is the new length; small_next_tok (and small_logits,
+ * fp32[vocab], may be NULL) hold the speculative model's prediction for position *T when a
+ * catch-up ran.  All pointers are host memory. */
+int st_handoff(st_model *small, st_model *large, int32_t *seq, int32_t *T, int32_t n_large,
+               int32_t budget, float *small_logits, int32_t *small_next_tok, st_spans *spans,
+               uint32_t flags);
+
+/* Statistics of one st_generate run. */
+typedef struct {
+    int32_t n_out;        /* output tokens written */
+    int32_t n_handoffs;   /* takeovers */
+    int32_t n_large;      /* tokens written by the target (modify ratio = n_large / n_out) */
+    int32_t n_spans;      /* entries written to `spans` */
+    double ms_small_decode, ms_large_decode, ms_small_prefill, ms_large_prefill; /* host wall clock */
+} st_gen_stats;
+
+/* The whole loop of Section 3 (1) with append semantics: both models prefill prompt[0,P);
+ * the speculative model decodes greedily; whenever the rule fires on a token IT emitted the
+ * target takes over for n_seg tokens (st_handoff); stops after n_out output tokens.
+ * forced_period > 0 replaces the rule by "every forced_period-th speculative token fires"
+ * (used to reproduce a given modify ratio with random weights).
+ * seq (host, capacity P + n_out) receives prompt + outputs; src (host, n_out bytes, may be NULL)
+ * receives 0 for speculative / 1 for target per output token; spans (host, capacity span_cap,
+ * may be NULL) one entry per takeover. */
+int st_generate(st_model *small, st_model *large, const st_trigger_rule *rule, int32_t forced_period,
+                const int32_t *prompt, int32_t P, int32_t n_out, int32_t n_seg,
+                int32_t *seq, uint8_t *src, st_spans *spans, int32_t span_cap, st_gen_stats *stats);
+
+const char *st_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -1,0 +1,233 @@
+"""Thin ctypes binding over libst.so: same names as include/st.h, argument marshalling only.
+
+PyTorch supplies device memory (weights, KV cache, workspace) and the stream handle; every
+step of the path runs in the library's HIP kernels.  Loading fails loudly when the library has
+not been built -- there is no fallback.
+"""
+import ctypes as C
+import os
+
+import numpy as np
+import torch
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libst.so")
+
+ST_OK, ST_EINVAL, ST_ENOMEM, ST_ERANGE, ST_EHIP = 0, -1, -2, -3, -4
+ST_TOKENS_DEVICE, ST_OUT_DEVICE, ST_TOKEN_CHAINED = 1, 2, 4
+
+EXPORTS = ("st_query_sizes", "st_model_create", "st_model_destroy", "st_kv_len", "st_kv_truncate", "st_prefill",
+           "st_decode_step", "st_decode_greedy", "st_trigger_scan", "st_handoff", "st_generate", "st_last_error")
+
+
+class StError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__(f"st error {code}: {msg}")
+        self.code = code
+
+
+class st_config(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in
+                ("n_layers", "hidden", "n_q_heads", "n_kv_heads", "head_dim", "intermediate", "vocab")] + \
+               [("rms_eps", C.c_float), ("rope_theta", C.c_float)] + \
+               [(n, C.c_int32) for n in ("tie_embeddings", "qkv_bias", "max_seq", "max_chunk")]
+
+
+_vpp = C.POINTER(C.c_void_p)
+
+
+class st_weights(C.Structure):
+    _fields_ = [("embed", C.c_void_p), ("lm_head", C.c_void_p), ("final_norm", C.c_void_p)] + \
+               [(n, _vpp) for n in ("wqkv", "bqkv", "wo", "w_gate_up", "w_down", "norm_attn", "norm_mlp")]
+
+
+class st_trigger_rule(C.Structure):
+    _fields_ = [("kw_bitmap", C.c_void_p), ("delim_bitmap", C.c_void_p), ("window", C.c_int32), ("vocab", C.c_int32)]
+
+
+class st_spans(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("large_prefill_lo", "large_prefill_hi", "large_decode_lo", "large_decode_hi",
+                                         "small_prefill_lo", "small_prefill_hi")]
+
+    def as_dict(self):
+        return {n: getattr(self, n) for n, _ in self._fields_}
+
+
+class st_gen_stats(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("n_out", "n_handoffs", "n_large", "n_spans")] + \
+               [(n, C.c_double) for n in ("ms_small_decode", "ms_large_decode", "ms_small_prefill", "ms_large_prefill")]
+
+
+_lib = None
+
+
+def lib():
+    """The loaded library; raises if it has not been built (python -m paper_2504_12329_amd.build)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2504_12329_amd.build`")
+        L = C.CDLL(LIB_PATH)
+        i32p, f32p = C.POINTER(C.c_int32), C.POINTER(C.c_float)
+        L.st_last_error.restype = C.c_char_p
+        L.st_query_sizes.argtypes = [C.POINTER(st_config), C.POINTER(C.c_size_t), C.POINTER(C.c_size_t)]
+        L.st_model_create.argtypes = [C.POINTER(st_config), C.POINTER(st_weights), C.c_void_p, C.c_size_t,
+                                      C.c_void_p, C.c_size_t, C.c_void_p, C.POINTER(C.c_void_p)]
+        L.st_model_destroy.argtypes = [C.c_void_p]
+        L.st_model_destroy.restype = None
+        L.st_kv_len.argtypes = [C.c_void_p, i32p]
+        L.st_kv_truncate.argtypes = [C.c_void_p, C.c_int32]
+        L.st_prefill.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_uint32]
+        L.st_decode_step.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_uint32]
+        L.st_decode_greedy.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_uint32]
+        L.st_trigger_scan.argtypes = [C.POINTER(st_trigger_rule), C.c_void_p, C.c_int32, C.c_int32, C.c_void_p,
+                                      C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32]
+        L.st_handoff.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, i32p, C.c_int32, C.c_int32, C.c_void_p,
+                                 i32p, C.POINTER(st_spans), C.c_uint32]
+        L.st_generate.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(st_trigger_rule), C.c_int32, C.c_void_p,
+                                  C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.POINTER(st_spans),
+                                  C.c_int32, C.POINTER(st_gen_stats)]
+        _lib = L
+    return _lib
+
+
+def _check(rc):
+    if rc != ST_OK:
+        raise StError(rc, lib().st_last_error().decode())
+
+
+def make_config(cfg):
+    return st_config(*(cfg[n] for n, _ in st_config._fields_))
+
+
+def st_query_sizes(cfg):
+    kv, ws = C.c_size_t(), C.c_size_t()
+    _check(lib().st_query_sizes(C.byref(make_config(cfg)), C.byref(kv), C.byref(ws)))
+    return kv.value, ws.value
+
+
+def _np_ptr(a):
+    return a.ctypes.data_as(C.c_void_p)
+
+
+class TriggerRule:
+    """Device bitmaps of the keyword and delimiter token sets."""
+
+    def __init__(self, vocab, kw_bitmap, delim_bitmap=None, window=1, device="cuda"):
+        self.kw = torch.from_numpy(np.ascontiguousarray(kw_bitmap).view(np.int32)).to(device)
+        self.delim = None if delim_bitmap is None else \
+            torch.from_numpy(np.ascontiguousarray(delim_bitmap).view(np.int32)).to(device)
+        self.c = st_trigger_rule(self.kw.data_ptr(), 0 if self.delim is None else self.delim.data_ptr(), window, vocab)
+
+
+def st_trigger_scan(rule, tokens_dev, lo, hi, cap, stream=None):
+    """tokens_dev: int32 CUDA tensor.  Returns (total_count, positions ndarray)."""
+    scratch = torch.empty(cap + 1, dtype=torch.int32, device=tokens_dev.device)
+    pos = np.empty(max(cap, 1), dtype=np.int32)
+    n = C.c_int32()
+    s = torch.cuda.current_stream().cuda_stream if stream is None else stream
+    _check(lib().st_trigger_scan(C.byref(rule.c), tokens_dev.data_ptr(), lo, hi, _np_ptr(pos), cap, C.byref(n),
+                                 scratch.data_ptr(), s, 0))
+    return n.value, pos[:min(n.value, cap)].copy()
+
+
+class Model:
+    """st_model over torch-owned device buffers.  `weights` is the dict made by synth.make_weights on the GPU."""
+
+    def __init__(self, cfg, weights, stream=None):
+        self.cfg = dict(cfg)
+        self.weights = weights                      # keeps the tensors alive
+        dev = weights["embed"].device
+        if dev.type != "cuda":
+            raise RuntimeError("weights must live on the GPU")
+        kv_bytes, ws_bytes = st_query_sizes(cfg)
+        self.kv = torch.empty(kv_bytes, dtype=torch.uint8, device=dev)
+        self.ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+        L = cfg["n_layers"]
+        w = st_weights()
+        w.embed = weights["embed"].data_ptr()
+        w.lm_head = 0 if weights.get("lm_head") is None else weights["lm_head"].data_ptr()
+        w.final_norm = weights["final_norm"].data_ptr()
+        self._arrays = []
+        for name in ("wqkv", "bqkv", "wo", "w_gate_up", "w_down", "norm_attn", "norm_mlp"):
+            arr = (C.c_void_p * L)(*[lw[name].data_ptr() for lw in weights["layers"]])
+            self._arrays.append(arr)
+            setattr(w, name, C.cast(arr, _vpp))
+        self.stream = torch.cuda.current_stream(dev).cuda_stream if stream is None else stream
+        h = C.c_void_p()
+        _check(lib().st_model_create(C.byref(make_config(cfg)), C.byref(w), self.kv.data_ptr(), kv_bytes,
+                                     self.ws.data_ptr(), ws_bytes, self.stream, C.byref(h)))
+        self._h = h
+
+    def close(self):
+        if getattr(self, "_h", None):
+            lib().st_model_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        self.close()
+
+    @property
+    def kv_len(self):
+        n = C.c_int32()
+        _check(lib().st_kv_len(self._h, C.byref(n)))
+        return n.value
+
+    def truncate(self, n):
+        _check(lib().st_kv_truncate(self._h, n))
+
+    def prefill(self, tokens, want_logits=True):
+        """tokens: host int array.  Returns (logits ndarray or None, greedy token)."""
+        t = np.ascontiguousarray(tokens, dtype=np.int32)
+        lg = np.empty(self.cfg["vocab"], dtype=np.float32) if want_logits else None
+        nt = C.c_int32()
+        _check(lib().st_prefill(self._h, _np_ptr(t), t.size, _np_ptr(lg) if want_logits else None,
+                                C.addressof(nt), 0))
+        return lg, nt.value
+
+    def prefill_device(self, tokens_dev):
+        """tokens_dev: int32 CUDA tensor; enqueues only (no outputs, no synchronisation)."""
+        _check(lib().st_prefill(self._h, tokens_dev.data_ptr(), tokens_dev.numel(), None, None,
+                                ST_TOKENS_DEVICE | ST_OUT_DEVICE))
+
+    def decode_step(self, token, want_logits=True):
+        lg = np.empty(self.cfg["vocab"], dtype=np.float32) if want_logits else None
+        nt = C.c_int32()
+        _check(lib().st_decode_step(self._h, int(token), _np_ptr(lg) if want_logits else None, C.addressof(nt), 0))
+        return lg, nt.value
+
+    def decode_greedy(self, first_token, n, chained=False, out_dev=None):
+        """n chained greedy steps.  Returns the tokens (host) unless out_dev (int32 CUDA tensor) is given."""
+        flags = ST_TOKEN_CHAINED if chained else 0
+        if out_dev is not None:
+            _check(lib().st_decode_greedy(self._h, int(first_token), n, out_dev.data_ptr(), flags | ST_OUT_DEVICE))
+            return None
+        out = np.empty(n, dtype=np.int32)
+        _check(lib().st_decode_greedy(self._h, int(first_token), n, _np_ptr(out), flags))
+        return out
+
+
+def st_handoff(small, large, seq, T, n_large, budget, want_logits=False):
+    """seq: host int32 ndarray with room for the segment.  Returns (new_T, small_next_tok, spans dict, logits)."""
+    t = C.c_int32(T)
+    nt = C.c_int32(-1)
+    sp = st_spans()
+    lg = np.empty(small.cfg["vocab"], dtype=np.float32) if want_logits else None
+    _check(lib().st_handoff(small._h, large._h, _np_ptr(seq), C.byref(t), n_large, budget,
+                            _np_ptr(lg) if want_logits else None, C.byref(nt), C.byref(sp), 0))
+    return t.value, nt.value, sp.as_dict(), lg
+
+
+def st_generate(small, large, rule, prompt, n_out, n_seg, forced_period=0, span_cap=4096):
+    """Runs the whole loop.  Returns dict(seq, src, spans, stats)."""
+    p = np.ascontiguousarray(prompt, dtype=np.int32)
+    seq = np.zeros(p.size + n_out, dtype=np.int32)
+    src = np.zeros(max(n_out, 1), dtype=np.uint8)
+    spans = (st_spans * max(span_cap, 1))()
+    stats = st_gen_stats()
+    _check(lib().st_generate(small._h, large._h, C.byref(rule.c) if rule is not None else None, forced_period,
+                             _np_ptr(p), p.size, n_out, n_seg, _np_ptr(seq), _np_ptr(src),
+                             C.cast(spans, C.POINTER(st_spans)), span_cap, C.byref(stats)))
+    return dict(seq=seq[:p.size + stats.n_out], src=src[:stats.n_out],
+                spans=[spans[i].as_dict() for i in range(stats.n_spans)],
+                stats={n: getattr(stats, n) for n, _ in st_gen_stats._fields_})

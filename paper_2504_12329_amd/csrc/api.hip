@@ -1,0 +1,438 @@
+// The C ABI: argument validation, model records, workspace carving, and the host-side
+// orchestration of prefill, decode, hand-over (paper Section 3 (1)) and the whole loop.
+#include <chrono>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+#include "st_device.h"
+#include "st_internal.h"
+
+namespace st {
+
+static thread_local char g_err[512] = "";
+
+static int fail(int code, const char *fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+#define ST_HIP(expr)                                                                          \
+    do {                                                                                      \
+        hipError_t e_ = (expr);                                                               \
+        if (e_ != hipSuccess) return fail(ST_EHIP, "%s: %s", #expr, hipGetErrorString(e_));   \
+    } while (0)
+
+static int check_launch(const char *what) {
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(ST_EHIP, "%s: %s", what, hipGetErrorString(e));
+    return ST_OK;
+}
+
+static int validate_config(const st_config *c) {
+    if (!c) return fail(ST_EINVAL, "config is NULL");
+    if (c->n_layers <= 0 || c->hidden <= 0 || c->n_q_heads <= 0 || c->n_kv_heads <= 0 || c->intermediate <= 0 ||
+        c->vocab <= 0 || c->max_seq <= 0 || c->max_chunk <= 0)
+        return fail(ST_EINVAL, "config has a non-positive dimension");
+    if (c->head_dim != 64 && c->head_dim != 128) return fail(ST_EINVAL, "head_dim must be 64 or 128");
+    if (c->hidden % 8 || c->intermediate % 8) return fail(ST_EINVAL, "hidden and intermediate must be multiples of 8");
+    if (c->hidden > 8192) return fail(ST_EINVAL, "hidden must be <= 8192");
+    if (c->n_q_heads % c->n_kv_heads) return fail(ST_EINVAL, "n_q_heads must be a multiple of n_kv_heads");
+    if (c->n_q_heads / c->n_kv_heads > 8) return fail(ST_EINVAL, "at most 8 query heads per kv head");
+    if (!(c->rms_eps >= 0.f) || !(c->rope_theta > 0.f)) return fail(ST_EINVAL, "bad rms_eps or rope_theta");
+    if ((c->tie_embeddings != 0 && c->tie_embeddings != 1) || (c->qkv_bias != 0 && c->qkv_bias != 1))
+        return fail(ST_EINVAL, "tie_embeddings and qkv_bias must be 0 or 1");
+    return ST_OK;
+}
+
+static size_t kv_bytes_of(const st_config &c) {
+    return (size_t)2 * c.n_layers * c.n_kv_heads * (size_t)c.max_seq * c.head_dim * sizeof(bf16_t);
+}
+
+void carve_workspace(const st_config &c, char *base, Workspace *ws) {
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        char *p = base ? base + off : nullptr;
+        off += (bytes + 255) & ~(size_t)255;
+        return p;
+    };
+    const size_t mc = c.max_chunk, h = c.hidden, qd = (size_t)c.n_q_heads * c.head_dim;
+    const size_t qkv = (size_t)(c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim, I = c.intermediate;
+    ws->state = (int32_t *)take(sizeof(int32_t) * kStateInts);
+    ws->counters = (int32_t *)take(sizeof(int32_t) * c.n_kv_heads);
+    ws->rope = (float2 *)take(sizeof(float2) * (size_t)c.max_seq * (c.head_dim / 2));
+    ws->tokens = (int32_t *)take(sizeof(int32_t) * mc);
+    ws->out_tokens = (int32_t *)take(sizeof(int32_t) * (size_t)c.max_seq);
+    ws->x = (float *)take(sizeof(float) * mc * h);
+    ws->xn = (bf16_t *)take(sizeof(bf16_t) * mc * h);
+    ws->qkv = (float *)take(sizeof(float) * mc * qkv);
+    ws->qb = (bf16_t *)take(sizeof(bf16_t) * mc * qd);
+    ws->attn = (bf16_t *)take(sizeof(bf16_t) * mc * qd);
+    ws->act = (bf16_t *)take(sizeof(bf16_t) * mc * I);
+    ws->q1 = (float *)take(sizeof(float) * qd);
+    ws->o1 = (float *)take(sizeof(float) * qd);
+    ws->a1 = (float *)take(sizeof(float) * I);
+    ws->part_ml = (float *)take(sizeof(float) * c.n_q_heads * kAttnSplits * 2);
+    ws->part_acc = (float *)take(sizeof(float) * c.n_q_heads * kAttnSplits * c.head_dim);
+    ws->logits = (float *)take(sizeof(float) * (size_t)c.vocab);
+    ws->amax_val = (float *)take(sizeof(float) * kLmBlocks);
+    ws->amax_idx = (int32_t *)take(sizeof(int32_t) * kLmBlocks);
+    ws->bytes = off;
+}
+
+// Enqueues the catch-up pass over `n` tokens (host or device ids); the last row's logits and greedy
+// token (with the trigger predicate when a rule is given) end up in ws.logits / state.
+static int prefill_impl(Model *m, const int32_t *tokens, int32_t n, bool tokens_dev, const st_trigger_rule *rule) {
+    const st_config &c = m->c;
+    if (!tokens) return fail(ST_EINVAL, "tokens is NULL");
+    if (n <= 0) return fail(ST_ERANGE, "n must be positive (got %d)", n);
+    if ((int64_t)m->kv_len + n > c.max_seq)
+        return fail(ST_ERANGE, "KV overflow: kv_len %d + n %d > max_seq %d", m->kv_len, n, c.max_seq);
+    if (!tokens_dev)
+        for (int32_t i = 0; i < n; ++i)
+            if (tokens[i] < 0 || tokens[i] >= c.vocab)
+                return fail(ST_ERANGE, "token id %d at index %d is outside the vocabulary [0,%d)", tokens[i], i, c.vocab);
+    for (int32_t done = 0; done < n; done += c.max_chunk) {
+        int32_t cn = n - done < c.max_chunk ? n - done : c.max_chunk;
+        ST_HIP(hipMemcpyAsync(m->ws.tokens, tokens + done, sizeof(int32_t) * cn,
+                              tokens_dev ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice, m->stream));
+        bool last_chunk = done + cn == n;
+        launch_prefill_layers(*m, m->kv_len + done, cn);
+        if (last_chunk) launch_head(*m, m->ws.x + (size_t)(cn - 1) * c.hidden, rule, cn, nullptr);
+        else launch_set_state(*m, kPos, m->kv_len + done + cn);
+        if (int rc = check_launch("prefill")) return rc;
+    }
+    m->kv_len += n;
+    return ST_OK;
+}
+
+static int decode_impl(Model *m, const st_trigger_rule *rule, int32_t *out_seq_dev) {
+    if (m->kv_len + 1 > m->c.max_seq)
+        return fail(ST_ERANGE, "KV overflow: kv_len %d + 1 > max_seq %d", m->kv_len, m->c.max_seq);
+    launch_decode_step(*m, rule, out_seq_dev);
+    if (int rc = check_launch("decode step")) return rc;
+    m->kv_len += 1;
+    return ST_OK;
+}
+
+// Copies logits / greedy token out; host destinations synchronise the stream.
+static int deliver(Model *m, float *logits, int32_t *next_tok, bool out_dev) {
+    hipMemcpyKind kind = out_dev ? hipMemcpyDeviceToDevice : hipMemcpyDeviceToHost;
+    if (logits) ST_HIP(hipMemcpyAsync(logits, m->ws.logits, sizeof(float) * (size_t)m->c.vocab, kind, m->stream));
+    if (next_tok) ST_HIP(hipMemcpyAsync(next_tok, m->ws.state + kTok, sizeof(int32_t), kind, m->stream));
+    if (!out_dev) ST_HIP(hipStreamSynchronize(m->stream));
+    return ST_OK;
+}
+
+// Reads (greedy token, fired) back to the host.
+static int fetch_token(Model *m, int32_t *tok, int32_t *fired) {
+    int32_t two[2];
+    ST_HIP(hipMemcpyAsync(two, m->ws.state + kTok, sizeof(two), hipMemcpyDeviceToHost, m->stream));
+    ST_HIP(hipStreamSynchronize(m->stream));
+    *tok = two[0];
+    if (fired) *fired = two[1];
+    return ST_OK;
+}
+
+static int handoff_impl(Model *small, Model *large, int32_t *seq, int32_t *T, int32_t n_large, int32_t budget,
+                        const st_trigger_rule *rule, float *small_logits, int32_t *small_next, int32_t *small_fired,
+                        st_spans *spans, double *ms_large_prefill, double *ms_large_decode, double *ms_small_prefill) {
+    using clk = std::chrono::steady_clock;
+    auto ms = [](clk::time_point a, clk::time_point b) { return std::chrono::duration<double, std::milli>(b - a).count(); };
+    int32_t t0 = *T;
+    if (t0 <= 0) return fail(ST_ERANGE, "sequence is empty");
+    if (n_large <= 0 || budget <= 0) return fail(ST_ERANGE, "n_large and budget must be positive");
+    if (large->kv_len >= t0 || small->kv_len >= t0)
+        return fail(ST_ERANGE, "a model has already been fed the whole sequence (kv_len %d / %d, T %d)", small->kv_len,
+                    large->kv_len, t0);
+    int32_t n = n_large < budget ? n_large : budget;
+    if ((int64_t)t0 + n - 1 > large->c.max_seq || (int64_t)t0 + n > small->c.max_seq)
+        return fail(ST_ERANGE, "KV overflow during hand-over (T %d, segment %d)", t0, n);
+    st_spans sp = {large->kv_len, t0, t0, t0, small->kv_len, small->kv_len};
+    auto a = clk::now();
+    if (int rc = prefill_impl(large, seq + large->kv_len, t0 - large->kv_len, false, nullptr)) return rc;
+    int32_t tok;
+    if (int rc = fetch_token(large, &tok, nullptr)) return rc;
+    auto b = clk::now();
+    int32_t t = t0;
+    for (int32_t j = 0; j < n; ++j) {
+        seq[t++] = tok;
+        if (j < n - 1) {  // the segment's last token is not fed to the target yet
+            if (int rc = decode_impl(large, nullptr, nullptr)) return rc;   // feeds state[kTok] == tok
+            if (int rc = fetch_token(large, &tok, nullptr)) return rc;
+        }
+    }
+    auto c = clk::now();
+    sp.large_decode_hi = t;
+    bool ended = budget <= n_large;
+    if (!ended) {
+        sp.small_prefill_hi = t;
+        if (int rc = prefill_impl(small, seq + small->kv_len, t - small->kv_len, false, rule)) return rc;
+        int32_t stok, sfired;
+        if (small_logits)
+            ST_HIP(hipMemcpyAsync(small_logits, small->ws.logits, sizeof(float) * (size_t)small->c.vocab,
+                                  hipMemcpyDeviceToHost, small->stream));
+        if (int rc = fetch_token(small, &stok, &sfired)) return rc;
+        if (small_next) *small_next = stok;
+        if (small_fired) *small_fired = sfired;
+    }
+    auto d = clk::now();
+    *T = t;
+    if (spans) *spans = sp;
+    if (ms_large_prefill) *ms_large_prefill += ms(a, b);
+    if (ms_large_decode) *ms_large_decode += ms(b, c);
+    if (ms_small_prefill) *ms_small_prefill += ms(c, d);
+    return ST_OK;
+}
+
+}  // namespace st
+
+using namespace st;
+
+extern "C" {
+
+const char *st_last_error(void) { return g_err; }
+
+int st_query_sizes(const st_config *cfg, size_t *kv_bytes, size_t *workspace_bytes) {
+    if (int rc = validate_config(cfg)) return rc;
+    if (kv_bytes) *kv_bytes = kv_bytes_of(*cfg);
+    if (workspace_bytes) {
+        Workspace ws;
+        carve_workspace(*cfg, nullptr, &ws);
+        *workspace_bytes = ws.bytes;
+    }
+    return ST_OK;
+}
+
+int st_model_create(const st_config *cfg, const st_weights *w, void *kv, size_t kv_bytes, void *workspace,
+                    size_t workspace_bytes, void *stream, st_model **out) {
+    if (!out) return fail(ST_EINVAL, "out is NULL");
+    *out = nullptr;
+    if (int rc = validate_config(cfg)) return rc;
+    if (!w) return fail(ST_EINVAL, "weights is NULL");
+    if (!w->embed || !w->final_norm || (!cfg->tie_embeddings && !w->lm_head))
+        return fail(ST_EINVAL, "embed, final_norm or lm_head is NULL");
+    if (!w->wqkv || !w->wo || !w->w_gate_up || !w->w_down || !w->norm_attn || !w->norm_mlp ||
+        (cfg->qkv_bias && !w->bqkv))
+        return fail(ST_EINVAL, "a per-layer weight array is NULL");
+    for (int l = 0; l < cfg->n_layers; ++l)
+        if (!w->wqkv[l] || !w->wo[l] || !w->w_gate_up[l] || !w->w_down[l] || !w->norm_attn[l] || !w->norm_mlp[l] ||
+            (cfg->qkv_bias && !w->bqkv[l]))
+            return fail(ST_EINVAL, "a weight pointer of layer %d is NULL", l);
+    if (!kv || !workspace) return fail(ST_EINVAL, "kv or workspace is NULL");
+    if (((uintptr_t)kv & 255) || ((uintptr_t)workspace & 255))
+        return fail(ST_EINVAL, "kv and workspace must be 256-byte aligned");
+    Workspace sized;
+    carve_workspace(*cfg, nullptr, &sized);
+    if (kv_bytes < kv_bytes_of(*cfg))
+        return fail(ST_ENOMEM, "kv buffer has %zu bytes, %zu needed", kv_bytes, kv_bytes_of(*cfg));
+    if (workspace_bytes < sized.bytes)
+        return fail(ST_ENOMEM, "workspace has %zu bytes, %zu needed", workspace_bytes, sized.bytes);
+
+    Model *m = new (std::nothrow) Model();
+    if (!m) return fail(ST_ENOMEM, "out of host memory");
+    m->c = *cfg;
+    m->qkv_dim = (cfg->n_q_heads + 2 * cfg->n_kv_heads) * cfg->head_dim;
+    auto cp = [&](std::vector<const bf16_t *> &dst, const void *const *src) {
+        dst.resize(cfg->n_layers);
+        for (int l = 0; l < cfg->n_layers; ++l) dst[l] = src ? (const bf16_t *)src[l] : nullptr;
+    };
+    cp(m->wqkv, w->wqkv);
+    cp(m->bqkv, cfg->qkv_bias ? w->bqkv : nullptr);
+    cp(m->wo, w->wo);
+    cp(m->wgu, w->w_gate_up);
+    cp(m->wdown, w->w_down);
+    cp(m->norm_attn, w->norm_attn);
+    cp(m->norm_mlp, w->norm_mlp);
+    m->embed = (const bf16_t *)w->embed;
+    m->lm_head = cfg->tie_embeddings ? m->embed : (const bf16_t *)w->lm_head;
+    m->final_norm = (const bf16_t *)w->final_norm;
+    m->kcache = (bf16_t *)kv;
+    m->vcache = m->kcache + (size_t)cfg->n_layers * cfg->n_kv_heads * (size_t)cfg->max_seq * cfg->head_dim;
+    carve_workspace(*cfg, (char *)workspace, &m->ws);
+    m->stream = (hipStream_t)stream;
+    m->kv_len = 0;
+    launch_init(*m);
+    if (int rc = check_launch("workspace initialisation")) {
+        delete m;
+        return rc;
+    }
+    *out = reinterpret_cast<st_model *>(m);
+    return ST_OK;
+}
+
+void st_model_destroy(st_model *h) { delete reinterpret_cast<Model *>(h); }
+
+int st_kv_len(const st_model *h, int32_t *out) {
+    if (!h || !out) return fail(ST_EINVAL, "model or out is NULL");
+    *out = reinterpret_cast<const Model *>(h)->kv_len;
+    return ST_OK;
+}
+
+int st_kv_truncate(st_model *h, int32_t new_len) {
+    if (!h) return fail(ST_EINVAL, "model is NULL");
+    Model *m = reinterpret_cast<Model *>(h);
+    if (new_len < 0 || new_len > m->kv_len)
+        return fail(ST_ERANGE, "new_len %d outside [0, %d]", new_len, m->kv_len);
+    launch_set_state(*m, kPos, new_len);
+    if (int rc = check_launch("truncate")) return rc;
+    m->kv_len = new_len;
+    return ST_OK;
+}
+
+static int check_flags(uint32_t flags, uint32_t allowed) {
+    if (flags & ~allowed) return fail(ST_EINVAL, "unsupported flag bits 0x%x", flags & ~allowed);
+    return ST_OK;
+}
+
+int st_prefill(st_model *h, const int32_t *tokens, int32_t n, float *logits, int32_t *next_tok, uint32_t flags) {
+    if (!h) return fail(ST_EINVAL, "model is NULL");
+    if (int rc = check_flags(flags, ST_TOKENS_DEVICE | ST_OUT_DEVICE)) return rc;
+    Model *m = reinterpret_cast<Model *>(h);
+    if (int rc = prefill_impl(m, tokens, n, flags & ST_TOKENS_DEVICE, nullptr)) return rc;
+    return deliver(m, logits, next_tok, flags & ST_OUT_DEVICE);
+}
+
+int st_decode_step(st_model *h, int32_t token, float *logits, int32_t *next_tok, uint32_t flags) {
+    if (!h) return fail(ST_EINVAL, "model is NULL");
+    if (int rc = check_flags(flags, ST_OUT_DEVICE | ST_TOKEN_CHAINED)) return rc;
+    Model *m = reinterpret_cast<Model *>(h);
+    if (!(flags & ST_TOKEN_CHAINED)) {
+        if (token < 0 || token >= m->c.vocab)
+            return fail(ST_ERANGE, "token id %d is outside the vocabulary [0,%d)", token, m->c.vocab);
+        if (m->kv_len + 1 > m->c.max_seq)
+            return fail(ST_ERANGE, "KV overflow: kv_len %d + 1 > max_seq %d", m->kv_len, m->c.max_seq);
+        launch_set_token(*m, token);
+    }
+    if (int rc = decode_impl(m, nullptr, nullptr)) return rc;
+    return deliver(m, logits, next_tok, flags & ST_OUT_DEVICE);
+}
+
+int st_decode_greedy(st_model *h, int32_t first_token, int32_t n, int32_t *out_tokens, uint32_t flags) {
+    if (!h) return fail(ST_EINVAL, "model is NULL");
+    if (int rc = check_flags(flags, ST_OUT_DEVICE | ST_TOKEN_CHAINED)) return rc;
+    Model *m = reinterpret_cast<Model *>(h);
+    if (n <= 0) return fail(ST_ERANGE, "n must be positive (got %d)", n);
+    if ((int64_t)m->kv_len + n > m->c.max_seq)
+        return fail(ST_ERANGE, "KV overflow: kv_len %d + n %d > max_seq %d", m->kv_len, n, m->c.max_seq);
+    if (!(flags & ST_TOKEN_CHAINED)) {
+        if (first_token < 0 || first_token >= m->c.vocab)
+            return fail(ST_ERANGE, "token id %d is outside the vocabulary [0,%d)", first_token, m->c.vocab);
+        launch_set_token(*m, first_token);
+    }
+    launch_set_state(*m, kStep, 0);
+    for (int32_t i = 0; i < n; ++i)
+        if (int rc = decode_impl(m, nullptr, m->ws.out_tokens)) return rc;
+    if (out_tokens) {
+        bool dev = flags & ST_OUT_DEVICE;
+        ST_HIP(hipMemcpyAsync(out_tokens, m->ws.out_tokens, sizeof(int32_t) * n,
+                              dev ? hipMemcpyDeviceToDevice : hipMemcpyDeviceToHost, m->stream));
+        if (!dev) ST_HIP(hipStreamSynchronize(m->stream));
+    }
+    return ST_OK;
+}
+
+int st_trigger_scan(const st_trigger_rule *rule, const int32_t *tokens, int32_t lo, int32_t hi, int32_t *positions,
+                    int32_t cap, int32_t *n_found, int32_t *scratch, void *stream, uint32_t flags) {
+    if (!rule || !rule->kw_bitmap || !tokens || !n_found) return fail(ST_EINVAL, "rule, bitmap, tokens or n_found is NULL");
+    if (rule->window != 1 && rule->window != 2) return fail(ST_EINVAL, "window must be 1 or 2");
+    if (rule->window == 2 && !rule->delim_bitmap) return fail(ST_EINVAL, "window 2 needs a delimiter bitmap");
+    if (rule->vocab <= 0) return fail(ST_EINVAL, "rule vocab must be positive");
+    if (int rc = check_flags(flags, ST_OUT_DEVICE)) return rc;
+    if (cap < 0 || (cap > 0 && !positions)) return fail(ST_EINVAL, "cap < 0, or positions is NULL with cap > 0");
+    if (lo < 0 || hi < lo) return fail(ST_ERANGE, "bad range [%d,%d)", lo, hi);
+    hipStream_t s = (hipStream_t)stream;
+    if (flags & ST_OUT_DEVICE) {
+        launch_trigger_scan(*rule, tokens, lo, hi, positions, cap, n_found, s);
+        return check_launch("trigger scan");
+    }
+    if (!scratch) return fail(ST_EINVAL, "host outputs need a device scratch of cap+1 int32");
+    launch_trigger_scan(*rule, tokens, lo, hi, scratch + 1, cap, scratch, s);
+    if (int rc = check_launch("trigger scan")) return rc;
+    ST_HIP(hipMemcpyAsync(n_found, scratch, sizeof(int32_t), hipMemcpyDeviceToHost, s));
+    ST_HIP(hipStreamSynchronize(s));
+    int32_t k = *n_found < cap ? *n_found : cap;
+    if (k > 0) {
+        ST_HIP(hipMemcpyAsync(positions, scratch + 1, sizeof(int32_t) * k, hipMemcpyDeviceToHost, s));
+        ST_HIP(hipStreamSynchronize(s));
+    }
+    return ST_OK;
+}
+
+int st_handoff(st_model *small, st_model *large, int32_t *seq, int32_t *T, int32_t n_large, int32_t budget,
+               float *small_logits, int32_t *small_next_tok, st_spans *spans, uint32_t flags) {
+    if (!small || !large || !seq || !T) return fail(ST_EINVAL, "small, large, seq or T is NULL");
+    if (small == large) return fail(ST_EINVAL, "small and large must be different models");
+    if (int rc = check_flags(flags, 0)) return rc;
+    return handoff_impl(reinterpret_cast<Model *>(small), reinterpret_cast<Model *>(large), seq, T, n_large, budget,
+                        nullptr, small_logits, small_next_tok, nullptr, spans, nullptr, nullptr, nullptr);
+}
+
+int st_generate(st_model *hs, st_model *hl, const st_trigger_rule *rule, int32_t forced_period, const int32_t *prompt,
+                int32_t P, int32_t n_out, int32_t n_seg, int32_t *seq, uint8_t *src, st_spans *spans, int32_t span_cap,
+                st_gen_stats *stats) {
+    using clk = std::chrono::steady_clock;
+    auto ms = [](clk::time_point a, clk::time_point b) { return std::chrono::duration<double, std::milli>(b - a).count(); };
+    if (!hs || !hl || !prompt || !seq) return fail(ST_EINVAL, "small, large, prompt or seq is NULL");
+    if (hs == hl) return fail(ST_EINVAL, "small and large must be different models");
+    if (forced_period < 0) return fail(ST_EINVAL, "forced_period must be >= 0");
+    if (forced_period == 0) {
+        if (!rule || !rule->kw_bitmap) return fail(ST_EINVAL, "a trigger rule (or forced_period > 0) is required");
+        if (rule->window != 1 && rule->window != 2) return fail(ST_EINVAL, "window must be 1 or 2");
+        if (rule->window == 2 && !rule->delim_bitmap) return fail(ST_EINVAL, "window 2 needs a delimiter bitmap");
+    }
+    if (P <= 0 || n_out < 0 || n_seg <= 0) return fail(ST_ERANGE, "P, n_seg must be positive and n_out non-negative");
+    if (span_cap < 0 || (span_cap > 0 && !spans)) return fail(ST_EINVAL, "bad span buffer");
+    Model *S = reinterpret_cast<Model *>(hs), *L = reinterpret_cast<Model *>(hl);
+    if (S->kv_len != 0 || L->kv_len != 0) return fail(ST_EINVAL, "both models must start with an empty KV cache");
+    if ((int64_t)P + n_out > S->c.max_seq || (int64_t)P + n_out > L->c.max_seq)
+        return fail(ST_ERANGE, "P + n_out = %d exceeds a model's max_seq", P + n_out);
+    const st_trigger_rule *use_rule = forced_period > 0 ? nullptr : rule;
+    st_gen_stats st = {};
+    memcpy(seq, prompt, sizeof(int32_t) * P);
+    int32_t T = P, tok = 0, fired = 0;
+    if (n_out > 0) {
+        auto a = clk::now();
+        if (int rc = prefill_impl(S, seq, P, false, use_rule)) return rc;
+        if (int rc = fetch_token(S, &tok, &fired)) return rc;
+        auto b = clk::now();
+        if (int rc = prefill_impl(L, seq, P, false, nullptr)) return rc;
+        ST_HIP(hipStreamSynchronize(L->stream));
+        auto c = clk::now();
+        st.ms_small_prefill += ms(a, b);
+        st.ms_large_prefill += ms(b, c);
+    }
+    int32_t small_count = 0;
+    while (T - P < n_out) {
+        seq[T++] = tok;
+        if (src) src[T - 1 - P] = 0;
+        ++small_count;
+        if (T - P == n_out) break;
+        bool fire = forced_period > 0 ? (small_count % forced_period == 0) : fired != 0;
+        if (fire) {
+            st_spans sp;
+            if (int rc = handoff_impl(S, L, seq, &T, n_seg, n_out - (T - P), use_rule, nullptr, &tok, &fired, &sp,
+                                      &st.ms_large_prefill, &st.ms_large_decode, &st.ms_small_prefill))
+                return rc;
+            if (src)
+                for (int32_t p = sp.large_decode_lo; p < sp.large_decode_hi; ++p) src[p - P] = 1;
+            st.n_large += sp.large_decode_hi - sp.large_decode_lo;
+            if (st.n_spans < span_cap) spans[st.n_spans++] = sp;
+            ++st.n_handoffs;
+        } else {
+            auto a = clk::now();
+            if (int rc = decode_impl(S, use_rule, nullptr)) return rc;   // feeds state[kTok] == tok
+            if (int rc = fetch_token(S, &tok, &fired)) return rc;
+            st.ms_small_decode += ms(a, clk::now());
+        }
+    }
+    st.n_out = T - P;
+    if (stats) *stats = st;
+    return ST_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,70 @@
+// Device-side helpers shared by the HIP kernels of the library (gfx950, wave64).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace st {
+
+constexpr int kWave = 64;
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));  // one 16-byte global load
+
+// Slots of the per-model device state block (int32 each).
+enum StateSlot {
+    kPos = 0,    // position the next fed token will take (== number of cached positions)
+    kTok = 1,    // last greedy token
+    kFired = 2,  // 1 if the trigger rule fired on kTok
+    kFed = 3,    // token fed by the step that produced kTok
+    kStep = 4,   // running index into the output-token buffer of a chained run
+    kStateInts = 16
+};
+
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+__device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
+
+// fp32 -> bf16, round to nearest even; NaN stays NaN.
+__device__ __forceinline__ uint16_t f32_to_bf16(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+    return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+    return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, kWave));
+    return v;
+}
+
+// Sum over a 256-thread block (4 waves); `red` is 4 floats of LDS.  Ends with a barrier.
+__device__ __forceinline__ float block_sum_256(float v, float *red) {
+    v = wave_sum(v);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+    __syncthreads();
+    return red[0] + red[1] + red[2] + red[3];
+}
+
+// fma of 8 bf16 weights (one 16-byte load) with 8 fp32 activations.
+__device__ __forceinline__ float dot8(const u32x4 &w, const float4 &xa, const float4 &xb, float acc) {
+    acc = fmaf(bf16_lo(w.x), xa.x, acc);
+    acc = fmaf(bf16_hi(w.x), xa.y, acc);
+    acc = fmaf(bf16_lo(w.y), xa.z, acc);
+    acc = fmaf(bf16_hi(w.y), xa.w, acc);
+    acc = fmaf(bf16_lo(w.z), xb.x, acc);
+    acc = fmaf(bf16_hi(w.z), xb.y, acc);
+    acc = fmaf(bf16_lo(w.w), xb.z, acc);
+    acc = fmaf(bf16_hi(w.w), xb.w, acc);
+    return acc;
+}
+
+}  // namespace st

@@ -1,0 +1,81 @@
+// Host-side internals of the library: the model record, workspace carving and the launchers
+// the API layer calls.  Nothing here is part of the public ABI.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include <vector>
+
+#include "../../include/st.h"
+
+namespace st {
+
+typedef uint16_t bf16_t;
+
+struct Workspace {
+    int32_t *state;        // kStateInts
+    int32_t *counters;     // n_kv_heads arrival counters of the split attention
+    float2 *rope;          // [max_seq][head_dim/2] (cos, sin)
+    int32_t *tokens;       // [max_chunk] staged ids
+    int32_t *out_tokens;   // [max_seq] tokens produced by chained steps
+    float *x;              // [max_chunk][hidden] residual stream
+    bf16_t *xn;            // [max_chunk][hidden] normalised rows (GEMM input)
+    float *qkv;            // [max_chunk][qkv] projections before RoPE
+    bf16_t *qb;            // [max_chunk][n_q*d] rotated queries
+    bf16_t *attn;          // [max_chunk][n_q*d] attention output (GEMM input)
+    bf16_t *act;           // [max_chunk][intermediate] SwiGLU output
+    float *q1;             // [n_q*d] decode query
+    float *o1;             // [n_q*d] decode attention output
+    float *a1;             // [intermediate] decode SwiGLU output
+    float *part_ml;        // [n_q][splits][2]
+    float *part_acc;       // [n_q][splits][d]
+    float *logits;         // [vocab]
+    float *amax_val;       // [kLmBlocks]
+    int32_t *amax_idx;     // [kLmBlocks]
+    size_t bytes;
+};
+
+constexpr int kLmBlocks = 1024;   // blocks (and arg-max partials) of the LM-head kernel
+constexpr int kAttnSplits = 128;  // most key ranges one kv head is split into at decode
+
+struct Model {
+    st_config c;
+    std::vector<const bf16_t *> wqkv, bqkv, wo, wgu, wdown, norm_attn, norm_mlp;
+    const bf16_t *embed, *lm_head, *final_norm;
+    bf16_t *kcache, *vcache;   // [layer][kv_head][max_seq][d]
+    Workspace ws;
+    hipStream_t stream;
+    int32_t kv_len;
+    int qkv_dim;
+};
+
+// Carves the workspace; with base == nullptr only sizes it.
+void carve_workspace(const st_config &c, char *base, Workspace *ws);
+
+// ---- launchers (decode.hip) ----
+void launch_init(const Model &m);
+void launch_set_token(const Model &m, int32_t token);
+void launch_set_token_from(const Model &m, const int32_t *tokens_dev, int32_t index);
+void launch_set_state(const Model &m, int slot, int32_t value);
+// Runs one whole single-token step on the model's stream: embeds state[kTok] at state[kPos],
+// all layers, LM head, arg-max; leaves state[kTok] = greedy token and state[kPos] += 1.
+// rule may be null (state[kFired] is then 0).  out_seq (device, may be null) receives the token at
+// index state[kStep]++.
+void launch_decode_step(const Model &m, const st_trigger_rule *rule, int32_t *out_seq_dev);
+// Embedding of state[kTok] and all layers at position state[kPos], on the residual row x (fp32[hidden]).
+void launch_decode_layers(const Model &m, float *x);
+// LM head + arg-max over the residual row x_row (fp32[hidden]); advances state[kPos] by `advance`.
+void launch_head(const Model &m, const float *x_row, const st_trigger_rule *rule, int32_t advance,
+                 int32_t *out_seq_dev);
+
+// ---- launchers (prefill.hip) ----
+// Feeds ws.tokens[0,n) at positions [pos0, pos0+n) through all layers; leaves the residual rows in ws.x.
+void launch_prefill_layers(const Model &m, int32_t pos0, int32_t n);
+
+// ---- launchers (trigger.hip) ----
+void launch_trigger_scan(const st_trigger_rule &rule, const int32_t *tokens, int32_t lo, int32_t hi,
+                         int32_t *positions, int32_t cap, int32_t *n_found, hipStream_t stream);
+
+}  // namespace st

@@ -1,0 +1,101 @@
+"""Host-only checks of the C-ABI library: it loads, exports every declared symbol, and rejects bad
+arguments before touching the GPU.  No compute calls."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2504_12329_amd import binding as B, synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def L():
+    if not os.path.exists(B.LIB_PATH):
+        from paper_2504_12329_amd import build
+        build.build()
+    return B.lib()
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "st.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(st_[a-z_]+)\s*\(", text)))
+
+
+def test_exports_every_declared_symbol(L):
+    names = _declared()
+    assert set(names) == set(B.EXPORTS)
+    for n in names:
+        assert getattr(L, n) is not None
+
+
+def test_struct_sizes_match_header():
+    assert C.sizeof(B.st_config) == 13 * 4
+    assert C.sizeof(B.st_spans) == 6 * 4
+    assert C.sizeof(B.st_trigger_rule) == 2 * 8 + 2 * 4
+    assert C.sizeof(B.st_gen_stats) == 4 * 4 + 4 * 8
+
+
+def test_query_sizes_and_config_validation(L):
+    cfg = synth.model_config("tiny_small", 128)
+    kv, ws = B.st_query_sizes(cfg)
+    assert kv == 2 * 2 * 2 * 128 * 64 * 2 and ws > 0
+    big = synth.model_config("qwen32b", 8192 + 64, max_chunk=4096)
+    kv, ws = B.st_query_sizes(big)
+    assert kv == 262144 * (8192 + 64) and ws < 2 << 30
+    for key, val in [("head_dim", 96), ("hidden", 260), ("n_kv_heads", 3), ("n_layers", 0), ("max_seq", 0),
+                     ("hidden", 16384), ("tie_embeddings", 2), ("rope_theta", 0.0), ("max_chunk", 0)]:
+        bad = dict(cfg, **{key: val})
+        with pytest.raises(B.StError) as e:
+            B.st_query_sizes(bad)
+        assert e.value.code == B.ST_EINVAL and str(e.value)
+    with pytest.raises(B.StError):
+        B.st_query_sizes(dict(cfg, n_q_heads=18, n_kv_heads=2))      # 9 query heads per kv head
+
+
+def test_null_and_bad_arguments_are_rejected_before_any_launch(L):
+    n = C.c_int32()
+    assert L.st_kv_len(None, C.byref(n)) == B.ST_EINVAL
+    assert L.st_kv_truncate(None, 0) == B.ST_EINVAL
+    assert L.st_prefill(None, None, 1, None, None, 0) == B.ST_EINVAL
+    assert L.st_decode_step(None, 0, None, None, 0) == B.ST_EINVAL
+    assert L.st_decode_greedy(None, 0, 1, None, 0) == B.ST_EINVAL
+    assert L.st_handoff(None, None, None, None, 1, 1, None, None, None, 0) == B.ST_EINVAL
+    assert L.st_generate(None, None, None, 0, None, 1, 1, 1, None, None, None, 0, None) == B.ST_EINVAL
+    assert b"NULL" in L.st_last_error()
+    cfg = B.make_config(synth.model_config("tiny_small", 128))
+    h = C.c_void_p()
+    assert L.st_model_create(C.byref(cfg), None, None, 0, None, 0, None, C.byref(h)) == B.ST_EINVAL
+    assert L.st_model_create(C.byref(cfg), None, None, 0, None, 0, None, None) == B.ST_EINVAL
+    # trigger scan argument checks
+    rule = B.st_trigger_rule(0x1000, 0, 2, 1024)
+    assert L.st_trigger_scan(C.byref(rule), 0x1000, 0, 4, None, 0, C.byref(n), None, None, 0) == B.ST_EINVAL  # no delim
+    rule = B.st_trigger_rule(0x1000, 0, 3, 1024)
+    assert L.st_trigger_scan(C.byref(rule), 0x1000, 0, 4, None, 0, C.byref(n), None, None, 0) == B.ST_EINVAL
+    rule = B.st_trigger_rule(0x1000, 0, 1, 1024)
+    assert L.st_trigger_scan(C.byref(rule), 0x1000, 5, 4, None, 0, C.byref(n), None, None, B.ST_OUT_DEVICE) == B.ST_ERANGE
+    assert L.st_trigger_scan(C.byref(rule), 0x1000, 0, 4, None, 0, C.byref(n), None, None, 0) == B.ST_EINVAL  # no scratch
+
+
+def test_model_create_checks_buffers(L):
+    cfg_d = synth.model_config("tiny_small", 128)
+    cfg = B.make_config(cfg_d)
+    kv, ws = B.st_query_sizes(cfg_d)
+    Lyr = cfg_d["n_layers"]
+    fake = (C.c_void_p * Lyr)(*([0x10000] * Lyr))
+    arr = C.cast(fake, C.POINTER(C.c_void_p))
+    w = B.st_weights(0x10000, 0x10000, 0x10000, arr, arr, arr, arr, arr, arr, arr)
+    h = C.c_void_p()
+    assert L.st_model_create(C.byref(cfg), C.byref(w), 0x10000, kv - 1, 0x20000, ws, None, C.byref(h)) == B.ST_ENOMEM
+    assert L.st_model_create(C.byref(cfg), C.byref(w), 0x10000, kv, 0x20000, ws - 1, None, C.byref(h)) == B.ST_ENOMEM
+    assert L.st_model_create(C.byref(cfg), C.byref(w), 0x10010, kv, 0x20000, ws, None, C.byref(h)) == B.ST_EINVAL
+    holes = (C.c_void_p * Lyr)(*([0x10000] * (Lyr - 1) + [None]))
+    w2 = B.st_weights(0x10000, 0x10000, 0x10000, arr, arr, C.cast(holes, C.POINTER(C.c_void_p)), arr, arr, arr, arr)
+    assert L.st_model_create(C.byref(cfg), C.byref(w2), 0x10000, kv, 0x20000, ws, None, C.byref(h)) == B.ST_EINVAL
+    assert b"layer" in L.st_last_error()
+    w3 = B.st_weights(0x10000, 0, 0x10000, arr, arr, arr, arr, arr, arr, arr)     # untied model without lm_head
+    assert L.st_model_create(C.byref(cfg), C.byref(w3), 0x10000, kv, 0x20000, ws, None, C.byref(h)) == B.ST_EINVAL
+    assert not h.value
