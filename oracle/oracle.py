@@ -109,7 +109,10 @@ class OracleModel:
             self._h = None
 
     def __del__(self):
-        self.close()
+        try:
+            self.close()
+        except Exception:       # interpreter shutdown: the library wrapper may already be gone
+            pass
 
     @property
     def kv_len(self):

@@ -165,7 +165,10 @@ class Model:
             self._h = None
 
     def __del__(self):
-        self.close()
+        try:
+            self.close()
+        except Exception:       # interpreter shutdown: the library wrapper may already be gone
+            pass
 
     @property
     def kv_len(self):

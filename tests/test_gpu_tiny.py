@@ -9,7 +9,15 @@ from tests.gpu_common import LOGIT_TOL, make_pair, print_case, rel_err
 
 pytestmark = pytest.mark.gpu
 
-PROMPT_SEED = 319     # prompt seed whose oracle run keeps every top-1/top-2 logit gap above 0.9 % of max|logit|
+# Greedy decoding of random-init weights has near-ties; a bf16 path may then legitimately pick the
+# other token.  The prompt seeds below were searched on the CPU so that, in the oracle's own run of
+# each scenario, every top-1/top-2 logit gap is at least MIN_MARGIN of max|logit| (3x the worst GPU
+# logit error seen on these models); each test re-checks that margin before comparing tokens.
+PROMPT_SEED = 319            # mod-16 rule, 64 outputs, segments of 8
+PROMPT_SEED_WINDOW2 = 477    # (prev % 3 == 0 and tok % 2 == 0) rule, segments of 5
+PROMPT_SEED_FORCED = 293     # hand-over every 6th speculative token, segments of 4
+PROMPT_SEED_GREEDY = 26      # the small model alone, 44 greedy steps
+MIN_MARGIN = 0.008
 N_OUT, N_SEG = 64, 8
 
 
@@ -50,26 +58,25 @@ def test_prefill_and_teacher_forced_decode_logits(small):
 def test_greedy_tokens_identical(small):
     cfg, g, o = small
     _fresh(g, o)
-    prompt = synth.make_prompt(32, cfg["vocab"], PROMPT_SEED)
+    prompt = synth.make_prompt(32, cfg["vocab"], PROMPT_SEED_GREEDY)
     tok_o = O.argmax(o.feed(prompt))
     _, tok_g = g.prefill(prompt, want_logits=False)
     assert tok_g == tok_o
     want = []
     t = tok_o
-    for _ in range(40):
-        t = O.argmax(o.feed([t]))
+    margins = []
+    for _ in range(44):
+        lg = o.feed([t])
+        t = O.argmax(lg)
         want.append(t)
+        margins.append((np.sort(lg)[-1] - np.sort(lg)[-2]) / np.abs(lg).max())
+    assert min(margins) >= MIN_MARGIN, f"near-tie in the oracle run: {min(margins):.4f}"
     got = g.decode_greedy(tok_g, 40)
     print_case("greedy", got[:40].tolist())
-    assert got[:32].tolist() == want[:32]
+    assert got.tolist() == want[:40]
     # chained continuation picks up the device-resident token
     more = g.decode_greedy(0, 4, chained=True)
-    t = want[-1]
-    ref = []
-    for _ in range(4):
-        t = O.argmax(o.feed([t]))
-        ref.append(t)
-    assert more.tolist() == ref
+    assert more.tolist() == want[40:]
 
 
 @pytest.mark.parametrize("split", [1, 7, 31, 45])
@@ -133,7 +140,11 @@ def test_error_paths_on_device(small):
 def _oracle_trace(prompt, n_out, n_seg, fire, o_small, o_large):
     o_small.truncate(0)
     o_large.truncate(0)
-    return S.speculative_thinking(S.GreedyModel(o_small), S.GreedyModel(o_large), prompt, n_out, n_seg, fire)
+    a, b = S.GreedyModel(o_small, keep_logits=True), S.GreedyModel(o_large, keep_logits=True)
+    tr = S.speculative_thinking(a, b, prompt, n_out, n_seg, fire)
+    margin = min((np.sort(lg)[-1] - np.sort(lg)[-2]) / np.abs(lg).max() for g in (a, b) for _, lg in g.logits)
+    assert margin >= MIN_MARGIN, f"oracle run has a near-tie (margin {margin:.4f}); pick another prompt seed"
+    return tr
 
 
 @pytest.fixture(scope="module")
@@ -170,9 +181,9 @@ def test_generate_matches_oracle_schedule(pair):
 
 def test_generate_window_two_and_budget_inside_segment(pair):
     (cfg, gs, os_), (_, gl, ol) = pair
-    prompt = synth.make_prompt(32, cfg["vocab"], PROMPT_SEED)
+    prompt = synth.make_prompt(32, cfg["vocab"], PROMPT_SEED_WINDOW2)
     kw, dl = (lambda t: t % 2 == 0), (lambda t: t % 3 == 0)
-    for n_out in (26, 57):
+    for n_out in (57, 29):                               # 29 outputs end inside the third segment
         tr = _oracle_trace(prompt, n_out, 5, S.window_rule(kw, dl, 2), os_, ol)
         gs.truncate(0)
         gl.truncate(0)
@@ -181,11 +192,13 @@ def test_generate_window_two_and_budget_inside_segment(pair):
         print_case("window-2 run", n_out, "triggers", tr.triggers)
         assert out["seq"].tolist() == tr.seq and out["src"].tolist() == tr.src
         assert [s["large_prefill_hi"] - 1 for s in out["spans"]] == tr.triggers
+        if n_out == 29:
+            assert tr.src[-1] == S.LARGE and len(tr.small_prefill) == len(tr.triggers) - 1
 
 
 def test_forced_period_schedule(pair):
     (cfg, gs, os_), (_, gl, ol) = pair
-    prompt = synth.make_prompt(32, cfg["vocab"], PROMPT_SEED)
+    prompt = synth.make_prompt(32, cfg["vocab"], PROMPT_SEED_FORCED)
     count = {"n": 0}
 
     def fire(seq, p):                                   # every 6th small-written token hands over
