@@ -174,6 +174,13 @@ int st_generate(st_model *small, st_model *large, const st_trigger_rule *rule, i
                 const int32_t *prompt, int32_t P, int32_t n_out, int32_t n_seg,
                 int32_t *seq, uint8_t *src, st_spans *spans, int32_t span_cap, st_gen_stats *stats);
 
+/* Measurement support: one chained greedy decode step (feeds the model's own last token) in which
+ * every launch of the gate/up projection kernel -- the kernel that moves the most bytes of a step
+ * (2 * intermediate * hidden bf16 weights per launch) -- carries HIP start/stop events on the
+ * model's stream.  Synchronises the stream.  *gateup_mean_us is the mean device time of the
+ * n_layers launches, *step_us the device time of the whole step.  kv_len += 1. */
+int st_decode_step_timed(st_model *m, double *gateup_mean_us, double *step_us);
+
 const char *st_last_error(void);
 
 #ifdef __cplusplus

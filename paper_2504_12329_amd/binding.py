@@ -17,7 +17,7 @@ ST_OK, ST_EINVAL, ST_ENOMEM, ST_ERANGE, ST_EHIP = 0, -1, -2, -3, -4
 ST_TOKENS_DEVICE, ST_OUT_DEVICE, ST_TOKEN_CHAINED = 1, 2, 4
 
 EXPORTS = ("st_query_sizes", "st_model_create", "st_model_destroy", "st_kv_len", "st_kv_truncate", "st_prefill",
-           "st_decode_step", "st_decode_greedy", "st_trigger_scan", "st_handoff", "st_generate", "st_last_error")
+           "st_decode_step", "st_decode_step_timed", "st_decode_greedy", "st_trigger_scan", "st_handoff", "st_generate", "st_last_error")
 
 
 class StError(RuntimeError):
@@ -79,6 +79,7 @@ def lib():
         L.st_kv_truncate.argtypes = [C.c_void_p, C.c_int32]
         L.st_prefill.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_uint32]
         L.st_decode_step.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_uint32]
+        L.st_decode_step_timed.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_double)]
         L.st_decode_greedy.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_uint32]
         L.st_trigger_scan.argtypes = [C.POINTER(st_trigger_rule), C.c_void_p, C.c_int32, C.c_int32, C.c_void_p,
                                       C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32]
@@ -198,6 +199,12 @@ class Model:
         nt = C.c_int32()
         _check(lib().st_decode_step(self._h, int(token), _np_ptr(lg) if want_logits else None, C.addressof(nt), 0))
         return lg, nt.value
+
+    def decode_step_timed(self):
+        """One chained step with per-launch events; returns (mean gate/up kernel us, whole step us)."""
+        a, b = C.c_double(), C.c_double()
+        _check(lib().st_decode_step_timed(self._h, C.byref(a), C.byref(b)))
+        return a.value, b.value
 
     def decode_greedy(self, first_token, n, chained=False, out_dev=None):
         """n chained greedy steps.  Returns the tokens (host) unless out_dev (int32 CUDA tensor) is given."""

@@ -6,6 +6,8 @@
 #include <cstring>
 #include <new>
 
+#include <hip/hip_ext.h>
+
 #include "st_device.h"
 #include "st_internal.h"
 
@@ -256,6 +258,7 @@ int st_model_create(const st_config *cfg, const st_weights *w, void *kv, size_t 
     carve_workspace(*cfg, (char *)workspace, &m->ws);
     m->stream = (hipStream_t)stream;
     m->kv_len = 0;
+    m->timers = nullptr;
     launch_init(*m);
     if (int rc = check_launch("workspace initialisation")) {
         delete m;
@@ -334,6 +337,44 @@ int st_decode_greedy(st_model *h, int32_t first_token, int32_t n, int32_t *out_t
         if (!dev) ST_HIP(hipStreamSynchronize(m->stream));
     }
     return ST_OK;
+}
+
+int st_decode_step_timed(st_model *h, double *gateup_mean_us, double *step_us) {
+    if (!h) return fail(ST_EINVAL, "model is NULL");
+    Model *m = reinterpret_cast<Model *>(h);
+    if (m->kv_len + 1 > m->c.max_seq)
+        return fail(ST_ERANGE, "KV overflow: kv_len %d + 1 > max_seq %d", m->kv_len, m->c.max_seq);
+    StepTimers t;
+    t.ev.resize(2 + 2 * (size_t)m->c.n_layers);
+    int rc = ST_OK;
+    for (auto &e : t.ev) {
+        e = nullptr;
+        if (rc == ST_OK && hipEventCreate(&e) != hipSuccess) rc = fail(ST_EHIP, "hipEventCreate failed");
+    }
+    if (rc == ST_OK) {
+        m->timers = &t;
+        hipEventRecord(t.ev[0], m->stream);
+        rc = decode_impl(m, nullptr, nullptr);
+        hipEventRecord(t.ev[1], m->stream);
+        m->timers = nullptr;
+        if (rc == ST_OK && hipStreamSynchronize(m->stream) != hipSuccess) rc = fail(ST_EHIP, "synchronise failed");
+    }
+    if (rc == ST_OK) {
+        float ms = 0.f;
+        double sum = 0.0;
+        for (int l = 0; l < m->c.n_layers && rc == ST_OK; ++l) {
+            if (hipEventElapsedTime(&ms, t.ev[2 + 2 * l], t.ev[3 + 2 * l]) != hipSuccess)
+                rc = fail(ST_EHIP, "hipEventElapsedTime failed");
+            sum += ms;
+        }
+        if (rc == ST_OK && gateup_mean_us) *gateup_mean_us = sum * 1e3 / m->c.n_layers;
+        if (rc == ST_OK && hipEventElapsedTime(&ms, t.ev[0], t.ev[1]) != hipSuccess)
+            rc = fail(ST_EHIP, "hipEventElapsedTime failed");
+        if (rc == ST_OK && step_us) *step_us = ms * 1e3;
+    }
+    for (auto &e : t.ev)
+        if (e) hipEventDestroy(e);
+    return rc;
 }
 
 int st_trigger_scan(const st_trigger_rule *rule, const int32_t *tokens, int32_t lo, int32_t hi, int32_t *positions,

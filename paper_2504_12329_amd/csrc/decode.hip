@@ -4,6 +4,8 @@
 //
 // Every kernel takes the position and the fed token from the model's device state block,
 // so a step can be enqueued (or replayed) without the host knowing either.
+#include <hip/hip_ext.h>
+
 #include "st_device.h"
 #include "st_internal.h"
 
@@ -581,18 +583,20 @@ void launch_decode_layers(const Model &m, float *x) {
         launch_gemv_residual(m, m.wo[l], m.ws.o1, x, h, nq * d);
         {
             dim3 grid((I + 4 * r_gu - 1) / (4 * r_gu)), block(256);
+            hipEvent_t e0 = m.timers ? m.timers->ev[2 + 2 * l] : nullptr;
+            hipEvent_t e1 = m.timers ? m.timers->ev[3 + 2 * l] : nullptr;
             switch (r_gu) {
                 case 4:
-                    hipLaunchKernelGGL(k_gateup_swiglu<4>, grid, block, lds_h, m.stream, m.wgu[l], x,
-                                       m.norm_mlp[l], m.ws.a1, h, I, c.rms_eps);
+                    hipExtLaunchKernelGGL(k_gateup_swiglu<4>, grid, block, lds_h, m.stream, e0, e1, 0, m.wgu[l], x,
+                                          m.norm_mlp[l], m.ws.a1, h, I, c.rms_eps);
                     break;
                 case 2:
-                    hipLaunchKernelGGL(k_gateup_swiglu<2>, grid, block, lds_h, m.stream, m.wgu[l], x,
-                                       m.norm_mlp[l], m.ws.a1, h, I, c.rms_eps);
+                    hipExtLaunchKernelGGL(k_gateup_swiglu<2>, grid, block, lds_h, m.stream, e0, e1, 0, m.wgu[l], x,
+                                          m.norm_mlp[l], m.ws.a1, h, I, c.rms_eps);
                     break;
                 default:
-                    hipLaunchKernelGGL(k_gateup_swiglu<1>, grid, block, lds_h, m.stream, m.wgu[l], x,
-                                       m.norm_mlp[l], m.ws.a1, h, I, c.rms_eps);
+                    hipExtLaunchKernelGGL(k_gateup_swiglu<1>, grid, block, lds_h, m.stream, e0, e1, 0, m.wgu[l], x,
+                                          m.norm_mlp[l], m.ws.a1, h, I, c.rms_eps);
                     break;
             }
         }

@@ -40,6 +40,11 @@ struct Workspace {
 constexpr int kLmBlocks = 1024;   // blocks (and arg-max partials) of the LM-head kernel
 constexpr int kAttnSplits = 128;  // most key ranges one kv head is split into at decode
 
+// Events recorded by a timed step: [0] step start, [1] step stop, then one (start, stop) pair per layer.
+struct StepTimers {
+    std::vector<hipEvent_t> ev;
+};
+
 struct Model {
     st_config c;
     std::vector<const bf16_t *> wqkv, bqkv, wo, wgu, wdown, norm_attn, norm_mlp;
@@ -49,6 +54,7 @@ struct Model {
     hipStream_t stream;
     int32_t kv_len;
     int qkv_dim;
+    StepTimers *timers;  // non-null only inside st_decode_step_timed
 };
 
 // Carves the workspace; with base == nullptr only sizes it.

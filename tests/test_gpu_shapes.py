@@ -1,0 +1,102 @@
+"""GPU parity at the paper's model shapes (1.5B whole, 7B- and 32B-shaped layer subsets) against the
+oracle, and cross-path properties at sizes the oracle cannot reach."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import oracle as O
+from paper_2504_12329_amd import binding as B, synth
+from tests.gpu_common import LOGIT_TOL, make_pair, print_case, rel_err
+
+pytestmark = pytest.mark.gpu
+
+MIN_MARGIN = 0.008
+
+
+def _margin(lg):
+    s = np.sort(lg)
+    return float((s[-1] - s[-2]) / np.abs(lg).max())
+
+
+def _teacher_forced(cfg, g, o, prompt, splits, n_decode):
+    """Feeds `prompt` in the given chunk sizes, then n_decode oracle-chosen tokens one by one."""
+    worst = 0.0
+    lo = hi = 0
+    for n in splits:
+        hi = lo + n
+        lg_g, tok_g = g.prefill(prompt[lo:hi])
+        lo = hi
+    assert hi == len(prompt)
+    lg_o = o.feed(prompt)
+    worst = max(worst, rel_err(lg_g, lg_o))
+    checked = 0
+    for _ in range(n_decode):
+        if _margin(lg_o) >= MIN_MARGIN:
+            assert tok_g == O.argmax(lg_o)
+            checked += 1
+        assert tok_g == O.argmax(lg_g)
+        tok = O.argmax(lg_o)
+        lg_o = o.feed([tok])
+        lg_g, tok_g = g.decode_step(tok)
+        worst = max(worst, rel_err(lg_g, lg_o))
+    print_case("worst relative logit error", worst, "tokens compared", checked)
+    return worst
+
+
+def test_qwen1p5b_whole_model():
+    print_case("1.5B shape, 28 layers: prefill 33+7 tokens, 6 decode steps")
+    cfg, g, o = make_pair("qwen1p5b", 1, max_seq=64, max_chunk=48, gen_device="cuda")
+    prompt = synth.make_prompt(40, cfg["vocab"], 3)
+    assert _teacher_forced(cfg, g, o, prompt, [33, 7], 6) <= LOGIT_TOL
+    g.close()
+
+
+def test_qwen7b_shaped_layers():
+    print_case("7B shape (7 query heads per kv head), 2 layers: prefill 37 tokens, 4 decode steps")
+    cfg, g, o = make_pair("qwen7b", 4, max_seq=64, max_chunk=64, n_layers=2, gen_device="cuda")
+    prompt = synth.make_prompt(37, cfg["vocab"], 5)
+    assert _teacher_forced(cfg, g, o, prompt, [37], 4) <= LOGIT_TOL
+    g.close()
+
+
+def test_qwen32b_shaped_layers_prefill_on_existing_cache():
+    print_case("32B shape, 2 layers: 70 cached tokens, catch-up chunk of 150 (128 + 22), 3 decode steps")
+    cfg, g, o = make_pair("qwen32b", 2, max_seq=256, max_chunk=256, n_layers=2, gen_device="cuda")
+    prompt = synth.make_prompt(220, cfg["vocab"], 6)
+    assert _teacher_forced(cfg, g, o, prompt, [70, 150], 3) <= LOGIT_TOL
+    g.close()
+
+
+def test_decode_and_prefill_paths_agree_at_long_context():
+    """At 4096 + 1024 tokens the oracle is out of reach; the GEMV/split-K decode path and the
+    MFMA/flash prefill path are two independent kernel sets and must agree with each other (each
+    carries its own bf16 rounding, so the bar is the same as against the oracle)."""
+    print_case("1.5B shape, 4 layers: 4096 cached + 1024-token chunk, decode vs prefill of the next tokens")
+    cfg = synth.model_config("qwen1p5b", max_seq=5400, max_chunk=1024, n_layers=4)
+    w = synth.make_weights(cfg, 1, device="cuda")
+    g = B.Model(cfg, w)
+    toks = synth.make_prompt(5200, cfg["vocab"], 7)
+    g.prefill(toks[:4096], want_logits=False)
+    a, _ = g.prefill(toks[4096:5120])                     # one 1024-row chunk on top of 4096 cached keys
+    g.truncate(4096)
+    g.prefill(toks[4096:4600], want_logits=False)          # same tokens, ragged chunks
+    b, _ = g.prefill(toks[4600:5120])
+    assert rel_err(b, a) <= LOGIT_TOL
+    g.truncate(5119)
+    c, _ = g.decode_step(int(toks[5119]))                 # last token again, through the decode kernels
+    assert rel_err(c, a) <= LOGIT_TOL
+    for i in range(5120, 5124):                           # and a few more, decode vs single-row prefill
+        d, _ = g.decode_step(int(toks[i]))
+        g.truncate(i)
+        e, _ = g.prefill(toks[i:i + 1])
+        assert rel_err(e, d) <= LOGIT_TOL
+    g.close()
+
+
+def test_split_attention_matches_oracle_over_many_ranges():
+    """One layer, 1.5B shape, 700 cached keys: the decode attention splits them over 11 ranges."""
+    print_case("1.5B shape, 1 layer: 700 tokens then 3 decode steps")
+    cfg, g, o = make_pair("qwen1p5b", 8, max_seq=720, max_chunk=512, n_layers=1, gen_device="cuda")
+    prompt = synth.make_prompt(700, cfg["vocab"], 9)
+    assert _teacher_forced(cfg, g, o, prompt, [512, 188], 3) <= LOGIT_TOL
+    g.close()
