@@ -3,6 +3,7 @@
 #include <chrono>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 
@@ -104,7 +105,7 @@ static int prefill_impl(Model *m, const int32_t *tokens, int32_t n, bool tokens_
                               tokens_dev ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice, m->stream));
         bool last_chunk = done + cn == n;
         launch_prefill_layers(*m, m->kv_len + done, cn);
-        if (last_chunk) launch_head(*m, m->ws.x + (size_t)(cn - 1) * c.hidden, rule, cn, nullptr);
+        if (last_chunk) launch_head(*m, m->ws.x + (size_t)(cn - 1) * c.hidden, rule, cn, nullptr, m->stream);
         else launch_set_state(*m, kPos, m->kv_len + done + cn);
         if (int rc = check_launch("prefill")) return rc;
     }
@@ -112,11 +113,50 @@ static int prefill_impl(Model *m, const int32_t *tokens, int32_t n, bool tokens_
     return ST_OK;
 }
 
+// The captured graph of one decode step for this rule / output buffer, or nullptr when graphs are off.
+// Every kernel of a step reads the position and token from the device state block, so one graph
+// serves every step.  Capture happens on a private stream (the caller's may be the legacy default
+// stream, which cannot be captured); the graph is then launched on the model's stream.
+static hipGraphExec_t step_graph(Model *m, const st_trigger_rule *rule, int32_t *out_seq_dev) {
+    if (m->graphs_off || m->timers) return nullptr;
+    const void *kw = rule ? rule->kw_bitmap : nullptr, *dl = rule ? rule->delim_bitmap : nullptr;
+    int window = rule ? rule->window : 0, vocab = rule ? rule->vocab : 0;
+    for (const StepGraph &g : m->graphs)
+        if (g.kw == kw && g.delim == dl && g.out_seq == out_seq_dev && g.window == window && g.vocab == vocab)
+            return g.exec;
+    if (m->graphs.size() >= 16) return nullptr;  // unusual caller: many distinct rules; launch directly
+    if (!m->capture_stream && hipStreamCreateWithFlags(&m->capture_stream, hipStreamNonBlocking) != hipSuccess) {
+        m->graphs_off = true;
+        (void)hipGetLastError();
+        return nullptr;
+    }
+    hipGraph_t graph = nullptr;
+    hipGraphExec_t exec = nullptr;
+    bool ok = hipStreamBeginCapture(m->capture_stream, hipStreamCaptureModeRelaxed) == hipSuccess;
+    if (ok) {
+        launch_decode_step(*m, rule, out_seq_dev, m->capture_stream);
+        ok = hipStreamEndCapture(m->capture_stream, &graph) == hipSuccess && graph != nullptr;
+    }
+    if (ok) ok = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0) == hipSuccess;
+    if (graph) (void)hipGraphDestroy(graph);
+    if (!ok) {
+        m->graphs_off = true;
+        (void)hipGetLastError();
+        return nullptr;
+    }
+    m->graphs.push_back(StepGraph{kw, dl, out_seq_dev, window, vocab, exec});
+    return exec;
+}
+
 static int decode_impl(Model *m, const st_trigger_rule *rule, int32_t *out_seq_dev) {
     if (m->kv_len + 1 > m->c.max_seq)
         return fail(ST_ERANGE, "KV overflow: kv_len %d + 1 > max_seq %d", m->kv_len, m->c.max_seq);
-    launch_decode_step(*m, rule, out_seq_dev);
-    if (int rc = check_launch("decode step")) return rc;
+    if (hipGraphExec_t exec = step_graph(m, rule, out_seq_dev)) {
+        ST_HIP(hipGraphLaunch(exec, m->stream));
+    } else {
+        launch_decode_step(*m, rule, out_seq_dev, m->stream);
+        if (int rc = check_launch("decode step")) return rc;
+    }
     m->kv_len += 1;
     return ST_OK;
 }
@@ -259,6 +299,8 @@ int st_model_create(const st_config *cfg, const st_weights *w, void *kv, size_t 
     m->stream = (hipStream_t)stream;
     m->kv_len = 0;
     m->timers = nullptr;
+    m->capture_stream = nullptr;
+    m->graphs_off = getenv("ST_NO_GRAPH") != nullptr;
     launch_init(*m);
     if (int rc = check_launch("workspace initialisation")) {
         delete m;
@@ -268,7 +310,13 @@ int st_model_create(const st_config *cfg, const st_weights *w, void *kv, size_t 
     return ST_OK;
 }
 
-void st_model_destroy(st_model *h) { delete reinterpret_cast<Model *>(h); }
+void st_model_destroy(st_model *h) {
+    Model *m = reinterpret_cast<Model *>(h);
+    if (!m) return;
+    for (StepGraph &g : m->graphs) (void)hipGraphExecDestroy(g.exec);
+    if (m->capture_stream) (void)hipStreamDestroy(m->capture_stream);
+    delete m;
+}
 
 int st_kv_len(const st_model *h, int32_t *out) {
     if (!h || !out) return fail(ST_EINVAL, "model or out is NULL");
@@ -353,9 +401,9 @@ int st_decode_step_timed(st_model *h, double *gateup_mean_us, double *step_us) {
     }
     if (rc == ST_OK) {
         m->timers = &t;
-        hipEventRecord(t.ev[0], m->stream);
+        (void)hipEventRecord(t.ev[0], m->stream);
         rc = decode_impl(m, nullptr, nullptr);
-        hipEventRecord(t.ev[1], m->stream);
+        (void)hipEventRecord(t.ev[1], m->stream);
         m->timers = nullptr;
         if (rc == ST_OK && hipStreamSynchronize(m->stream) != hipSuccess) rc = fail(ST_EHIP, "synchronise failed");
     }
@@ -373,7 +421,7 @@ int st_decode_step_timed(st_model *h, double *gateup_mean_us, double *step_us) {
         if (rc == ST_OK && step_us) *step_us = ms * 1e3;
     }
     for (auto &e : t.ev)
-        if (e) hipEventDestroy(e);
+        if (e) (void)hipEventDestroy(e);
     return rc;
 }
 

@@ -3,7 +3,10 @@
 // epilogues, split-K GQA attention over the KV cache, LM head with greedy arg-max.
 //
 // Every kernel takes the position and the fed token from the model's device state block,
-// so a step can be enqueued (or replayed) without the host knowing either.
+// so a step can be enqueued, captured into a graph and replayed without the host knowing
+// either.  All kernels are latency-shaped for batch 1: weight loads are issued before anything
+// that waits (the activation vector, the norm), and the RMSNorm scale is applied to the dot
+// products afterwards as a scalar.
 #include <hip/hip_ext.h>
 
 #include "st_device.h"
@@ -11,71 +14,109 @@
 
 namespace st {
 
-// ---------------------------------------------------------------------------------------
-// x vector in LDS.  A lane consumes 8 consecutive activations per 16-byte weight load; they
-// are stored as two float4 arrays (elements 0-3 and 4-7 of every group of 8) so that the
-// 64 lanes of a wave read 64 consecutive float4 from each array.
-// ---------------------------------------------------------------------------------------
-__device__ __forceinline__ int xs_slot(int e, int half) { return ((e >> 3) << 2) + (e & 3) + ((e >> 2) & 1) * half; }
+__device__ __forceinline__ u32x4 ldw(const u32x4 *p) { return __builtin_nontemporal_load(p); }
 
-constexpr int kMaxChunk = 8192;  // floats of x staged at once
+// ---------------------------------------------------------------------------------------
+// Activation vector in LDS for the kernels whose input is rmsnorm(x) * g.  A lane consumes 8
+// consecutive activations per 16-byte weight load; they are kept as two float4 arrays (elements
+// 0-3 and 4-7 of every group of 8) so that 64 lanes read 64 consecutive float4 from each.
+// The vector stored is x * g; the 1/rms factor is returned and applied to the dot products.
+// n <= 8192, 256 threads.  Ends with the block's only barrier.
+// ---------------------------------------------------------------------------------------
+// XI = 16-byte groups of x per thread: 1 covers n <= 2048, 4 covers n <= 8192.
+template <int XI>
+struct XRegs {
+    float4 a[XI], b[XI];
+    u32x4 g[XI];
+};
 
-// Dot products of NR weight rows with the staged x chunk.  wrow[r] points at the first
-// 16-byte group of row r inside the chunk; n8 = number of 8-element groups in the chunk.
-template <int NR>
-__device__ __forceinline__ void wave_rows_dot(const u32x4 *const (&wrow)[NR], const float *xs, int half,
-                                              int n8, int lane, float (&acc)[NR]) {
-    const float4 *xa = reinterpret_cast<const float4 *>(xs);
-    const float4 *xb = reinterpret_cast<const float4 *>(xs + half);
-    int c = lane;
-    for (; c + 64 < n8; c += 128) {
-        u32x4 w0[NR], w1[NR];
+template <int XI>
+__device__ __forceinline__ void xload(const float *__restrict__ x, const bf16_t *__restrict__ g, int n8,
+                                      XRegs<XI> &r) {
 #pragma unroll
-        for (int r = 0; r < NR; ++r) {
-            w0[r] = __builtin_nontemporal_load(wrow[r] + c);
-            w1[r] = __builtin_nontemporal_load(wrow[r] + c + 64);
+    for (int i = 0; i < XI; ++i) {
+        int c = threadIdx.x + i * 256;
+        if (c < n8) {
+            r.a[i] = reinterpret_cast<const float4 *>(x)[2 * c];
+            r.b[i] = reinterpret_cast<const float4 *>(x)[2 * c + 1];
+            r.g[i] = reinterpret_cast<const u32x4 *>(g)[c];
         }
-        float4 a0 = xa[c], b0 = xb[c], a1 = xa[c + 64], b1 = xb[c + 64];
-#pragma unroll
-        for (int r = 0; r < NR; ++r) {
-            acc[r] = dot8(w0[r], a0, b0, acc[r]);
-            acc[r] = dot8(w1[r], a1, b1, acc[r]);
-        }
-    }
-    if (c < n8) {
-        u32x4 w0[NR];
-#pragma unroll
-        for (int r = 0; r < NR; ++r) w0[r] = __builtin_nontemporal_load(wrow[r] + c);
-        float4 a0 = xa[c], b0 = xb[c];
-#pragma unroll
-        for (int r = 0; r < NR; ++r) acc[r] = dot8(w0[r], a0, b0, acc[r]);
     }
 }
 
-// Stages rmsnorm(x) * g (whole vector, n <= kMaxChunk) into xs.  256 threads.
-__device__ __forceinline__ void stage_rmsnorm(const float *__restrict__ x, const bf16_t *__restrict__ g, int n,
-                                              float eps, float *xs, float *red) {
-    int half = n >> 1;
+template <int XI>
+__device__ __forceinline__ float xstage(const XRegs<XI> &r, int n, float eps, float *xs, float *red) {
+    const int n8 = n >> 3;
+    float4 *xa = reinterpret_cast<float4 *>(xs);
+    float4 *xb = reinterpret_cast<float4 *>(xs + (n >> 1));
     float ss = 0.f;
-    for (int i = threadIdx.x; i < n; i += 256) {
-        float v = x[i];
-        ss = fmaf(v, v, ss);
-        xs[xs_slot(i, half)] = v;
+#pragma unroll
+    for (int i = 0; i < XI; ++i) {
+        int c = threadIdx.x + i * 256;
+        if (c < n8) {
+            float4 a = r.a[i], b = r.b[i];
+            ss += a.x * a.x + a.y * a.y + a.z * a.z + a.w * a.w + b.x * b.x + b.y * b.y + b.z * b.z + b.w * b.w;
+            u32x4 g = r.g[i];
+            xa[c] = make_float4(a.x * bf16_lo(g.x), a.y * bf16_hi(g.x), a.z * bf16_lo(g.y), a.w * bf16_hi(g.y));
+            xb[c] = make_float4(b.x * bf16_lo(g.z), b.y * bf16_hi(g.z), b.z * bf16_lo(g.w), b.w * bf16_hi(g.w));
+        }
     }
-    ss = block_sum_256(ss, red);
-    float inv = 1.0f / sqrtf(ss / (float)n + eps);
-    for (int i = threadIdx.x; i < n; i += 256) {
-        int s = xs_slot(i, half);
-        xs[s] = xs[s] * inv * bf16_to_f32(g[i]);
-    }
+    ss = wave_sum(ss);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
     __syncthreads();
+    ss = red[0] + red[1] + red[2] + red[3];
+    return 1.0f / sqrtf(ss / (float)n + eps);
 }
 
-__device__ __forceinline__ void stage_plain(const float *__restrict__ v, int n, float *xs) {
-    int half = n >> 1;
-    for (int i = threadIdx.x; i < n; i += 256) xs[xs_slot(i, half)] = v[i];
-    __syncthreads();
-}
+// Weight rows of one wave: the first PF 16-byte groups per lane are fetched up front (before the
+// activation vector is waited for), the rest in the loop.
+template <int NR, int PF>
+struct RowFetch {
+    const u32x4 *p[NR];
+    u32x4 w[PF][NR];
+    __device__ __forceinline__ void prefetch(int n8, int lane) {
+        const u32x4 zero = {0, 0, 0, 0};
+#pragma unroll
+        for (int f = 0; f < PF; ++f)
+#pragma unroll
+            for (int r = 0; r < NR; ++r) w[f][r] = lane + 64 * f < n8 ? ldw(p[r] + lane + 64 * f) : zero;
+    }
+    __device__ __forceinline__ void dot(const float *xs, int n, int lane, float (&acc)[NR]) const {
+        const int n8 = n >> 3;
+        const float4 *xa = reinterpret_cast<const float4 *>(xs);
+        const float4 *xb = reinterpret_cast<const float4 *>(xs + (n >> 1));
+#pragma unroll
+        for (int f = 0; f < PF; ++f) {
+            int c = min(lane + 64 * f, n8 - 1);  // out-of-range lanes hold zero weights
+            float4 a = xa[c], b = xb[c];
+#pragma unroll
+            for (int r = 0; r < NR; ++r) acc[r] = dot8(w[f][r], a, b, acc[r]);
+        }
+        int c = lane + 64 * PF;
+        for (; c + 64 < n8; c += 128) {
+            u32x4 u0[NR], u1[NR];
+#pragma unroll
+            for (int r = 0; r < NR; ++r) {
+                u0[r] = ldw(p[r] + c);
+                u1[r] = ldw(p[r] + c + 64);
+            }
+            float4 a0 = xa[c], b0 = xb[c], a1 = xa[c + 64], b1 = xb[c + 64];
+#pragma unroll
+            for (int r = 0; r < NR; ++r) {
+                acc[r] = dot8(u0[r], a0, b0, acc[r]);
+                acc[r] = dot8(u1[r], a1, b1, acc[r]);
+            }
+        }
+        if (c < n8) {
+            u32x4 u0[NR];
+#pragma unroll
+            for (int r = 0; r < NR; ++r) u0[r] = ldw(p[r] + c);
+            float4 a0 = xa[c], b0 = xb[c];
+#pragma unroll
+            for (int r = 0; r < NR; ++r) acc[r] = dot8(u0[r], a0, b0, acc[r]);
+        }
+    }
+};
 
 // ---------------------------------------------------------------------------------------
 // state / embedding
@@ -111,9 +152,9 @@ __global__ __launch_bounds__(256) void k_embed(const bf16_t *__restrict__ E, int
 // ---------------------------------------------------------------------------------------
 // QKV projection: rmsnorm prologue, bias, rotate-half RoPE on q and k, K/V appended to the cache.
 // A wave owns R "units"; unit u is the row pair (i, i + d/2) of one head so that the rotation
-// needs no exchange.
+// needs no exchange.  One group of units per wave (the grid covers all of them).
 // ---------------------------------------------------------------------------------------
-template <int R>
+template <int R, int XI>
 __global__ __launch_bounds__(256) void k_qkv_rope(const bf16_t *__restrict__ W, const bf16_t *__restrict__ bias,
                                                   const float *__restrict__ x, const bf16_t *__restrict__ g,
                                                   const int32_t *__restrict__ state, const float2 *__restrict__ rope,
@@ -122,37 +163,41 @@ __global__ __launch_bounds__(256) void k_qkv_rope(const bf16_t *__restrict__ W, 
                                                   int max_seq, float eps) {
     extern __shared__ __align__(16) float xs[];
     __shared__ float red[4];
-    stage_rmsnorm(x, g, h, eps, xs, red);
-
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int half_d = d >> 1;
+    const int half_d = d >> 1, n8 = h >> 3;
     const int n_units = (nq + 2 * nkv) * half_d;
     const int u0 = (blockIdx.x * 4 + wave) * R;
-    if (u0 >= n_units) return;
-    const int n8 = h >> 3;
-    const u32x4 *wrow[2 * R];
-    float acc[2 * R];
+
+    XRegs<XI> xr;
+    xload(x, g, n8, xr);
+    RowFetch<2 * R, (XI == 1 ? 3 : 2)> rf;
     int row0[R];
 #pragma unroll
     for (int j = 0; j < R; ++j) {
         int u = min(u0 + j, n_units - 1);
         int head = u / half_d, i = u - head * half_d;
         row0[j] = head * d + i;
-        wrow[2 * j] = reinterpret_cast<const u32x4 *>(W + (size_t)row0[j] * h);
-        wrow[2 * j + 1] = reinterpret_cast<const u32x4 *>(W + (size_t)(row0[j] + half_d) * h);
-        acc[2 * j] = acc[2 * j + 1] = 0.f;
+        rf.p[2 * j] = reinterpret_cast<const u32x4 *>(W + (size_t)row0[j] * h);
+        rf.p[2 * j + 1] = reinterpret_cast<const u32x4 *>(W + (size_t)(row0[j] + half_d) * h);
     }
-    wave_rows_dot<2 * R>(wrow, xs, h >> 1, n8, lane, acc);
+    rf.prefetch(n8, lane);
+    const int pos = state[kPos];
+    const float inv = xstage(xr, h, eps, xs, red);
+    if (u0 >= n_units) return;
+
+    float acc[2 * R];
+#pragma unroll
+    for (int r = 0; r < 2 * R; ++r) acc[r] = 0.f;
+    rf.dot(xs, h, lane, acc);
 #pragma unroll
     for (int r = 0; r < 2 * R; ++r) acc[r] = wave_sum(acc[r]);
 
-    const int pos = state[kPos];
 #pragma unroll
     for (int j = 0; j < R; ++j) {
         if (lane == j && u0 + j < n_units) {
             int r0 = row0[j], r1 = r0 + half_d;
             int head = r0 / d, i = r0 - head * d;
-            float lo = acc[2 * j], hi = acc[2 * j + 1];
+            float lo = acc[2 * j] * inv, hi = acc[2 * j + 1] * inv;
             if (bias) {
                 lo += bf16_to_f32(bias[r0]);
                 hi += bf16_to_f32(bias[r1]);
@@ -181,68 +226,118 @@ __global__ __launch_bounds__(256) void k_qkv_rope(const bf16_t *__restrict__ W, 
 }
 
 // ---------------------------------------------------------------------------------------
-// y[i] = res[i] + W[i,:] . v   (O projection and down projection; res may alias y)
-// ---------------------------------------------------------------------------------------
-template <int NR>
-__global__ __launch_bounds__(256) void k_gemv_residual(const bf16_t *__restrict__ W, const float *__restrict__ v,
-                                                       const float *res, float *y, int N, int K) {
-    extern __shared__ __align__(16) float xs[];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int r0 = (blockIdx.x * 4 + wave) * NR;
-    float acc[NR];
-#pragma unroll
-    for (int r = 0; r < NR; ++r) acc[r] = 0.f;
-    for (int k0 = 0; k0 < K; k0 += kMaxChunk) {
-        int kc = min(kMaxChunk, K - k0);
-        if (k0 > 0) __syncthreads();
-        stage_plain(v + k0, kc, xs);
-        if (r0 < N) {
-            const u32x4 *wrow[NR];
-#pragma unroll
-            for (int r = 0; r < NR; ++r)
-                wrow[r] = reinterpret_cast<const u32x4 *>(W + (size_t)min(r0 + r, N - 1) * K + k0);
-            wave_rows_dot<NR>(wrow, xs, kc >> 1, kc >> 3, lane, acc);
-        }
-    }
-    if (r0 >= N) return;
-#pragma unroll
-    for (int r = 0; r < NR; ++r) acc[r] = wave_sum(acc[r]);
-#pragma unroll
-    for (int r = 0; r < NR; ++r)
-        if (lane == r && r0 + r < N) y[r0 + r] = res[r0 + r] + acc[r];
-}
-
-// ---------------------------------------------------------------------------------------
 // a[i] = silu(Wg[i,:] . y) * (Wu[i,:] . y),  y = rmsnorm(x) * g.  Gate rows [0,I), up rows [I,2I).
+// A wave owns a balanced contiguous range of pairs and walks it R pairs at a time.
 // ---------------------------------------------------------------------------------------
-template <int R>
+template <int R, int XI, bool ONE>
 __global__ __launch_bounds__(256) void k_gateup_swiglu(const bf16_t *__restrict__ W, const float *__restrict__ x,
                                                        const bf16_t *__restrict__ g, float *__restrict__ a, int h,
                                                        int I, float eps) {
     extern __shared__ __align__(16) float xs[];
     __shared__ float red[4];
-    stage_rmsnorm(x, g, h, eps, xs, red);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int u0 = (blockIdx.x * 4 + wave) * R;
-    if (u0 >= I) return;
-    const u32x4 *wrow[2 * R];
-    float acc[2 * R];
+    const int n8 = h >> 3;
+    const long nw = (long)gridDim.x * 4, wg = (long)blockIdx.x * 4 + wave;
+    // ONE: the grid has a wave for every group of R pairs; otherwise a balanced contiguous range per wave
+    const int ub = ONE ? (int)min((long)I, wg * R) : (int)((long)I * wg / nw);
+    const int ue = ONE ? min(I, ub + R) : (int)((long)I * (wg + 1) / nw);
+
+    XRegs<XI> xr;
+    xload(x, g, n8, xr);
+    RowFetch<2 * R, (XI == 1 ? 3 : 2)> rf;
+    auto point = [&](int u0) {
 #pragma unroll
-    for (int j = 0; j < R; ++j) {
-        int u = min(u0 + j, I - 1);
-        wrow[2 * j] = reinterpret_cast<const u32x4 *>(W + (size_t)u * h);
-        wrow[2 * j + 1] = reinterpret_cast<const u32x4 *>(W + (size_t)(I + u) * h);
-        acc[2 * j] = acc[2 * j + 1] = 0.f;
-    }
-    wave_rows_dot<2 * R>(wrow, xs, h >> 1, h >> 3, lane, acc);
-#pragma unroll
-    for (int r = 0; r < 2 * R; ++r) acc[r] = wave_sum(acc[r]);
-#pragma unroll
-    for (int j = 0; j < R; ++j)
-        if (lane == j && u0 + j < I) {
-            float gt = acc[2 * j], up = acc[2 * j + 1];
-            a[u0 + j] = gt / (1.0f + expf(-gt)) * up;
+        for (int j = 0; j < R; ++j) {
+            int u = min(u0 + j, I - 1);
+            rf.p[2 * j] = reinterpret_cast<const u32x4 *>(W + (size_t)u * h);
+            rf.p[2 * j + 1] = reinterpret_cast<const u32x4 *>(W + (size_t)(I + u) * h);
         }
+    };
+    point(ub);
+    if (ub < ue) rf.prefetch(n8, lane);
+    const float inv = xstage(xr, h, eps, xs, red);
+
+    auto group = [&](int u0) {
+        float acc[2 * R];
+#pragma unroll
+        for (int r = 0; r < 2 * R; ++r) acc[r] = 0.f;
+        rf.dot(xs, h, lane, acc);
+#pragma unroll
+        for (int r = 0; r < 2 * R; ++r) acc[r] = wave_sum(acc[r]);
+#pragma unroll
+        for (int j = 0; j < R; ++j)
+            if (lane == j && u0 + j < ue) {
+                float gt = acc[2 * j] * inv, up = acc[2 * j + 1] * inv;
+                a[u0 + j] = gt / (1.0f + expf(-gt)) * up;
+            }
+    };
+    if (ONE) {
+        if (ub < ue) group(ub);
+    } else {
+        for (int u0 = ub; u0 < ue; u0 += R) {
+            if (u0 != ub) {
+                point(u0);
+                rf.prefetch(n8, lane);
+            }
+            group(u0);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// y[i] = res[i] + W[i,:] . v   (O projection and down projection; res may alias y).
+// A block owns RB rows; its four waves split K and combine through LDS.  The activation vector is
+// read straight from global memory (L2) next to the weights: no staging, no barrier before the loads.
+// ---------------------------------------------------------------------------------------
+template <int RB>
+__global__ __launch_bounds__(256) void k_gemv_residual(const bf16_t *__restrict__ W, const float *__restrict__ v,
+                                                       const float *res, float *y, int N, int K) {
+    __shared__ float part[4][RB];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int r0 = blockIdx.x * RB;
+    const int n8 = K >> 3;
+    const int cb = (int)((long)n8 * wave / 4), ce = (int)((long)n8 * (wave + 1) / 4);
+    const u32x4 *wrow[RB];
+#pragma unroll
+    for (int r = 0; r < RB; ++r) wrow[r] = reinterpret_cast<const u32x4 *>(W + (size_t)min(r0 + r, N - 1) * K);
+    const float4 *xv = reinterpret_cast<const float4 *>(v);
+    float acc[RB];
+#pragma unroll
+    for (int r = 0; r < RB; ++r) acc[r] = 0.f;
+    int c = cb + lane;
+    for (; c + 64 < ce; c += 128) {
+        u32x4 w0[RB], w1[RB];
+#pragma unroll
+        for (int r = 0; r < RB; ++r) {
+            w0[r] = ldw(wrow[r] + c);
+            w1[r] = ldw(wrow[r] + c + 64);
+        }
+        float4 a0 = xv[2 * c], b0 = xv[2 * c + 1], a1 = xv[2 * (c + 64)], b1 = xv[2 * (c + 64) + 1];
+#pragma unroll
+        for (int r = 0; r < RB; ++r) {
+            acc[r] = dot8(w0[r], a0, b0, acc[r]);
+            acc[r] = dot8(w1[r], a1, b1, acc[r]);
+        }
+    }
+    if (c < ce) {
+        u32x4 w0[RB];
+#pragma unroll
+        for (int r = 0; r < RB; ++r) w0[r] = ldw(wrow[r] + c);
+        float4 a0 = xv[2 * c], b0 = xv[2 * c + 1];
+#pragma unroll
+        for (int r = 0; r < RB; ++r) acc[r] = dot8(w0[r], a0, b0, acc[r]);
+    }
+#pragma unroll
+    for (int r = 0; r < RB; ++r) acc[r] = wave_sum(acc[r]);
+    if (lane == 0) {
+#pragma unroll
+        for (int r = 0; r < RB; ++r) part[wave][r] = acc[r];
+    }
+    __syncthreads();
+    if (threadIdx.x < RB && r0 + (int)threadIdx.x < N) {
+        int r = threadIdx.x;
+        y[r0 + r] = res[r0 + r] + ((part[0][r] + part[1][r]) + (part[2][r] + part[3][r]));
+    }
 }
 
 // ---------------------------------------------------------------------------------------
@@ -257,6 +352,7 @@ __device__ __forceinline__ void amax_merge(float &v, int &i, float v2, int i2) {
 
 constexpr int kLmRows = 4;  // rows per wave per pass
 
+template <int XI>
 __global__ __launch_bounds__(256) void k_lm_head(const bf16_t *__restrict__ W, const float *__restrict__ x,
                                                  const bf16_t *__restrict__ g, float *__restrict__ logits,
                                                  float *__restrict__ pval, int32_t *__restrict__ pidx, int h, int V,
@@ -265,26 +361,41 @@ __global__ __launch_bounds__(256) void k_lm_head(const bf16_t *__restrict__ W, c
     __shared__ float red[4];
     __shared__ float bv[4];
     __shared__ int bi[4];
-    stage_rmsnorm(x, g, h, eps, xs, red);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int n8 = h >> 3;
+    const long nw = (long)gridDim.x * 4, wg = (long)blockIdx.x * 4 + wave;
+    const int groups = (V + kLmRows - 1) / kLmRows;
+    const int gb = (int)((long)groups * wg / nw), ge = (int)((long)groups * (wg + 1) / nw);
+
+    XRegs<XI> xr;
+    xload(x, g, n8, xr);
+    RowFetch<kLmRows, (XI == 1 ? 3 : 2)> rf;
+    auto point = [&](int r0) {
+#pragma unroll
+        for (int r = 0; r < kLmRows; ++r) rf.p[r] = reinterpret_cast<const u32x4 *>(W + (size_t)min(r0 + r, V - 1) * h);
+    };
+    point(gb * kLmRows);
+    if (gb < ge) rf.prefetch(n8, lane);
+    const float inv = xstage(xr, h, eps, xs, red);
+
     float best = -INFINITY;
     int besti = 0x7fffffff;
-    const int rows_per_pass = gridDim.x * 4 * kLmRows;
-    for (int r0 = (blockIdx.x * 4 + wave) * kLmRows; r0 < V; r0 += rows_per_pass) {
-        const u32x4 *wrow[kLmRows];
+    for (int gi = gb; gi < ge; ++gi) {
+        const int r0 = gi * kLmRows;
+        if (gi != gb) {
+            point(r0);
+            rf.prefetch(n8, lane);
+        }
         float acc[kLmRows];
 #pragma unroll
-        for (int r = 0; r < kLmRows; ++r) {
-            wrow[r] = reinterpret_cast<const u32x4 *>(W + (size_t)min(r0 + r, V - 1) * h);
-            acc[r] = 0.f;
-        }
-        wave_rows_dot<kLmRows>(wrow, xs, h >> 1, h >> 3, lane, acc);
+        for (int r = 0; r < kLmRows; ++r) acc[r] = 0.f;
+        rf.dot(xs, h, lane, acc);
 #pragma unroll
         for (int r = 0; r < kLmRows; ++r) acc[r] = wave_sum(acc[r]);
 #pragma unroll
         for (int r = 0; r < kLmRows; ++r)
             if (r0 + r < V) {
-                float val = acc[r];
+                float val = acc[r] * inv;
                 if (lane == r) logits[r0 + r] = val;
                 if (val == val) amax_merge(best, besti, val, r0 + r);  // NaN never wins
             }
@@ -348,26 +459,41 @@ __global__ __launch_bounds__(256) void k_argmax_final(const float *__restrict__ 
 
 // ---------------------------------------------------------------------------------------
 // GQA decode attention, split over the key range.  Block (s, g): kv head g, key range s, all G
-// query heads of the group.  D/8 lanes share one key (16 bytes of K and of V each); online
-// softmax in base 2 per lane group; groups, then waves, are merged; the last block to finish
-// for a kv head merges the ranges (fixed order, so the result does not depend on timing).
+// query heads of the group.  D/8 lanes share one key (16 bytes of K and of V each) and take 4
+// keys per pass: one running-max update per pass, softmax in base 2.  Lane groups, then waves,
+// are merged; the last block to finish for a kv head merges the ranges in a fixed order, so the
+// result does not depend on timing.
 // ---------------------------------------------------------------------------------------
 __device__ __forceinline__ float merge_w(float m, float M) { return m == -INFINITY ? 0.f : exp2f(m - M); }
+
+constexpr int kKeysPerPass = 4;
+
+__device__ __forceinline__ void unpack8(const uint4 &w, float (&f)[8]) {
+    f[0] = bf16_lo(w.x);
+    f[1] = bf16_hi(w.x);
+    f[2] = bf16_lo(w.y);
+    f[3] = bf16_hi(w.y);
+    f[4] = bf16_lo(w.z);
+    f[5] = bf16_hi(w.z);
+    f[6] = bf16_lo(w.w);
+    f[7] = bf16_hi(w.w);
+}
 
 template <int D, int G>
 __global__ __launch_bounds__(256) void k_attn_decode(const float *__restrict__ q, const bf16_t *__restrict__ kc,
                                                      const bf16_t *__restrict__ vc, const int32_t *__restrict__ state,
                                                      int max_seq, int S, float *part_ml, float *part_acc,
                                                      int32_t *counters, float *__restrict__ out) {
-    constexpr int LPK = D / 8;     // lanes per key
-    constexpr int KPW = 64 / LPK;  // keys per wave per pass
+    constexpr int LPK = D / 8;                    // lanes per key
+    constexpr int KPW = 64 / LPK;                 // lane groups per wave
+    constexpr int PASS = 4 * KPW * kKeysPerPass;  // keys one block covers per pass
     __shared__ float sm_ml[4][G][2];
     __shared__ float sm_acc[4][G][D];
     __shared__ int is_last;
 
     const int t = state[kPos] + 1;  // keys 0..pos, the new one included
     int chunk = (t + S - 1) / S;
-    chunk = max(64, (chunk + 15) & ~15);
+    chunk = ((chunk + PASS - 1) / PASS) * PASS;
     const int s_active = (t + chunk - 1) / chunk;
     const int s = blockIdx.x, g = blockIdx.y;
     if (s >= s_active) return;
@@ -376,45 +502,79 @@ __global__ __launch_bounds__(256) void k_attn_decode(const float *__restrict__ q
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int slot = lane / LPK, dl = lane % LPK;
     const float scale = 1.4426950408889634f / sqrtf((float)D);
+    const uint4 *kb = reinterpret_cast<const uint4 *>(kc + (size_t)g * max_seq * D);
+    const uint4 *vb = reinterpret_cast<const uint4 *>(vc + (size_t)g * max_seq * D);
+    const uint4 zero4 = make_uint4(0, 0, 0, 0);
 
     float qf[G][8], acc[G][8], m[G], l[G];
 #pragma unroll
     for (int hh = 0; hh < G; ++hh) {
-        const float *qp = q + (size_t)(g * G + hh) * D + dl * 8;
+        const float4 *qp = reinterpret_cast<const float4 *>(q + (size_t)(g * G + hh) * D + dl * 8);
+        float4 qa = qp[0], qb = qp[1];
+        qf[hh][0] = qa.x * scale;
+        qf[hh][1] = qa.y * scale;
+        qf[hh][2] = qa.z * scale;
+        qf[hh][3] = qa.w * scale;
+        qf[hh][4] = qb.x * scale;
+        qf[hh][5] = qb.y * scale;
+        qf[hh][6] = qb.z * scale;
+        qf[hh][7] = qb.w * scale;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            qf[hh][e] = qp[e] * scale;
-            acc[hh][e] = 0.f;
-        }
+        for (int e = 0; e < 8; ++e) acc[hh][e] = 0.f;
         m[hh] = -INFINITY;
         l[hh] = 0.f;
     }
-    const uint4 *kb = reinterpret_cast<const uint4 *>(kc + (size_t)g * max_seq * D);
-    const uint4 *vb = reinterpret_cast<const uint4 *>(vc + (size_t)g * max_seq * D);
-    for (int j = k0 + wave * KPW + slot; j < k1; j += 4 * KPW) {
-        uint4 kk = kb[(size_t)j * LPK + dl];
-        uint4 vv = vb[(size_t)j * LPK + dl];
-        float kf[8] = {bf16_lo(kk.x), bf16_hi(kk.x), bf16_lo(kk.y), bf16_hi(kk.y),
-                       bf16_lo(kk.z), bf16_hi(kk.z), bf16_lo(kk.w), bf16_hi(kk.w)};
-        float vf[8] = {bf16_lo(vv.x), bf16_hi(vv.x), bf16_lo(vv.y), bf16_hi(vv.y),
-                       bf16_lo(vv.z), bf16_hi(vv.z), bf16_lo(vv.w), bf16_hi(vv.w)};
+    // this lane group's keys of a pass: base + i * (4 * KPW), i = 0..3
+    for (int base = k0 + wave * KPW + slot; base < k1; base += PASS) {
+        uint4 kk[kKeysPerPass], vv[kKeysPerPass];
+#pragma unroll
+        for (int i = 0; i < kKeysPerPass; ++i) {
+            int j = base + i * 4 * KPW;
+            bool ok = j < k1;
+            kk[i] = ok ? kb[(size_t)j * LPK + dl] : zero4;
+            vv[i] = ok ? vb[(size_t)j * LPK + dl] : zero4;
+        }
+        float sc[kKeysPerPass][G];
+#pragma unroll
+        for (int i = 0; i < kKeysPerPass; ++i) {
+            float kf[8];
+            unpack8(kk[i], kf);
+            bool ok = base + i * 4 * KPW < k1;
+#pragma unroll
+            for (int hh = 0; hh < G; ++hh) {
+                float d0 = 0.f;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) d0 = fmaf(qf[hh][e], kf[e], d0);
+#pragma unroll
+                for (int o = 1; o < LPK; o <<= 1) d0 += __shfl_xor(d0, o, kWave);
+                sc[i][hh] = ok ? d0 : -INFINITY;
+            }
+        }
 #pragma unroll
         for (int hh = 0; hh < G; ++hh) {
-            float sc = 0.f;
+            float mn = m[hh];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) sc = fmaf(qf[hh][e], kf[e], sc);
-#pragma unroll
-            for (int o = 1; o < LPK; o <<= 1) sc += __shfl_xor(sc, o, kWave);
-            float mn = fmaxf(m[hh], sc);
-            float c = merge_w(m[hh], mn);
-            float p = exp2f(sc - mn);
-            l[hh] = l[hh] * c + p;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) acc[hh][e] = acc[hh][e] * c + p * vf[e];
+            for (int i = 0; i < kKeysPerPass; ++i) mn = fmaxf(mn, sc[i][hh]);
+            float c = merge_w(m[hh], mn);  // the pass's first key is always valid, so mn is finite
             m[hh] = mn;
+            l[hh] *= c;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[hh][e] *= c;
+        }
+#pragma unroll
+        for (int i = 0; i < kKeysPerPass; ++i) {
+            float vf[8];
+            unpack8(vv[i], vf);
+#pragma unroll
+            for (int hh = 0; hh < G; ++hh) {
+                float p = exp2f(sc[i][hh] - m[hh]);  // exp2(-inf) = 0 for keys past the range
+                l[hh] += p;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) acc[hh][e] = fmaf(p, vf[e], acc[hh][e]);
+            }
         }
     }
-    // merge the KPW lane groups of the wave
+    // merge the lane groups of the wave
 #pragma unroll
     for (int o = LPK; o < 64; o <<= 1) {
 #pragma unroll
@@ -454,13 +614,18 @@ __global__ __launch_bounds__(256) void k_attn_decode(const float *__restrict__ q
             L += sm_ml[w][hh][1] * ww;
             A += sm_acc[w][hh][e] * ww;
         }
-        size_t pi = (size_t)(g * G + hh) * S + s;
-        part_acc[pi * D + e] = A;
-        if (e == 0) {
-            part_ml[pi * 2] = M;
-            part_ml[pi * 2 + 1] = L;
+        if (s_active == 1) {  // short context: this block has the whole answer
+            out[(size_t)(g * G + hh) * D + e] = A / L;
+        } else {
+            size_t pi = (size_t)(g * G + hh) * S + s;
+            part_acc[pi * D + e] = A;
+            if (e == 0) {
+                part_ml[pi * 2] = M;
+                part_ml[pi * 2 + 1] = L;
+            }
         }
     }
+    if (s_active == 1) return;
     __threadfence();
     __syncthreads();
     if (threadIdx.x == 0) {
@@ -476,7 +641,23 @@ __global__ __launch_bounds__(256) void k_attn_decode(const float *__restrict__ q
         float M = -INFINITY;
         for (int i = 0; i < s_active; ++i) M = fmaxf(M, part_ml[(p0 + i) * 2]);
         float L = 0.f, A = 0.f;
-        for (int i = 0; i < s_active; ++i) {
+        int i = 0;
+        for (; i + 4 <= s_active; i += 4) {
+            float mm[4], ll[4], aa[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                mm[u] = part_ml[(p0 + i + u) * 2];
+                ll[u] = part_ml[(p0 + i + u) * 2 + 1];
+                aa[u] = part_acc[(p0 + i + u) * D + e];
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                float ww = merge_w(mm[u], M);
+                L += ll[u] * ww;
+                A += aa[u] * ww;
+            }
+        }
+        for (; i < s_active; ++i) {
             float ww = merge_w(part_ml[(p0 + i) * 2], M);
             L += part_ml[(p0 + i) * 2 + 1] * ww;
             A += part_acc[(p0 + i) * D + e] * ww;
@@ -489,13 +670,6 @@ __global__ __launch_bounds__(256) void k_attn_decode(const float *__restrict__ q
 // ---------------------------------------------------------------------------------------
 // launchers
 // ---------------------------------------------------------------------------------------
-static int pick_rows(int units, int max_r) {
-    // most rows per wave that still leaves >= 2048 waves (8 per CU), at least 1
-    int r = max_r;
-    while (r > 1 && (units + r - 1) / r < 2048) r >>= 1;
-    return r;
-}
-
 void launch_init(const Model &m) {
     const st_config &c = m.c;
     hipLaunchKernelGGL(k_init, dim3(256), dim3(256), 0, m.stream, m.ws.state, m.ws.counters, c.n_kv_heads,
@@ -512,16 +686,16 @@ void launch_set_state(const Model &m, int slot, int32_t value) {
 }
 
 template <int D>
-static void launch_attn(const Model &m, int layer) {
+static void launch_attn(const Model &m, int layer, hipStream_t stream) {
     const st_config &c = m.c;
     const int G = c.n_q_heads / c.n_kv_heads;
     size_t lofs = (size_t)layer * c.n_kv_heads * c.max_seq * c.head_dim;
     dim3 grid(kAttnSplits, c.n_kv_heads), block(256);
-#define ST_ATTN_CASE(GG)                                                                                   \
-    case GG:                                                                                               \
-        hipLaunchKernelGGL((k_attn_decode<D, GG>), grid, block, 0, m.stream, m.ws.q1, m.kcache + lofs,     \
+#define ST_ATTN_CASE(GG)                                                                                     \
+    case GG:                                                                                                 \
+        hipLaunchKernelGGL((k_attn_decode<D, GG>), grid, block, 0, stream, m.ws.q1, m.kcache + lofs,       \
                            m.vcache + lofs, m.ws.state, c.max_seq, kAttnSplits, m.ws.part_ml, m.ws.part_acc, \
-                           m.ws.counters, m.ws.o1);                                                        \
+                           m.ws.counters, m.ws.o1);                                                          \
         break;
     switch (G) {
         ST_ATTN_CASE(1) ST_ATTN_CASE(2) ST_ATTN_CASE(3) ST_ATTN_CASE(4)
@@ -530,83 +704,129 @@ static void launch_attn(const Model &m, int layer) {
 #undef ST_ATTN_CASE
 }
 
-static void launch_gemv_residual(const Model &m, const bf16_t *W, const float *v, float *x, int N, int K) {
-    int nr = pick_rows(N, 4);
-    size_t lds = sizeof(float) * (size_t)(K < kMaxChunk ? K : kMaxChunk);
-    int rows_per_block = 4 * nr;
-    dim3 grid((N + rows_per_block - 1) / rows_per_block), block(256);
-    switch (nr) {
-        case 4: hipLaunchKernelGGL(k_gemv_residual<4>, grid, block, lds, m.stream, W, v, x, x, N, K); break;
-        case 2: hipLaunchKernelGGL(k_gemv_residual<2>, grid, block, lds, m.stream, W, v, x, x, N, K); break;
-        default: hipLaunchKernelGGL(k_gemv_residual<1>, grid, block, lds, m.stream, W, v, x, x, N, K); break;
+// Rows per block of the residual GEMV: the candidate with the least padding among those that
+// still give the chip about two blocks per CU; small matrices take the smallest candidate.
+static int pick_rb(int N) {
+    const int cand[] = {8, 7, 5, 4, 3, 2};
+    int best = 2;
+    long best_waste = -1;
+    for (int rb : cand) {
+        int blocks = (N + rb - 1) / rb;
+        if (blocks < 480) continue;
+        long waste = (long)blocks * rb - N;
+        if (best_waste < 0 || waste < best_waste) {
+            best = rb;
+            best_waste = waste;
+        }
     }
+    return best;
+}
+
+static void launch_gemv_residual(const Model &m, const bf16_t *W, const float *v, float *x, int N, int K,
+                                 hipStream_t stream) {
+    const int rb = pick_rb(N);
+    dim3 grid((N + rb - 1) / rb), block(256);
+#define ST_RB_CASE(RBV)                                                                       \
+    case RBV:                                                                                 \
+        hipLaunchKernelGGL(k_gemv_residual<RBV>, grid, block, 0, stream, W, v, x, x, N, K); \
+        break;
+    switch (rb) {
+        ST_RB_CASE(8) ST_RB_CASE(7) ST_RB_CASE(5) ST_RB_CASE(4) ST_RB_CASE(3) ST_RB_CASE(2)
+    }
+#undef ST_RB_CASE
 }
 
 void launch_head(const Model &m, const float *x_row, const st_trigger_rule *rule, int32_t advance,
-                 int32_t *out_seq_dev) {
+                 int32_t *out_seq_dev, hipStream_t stream) {
     const st_config &c = m.c;
     size_t lds = sizeof(float) * (size_t)c.hidden;
     int blocks = (c.vocab + 4 * kLmRows - 1) / (4 * kLmRows);
     if (blocks > kLmBlocks) blocks = kLmBlocks;
-    hipLaunchKernelGGL(k_lm_head, dim3(blocks), dim3(256), lds, m.stream, m.lm_head, x_row, m.final_norm,
-                       m.ws.logits, m.ws.amax_val, m.ws.amax_idx, c.hidden, c.vocab, c.rms_eps);
-    hipLaunchKernelGGL(k_argmax_final, dim3(1), dim3(256), 0, m.stream, m.ws.amax_val, m.ws.amax_idx, blocks,
+    if (c.hidden <= 2048)
+        hipLaunchKernelGGL(k_lm_head<1>, dim3(blocks), dim3(256), lds, stream, m.lm_head, x_row, m.final_norm,
+                           m.ws.logits, m.ws.amax_val, m.ws.amax_idx, c.hidden, c.vocab, c.rms_eps);
+    else
+        hipLaunchKernelGGL(k_lm_head<4>, dim3(blocks), dim3(256), lds, stream, m.lm_head, x_row, m.final_norm,
+                           m.ws.logits, m.ws.amax_val, m.ws.amax_idx, c.hidden, c.vocab, c.rms_eps);
+    hipLaunchKernelGGL(k_argmax_final, dim3(1), dim3(256), 0, stream, m.ws.amax_val, m.ws.amax_idx, blocks,
                        m.ws.state, rule ? rule->kw_bitmap : nullptr, rule ? rule->delim_bitmap : nullptr,
                        rule ? rule->window : 1, rule ? rule->vocab : 0, advance, out_seq_dev);
 }
 
-void launch_decode_layers(const Model &m, float *x) {
+// Pairs per wave-group of the gate/up kernel and its grid: one group per wave while the whole grid
+// can be resident (3 blocks of 256 threads per CU), a balanced walk over 768 blocks otherwise.
+static void gateup_shape(int I, int k_iters, int *r_out, int *blocks_out, bool *one_out) {
+    int r = k_iters <= 4 ? 3 : (k_iters <= 8 ? 2 : 1);  // keeps the up-front loads within the register file
+    int groups = (I + r - 1) / r;
+    int blocks = (groups + 3) / 4;
+    *one_out = blocks <= 768;
+    if (blocks > 768) blocks = 768;
+    *r_out = r;
+    *blocks_out = blocks;
+}
+
+void launch_decode_layers(const Model &m, float *x, hipStream_t stream) {
     const st_config &c = m.c;
     const int h = c.hidden, d = c.head_dim, nq = c.n_q_heads, nkv = c.n_kv_heads, I = c.intermediate;
     size_t lds_h = sizeof(float) * (size_t)h;
-    hipLaunchKernelGGL(k_embed, dim3((h + 255) / 256), dim3(256), 0, m.stream, m.embed, m.ws.state, x, h, c.vocab);
+    hipLaunchKernelGGL(k_embed, dim3((h + 255) / 256), dim3(256), 0, stream, m.embed, m.ws.state, x, h, c.vocab);
     const int qkv_units = (nq + 2 * nkv) * (d / 2);
-    const int r_qkv = pick_rows(qkv_units, 2);
-    const int r_gu = pick_rows(I, 4);
+    const int r_qkv = qkv_units >= 2048 ? 2 : 1;
+    const bool small_h = h <= 2048;
+    int r_gu, gu_blocks;
+    bool gu_one;
+    gateup_shape(I, (h + 511) / 512, &r_gu, &gu_blocks, &gu_one);
     for (int l = 0; l < c.n_layers; ++l) {
         size_t lofs = (size_t)l * nkv * c.max_seq * d;
         {
             dim3 grid((qkv_units + 4 * r_qkv - 1) / (4 * r_qkv)), block(256);
-            if (r_qkv == 2)
-                hipLaunchKernelGGL(k_qkv_rope<2>, grid, block, lds_h, m.stream, m.wqkv[l], m.bqkv[l], x,
-                                   m.norm_attn[l], m.ws.state, m.ws.rope, m.ws.q1, m.kcache + lofs,
-                                   m.vcache + lofs, h, nq, nkv, d, c.max_seq, c.rms_eps);
-            else
-                hipLaunchKernelGGL(k_qkv_rope<1>, grid, block, lds_h, m.stream, m.wqkv[l], m.bqkv[l], x,
-                                   m.norm_attn[l], m.ws.state, m.ws.rope, m.ws.q1, m.kcache + lofs,
-                                   m.vcache + lofs, h, nq, nkv, d, c.max_seq, c.rms_eps);
+#define ST_QKV(RR, XX)                                                                                       \
+    hipLaunchKernelGGL((k_qkv_rope<RR, XX>), grid, block, lds_h, stream, m.wqkv[l], m.bqkv[l], x,          \
+                       m.norm_attn[l], m.ws.state, m.ws.rope, m.ws.q1, m.kcache + lofs, m.vcache + lofs, h, \
+                       nq, nkv, d, c.max_seq, c.rms_eps)
+            if (r_qkv == 2 && small_h) ST_QKV(2, 1);
+            else if (r_qkv == 2) ST_QKV(2, 4);
+            else if (small_h) ST_QKV(1, 1);
+            else ST_QKV(1, 4);
+#undef ST_QKV
         }
         if (d == 128)
-            launch_attn<128>(m, l);
+            launch_attn<128>(m, l, stream);
         else
-            launch_attn<64>(m, l);
-        launch_gemv_residual(m, m.wo[l], m.ws.o1, x, h, nq * d);
+            launch_attn<64>(m, l, stream);
+        launch_gemv_residual(m, m.wo[l], m.ws.o1, x, h, nq * d, stream);
         {
-            dim3 grid((I + 4 * r_gu - 1) / (4 * r_gu)), block(256);
+            dim3 grid(gu_blocks), block(256);
             hipEvent_t e0 = m.timers ? m.timers->ev[2 + 2 * l] : nullptr;
             hipEvent_t e1 = m.timers ? m.timers->ev[3 + 2 * l] : nullptr;
-            switch (r_gu) {
-                case 4:
-                    hipExtLaunchKernelGGL(k_gateup_swiglu<4>, grid, block, lds_h, m.stream, e0, e1, 0, m.wgu[l], x,
-                                          m.norm_mlp[l], m.ws.a1, h, I, c.rms_eps);
-                    break;
-                case 2:
-                    hipExtLaunchKernelGGL(k_gateup_swiglu<2>, grid, block, lds_h, m.stream, e0, e1, 0, m.wgu[l], x,
-                                          m.norm_mlp[l], m.ws.a1, h, I, c.rms_eps);
-                    break;
-                default:
-                    hipExtLaunchKernelGGL(k_gateup_swiglu<1>, grid, block, lds_h, m.stream, e0, e1, 0, m.wgu[l], x,
-                                          m.norm_mlp[l], m.ws.a1, h, I, c.rms_eps);
-                    break;
-            }
+#define ST_GU(RR, XX)                                                                                     \
+    do {                                                                                                  \
+        if (!m.timers && gu_one)                                                                          \
+            hipLaunchKernelGGL((k_gateup_swiglu<RR, XX, true>), grid, block, lds_h, stream, m.wgu[l], x,  \
+                               m.norm_mlp[l], m.ws.a1, h, I, c.rms_eps);                                  \
+        else if (!m.timers)                                                                               \
+            hipLaunchKernelGGL((k_gateup_swiglu<RR, XX, false>), grid, block, lds_h, stream, m.wgu[l], x, \
+                               m.norm_mlp[l], m.ws.a1, h, I, c.rms_eps);                                  \
+        else if (gu_one)                                                                                  \
+            hipExtLaunchKernelGGL((k_gateup_swiglu<RR, XX, true>), grid, block, lds_h, stream, e0, e1, 0, \
+                                  m.wgu[l], x, m.norm_mlp[l], m.ws.a1, h, I, c.rms_eps);                  \
+        else                                                                                              \
+            hipExtLaunchKernelGGL((k_gateup_swiglu<RR, XX, false>), grid, block, lds_h, stream, e0, e1, 0, \
+                                  m.wgu[l], x, m.norm_mlp[l], m.ws.a1, h, I, c.rms_eps);                  \
+    } while (0)
+            if (r_gu == 3 && small_h) ST_GU(3, 1);
+            else if (r_gu == 3) ST_GU(3, 4);
+            else if (r_gu == 2) ST_GU(2, 4);
+            else ST_GU(1, 4);
+#undef ST_GU
         }
-        launch_gemv_residual(m, m.wdown[l], m.ws.a1, x, h, I);
+        launch_gemv_residual(m, m.wdown[l], m.ws.a1, x, h, I, stream);
     }
 }
 
-void launch_decode_step(const Model &m, const st_trigger_rule *rule, int32_t *out_seq_dev) {
-    launch_decode_layers(m, m.ws.x);
-    launch_head(m, m.ws.x, rule, 1, out_seq_dev);
+void launch_decode_step(const Model &m, const st_trigger_rule *rule, int32_t *out_seq_dev, hipStream_t stream) {
+    launch_decode_layers(m, m.ws.x, stream);
+    launch_head(m, m.ws.x, rule, 1, out_seq_dev, stream);
 }
 
 }  // namespace st

@@ -45,6 +45,13 @@ struct StepTimers {
     std::vector<hipEvent_t> ev;
 };
 
+// One captured decode step (all kernels of a token) for a given trigger rule / output buffer.
+struct StepGraph {
+    const void *kw, *delim, *out_seq;
+    int window, vocab;
+    hipGraphExec_t exec;
+};
+
 struct Model {
     st_config c;
     std::vector<const bf16_t *> wqkv, bqkv, wo, wgu, wdown, norm_attn, norm_mlp;
@@ -55,6 +62,9 @@ struct Model {
     int32_t kv_len;
     int qkv_dim;
     StepTimers *timers;  // non-null only inside st_decode_step_timed
+    hipStream_t capture_stream;      // private stream the step graphs are captured on (lazily created)
+    std::vector<StepGraph> graphs;
+    bool graphs_off;                 // capture failed or was disabled: steps are launched kernel by kernel
 };
 
 // Carves the workspace; with base == nullptr only sizes it.
@@ -69,12 +79,12 @@ void launch_set_state(const Model &m, int slot, int32_t value);
 // all layers, LM head, arg-max; leaves state[kTok] = greedy token and state[kPos] += 1.
 // rule may be null (state[kFired] is then 0).  out_seq (device, may be null) receives the token at
 // index state[kStep]++.
-void launch_decode_step(const Model &m, const st_trigger_rule *rule, int32_t *out_seq_dev);
+void launch_decode_step(const Model &m, const st_trigger_rule *rule, int32_t *out_seq_dev, hipStream_t stream);
 // Embedding of state[kTok] and all layers at position state[kPos], on the residual row x (fp32[hidden]).
-void launch_decode_layers(const Model &m, float *x);
+void launch_decode_layers(const Model &m, float *x, hipStream_t stream);
 // LM head + arg-max over the residual row x_row (fp32[hidden]); advances state[kPos] by `advance`.
 void launch_head(const Model &m, const float *x_row, const st_trigger_rule *rule, int32_t advance,
-                 int32_t *out_seq_dev);
+                 int32_t *out_seq_dev, hipStream_t stream);
 
 // ---- launchers (prefill.hip) ----
 // Feeds ws.tokens[0,n) at positions [pos0, pos0+n) through all layers; leaves the residual rows in ws.x.
