@@ -459,16 +459,20 @@ __global__ __launch_bounds__(256) void k_argmax_final(const float *__restrict__ 
 
 // ---------------------------------------------------------------------------------------
 // GQA decode attention, split over the key range.  Block (s, g): kv head g, key range s, all G
-// query heads of the group.  D/8 lanes share one key (16 bytes of K and of V each) and take 4
-// keys per pass: one running-max update per pass, softmax in base 2.  Lane groups, then waves,
-// are merged; the last block to finish for a kv head merges the ranges in a fixed order, so the
-// result does not depend on timing.
+// query heads of the group; keys are taken in tiles of 64.
+//   scores : lane = key, wave = quarter of head_dim; q is read from LDS as broadcasts, so there is
+//            no cross-lane reduction; the four quarters meet in LDS
+//   softmax: wave = query head, lane = key (base 2, running max / sum per head across tiles)
+//   P.V    : D/8 lanes share a key (16 bytes of V each), 64/(256/(D/8)) keys per lane group
+// Each range publishes (max, sum, unnormalised output); a second kernel merges the ranges in a
+// fixed order, so the result does not depend on timing.  A context that fits one range is
+// finished by the first kernel alone.
 // ---------------------------------------------------------------------------------------
 __device__ __forceinline__ float merge_w(float m, float M) { return m == -INFINITY ? 0.f : exp2f(m - M); }
 
-constexpr int kKeysPerPass = 4;
+constexpr int kKeyTile = 64;
 
-__device__ __forceinline__ void unpack8(const uint4 &w, float (&f)[8]) {
+__device__ __forceinline__ void unpack8(const u32x4 &w, float (&f)[8]) {
     f[0] = bf16_lo(w.x);
     f[1] = bf16_hi(w.x);
     f[2] = bf16_lo(w.y);
@@ -479,192 +483,205 @@ __device__ __forceinline__ void unpack8(const uint4 &w, float (&f)[8]) {
     f[7] = bf16_hi(w.w);
 }
 
+// Keys per range for a context of t keys split into at most S ranges (whole tiles).
+__device__ __forceinline__ int attn_chunk(int t, int S) {
+    int chunk = (t + S - 1) / S;
+    return ((chunk + kKeyTile - 1) / kKeyTile) * kKeyTile;
+}
+
 template <int D, int G>
-__global__ __launch_bounds__(256) void k_attn_decode(const float *__restrict__ q, const bf16_t *__restrict__ kc,
-                                                     const bf16_t *__restrict__ vc, const int32_t *__restrict__ state,
-                                                     int max_seq, int S, float *part_ml, float *part_acc,
-                                                     int32_t *counters, float *__restrict__ out) {
-    constexpr int LPK = D / 8;                    // lanes per key
-    constexpr int KPW = 64 / LPK;                 // lane groups per wave
-    constexpr int PASS = 4 * KPW * kKeysPerPass;  // keys one block covers per pass
-    __shared__ float sm_ml[4][G][2];
-    __shared__ float sm_acc[4][G][D];
-    __shared__ int is_last;
+__global__ __launch_bounds__(256) void k_attn_partial(const float *__restrict__ q, const bf16_t *__restrict__ kc,
+                                                      const bf16_t *__restrict__ vc, const int32_t *__restrict__ state,
+                                                      int max_seq, int S, float *__restrict__ part_ml,
+                                                      float *__restrict__ part_acc, float *__restrict__ out) {
+    constexpr int LPK = D / 8;            // lanes sharing one key in the P.V phase
+    constexpr int KSL = 256 / LPK;        // key slots of the block in the P.V phase
+    constexpr int KPS = kKeyTile / KSL;   // keys per slot per tile
+    constexpr int DS = D / 4;             // head_dim slice of one wave in the score phase
+    __shared__ __align__(16) float q_s[G][D];
+    __shared__ float sc_part[4][G][kKeyTile];
+    __shared__ float p_s[G][kKeyTile];
+    __shared__ float run_m[G], run_l[G], corr_s[G];
+    __shared__ float red_acc[4][G][D];
 
     const int t = state[kPos] + 1;  // keys 0..pos, the new one included
-    int chunk = (t + S - 1) / S;
-    chunk = ((chunk + PASS - 1) / PASS) * PASS;
+    const int chunk = attn_chunk(t, S);
     const int s_active = (t + chunk - 1) / chunk;
     const int s = blockIdx.x, g = blockIdx.y;
     if (s >= s_active) return;
     const int k0 = s * chunk, k1 = min(t, k0 + chunk);
 
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int slot = lane / LPK, dl = lane % LPK;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int dl = tid % LPK, ks = tid / LPK;
     const float scale = 1.4426950408889634f / sqrtf((float)D);
-    const uint4 *kb = reinterpret_cast<const uint4 *>(kc + (size_t)g * max_seq * D);
-    const uint4 *vb = reinterpret_cast<const uint4 *>(vc + (size_t)g * max_seq * D);
-    const uint4 zero4 = make_uint4(0, 0, 0, 0);
-
-    float qf[G][8], acc[G][8], m[G], l[G];
+    const bf16_t *kbase = kc + (size_t)g * max_seq * D;
+    const bf16_t *vbase = vc + (size_t)g * max_seq * D;
+    if (tid < G) {
+        run_m[tid] = -INFINITY;
+        run_l[tid] = 0.f;
+    }
+    float acc[G][8];
 #pragma unroll
-    for (int hh = 0; hh < G; ++hh) {
-        const float4 *qp = reinterpret_cast<const float4 *>(q + (size_t)(g * G + hh) * D + dl * 8);
-        float4 qa = qp[0], qb = qp[1];
-        qf[hh][0] = qa.x * scale;
-        qf[hh][1] = qa.y * scale;
-        qf[hh][2] = qa.z * scale;
-        qf[hh][3] = qa.w * scale;
-        qf[hh][4] = qb.x * scale;
-        qf[hh][5] = qb.y * scale;
-        qf[hh][6] = qb.z * scale;
-        qf[hh][7] = qb.w * scale;
+    for (int hh = 0; hh < G; ++hh)
 #pragma unroll
         for (int e = 0; e < 8; ++e) acc[hh][e] = 0.f;
-        m[hh] = -INFINITY;
-        l[hh] = 0.f;
+
+    // Loads of a tile: rows past the range are read from the range's last key (in bounds, finite); their
+    // scores are masked to -inf, so their probabilities are exactly 0.
+    u32x4 kreg[DS / 8], vreg[KPS];
+    auto issue = [&](int tile0) {
+        const u32x4 *kp =
+            reinterpret_cast<const u32x4 *>(kbase + (size_t)min(tile0 + lane, k1 - 1) * D + wave * DS);
+#pragma unroll
+        for (int i = 0; i < DS / 8; ++i) kreg[i] = kp[i];
+#pragma unroll
+        for (int i = 0; i < KPS; ++i)
+            vreg[i] = *reinterpret_cast<const u32x4 *>(vbase + (size_t)min(tile0 + ks + KSL * i, k1 - 1) * D + dl * 8);
+    };
+    issue(k0);  // in flight while q is staged
+    static_assert(G * D / 4 <= 256, "one float4 of q per thread");
+    {
+        float4 v = reinterpret_cast<const float4 *>(q + (size_t)g * G * D)[min(tid, G * D / 4 - 1)];
+        if (tid < G * D / 4)
+            reinterpret_cast<float4 *>(&q_s[0][0])[tid] =
+                make_float4(v.x * scale, v.y * scale, v.z * scale, v.w * scale);
     }
-    // this lane group's keys of a pass: base + i * (4 * KPW), i = 0..3
-    for (int base = k0 + wave * KPW + slot; base < k1; base += PASS) {
-        uint4 kk[kKeysPerPass], vv[kKeysPerPass];
+
+    for (int tile0 = k0; tile0 < k1; tile0 += kKeyTile) {
+        const bool ok1 = tile0 + lane < k1;
+        if (tile0 != k0) issue(tile0);
+        __syncthreads();  // q_s staged (first tile); previous tile's p_s / sc_part fully consumed
+        {
+            float pa[G];
 #pragma unroll
-        for (int i = 0; i < kKeysPerPass; ++i) {
-            int j = base + i * 4 * KPW;
-            bool ok = j < k1;
-            kk[i] = ok ? kb[(size_t)j * LPK + dl] : zero4;
-            vv[i] = ok ? vb[(size_t)j * LPK + dl] : zero4;
+            for (int hh = 0; hh < G; ++hh) pa[hh] = 0.f;
+#pragma unroll
+            for (int i = 0; i < DS / 8; ++i) {
+                float kf[8];
+                unpack8(kreg[i], kf);
+#pragma unroll
+                for (int hh = 0; hh < G; ++hh) {
+                    const float4 qa = *reinterpret_cast<const float4 *>(&q_s[hh][wave * DS + 8 * i]);
+                    const float4 qb = *reinterpret_cast<const float4 *>(&q_s[hh][wave * DS + 8 * i + 4]);
+                    float d0 = pa[hh];
+                    d0 = fmaf(qa.x, kf[0], d0);
+                    d0 = fmaf(qa.y, kf[1], d0);
+                    d0 = fmaf(qa.z, kf[2], d0);
+                    d0 = fmaf(qa.w, kf[3], d0);
+                    d0 = fmaf(qb.x, kf[4], d0);
+                    d0 = fmaf(qb.y, kf[5], d0);
+                    d0 = fmaf(qb.z, kf[6], d0);
+                    d0 = fmaf(qb.w, kf[7], d0);
+                    pa[hh] = d0;
+                }
+            }
+#pragma unroll
+            for (int hh = 0; hh < G; ++hh) sc_part[wave][hh][lane] = pa[hh];
         }
-        float sc[kKeysPerPass][G];
-#pragma unroll
-        for (int i = 0; i < kKeysPerPass; ++i) {
-            float kf[8];
-            unpack8(kk[i], kf);
-            bool ok = base + i * 4 * KPW < k1;
-#pragma unroll
-            for (int hh = 0; hh < G; ++hh) {
-                float d0 = 0.f;
-#pragma unroll
-                for (int e = 0; e < 8; ++e) d0 = fmaf(qf[hh][e], kf[e], d0);
-#pragma unroll
-                for (int o = 1; o < LPK; o <<= 1) d0 += __shfl_xor(d0, o, kWave);
-                sc[i][hh] = ok ? d0 : -INFINITY;
+        __syncthreads();
+        for (int hh = wave; hh < G; hh += 4) {
+            float sc = (sc_part[0][hh][lane] + sc_part[1][hh][lane]) + (sc_part[2][hh][lane] + sc_part[3][hh][lane]);
+            if (!ok1) sc = -INFINITY;
+            const float m_old = run_m[hh];
+            const float m_new = fmaxf(m_old, wave_max(sc));  // finite: the tile's first key is valid
+            const float p = exp2f(sc - m_new);
+            const float ps = wave_sum(p);
+            p_s[hh][lane] = p;
+            if (lane == 0) {
+                const float c = merge_w(m_old, m_new);
+                corr_s[hh] = c;
+                run_l[hh] = run_l[hh] * c + ps;
+                run_m[hh] = m_new;
             }
         }
+        __syncthreads();
 #pragma unroll
         for (int hh = 0; hh < G; ++hh) {
-            float mn = m[hh];
-#pragma unroll
-            for (int i = 0; i < kKeysPerPass; ++i) mn = fmaxf(mn, sc[i][hh]);
-            float c = merge_w(m[hh], mn);  // the pass's first key is always valid, so mn is finite
-            m[hh] = mn;
-            l[hh] *= c;
+            const float c = corr_s[hh];
 #pragma unroll
             for (int e = 0; e < 8; ++e) acc[hh][e] *= c;
         }
 #pragma unroll
-        for (int i = 0; i < kKeysPerPass; ++i) {
+        for (int i = 0; i < KPS; ++i) {
             float vf[8];
-            unpack8(vv[i], vf);
+            unpack8(vreg[i], vf);
+            const int kl = ks + KSL * i;
 #pragma unroll
             for (int hh = 0; hh < G; ++hh) {
-                float p = exp2f(sc[i][hh] - m[hh]);  // exp2(-inf) = 0 for keys past the range
-                l[hh] += p;
+                const float p = p_s[hh][kl];  // exactly 0 for keys past the range
 #pragma unroll
                 for (int e = 0; e < 8; ++e) acc[hh][e] = fmaf(p, vf[e], acc[hh][e]);
             }
         }
     }
-    // merge the lane groups of the wave
+    // sum the key slots of a wave, then the four waves
 #pragma unroll
-    for (int o = LPK; o < 64; o <<= 1) {
+    for (int o = LPK; o < 64; o <<= 1)
 #pragma unroll
-        for (int hh = 0; hh < G; ++hh) {
-            float m2 = __shfl_xor(m[hh], o, kWave), l2 = __shfl_xor(l[hh], o, kWave);
-            float M = fmaxf(m[hh], m2);
-            float w1 = merge_w(m[hh], M), w2 = merge_w(m2, M);
-            l[hh] = l[hh] * w1 + l2 * w2;
+        for (int hh = 0; hh < G; ++hh)
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                float a2 = __shfl_xor(acc[hh][e], o, kWave);
-                acc[hh][e] = acc[hh][e] * w1 + a2 * w2;
-            }
-            m[hh] = M;
-        }
-    }
+            for (int e = 0; e < 8; ++e) acc[hh][e] += __shfl_xor(acc[hh][e], o, kWave);
     if (lane < LPK) {
 #pragma unroll
-        for (int hh = 0; hh < G; ++hh) {
-            if (lane == 0) {
-                sm_ml[wave][hh][0] = m[hh];
-                sm_ml[wave][hh][1] = l[hh];
-            }
+        for (int hh = 0; hh < G; ++hh)
 #pragma unroll
-            for (int e = 0; e < 8; ++e) sm_acc[wave][hh][lane * 8 + e] = acc[hh][e];
-        }
+            for (int e = 0; e < 8; ++e) red_acc[wave][hh][lane * 8 + e] = acc[hh][e];
     }
     __syncthreads();
-    // merge the four waves and publish this range's partial result
-    for (int idx = threadIdx.x; idx < G * D; idx += 256) {
-        int hh = idx / D, e = idx - hh * D;
-        float M = fmaxf(fmaxf(sm_ml[0][hh][0], sm_ml[1][hh][0]), fmaxf(sm_ml[2][hh][0], sm_ml[3][hh][0]));
-        float L = 0.f, A = 0.f;
-#pragma unroll
-        for (int w = 0; w < 4; ++w) {
-            float ww = merge_w(sm_ml[w][hh][0], M);
-            L += sm_ml[w][hh][1] * ww;
-            A += sm_acc[w][hh][e] * ww;
-        }
-        if (s_active == 1) {  // short context: this block has the whole answer
-            out[(size_t)(g * G + hh) * D + e] = A / L;
+    for (int idx = tid; idx < G * D; idx += 256) {
+        const int hh = idx / D, e = idx - hh * D;
+        const float A = (red_acc[0][hh][e] + red_acc[1][hh][e]) + (red_acc[2][hh][e] + red_acc[3][hh][e]);
+        if (s_active == 1) {
+            out[(size_t)(g * G + hh) * D + e] = A / run_l[hh];
         } else {
-            size_t pi = (size_t)(g * G + hh) * S + s;
+            const size_t pi = (size_t)(g * G + hh) * S + s;
             part_acc[pi * D + e] = A;
             if (e == 0) {
-                part_ml[pi * 2] = M;
-                part_ml[pi * 2 + 1] = L;
+                part_ml[pi * 2] = run_m[hh];
+                part_ml[pi * 2 + 1] = run_l[hh];
             }
         }
     }
-    if (s_active == 1) return;
-    __threadfence();
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        int prev = atomicAdd(&counters[g], 1);
-        is_last = (prev == s_active - 1);
-    }
-    __syncthreads();
-    if (!is_last) return;
-    __threadfence();
-    for (int idx = threadIdx.x; idx < G * D; idx += 256) {
-        int hh = idx / D, e = idx - hh * D;
-        size_t p0 = (size_t)(g * G + hh) * S;
-        float M = -INFINITY;
-        for (int i = 0; i < s_active; ++i) M = fmaxf(M, part_ml[(p0 + i) * 2]);
-        float L = 0.f, A = 0.f;
-        int i = 0;
-        for (; i + 4 <= s_active; i += 4) {
-            float mm[4], ll[4], aa[4];
+}
+
+// Merges the ranges of one query head: block = head, thread = output element.
+template <int D>
+__global__ __launch_bounds__(D) void k_attn_combine(const int32_t *__restrict__ state, int S,
+                                                    const float *__restrict__ part_ml,
+                                                    const float *__restrict__ part_acc, float *__restrict__ out) {
+    const int t = state[kPos] + 1;
+    const int chunk = attn_chunk(t, S);
+    const int s_active = (t + chunk - 1) / chunk;
+    if (s_active == 1) return;  // the first kernel already wrote the result
+    const int hh = blockIdx.x, e = threadIdx.x;
+    const size_t p0 = (size_t)hh * S;
+    // first pass: the maximum, eight ranges per batch of loads
+    float M = -INFINITY;
+    for (int i = 0; i < s_active; i += 8) {
+        float mm[8];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                mm[u] = part_ml[(p0 + i + u) * 2];
-                ll[u] = part_ml[(p0 + i + u) * 2 + 1];
-                aa[u] = part_acc[(p0 + i + u) * D + e];
-            }
+        for (int u = 0; u < 8; ++u) mm[u] = part_ml[(p0 + min(i + u, s_active - 1)) * 2];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                float ww = merge_w(mm[u], M);
-                L += ll[u] * ww;
-                A += aa[u] * ww;
-            }
-        }
-        for (; i < s_active; ++i) {
-            float ww = merge_w(part_ml[(p0 + i) * 2], M);
-            L += part_ml[(p0 + i) * 2 + 1] * ww;
-            A += part_acc[(p0 + i) * D + e] * ww;
-        }
-        out[(size_t)(g * G + hh) * D + e] = A / L;
+        for (int u = 0; u < 8; ++u) M = fmaxf(M, mm[u]);
     }
-    if (threadIdx.x == 0) counters[g] = 0;
+    float L = 0.f, A = 0.f;
+    for (int i = 0; i < s_active; i += 8) {
+        float mm[8], ll[8], aa[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const size_t pi = p0 + min(i + u, s_active - 1);
+            mm[u] = part_ml[pi * 2];
+            ll[u] = part_ml[pi * 2 + 1];
+            aa[u] = part_acc[pi * D + e];
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const float ww = i + u < s_active ? merge_w(mm[u], M) : 0.f;
+            L += ll[u] * ww;
+            A += aa[u] * ww;
+        }
+    }
+    out[(size_t)hh * D + e] = A / L;
 }
 
 // ---------------------------------------------------------------------------------------
@@ -693,15 +710,17 @@ static void launch_attn(const Model &m, int layer, hipStream_t stream) {
     dim3 grid(kAttnSplits, c.n_kv_heads), block(256);
 #define ST_ATTN_CASE(GG)                                                                                     \
     case GG:                                                                                                 \
-        hipLaunchKernelGGL((k_attn_decode<D, GG>), grid, block, 0, stream, m.ws.q1, m.kcache + lofs,       \
+        hipLaunchKernelGGL((k_attn_partial<D, GG>), grid, block, 0, stream, m.ws.q1, m.kcache + lofs,        \
                            m.vcache + lofs, m.ws.state, c.max_seq, kAttnSplits, m.ws.part_ml, m.ws.part_acc, \
-                           m.ws.counters, m.ws.o1);                                                          \
+                           m.ws.o1);                                                                         \
         break;
     switch (G) {
         ST_ATTN_CASE(1) ST_ATTN_CASE(2) ST_ATTN_CASE(3) ST_ATTN_CASE(4)
         ST_ATTN_CASE(5) ST_ATTN_CASE(6) ST_ATTN_CASE(7) ST_ATTN_CASE(8)
     }
 #undef ST_ATTN_CASE
+    hipLaunchKernelGGL(k_attn_combine<D>, dim3(c.n_q_heads), dim3(D), 0, stream, m.ws.state, kAttnSplits,
+                       m.ws.part_ml, m.ws.part_acc, m.ws.o1);
 }
 
 // Rows per block of the residual GEMV: the candidate with the least padding among those that
