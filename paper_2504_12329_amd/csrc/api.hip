@@ -121,10 +121,12 @@ static hipGraphExec_t step_graph(Model *m, const st_trigger_rule *rule, int32_t 
     if (m->graphs_off || m->timers) return nullptr;
     const void *kw = rule ? rule->kw_bitmap : nullptr, *dl = rule ? rule->delim_bitmap : nullptr;
     int window = rule ? rule->window : 0, vocab = rule ? rule->vocab : 0;
+    const int bucket = attn_bucket(m->kv_len + 1);
     for (const StepGraph &g : m->graphs)
-        if (g.kw == kw && g.delim == dl && g.out_seq == out_seq_dev && g.window == window && g.vocab == vocab)
+        if (g.kw == kw && g.delim == dl && g.out_seq == out_seq_dev && g.window == window && g.vocab == vocab &&
+            g.attn_blocks == bucket)
             return g.exec;
-    if (m->graphs.size() >= 16) return nullptr;  // unusual caller: many distinct rules; launch directly
+    if (m->graphs.size() >= 64) return nullptr;  // unusual caller: many distinct rules; launch directly
     if (!m->capture_stream && hipStreamCreateWithFlags(&m->capture_stream, hipStreamNonBlocking) != hipSuccess) {
         m->graphs_off = true;
         (void)hipGetLastError();
@@ -134,7 +136,7 @@ static hipGraphExec_t step_graph(Model *m, const st_trigger_rule *rule, int32_t 
     hipGraphExec_t exec = nullptr;
     bool ok = hipStreamBeginCapture(m->capture_stream, hipStreamCaptureModeRelaxed) == hipSuccess;
     if (ok) {
-        launch_decode_step(*m, rule, out_seq_dev, m->capture_stream);
+        launch_decode_step(*m, rule, out_seq_dev, m->capture_stream, bucket);
         ok = hipStreamEndCapture(m->capture_stream, &graph) == hipSuccess && graph != nullptr;
     }
     if (ok) ok = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0) == hipSuccess;
@@ -144,7 +146,7 @@ static hipGraphExec_t step_graph(Model *m, const st_trigger_rule *rule, int32_t 
         (void)hipGetLastError();
         return nullptr;
     }
-    m->graphs.push_back(StepGraph{kw, dl, out_seq_dev, window, vocab, exec});
+    m->graphs.push_back(StepGraph{kw, dl, out_seq_dev, window, vocab, bucket, exec});
     return exec;
 }
 
@@ -154,7 +156,7 @@ static int decode_impl(Model *m, const st_trigger_rule *rule, int32_t *out_seq_d
     if (hipGraphExec_t exec = step_graph(m, rule, out_seq_dev)) {
         ST_HIP(hipGraphLaunch(exec, m->stream));
     } else {
-        launch_decode_step(*m, rule, out_seq_dev, m->stream);
+        launch_decode_step(*m, rule, out_seq_dev, m->stream, attn_bucket(m->kv_len + 1));
         if (int rc = check_launch("decode step")) return rc;
     }
     m->kv_len += 1;

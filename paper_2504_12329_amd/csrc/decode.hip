@@ -289,14 +289,13 @@ __global__ __launch_bounds__(256) void k_gateup_swiglu(const bf16_t *__restrict_
 // A block owns RB rows; its four waves split K and combine through LDS.  The activation vector is
 // read straight from global memory (L2) next to the weights: no staging, no barrier before the loads.
 // ---------------------------------------------------------------------------------------
-template <int RB>
+template <int RB, int U>
 __global__ __launch_bounds__(256) void k_gemv_residual(const bf16_t *__restrict__ W, const float *__restrict__ v,
                                                        const float *res, float *y, int N, int K) {
     __shared__ float part[4][RB];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int r0 = blockIdx.x * RB;
     const int n8 = K >> 3;
-    const int cb = (int)((long)n8 * wave / 4), ce = (int)((long)n8 * (wave + 1) / 4);
     const u32x4 *wrow[RB];
 #pragma unroll
     for (int r = 0; r < RB; ++r) wrow[r] = reinterpret_cast<const u32x4 *>(W + (size_t)min(r0 + r, N - 1) * K);
@@ -304,22 +303,24 @@ __global__ __launch_bounds__(256) void k_gemv_residual(const bf16_t *__restrict_
     float acc[RB];
 #pragma unroll
     for (int r = 0; r < RB; ++r) acc[r] = 0.f;
-    int c = cb + lane;
-    for (; c + 64 < ce; c += 128) {
-        u32x4 w0[RB], w1[RB];
+    // the four waves interleave along K: together they read 4 KB of every row per step
+    int c = wave * 64 + lane;
+    for (; c + 256 * (U - 1) < n8; c += 256 * U) {  // U groups of 16 bytes per row in flight
+        u32x4 w[U][RB];
+        float4 a[U], b[U];
 #pragma unroll
-        for (int r = 0; r < RB; ++r) {
-            w0[r] = ldw(wrow[r] + c);
-            w1[r] = ldw(wrow[r] + c + 64);
-        }
-        float4 a0 = xv[2 * c], b0 = xv[2 * c + 1], a1 = xv[2 * (c + 64)], b1 = xv[2 * (c + 64) + 1];
+        for (int u = 0; u < U; ++u) {
 #pragma unroll
-        for (int r = 0; r < RB; ++r) {
-            acc[r] = dot8(w0[r], a0, b0, acc[r]);
-            acc[r] = dot8(w1[r], a1, b1, acc[r]);
+            for (int r = 0; r < RB; ++r) w[u][r] = ldw(wrow[r] + c + 256 * u);
+            a[u] = xv[2 * (c + 256 * u)];
+            b[u] = xv[2 * (c + 256 * u) + 1];
         }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int r = 0; r < RB; ++r) acc[r] = dot8(w[u][r], a[u], b[u], acc[r]);
     }
-    if (c < ce) {
+    for (; c < n8; c += 256) {
         u32x4 w0[RB];
 #pragma unroll
         for (int r = 0; r < RB; ++r) w0[r] = ldw(wrow[r] + c);
@@ -644,44 +645,57 @@ __global__ __launch_bounds__(256) void k_attn_partial(const float *__restrict__ 
     }
 }
 
-// Merges the ranges of one query head: block = head, thread = output element.
+// Merges the ranges of one query head.  Block = head, 256 threads = 256/D groups x D output
+// elements; group j sums the ranges i = j (mod 256/D) in ascending order and the groups are
+// added in a fixed order.  The per-range weights exp2(m_i - M) are computed once into LDS.
 template <int D>
-__global__ __launch_bounds__(D) void k_attn_combine(const int32_t *__restrict__ state, int S,
-                                                    const float *__restrict__ part_ml,
-                                                    const float *__restrict__ part_acc, float *__restrict__ out) {
+__global__ __launch_bounds__(256) void k_attn_combine(const int32_t *__restrict__ state, int S,
+                                                      const float *__restrict__ part_ml,
+                                                      const float *__restrict__ part_acc, float *__restrict__ out) {
+    constexpr int NG = 256 / D;
+    __shared__ float m_s[kAttnSplits], wl_s[kAttnSplits][2];
+    __shared__ float red[NG][D];
     const int t = state[kPos] + 1;
     const int chunk = attn_chunk(t, S);
     const int s_active = (t + chunk - 1) / chunk;
     if (s_active == 1) return;  // the first kernel already wrote the result
-    const int hh = blockIdx.x, e = threadIdx.x;
+    const int hh = blockIdx.x, tid = threadIdx.x, e = tid % D, grp = tid / D;
     const size_t p0 = (size_t)hh * S;
-    // first pass: the maximum, eight ranges per batch of loads
+    // this thread's slice of the unnormalised outputs, issued before anything waits
+    constexpr int BATCH = kAttnSplits / NG;
+    float aa[BATCH];
+#pragma unroll
+    for (int u = 0; u < BATCH; ++u) {
+        int i = grp + NG * u;
+        aa[u] = i < s_active ? part_acc[(p0 + i) * D + e] : 0.f;
+    }
+    float2 ml = make_float2(-INFINITY, 0.f);
+    if (tid < s_active) ml = reinterpret_cast<const float2 *>(part_ml)[p0 + tid];
+    if (tid < kAttnSplits) m_s[tid] = ml.x;
+    __syncthreads();
     float M = -INFINITY;
-    for (int i = 0; i < s_active; i += 8) {
-        float mm[8];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) mm[u] = part_ml[(p0 + min(i + u, s_active - 1)) * 2];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) M = fmaxf(M, mm[u]);
+    for (int i = 0; i < s_active; ++i) M = fmaxf(M, m_s[i]);
+    if (tid < kAttnSplits) {
+        float w = merge_w(ml.x, M);
+        wl_s[tid][0] = w;
+        wl_s[tid][1] = w * ml.y;
     }
-    float L = 0.f, A = 0.f;
-    for (int i = 0; i < s_active; i += 8) {
-        float mm[8], ll[8], aa[8];
+    __syncthreads();
+    float A = 0.f;
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            const size_t pi = p0 + min(i + u, s_active - 1);
-            mm[u] = part_ml[pi * 2];
-            ll[u] = part_ml[pi * 2 + 1];
-            aa[u] = part_acc[pi * D + e];
-        }
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            const float ww = i + u < s_active ? merge_w(mm[u], M) : 0.f;
-            L += ll[u] * ww;
-            A += aa[u] * ww;
-        }
+    for (int u = 0; u < BATCH; ++u) {
+        int i = grp + NG * u;
+        if (i < s_active) A += aa[u] * wl_s[i][0];
     }
-    out[(size_t)hh * D + e] = A / L;
+    red[grp][e] = A;
+    __syncthreads();
+    if (grp == 0) {
+        float L = 0.f;
+        for (int i = 0; i < s_active; ++i) L += wl_s[i][1];
+#pragma unroll
+        for (int j = 1; j < NG; ++j) A += red[j][e];
+        out[(size_t)hh * D + e] = A / L;
+    }
 }
 
 // ---------------------------------------------------------------------------------------
@@ -703,11 +717,11 @@ void launch_set_state(const Model &m, int slot, int32_t value) {
 }
 
 template <int D>
-static void launch_attn(const Model &m, int layer, hipStream_t stream) {
+static void launch_attn(const Model &m, int layer, hipStream_t stream, int attn_blocks) {
     const st_config &c = m.c;
     const int G = c.n_q_heads / c.n_kv_heads;
     size_t lofs = (size_t)layer * c.n_kv_heads * c.max_seq * c.head_dim;
-    dim3 grid(kAttnSplits, c.n_kv_heads), block(256);
+    dim3 grid(attn_blocks, c.n_kv_heads), block(256);
 #define ST_ATTN_CASE(GG)                                                                                     \
     case GG:                                                                                                 \
         hipLaunchKernelGGL((k_attn_partial<D, GG>), grid, block, 0, stream, m.ws.q1, m.kcache + lofs,        \
@@ -719,23 +733,25 @@ static void launch_attn(const Model &m, int layer, hipStream_t stream) {
         ST_ATTN_CASE(5) ST_ATTN_CASE(6) ST_ATTN_CASE(7) ST_ATTN_CASE(8)
     }
 #undef ST_ATTN_CASE
-    hipLaunchKernelGGL(k_attn_combine<D>, dim3(c.n_q_heads), dim3(D), 0, stream, m.ws.state, kAttnSplits,
-                       m.ws.part_ml, m.ws.part_acc, m.ws.o1);
+    if (attn_blocks > 1)  // a single range is finished by the first kernel
+        hipLaunchKernelGGL(k_attn_combine<D>, dim3(c.n_q_heads), dim3(256), 0, stream, m.ws.state, kAttnSplits,
+                           m.ws.part_ml, m.ws.part_acc, m.ws.o1);
 }
 
-// Rows per block of the residual GEMV: the candidate with the least padding among those that
-// still give the chip about two blocks per CU; small matrices take the smallest candidate.
+// Rows per block of the residual GEMV: among the candidates that give 480..1024 blocks, the one
+// with the least padding, then the most blocks; small matrices take the smallest candidate.
 static int pick_rb(int N) {
     const int cand[] = {8, 7, 5, 4, 3, 2};
-    int best = 2;
+    int best = 2, best_blocks = 0;
     long best_waste = -1;
     for (int rb : cand) {
         int blocks = (N + rb - 1) / rb;
-        if (blocks < 480) continue;
+        if (blocks < 480 || blocks > 1024) continue;
         long waste = (long)blocks * rb - N;
-        if (best_waste < 0 || waste < best_waste) {
+        if (best_waste < 0 || waste < best_waste || (waste == best_waste && blocks > best_blocks)) {
             best = rb;
             best_waste = waste;
+            best_blocks = blocks;
         }
     }
     return best;
@@ -744,10 +760,14 @@ static int pick_rb(int N) {
 static void launch_gemv_residual(const Model &m, const bf16_t *W, const float *v, float *x, int N, int K,
                                  hipStream_t stream) {
     const int rb = pick_rb(N);
+    const bool deep = K >= 16384;  // long rows: four 16-byte groups per row in flight instead of two
     dim3 grid((N + rb - 1) / rb), block(256);
-#define ST_RB_CASE(RBV)                                                                       \
-    case RBV:                                                                                 \
-        hipLaunchKernelGGL(k_gemv_residual<RBV>, grid, block, 0, stream, W, v, x, x, N, K); \
+#define ST_RB_CASE(RBV)                                                                              \
+    case RBV:                                                                                        \
+        if (deep)                                                                                    \
+            hipLaunchKernelGGL((k_gemv_residual<RBV, 4>), grid, block, 0, stream, W, v, x, x, N, K); \
+        else                                                                                         \
+            hipLaunchKernelGGL((k_gemv_residual<RBV, 2>), grid, block, 0, stream, W, v, x, x, N, K); \
         break;
     switch (rb) {
         ST_RB_CASE(8) ST_RB_CASE(7) ST_RB_CASE(5) ST_RB_CASE(4) ST_RB_CASE(3) ST_RB_CASE(2)
@@ -784,7 +804,16 @@ static void gateup_shape(int I, int k_iters, int *r_out, int *blocks_out, bool *
     *blocks_out = blocks;
 }
 
-void launch_decode_layers(const Model &m, float *x, hipStream_t stream) {
+int attn_bucket(int t) {
+    int need = (t + kKeyTile - 1) / kKeyTile;
+    if (need >= kAttnSplits) return kAttnSplits;
+    if (need > 16) return (need + 7) & ~7;  // multiples of 8 ranges above 1024 keys
+    int b = 1;
+    while (b < need) b <<= 1;
+    return b;
+}
+
+void launch_decode_layers(const Model &m, float *x, hipStream_t stream, int attn_blocks) {
     const st_config &c = m.c;
     const int h = c.hidden, d = c.head_dim, nq = c.n_q_heads, nkv = c.n_kv_heads, I = c.intermediate;
     size_t lds_h = sizeof(float) * (size_t)h;
@@ -810,9 +839,9 @@ void launch_decode_layers(const Model &m, float *x, hipStream_t stream) {
 #undef ST_QKV
         }
         if (d == 128)
-            launch_attn<128>(m, l, stream);
+            launch_attn<128>(m, l, stream, attn_blocks);
         else
-            launch_attn<64>(m, l, stream);
+            launch_attn<64>(m, l, stream, attn_blocks);
         launch_gemv_residual(m, m.wo[l], m.ws.o1, x, h, nq * d, stream);
         {
             dim3 grid(gu_blocks), block(256);
@@ -843,8 +872,9 @@ void launch_decode_layers(const Model &m, float *x, hipStream_t stream) {
     }
 }
 
-void launch_decode_step(const Model &m, const st_trigger_rule *rule, int32_t *out_seq_dev, hipStream_t stream) {
-    launch_decode_layers(m, m.ws.x, stream);
+void launch_decode_step(const Model &m, const st_trigger_rule *rule, int32_t *out_seq_dev, hipStream_t stream,
+                        int attn_blocks) {
+    launch_decode_layers(m, m.ws.x, stream, attn_blocks);
     launch_head(m, m.ws.x, rule, 1, out_seq_dev, stream);
 }
 

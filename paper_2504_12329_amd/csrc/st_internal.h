@@ -49,6 +49,7 @@ struct StepTimers {
 struct StepGraph {
     const void *kw, *delim, *out_seq;
     int window, vocab;
+    int attn_blocks;  // key ranges the attention grid provides (context-length bucket)
     hipGraphExec_t exec;
 };
 
@@ -79,9 +80,13 @@ void launch_set_state(const Model &m, int slot, int32_t value);
 // all layers, LM head, arg-max; leaves state[kTok] = greedy token and state[kPos] += 1.
 // rule may be null (state[kFired] is then 0).  out_seq (device, may be null) receives the token at
 // index state[kStep]++.
-void launch_decode_step(const Model &m, const st_trigger_rule *rule, int32_t *out_seq_dev, hipStream_t stream);
+void launch_decode_step(const Model &m, const st_trigger_rule *rule, int32_t *out_seq_dev, hipStream_t stream,
+                        int attn_blocks);
+// Key ranges the decode attention needs for a context of t keys, rounded up to a bucket (the grid of
+// a captured step is fixed, so steps are captured per bucket).
+int attn_bucket(int t);
 // Embedding of state[kTok] and all layers at position state[kPos], on the residual row x (fp32[hidden]).
-void launch_decode_layers(const Model &m, float *x, hipStream_t stream);
+void launch_decode_layers(const Model &m, float *x, hipStream_t stream, int attn_blocks);
 // LM head + arg-max over the residual row x_row (fp32[hidden]); advances state[kPos] by `advance`.
 void launch_head(const Model &m, const float *x_row, const st_trigger_rule *rule, int32_t advance,
                  int32_t *out_seq_dev, hipStream_t stream);
