@@ -72,10 +72,14 @@ void carve_workspace(const st_config &c, char *base, Workspace *ws) {
     ws->out_tokens = (int32_t *)take(sizeof(int32_t) * (size_t)c.max_seq);
     ws->x = (float *)take(sizeof(float) * mc * h);
     ws->xn = (bf16_t *)take(sizeof(bf16_t) * mc * h);
-    ws->qkv = (float *)take(sizeof(float) * mc * qkv);
+    ws->qkv = (float *)take(sizeof(float) * (mc > 1024 ? mc : 1024) * (qkv > h ? qkv : h));
     ws->qb = (bf16_t *)take(sizeof(bf16_t) * mc * qd);
     ws->attn = (bf16_t *)take(sizeof(bf16_t) * mc * qd);
     ws->act = (bf16_t *)take(sizeof(bf16_t) * mc * I);
+    const size_t sr = mc < 256 ? mc : 256;  // rows of the two-term activation buffers
+    ws->xn_lo = (bf16_t *)take(sizeof(bf16_t) * sr * h);
+    ws->attn_lo = (bf16_t *)take(sizeof(bf16_t) * sr * qd);
+    ws->act_lo = (bf16_t *)take(sizeof(bf16_t) * sr * I);
     ws->q1 = (float *)take(sizeof(float) * qd);
     ws->o1 = (float *)take(sizeof(float) * qd);
     ws->a1 = (float *)take(sizeof(float) * I);

@@ -30,145 +30,239 @@ __global__ void k_note_fed(int32_t *state, const int32_t *tokens, int index, int
     state[kFed] = tok < 0 ? 0 : (tok >= vocab ? vocab - 1 : tok);
 }
 
-__global__ __launch_bounds__(256) void k_rmsnorm_rows(const float *__restrict__ X, const bf16_t *__restrict__ g,
-                                                      bf16_t *__restrict__ Y, int h, float eps) {
+// x[row] += sum of the pending split-K partial results (fixed order), then y[row] = bf16(rmsnorm(x) * g).
+// part is [n_part][rows][h]; with g == nullptr only the residual update is done.  With Ylo the
+// normalised row is written as a sum of two bf16 numbers (Y + Ylo), which keeps 16 mantissa bits.
+__global__ __launch_bounds__(256) void k_rmsnorm_rows(float *__restrict__ X, const float *__restrict__ part, int n_part,
+                                                      size_t part_stride, const bf16_t *__restrict__ g,
+                                                      bf16_t *__restrict__ Y, bf16_t *__restrict__ Ylo, int h,
+                                                      float eps) {
     __shared__ float red[4];
-    const float *x = X + (size_t)blockIdx.x * h;
-    bf16_t *y = Y + (size_t)blockIdx.x * h;
+    float4 *x = reinterpret_cast<float4 *>(X + (size_t)blockIdx.x * h);
+    const float4 *p0 = reinterpret_cast<const float4 *>(part + (size_t)blockIdx.x * h);
+    const size_t ps4 = part_stride / 4;
+    const int n4 = h >> 2;  // h is a multiple of 8
     float ss = 0.f;
-    for (int i = threadIdx.x; i < h; i += 256) {
-        float v = x[i];
-        ss = fmaf(v, v, ss);
+    for (int i = threadIdx.x; i < n4; i += 256) {
+        float4 v = x[i];
+        for (int s0 = 0; s0 < n_part; s0 += 4) {  // slices in ascending order, four loads in flight
+            float4 q[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) q[u] = s0 + u < n_part ? p0[(size_t)(s0 + u) * ps4 + i] : make_float4(0, 0, 0, 0);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                v.x += q[u].x;
+                v.y += q[u].y;
+                v.z += q[u].z;
+                v.w += q[u].w;
+            }
+        }
+        if (n_part) x[i] = v;
+        ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
     }
+    if (!g) return;
     ss = block_sum_256(ss, red);
-    float inv = 1.0f / sqrtf(ss / (float)h + eps);
-    for (int i = threadIdx.x; i < h; i += 256) y[i] = f32_to_bf16(x[i] * inv * bf16_to_f32(g[i]));
+    const float inv = 1.0f / sqrtf(ss / (float)h + eps);
+    u32x2 *y = reinterpret_cast<u32x2 *>(Y + (size_t)blockIdx.x * h);
+    u32x2 *ylo = Ylo ? reinterpret_cast<u32x2 *>(Ylo + (size_t)blockIdx.x * h) : nullptr;
+    const u32x2 *g2 = reinterpret_cast<const u32x2 *>(g);
+    for (int i = threadIdx.x; i < n4; i += 256) {
+        float4 v = x[i];
+        u32x2 gg = g2[i];
+        float a = v.x * inv * bf16_lo(gg.x), b = v.y * inv * bf16_hi(gg.x);
+        float c = v.z * inv * bf16_lo(gg.y), d = v.w * inv * bf16_hi(gg.y);
+        u32x2 hi = {pack_bf16x2(a, b), pack_bf16x2(c, d)};
+        y[i] = hi;
+        if (ylo) {  // second bf16 term of the activation
+            u32x2 lo = {pack_bf16x2(a - bf16_lo(hi.x), b - bf16_hi(hi.x)), pack_bf16x2(c - bf16_lo(hi.y), d - bf16_hi(hi.y))};
+            ylo[i] = lo;
+        }
+    }
 }
 
 // ---------------------------------------------------------------------------------------
-// C[M][N] = A[M][K] * B[N][K]^T on MFMA 32x32x16 bf16.  Block 256 threads = 2x2 waves, block
-// tile 128 x 128 (B-tile rows), wave tile 64 x 64, K step 32, LDS double-buffered.
-//   EPI 0: out_f32 = acc + bias        EPI 1: out_f32 += acc (residual)
-//   EPI 2: the B tile holds 64 gate rows then the matching 64 up rows; out_bf16 = silu(gate)*up
+// C[M][N] = A[M][K] * B[N][K]^T on MFMA 32x32x16 bf16.  Block 256 threads = 2x2 waves, block tile
+// BM x 128 (B-tile rows), wave tile BM/2 x 64, K step 32, LDS double-buffered.
+//   plain: raw fp32 accumulators of K-slice z go to part[z][M][N]; the consumer kernel adds the
+//          slices (fixed order), bias and residual.  Slices give small-M problems enough blocks to
+//          stream the weights with every CU and keep the result independent of timing.
+//   DUAL : the B tile holds 64 gate rows then the matching 64 up rows; out_bf16 = silu(gate) * up.
+//   SPLITA: activations arrive as two bf16 terms (A + Alo, 16 mantissa bits) and each weight fragment is
+//          multiplied by both; used for short chunks, where the weight stream, not the MFMA rate, sets the
+//          time, so catch-up passes of paper-like length keep near-fp32 activations for free.
+// Block ids map to tiles XCD-aware: ids are dealt round-robin to the 8 XCDs, and inside an XCD 32
+// consecutive blocks form a TY x TX patch of tiles over a strided set of weight columns, so the
+// weight and activation panels a patch streams are shared in that XCD's L2.
 // ---------------------------------------------------------------------------------------
-constexpr int kBM = 128, kBN = 128, kBK = 32, kLdsStride = kBK + 8;  // 80-byte rows: conflict-free 16-byte reads
+constexpr int kBK = 32, kLdsStride = kBK + 8;  // 80-byte rows: conflict-free 16-byte reads
 
-template <int EPI>
-__global__ __launch_bounds__(256) void k_gemm(const bf16_t *__restrict__ A, int lda, const bf16_t *__restrict__ B,
-                                              int M, int N, int K, float *outf, bf16_t *__restrict__ outb, int ldo,
-                                              const bf16_t *__restrict__ bias) {
-    __shared__ __align__(16) bf16_t As[2][kBM * kLdsStride];
-    __shared__ __align__(16) bf16_t Bs[2][kBN * kLdsStride];
+struct GemmGrid {
+    int My, Nx, TY, TX, YB, blocks;
+};
+
+// BM x BNR block tile (BNR = rows of the weight tile), WGM x WGN waves, wave tile (BM/WGM) x (BNR/WGN).
+// Two shapes are used: 128 x 128 with 2 x 2 waves (short and medium chunks, and the two-term form),
+// and 256 x 256 with 2 x 4 waves (long chunks: twice the flops per byte staged through LDS).
+template <int BM, int BNR, int WGM, int WGN, bool DUAL, bool SPLITA>
+__global__ __launch_bounds__(64 * WGM * WGN) void k_gemm(const bf16_t *__restrict__ A, const bf16_t *__restrict__ Alo,
+                                                         int lda, const bf16_t *__restrict__ B, int M, int N, int K,
+                                                         int kps, float *__restrict__ part,
+                                                         bf16_t *__restrict__ outb, bf16_t *__restrict__ outlo,
+                                                         int ldo, GemmGrid gg) {
+    constexpr int NTH = 64 * WGM * WGN;
+    constexpr int MT = BM / WGM / 32, NT = BNR / WGN / 32;
+    constexpr int ACH = BM * 4 / NTH, BCH = BNR * 4 / NTH;  // 16-byte chunks per thread per tile
+    constexpr int RPP = NTH / 4;                            // tile rows covered per staging pass
+    constexpr int BNO = DUAL ? BNR / 2 : BNR;               // output columns per block
+    static_assert(!DUAL || NT == 2, "fused SwiGLU pairs the wave's two column tiles");
+    constexpr int A_ELEMS = BM * kLdsStride, B_ELEMS = BNR * kLdsStride;
+    extern __shared__ __align__(16) bf16_t lds[];
+    bf16_t *As = lds;                                       // [2][A_ELEMS]
+    bf16_t *Al = lds + 2 * A_ELEMS;                         // [2][A_ELEMS] low terms (SPLITA only)
+    bf16_t *Bs = lds + (SPLITA ? 4 : 2) * A_ELEMS;          // [2][B_ELEMS]
+    int x, y;
+    {
+        const int id = blockIdx.x, xcd = id & 7, j = id >> 3;
+        const int st = j >> 5, r = j & 31;
+        const int tx = r % gg.TX, ty = r / gg.TX;
+        const int yb = st % gg.YB, xb = st / gg.YB;
+        y = yb * gg.TY + ty;
+        x = (xb * gg.TX + tx) * 8 + xcd;
+        if (y >= gg.My || x >= gg.Nx) return;
+    }
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
-    const int m0 = blockIdx.y * kBM;
-    const int n0 = blockIdx.x * (EPI == 2 ? kBN / 2 : kBN);
+    const int wm = wave / WGN, wn = wave % WGN;
+    const int m0 = y * BM, n0 = x * BNO;
     const int l32 = lane & 31, kg = lane >> 5;
+    const int kbeg = blockIdx.y * kps, kend = min(K, kbeg + kps);
 
-    // global -> register staging: every thread owns chunks q = tid and tid + 256 of both tiles
-    const bf16_t *ga[2], *gb[2];
-    bool va[2], vb[2];
-    int soff[2], kcol[2];
+    // global -> register staging: thread owns chunks (row = tid/4 + i*RPP, 8 columns at (tid%4)*8)
+    const bf16_t *ga[ACH], *gl[ACH], *gb[BCH];
+    bool va[ACH], vb[BCH];
+    const int kcol = (tid & 3) * 8;
+    const int so = (tid >> 2) * kLdsStride + kcol;
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        int q = tid + i * 256, row = q >> 2, kc = q & 3;
-        kcol[i] = kc * 8;
-        soff[i] = row * kLdsStride + kc * 8;
-        int am = m0 + row;
+    for (int i = 0; i < ACH; ++i) {
+        int am = m0 + (tid >> 2) + i * RPP;
         va[i] = am < M;
-        ga[i] = A + (size_t)(va[i] ? am : 0) * lda + kc * 8;
+        ga[i] = A + (size_t)(va[i] ? am : 0) * lda + kcol;
+        gl[i] = SPLITA ? Alo + (size_t)(va[i] ? am : 0) * lda + kcol : nullptr;
+    }
+#pragma unroll
+    for (int i = 0; i < BCH; ++i) {
+        int row = (tid >> 2) + i * RPP;
         int bn;
-        if (EPI == 2) {
-            int half = row >> 6, r = row & 63;
+        if (DUAL) {
+            int half = row / (BNR / 2), r = row % (BNR / 2);
             vb[i] = n0 + r < N;  // N is the number of output columns (I)
             bn = (vb[i] ? n0 + r : 0) + half * N;
         } else {
             vb[i] = n0 + row < N;
             bn = vb[i] ? n0 + row : 0;
         }
-        gb[i] = B + (size_t)bn * K + kc * 8;
+        gb[i] = B + (size_t)bn * K + kcol;
     }
-    u32x4 ra[2], rb[2];
+    u32x4 ra[ACH], rl[SPLITA ? ACH : 1], rb[BCH];
     const u32x4 zero = {0, 0, 0, 0};
     auto fetch = [&](int k0) {
+        const bool kin = k0 + kcol < kend;
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            bool kin = k0 + kcol[i] < K;
-            ra[i] = (va[i] && kin) ? *reinterpret_cast<const u32x4 *>(ga[i] + k0) : zero;
-            rb[i] = (vb[i] && kin) ? *reinterpret_cast<const u32x4 *>(gb[i] + k0) : zero;
+        for (int i = 0; i < ACH; ++i) ra[i] = (va[i] && kin) ? *reinterpret_cast<const u32x4 *>(ga[i] + k0) : zero;
+        if (SPLITA) {
+#pragma unroll
+            for (int i = 0; i < ACH; ++i)
+                rl[i] = (va[i] && kin) ? *reinterpret_cast<const u32x4 *>(gl[i] + k0) : zero;
         }
+#pragma unroll
+        for (int i = 0; i < BCH; ++i) rb[i] = (vb[i] && kin) ? *reinterpret_cast<const u32x4 *>(gb[i] + k0) : zero;
     };
     auto stash = [&](int buf) {
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            *reinterpret_cast<u32x4 *>(&As[buf][soff[i]]) = ra[i];
-            *reinterpret_cast<u32x4 *>(&Bs[buf][soff[i]]) = rb[i];
+        for (int i = 0; i < ACH; ++i)
+            *reinterpret_cast<u32x4 *>(&As[buf * A_ELEMS + so + i * RPP * kLdsStride]) = ra[i];
+        if (SPLITA) {
+#pragma unroll
+            for (int i = 0; i < ACH; ++i)
+                *reinterpret_cast<u32x4 *>(&Al[buf * A_ELEMS + so + i * RPP * kLdsStride]) = rl[i];
         }
+#pragma unroll
+        for (int i = 0; i < BCH; ++i)
+            *reinterpret_cast<u32x4 *>(&Bs[buf * B_ELEMS + so + i * RPP * kLdsStride]) = rb[i];
     };
 
-    f32x16 acc[2][2];
+    f32x16 acc[MT][NT];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < MT; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int j = 0; j < NT; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    int brow[2];
+    int brow[NT];
 #pragma unroll
-    for (int j = 0; j < 2; ++j) brow[j] = (EPI == 2 ? j * 64 + wn * 32 : wn * 64 + j * 32) + l32;
+    for (int j = 0; j < NT; ++j) brow[j] = (DUAL ? j * (BNR / 2) + wn * 32 : wn * (BNR / WGN) + j * 32) + l32;
+    const int arow = wm * (BM / WGM) + l32;
 
-    const int nk = (K + kBK - 1) / kBK;
-    fetch(0);
+    const int nk = (kend - kbeg + kBK - 1) / kBK;
+    fetch(kbeg);
     stash(0);
     __syncthreads();
     for (int kt = 0; kt < nk; ++kt) {
         const int buf = kt & 1;
-        if (kt + 1 < nk) fetch((kt + 1) * kBK);
+        if (kt + 1 < nk) fetch(kbeg + (kt + 1) * kBK);
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks) {
-            bf16x8 af[2], bfr[2];
+            bf16x8 af[MT], bfr[NT];
 #pragma unroll
-            for (int i = 0; i < 2; ++i)
+            for (int i = 0; i < MT; ++i)
                 af[i] = as_bf16x8(*reinterpret_cast<const u32x4 *>(
-                    &As[buf][(wm * 64 + i * 32 + l32) * kLdsStride + ks * 16 + kg * 8]));
+                    &As[buf * A_ELEMS + (arow + i * 32) * kLdsStride + ks * 16 + kg * 8]));
 #pragma unroll
-            for (int j = 0; j < 2; ++j)
-                bfr[j] = as_bf16x8(
-                    *reinterpret_cast<const u32x4 *>(&Bs[buf][brow[j] * kLdsStride + ks * 16 + kg * 8]));
+            for (int j = 0; j < NT; ++j)
+                bfr[j] = as_bf16x8(*reinterpret_cast<const u32x4 *>(
+                    &Bs[buf * B_ELEMS + brow[j] * kLdsStride + ks * 16 + kg * 8]));
 #pragma unroll
-            for (int i = 0; i < 2; ++i)
+            for (int i = 0; i < MT; ++i)
 #pragma unroll
-                for (int j = 0; j < 2; ++j)
+                for (int j = 0; j < NT; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+            if (SPLITA) {
+#pragma unroll
+                for (int i = 0; i < MT; ++i) {
+                    bf16x8 al = as_bf16x8(*reinterpret_cast<const u32x4 *>(
+                        &Al[buf * A_ELEMS + (arow + i * 32) * kLdsStride + ks * 16 + kg * 8]));
+#pragma unroll
+                    for (int j = 0; j < NT; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, bfr[j], acc[i][j], 0, 0, 0);
+                }
+            }
         }
         if (kt + 1 < nk) stash(buf ^ 1);
         __syncthreads();
     }
 
     // epilogue: register r of a 32x32 tile is row 8*(r/4) + 4*(lane/32) + r%4, column lane%32
+    float *pz = DUAL ? nullptr : part + (size_t)blockIdx.y * M * N;
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
+    for (int i = 0; i < MT; ++i) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-            int row = m0 + wm * 64 + i * 32 + 8 * (r >> 2) + 4 * kg + (r & 3);
+            int row = m0 + wm * (BM / WGM) + i * 32 + 8 * (r >> 2) + 4 * kg + (r & 3);
             if (row >= M) continue;
-            if (EPI == 2) {
+            if (DUAL) {
                 int col = n0 + wn * 32 + l32;
                 if (col < N) {
-                    float gt = acc[i][0][r], up = acc[i][1][r];
-                    outb[(size_t)row * ldo + col] = f32_to_bf16(gt / (1.0f + expf(-gt)) * up);
+                    float gt = acc[i][0][r], up = acc[i][NT - 1][r];
+                    float a = gt / (1.0f + expf(-gt)) * up;
+                    bf16_t hi = f32_to_bf16(a);
+                    outb[(size_t)row * ldo + col] = hi;
+                    if (SPLITA) outlo[(size_t)row * ldo + col] = f32_to_bf16(a - bf16_to_f32(hi));
                 }
             } else {
 #pragma unroll
-                for (int j = 0; j < 2; ++j) {
-                    int col = n0 + wn * 64 + j * 32 + l32;
-                    if (col >= N) continue;
-                    float *o = outf + (size_t)row * ldo + col;
-                    if (EPI == 0)
-                        *o = acc[i][j][r] + (bias ? bf16_to_f32(bias[col]) : 0.f);
-                    else
-                        *o += acc[i][j][r];
+                for (int j = 0; j < NT; ++j) {
+                    int col = n0 + wn * (BNR / WGN) + j * 32 + l32;
+                    if (col < N) pz[(size_t)row * N + col] = acc[i][j][r];
                 }
             }
         }
@@ -179,13 +273,23 @@ __global__ __launch_bounds__(256) void k_gemm(const bf16_t *__restrict__ A, int 
 // RoPE on q and k at absolute positions pos0 + row, K/V appended to the cache, q kept as bf16.
 // grid (rows, heads), block d/2 threads: one rotation pair per thread.
 // ---------------------------------------------------------------------------------------
-__global__ void k_rope_append(const float *__restrict__ qkv, const float2 *__restrict__ rope,
+__global__ void k_rope_append(const float *__restrict__ part, int n_part, size_t part_stride,
+                              const bf16_t *__restrict__ bias, const float2 *__restrict__ rope,
                               bf16_t *__restrict__ qb, bf16_t *__restrict__ kc, bf16_t *__restrict__ vc, int pos0,
                               int nq, int nkv, int d, int max_seq) {
     const int row = blockIdx.x, head = blockIdx.y, i = threadIdx.x, half = d >> 1;
     const int pos = pos0 + row;
-    const float *src = qkv + (size_t)row * (nq + 2 * nkv) * d + head * d;
-    float lo = src[i], hi = src[i + half];
+    const size_t off = (size_t)row * (nq + 2 * nkv) * d + head * d;
+    float lo = 0.f, hi = 0.f;
+    for (int s = 0; s < n_part; ++s) {
+        const float *src = part + (size_t)s * part_stride + off;
+        lo += src[i];
+        hi += src[i + half];
+    }
+    if (bias) {
+        lo += bf16_to_f32(bias[head * d + i]);
+        hi += bf16_to_f32(bias[head * d + i + half]);
+    }
     if (head < nq + nkv) {
         float2 cs = rope[(size_t)pos * half + i];
         float nlo = lo * cs.x - hi * cs.y;
@@ -205,38 +309,52 @@ __global__ void k_rope_append(const float *__restrict__ qkv, const float2 *__res
 }
 
 // ---------------------------------------------------------------------------------------
-// Causal flash attention of m query rows at absolute positions kv0 + row over keys [0, kv0 + row].
-// Block = 4 waves x 32 queries of one head; keys go through LDS in tiles of 32 (V transposed).
-// Each wave computes S^T = K Q^T, so a lane owns one query column: the online-softmax statistics
-// are per-lane scalars, and P^T feeds the second MFMA (O^T = V^T P^T) straight from registers.
+// Causal flash attention of m query tokens at absolute positions kv0 + q over keys [0, kv0 + q].
+// The G query heads that share a kv head are folded into the row dimension: row r of kv head g is
+// (token r / G, head g*G + r % G), so one staged K/V tile serves all of them.  Block = 4 waves x 32
+// rows; keys go through LDS in tiles of 64 (V transposed on the way in), the next tile is already
+// in registers while the current one is multiplied.  Each wave computes S^T = K Q^T, so a lane owns
+// one row: the online-softmax statistics are per-lane scalars, and P^T feeds the second MFMA
+// (O^T = V^T P^T) straight from registers.  grid.z splits the key range; with more than one
+// split each block publishes (max, sum, unnormalised output) and k_flash_combine merges them in a
+// fixed order -- that is what gives a 20-token catch-up chunk on a 4k context enough blocks.
 // ---------------------------------------------------------------------------------------
+constexpr int kFlashKeys = 64;
+
 template <int D>
 __global__ __launch_bounds__(256) void k_flash_prefill(const bf16_t *__restrict__ qb, const bf16_t *__restrict__ kc,
-                                                       const bf16_t *__restrict__ vc, bf16_t *__restrict__ out, int m,
-                                                       int kv0, int nq, int G, int max_seq) {
-    constexpr int KS = D + 8;  // K tile row stride (elements): 16-byte reads conflict-free
-    constexpr int VS = 36;     // V^T row stride (elements): 8-byte reads conflict-free
-    constexpr int CH = D / 8;  // 16-byte chunks per key
-    __shared__ __align__(16) bf16_t Ks[32 * KS];
+                                                       const bf16_t *__restrict__ vc, bf16_t *__restrict__ out,
+                                                       bf16_t *__restrict__ outlo, float *__restrict__ part_o,
+                                                       float *__restrict__ part_ml, int m, int kv0, int nq, int G,
+                                                       int max_seq) {
+    constexpr int KS = D + 8;             // K tile row stride (elements): 16-byte reads conflict-free
+    constexpr int VS = kFlashKeys + 4;    // V^T row stride (elements)
+    constexpr int CH = D / 8;             // 16-byte chunks per key
+    constexpr int CPT = kFlashKeys * CH / 256;  // chunks per thread per tile (4 for D=128, 2 for D=64)
+    __shared__ __align__(16) bf16_t Ks[kFlashKeys * KS];
     __shared__ __align__(16) bf16_t Vt[D * VS];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, kg = lane >> 5;
-    const int head = blockIdx.y, g = head / G;
-    const int q0 = blockIdx.x * 128, qw0 = q0 + wave * 32;
+    const int g = blockIdx.y, n_split = gridDim.z, z = blockIdx.z;
+    const int rows = m * G;
+    const int r0 = blockIdx.x * 128, rw0 = r0 + wave * 32;
     const int ldq = nq * D;
-    const bool wave_active = qw0 < m;
-    const int qrow = min(qw0 + l32, m - 1);
-    const int q_abs = kv0 + qrow;
-    const int wave_last_key = kv0 + min(qw0 + 31, m - 1);
-    const int n_keys = kv0 + min(q0 + 128, m);
-    const int n_tiles = (n_keys + 31) >> 5;
+    const bool wave_active = rw0 < rows;
+    const int row = min(rw0 + l32, rows - 1);
+    const int qtok = row / G, head = g * G + row % G;
+    const int q_abs = kv0 + qtok;
+    const int wave_last_key = kv0 + min(rw0 + 31, rows - 1) / G;
+    const int n_keys = kv0 + min(r0 + 127, rows - 1) / G + 1;       // keys any row of the block may see
+    const int n_tiles = (n_keys + kFlashKeys - 1) / kFlashKeys;
+    const int tps = (n_tiles + n_split - 1) / n_split;             // tiles per split
+    const int t_begin = z * tps, t_end = min(n_tiles, t_begin + tps);
     const float scale = 1.4426950408889634f / sqrtf((float)D);
 
     bf16x8 qf[D / 16];
 #pragma unroll
     for (int s = 0; s < D / 16; ++s)
-        qf[s] = as_bf16x8(*reinterpret_cast<const u32x4 *>(qb + (size_t)qrow * ldq + head * D + 16 * s + 8 * kg));
+        qf[s] = as_bf16x8(*reinterpret_cast<const u32x4 *>(qb + (size_t)qtok * ldq + head * D + 16 * s + 8 * kg));
 
     f32x16 o[D / 32];
 #pragma unroll
@@ -247,61 +365,107 @@ __global__ __launch_bounds__(256) void k_flash_prefill(const bf16_t *__restrict_
 
     const bf16_t *kbase = kc + (size_t)g * max_seq * D;
     const bf16_t *vbase = vc + (size_t)g * max_seq * D;
-    const u32x4 zero = {0, 0, 0, 0};
+    // staging ownership: K chunk c = tid + 256*i is (key c / CH, columns 8*(c % CH) .. +7); V: consecutive
+    // keys of one chunk column per thread, so the transposed tile is written four (two) keys at a time
+    u32x4 kr[CPT], vr[CPT];
+    auto fetch = [&](int t) {
+        const int key0 = t * kFlashKeys;
+#pragma unroll
+        for (int i = 0; i < CPT; ++i) {
+            int c = tid + i * 256;
+            int kabs = min(key0 + c / CH, n_keys - 1);  // clamped rows are masked by the causal test
+            kr[i] = *reinterpret_cast<const u32x4 *>(kbase + (size_t)kabs * D + (c % CH) * 8);
+        }
+        // V: D = 128 -> keys 4*kq + p (p < 4) of chunk column tid/16;
+        //    D = 64  -> keys 4*kq + 2*pair + p (p < 2) of chunk column (tid/16) % 8, pair = tid/128
+        const int kq = tid & 15;
+        const int col = CPT == 4 ? tid >> 4 : (tid >> 4) & (CH - 1);
+        const int kfirst = CPT == 4 ? 4 * kq : 4 * kq + 2 * ((tid >> 4) / CH);
+#pragma unroll
+        for (int p = 0; p < CPT; ++p) {
+            int kabs = min(key0 + kfirst + p, n_keys - 1);
+            vr[p] = *reinterpret_cast<const u32x4 *>(vbase + (size_t)kabs * D + col * 8);
+        }
+    };
+    auto stash = [&]() {
+#pragma unroll
+        for (int i = 0; i < CPT; ++i) {
+            int c = tid + i * 256;
+            *reinterpret_cast<u32x4 *>(&Ks[(c / CH) * KS + (c % CH) * 8]) = kr[i];
+        }
+        if (CPT == 4) {
+            // four keys x eight d of one chunk column -> eight 8-byte writes of four consecutive keys
+            const int kq = tid & 15, col = tid >> 4;
+            const uint32_t w[4][4] = {{vr[0].x, vr[0].y, vr[0].z, vr[0].w},
+                                      {vr[1].x, vr[1].y, vr[1].z, vr[1].w},
+                                      {vr[2].x, vr[2].y, vr[2].z, vr[2].w},
+                                      {vr[3].x, vr[3].y, vr[3].z, vr[3].w}};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {  // d = 8*col + 2e (low halves) and 2e+1 (high halves)
+                u32x2 lo = {(w[0][e] & 0xffffu) | (w[1][e] << 16), (w[2][e] & 0xffffu) | (w[3][e] << 16)};
+                u32x2 hi = {(w[0][e] >> 16) | (w[1][e] & 0xffff0000u), (w[2][e] >> 16) | (w[3][e] & 0xffff0000u)};
+                *reinterpret_cast<u32x2 *>(&Vt[(8 * col + 2 * e) * VS + 4 * kq]) = lo;
+                *reinterpret_cast<u32x2 *>(&Vt[(8 * col + 2 * e + 1) * VS + 4 * kq]) = hi;
+            }
+        } else {
+            // D = 64: two keys x eight d per thread -> eight 4-byte writes of two consecutive keys
+            const int kq = tid & 15, col = (tid >> 4) & (CH - 1), pair = (tid >> 4) / CH;
+            const uint32_t w[2][4] = {{vr[0].x, vr[0].y, vr[0].z, vr[0].w}, {vr[1].x, vr[1].y, vr[1].z, vr[1].w}};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                uint32_t lo = (w[0][e] & 0xffffu) | (w[1][e] << 16);
+                uint32_t hi = (w[0][e] >> 16) | (w[1][e] & 0xffff0000u);
+                *reinterpret_cast<uint32_t *>(&Vt[(8 * col + 2 * e) * VS + 4 * kq + 2 * pair]) = lo;
+                *reinterpret_cast<uint32_t *>(&Vt[(8 * col + 2 * e + 1) * VS + 4 * kq + 2 * pair]) = hi;
+            }
+        }
+    };
 
-    for (int t = 0; t < n_tiles; ++t) {
-        const int key0 = t * 32;
+    if (t_begin < t_end) fetch(t_begin);
+    for (int t = t_begin; t < t_end; ++t) {
+        const int key0 = t * kFlashKeys;
+        __syncthreads();  // previous tile fully consumed
+        stash();
         __syncthreads();
-        for (int c = tid; c < 32 * CH; c += 256) {
-            int key = c / CH, ch = c - key * CH;
-            int kabs = key0 + key;
-            u32x4 v = kabs < n_keys ? *reinterpret_cast<const u32x4 *>(kbase + (size_t)kabs * D + ch * 8) : zero;
-            *reinterpret_cast<u32x4 *>(&Ks[key * KS + ch * 8]) = v;
-        }
-        for (int c = tid; c < 32 * CH; c += 256) {
-            int key = c & 31, ch = c >> 5;
-            int kabs = key0 + key;
-            u32x4 v = kabs < n_keys ? *reinterpret_cast<const u32x4 *>(vbase + (size_t)kabs * D + ch * 8) : zero;
-            bf16_t *dst = &Vt[(ch * 8) * VS + key];
-            dst[0 * VS] = (bf16_t)(v.x & 0xffff);
-            dst[1 * VS] = (bf16_t)(v.x >> 16);
-            dst[2 * VS] = (bf16_t)(v.y & 0xffff);
-            dst[3 * VS] = (bf16_t)(v.y >> 16);
-            dst[4 * VS] = (bf16_t)(v.z & 0xffff);
-            dst[5 * VS] = (bf16_t)(v.z >> 16);
-            dst[6 * VS] = (bf16_t)(v.w & 0xffff);
-            dst[7 * VS] = (bf16_t)(v.w >> 16);
-        }
-        __syncthreads();
+        if (t + 1 < t_end) fetch(t + 1);
         if (!wave_active || key0 > wave_last_key) continue;
 
-        f32x16 sacc;
+        // S^T: two 32-key sub-tiles x 32 rows
+        f32x16 sacc[2];
 #pragma unroll
-        for (int r = 0; r < 16; ++r) sacc[r] = 0.f;
+        for (int u = 0; u < 2; ++u) {
 #pragma unroll
-        for (int s = 0; s < D / 16; ++s) {
-            bf16x8 kf = as_bf16x8(*reinterpret_cast<const u32x4 *>(&Ks[l32 * KS + 16 * s + 8 * kg]));
-            sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[s], sacc, 0, 0, 0);
+            for (int r = 0; r < 16; ++r) sacc[u][r] = 0.f;
+#pragma unroll
+            for (int s = 0; s < D / 16; ++s) {
+                bf16x8 kf = as_bf16x8(*reinterpret_cast<const u32x4 *>(&Ks[(u * 32 + l32) * KS + 16 * s + 8 * kg]));
+                sacc[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[s], sacc[u], 0, 0, 0);
+            }
         }
-        // lane = query column l32; register r = key 8*(r/4) + 4*kg + r%4 of the tile
+        // lane = row l32; register r of sub-tile u = key 32*u + 8*(r/4) + 4*kg + r%4 of the tile
         float mx = -INFINITY;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            int kabs = key0 + 8 * (r >> 2) + 4 * kg + (r & 3);
-            float sc = kabs > q_abs ? -INFINITY : sacc[r] * scale;
-            sacc[r] = sc;
-            mx = fmaxf(mx, sc);
-        }
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                int kabs = key0 + 32 * u + 8 * (r >> 2) + 4 * kg + (r & 3);
+                float sc = kabs > q_abs ? -INFINITY : sacc[u][r] * scale;
+                sacc[u][r] = sc;
+                mx = fmaxf(mx, sc);
+            }
         mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
-        const float m_new = fmaxf(m_i, mx);  // finite: key 0 is visible to every query
-        const float corr = exp2f(m_i - m_new);
+        const float m_new = fmaxf(m_i, mx);
+        const float m_use = m_new == -INFINITY ? 0.f : m_new;  // a row may see no key of this split yet
+        const float corr = exp2f(m_i - m_use);                 // m_i = -inf gives 0
         float rs = 0.f;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            float p = exp2f(sacc[r] - m_new);
-            sacc[r] = p;
-            rs += p;
-        }
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                float p = exp2f(sacc[u][r] - m_use);
+                sacc[u][r] = p;
+                rs += p;
+            }
         rs += __shfl_xor(rs, 32, kWave);
         l_i = l_i * corr + rs;
         m_i = m_new;
@@ -309,18 +473,20 @@ __global__ __launch_bounds__(256) void k_flash_prefill(const bf16_t *__restrict_
         for (int tt = 0; tt < D / 32; ++tt)
 #pragma unroll
             for (int r = 0; r < 16; ++r) o[tt][r] *= corr;
-        // P^T as the B operand: k-step s2 covers keys 16*s2 .. 16*s2+15, this lane holds registers 8*s2 .. 8*s2+7
-        bf16x8 pf[2];
+        // P^T as the B operand: k-step s2 covers keys 16*s2 .. +15 of the tile; this lane holds registers
+        // 8*(s2%2) .. +7 of sub-tile s2/2, i.e. keys 16*s2 + {4kg..4kg+3, 8+4kg..8+4kg+3}
+        bf16x8 pf[4];
 #pragma unroll
-        for (int s2 = 0; s2 < 2; ++s2) {
-            u32x4 pk = {pack_bf16x2(sacc[8 * s2 + 0], sacc[8 * s2 + 1]), pack_bf16x2(sacc[8 * s2 + 2], sacc[8 * s2 + 3]),
-                        pack_bf16x2(sacc[8 * s2 + 4], sacc[8 * s2 + 5]), pack_bf16x2(sacc[8 * s2 + 6], sacc[8 * s2 + 7])};
+        for (int s2 = 0; s2 < 4; ++s2) {
+            const int u = s2 >> 1, b = 8 * (s2 & 1);
+            u32x4 pk = {pack_bf16x2(sacc[u][b + 0], sacc[u][b + 1]), pack_bf16x2(sacc[u][b + 2], sacc[u][b + 3]),
+                        pack_bf16x2(sacc[u][b + 4], sacc[u][b + 5]), pack_bf16x2(sacc[u][b + 6], sacc[u][b + 7])};
             pf[s2] = as_bf16x8(pk);
         }
 #pragma unroll
         for (int tt = 0; tt < D / 32; ++tt) {
 #pragma unroll
-            for (int s2 = 0; s2 < 2; ++s2) {
+            for (int s2 = 0; s2 < 4; ++s2) {
                 const bf16_t *vrow = &Vt[(tt * 32 + l32) * VS + 16 * s2 + 4 * kg];
                 u32x2 a0 = *reinterpret_cast<const u32x2 *>(vrow);
                 u32x2 a1 = *reinterpret_cast<const u32x2 *>(vrow + 8);
@@ -329,29 +495,125 @@ __global__ __launch_bounds__(256) void k_flash_prefill(const bf16_t *__restrict_
             }
         }
     }
-    if (!wave_active || qw0 + l32 >= m) return;
-    const float inv = 1.0f / l_i;
-    bf16_t *orow = out + (size_t)(qw0 + l32) * ldq + head * D;
+    if (!wave_active || rw0 + l32 >= rows) return;
+    if (n_split == 1) {
+        const float inv = 1.0f / l_i;
+        bf16_t *orow = out + (size_t)qtok * ldq + head * D;
+        bf16_t *lrow = outlo ? outlo + (size_t)qtok * ldq + head * D : nullptr;
 #pragma unroll
-    for (int tt = 0; tt < D / 32; ++tt)
+        for (int tt = 0; tt < D / 32; ++tt)
 #pragma unroll
-        for (int rq = 0; rq < 4; ++rq) {
-            int dcol = tt * 32 + 8 * rq + 4 * kg;
-            u32x2 pk = {pack_bf16x2(o[tt][4 * rq + 0] * inv, o[tt][4 * rq + 1] * inv),
-                        pack_bf16x2(o[tt][4 * rq + 2] * inv, o[tt][4 * rq + 3] * inv)};
-            *reinterpret_cast<u32x2 *>(orow + dcol) = pk;
+            for (int rq = 0; rq < 4; ++rq) {
+                int dcol = tt * 32 + 8 * rq + 4 * kg;
+                float v0 = o[tt][4 * rq + 0] * inv, v1 = o[tt][4 * rq + 1] * inv;
+                float v2 = o[tt][4 * rq + 2] * inv, v3 = o[tt][4 * rq + 3] * inv;
+                u32x2 pk = {pack_bf16x2(v0, v1), pack_bf16x2(v2, v3)};
+                *reinterpret_cast<u32x2 *>(orow + dcol) = pk;
+                if (lrow) {
+                    u32x2 lo = {pack_bf16x2(v0 - bf16_lo(pk.x), v1 - bf16_hi(pk.x)),
+                                pack_bf16x2(v2 - bf16_lo(pk.y), v3 - bf16_hi(pk.y))};
+                    *reinterpret_cast<u32x2 *>(lrow + dcol) = lo;
+                }
+            }
+    } else {
+        // partial result of this key split for (token, head): [z][token*nq + head]
+        const size_t pr = (size_t)z * m * nq + (size_t)qtok * nq + head;
+        float *po = part_o + pr * D;
+#pragma unroll
+        for (int tt = 0; tt < D / 32; ++tt)
+#pragma unroll
+            for (int rq = 0; rq < 4; ++rq) {
+                int dcol = tt * 32 + 8 * rq + 4 * kg;
+                *reinterpret_cast<float4 *>(po + dcol) =
+                    make_float4(o[tt][4 * rq + 0], o[tt][4 * rq + 1], o[tt][4 * rq + 2], o[tt][4 * rq + 3]);
+            }
+        if (kg == 0) {
+            part_ml[pr * 2] = m_i;
+            part_ml[pr * 2 + 1] = l_i;
         }
+    }
+}
+
+// Merges the key splits of one (token, head): block = 256 threads = 256/D rows x D elements.
+template <int D>
+__global__ __launch_bounds__(256) void k_flash_combine(const float *__restrict__ part_o,
+                                                       const float *__restrict__ part_ml, int n_split, int n_rows,
+                                                       bf16_t *__restrict__ out, bf16_t *__restrict__ outlo) {
+    const int r = blockIdx.x * (256 / D) + threadIdx.x / D, e = threadIdx.x % D;
+    if (r >= n_rows) return;
+    float M = -INFINITY;
+    for (int z = 0; z < n_split; ++z) M = fmaxf(M, part_ml[((size_t)z * n_rows + r) * 2]);
+    float L = 0.f, A = 0.f;
+    for (int z = 0; z < n_split; ++z) {
+        const size_t pr = (size_t)z * n_rows + r;
+        const float mz = part_ml[pr * 2];
+        const float w = mz == -INFINITY ? 0.f : exp2f(mz - M);
+        L += part_ml[pr * 2 + 1] * w;
+        A += part_o[pr * D + e] * w;
+    }
+    const float v = A / L;
+    const bf16_t hi = f32_to_bf16(v);
+    out[(size_t)r * D + e] = hi;
+    if (outlo) outlo[(size_t)r * D + e] = f32_to_bf16(v - bf16_to_f32(hi));
 }
 
 // ---------------------------------------------------------------------------------------
 // launcher
 // ---------------------------------------------------------------------------------------
-template <int EPI>
-static void gemm(const Model &m, const bf16_t *A, int lda, const bf16_t *B, int M, int N, int K, float *outf,
-                 bf16_t *outb, int ldo, const bf16_t *bias) {
-    const int bn = EPI == 2 ? kBN / 2 : kBN;
-    dim3 grid((N + bn - 1) / bn, (M + kBM - 1) / kBM), block(256);
-    hipLaunchKernelGGL(k_gemm<EPI>, grid, block, 0, m.stream, A, lda, B, M, N, K, outf, outb, ldo, bias);
+// Launches one GEMM; returns the number of K slices written to ws.qkv (0 for the fused SwiGLU form).
+// Alo != nullptr selects the two-term activation form (chunks of at most kSplitRows rows).
+constexpr int kSplitRows = 256;
+constexpr int kBigRows = 512;  // chunks at least this long use the 256 x 256 tile
+
+template <int BM, int BNR, int WGM, int WGN, bool DUAL, bool SPLITA>
+static void gemm_launch(const Model &m, dim3 grid, const bf16_t *A, const bf16_t *Alo, int lda, const bf16_t *B, int M,
+                        int N, int K, int kps, bf16_t *outb, bf16_t *outlo, int ldo, const GemmGrid &gg) {
+    auto kern = k_gemm<BM, BNR, WGM, WGN, DUAL, SPLITA>;
+    constexpr size_t lds = sizeof(bf16_t) * 2 * ((SPLITA ? 2 : 1) * BM + BNR) * kLdsStride;
+    static bool raised = false;  // more than 64 KB of dynamic LDS has to be allowed once per kernel
+    if (lds > 65536 && !raised) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  (int)lds);
+        raised = true;
+    }
+    hipLaunchKernelGGL(kern, grid, dim3(64 * WGM * WGN), lds, m.stream, A, Alo, lda, B, M, N, K, kps, m.ws.qkv, outb,
+                       outlo, ldo, gg);
+}
+
+template <bool DUAL>
+static int gemm(const Model &m, const bf16_t *A, const bf16_t *Alo, int lda, const bf16_t *B, int M, int N, int K,
+                bf16_t *outb, bf16_t *outlo, int ldo) {
+    const bool big = !Alo && M >= kBigRows;
+    const int BM = big ? 256 : 128, BNO = (big ? 256 : 128) / (DUAL ? 2 : 1);
+    GemmGrid gg;
+    gg.My = (M + BM - 1) / BM;
+    gg.Nx = (N + BNO - 1) / BNO;
+    gg.TY = 1;
+    while (gg.TY * 2 <= gg.My && gg.TY < 8) gg.TY *= 2;
+    gg.TX = 32 / gg.TY;
+    gg.YB = (gg.My + gg.TY - 1) / gg.TY;
+    const int nxl = (gg.Nx + 7) / 8, xb = (nxl + gg.TX - 1) / gg.TX;
+    gg.blocks = 8 * xb * gg.YB * 32;
+    int splits = 1, kps = K;
+    if (!DUAL) {
+        const int tiles = gg.My * gg.Nx;
+        const int max_rows = m.c.max_chunk > 1024 ? m.c.max_chunk : 1024;  // rows the partial buffer holds
+        splits = ((big ? 320 : 640) + tiles - 1) / tiles;
+        if (splits > 8) splits = 8;
+        if (splits * M > max_rows) splits = max_rows / M;
+        if (splits < 1) splits = 1;
+        kps = ((K + splits - 1) / splits + kBK - 1) / kBK * kBK;
+        if (kps < 256) kps = 256;
+        splits = (K + kps - 1) / kps;
+    }
+    dim3 grid(gg.blocks, splits);
+    if (Alo)
+        gemm_launch<128, 128, 2, 2, DUAL, true>(m, grid, A, Alo, lda, B, M, N, K, kps, outb, outlo, ldo, gg);
+    else if (big)
+        gemm_launch<256, 256, 2, 4, DUAL, false>(m, grid, A, Alo, lda, B, M, N, K, kps, outb, outlo, ldo, gg);
+    else
+        gemm_launch<128, 128, 2, 2, DUAL, false>(m, grid, A, Alo, lda, B, M, N, K, kps, outb, outlo, ldo, gg);
+    return DUAL ? 0 : splits;
 }
 
 void launch_prefill_layers(const Model &m, int32_t pos0, int32_t n) {
@@ -359,26 +621,55 @@ void launch_prefill_layers(const Model &m, int32_t pos0, int32_t n) {
     const int h = c.hidden, d = c.head_dim, nq = c.n_q_heads, nkv = c.n_kv_heads, I = c.intermediate;
     const int qd = nq * d, qkv = m.qkv_dim;
     const Workspace &w = m.ws;
+    const bool two = n <= kSplitRows;  // short chunk: GEMM inputs carried as two bf16 terms
+    bf16_t *xn_lo = two ? w.xn_lo : nullptr, *attn_lo = two ? w.attn_lo : nullptr, *act_lo = two ? w.act_lo : nullptr;
     hipLaunchKernelGGL(k_embed_rows, dim3(n), dim3(256), 0, m.stream, m.embed, w.tokens, w.x, h, c.vocab);
     hipLaunchKernelGGL(k_note_fed, dim3(1), dim3(1), 0, m.stream, w.state, w.tokens, n - 1, c.vocab);
+    int pending = 0;  // K slices of the previous layer's down projection still to be added to x
     for (int l = 0; l < c.n_layers; ++l) {
         size_t lofs = (size_t)l * nkv * c.max_seq * d;
-        hipLaunchKernelGGL(k_rmsnorm_rows, dim3(n), dim3(256), 0, m.stream, w.x, m.norm_attn[l], w.xn, h, c.rms_eps);
-        gemm<0>(m, w.xn, h, m.wqkv[l], n, qkv, h, w.qkv, nullptr, qkv, m.bqkv[l]);
-        hipLaunchKernelGGL(k_rope_append, dim3(n, nq + 2 * nkv), dim3(d / 2), 0, m.stream, w.qkv, w.rope, w.qb,
-                           m.kcache + lofs, m.vcache + lofs, pos0, nq, nkv, d, c.max_seq);
-        dim3 fgrid((n + 127) / 128, nq);
-        if (d == 128)
-            hipLaunchKernelGGL(k_flash_prefill<128>, fgrid, dim3(256), 0, m.stream, w.qb, m.kcache + lofs,
-                               m.vcache + lofs, w.attn, n, pos0, nq, nq / nkv, c.max_seq);
-        else
-            hipLaunchKernelGGL(k_flash_prefill<64>, fgrid, dim3(256), 0, m.stream, w.qb, m.kcache + lofs,
-                               m.vcache + lofs, w.attn, n, pos0, nq, nq / nkv, c.max_seq);
-        gemm<1>(m, w.attn, qd, m.wo[l], n, h, qd, w.x, nullptr, h, nullptr);
-        hipLaunchKernelGGL(k_rmsnorm_rows, dim3(n), dim3(256), 0, m.stream, w.x, m.norm_mlp[l], w.xn, h, c.rms_eps);
-        gemm<2>(m, w.xn, h, m.wgu[l], n, I, h, nullptr, w.act, I, nullptr);
-        gemm<1>(m, w.act, I, m.wdown[l], n, h, I, w.x, nullptr, h, nullptr);
+        hipLaunchKernelGGL(k_rmsnorm_rows, dim3(n), dim3(256), 0, m.stream, w.x, w.qkv, pending, (size_t)n * h,
+                           m.norm_attn[l], w.xn, xn_lo, h, c.rms_eps);
+        int sq = gemm<false>(m, w.xn, xn_lo, h, m.wqkv[l], n, qkv, h, nullptr, nullptr, 0);
+        hipLaunchKernelGGL(k_rope_append, dim3(n, nq + 2 * nkv), dim3(d / 2), 0, m.stream, w.qkv, sq,
+                           (size_t)n * qkv, m.bqkv[l], w.rope, w.qb, m.kcache + lofs, m.vcache + lofs, pos0, nq, nkv,
+                           d, c.max_seq);
+        {
+            const int G = nq / nkv, rows = n * G, rblocks = (rows + 127) / 128;
+            const int n_tiles = (pos0 + n + kFlashKeys - 1) / kFlashKeys;
+            // key splits: enough blocks for every CU, bounded by the tiles and by the partial buffer
+            int splits = (512 + rblocks * nkv - 1) / (rblocks * nkv);
+            if (splits > n_tiles) splits = n_tiles;
+            if (splits > 32) splits = 32;
+            const size_t cap = (size_t)(c.max_chunk > 1024 ? c.max_chunk : 1024) * (qkv > h ? qkv : h);  // floats
+            while (splits > 1 && (size_t)splits * n * nq * (d + 2) > cap) --splits;
+            float *part_o = w.qkv, *part_ml = w.qkv + (size_t)splits * n * nq * d;
+            dim3 fgrid(rblocks, nkv, splits);
+            if (d == 128)
+                hipLaunchKernelGGL(k_flash_prefill<128>, fgrid, dim3(256), 0, m.stream, w.qb, m.kcache + lofs,
+                                   m.vcache + lofs, w.attn, attn_lo, part_o, part_ml, n, pos0, nq, G, c.max_seq);
+            else
+                hipLaunchKernelGGL(k_flash_prefill<64>, fgrid, dim3(256), 0, m.stream, w.qb, m.kcache + lofs,
+                                   m.vcache + lofs, w.attn, attn_lo, part_o, part_ml, n, pos0, nq, G, c.max_seq);
+            if (splits > 1) {
+                const int n_rows = n * nq;
+                if (d == 128)
+                    hipLaunchKernelGGL(k_flash_combine<128>, dim3((n_rows + 1) / 2), dim3(256), 0, m.stream, part_o,
+                                       part_ml, splits, n_rows, w.attn, attn_lo);
+                else
+                    hipLaunchKernelGGL(k_flash_combine<64>, dim3((n_rows + 3) / 4), dim3(256), 0, m.stream, part_o,
+                                       part_ml, splits, n_rows, w.attn, attn_lo);
+            }
+        }
+        int so = gemm<false>(m, w.attn, attn_lo, qd, m.wo[l], n, h, qd, nullptr, nullptr, 0);
+        hipLaunchKernelGGL(k_rmsnorm_rows, dim3(n), dim3(256), 0, m.stream, w.x, w.qkv, so, (size_t)n * h,
+                           m.norm_mlp[l], w.xn, xn_lo, h, c.rms_eps);
+        gemm<true>(m, w.xn, xn_lo, h, m.wgu[l], n, I, h, w.act, act_lo, I);
+        pending = gemm<false>(m, w.act, act_lo, I, m.wdown[l], n, h, I, nullptr, nullptr, 0);
     }
+    // the head needs the last row only: fold the last down projection into it
+    hipLaunchKernelGGL(k_rmsnorm_rows, dim3(1), dim3(256), 0, m.stream, w.x + (size_t)(n - 1) * h,
+                       w.qkv + (size_t)(n - 1) * h, pending, (size_t)n * h, nullptr, nullptr, nullptr, h, c.rms_eps);
 }
 
 }  // namespace st

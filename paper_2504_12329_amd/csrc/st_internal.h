@@ -22,10 +22,11 @@ struct Workspace {
     int32_t *out_tokens;   // [max_seq] tokens produced by chained steps
     float *x;              // [max_chunk][hidden] residual stream
     bf16_t *xn;            // [max_chunk][hidden] normalised rows (GEMM input)
-    float *qkv;            // [max_chunk][qkv] projections before RoPE
+    float *qkv;            // [max(max_chunk,1024)][max(qkv,hidden)] split-K partial results of the prefill GEMMs
     bf16_t *qb;            // [max_chunk][n_q*d] rotated queries
     bf16_t *attn;          // [max_chunk][n_q*d] attention output (GEMM input)
     bf16_t *act;           // [max_chunk][intermediate] SwiGLU output
+    bf16_t *xn_lo, *attn_lo, *act_lo;  // [256][...] second bf16 terms of the three above (short chunks)
     float *q1;             // [n_q*d] decode query
     float *o1;             // [n_q*d] decode attention output
     float *a1;             // [intermediate] decode SwiGLU output
