@@ -72,7 +72,10 @@ void carve_workspace(const st_config &c, char *base, Workspace *ws) {
     ws->out_tokens = (int32_t *)take(sizeof(int32_t) * (size_t)c.max_seq);
     ws->x = (float *)take(sizeof(float) * mc * h);
     ws->xn = (bf16_t *)take(sizeof(bf16_t) * mc * h);
-    ws->qkv = (float *)take(sizeof(float) * (mc > 1024 ? mc : 1024) * (qkv > h ? qkv : h));
+    {
+        size_t a = (mc > 1024 ? mc : 1024) * (qkv > h ? qkv : h), b = (size_t)1024 * 2 * I;
+        ws->qkv = (float *)take(sizeof(float) * (a > b ? a : b));
+    }
     ws->qb = (bf16_t *)take(sizeof(bf16_t) * mc * qd);
     ws->attn = (bf16_t *)take(sizeof(bf16_t) * mc * qd);
     ws->act = (bf16_t *)take(sizeof(bf16_t) * mc * I);

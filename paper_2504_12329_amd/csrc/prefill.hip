@@ -308,6 +308,38 @@ __global__ void k_rope_append(const float *__restrict__ part, int n_part, size_t
     dst[i + half] = f32_to_bf16(hi);
 }
 
+// a[row][i] = silu(gate) * up from the K slices of the gate/up projection of a short chunk
+// (part is [n_part][rows][2I]: gate columns [0,I), up columns [I,2I)), written as two bf16 terms.
+__global__ __launch_bounds__(256) void k_swiglu_rows(const float *__restrict__ part, int n_part, size_t part_stride,
+                                                     int I, bf16_t *__restrict__ act, bf16_t *__restrict__ act_lo) {
+    const int row = blockIdx.y;
+    const int i4 = blockIdx.x * 256 + threadIdx.x;  // group of four columns
+    if (i4 * 4 >= I) return;
+    const float4 *p0 = reinterpret_cast<const float4 *>(part + (size_t)row * 2 * I);
+    const size_t ps4 = part_stride / 4;
+    float4 gt = make_float4(0, 0, 0, 0), up = gt;
+    for (int s0 = 0; s0 < n_part; s0 += 4) {
+        float4 a[4], b[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            bool ok = s0 + u < n_part;
+            a[u] = ok ? p0[(size_t)(s0 + u) * ps4 + i4] : make_float4(0, 0, 0, 0);
+            b[u] = ok ? p0[(size_t)(s0 + u) * ps4 + I / 4 + i4] : make_float4(0, 0, 0, 0);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            gt.x += a[u].x; gt.y += a[u].y; gt.z += a[u].z; gt.w += a[u].w;
+            up.x += b[u].x; up.y += b[u].y; up.z += b[u].z; up.w += b[u].w;
+        }
+    }
+    const float v0 = gt.x / (1.0f + expf(-gt.x)) * up.x, v1 = gt.y / (1.0f + expf(-gt.y)) * up.y;
+    const float v2 = gt.z / (1.0f + expf(-gt.z)) * up.z, v3 = gt.w / (1.0f + expf(-gt.w)) * up.w;
+    u32x2 hi = {pack_bf16x2(v0, v1), pack_bf16x2(v2, v3)};
+    u32x2 lo = {pack_bf16x2(v0 - bf16_lo(hi.x), v1 - bf16_hi(hi.x)), pack_bf16x2(v2 - bf16_lo(hi.y), v3 - bf16_hi(hi.y))};
+    reinterpret_cast<u32x2 *>(act + (size_t)row * I)[i4] = hi;
+    reinterpret_cast<u32x2 *>(act_lo + (size_t)row * I)[i4] = lo;
+}
+
 // ---------------------------------------------------------------------------------------
 // Causal flash attention of m query tokens at absolute positions kv0 + q over keys [0, kv0 + q].
 // The G query heads that share a kv head are folded into the row dimension: row r of kv head g is
@@ -560,6 +592,15 @@ __global__ __launch_bounds__(256) void k_flash_combine(const float *__restrict__
 // ---------------------------------------------------------------------------------------
 // launcher
 // ---------------------------------------------------------------------------------------
+// Floats the split-K partial buffer (ws.qkv) holds; also sized in carve_workspace.
+static size_t partial_floats(const st_config &c) {
+    size_t rows = c.max_chunk > 1024 ? c.max_chunk : 1024;
+    size_t qkv = (size_t)(c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim;
+    size_t cols = qkv > (size_t)c.hidden ? qkv : (size_t)c.hidden;
+    size_t short_chunk = (size_t)1024 * 2 * c.intermediate;  // gate/up slices of chunks up to 256 rows
+    return rows * cols > short_chunk ? rows * cols : short_chunk;
+}
+
 // Launches one GEMM; returns the number of K slices written to ws.qkv (0 for the fused SwiGLU form).
 // Alo != nullptr selects the two-term activation form (chunks of at most kSplitRows rows).
 constexpr int kSplitRows = 256;
@@ -580,11 +621,17 @@ static void gemm_launch(const Model &m, dim3 grid, const bf16_t *A, const bf16_t
                        outlo, ldo, gg);
 }
 
+// Chunks of at most kSmallRows rows use the 32- / 64-row tiles, many K slices and an unfused SwiGLU.
+constexpr int kSmallRows = 64;
+
 template <bool DUAL>
 static int gemm(const Model &m, const bf16_t *A, const bf16_t *Alo, int lda, const bf16_t *B, int M, int N, int K,
                 bf16_t *outb, bf16_t *outlo, int ldo) {
     const bool big = !Alo && M >= kBigRows;
-    const int BM = big ? 256 : 128, BNO = (big ? 256 : 128) / (DUAL ? 2 : 1);
+    // two-term chunks of at most 32 / 64 rows use 32- / 64-row tiles with two waves: less LDS per block,
+    // so more blocks per CU keep more of the weight stream in flight
+    const int BM = big ? 256 : (Alo && M <= 32) ? 32 : (Alo && M <= 64) ? 64 : 128;
+    const int BNO = (big ? 256 : 128) / (DUAL ? 2 : 1);
     GemmGrid gg;
     gg.My = (M + BM - 1) / BM;
     gg.Nx = (N + BNO - 1) / BNO;
@@ -596,18 +643,25 @@ static int gemm(const Model &m, const bf16_t *A, const bf16_t *Alo, int lda, con
     gg.blocks = 8 * xb * gg.YB * 32;
     int splits = 1, kps = K;
     if (!DUAL) {
+        // K slices: enough blocks to keep every CU streaming weights (the small tiles have two waves
+        // each, so they need more of them), bounded by the partial-result buffer
         const int tiles = gg.My * gg.Nx;
-        const int max_rows = m.c.max_chunk > 1024 ? m.c.max_chunk : 1024;  // rows the partial buffer holds
-        splits = ((big ? 320 : 640) + tiles - 1) / tiles;
-        if (splits > 8) splits = 8;
-        if (splits * M > max_rows) splits = max_rows / M;
-        if (splits < 1) splits = 1;
+        const bool small = BM <= 64;
+        const int want = big ? 320 : (small ? 2048 : 640);
+        splits = (want + tiles - 1) / tiles;
+        if (splits > (small ? 32 : 8)) splits = small ? 32 : 8;
+        const size_t cap = partial_floats(m.c);
+        while (splits > 1 && (size_t)splits * M * N > cap) --splits;
         kps = ((K + splits - 1) / splits + kBK - 1) / kBK * kBK;
         if (kps < 256) kps = 256;
         splits = (K + kps - 1) / kps;
     }
     dim3 grid(gg.blocks, splits);
-    if (Alo)
+    if (Alo && BM == 32)
+        gemm_launch<32, 128, 1, 2, DUAL, true>(m, grid, A, Alo, lda, B, M, N, K, kps, outb, outlo, ldo, gg);
+    else if (Alo && BM == 64)
+        gemm_launch<64, 128, 1, 2, DUAL, true>(m, grid, A, Alo, lda, B, M, N, K, kps, outb, outlo, ldo, gg);
+    else if (Alo)
         gemm_launch<128, 128, 2, 2, DUAL, true>(m, grid, A, Alo, lda, B, M, N, K, kps, outb, outlo, ldo, gg);
     else if (big)
         gemm_launch<256, 256, 2, 4, DUAL, false>(m, grid, A, Alo, lda, B, M, N, K, kps, outb, outlo, ldo, gg);
@@ -641,7 +695,7 @@ void launch_prefill_layers(const Model &m, int32_t pos0, int32_t n) {
             int splits = (512 + rblocks * nkv - 1) / (rblocks * nkv);
             if (splits > n_tiles) splits = n_tiles;
             if (splits > 32) splits = 32;
-            const size_t cap = (size_t)(c.max_chunk > 1024 ? c.max_chunk : 1024) * (qkv > h ? qkv : h);  // floats
+            const size_t cap = partial_floats(c);
             while (splits > 1 && (size_t)splits * n * nq * (d + 2) > cap) --splits;
             float *part_o = w.qkv, *part_ml = w.qkv + (size_t)splits * n * nq * d;
             dim3 fgrid(rblocks, nkv, splits);
@@ -664,7 +718,13 @@ void launch_prefill_layers(const Model &m, int32_t pos0, int32_t n) {
         int so = gemm<false>(m, w.attn, attn_lo, qd, m.wo[l], n, h, qd, nullptr, nullptr, 0);
         hipLaunchKernelGGL(k_rmsnorm_rows, dim3(n), dim3(256), 0, m.stream, w.x, w.qkv, so, (size_t)n * h,
                            m.norm_mlp[l], w.xn, xn_lo, h, c.rms_eps);
-        gemm<true>(m, w.xn, xn_lo, h, m.wgu[l], n, I, h, w.act, act_lo, I);
+        if (n <= kSmallRows) {  // small chunk: gate/up as a plain split-K GEMM over all 2I rows, SwiGLU in the consumer
+            int sg = gemm<false>(m, w.xn, xn_lo, h, m.wgu[l], n, 2 * I, h, nullptr, nullptr, 0);
+            hipLaunchKernelGGL(k_swiglu_rows, dim3((I / 4 + 255) / 256, n), dim3(256), 0, m.stream, w.qkv, sg,
+                               (size_t)n * 2 * I, I, w.act, act_lo);
+        } else {
+            gemm<true>(m, w.xn, xn_lo, h, m.wgu[l], n, I, h, w.act, act_lo, I);
+        }
         pending = gemm<false>(m, w.act, act_lo, I, m.wdown[l], n, h, I, nullptr, nullptr, 0);
     }
     // the head needs the last row only: fold the last down projection into it
