@@ -5,8 +5,14 @@ of a 512-token prompt onto an empty cache, 4096 chained greedy decode steps (eve
 the split attention, LM head and arg-max), and the trigger scan over the produced tokens, all
 enqueued without host round trips.  `value` is output tokens per second over the timed jobs with
 weights, prompt and cache resident in HBM.  Prints one JSON line.
+
+Besides the headline it reports, in the same line: decode throughput and HBM fraction in windows
+around kv = 1k / 2k / 4k, the roofline of the kernel that moves the most bytes, the target
+(32B-shaped) model's decode and catch-up prefill rates, a short run of the whole two-model loop
+at the paper's hand-over density, and the CPU oracle timed on this machine.
 """
 import argparse
+import ctypes
 import json
 import os
 import sys
@@ -17,11 +23,11 @@ sys.path.insert(0, ROOT)
 
 PROMPT, N_DECODE = 512, 4096
 HBM_PEAK = 8.0e12          # bytes/s, MI355X HBM3E
+MFMA_PEAK = 2.5e15         # dense bf16 flop/s
 
 
 def cpu_baseline(cfg, w_gpu, prompt):
     """The oracle as it stands, timed on this machine's host cores on a bounded sample of the same workload."""
-    import numpy as np
     from oracle import oracle as O
     from paper_2504_12329_amd import synth
     ocfg = synth.oracle_config(dict(cfg, max_seq=64))
@@ -40,12 +46,68 @@ def cpu_baseline(cfg, w_gpu, prompt):
                       f"(kv length {n_pre}..{n_pre + n_dec}), fp32 weights"}
 
 
+def target_model_extras(torch, B, synth, cost, small):
+    """32B-shaped target: decode rate at kv ~ 4k, catch-up prefill on a 4096-token cache, and the loop."""
+    cfg = synth.model_config("qwen32b", max_seq=4096 + 4096 + 64, max_chunk=4096)
+    w = synth.make_weights(cfg, 2, device="cuda")
+    large = B.Model(cfg, w)
+    toks = torch.from_numpy(synth.make_prompt(8192, cfg["vocab"], 5)).cuda()
+    out = torch.empty(64, dtype=torch.int32, device="cuda")
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    large.prefill_device(toks[:4096])
+    large.decode_greedy(0, 8, chained=True, out_dev=out)
+    e0.record()
+    large.decode_greedy(0, 20, chained=True, out_dev=out)
+    e1.record()
+    torch.cuda.synchronize()
+    sec = e0.elapsed_time(e1) / 1e3 / 20
+    res = {"decode_kv4096": {"tok_s": 1 / sec, "GB_s": cost.decode_bytes(cfg, 4110) / sec / 1e9,
+                             "hbm_frac": cost.decode_bytes(cfg, 4110) / sec / HBM_PEAK}, "prefill_on_kv4096": {}}
+    for m in (21, 86, 256, 1024, 4096):
+        for _ in range(2):
+            large.truncate(4096)
+            e0.record()
+            large.prefill_device(toks[4096:4096 + m])
+            e1.record()
+            torch.cuda.synchronize()
+        sec = e0.elapsed_time(e1) / 1e3
+        fl = cost.prefill_flops(cfg, m, 4096)
+        res["prefill_on_kv4096"][str(m)] = {
+            "ms": sec * 1e3, "tok_s": m / sec, "TFLOP_s": fl / sec / 1e12, "mfma_frac": fl / sec / MFMA_PEAK,
+            "weight_GB_s": cost.weight_bytes(cfg) / sec / 1e9, "hbm_frac": cost.weight_bytes(cfg) / sec / HBM_PEAK,
+            "bound": "hbm" if m < 312 else "mfma"}
+    # the whole two-model loop at the paper's density: hand-over every 85 speculative tokens, segments of 20
+    # (both models must share one vocabulary: the target is re-wrapped over the first 151936 rows of its
+    # embedding and LM head, the speculative model's vocabulary size)
+    large.close()
+    vocab = small.cfg["vocab"]
+    cfg_l = dict(cfg, vocab=vocab, max_seq=2048, max_chunk=256)
+    w_l = dict(w, embed=w["embed"][:vocab], lm_head=w["lm_head"][:vocab])
+    large = B.Model(cfg_l, w_l)
+    small.truncate(0)
+    prompt = synth.make_prompt(256, vocab, 7)
+    n_out = 1050
+    t0 = time.perf_counter()
+    g = B.st_generate(small, large, None, prompt, n_out, 20, forced_period=85)
+    dt = time.perf_counter() - t0
+    st = g["stats"]
+    res["loop_1p5b_32b"] = {"tok_s": st["n_out"] / dt, "n_out": st["n_out"], "n_handoffs": st["n_handoffs"],
+                            "modify_ratio": st["n_large"] / max(1, st["n_out"]),
+                            "ms_small_decode": st["ms_small_decode"], "ms_large_decode": st["ms_large_decode"],
+                            "ms_small_prefill": st["ms_small_prefill"], "ms_large_prefill": st["ms_large_prefill"],
+                            "schedule": "forced: every 85th speculative token hands over, target writes 20"}
+    large.close()
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--decode-steps", type=int, default=N_DECODE, help="decode steps per job (shorten for profiling)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true", help="skip the 32B-shaped model and the two-model loop")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: this path uses no second GPU, run with --gpus 1")
@@ -55,6 +117,7 @@ def main():
     from paper_2504_12329_amd import binding as B, cost, synth
 
     torch.cuda.set_device(0)
+    n_dec = args.decode_steps
     cfg = synth.model_config("qwen1p5b", max_seq=PROMPT + N_DECODE + 64, max_chunk=PROMPT)
     w = synth.make_weights(cfg, 1, device="cuda")
     model = B.Model(cfg, w)
@@ -68,10 +131,9 @@ def main():
     def job():
         model.truncate(0)
         model.prefill_device(prompt_dev)
-        model.decode_greedy(0, N_DECODE, chained=True, out_dev=out_dev)
-        B._check(B.lib().st_trigger_scan(__import__("ctypes").byref(rule.c), out_dev.data_ptr(), 0, N_DECODE,
-                                         hits_dev[1:].data_ptr(), 64, hits_dev.data_ptr(), None, stream,
-                                         B.ST_OUT_DEVICE))
+        model.decode_greedy(0, n_dec, chained=True, out_dev=out_dev)
+        B._check(B.lib().st_trigger_scan(ctypes.byref(rule.c), out_dev.data_ptr(), 0, n_dec, hits_dev[1:].data_ptr(),
+                                         64, hits_dev.data_ptr(), None, stream, B.ST_OUT_DEVICE))
 
     for _ in range(args.warmup):
         job()
@@ -82,7 +144,7 @@ def main():
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     ms_per_step = dt / args.steps * 1e3
-    value = args.steps * N_DECODE / dt
+    value = args.steps * n_dec / dt
 
     # decode-only windows of 128 steps centred on kv = 1024 / 2048 / 4096
     windows = {}
@@ -90,6 +152,8 @@ def main():
     model.prefill_device(prompt_dev)
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     for kv in (1024, 2048, 4096):
+        if kv + 64 > PROMPT + n_dec:
+            break
         lead = kv - 64 - model.kv_len
         model.decode_greedy(0, lead, chained=True, out_dev=out_dev)
         e0.record()
@@ -100,8 +164,9 @@ def main():
         windows[str(kv)] = {"tok_s": 1.0 / sec, "GB_s": cost.decode_bytes(cfg, kv) / sec / 1e9,
                             "hbm_frac": cost.decode_bytes(cfg, kv) / sec / HBM_PEAK}
 
-    # roofline of the dominant kernel (gate/up projection): per-launch HIP events inside the library
-    model.truncate(2048)
+    # roofline of the kernel that moves the most bytes (gate/up projection): HIP events on every launch,
+    # recorded inside the library on the stream the kernel runs on
+    model.truncate(min(2048, model.kv_len))
     gu, st = [], []
     for _ in range(40):
         a, b = model.decode_step_timed()
@@ -122,12 +187,14 @@ def main():
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "qwen2.5-1.5B-shaped greedy decode: 512-token random prompt prefill + 4096 decode "
                                "steps + trigger scan, batch 1, contiguous bf16 KV cache, seeded random bf16 weights",
-                   "prompt_tokens": PROMPT, "decode_steps": N_DECODE},
+                   "prompt_tokens": PROMPT, "decode_steps": n_dec},
         "decode_windows": windows,
-        "whole_step_us_at_kv2048": float(np.mean(st[8:])),
+        "whole_step_us_ungraphed": float(np.mean(st[8:])),
         "algorithmic_bytes_per_token": {k: cost.decode_bytes(cfg, int(k)) for k in windows},
         "roofline": roofline,
     }
+    if not args.no_extras:
+        line["target_model_32b"] = target_model_extras(torch, B, synth, cost, model)
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(cfg, w, prompt)
     print(json.dumps(line))
