@@ -23,6 +23,9 @@ sys.path.insert(0, ROOT)
 
 PROMPT, N_DECODE = 512, 4096
 HBM_PEAK = 8.0e12          # bytes/s, MI355X HBM3E
+# HBM bytes per launch of k_gateup_swiglu<3,1,true> from rocprofv3 FETCH_SIZE (x2.00) + WRITE_SIZE (x1.00), see
+# profiles/decode_qwen1p5b_hbm_counters.md; set to None whenever that kernel changes until the counters are re-taken
+GATEUP_TRAFFIC_BYTES = 55.30e6
 MFMA_PEAK = 2.5e15         # dense bf16 flop/s
 
 
@@ -108,6 +111,8 @@ def main():
     ap.add_argument("--decode-steps", type=int, default=N_DECODE, help="decode steps per job (shorten for profiling)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the 32B-shaped model and the two-model loop")
+    ap.add_argument("--no-roofline", action="store_true",
+                    help="skip the decode windows and the per-launch event timing (for counter-collection runs)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: this path uses no second GPU, run with --gpus 1")
@@ -152,7 +157,7 @@ def main():
     model.prefill_device(prompt_dev)
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     for kv in (1024, 2048, 4096):
-        if kv + 64 > PROMPT + n_dec:
+        if args.no_roofline or kv + 64 > PROMPT + n_dec:
             break
         lead = kv - 64 - model.kv_len
         model.decode_greedy(0, lead, chained=True, out_dev=out_dev)
@@ -168,7 +173,7 @@ def main():
     # recorded inside the library on the stream the kernel runs on
     model.truncate(min(2048, model.kv_len))
     gu, st = [], []
-    for _ in range(40):
+    for _ in range(10 if args.no_roofline else 40):
         a, b = model.decode_step_timed()
         gu.append(a)
         st.append(b)
@@ -176,7 +181,7 @@ def main():
     bytes_per_launch = 2 * cfg["intermediate"] * cfg["hidden"] * 2
     achieved = bytes_per_launch / (gu_us * 1e-6)
     roofline = {"bound": "hbm", "kernel": "k_gateup_swiglu", "achieved": achieved / 1e9, "peak": HBM_PEAK / 1e9,
-                "unit": "GB/s", "frac": achieved / HBM_PEAK, "traffic": None,
+                "unit": "GB/s", "frac": achieved / HBM_PEAK, "traffic": GATEUP_TRAFFIC_BYTES,
                 "bytes_per_launch": bytes_per_launch, "avg_launch_us": gu_us,
                 "launches_timed": len(gu[8:]) * cfg["n_layers"]}
 
