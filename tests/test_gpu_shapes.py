@@ -100,3 +100,51 @@ def test_split_attention_matches_oracle_over_many_ranges():
     prompt = synth.make_prompt(700, cfg["vocab"], 9)
     assert _teacher_forced(cfg, g, o, prompt, [512, 188], 3) <= LOGIT_TOL
     g.close()
+
+
+@pytest.mark.parametrize("m", [64, 65, 256, 257, 512, 513])
+def test_prefill_kernel_regime_boundaries(m):
+    """Chunk lengths on both sides of every kernel switch (32/64-row tiles, two-term activations up to
+    256 rows, 256x256 tiles from 512 rows), on top of 100 cached keys, against the oracle (2 layers)."""
+    print_case(f"1.5B shape, 2 layers: 100 cached + chunk of {m}")
+    cfg, g, o = make_pair("qwen1p5b", 11, max_seq=640, max_chunk=520, n_layers=2, gen_device="cuda")
+    prompt = synth.make_prompt(100 + m, cfg["vocab"], 12)
+    assert _teacher_forced(cfg, g, o, prompt, [100, m], 1) <= LOGIT_TOL
+    g.close()
+
+
+def test_prefill_is_bit_reproducible():
+    """Split-K partial sums and split-key attention are merged in fixed orders: same input, same bits."""
+    cfg = synth.model_config("qwen1p5b", max_seq=1400, max_chunk=1024, n_layers=2)
+    g = B.Model(cfg, synth.make_weights(cfg, 3, device="cuda"))
+    toks = synth.make_prompt(1300, cfg["vocab"], 4)
+    outs = []
+    for _ in range(3):
+        g.truncate(0)
+        g.prefill(toks[:900], want_logits=False)          # 256x256 tiles
+        a, _ = g.prefill(toks[900:1121])                  # 221 rows: two-term path, key splits
+        b, _ = g.prefill(toks[1121:1142])                 # 21 rows: small tiles, many K slices
+        outs.append((a, b))
+    for a, b in outs[1:]:
+        assert np.array_equal(a, outs[0][0]) and np.array_equal(b, outs[0][1])
+    g.close()
+
+
+def test_kv_capacity_edge_and_long_decode_buckets():
+    """Fill the cache to its last position through both paths; decode across attention-grid buckets."""
+    cfg, g, o = make_pair("qwen1p5b", 13, max_seq=1100, max_chunk=512, n_layers=1, gen_device="cuda")
+    toks = synth.make_prompt(1100, cfg["vocab"], 14)
+    g.prefill(toks[:1020], want_logits=False)
+    o.feed(toks[:1020])
+    worst = 0.0
+    for i in range(1020, 1099):                           # crosses the 1024-key bucket boundary
+        lg, _ = g.decode_step(int(toks[i]), want_logits=(i % 13 == 0 or i > 1090))
+        lo = o.feed(toks[i:i + 1])
+        if lg is not None:
+            worst = max(worst, rel_err(lg, lo))
+    lg, _ = g.prefill(toks[1099:1100])                    # the very last position, through the prefill path
+    worst = max(worst, rel_err(lg, o.feed(toks[1099:1100])))
+    assert worst <= LOGIT_TOL and g.kv_len == 1100
+    with pytest.raises(B.StError):
+        g.decode_step(1)
+    g.close()
