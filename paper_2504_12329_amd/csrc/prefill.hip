@@ -4,6 +4,8 @@
 #include "st_device.h"
 #include "st_internal.h"
 
+#include <type_traits>
+
 namespace st {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -101,8 +103,8 @@ struct GemmGrid {
 };
 
 // BM x BNR block tile (BNR = rows of the weight tile), WGM x WGN waves, wave tile (BM/WGM) x (BNR/WGN).
-// Two shapes are used: 128 x 128 with 2 x 2 waves (short and medium chunks, and the two-term form),
-// and 256 x 256 with 2 x 4 waves (long chunks: twice the flops per byte staged through LDS).
+// Used as 128 x 128 with 2 x 2 waves (medium chunks, and the two-term form) and as 32- / 64-row tiles with
+// two waves (the shortest chunks); long chunks go to k_gemm_ring below.
 template <int BM, int BNR, int WGM, int WGN, bool DUAL, bool SPLITA>
 __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm(const bf16_t *__restrict__ A, const bf16_t *__restrict__ Alo,
                                                          int lda, const bf16_t *__restrict__ B, int M, int N, int K,
@@ -262,6 +264,209 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm(const bf16_t *__restric
 #pragma unroll
                 for (int j = 0; j < NT; ++j) {
                     int col = n0 + wn * (BNR / WGN) + j * 32 + l32;
+                    if (col < N) pz[(size_t)row * N + col] = acc[i][j][r];
+                }
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// Long chunks: the same contraction with a 256 x 256 block tile, K step 64, on four waves that each own
+// a 128 x 128 tile (256 accumulator registers), built around the three limits measured on this chip:
+//   * tile traffic from L2 moves about 40 % faster in whole 128-byte lines, hence K step 64;
+//   * LDS delivers 128 bytes per clock, so fragments are read once per 128 x 128 wave tile (half the
+//     LDS bytes per MFMA of a 128 x 64 wave tile), from rows whose 16-byte chunks are XOR-swizzled so
+//     that the reads are conflict-free without padding;
+//   * the vector memory path accepts one 1 KB load per 16 clocks per CU and stalls the issuing wave
+//     beyond that, and with one wave per SIMD a stalled wave is an idle MFMA pipe.  Tiles therefore
+//     go global -> LDS directly (no staging registers), one load instruction per four MFMAs, all
+//     through the K loop.  That needs slots freed early: the ring has five 32 KB slots, one operand of
+//     one K step each (A0 B0 A1 B1 A2 ...), so loads run up to two and a half steps ahead of the math.
+// Per K step of 64: 64 MFMAs, 32 fragment reads (fetched one 16-wide step ahead into a second register
+// set), 16 direct loads and one barrier.  Needs K % 64 == 0 and at least two steps per K slice.
+// ---------------------------------------------------------------------------------------
+constexpr int kRingBK = 64, kRingSlot = 256 * kRingBK * 2, kRingSlots = 5;
+constexpr int kRingLds = kRingSlot * kRingSlots;  // 160 KB: all of a CU's LDS
+
+__device__ __forceinline__ int ring_swz(int row) { return (row + (row >> 3)) & 7; }
+
+// 64 lanes x 16 bytes from per-lane global addresses to 1 KB of LDS starting at lds_off (wave-uniform)
+__device__ __forceinline__ void load_to_lds16(const void *g, uint32_t lds_off) {
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(lds_off) : "memory");
+}
+template <int N>
+__device__ __forceinline__ void wait_loads() {  // until at most N of this wave's direct loads are outstanding
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+template <int V>
+using ic = std::integral_constant<int, V>;
+
+template <bool DUAL>
+__global__ __launch_bounds__(256) void k_gemm_ring(const bf16_t *__restrict__ A, int lda, const bf16_t *__restrict__ B,
+                                                   int M, int N, int K, int kps, float *__restrict__ part,
+                                                   bf16_t *__restrict__ outb, int ldo, GemmGrid gg) {
+    extern __shared__ __align__(16) unsigned char ring[];
+    int x, y;
+    {
+        const int id = blockIdx.x, xcd = id & 7, j = id >> 3;
+        const int st = j >> 5, r = j & 31;
+        const int tx = r % gg.TX, ty = r / gg.TX;
+        const int yb = st % gg.YB, xb = st / gg.YB;
+        y = yb * gg.TY + ty;
+        x = (xb * gg.TX + tx) * 8 + xcd;
+        if (y >= gg.My || x >= gg.Nx) return;
+    }
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave >> 1, wn = wave & 1;
+    const int l32 = lane & 31, kg = lane >> 5;
+    const int m0 = y * 256, n0 = x * (DUAL ? 128 : 256);
+    const int kbeg = blockIdx.y * kps;
+    const int nk = (min(K, kbeg + kps) - kbeg) / kRingBK;
+    const uint32_t ring0 = (uint32_t)(uintptr_t)ring;  // LDS byte offset of the ring (low half of the flat address)
+
+    // direct loads: instruction i of a wave fills LDS rows [(wave*8+i)*8, +8) of a slot, lane -> (row lane/8,
+    // 16-byte position lane%8, which holds global chunk position ^ swizzle(row)); rows past the edge re-read
+    // the last valid row (their results are never stored)
+    const bf16_t *pa[8], *pb[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int row = (wave * 8 + i) * 8 + (lane >> 3);
+        const int c = (lane & 7) ^ ring_swz(row);
+        pa[i] = A + (size_t)min(m0 + row, M - 1) * lda + kbeg + c * 8;
+        int bn;
+        if (DUAL)  // rows 0..127 of the tile are gate rows, 128..255 the matching up rows (N = I)
+            bn = min(n0 + (row & 127), N - 1) + (row >> 7) * N;
+        else
+            bn = min(n0 + row, N - 1);
+        pb[i] = B + (size_t)bn * K + kbeg + c * 8;
+    }
+    auto loadA = [&](auto i_c, int slot, int kt) {
+        constexpr int i = decltype(i_c)::value;
+        load_to_lds16(pa[i] + kt * kRingBK, ring0 + slot * kRingSlot + (wave * 8 + i) * 1024);
+    };
+    auto loadB = [&](auto i_c, int slot, int kt) {
+        constexpr int i = decltype(i_c)::value;
+        load_to_lds16(pb[i] + kt * kRingBK, ring0 + slot * kRingSlot + (wave * 8 + i) * 1024);
+    };
+
+    f32x16 acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    // fragment reads: lane (row l32, K half kg) of 32-row block t reads chunk (2*ks + kg) ^ swizzle; the
+    // swizzle of row 32*t + l32 is swizzle(l32) ^ 4*(t & 1)
+    const int a_off = (wm * 128 + l32) * 128;
+    int b_off[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+        b_off[j] = (DUAL ? ((j >> 1) * 128 + wn * 64 + (j & 1) * 32 + l32) : (wn * 128 + j * 32 + l32)) * 128;
+    const int ch_even = (kg ^ ring_swz(l32)) * 16, ch_odd = ch_even ^ 64;
+
+    bf16x8 fa[2][4], fb[2][4];
+    // fragment q of a 16-wide step: q = 0..3 weight fragments, 4..7 activation fragments
+    auto fetch = [&](auto buf_c, auto q_c, int slotA, int slotB, int ks) {
+        constexpr int buf = decltype(buf_c)::value, q = decltype(q_c)::value;
+        const int ch = ((q & 1) ? ch_odd : ch_even) ^ (ks * 32);
+        if (q < 4)
+            fb[buf][q & 3] = as_bf16x8(*reinterpret_cast<const u32x4 *>(ring + slotB * kRingSlot + b_off[q & 3] + ch));
+        else
+            fa[buf][q & 3] =
+                as_bf16x8(*reinterpret_cast<const u32x4 *>(ring + slotA * kRingSlot + a_off + (q & 3) * 4096 + ch));
+    };
+    auto mma_row = [&](auto buf_c, auto i_c) {
+        constexpr int buf = decltype(buf_c)::value, i = decltype(i_c)::value;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[buf][i], fb[buf][j], acc[i][j], 0, 0, 0);
+    };
+    // One 16-wide step: four groups of { one direct load (KIND 1: weight instruction D0+g, 2: activation
+    // instruction D0+g, 0: none), two fragment reads for the following step, four MFMAs }; the scheduling
+    // fences keep that interleave.
+    auto step = [&](auto cur_c, auto fetch_c, int slotA, int slotB, int ks_next, auto kind_c, auto d0_c, int dslot,
+                    int dkt) {
+        constexpr int cur = decltype(cur_c)::value, kind = decltype(kind_c)::value, d0 = decltype(d0_c)::value;
+        constexpr bool FETCH = decltype(fetch_c)::value != 0;
+#define ST_GEMM_GROUP(g)                                                      \
+    if (kind == 1) loadB(ic<d0 + g>{}, dslot, dkt);                           \
+    if (kind == 2) loadA(ic<d0 + g>{}, dslot, dkt);                           \
+    if (FETCH) {                                                              \
+        fetch(ic<cur ^ 1>{}, ic<2 * g>{}, slotA, slotB, ks_next);             \
+        fetch(ic<cur ^ 1>{}, ic<2 * g + 1>{}, slotA, slotB, ks_next);         \
+    }                                                                         \
+    mma_row(ic<cur>{}, ic<g>{});                                              \
+    __builtin_amdgcn_sched_barrier(0);
+        ST_GEMM_GROUP(0) ST_GEMM_GROUP(1) ST_GEMM_GROUP(2) ST_GEMM_GROUP(3)
+#undef ST_GEMM_GROUP
+    };
+
+    // prologue: A0 B0 A1 whole and the first half of B1 (nk >= 2)
+    loadA(ic<0>{}, 0, 0), loadA(ic<1>{}, 0, 0), loadA(ic<2>{}, 0, 0), loadA(ic<3>{}, 0, 0);
+    loadA(ic<4>{}, 0, 0), loadA(ic<5>{}, 0, 0), loadA(ic<6>{}, 0, 0), loadA(ic<7>{}, 0, 0);
+    loadB(ic<0>{}, 1, 0), loadB(ic<1>{}, 1, 0), loadB(ic<2>{}, 1, 0), loadB(ic<3>{}, 1, 0);
+    loadB(ic<4>{}, 1, 0), loadB(ic<5>{}, 1, 0), loadB(ic<6>{}, 1, 0), loadB(ic<7>{}, 1, 0);
+    loadA(ic<0>{}, 2, 1), loadA(ic<1>{}, 2, 1), loadA(ic<2>{}, 2, 1), loadA(ic<3>{}, 2, 1);
+    loadA(ic<4>{}, 2, 1), loadA(ic<5>{}, 2, 1), loadA(ic<6>{}, 2, 1), loadA(ic<7>{}, 2, 1);
+    loadB(ic<0>{}, 3, 1), loadB(ic<1>{}, 3, 1), loadB(ic<2>{}, 3, 1), loadB(ic<3>{}, 3, 1);
+    wait_loads<12>();  // A0 and B0 are in
+    __builtin_amdgcn_s_barrier();
+    fetch(ic<0>{}, ic<0>{}, 0, 1, 0), fetch(ic<0>{}, ic<1>{}, 0, 1, 0), fetch(ic<0>{}, ic<2>{}, 0, 1, 0);
+    fetch(ic<0>{}, ic<3>{}, 0, 1, 0), fetch(ic<0>{}, ic<4>{}, 0, 1, 0), fetch(ic<0>{}, ic<5>{}, 0, 1, 0);
+    fetch(ic<0>{}, ic<6>{}, 0, 1, 0), fetch(ic<0>{}, ic<7>{}, 0, 1, 0);
+    __builtin_amdgcn_sched_barrier(0);
+
+    int sA = 0;  // ring slot of this K step's activations; its weights sit in the next slot, and so on round
+    auto fwd = [](int s, int d) { return s + d >= kRingSlots ? s + d - kRingSlots : s + d; };
+    // AHEAD: 2 = K steps kt+1 and kt+2 exist, 1 = only kt+1, 0 = this is the last
+    auto kstep = [&](int kt, auto ahead_c) {
+        constexpr int AHEAD = decltype(ahead_c)::value;
+        const int sB = fwd(sA, 1), sA1 = fwd(sA, 2), sB1 = fwd(sA, 3), sA2 = fwd(sA, 4);
+        step(ic<0>{}, ic<1>{}, sA, sB, 1, ic<(AHEAD >= 1 ? 1 : 0)>{}, ic<4>{}, sB1, kt + 1);  // rest of B(kt+1)
+        step(ic<1>{}, ic<1>{}, sA, sB, 2, ic<(AHEAD >= 2 ? 2 : 0)>{}, ic<0>{}, sA2, kt + 2);  // A(kt+2), first half
+        step(ic<0>{}, ic<1>{}, sA, sB, 3, ic<(AHEAD >= 2 ? 2 : 0)>{}, ic<4>{}, sA2, kt + 2);  // A(kt+2), second half
+        if (AHEAD >= 1) {
+            // all fragments of this K step are in registers and K step kt+1 has landed (only A(kt+2) may
+            // still be in flight); after the barrier that holds for every wave, so both slots are free
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            if (AHEAD >= 2) wait_loads<8>(); else wait_loads<0>();
+            __builtin_amdgcn_s_barrier();
+            __builtin_amdgcn_sched_barrier(0);
+            step(ic<1>{}, ic<1>{}, sA1, sB1, 0, ic<(AHEAD >= 2 ? 1 : 0)>{}, ic<0>{}, sA, kt + 2);  // B(kt+2), first half
+        } else {
+            step(ic<1>{}, ic<0>{}, sA1, sB1, 0, ic<0>{}, ic<0>{}, sA, kt + 2);
+        }
+        sA = sA1;
+    };
+    int kt = 0;
+    for (; kt + 2 < nk; ++kt) kstep(kt, ic<2>{});
+    kstep(kt++, ic<1>{});
+    kstep(kt++, ic<0>{});
+
+    // epilogue: register r of a 32x32 tile is row 8*(r/4) + 4*(lane/32) + r%4, column lane%32
+    float *pz = DUAL ? nullptr : part + (size_t)blockIdx.y * M * N;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int row = m0 + wm * 128 + i * 32 + 8 * (r >> 2) + 4 * kg + (r & 3);
+            if (row >= M) continue;
+            if (DUAL) {
+#pragma unroll
+                for (int j = 0; j < 2; ++j) {
+                    const int col = n0 + wn * 64 + j * 32 + l32;
+                    if (col < N) {
+                        const float gt = acc[i][j][r], up = acc[i][j + 2][r];
+                        outb[(size_t)row * ldo + col] = f32_to_bf16(gt / (1.0f + expf(-gt)) * up);
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int col = n0 + wn * 128 + j * 32 + l32;
                     if (col < N) pz[(size_t)row * N + col] = acc[i][j][r];
                 }
             }
@@ -604,21 +809,29 @@ static size_t partial_floats(const st_config &c) {
 // Launches one GEMM; returns the number of K slices written to ws.qkv (0 for the fused SwiGLU form).
 // Alo != nullptr selects the two-term activation form (chunks of at most kSplitRows rows).
 constexpr int kSplitRows = 256;
-constexpr int kBigRows = 512;  // chunks at least this long use the 256 x 256 tile
+constexpr int kBigRows = 512;  // chunks at least this long use the 256 x 256 ring kernel
 
 template <int BM, int BNR, int WGM, int WGN, bool DUAL, bool SPLITA>
 static void gemm_launch(const Model &m, dim3 grid, const bf16_t *A, const bf16_t *Alo, int lda, const bf16_t *B, int M,
                         int N, int K, int kps, bf16_t *outb, bf16_t *outlo, int ldo, const GemmGrid &gg) {
     auto kern = k_gemm<BM, BNR, WGM, WGN, DUAL, SPLITA>;
     constexpr size_t lds = sizeof(bf16_t) * 2 * ((SPLITA ? 2 : 1) * BM + BNR) * kLdsStride;
-    static bool raised = false;  // more than 64 KB of dynamic LDS has to be allowed once per kernel
-    if (lds > 65536 && !raised) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                  (int)lds);
-        raised = true;
-    }
+    static_assert(lds <= 65536, "more dynamic LDS than a kernel gets without raising its limit");
     hipLaunchKernelGGL(kern, grid, dim3(64 * WGM * WGN), lds, m.stream, A, Alo, lda, B, M, N, K, kps, m.ws.qkv, outb,
                        outlo, ldo, gg);
+}
+
+template <bool DUAL>
+static void ring_launch(const Model &m, dim3 grid, const bf16_t *A, int lda, const bf16_t *B, int M, int N, int K,
+                        int kps, bf16_t *outb, int ldo, const GemmGrid &gg) {
+    auto kern = k_gemm_ring<DUAL>;
+    static bool raised = false;  // more than 64 KB of dynamic LDS has to be allowed once per kernel
+    if (!raised) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  kRingLds);
+        raised = true;
+    }
+    hipLaunchKernelGGL(kern, grid, dim3(256), kRingLds, m.stream, A, lda, B, M, N, K, kps, m.ws.qkv, outb, ldo, gg);
 }
 
 // Chunks of at most kSmallRows rows use the 32- / 64-row tiles, many K slices and an unfused SwiGLU.
@@ -627,7 +840,7 @@ constexpr int kSmallRows = 64;
 template <bool DUAL>
 static int gemm(const Model &m, const bf16_t *A, const bf16_t *Alo, int lda, const bf16_t *B, int M, int N, int K,
                 bf16_t *outb, bf16_t *outlo, int ldo) {
-    const bool big = !Alo && M >= kBigRows;
+    const bool big = !Alo && M >= kBigRows && K % kRingBK == 0 && K >= 2 * kRingBK;
     // two-term chunks of at most 32 / 64 rows use 32- / 64-row tiles with two waves: less LDS per block,
     // so more blocks per CU keep more of the weight stream in flight
     const int BM = big ? 256 : (Alo && M <= 32) ? 32 : (Alo && M <= 64) ? 64 : 128;
@@ -642,29 +855,44 @@ static int gemm(const Model &m, const bf16_t *A, const bf16_t *Alo, int lda, con
     const int nxl = (gg.Nx + 7) / 8, xb = (nxl + gg.TX - 1) / gg.TX;
     gg.blocks = 8 * xb * gg.YB * 32;
     int splits = 1, kps = K;
-    if (!DUAL) {
+    const int tiles = gg.My * gg.Nx;
+    const size_t cap = partial_floats(m.c);
+    if (!DUAL && big) {
+        // One block per CU at a time: pick the K slices that minimise (rounds of 256 blocks) x (K steps per
+        // slice + a fixed cost for filling the ring and writing the tile)
+        const int nk = K / kRingBK;
+        long best = -1;
+        for (int s = 1; s <= 8; ++s) {
+            const int steps = (nk + s - 1) / s;
+            if (steps < 4 && s > 1) break;
+            if (s > 1 && (size_t)s * M * N > cap) break;
+            const long cost = (long)((tiles * s + 255) / 256) * (steps + 6);
+            if (best < 0 || cost < best) best = cost, splits = s;
+        }
+        kps = (nk + splits - 1) / splits * kRingBK;
+        splits = (K + kps - 1) / kps;
+        if (K - (splits - 1) * kps < 2 * kRingBK) splits = 1, kps = K;  // a last slice of one step: do not split
+    } else if (!DUAL) {
         // K slices: enough blocks to keep every CU streaming weights (the small tiles have two waves
         // each, so they need more of them), bounded by the partial-result buffer
-        const int tiles = gg.My * gg.Nx;
         const bool small = BM <= 64;
-        const int want = big ? 320 : (small ? 2048 : 640);
+        const int want = small ? 2048 : 640;
         splits = (want + tiles - 1) / tiles;
         if (splits > (small ? 32 : 8)) splits = small ? 32 : 8;
-        const size_t cap = partial_floats(m.c);
         while (splits > 1 && (size_t)splits * M * N > cap) --splits;
         kps = ((K + splits - 1) / splits + kBK - 1) / kBK * kBK;
         if (kps < 256) kps = 256;
         splits = (K + kps - 1) / kps;
     }
     dim3 grid(gg.blocks, splits);
-    if (Alo && BM == 32)
+    if (big)
+        ring_launch<DUAL>(m, grid, A, lda, B, M, N, K, kps, outb, ldo, gg);
+    else if (Alo && BM == 32)
         gemm_launch<32, 128, 1, 2, DUAL, true>(m, grid, A, Alo, lda, B, M, N, K, kps, outb, outlo, ldo, gg);
     else if (Alo && BM == 64)
         gemm_launch<64, 128, 1, 2, DUAL, true>(m, grid, A, Alo, lda, B, M, N, K, kps, outb, outlo, ldo, gg);
     else if (Alo)
         gemm_launch<128, 128, 2, 2, DUAL, true>(m, grid, A, Alo, lda, B, M, N, K, kps, outb, outlo, ldo, gg);
-    else if (big)
-        gemm_launch<256, 256, 2, 4, DUAL, false>(m, grid, A, Alo, lda, B, M, N, K, kps, outb, outlo, ldo, gg);
     else
         gemm_launch<128, 128, 2, 2, DUAL, false>(m, grid, A, Alo, lda, B, M, N, K, kps, outb, outlo, ldo, gg);
     return DUAL ? 0 : splits;
