@@ -293,7 +293,9 @@ __device__ __forceinline__ int ring_swz(int row) { return (row + (row >> 3)) & 7
 
 // 64 lanes x 16 bytes from per-lane global addresses to 1 KB of LDS starting at lds_off (wave-uniform)
 __device__ __forceinline__ void load_to_lds16(const void *g, uint32_t lds_off) {
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(lds_off) : "memory");
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g),
+                 "s"(__builtin_amdgcn_readfirstlane(lds_off))
+                 : "memory");
 }
 template <int N>
 __device__ __forceinline__ void wait_loads() {  // until at most N of this wave's direct loads are outstanding
@@ -771,6 +773,242 @@ __global__ __launch_bounds__(256) void k_flash_prefill(const bf16_t *__restrict_
     }
 }
 
+// Long chunks, head_dim 128: the same attention with at most 256 registers per lane, so that two waves
+// share a SIMD and one wave's softmax runs under another's MFMAs, and one barrier per 64-key tile:
+//   * K tiles go global -> LDS directly into two 16 KB slots whose 16-byte chunks are XOR-swizzled by the key
+//     row, so the S^T fragment reads need neither staging registers nor padding;
+//   * the S^T fragment of lane i reads key row swap(i) (bits 2 and 3 of i exchanged): the 32x32 MFMA output
+//     then leaves every lane with eight *consecutive* keys per 16-key step, so P^T feeds the second MFMA
+//     straight from registers and each V^T fragment is one 16-byte read;
+//   * the running maximum is raised only when it would grow by more than 2^8 (softmax is shift-invariant and
+//     the final division by the row sum absorbs the reference), which makes the rescale of the 64 output
+//     registers rare; tiles wholly below the diagonal skip the causal compare.
+// Interface and key-split partial results are those of k_flash_prefill.
+// ---------------------------------------------------------------------------------------
+template <int NW>  // waves per block: 32 folded rows each
+__global__ __launch_bounds__(64 * NW, 2) void k_flash_long(const bf16_t *__restrict__ qb, const bf16_t *__restrict__ kc,
+                                                    const bf16_t *__restrict__ vc, bf16_t *__restrict__ out,
+                                                    float *__restrict__ part_o, float *__restrict__ part_ml, int m,
+                                                    int kv0, int nq, int G, int max_seq) {
+    constexpr int D = 128, VS = kFlashKeys + 8;  // V^T rows of 144 bytes: 16-byte reads conflict-free
+    __shared__ __align__(16) unsigned char Ks[2][kFlashKeys * D * 2];
+    __shared__ __align__(16) bf16_t Vt[2][D * VS];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l32 = lane & 31, kg = lane >> 5;
+    const int g = blockIdx.y, n_split = gridDim.z, z = blockIdx.z;
+    const int rows = m * G;
+    constexpr int kLongRows = 32 * NW, NT = 64 * NW;
+    // blocks with the most keys (the last rows) are dispatched first, so the causal tail is made of short blocks
+    const int r0 = (gridDim.x - 1 - blockIdx.x) * kLongRows, rw0 = r0 + wave * 32;
+    const int ldq = nq * D;
+    const bool wave_active = rw0 < rows;
+    const int row = min(rw0 + l32, rows - 1);
+    const int qtok = row / G, head = g * G + row % G;
+    const int q_abs = kv0 + qtok;
+    const int wave_first_q = kv0 + min(rw0, rows - 1) / G;          // smallest position among the wave's rows
+    const int wave_last_key = kv0 + min(rw0 + 31, rows - 1) / G;
+    const int n_keys = kv0 + min(r0 + kLongRows - 1, rows - 1) / G + 1;
+    const int n_tiles = (n_keys + kFlashKeys - 1) / kFlashKeys;
+    const int tps = (n_tiles + n_split - 1) / n_split;
+    const int t_begin = z * tps, t_end = min(n_tiles, t_begin + tps);
+    const float scale = 1.4426950408889634f / sqrtf((float)D);
+
+    bf16x8 qf[D / 16];
+#pragma unroll
+    for (int s = 0; s < D / 16; ++s)
+        qf[s] = as_bf16x8(*reinterpret_cast<const u32x4 *>(qb + (size_t)qtok * ldq + head * D + 16 * s + 8 * kg));
+
+    f32x16 o[D / 32];
+#pragma unroll
+    for (int t = 0; t < D / 32; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[t][r] = 0.f;
+    float m_i = -INFINITY, l_i = 0.f;
+
+    const bf16_t *kbase = kc + (size_t)g * max_seq * D;
+    const bf16_t *vbase = vc + (size_t)g * max_seq * D;
+    const uint32_t ks0 = (uint32_t)(uintptr_t)&Ks[0][0];
+    // K: a wave loads 64/NW key rows of the tile with 1 KB instructions of four 256-byte rows each;
+    // lane -> (row lane/16, 16-byte position lane%16 holding chunk position ^ (row & 15))
+    constexpr int KI = 16 / NW;  // K instructions per wave per tile
+    auto load_k = [&](int t) {
+        const int key0 = t * kFlashKeys;
+#pragma unroll
+        for (int i = 0; i < KI; ++i) {
+            const int r4 = (wave * KI + i) * 4, r = r4 + (lane >> 4);
+            const int c = (lane & 15) ^ (r & 15);
+            const int kabs = min(key0 + r, n_keys - 1);  // clamped rows lie above the diagonal: masked
+            load_to_lds16(kbase + (size_t)kabs * D + c * 8, ks0 + (t & 1) * (kFlashKeys * D * 2) + r4 * 256);
+        }
+    };
+    // V: thread -> keys 2*(tid%32), +1 of 8-column groups tid/32 + (NT/32)*q; written transposed, two keys per word
+    constexpr int VQ = 16 / (NT / 32);
+    u32x4 vr[VQ][2];
+    auto load_v = [&](int t) {
+        const int key0 = t * kFlashKeys;
+#pragma unroll
+        for (int q = 0; q < VQ; ++q)
+#pragma unroll
+            for (int p = 0; p < 2; ++p) {
+                const int kabs = min(key0 + 2 * (tid & 31) + p, n_keys - 1);
+                vr[q][p] = *reinterpret_cast<const u32x4 *>(vbase + (size_t)kabs * D + ((tid >> 5) + (NT / 32) * q) * 8);
+            }
+    };
+    auto stash_v = [&](int t) {
+        bf16_t *vt = &Vt[t & 1][0];
+        const int kp = tid & 31;
+#pragma unroll
+        for (int q = 0; q < VQ; ++q) {
+            const int col = (tid >> 5) + (NT / 32) * q;
+            const uint32_t a[4] = {vr[q][0].x, vr[q][0].y, vr[q][0].z, vr[q][0].w};
+            const uint32_t b[4] = {vr[q][1].x, vr[q][1].y, vr[q][1].z, vr[q][1].w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                *reinterpret_cast<uint32_t *>(&vt[(8 * col + 2 * e) * VS + 2 * kp]) = (a[e] & 0xffffu) | (b[e] << 16);
+                *reinterpret_cast<uint32_t *>(&vt[(8 * col + 2 * e + 1) * VS + 2 * kp]) =
+                    (a[e] >> 16) | (b[e] & 0xffff0000u);
+            }
+        }
+    };
+
+    // S^T fragment rows: lane i of a 32-key sub-tile reads key swap(i)
+    const int krow = (l32 & 19) | ((l32 & 4) << 1) | ((l32 & 8) >> 1);
+    const int k_swz = krow & 15;
+
+    f32x16 sacc[2];
+    bf16x8 pf[4];
+    auto tile_active = [&](int t) { return wave_active && t * kFlashKeys <= wave_last_key; };
+    // S^T of tile t: two 32-key sub-tiles x 32 rows
+    auto scores = [&](int t) {
+        if (!tile_active(t)) return;
+        const unsigned char *kt = &Ks[t & 1][0];
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) sacc[u][r] = 0.f;
+#pragma unroll
+            for (int s = 0; s < D / 16; ++s) {
+                bf16x8 kf = as_bf16x8(
+                    *reinterpret_cast<const u32x4 *>(kt + (u * 32 + krow) * 256 + (((2 * s + kg) ^ k_swz) * 16)));
+                sacc[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[s], sacc[u], 0, 0, 0);
+            }
+        }
+    };
+    // online softmax of tile t: lane = query row; register r of sub-tile u is key 32u + 16*(r/8) + 8*kg + r%8
+    auto softmax = [&](int t) {
+        if (!tile_active(t)) return;
+        const int key0 = t * kFlashKeys;
+        if (key0 + kFlashKeys - 1 > wave_first_q) {  // the tile touches the diagonal for some row of this wave
+#pragma unroll
+            for (int u = 0; u < 2; ++u)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int kabs = key0 + 32 * u + 16 * (r >> 3) + 8 * kg + (r & 7);
+                    if (kabs > q_abs) sacc[u][r] = -INFINITY;
+                }
+        }
+        float mx = sacc[0][0];
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[u][r]);
+        mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
+        const float m_cand = mx * scale;
+        const bool raise = m_cand > m_i + 8.0f;                    // also the first keys a row sees (m_i = -inf)
+        const float m_new = raise ? m_cand : m_i;
+        const float base = m_new == -INFINITY ? 0.f : m_new;       // a row may have seen no key yet
+        float rs = 0.f;
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const float p = __builtin_amdgcn_exp2f(fmaf(sacc[u][r], scale, -base));
+                sacc[u][r] = p;
+                rs += p;
+            }
+        rs += __shfl_xor(rs, 32, kWave);
+        if (__builtin_amdgcn_ballot_w64(raise) != 0) {
+            const float corr = raise ? __builtin_amdgcn_exp2f(m_i - base) : 1.0f;  // m_i = -inf gives 0
+            l_i *= corr;
+#pragma unroll
+            for (int tt = 0; tt < D / 32; ++tt)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) o[tt][r] *= corr;
+        }
+        l_i += rs;
+        m_i = m_new;
+        // P^T as the B operand: 16-key step s2 = registers 8*(s2%2) .. +7 of sub-tile s2/2 = keys 16*s2 + 8*kg .. +7
+#pragma unroll
+        for (int s2 = 0; s2 < 4; ++s2) {
+            const int u = s2 >> 1, b = 8 * (s2 & 1);
+            u32x4 pk = {pack_bf16x2(sacc[u][b + 0], sacc[u][b + 1]), pack_bf16x2(sacc[u][b + 2], sacc[u][b + 3]),
+                        pack_bf16x2(sacc[u][b + 4], sacc[u][b + 5]), pack_bf16x2(sacc[u][b + 6], sacc[u][b + 7])};
+            pf[s2] = as_bf16x8(pk);
+        }
+    };
+    // O^T += V^T P^T for tile t
+    auto weighted_values = [&](int t) {
+        if (!tile_active(t)) return;
+        const bf16_t *vt = &Vt[t & 1][0];
+#pragma unroll
+        for (int tt = 0; tt < D / 32; ++tt)
+#pragma unroll
+            for (int s2 = 0; s2 < 4; ++s2) {
+                bf16x8 vf = as_bf16x8(*reinterpret_cast<const u32x4 *>(&vt[(tt * 32 + l32) * VS + 16 * s2 + 8 * kg]));
+                o[tt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[s2], o[tt], 0, 0, 0);
+            }
+    };
+
+    // One barrier per tile: before it a wave writes its part of V^T(t) and waits for its part of K(t); after it
+    // the loads of tile t+1 start into the other slots, which every wave finished reading before the barrier.
+    if (t_begin < t_end) {
+        load_k(t_begin);
+        load_v(t_begin);
+    }
+    for (int t = t_begin; t < t_end; ++t) {
+        stash_v(t);
+        wait_loads<0>();
+        __builtin_amdgcn_s_barrier();
+        if (t + 1 < t_end) {
+            load_k(t + 1);
+            load_v(t + 1);
+        }
+        scores(t);
+        softmax(t);
+        weighted_values(t);
+    }
+    if (!wave_active || rw0 + l32 >= rows) return;
+    if (n_split == 1) {
+        const float inv = 1.0f / l_i;
+        bf16_t *orow = out + (size_t)qtok * ldq + head * D;
+#pragma unroll
+        for (int tt = 0; tt < D / 32; ++tt)
+#pragma unroll
+            for (int rq = 0; rq < 4; ++rq) {
+                const int dcol = tt * 32 + 8 * rq + 4 * kg;
+                u32x2 pk = {pack_bf16x2(o[tt][4 * rq + 0] * inv, o[tt][4 * rq + 1] * inv),
+                            pack_bf16x2(o[tt][4 * rq + 2] * inv, o[tt][4 * rq + 3] * inv)};
+                *reinterpret_cast<u32x2 *>(orow + dcol) = pk;
+            }
+    } else {
+        const size_t pr = (size_t)z * m * nq + (size_t)qtok * nq + head;
+        float *po = part_o + pr * D;
+#pragma unroll
+        for (int tt = 0; tt < D / 32; ++tt)
+#pragma unroll
+            for (int rq = 0; rq < 4; ++rq) {
+                const int dcol = tt * 32 + 8 * rq + 4 * kg;
+                *reinterpret_cast<float4 *>(po + dcol) =
+                    make_float4(o[tt][4 * rq + 0], o[tt][4 * rq + 1], o[tt][4 * rq + 2], o[tt][4 * rq + 3]);
+            }
+        if (kg == 0) {
+            part_ml[pr * 2] = m_i;
+            part_ml[pr * 2 + 1] = l_i;
+        }
+    }
+}
+
 // Merges the key splits of one (token, head): block = 256 threads = 256/D rows x D elements.
 template <int D>
 __global__ __launch_bounds__(256) void k_flash_combine(const float *__restrict__ part_o,
@@ -797,6 +1035,8 @@ __global__ __launch_bounds__(256) void k_flash_combine(const float *__restrict__
 // ---------------------------------------------------------------------------------------
 // launcher
 // ---------------------------------------------------------------------------------------
+constexpr int kLongWaves = 4;  // waves per block of the long-chunk attention
+
 // Floats the split-K partial buffer (ws.qkv) holds; also sized in carve_workspace.
 static size_t partial_floats(const st_config &c) {
     size_t rows = c.max_chunk > 1024 ? c.max_chunk : 1024;
@@ -917,7 +1157,8 @@ void launch_prefill_layers(const Model &m, int32_t pos0, int32_t n) {
                            (size_t)n * qkv, m.bqkv[l], w.rope, w.qb, m.kcache + lofs, m.vcache + lofs, pos0, nq, nkv,
                            d, c.max_seq);
         {
-            const int G = nq / nkv, rows = n * G, rblocks = (rows + 127) / 128;
+            const bool long_chunk = d == 128 && n >= kBigRows;
+            const int G = nq / nkv, rows = n * G, rpb = long_chunk ? 32 * kLongWaves : 128, rblocks = (rows + rpb - 1) / rpb;
             const int n_tiles = (pos0 + n + kFlashKeys - 1) / kFlashKeys;
             // key splits: enough blocks for every CU, bounded by the tiles and by the partial buffer
             int splits = (512 + rblocks * nkv - 1) / (rblocks * nkv);
@@ -927,7 +1168,10 @@ void launch_prefill_layers(const Model &m, int32_t pos0, int32_t n) {
             while (splits > 1 && (size_t)splits * n * nq * (d + 2) > cap) --splits;
             float *part_o = w.qkv, *part_ml = w.qkv + (size_t)splits * n * nq * d;
             dim3 fgrid(rblocks, nkv, splits);
-            if (d == 128)
+            if (long_chunk)
+                hipLaunchKernelGGL(k_flash_long<kLongWaves>, fgrid, dim3(64 * kLongWaves), 0, m.stream, w.qb, m.kcache + lofs, m.vcache + lofs,
+                                   w.attn, part_o, part_ml, n, pos0, nq, G, c.max_seq);
+            else if (d == 128)
                 hipLaunchKernelGGL(k_flash_prefill<128>, fgrid, dim3(256), 0, m.stream, w.qb, m.kcache + lofs,
                                    m.vcache + lofs, w.attn, attn_lo, part_o, part_ml, n, pos0, nq, G, c.max_seq);
             else
