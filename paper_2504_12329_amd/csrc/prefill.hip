@@ -1049,7 +1049,7 @@ static size_t partial_floats(const st_config &c) {
 // Launches one GEMM; returns the number of K slices written to ws.qkv (0 for the fused SwiGLU form).
 // Alo != nullptr selects the two-term activation form (chunks of at most kSplitRows rows).
 constexpr int kSplitRows = 256;
-constexpr int kBigRows = 512;  // chunks at least this long use the 256 x 256 ring kernel
+constexpr int kBigRows = 257;  // every chunk too long for the two-term form uses the 256 x 256 ring kernel
 
 template <int BM, int BNR, int WGM, int WGN, bool DUAL, bool SPLITA>
 static void gemm_launch(const Model &m, dim3 grid, const bf16_t *A, const bf16_t *Alo, int lda, const bf16_t *B, int M,
