@@ -49,9 +49,9 @@ def cpu_baseline(cfg, w_gpu, prompt):
                       f"(kv length {n_pre}..{n_pre + n_dec}), fp32 weights"}
 
 
-def target_model_extras(torch, B, synth, cost, small):
+def target_model_extras(torch, B, synth, cost, small, sizes=(21, 86, 256, 1024, 4096), loop=True, n_layers=None):
     """32B-shaped target: decode rate at kv ~ 4k, catch-up prefill on a 4096-token cache, and the loop."""
-    cfg = synth.model_config("qwen32b", max_seq=4096 + 4096 + 64, max_chunk=4096)
+    cfg = synth.model_config("qwen32b", max_seq=4096 + 4096 + 64, max_chunk=4096, n_layers=n_layers)
     w = synth.make_weights(cfg, 2, device="cuda")
     large = B.Model(cfg, w)
     toks = torch.from_numpy(synth.make_prompt(8192, cfg["vocab"], 5)).cuda()
@@ -66,7 +66,7 @@ def target_model_extras(torch, B, synth, cost, small):
     sec = e0.elapsed_time(e1) / 1e3 / 20
     res = {"decode_kv4096": {"tok_s": 1 / sec, "GB_s": cost.decode_bytes(cfg, 4110) / sec / 1e9,
                              "hbm_frac": cost.decode_bytes(cfg, 4110) / sec / HBM_PEAK}, "prefill_on_kv4096": {}}
-    for m in (21, 86, 256, 1024, 4096):
+    for m in sizes:
         for _ in range(2):
             large.truncate(4096)
             e0.record()
@@ -83,6 +83,8 @@ def target_model_extras(torch, B, synth, cost, small):
     # (both models must share one vocabulary: the target is re-wrapped over the first 151936 rows of its
     # embedding and LM head, the speculative model's vocabulary size)
     large.close()
+    if not loop:
+        return res
     vocab = small.cfg["vocab"]
     cfg_l = dict(cfg, vocab=vocab, max_seq=2048, max_chunk=256)
     w_l = dict(w, embed=w["embed"][:vocab], lm_head=w["lm_head"][:vocab])
@@ -111,6 +113,12 @@ def main():
     ap.add_argument("--decode-steps", type=int, default=N_DECODE, help="decode steps per job (shorten for profiling)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the 32B-shaped model and the two-model loop")
+    ap.add_argument("--prefill-sizes", default="21,86,256,1024,4096",
+                    help="catch-up chunk lengths timed on the 32B-shaped model (one size for a kernel profile)")
+    ap.add_argument("--extras-layers", type=int, default=None,
+                    help="profiling aid: give the 32B-shaped model this many layers (per-kernel figures are unchanged)")
+    ap.add_argument("--only-extras", action="store_true",
+                    help="profiling aid: run only the 32B-shaped decode / prefill measurements, no headline job")
     ap.add_argument("--no-roofline", action="store_true",
                     help="skip the decode windows and the per-launch event timing (for counter-collection runs)")
     args = ap.parse_args()
@@ -122,6 +130,11 @@ def main():
     from paper_2504_12329_amd import binding as B, cost, synth
 
     torch.cuda.set_device(0)
+    sizes = tuple(int(v) for v in args.prefill_sizes.split(","))
+    if args.only_extras:
+        print(json.dumps({"target_model_32b": target_model_extras(torch, B, synth, cost, None, sizes, loop=False,
+                                                                       n_layers=args.extras_layers)}))
+        return
     n_dec = args.decode_steps
     cfg = synth.model_config("qwen1p5b", max_seq=PROMPT + N_DECODE + 64, max_chunk=PROMPT)
     w = synth.make_weights(cfg, 1, device="cuda")
@@ -199,7 +212,7 @@ def main():
         "roofline": roofline,
     }
     if not args.no_extras:
-        line["target_model_32b"] = target_model_extras(torch, B, synth, cost, model)
+        line["target_model_32b"] = target_model_extras(torch, B, synth, cost, model, sizes)
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(cfg, w, prompt)
     print(json.dumps(line))
