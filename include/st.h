@@ -115,12 +115,16 @@ int st_decode_step(st_model *m, int32_t token, float *logits, int32_t *next_tok,
 int st_decode_greedy(st_model *m, int32_t first_token, int32_t n, int32_t *out_tokens, uint32_t flags);
 
 /* Token-level form of the takeover trigger (Section 3 (1); keyword sets of Appendix C become
- * sets of token ids): a position p fires when tokens[p] is in the keyword set and, for
- * window == 2, p >= 1 and tokens[p-1] is in the delimiter set.  Sets are bitmaps over the
- * vocabulary (bit id&31 of 32-bit word id>>5) in device memory. */
+ * sets of token ids).  window == 1: a position p fires when tokens[p] is in the keyword set.
+ * window == w + 1 >= 2: p fires when the w tokens ending at p are the sentence after a delimiter
+ * (tokens[p-w] is a delimiter, none of tokens[p-w+1 .. p-1] is) and one of them is a keyword;
+ * w == 1 is "delimiter, then keyword".  Sets are bitmaps over the vocabulary (bit id&31 of 32-bit
+ * word id>>5) in device memory.  The decode step and st_generate evaluate windows 1 and 2 next to the
+ * arg-max; st_trigger_scan accepts windows up to ST_MAX_SCAN_WINDOW (sentences of n1 tokens). */
+#define ST_MAX_SCAN_WINDOW 257
 typedef struct {
     const uint32_t *kw_bitmap, *delim_bitmap; /* device; delim may be NULL when window == 1 */
-    int32_t window;                           /* 1 or 2 */
+    int32_t window;
     int32_t vocab;
 } st_trigger_rule;
 
@@ -173,6 +177,49 @@ typedef struct {
 int st_generate(st_model *small, st_model *large, const st_trigger_rule *rule, int32_t forced_period,
                 const int32_t *prompt, int32_t P, int32_t n_out, int32_t n_seg,
                 int32_t *seq, uint8_t *src, st_spans *spans, int32_t span_cap, st_gen_stats *stats);
+
+/* The full takeover policy of Section 3 on token ids: after every delimiter (written by either model, or the
+ * prompt's last token) the next `sentence_len` tokens form a sentence (a delimiter inside it restarts it); when its
+ * last token has been written -- and is not the last budgeted token -- it is classified:
+ *   (3) a sentence holding a `neg` token raises a counter; when the counter exceeds neg_threshold it restarts, the
+ *       auxiliary sentence aux_tokens is inserted and the target writes n3 tokens;
+ *   (2) else a sentence holding a `verify` token: the target writes n2 tokens;
+ *   (1) else, if the speculative model wrote the whole sentence and it holds an `ar` token (or `unconditional` is
+ *       set): the target writes n1 tokens -- after the sentence, or, with `replace`, in its place (the sentence is
+ *       dropped from seq and both KV caches are truncated to its start).
+ * (2) and (3) also fire on sentences inside the target's own segment: the tokens it still owes are replaced by the
+ * new grant.  The target first catches up on every token it has not seen; the last token it writes is not fed to
+ * it; the speculative model then catches up.  With initial_target > 0 the target writes that many tokens first.
+ * Bitmaps are HOST arrays of `vocab` bits (bit t of word t/32); NULL is the empty class.  aux_tokens is host memory. */
+typedef struct {
+    const uint32_t *delim_bitmap, *ar_bitmap, *verify_bitmap, *neg_bitmap;
+    int32_t vocab;
+    int32_t sentence_len;
+    int32_t n1, n2, n3;
+    int32_t neg_threshold;
+    const int32_t *aux_tokens;
+    int32_t n_aux;
+    int32_t replace, unconditional, initial_target;
+} st_policy;
+
+enum { ST_KIND_INITIAL = 0, ST_KIND_AR = 1, ST_KIND_VERIFY = 2, ST_KIND_EXCESS = 3 };
+enum { ST_SRC_SMALL = 0, ST_SRC_LARGE = 1, ST_SRC_AUX = 2 };
+
+/* One takeover: its kind, the position of the sentence's last token (-1 for the initial segment), tokens dropped
+ * by the replace reading, the positions of the inserted auxiliary sentence [aux_lo, aux_hi) (empty otherwise:
+ * both are the position where the target starts writing), and the tokens granted to the target. */
+typedef struct {
+    int32_t kind, sentence_end, dropped, aux_lo, aux_hi, granted;
+} st_action;
+
+/* Runs the policy until n_out output tokens exist.  Both models must have empty caches.  seq (host, capacity
+ * P + n_out) receives prompt + outputs; src (host, n_out bytes, may be NULL) an ST_SRC_* per output token; actions
+ * (host, capacity action_cap, may be NULL) one entry per takeover in order; stats->n_handoffs counts them all,
+ * stats->n_spans those written.  Errors: ST_EINVAL (NULL or malformed policy), ST_ERANGE (P + n_out exceeds a
+ * model's max_seq, token id outside the vocabulary), ST_EHIP. */
+int st_generate_policy(st_model *small, st_model *large, const st_policy *policy, const int32_t *prompt, int32_t P,
+                       int32_t n_out, int32_t *seq, uint8_t *src, st_action *actions, int32_t action_cap,
+                       st_gen_stats *stats);
 
 /* Measurement support: one chained greedy decode step (feeds the model's own last token) in which
  * every launch of the gate/up projection kernel -- the kernel that moves the most bytes of a step

@@ -32,13 +32,17 @@ class Trace:
 
 
 def window_rule(kw: Callable[[int], bool], delim: Callable[[int], bool] = None, window: int = 1):
-    """Predicate on (seq, p): kw(seq[p]) and, for window 2, p >= 1 and delim(seq[p-1])."""
+    """Predicate on (seq, p).  window 1: kw(seq[p]).  window w + 1 >= 2: the w tokens ending at p are the
+    sentence after a delimiter -- delim(seq[p-w]), no delimiter among seq[p-w+1 .. p-1] -- and hold a keyword."""
     def fire(seq: Sequence[int], p: int) -> bool:
-        if not kw(seq[p]):
-            return False
         if window == 1:
-            return True
-        return p >= 1 and delim(seq[p - 1])
+            return kw(seq[p])
+        w = window - 1
+        if p - w < 0 or not delim(seq[p - w]):
+            return False
+        if any(delim(t) for t in seq[p - w + 1:p]):
+            return False
+        return any(kw(t) for t in seq[p - w + 1:p + 1])
     return fire
 
 
@@ -103,6 +107,9 @@ class GreedyModel:
             self.logits.append((self.model.kv_len, lg))
         return self._o.argmax(lg)
 
+    def truncate(self, new_len):
+        self.model.truncate(new_len)
+
 
 # ---------------------------------------------------------------------------------------------------
 # The full policy of Section 3: (1) Affirmation/Reflection, (2) Verification and (3) Excessive-reflection
@@ -153,15 +160,18 @@ def speculative_thinking_policy(small, large, prompt: Sequence[int], n_out: int,
     if n_out <= 0:
         return tr
     w = pol.sentence_len
-    st = dict(kv_s=0, kv_l=0, c=0, start=None, all_small=True, pending=None)
+    st = dict(kv_s=0, kv_l=0, c=0, start=None, all_small=True, pending=None, pred={})
 
     def feed(which):
         model, key, log = (small, "kv_s", tr.small_feeds) if which == SMALL else (large, "kv_l", tr.large_feeds)
         lo, hi = st[key], len(seq)
+        if hi == lo:                       # nothing new (a replaced sentence right after the prompt): the
+            return st["pred"][which]       # prediction made for this position stands
         assert hi > lo
         log.append((lo, hi))
         st[key] = hi
-        return model.feed(seq[lo:hi])
+        st["pred"][which] = model.feed(seq[lo:hi])
+        return st["pred"][which]
 
     def done():
         return len(seq) - P >= n_out

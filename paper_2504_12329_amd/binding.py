@@ -17,7 +17,8 @@ ST_OK, ST_EINVAL, ST_ENOMEM, ST_ERANGE, ST_EHIP = 0, -1, -2, -3, -4
 ST_TOKENS_DEVICE, ST_OUT_DEVICE, ST_TOKEN_CHAINED = 1, 2, 4
 
 EXPORTS = ("st_query_sizes", "st_model_create", "st_model_destroy", "st_kv_len", "st_kv_truncate", "st_prefill",
-           "st_decode_step", "st_decode_step_timed", "st_decode_greedy", "st_trigger_scan", "st_handoff", "st_generate", "st_last_error")
+           "st_decode_step", "st_decode_step_timed", "st_decode_greedy", "st_trigger_scan", "st_handoff", "st_generate",
+           "st_generate_policy", "st_last_error")
 
 
 class StError(RuntimeError):
@@ -88,6 +89,9 @@ def lib():
         L.st_generate.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(st_trigger_rule), C.c_int32, C.c_void_p,
                                   C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.POINTER(st_spans),
                                   C.c_int32, C.POINTER(st_gen_stats)]
+        L.st_generate_policy.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(st_policy), C.c_void_p, C.c_int32, C.c_int32,
+                                         C.c_void_p, C.c_void_p, C.POINTER(st_action), C.c_int32,
+                                         C.POINTER(st_gen_stats)]
         _lib = L
     return _lib
 
@@ -240,4 +244,46 @@ def st_generate(small, large, rule, prompt, n_out, n_seg, forced_period=0, span_
                              C.cast(spans, C.POINTER(st_spans)), span_cap, C.byref(stats)))
     return dict(seq=seq[:p.size + stats.n_out], src=src[:stats.n_out],
                 spans=[spans[i].as_dict() for i in range(stats.n_spans)],
+                stats={n: getattr(stats, n) for n, _ in st_gen_stats._fields_})
+
+
+class st_policy(C.Structure):
+    _fields_ = [("delim_bitmap", C.c_void_p), ("ar_bitmap", C.c_void_p), ("verify_bitmap", C.c_void_p),
+                ("neg_bitmap", C.c_void_p), ("vocab", C.c_int32), ("sentence_len", C.c_int32), ("n1", C.c_int32),
+                ("n2", C.c_int32), ("n3", C.c_int32), ("neg_threshold", C.c_int32), ("aux_tokens", C.c_void_p),
+                ("n_aux", C.c_int32), ("replace", C.c_int32), ("unconditional", C.c_int32),
+                ("initial_target", C.c_int32)]
+
+
+class st_action(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("kind", "sentence_end", "dropped", "aux_lo", "aux_hi", "granted")]
+
+
+def host_bitmap(vocab, ids):
+    """Host bitmap of `vocab` bits with the given token ids set (uint32 words, bit t of word t // 32)."""
+    bm = np.zeros((vocab + 31) // 32, dtype=np.uint32)
+    ids = np.asarray(list(ids), dtype=np.int64)
+    np.bitwise_or.at(bm, ids >> 5, (np.uint32(1) << (ids & 31).astype(np.uint32)))
+    return bm
+
+
+def st_generate_policy(small, large, prompt, n_out, vocab, delim, sentence_len=1, ar=None, n1=20, verify=None, n2=125,
+                       neg=None, neg_threshold=15, aux=(), n3=125, replace=False, unconditional=False,
+                       initial_target=0, action_cap=4096):
+    """Runs the full takeover policy; delim / ar / verify / neg are host bitmaps (see host_bitmap) or None.
+    Returns dict(seq, src, actions, stats)."""
+    p = np.ascontiguousarray(prompt, dtype=np.int32)
+    seq = np.zeros(p.size + n_out, dtype=np.int32)
+    src = np.zeros(max(n_out, 1), dtype=np.uint8)
+    keep = [np.ascontiguousarray(b, dtype=np.uint32) if b is not None else None for b in (delim, ar, verify, neg)]
+    auxa = np.ascontiguousarray(list(aux), dtype=np.int32)
+    ptr = lambda a: a.ctypes.data if a is not None and a.size else None
+    pol = st_policy(ptr(keep[0]), ptr(keep[1]), ptr(keep[2]), ptr(keep[3]), vocab, sentence_len, n1, n2, n3,
+                    neg_threshold, ptr(auxa), auxa.size, int(replace), int(unconditional), initial_target)
+    acts = (st_action * max(action_cap, 1))()
+    stats = st_gen_stats()
+    _check(lib().st_generate_policy(small._h, large._h, C.byref(pol), _np_ptr(p), p.size, n_out, _np_ptr(seq),
+                                    _np_ptr(src), C.cast(acts, C.POINTER(st_action)), action_cap, C.byref(stats)))
+    return dict(seq=seq[:p.size + stats.n_out], src=src[:stats.n_out],
+                actions=[tuple(getattr(acts[i], n) for n, _ in st_action._fields_) for i in range(stats.n_spans)],
                 stats={n: getattr(stats, n) for n, _ in st_gen_stats._fields_})

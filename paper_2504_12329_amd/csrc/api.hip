@@ -437,8 +437,8 @@ int st_decode_step_timed(st_model *h, double *gateup_mean_us, double *step_us) {
 int st_trigger_scan(const st_trigger_rule *rule, const int32_t *tokens, int32_t lo, int32_t hi, int32_t *positions,
                     int32_t cap, int32_t *n_found, int32_t *scratch, void *stream, uint32_t flags) {
     if (!rule || !rule->kw_bitmap || !tokens || !n_found) return fail(ST_EINVAL, "rule, bitmap, tokens or n_found is NULL");
-    if (rule->window != 1 && rule->window != 2) return fail(ST_EINVAL, "window must be 1 or 2");
-    if (rule->window == 2 && !rule->delim_bitmap) return fail(ST_EINVAL, "window 2 needs a delimiter bitmap");
+    if (rule->window < 1 || rule->window > ST_MAX_SCAN_WINDOW) return fail(ST_EINVAL, "window must be in [1, %d]", ST_MAX_SCAN_WINDOW);
+    if (rule->window >= 2 && !rule->delim_bitmap) return fail(ST_EINVAL, "a window above 1 needs a delimiter bitmap");
     if (rule->vocab <= 0) return fail(ST_EINVAL, "rule vocab must be positive");
     if (int rc = check_flags(flags, ST_OUT_DEVICE)) return rc;
     if (cap < 0 || (cap > 0 && !positions)) return fail(ST_EINVAL, "cap < 0, or positions is NULL with cap > 0");
@@ -528,6 +528,183 @@ int st_generate(st_model *hs, st_model *hl, const st_trigger_rule *rule, int32_t
             st.ms_small_decode += ms(a, clk::now());
         }
     }
+    st.n_out = T - P;
+    if (stats) *stats = st;
+    return ST_OK;
+}
+
+int st_generate_policy(st_model *hs, st_model *hl, const st_policy *pol, const int32_t *prompt, int32_t P,
+                       int32_t n_out, int32_t *seq, uint8_t *src, st_action *actions, int32_t action_cap,
+                       st_gen_stats *stats) {
+    using clk = std::chrono::steady_clock;
+    if (!hs || !hl || !pol || !prompt || !seq) return fail(ST_EINVAL, "small, large, policy, prompt or seq is NULL");
+    if (hs == hl) return fail(ST_EINVAL, "small and large must be different models");
+    if (!pol->delim_bitmap || pol->vocab <= 0) return fail(ST_EINVAL, "the policy needs a delimiter bitmap and a vocabulary size");
+    if (pol->sentence_len < 1) return fail(ST_EINVAL, "sentence_len must be >= 1");
+    if ((pol->ar_bitmap || pol->unconditional) && pol->n1 < 1) return fail(ST_EINVAL, "n1 must be positive");
+    if (pol->verify_bitmap && pol->n2 < 1) return fail(ST_EINVAL, "n2 must be positive");
+    if (pol->neg_bitmap && (pol->n3 < 1 || pol->neg_threshold < 0 || pol->n_aux < 0 || (pol->n_aux > 0 && !pol->aux_tokens)))
+        return fail(ST_EINVAL, "malformed excessive-reflection settings");
+    if (pol->initial_target < 0) return fail(ST_EINVAL, "initial_target must be >= 0");
+    if (P <= 0 || n_out < 0) return fail(ST_ERANGE, "P must be positive and n_out non-negative");
+    if (action_cap < 0 || (action_cap > 0 && !actions)) return fail(ST_EINVAL, "bad action buffer");
+    Model *M[2] = {reinterpret_cast<Model *>(hs), reinterpret_cast<Model *>(hl)};
+    if (M[0]->kv_len != 0 || M[1]->kv_len != 0) return fail(ST_EINVAL, "both models must start with an empty KV cache");
+    if ((int64_t)P + n_out > M[0]->c.max_seq || (int64_t)P + n_out > M[1]->c.max_seq)
+        return fail(ST_ERANGE, "P + n_out = %d exceeds a model's max_seq", P + n_out);
+    for (int32_t i = 0; i < pol->n_aux; ++i)
+        if (pol->aux_tokens[i] < 0 || pol->aux_tokens[i] >= pol->vocab) return fail(ST_ERANGE, "auxiliary token outside the vocabulary");
+
+    auto in_class = [&](const uint32_t *bm, int32_t t) {
+        return bm && t >= 0 && t < pol->vocab && ((bm[t >> 5] >> (t & 31)) & 1u);
+    };
+    st_gen_stats st = {};
+    memcpy(seq, prompt, sizeof(int32_t) * P);
+    int32_t T = P;                       // tokens in seq
+    int32_t pred_pos[2] = {-1, -1};      // position the model's last feed predicted, and that token
+    int32_t pred_tok[2] = {0, 0};
+    double *ms_prefill[2] = {&st.ms_small_prefill, &st.ms_large_prefill};
+    double *ms_decode[2] = {&st.ms_small_decode, &st.ms_large_decode};
+    int rc_out = ST_OK;
+
+    // feeds model w every token of seq it has not seen; its greedy prediction becomes pred_tok[w]
+    auto feed = [&](int w) -> bool {
+        Model *m = M[w];
+        const int32_t lo = m->kv_len, n = T - lo;
+        if (n == 0 && pred_pos[w] == T) return true;  // nothing new (a replaced sentence right after the prompt)
+        auto a = clk::now();
+        int rc;
+        const bool own = n == 1 && pred_pos[w] == lo && pred_tok[w] == seq[lo];  // its own last token: decode step
+        if (own)
+            rc = decode_impl(m, nullptr, nullptr);
+        else
+            rc = prefill_impl(m, seq + lo, n, false, nullptr);
+        if (!rc) rc = fetch_token(m, &pred_tok[w], nullptr);
+        if (rc) {
+            rc_out = rc;
+            return false;
+        }
+        pred_pos[w] = T;
+        *(own ? ms_decode[w] : ms_prefill[w]) += std::chrono::duration<double, std::milli>(clk::now() - a).count();
+        return true;
+    };
+    auto done = [&]() { return T - P >= n_out; };
+    if (n_out == 0) {
+        if (stats) *stats = st;
+        return ST_OK;
+    }
+
+    int32_t start = -1, counter = 0;     // armed sentence start (or -1) and the negativity counter
+    bool all_small = true;
+    int pend_kind = -1, pend_s = 0, pend_e = 0;
+    // appends one output token, does the sentence bookkeeping; true when the budget is spent
+    auto emit = [&](int32_t tok, int source) {
+        seq[T] = tok;
+        if (src) src[T - P] = (uint8_t)source;
+        const int32_t pos = T++;
+        if (source == ST_SRC_LARGE) ++st.n_large;
+        pend_kind = -1;
+        if (start >= 0) {
+            if (source != ST_SRC_SMALL) all_small = false;
+            if (pos == start + pol->sentence_len - 1) {
+                bool neg = false, ver = false, ar = false;
+                for (int32_t q = start; q <= pos; ++q) {
+                    neg |= in_class(pol->neg_bitmap, seq[q]);
+                    ver |= in_class(pol->verify_bitmap, seq[q]);
+                    ar |= in_class(pol->ar_bitmap, seq[q]);
+                }
+                int kind = -1;
+                if (neg && ++counter > pol->neg_threshold) {
+                    counter = 0;
+                    kind = ST_KIND_EXCESS;
+                }
+                if (kind < 0 && ver) kind = ST_KIND_VERIFY;
+                if (kind < 0 && all_small && (pol->unconditional || ar)) kind = ST_KIND_AR;
+                if (kind >= 0) pend_kind = kind, pend_s = start, pend_e = pos;
+                start = -1;
+            }
+        }
+        if (in_class(pol->delim_bitmap, tok)) start = pos + 1, all_small = true;
+        return done();
+    };
+    auto log_action = [&](int kind, int32_t e, int32_t dropped, int32_t aux_lo, int32_t aux_hi, int32_t granted) {
+        if (st.n_spans < action_cap) actions[st.n_spans++] = st_action{kind, e, dropped, aux_lo, aux_hi, granted};
+        ++st.n_handoffs;
+    };
+    auto insert_aux = [&](int32_t *lo, int32_t *hi) {
+        *lo = T;
+        for (int32_t i = 0; i < pol->n_aux; ++i)
+            if (emit(pol->aux_tokens[i], ST_SRC_AUX)) break;
+        pend_kind = -1;  // the inserted sentence triggers nothing itself
+        *hi = T;
+    };
+    // the target writes n tokens (the count restarts when (2) or (3) fires on its own text), then the speculative
+    // model catches up; returns 1 when the budget ran out, 0 to continue, negative on error
+    auto target_segment = [&](int32_t n, bool have_pred) -> int {
+        int32_t remaining = n;
+        if (!have_pred && !feed(1)) return -1;
+        while (remaining > 0) {
+            if (emit(pred_tok[1], ST_SRC_LARGE)) return 1;
+            --remaining;
+            if (pend_kind == ST_KIND_EXCESS) {
+                int32_t lo, hi, e = pend_e;
+                insert_aux(&lo, &hi);
+                log_action(ST_KIND_EXCESS, e, 0, lo, hi, pol->n3);
+                if (done()) return 1;
+                remaining = pol->n3;
+            } else if (pend_kind == ST_KIND_VERIFY) {
+                log_action(ST_KIND_VERIFY, pend_e, 0, T, T, pol->n2);
+                remaining = pol->n2;
+            }
+            if (remaining > 0 && !feed(1)) return -1;  // the segment's last token is not fed to the target
+        }
+        return feed(0) ? 0 : -1;
+    };
+
+    if (!feed(0) || !feed(1)) return rc_out;
+    if (in_class(pol->delim_bitmap, seq[P - 1])) start = P, all_small = true;
+    if (pol->initial_target > 0) {
+        log_action(ST_KIND_INITIAL, -1, 0, P, P, pol->initial_target);
+        int r = target_segment(pol->initial_target, true);
+        if (r < 0) return rc_out;
+        if (r > 0) goto finished;
+    }
+    while (true) {
+        if (emit(pred_tok[0], ST_SRC_SMALL)) break;
+        if (pend_kind < 0) {
+            if (!feed(0)) return rc_out;
+            continue;
+        }
+        int32_t n;
+        if (pend_kind == ST_KIND_AR) {
+            int32_t dropped = 0;
+            if (pol->replace) {  // the drafted sentence goes; the target writes in its place
+                dropped = pend_e - pend_s + 1;
+                T = pend_s;
+                for (int w = 0; w < 2; ++w)
+                    if (M[w]->kv_len > pend_s) {
+                        launch_set_state(*M[w], kPos, pend_s);
+                        if (int rc = check_launch("truncate")) return rc;
+                        M[w]->kv_len = pend_s;
+                    }
+            }
+            log_action(ST_KIND_AR, pend_e, dropped, T, T, pol->n1);
+            n = pol->n1;
+        } else if (pend_kind == ST_KIND_VERIFY) {
+            log_action(ST_KIND_VERIFY, pend_e, 0, T, T, pol->n2);
+            n = pol->n2;
+        } else {
+            int32_t lo, hi, e = pend_e;
+            insert_aux(&lo, &hi);
+            log_action(ST_KIND_EXCESS, e, 0, lo, hi, pol->n3);
+            if (done()) break;
+            n = pol->n3;
+        }
+        int r = target_segment(n, false);
+        if (r < 0) return rc_out;
+        if (r > 0) break;
+    }
+finished:
     st.n_out = T - P;
     if (stats) *stats = st;
     return ST_OK;

@@ -1,5 +1,5 @@
-// Token-level takeover trigger (paper Section 3 (1), keyword sets of Appendix C as id bitmaps):
-// an ordered, exact scan of a token range.  One 1024-thread block walks the range in tiles and
+// Token-level takeover trigger (paper Section 3 (1), keyword sets of Appendix C as id bitmaps; window > 2
+// is the n1-token sentence after a delimiter): an ordered, exact scan of a token range.  One 1024-thread block walks the range in tiles and
 // compacts the firing positions in ascending order with wave ballots.
 #include "st_device.h"
 #include "st_internal.h"
@@ -24,8 +24,22 @@ __global__ __launch_bounds__(1024) void k_trigger_scan(const int32_t *__restrict
         int p = start + (int)threadIdx.x;
         bool fire = false;
         if (p < hi) {
-            fire = in_set(kw, tokens[p], vocab);
-            if (fire && window == 2) fire = p >= 1 && in_set(delim, tokens[p - 1], vocab);
+            if (window == 1) {
+                fire = in_set(kw, tokens[p], vocab);
+            } else {
+                // the sentence of window - 1 tokens ending at p: delimiter right before it, none inside it
+                // before its last token, a keyword somewhere in it
+                const int first = p - (window - 1) + 1;
+                if (first >= 1 && in_set(delim, tokens[first - 1], vocab)) {
+                    bool ok = true, any = false;
+                    for (int q = first; q <= p; ++q) {
+                        const int t = tokens[q];
+                        if (q < p && in_set(delim, t, vocab)) ok = false;
+                        any |= in_set(kw, t, vocab);
+                    }
+                    fire = ok && any;
+                }
+            }
         }
         unsigned long long mask = __ballot(fire);
         int before = __popcll(mask & ((1ull << lane) - 1ull));

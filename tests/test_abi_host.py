@@ -37,6 +37,8 @@ def test_struct_sizes_match_header():
     assert C.sizeof(B.st_spans) == 6 * 4
     assert C.sizeof(B.st_trigger_rule) == 2 * 8 + 2 * 4
     assert C.sizeof(B.st_gen_stats) == 4 * 4 + 4 * 8
+    assert C.sizeof(B.st_policy) == 4 * 8 + 6 * 4 + 8 + 4 * 4     # 4 bitmaps, 6 ints, aux pointer, 4 ints
+    assert C.sizeof(B.st_action) == 6 * 4
 
 
 def test_query_sizes_and_config_validation(L):

@@ -249,7 +249,7 @@ def test_single_handoff_call(pair):
         B.st_handoff(gs, gl, seq, 44, 8, 100)
 
 
-@pytest.mark.parametrize("window", [1, 2])
+@pytest.mark.parametrize("window", [1, 2, 4, 21])
 def test_trigger_scan_bit_exact(window):
     rng = np.random.default_rng(10 + window)
     V = 151936
@@ -262,6 +262,8 @@ def test_trigger_scan_bit_exact(window):
             idx = rng.integers(1, n, 40)
             toks[idx] = 97 * rng.integers(0, 1500, 40)
             toks[idx - 1] = 89 * rng.integers(0, 1700, 40)
+            back = np.maximum(idx - rng.integers(1, max(window, 2), 40), 0)   # delimiters up to a sentence back
+            toks[back] = 89 * rng.integers(0, 1700, 40)
             toks[0] = 0
             toks[n - 1] = 97
             toks[n - 2] = 89
@@ -270,6 +272,8 @@ def test_trigger_scan_bit_exact(window):
         assert got_n == want_n and got_pos.tolist() == want_pos.tolist(), (n, lo, hi)
         got_n, got_pos = B.st_trigger_scan(rule, torch.from_numpy(toks).cuda(), lo, hi, cap=3)
         assert got_n == want_n and got_pos.tolist() == want_pos.tolist()[:3]
+    with pytest.raises(B.StError):
+        B.st_trigger_scan(B.TriggerRule(V, kw, dl, 300), torch.zeros(4, dtype=torch.int32).cuda(), 0, 4, cap=4)
     # ids outside the vocabulary never fire on the device (the oracle rejects them outright)
     small_rule = B.TriggerRule(64, synth.modulo_bitmap(64, 1))
     toks = np.array([3, 64, -1, 5, 1 << 30], np.int32)

@@ -101,3 +101,15 @@ def test_budget_spent_inside_the_auxiliary_sentence():
     tr = S.speculative_thinking_policy(Stub(0), Stub(base), [1, 2, 3, 5], 18, pol)   # 17 small tokens + 1 of 2 aux
     assert tr.seq[-1] == 901 and tr.src[-1] == S.AUX and len(tr.src) == 18
     assert tr.large_feeds == [(0, 4)]
+
+
+def test_replaced_sentence_right_after_the_prompt():
+    """The prompt ends on a delimiter and the first sentence is replaced: the target has nothing to catch up on
+    and writes from its prediction after the prompt."""
+    pol = S.Policy(delim=lambda t: t % 6 == 0, sentence_len=2, ar=lambda t: t % 5 == 0, n1=2, replace=True)
+    small, large = Stub(0), Stub(500)
+    tr = S.speculative_thinking_policy(small, large, [1, 2, 3, 6], 6, pol)       # sentence = ids 4, 5 -> dropped
+    assert tr.seq == [1, 2, 3, 6, 504, 505, 6, 7, 8, 9]
+    assert tr.actions == [(S.KIND_AR, 5, 2, 4, 4, 2)]
+    assert tr.large_feeds == [(0, 4), (4, 5)] and tr.small_truncates == [4]
+    assert tr.small_feeds == [(0, 4), (4, 5), (4, 6), (6, 7), (7, 8), (8, 9)]

@@ -6,10 +6,19 @@ from paper_2504_12329_amd import cost, synth
 
 
 def _brute(tokens, lo, hi, kwset, delimset, window):
-    out = []
-    for p in range(lo, hi):
-        if tokens[p] in kwset and (window == 1 or (p >= 1 and tokens[p - 1] in delimset)):
-            out.append(p)
+    """Window 1: keyword positions.  Otherwise the sentence bookkeeping of the takeover policy replayed from the
+    first token: a delimiter arms the sentence that starts after it (a delimiter inside re-arms it); the position
+    where a sentence of window - 1 tokens completes fires when the sentence holds a keyword."""
+    if window == 1:
+        return [p for p in range(lo, hi) if tokens[p] in kwset]
+    w, start, out = window - 1, None, []
+    for q in range(len(tokens)):
+        if start is not None and q == start + w - 1:
+            if lo <= q < hi and any(t in kwset for t in tokens[start:q + 1]):
+                out.append(q)
+            start = None
+        if tokens[q] in delimset:
+            start = q + 1
     return out
 
 
@@ -21,7 +30,7 @@ def test_modulo_bitmap():
     assert sum(bin(int(x)).count("1") for x in bm) == len(range(0, 151936, 97))
 
 
-@pytest.mark.parametrize("window", [1, 2])
+@pytest.mark.parametrize("window", [1, 2, 3, 5, 21])
 def test_trigger_scan_bruteforce(oracle_lib, window):
     rng = np.random.default_rng(window)
     V = 300
@@ -30,6 +39,9 @@ def test_trigger_scan_bruteforce(oracle_lib, window):
     for trial in range(30):
         n = int(rng.integers(0, 200))
         toks = rng.integers(0, V, n).astype(np.int32)
+        if window > 2 and n:                  # long windows need sparse delimiters to fire at all
+            toks[toks % 3 == 0] += 1
+            toks[rng.integers(0, n, max(1, n // (2 * window)))] = 3 * rng.integers(0, V // 3, max(1, n // (2 * window)))
         if n > 3:
             toks[0] = 0                       # id 0 is divisible by everything; p = 0 has no predecessor
             toks[rng.integers(0, n)] = 21
@@ -50,6 +62,13 @@ def test_trigger_scan_hand_cases(oracle_lib):
     assert oracle_lib.trigger_scan(toks, 0, 9, V, kw, dl, 1, 9)[1].tolist() == [0, 2, 3, 6, 8]
     assert oracle_lib.trigger_scan(toks, 2, 3, V, kw, dl, 2, 9)[1].tolist() == [2]   # looks back before lo
     assert oracle_lib.trigger_scan(toks, 4, 4, V, kw, dl, 1, 9)[0] == 0              # empty range
+    # sentences of 3 tokens (window 4) worked by hand; ids: delimiter % 3, keyword % 5
+    #        pos 0  1  2  3  4  5   6  7  8  9  10 11 12 13 14
+    toks = np.array([1, 3, 7, 8, 5, 2, 6, 4, 9, 10, 7, 3, 1, 1, 20], np.int32)
+    # 3@1 arms (2,3,4): 5 at 4 -> fires at 4.  6@6 arms (7,8,9) but 9@8 is a delimiter inside -> re-armed at 9:
+    # (9,10,11) holds 10 and ends on a delimiter (allowed) -> fires at 11.  3@11 arms (12,13,14): 20 -> fires at 14.
+    assert oracle_lib.trigger_scan(toks, 0, 15, V, kw, dl, 4, 9)[1].tolist() == [4, 11, 14]
+    assert oracle_lib.trigger_scan(toks, 5, 14, V, kw, dl, 4, 9)[1].tolist() == [11]
     with pytest.raises(ValueError):
         oracle_lib.trigger_scan(np.array([64], np.int32), 0, 1, V, kw, dl, 1, 4)
 
