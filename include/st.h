@@ -221,6 +221,27 @@ int st_generate_policy(st_model *small, st_model *large, const st_policy *policy
                        int32_t n_out, int32_t *seq, uint8_t *src, st_action *actions, int32_t action_cap,
                        st_gen_stats *stats);
 
+/* A batch of up to 64 independent sequences that share one set of weights (the many-concurrent-sequences regime
+ * the paper's outlook describes): every sequence has its own KV cache and length; one decode step advances any
+ * subset of them by one token each, streaming the weights once for all rows.  Sizes as for a model, times n_seq
+ * for the cache; cfg->max_chunk must be at least n_seq.  All token / logits pointers are host memory and the
+ * calls synchronise the stream.  Errors as for the single-sequence calls. */
+typedef struct st_batch st_batch;
+int st_batch_query_sizes(const st_config *cfg, int32_t n_seq, size_t *kv_bytes, size_t *workspace_bytes);
+int st_batch_create(const st_config *cfg, const st_weights *w, int32_t n_seq, void *kv, size_t kv_bytes,
+                    void *workspace, size_t workspace_bytes, void *stream, st_batch **out);
+void st_batch_destroy(st_batch *b);
+int st_batch_kv_len(const st_batch *b, int32_t seq, int32_t *out);
+int st_batch_truncate(st_batch *b, int32_t seq, int32_t new_len);
+/* Feeds n tokens to sequence `seq` (catch-up pass of that sequence alone); logits (fp32[vocab]) and next_tok of the
+ * last position if not NULL. */
+int st_batch_prefill(st_batch *b, int32_t seq, const int32_t *tokens, int32_t n, float *logits, int32_t *next_tok);
+/* One decode step for the n_rows distinct sequences seqs[r], feeding tokens[r] at each sequence's own position
+ * (ragged lengths): logits (fp32[n_rows][vocab], may be NULL) and greedy next_tokens[r] (may be NULL); every listed
+ * sequence grows by one. */
+int st_batch_decode_step(st_batch *b, int32_t n_rows, const int32_t *seqs, const int32_t *tokens, float *logits,
+                         int32_t *next_tokens);
+
 /* Measurement support: one chained greedy decode step (feeds the model's own last token) in which
  * every launch of the gate/up projection kernel -- the kernel that moves the most bytes of a step
  * (2 * intermediate * hidden bf16 weights per launch) -- carries HIP start/stop events on the

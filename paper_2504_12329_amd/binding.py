@@ -18,7 +18,8 @@ ST_TOKENS_DEVICE, ST_OUT_DEVICE, ST_TOKEN_CHAINED = 1, 2, 4
 
 EXPORTS = ("st_query_sizes", "st_model_create", "st_model_destroy", "st_kv_len", "st_kv_truncate", "st_prefill",
            "st_decode_step", "st_decode_step_timed", "st_decode_greedy", "st_trigger_scan", "st_handoff", "st_generate",
-           "st_generate_policy", "st_last_error")
+           "st_generate_policy", "st_batch_query_sizes", "st_batch_create", "st_batch_destroy", "st_batch_kv_len",
+           "st_batch_truncate", "st_batch_prefill", "st_batch_decode_step", "st_last_error")
 
 
 class StError(RuntimeError):
@@ -92,6 +93,15 @@ def lib():
         L.st_generate_policy.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(st_policy), C.c_void_p, C.c_int32, C.c_int32,
                                          C.c_void_p, C.c_void_p, C.POINTER(st_action), C.c_int32,
                                          C.POINTER(st_gen_stats)]
+        L.st_batch_query_sizes.argtypes = [C.POINTER(st_config), C.c_int32, C.POINTER(C.c_size_t), C.POINTER(C.c_size_t)]
+        L.st_batch_create.argtypes = [C.POINTER(st_config), C.POINTER(st_weights), C.c_int32, C.c_void_p, C.c_size_t,
+                                      C.c_void_p, C.c_size_t, C.c_void_p, C.POINTER(C.c_void_p)]
+        L.st_batch_destroy.argtypes = [C.c_void_p]
+        L.st_batch_destroy.restype = None
+        L.st_batch_kv_len.argtypes = [C.c_void_p, C.c_int32, i32p]
+        L.st_batch_truncate.argtypes = [C.c_void_p, C.c_int32, C.c_int32]
+        L.st_batch_prefill.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
+        L.st_batch_decode_step.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         _lib = L
     return _lib
 
@@ -287,3 +297,75 @@ def st_generate_policy(small, large, prompt, n_out, vocab, delim, sentence_len=1
     return dict(seq=seq[:p.size + stats.n_out], src=src[:stats.n_out],
                 actions=[tuple(getattr(acts[i], n) for n, _ in st_action._fields_) for i in range(stats.n_spans)],
                 stats={n: getattr(stats, n) for n, _ in st_gen_stats._fields_})
+
+
+def _weights_struct(cfg, weights):
+    """st_weights over the tensors of synth.make_weights; returns (struct, objects to keep alive)."""
+    L = cfg["n_layers"]
+    w = st_weights()
+    w.embed = weights["embed"].data_ptr()
+    w.lm_head = 0 if weights.get("lm_head") is None else weights["lm_head"].data_ptr()
+    w.final_norm = weights["final_norm"].data_ptr()
+    keep = []
+    for name in ("wqkv", "bqkv", "wo", "w_gate_up", "w_down", "norm_attn", "norm_mlp"):
+        arr = (C.c_void_p * L)(*[lw[name].data_ptr() for lw in weights["layers"]])
+        keep.append(arr)
+        setattr(w, name, C.cast(arr, _vpp))
+    return w, keep
+
+
+class Batch:
+    """st_batch: n_seq independent sequences over one set of weights, torch-owned device buffers."""
+
+    def __init__(self, cfg, weights, n_seq, stream=None):
+        self.cfg, self.weights, self.n_seq = dict(cfg), weights, n_seq
+        dev = weights["embed"].device
+        if dev.type != "cuda":
+            raise RuntimeError("weights must live on the GPU")
+        kv, ws = C.c_size_t(), C.c_size_t()
+        _check(lib().st_batch_query_sizes(C.byref(make_config(cfg)), n_seq, C.byref(kv), C.byref(ws)))
+        self.kv = torch.empty(kv.value, dtype=torch.uint8, device=dev)
+        self.ws = torch.empty(ws.value, dtype=torch.uint8, device=dev)
+        w, self._arrays = _weights_struct(cfg, weights)
+        self.stream = torch.cuda.current_stream(dev).cuda_stream if stream is None else stream
+        h = C.c_void_p()
+        _check(lib().st_batch_create(C.byref(make_config(cfg)), C.byref(w), n_seq, self.kv.data_ptr(), kv.value,
+                                     self.ws.data_ptr(), ws.value, self.stream, C.byref(h)))
+        self._h = h
+
+    def close(self):
+        if getattr(self, "_h", None):
+            lib().st_batch_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def kv_len(self, seq):
+        n = C.c_int32()
+        _check(lib().st_batch_kv_len(self._h, seq, C.byref(n)))
+        return n.value
+
+    def truncate(self, seq, n):
+        _check(lib().st_batch_truncate(self._h, seq, n))
+
+    def prefill(self, seq, tokens, want_logits=True):
+        t = np.ascontiguousarray(tokens, dtype=np.int32)
+        lg = np.empty(self.cfg["vocab"], dtype=np.float32) if want_logits else None
+        tok = C.c_int32()
+        _check(lib().st_batch_prefill(self._h, seq, _np_ptr(t), t.size, _np_ptr(lg) if want_logits else None,
+                                      C.byref(tok)))
+        return lg, tok.value
+
+    def decode_step(self, seqs, tokens, want_logits=False):
+        s = np.ascontiguousarray(seqs, dtype=np.int32)
+        t = np.ascontiguousarray(tokens, dtype=np.int32)
+        assert s.size == t.size
+        lg = np.empty((s.size, self.cfg["vocab"]), dtype=np.float32) if want_logits else None
+        nxt = np.empty(s.size, dtype=np.int32)
+        _check(lib().st_batch_decode_step(self._h, s.size, _np_ptr(s), _np_ptr(t),
+                                          _np_ptr(lg) if want_logits else None, _np_ptr(nxt)))
+        return lg, nxt

@@ -259,11 +259,8 @@ int st_query_sizes(const st_config *cfg, size_t *kv_bytes, size_t *workspace_byt
     return ST_OK;
 }
 
-int st_model_create(const st_config *cfg, const st_weights *w, void *kv, size_t kv_bytes, void *workspace,
-                    size_t workspace_bytes, void *stream, st_model **out) {
-    if (!out) return fail(ST_EINVAL, "out is NULL");
-    *out = nullptr;
-    if (int rc = validate_config(cfg)) return rc;
+// Checks the weights and fills a model record over the given cache and workspace (sizes checked by the caller).
+static int build_model(const st_config *cfg, const st_weights *w, void *kv, void *workspace, void *stream, Model *m) {
     if (!w) return fail(ST_EINVAL, "weights is NULL");
     if (!w->embed || !w->final_norm || (!cfg->tie_embeddings && !w->lm_head))
         return fail(ST_EINVAL, "embed, final_norm or lm_head is NULL");
@@ -277,15 +274,6 @@ int st_model_create(const st_config *cfg, const st_weights *w, void *kv, size_t 
     if (!kv || !workspace) return fail(ST_EINVAL, "kv or workspace is NULL");
     if (((uintptr_t)kv & 255) || ((uintptr_t)workspace & 255))
         return fail(ST_EINVAL, "kv and workspace must be 256-byte aligned");
-    Workspace sized;
-    carve_workspace(*cfg, nullptr, &sized);
-    if (kv_bytes < kv_bytes_of(*cfg))
-        return fail(ST_ENOMEM, "kv buffer has %zu bytes, %zu needed", kv_bytes, kv_bytes_of(*cfg));
-    if (workspace_bytes < sized.bytes)
-        return fail(ST_ENOMEM, "workspace has %zu bytes, %zu needed", workspace_bytes, sized.bytes);
-
-    Model *m = new (std::nothrow) Model();
-    if (!m) return fail(ST_ENOMEM, "out of host memory");
     m->c = *cfg;
     m->qkv_dim = (cfg->n_q_heads + 2 * cfg->n_kv_heads) * cfg->head_dim;
     auto cp = [&](std::vector<const bf16_t *> &dst, const void *const *src) {
@@ -311,7 +299,23 @@ int st_model_create(const st_config *cfg, const st_weights *w, void *kv, size_t 
     m->capture_stream = nullptr;
     m->graphs_off = getenv("ST_NO_GRAPH") != nullptr;
     launch_init(*m);
-    if (int rc = check_launch("workspace initialisation")) {
+    return check_launch("workspace initialisation");
+}
+
+int st_model_create(const st_config *cfg, const st_weights *w, void *kv, size_t kv_bytes, void *workspace,
+                    size_t workspace_bytes, void *stream, st_model **out) {
+    if (!out) return fail(ST_EINVAL, "out is NULL");
+    *out = nullptr;
+    if (int rc = validate_config(cfg)) return rc;
+    Workspace sized;
+    carve_workspace(*cfg, nullptr, &sized);
+    if (kv && kv_bytes < kv_bytes_of(*cfg))
+        return fail(ST_ENOMEM, "kv buffer has %zu bytes, %zu needed", kv_bytes, kv_bytes_of(*cfg));
+    if (workspace && workspace_bytes < sized.bytes)
+        return fail(ST_ENOMEM, "workspace has %zu bytes, %zu needed", workspace_bytes, sized.bytes);
+    Model *m = new (std::nothrow) Model();
+    if (!m) return fail(ST_ENOMEM, "out of host memory");
+    if (int rc = build_model(cfg, w, kv, workspace, stream, m)) {
         delete m;
         return rc;
     }
@@ -707,6 +711,152 @@ int st_generate_policy(st_model *hs, st_model *hl, const st_policy *pol, const i
 finished:
     st.n_out = T - P;
     if (stats) *stats = st;
+    return ST_OK;
+}
+
+// ---- a batch of independent sequences sharing one set of weights ----
+namespace {
+struct Batch {
+    Model base;                    // sequence 0's caches; the workspace is shared by all sequences
+    int32_t n_seq;
+    std::vector<int32_t> kv_len;
+    size_t seq_stride;             // elements between consecutive sequences' caches
+    int32_t *row_ints;             // device: tok | pos | seq | next, n_seq each
+    float *q_rows, *o_rows, *part_ml, *part_acc, *logits;
+};
+constexpr int kMaxBatch = 64;
+
+size_t batch_extra(const st_config &c, int32_t n, char *base, Batch *b) {
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        char *p = base ? base + off : nullptr;
+        off += (bytes + 255) & ~(size_t)255;
+        return p;
+    };
+    const size_t qd = (size_t)c.n_q_heads * c.head_dim;
+    int32_t *ri = (int32_t *)take(sizeof(int32_t) * 4 * n);
+    float *q = (float *)take(sizeof(float) * n * qd), *o = (float *)take(sizeof(float) * n * qd);
+    float *ml = (float *)take(sizeof(float) * (size_t)n * c.n_q_heads * kAttnSplits * 2);
+    float *acc = (float *)take(sizeof(float) * (size_t)n * c.n_q_heads * kAttnSplits * c.head_dim);
+    float *lg = (float *)take(sizeof(float) * (size_t)n * c.vocab);
+    if (b) b->row_ints = ri, b->q_rows = q, b->o_rows = o, b->part_ml = ml, b->part_acc = acc, b->logits = lg;
+    return off;
+}
+int check_batch(const st_config *cfg, int32_t n_seq) {
+    if (int rc = validate_config(cfg)) return rc;
+    if (n_seq < 1 || n_seq > kMaxBatch) return fail(ST_ERANGE, "n_seq must be in [1, %d]", kMaxBatch);
+    if (cfg->max_chunk < n_seq) return fail(ST_ERANGE, "max_chunk (%d) must be at least n_seq (%d)", cfg->max_chunk, n_seq);
+    return ST_OK;
+}
+}  // namespace
+
+int st_batch_query_sizes(const st_config *cfg, int32_t n_seq, size_t *kv_bytes, size_t *workspace_bytes) {
+    if (int rc = check_batch(cfg, n_seq)) return rc;
+    if (kv_bytes) *kv_bytes = kv_bytes_of(*cfg) * (size_t)n_seq;
+    if (workspace_bytes) {
+        Workspace ws;
+        carve_workspace(*cfg, nullptr, &ws);
+        *workspace_bytes = ws.bytes + batch_extra(*cfg, n_seq, nullptr, nullptr);
+    }
+    return ST_OK;
+}
+
+int st_batch_create(const st_config *cfg, const st_weights *w, int32_t n_seq, void *kv, size_t kv_bytes,
+                    void *workspace, size_t workspace_bytes, void *stream, st_batch **out) {
+    if (!out) return fail(ST_EINVAL, "out is NULL");
+    *out = nullptr;
+    if (int rc = check_batch(cfg, n_seq)) return rc;
+    Workspace sized;
+    carve_workspace(*cfg, nullptr, &sized);
+    const size_t need_kv = kv_bytes_of(*cfg) * (size_t)n_seq, need_ws = sized.bytes + batch_extra(*cfg, n_seq, nullptr, nullptr);
+    if (kv && kv_bytes < need_kv) return fail(ST_ENOMEM, "kv buffer has %zu bytes, %zu needed", kv_bytes, need_kv);
+    if (workspace && workspace_bytes < need_ws)
+        return fail(ST_ENOMEM, "workspace has %zu bytes, %zu needed", workspace_bytes, need_ws);
+    Batch *b = new (std::nothrow) Batch();
+    if (!b) return fail(ST_ENOMEM, "out of host memory");
+    if (int rc = build_model(cfg, w, kv, workspace, stream, &b->base)) {
+        delete b;
+        return rc;
+    }
+    b->base.graphs_off = true;  // the batched step is launched kernel by kernel
+    b->n_seq = n_seq;
+    b->kv_len.assign(n_seq, 0);
+    b->seq_stride = kv_bytes_of(*cfg) / sizeof(bf16_t);
+    batch_extra(*cfg, n_seq, (char *)workspace + sized.bytes, b);
+    *out = reinterpret_cast<st_batch *>(b);
+    return ST_OK;
+}
+
+void st_batch_destroy(st_batch *h) { delete reinterpret_cast<Batch *>(h); }
+
+int st_batch_kv_len(const st_batch *h, int32_t seq, int32_t *out) {
+    const Batch *b = reinterpret_cast<const Batch *>(h);
+    if (!b || !out) return fail(ST_EINVAL, "batch or out is NULL");
+    if (seq < 0 || seq >= b->n_seq) return fail(ST_ERANGE, "sequence %d outside [0, %d)", seq, b->n_seq);
+    *out = b->kv_len[seq];
+    return ST_OK;
+}
+
+int st_batch_truncate(st_batch *h, int32_t seq, int32_t new_len) {
+    Batch *b = reinterpret_cast<Batch *>(h);
+    if (!b) return fail(ST_EINVAL, "batch is NULL");
+    if (seq < 0 || seq >= b->n_seq) return fail(ST_ERANGE, "sequence %d outside [0, %d)", seq, b->n_seq);
+    if (new_len < 0 || new_len > b->kv_len[seq])
+        return fail(ST_ERANGE, "new_len %d outside [0, %d]", new_len, b->kv_len[seq]);
+    b->kv_len[seq] = new_len;
+    return ST_OK;
+}
+
+int st_batch_prefill(st_batch *h, int32_t seq, const int32_t *tokens, int32_t n, float *logits, int32_t *next_tok) {
+    Batch *b = reinterpret_cast<Batch *>(h);
+    if (!b) return fail(ST_EINVAL, "batch is NULL");
+    if (seq < 0 || seq >= b->n_seq) return fail(ST_ERANGE, "sequence %d outside [0, %d)", seq, b->n_seq);
+    Model view = b->base;  // same weights and workspace, this sequence's caches
+    view.kcache = b->base.kcache + (size_t)seq * b->seq_stride;
+    view.vcache = b->base.vcache + (size_t)seq * b->seq_stride;
+    view.kv_len = b->kv_len[seq];
+    if (int rc = prefill_impl(&view, tokens, n, false, nullptr)) return rc;
+    b->kv_len[seq] = view.kv_len;
+    return deliver(&view, logits, next_tok, false);
+}
+
+int st_batch_decode_step(st_batch *h, int32_t n_rows, const int32_t *seqs, const int32_t *tokens, float *logits,
+                         int32_t *next_tokens) {
+    Batch *b = reinterpret_cast<Batch *>(h);
+    if (!b || !seqs || !tokens) return fail(ST_EINVAL, "batch, seqs or tokens is NULL");
+    if (n_rows < 1 || n_rows > b->n_seq) return fail(ST_ERANGE, "n_rows must be in [1, %d]", b->n_seq);
+    const st_config &c = b->base.c;
+    std::vector<int32_t> host(3 * (size_t)n_rows);
+    uint64_t seen = 0;
+    int32_t max_pos = 0;
+    for (int32_t r = 0; r < n_rows; ++r) {
+        const int32_t s = seqs[r];
+        if (s < 0 || s >= b->n_seq) return fail(ST_ERANGE, "sequence %d outside [0, %d)", s, b->n_seq);
+        if (seen >> s & 1) return fail(ST_EINVAL, "sequence %d appears twice in one step", s);
+        seen |= (uint64_t)1 << s;
+        if (tokens[r] < 0 || tokens[r] >= c.vocab)
+            return fail(ST_ERANGE, "token id %d of row %d is outside the vocabulary [0,%d)", tokens[r], r, c.vocab);
+        if (b->kv_len[s] + 1 > c.max_seq) return fail(ST_ERANGE, "KV overflow in sequence %d", s);
+        host[r] = tokens[r];
+        host[n_rows + r] = b->kv_len[s];
+        host[2 * (size_t)n_rows + r] = s;
+        if (b->kv_len[s] > max_pos) max_pos = b->kv_len[s];
+    }
+    int32_t *dev = b->row_ints;
+    ST_HIP(hipMemcpyAsync(dev, host.data(), sizeof(int32_t) * host.size(), hipMemcpyHostToDevice, b->base.stream));
+    ST_HIP(hipStreamSynchronize(b->base.stream));  // `host` leaves scope before the copy would otherwise be read
+    BatchRows rows = {dev, dev + n_rows, dev + 2 * (size_t)n_rows, dev + 3 * (size_t)b->n_seq, b->seq_stride,
+                      b->q_rows, b->o_rows, b->part_ml, b->part_acc, logits ? b->logits : nullptr};
+    launch_batch_step(b->base, rows, n_rows, attn_bucket(max_pos + 1));
+    if (int rc = check_launch("batched decode step")) return rc;
+    if (logits)
+        ST_HIP(hipMemcpyAsync(logits, b->logits, sizeof(float) * (size_t)n_rows * c.vocab, hipMemcpyDeviceToHost,
+                              b->base.stream));
+    if (next_tokens)
+        ST_HIP(hipMemcpyAsync(next_tokens, rows.row_next, sizeof(int32_t) * n_rows, hipMemcpyDeviceToHost,
+                              b->base.stream));
+    ST_HIP(hipStreamSynchronize(b->base.stream));
+    for (int32_t r = 0; r < n_rows; ++r) b->kv_len[seqs[r]] += 1;
     return ST_OK;
 }
 

@@ -490,11 +490,13 @@ __device__ __forceinline__ int attn_chunk(int t, int S) {
     return ((chunk + kKeyTile - 1) / kKeyTile) * kKeyTile;
 }
 
+// blockIdx.z is a row of a batch of independent sequences (one row, sequence 0, in the single-sequence step):
+// rows.pos[z] is the position of that row's new token, rows.seq[z] the sequence whose cache it attends to.
 template <int D, int G>
 __global__ __launch_bounds__(256) void k_attn_partial(const float *__restrict__ q, const bf16_t *__restrict__ kc,
-                                                      const bf16_t *__restrict__ vc, const int32_t *__restrict__ state,
-                                                      int max_seq, int S, float *__restrict__ part_ml,
-                                                      float *__restrict__ part_acc, float *__restrict__ out) {
+                                                      const bf16_t *__restrict__ vc, AttnRows rows, int max_seq, int S,
+                                                      float *__restrict__ part_ml, float *__restrict__ part_acc,
+                                                      float *__restrict__ out) {
     constexpr int LPK = D / 8;            // lanes sharing one key in the P.V phase
     constexpr int KSL = 256 / LPK;        // key slots of the block in the P.V phase
     constexpr int KPS = kKeyTile / KSL;   // keys per slot per tile
@@ -505,12 +507,22 @@ __global__ __launch_bounds__(256) void k_attn_partial(const float *__restrict__ 
     __shared__ float run_m[G], run_l[G], corr_s[G];
     __shared__ float red_acc[4][G][D];
 
-    const int t = state[kPos] + 1;  // keys 0..pos, the new one included
+    const int row = blockIdx.z;
+    const int t = rows.pos[row] + 1;  // keys 0..pos, the new one included
     const int chunk = attn_chunk(t, S);
     const int s_active = (t + chunk - 1) / chunk;
     const int s = blockIdx.x, g = blockIdx.y;
     if (s >= s_active) return;
     const int k0 = s * chunk, k1 = min(t, k0 + chunk);
+    {
+        const size_t cache = (rows.seq ? (size_t)rows.seq[row] : 0) * rows.seq_stride;
+        kc += cache;
+        vc += cache;
+        q += (size_t)row * rows.q_stride;
+        out += (size_t)row * rows.q_stride;
+        part_ml += (size_t)row * rows.ml_stride;
+        part_acc += (size_t)row * rows.acc_stride;
+    }
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int dl = tid % LPK, ks = tid / LPK;
@@ -649,16 +661,19 @@ __global__ __launch_bounds__(256) void k_attn_partial(const float *__restrict__ 
 // elements; group j sums the ranges i = j (mod 256/D) in ascending order and the groups are
 // added in a fixed order.  The per-range weights exp2(m_i - M) are computed once into LDS.
 template <int D>
-__global__ __launch_bounds__(256) void k_attn_combine(const int32_t *__restrict__ state, int S,
-                                                      const float *__restrict__ part_ml,
+__global__ __launch_bounds__(256) void k_attn_combine(AttnRows rows, int S, const float *__restrict__ part_ml,
                                                       const float *__restrict__ part_acc, float *__restrict__ out) {
     constexpr int NG = 256 / D;
     __shared__ float m_s[kAttnSplits], wl_s[kAttnSplits][2];
     __shared__ float red[NG][D];
-    const int t = state[kPos] + 1;
+    const int row = blockIdx.z;
+    const int t = rows.pos[row] + 1;
     const int chunk = attn_chunk(t, S);
     const int s_active = (t + chunk - 1) / chunk;
     if (s_active == 1) return;  // the first kernel already wrote the result
+    part_ml += (size_t)row * rows.ml_stride;
+    part_acc += (size_t)row * rows.acc_stride;
+    out += (size_t)row * rows.q_stride;
     const int hh = blockIdx.x, tid = threadIdx.x, e = tid % D, grp = tid / D;
     const size_t p0 = (size_t)hh * S;
     // this thread's slice of the unnormalised outputs, issued before anything waits
@@ -717,16 +732,16 @@ void launch_set_state(const Model &m, int slot, int32_t value) {
 }
 
 template <int D>
-static void launch_attn(const Model &m, int layer, hipStream_t stream, int attn_blocks) {
+static void launch_attn_t(const Model &m, int layer, hipStream_t stream, int attn_blocks, const AttnRows &rows,
+                          int n_rows, const float *q, float *part_ml, float *part_acc, float *out) {
     const st_config &c = m.c;
     const int G = c.n_q_heads / c.n_kv_heads;
     size_t lofs = (size_t)layer * c.n_kv_heads * c.max_seq * c.head_dim;
-    dim3 grid(attn_blocks, c.n_kv_heads), block(256);
-#define ST_ATTN_CASE(GG)                                                                                     \
-    case GG:                                                                                                 \
-        hipLaunchKernelGGL((k_attn_partial<D, GG>), grid, block, 0, stream, m.ws.q1, m.kcache + lofs,        \
-                           m.vcache + lofs, m.ws.state, c.max_seq, kAttnSplits, m.ws.part_ml, m.ws.part_acc, \
-                           m.ws.o1);                                                                         \
+    dim3 grid(attn_blocks, c.n_kv_heads, n_rows), block(256);
+#define ST_ATTN_CASE(GG)                                                                                           \
+    case GG:                                                                                                       \
+        hipLaunchKernelGGL((k_attn_partial<D, GG>), grid, block, 0, stream, q, m.kcache + lofs, m.vcache + lofs,   \
+                           rows, c.max_seq, kAttnSplits, part_ml, part_acc, out);                                  \
         break;
     switch (G) {
         ST_ATTN_CASE(1) ST_ATTN_CASE(2) ST_ATTN_CASE(3) ST_ATTN_CASE(4)
@@ -734,8 +749,23 @@ static void launch_attn(const Model &m, int layer, hipStream_t stream, int attn_
     }
 #undef ST_ATTN_CASE
     if (attn_blocks > 1)  // a single range is finished by the first kernel
-        hipLaunchKernelGGL(k_attn_combine<D>, dim3(c.n_q_heads), dim3(256), 0, stream, m.ws.state, kAttnSplits,
-                           m.ws.part_ml, m.ws.part_acc, m.ws.o1);
+        hipLaunchKernelGGL(k_attn_combine<D>, dim3(c.n_q_heads, 1, n_rows), dim3(256), 0, stream, rows, kAttnSplits,
+                           part_ml, part_acc, out);
+}
+
+// the single-sequence step: one row whose position is state[kPos], sequence 0
+template <int D>
+static void launch_attn(const Model &m, int layer, hipStream_t stream, int attn_blocks) {
+    const AttnRows rows = {m.ws.state + kPos, nullptr, 0, 0, 0, 0};
+    launch_attn_t<D>(m, layer, stream, attn_blocks, rows, 1, m.ws.q1, m.ws.part_ml, m.ws.part_acc, m.ws.o1);
+}
+
+void launch_attn_rows(const Model &m, int layer, hipStream_t stream, int attn_blocks, const AttnRows &rows, int n_rows,
+                      const float *q, float *part_ml, float *part_acc, float *out) {
+    if (m.c.head_dim == 128)
+        launch_attn_t<128>(m, layer, stream, attn_blocks, rows, n_rows, q, part_ml, part_acc, out);
+    else
+        launch_attn_t<64>(m, layer, stream, attn_blocks, rows, n_rows, q, part_ml, part_acc, out);
 }
 
 // Rows per block of the residual GEMV: among the candidates that give 480..1024 blocks, the one

@@ -477,6 +477,122 @@ __global__ __launch_bounds__(256) void k_gemm_ring(const bf16_t *__restrict__ A,
 }
 
 // ---------------------------------------------------------------------------------------
+// Short chunks (at most 128 rows, two-term activations): the weight stream sets the time, so the kernel is built
+// to keep bytes in flight.  A block owns 128 weight rows and a K slice; weights and both activation terms go
+// global -> LDS directly in 128-byte row segments into a ring of NS stages of (16 + MT*8) KB (all of LDS: up to
+// 80 KB of weights in flight per CU, no staging registers), one barrier per 64-wide K step.  Wave w multiplies its
+// 32 weight rows with every 32-row activation tile (C^T = W A^T, so a lane owns an activation row) and the raw fp32
+// partial sums of the K slice go to part[z][M][N] like those of the other GEMMs.  Needs K % 64 == 0.
+// ---------------------------------------------------------------------------------------
+template <int MT>
+struct SkinnyShape {
+    static constexpr int kWBytes = 128 * kRingBK * 2;             // 16 KB of weights per stage
+    static constexpr int kABytes = MT * 64 * kRingBK * 2;         // hi and lo rows of MT 32-row tiles
+    static constexpr int kStage = kWBytes + kABytes;
+    static constexpr int kStages = (160 * 1024) / kStage;         // 6, 5, 4, 3 for MT = 1..4
+    static constexpr int kLoads = 4 + 2 * MT;                     // direct loads per wave per stage
+};
+
+template <int MT>
+__global__ __launch_bounds__(256) void k_gemm_skinny(const bf16_t *__restrict__ A, const bf16_t *__restrict__ Alo,
+                                                     int lda, const bf16_t *__restrict__ B, int M, int N, int K,
+                                                     int kps, float *__restrict__ part) {
+    using S = SkinnyShape<MT>;
+    constexpr int NS = S::kStages, DPS = S::kLoads;
+    extern __shared__ __align__(16) unsigned char ring[];
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l32 = lane & 31, kg = lane >> 5;
+    const int n0 = blockIdx.x * 128;
+    const int kbeg = blockIdx.y * kps;
+    const int nk = (min(K, kbeg + kps) - kbeg) / kRingBK;
+    const uint32_t ring0 = (uint32_t)(uintptr_t)ring;
+
+    // direct loads: a 1 KB instruction fills 8 LDS rows of 128 bytes; lane -> (row lane/8, 16-byte position lane%8
+    // holding global chunk position ^ swizzle(row)).  Weights: instructions 4*wave .. +3 (rows 32*wave .. +31);
+    // activations: LDS row 64*t + 32*term + r is row 32*t + r of term (0 = high, 1 = low); rows past the edge re-read
+    // the last valid row and are never stored.
+    const bf16_t *pw[4], *pa[2 * MT];
+    int a_lds[2 * MT];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int row = (wave * 4 + i) * 8 + (lane >> 3);
+        pw[i] = B + (size_t)min(n0 + row, N - 1) * K + kbeg + ((lane & 7) ^ ring_swz(row)) * 8;
+    }
+#pragma unroll
+    for (int i = 0; i < 2 * MT; ++i) {
+        const int inst = wave * 2 * MT + i;                       // of 8*MT instructions, 8 rows each
+        const int row = inst * 8 + (lane >> 3);
+        const int t = row >> 6, term = (row >> 5) & 1, r = row & 31;
+        pa[i] = (term ? Alo : A) + (size_t)min(t * 32 + r, M - 1) * lda + kbeg + ((lane & 7) ^ ring_swz(row)) * 8;
+        a_lds[i] = S::kWBytes + inst * 1024;
+    }
+    auto issue = [&](int st) {
+        const uint32_t base = ring0 + (st % NS) * S::kStage;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) load_to_lds16(pw[i] + st * kRingBK, base + (wave * 4 + i) * 1024);
+#pragma unroll
+        for (int i = 0; i < 2 * MT; ++i) load_to_lds16(pa[i] + st * kRingBK, base + a_lds[i]);
+    };
+
+    f32x16 acc[MT];
+#pragma unroll
+    for (int t = 0; t < MT; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
+
+    // fragment reads (see k_gemm_ring): chunk (2*ks + kg) ^ swizzle, swizzle(32*b + l32) = swizzle(l32) ^ 4*(b & 1)
+    const int ch0 = (kg ^ ring_swz(l32)) * 16;
+    const int w_off = (wave * 32 + l32) * 128, w_ch = ch0 ^ ((wave & 1) * 64);
+
+    for (int st = 0; st < NS - 1 && st < nk; ++st) issue(st);
+    for (int st = 0; st < nk; ++st) {
+        // stage st has landed once at most the stages after it are outstanding
+        switch (min(nk, st + NS - 1) - (st + 1)) {
+            case 0: wait_loads<0>(); break;
+            case 1: wait_loads<DPS>(); break;
+            case 2: wait_loads<2 * DPS>(); break;
+            case 3: wait_loads<(NS > 4 ? 3 : 0) * DPS>(); break;
+            default: wait_loads<(NS > 5 ? 4 : 0) * DPS>(); break;
+        }
+        __builtin_amdgcn_s_barrier();  // stage st complete for every wave; every wave is done with stage st-1
+        if (st + NS - 1 < nk) issue(st + NS - 1);
+        const unsigned char *base = ring + (st % NS) * S::kStage;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            const bf16x8 wf = as_bf16x8(*reinterpret_cast<const u32x4 *>(base + w_off + (w_ch ^ (ks * 32))));
+#pragma unroll
+            for (int t = 0; t < MT; ++t) {
+                const unsigned char *ab = base + S::kWBytes + (t * 64 + l32) * 128;
+                const bf16x8 ah = as_bf16x8(*reinterpret_cast<const u32x4 *>(ab + (ch0 ^ (ks * 32))));
+                const bf16x8 al = as_bf16x8(*reinterpret_cast<const u32x4 *>(ab + 32 * 128 + (ch0 ^ 64 ^ (ks * 32))));
+                acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, ah, acc[t], 0, 0, 0);
+                acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, al, acc[t], 0, 0, 0);
+            }
+        }
+    }
+    // C^T tile: lane = activation row (column of the MFMA result), register r = weight row 8*(r/4) + 4*kg + r%4
+    float *pz = part + (size_t)blockIdx.y * M * N;
+#pragma unroll
+    for (int t = 0; t < MT; ++t) {
+        const int m = t * 32 + l32;
+        if (m >= M) continue;
+#pragma unroll
+        for (int rq = 0; rq < 4; ++rq) {
+            const int n = n0 + wave * 32 + 8 * rq + 4 * kg;
+            float *dst = pz + (size_t)m * N + n;
+            if (n + 3 < N && (N & 3) == 0) {
+                *reinterpret_cast<float4 *>(dst) =
+                    make_float4(acc[t][4 * rq + 0], acc[t][4 * rq + 1], acc[t][4 * rq + 2], acc[t][4 * rq + 3]);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (n + e < N) dst[e] = acc[t][4 * rq + e];
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------
 // RoPE on q and k at absolute positions pos0 + row, K/V appended to the cache, q kept as bf16.
 // grid (rows, heads), block d/2 threads: one rotation pair per thread.
 // ---------------------------------------------------------------------------------------
@@ -1009,24 +1125,51 @@ __global__ __launch_bounds__(64 * NW, 2) void k_flash_long(const bf16_t *__restr
     }
 }
 
-// Merges the key splits of one (token, head): block = 256 threads = 256/D rows x D elements.
+// Merges the key splits of one (token, head): block = 256 threads = 256/D rows x D elements.  The (max, sum) pairs
+// of all splits (at most 32) are fetched by the first threads of each row in one go and turned into weights in
+// LDS; the partial outputs are then loaded eight splits at a time, so nothing waits on a chain of dependent loads.
+// Splits are added in ascending order.
 template <int D>
 __global__ __launch_bounds__(256) void k_flash_combine(const float *__restrict__ part_o,
                                                        const float *__restrict__ part_ml, int n_split, int n_rows,
                                                        bf16_t *__restrict__ out, bf16_t *__restrict__ outlo) {
-    const int r = blockIdx.x * (256 / D) + threadIdx.x / D, e = threadIdx.x % D;
-    if (r >= n_rows) return;
+    constexpr int RPB = 256 / D, kMaxSplits = 32;
+    __shared__ float m_s[RPB][kMaxSplits], w_s[RPB][kMaxSplits], l_s[RPB];
+    const int g = threadIdx.x / D, e = threadIdx.x % D;
+    const int r = blockIdx.x * RPB + g;
+    const bool live = r < n_rows;
+    float2 ml = make_float2(-INFINITY, 0.f);
+    if (live && e < n_split) ml = reinterpret_cast<const float2 *>(part_ml)[(size_t)e * n_rows + r];
+    if (e < kMaxSplits) m_s[g][e] = ml.x;
+    __syncthreads();
     float M = -INFINITY;
-    for (int z = 0; z < n_split; ++z) M = fmaxf(M, part_ml[((size_t)z * n_rows + r) * 2]);
-    float L = 0.f, A = 0.f;
-    for (int z = 0; z < n_split; ++z) {
-        const size_t pr = (size_t)z * n_rows + r;
-        const float mz = part_ml[pr * 2];
-        const float w = mz == -INFINITY ? 0.f : exp2f(mz - M);
-        L += part_ml[pr * 2 + 1] * w;
-        A += part_o[pr * D + e] * w;
+    for (int z = 0; z < n_split; ++z) M = fmaxf(M, m_s[g][z]);
+    if (e < kMaxSplits) {
+        const float w = ml.x == -INFINITY ? 0.f : exp2f(ml.x - M);
+        w_s[g][e] = w;
+        m_s[g][e] = w * ml.y;   // reused: weighted row sums
     }
-    const float v = A / L;
+    __syncthreads();
+    if (e == 0) {
+        float L = 0.f;
+        for (int z = 0; z < n_split; ++z) L += m_s[g][z];
+        l_s[g] = L;
+    }
+    float A = 0.f;
+    if (live) {
+        for (int z0 = 0; z0 < n_split; z0 += 8) {
+            float v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                v[u] = z0 + u < n_split ? part_o[((size_t)(z0 + u) * n_rows + r) * D + e] : 0.f;
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                if (z0 + u < n_split) A += v[u] * w_s[g][z0 + u];
+        }
+    }
+    __syncthreads();
+    if (!live) return;
+    const float v = A / l_s[g];
     const bf16_t hi = f32_to_bf16(v);
     out[(size_t)r * D + e] = hi;
     if (outlo) outlo[(size_t)r * D + e] = f32_to_bf16(v - bf16_to_f32(hi));
@@ -1074,13 +1217,50 @@ static void ring_launch(const Model &m, dim3 grid, const bf16_t *A, int lda, con
     hipLaunchKernelGGL(kern, grid, dim3(256), kRingLds, m.stream, A, lda, B, M, N, K, kps, m.ws.qkv, outb, ldo, gg);
 }
 
-// Chunks of at most kSmallRows rows use the 32- / 64-row tiles, many K slices and an unfused SwiGLU.
-constexpr int kSmallRows = 64;
+template <int MT>
+static void skinny_launch(const Model &m, dim3 grid, const bf16_t *A, const bf16_t *Alo, int lda, const bf16_t *B, int M,
+                          int N, int K, int kps) {
+    auto kern = k_gemm_skinny<MT>;
+    constexpr int lds = SkinnyShape<MT>::kStages * SkinnyShape<MT>::kStage;
+    static bool raised = false;  // more than 64 KB of dynamic LDS has to be allowed once per kernel
+    if (!raised) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        raised = true;
+    }
+    hipLaunchKernelGGL(kern, grid, dim3(256), lds, m.stream, A, Alo, lda, B, M, N, K, kps, m.ws.qkv);
+}
+
+// Chunks of at most kSmallRows rows (kSkinnyRows where the skinny kernel applies) use many K slices and an unfused
+// SwiGLU.
+constexpr int kSmallRows = 64, kSkinnyRows = 128;
 
 template <bool DUAL>
 static int gemm(const Model &m, const bf16_t *A, const bf16_t *Alo, int lda, const bf16_t *B, int M, int N, int K,
                 bf16_t *outb, bf16_t *outlo, int ldo) {
     const bool big = !Alo && M >= kBigRows && K % kRingBK == 0 && K >= 2 * kRingBK;
+    if (!DUAL && Alo && M <= kSkinnyRows && K % kRingBK == 0) {
+        // short two-term chunk: 128 weight rows per block; K slices so that every CU holds a block where the tiles
+        // are few, as long as a slice keeps eight K steps and the partial sums (slices x M x N x 8 bytes written
+        // and read) stay below half the weight bytes (N x K x 2)
+        const int tiles = (N + 127) / 128, nk = K / kRingBK;
+        int splits = tiles < 256 ? 256 / tiles : 1;
+        if (splits > nk / 8) splits = nk / 8 > 1 ? nk / 8 : 1;
+        const int by_traffic = K / (8 * M) > 1 ? K / (8 * M) : 1;
+        if (splits > by_traffic) splits = by_traffic;
+        if (splits > 32) splits = 32;
+        const size_t cap = partial_floats(m.c);
+        while (splits > 1 && (size_t)splits * M * N > cap) --splits;
+        const int kps = (nk + splits - 1) / splits * kRingBK;
+        splits = (K + kps - 1) / kps;
+        dim3 grid(tiles, splits);
+        switch ((M + 31) / 32) {
+            case 1: skinny_launch<1>(m, grid, A, Alo, lda, B, M, N, K, kps); break;
+            case 2: skinny_launch<2>(m, grid, A, Alo, lda, B, M, N, K, kps); break;
+            case 3: skinny_launch<3>(m, grid, A, Alo, lda, B, M, N, K, kps); break;
+            default: skinny_launch<4>(m, grid, A, Alo, lda, B, M, N, K, kps); break;
+        }
+        return splits;
+    }
     // two-term chunks of at most 32 / 64 rows use 32- / 64-row tiles with two waves: less LDS per block,
     // so more blocks per CU keep more of the weight stream in flight
     const int BM = big ? 256 : (Alo && M <= 32) ? 32 : (Alo && M <= 64) ? 64 : 128;
@@ -1190,7 +1370,8 @@ void launch_prefill_layers(const Model &m, int32_t pos0, int32_t n) {
         int so = gemm<false>(m, w.attn, attn_lo, qd, m.wo[l], n, h, qd, nullptr, nullptr, 0);
         hipLaunchKernelGGL(k_rmsnorm_rows, dim3(n), dim3(256), 0, m.stream, w.x, w.qkv, so, (size_t)n * h,
                            m.norm_mlp[l], w.xn, xn_lo, h, c.rms_eps);
-        if (n <= kSmallRows) {  // small chunk: gate/up as a plain split-K GEMM over all 2I rows, SwiGLU in the consumer
+        if (n <= (h % kRingBK == 0 ? kSkinnyRows : kSmallRows)) {  // small chunk: gate/up as a plain split-K GEMM over
+                                                                   // all 2I rows, SwiGLU in the consumer
             int sg = gemm<false>(m, w.xn, xn_lo, h, m.wgu[l], n, 2 * I, h, nullptr, nullptr, 0);
             hipLaunchKernelGGL(k_swiglu_rows, dim3((I / 4 + 255) / 256, n), dim3(256), 0, m.stream, w.qkv, sg,
                                (size_t)n * 2 * I, I, w.act, act_lo);
@@ -1202,6 +1383,126 @@ void launch_prefill_layers(const Model &m, int32_t pos0, int32_t n) {
     // the head needs the last row only: fold the last down projection into it
     hipLaunchKernelGGL(k_rmsnorm_rows, dim3(1), dim3(256), 0, m.stream, w.x + (size_t)(n - 1) * h,
                        w.qkv + (size_t)(n - 1) * h, pending, (size_t)n * h, nullptr, nullptr, nullptr, h, c.rms_eps);
+}
+
+// ---------------------------------------------------------------------------------------
+// One decode step for a batch of independent sequences sharing the weights (the "many sequences at once" regime):
+// the rows of the step are different sequences at their own positions, so the projections are the short-chunk
+// GEMMs above (the weights are streamed once for all rows), RoPE / KV append go row by row to each sequence's
+// cache, attention is the split decode attention with one grid plane per row, and the LM head is one more GEMM
+// followed by a per-row arg-max.
+// ---------------------------------------------------------------------------------------
+// RoPE at each row's own position, K/V appended to each row's own cache, q kept in fp32 (as in the single step).
+__global__ void k_rope_append_rows(const float *__restrict__ part, int n_part, size_t part_stride,
+                                   const bf16_t *__restrict__ bias, const float2 *__restrict__ rope,
+                                   float *__restrict__ q_rows, bf16_t *__restrict__ kc, bf16_t *__restrict__ vc,
+                                   const int32_t *__restrict__ row_pos, const int32_t *__restrict__ row_seq,
+                                   size_t seq_stride, int nq, int nkv, int d, int max_seq) {
+    const int row = blockIdx.x, head = blockIdx.y, i = threadIdx.x, half = d >> 1;
+    const int pos = row_pos[row];
+    const size_t cache = (size_t)row_seq[row] * seq_stride;
+    const size_t off = (size_t)row * (nq + 2 * nkv) * d + head * d;
+    float lo = 0.f, hi = 0.f;
+    for (int s = 0; s < n_part; ++s) {
+        const float *src = part + (size_t)s * part_stride + off;
+        lo += src[i];
+        hi += src[i + half];
+    }
+    if (bias) {
+        lo += bf16_to_f32(bias[head * d + i]);
+        hi += bf16_to_f32(bias[head * d + i + half]);
+    }
+    if (head < nq + nkv) {
+        float2 cs = rope[(size_t)pos * half + i];
+        float nlo = lo * cs.x - hi * cs.y;
+        float nhi = hi * cs.x + lo * cs.y;
+        lo = nlo;
+        hi = nhi;
+    }
+    if (head < nq) {
+        float *dst = q_rows + (size_t)row * nq * d + head * d;
+        dst[i] = lo;
+        dst[i + half] = hi;
+        return;
+    }
+    bf16_t *dst = head < nq + nkv ? kc + cache + ((size_t)(head - nq) * max_seq + pos) * d
+                                  : vc + cache + ((size_t)(head - nq - nkv) * max_seq + pos) * d;
+    dst[i] = f32_to_bf16(lo);
+    dst[i + half] = f32_to_bf16(hi);
+}
+
+// fp32 rows -> two bf16 terms (GEMM input of the O projection)
+__global__ __launch_bounds__(256) void k_rows_two_term(const float *__restrict__ src, bf16_t *__restrict__ hi,
+                                                       bf16_t *__restrict__ lo, size_t n) {
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n) return;
+    const float v = src[i];
+    const bf16_t h = f32_to_bf16(v);
+    hi[i] = h;
+    lo[i] = f32_to_bf16(v - bf16_to_f32(h));
+}
+
+// Row r: logits[r][:] = sum of the K slices (also stored when logits != nullptr), next[r] = arg-max, lowest id on ties.
+__global__ __launch_bounds__(1024) void k_argmax_rows(const float *__restrict__ part, int n_part, size_t part_stride,
+                                                      int V, float *__restrict__ logits, int32_t *__restrict__ next) {
+    __shared__ float bv[16];
+    __shared__ int bi[16];
+    const int row = blockIdx.x, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    float best = -INFINITY;
+    int arg = 0x7fffffff;
+    for (int v = threadIdx.x; v < V; v += 1024) {
+        float a = 0.f;
+        for (int s = 0; s < n_part; ++s) a += part[(size_t)s * part_stride + (size_t)row * V + v];
+        if (logits) logits[(size_t)row * V + v] = a;
+        if (a > best) best = a, arg = v;  // ascending v per thread: the first maximum is kept
+    }
+    for (int o = 32; o > 0; o >>= 1) {
+        const float ob = __shfl_xor(best, o, kWave);
+        const int oa = __shfl_xor(arg, o, kWave);
+        if (ob > best || (ob == best && oa < arg)) best = ob, arg = oa;
+    }
+    if (lane == 0) bv[wave] = best, bi[wave] = arg;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int w = 1; w < 16; ++w)
+            if (bv[w] > best || (bv[w] == best && bi[w] < arg)) best = bv[w], arg = bi[w];
+        next[row] = arg;
+    }
+}
+
+void launch_batch_step(const Model &m, const BatchRows &b, int n, int attn_blocks) {
+    const st_config &c = m.c;
+    const int h = c.hidden, d = c.head_dim, nq = c.n_q_heads, nkv = c.n_kv_heads, I = c.intermediate;
+    const int qd = nq * d, qkv = m.qkv_dim;
+    const Workspace &w = m.ws;
+    const AttnRows rows = {b.row_pos, b.row_seq, b.seq_stride, qd, (size_t)nq * kAttnSplits * 2,
+                           (size_t)nq * kAttnSplits * d};
+    hipLaunchKernelGGL(k_embed_rows, dim3(n), dim3(256), 0, m.stream, m.embed, b.row_tok, w.x, h, c.vocab);
+    int pending = 0;
+    for (int l = 0; l < c.n_layers; ++l) {
+        const size_t lofs = (size_t)l * nkv * c.max_seq * d;
+        hipLaunchKernelGGL(k_rmsnorm_rows, dim3(n), dim3(256), 0, m.stream, w.x, w.qkv, pending, (size_t)n * h,
+                           m.norm_attn[l], w.xn, w.xn_lo, h, c.rms_eps);
+        const int sq = gemm<false>(m, w.xn, w.xn_lo, h, m.wqkv[l], n, qkv, h, nullptr, nullptr, 0);
+        hipLaunchKernelGGL(k_rope_append_rows, dim3(n, nq + 2 * nkv), dim3(d / 2), 0, m.stream, w.qkv, sq,
+                           (size_t)n * qkv, m.bqkv[l], w.rope, b.q_rows, m.kcache + lofs, m.vcache + lofs, b.row_pos,
+                           b.row_seq, b.seq_stride, nq, nkv, d, c.max_seq);
+        launch_attn_rows(m, l, m.stream, attn_blocks, rows, n, b.q_rows, b.part_ml, b.part_acc, b.o_rows);
+        hipLaunchKernelGGL(k_rows_two_term, dim3(((size_t)n * qd + 255) / 256), dim3(256), 0, m.stream, b.o_rows,
+                           w.attn, w.attn_lo, (size_t)n * qd);
+        const int so = gemm<false>(m, w.attn, w.attn_lo, qd, m.wo[l], n, h, qd, nullptr, nullptr, 0);
+        hipLaunchKernelGGL(k_rmsnorm_rows, dim3(n), dim3(256), 0, m.stream, w.x, w.qkv, so, (size_t)n * h,
+                           m.norm_mlp[l], w.xn, w.xn_lo, h, c.rms_eps);
+        const int sg = gemm<false>(m, w.xn, w.xn_lo, h, m.wgu[l], n, 2 * I, h, nullptr, nullptr, 0);
+        hipLaunchKernelGGL(k_swiglu_rows, dim3((I / 4 + 255) / 256, n), dim3(256), 0, m.stream, w.qkv, sg,
+                           (size_t)n * 2 * I, I, w.act, w.act_lo);
+        pending = gemm<false>(m, w.act, w.act_lo, I, m.wdown[l], n, h, I, nullptr, nullptr, 0);
+    }
+    hipLaunchKernelGGL(k_rmsnorm_rows, dim3(n), dim3(256), 0, m.stream, w.x, w.qkv, pending, (size_t)n * h,
+                       m.final_norm, w.xn, w.xn_lo, h, c.rms_eps);
+    const int sl = gemm<false>(m, w.xn, w.xn_lo, h, m.lm_head, n, c.vocab, h, nullptr, nullptr, 0);
+    hipLaunchKernelGGL(k_argmax_rows, dim3(n), dim3(1024), 0, m.stream, w.qkv, sl, (size_t)n * c.vocab, c.vocab,
+                       b.logits, b.row_next);
 }
 
 }  // namespace st

@@ -38,6 +38,16 @@ struct Workspace {
     size_t bytes;
 };
 
+// Rows of the decode attention: row z attends with its new token at position pos[z] to the cache of sequence
+// seq[z] (seq == nullptr: sequence 0), caches seq_stride elements apart; q / out rows q_stride floats apart and
+// the per-row partial buffers ml_stride / acc_stride floats apart.
+struct AttnRows {
+    const int32_t *pos, *seq;
+    size_t seq_stride;
+    int q_stride;
+    size_t ml_stride, acc_stride;
+};
+
 constexpr int kLmBlocks = 1024;   // blocks (and arg-max partials) of the LM-head kernel
 constexpr int kAttnSplits = 128;  // most key ranges one kv head is split into at decode
 
@@ -86,6 +96,10 @@ void launch_decode_step(const Model &m, const st_trigger_rule *rule, int32_t *ou
 // Key ranges the decode attention needs for a context of t keys, rounded up to a bucket (the grid of
 // a captured step is fixed, so steps are captured per bucket).
 int attn_bucket(int t);
+// Decode attention of layer `layer` for n_rows rows of a batch (see AttnRows); m.kcache / m.vcache are the caches of
+// sequence 0.
+void launch_attn_rows(const Model &m, int layer, hipStream_t stream, int attn_blocks, const AttnRows &rows, int n_rows,
+                      const float *q, float *part_ml, float *part_acc, float *out);
 // Embedding of state[kTok] and all layers at position state[kPos], on the residual row x (fp32[hidden]).
 void launch_decode_layers(const Model &m, float *x, hipStream_t stream, int attn_blocks);
 // LM head + arg-max over the residual row x_row (fp32[hidden]); advances state[kPos] by `advance`.
@@ -95,6 +109,18 @@ void launch_head(const Model &m, const float *x_row, const st_trigger_rule *rule
 // ---- launchers (prefill.hip) ----
 // Feeds ws.tokens[0,n) at positions [pos0, pos0+n) through all layers; leaves the residual rows in ws.x.
 void launch_prefill_layers(const Model &m, int32_t pos0, int32_t n);
+
+// Device arrays of one batched decode step (n rows = n sequences, each at its own position).
+struct BatchRows {
+    const int32_t *row_tok, *row_pos, *row_seq;  // [n] token fed, its position, sequence index
+    int32_t *row_next;                           // [n] greedy next token
+    size_t seq_stride;                           // elements between the caches of consecutive sequences
+    float *q_rows, *o_rows;                      // [n][n_q*d]
+    float *part_ml, *part_acc;                   // [n][n_q][kAttnSplits][2 | d]
+    float *logits;                               // [n][vocab] or nullptr
+};
+// All layers, LM head and arg-max for n rows (n <= 64); m.kcache / m.vcache are the caches of sequence 0.
+void launch_batch_step(const Model &m, const BatchRows &b, int n, int attn_blocks);
 
 // ---- launchers (trigger.hip) ----
 void launch_trigger_scan(const st_trigger_rule &rule, const int32_t *tokens, int32_t lo, int32_t hi,

@@ -1,0 +1,117 @@
+"""GPU parity of the batched decode step (independent sequences of ragged length sharing one set of weights)
+against one CPU oracle model per sequence."""
+import numpy as np
+import pytest
+
+from oracle import oracle as O
+from paper_2504_12329_amd import binding as B, synth
+from tests.gpu_common import LOGIT_TOL, print_case, rel_err
+
+pytestmark = pytest.mark.gpu
+
+MIN_MARGIN = 0.008
+
+
+def _margin(lg):
+    s = np.sort(lg)
+    return float((s[-1] - s[-2]) / np.abs(lg).max())
+
+
+def _setup(name, n_seq, seed, max_seq, n_layers=None, gen_device="cpu"):
+    cfg = synth.model_config(name, max_seq=max_seq, max_chunk=64, n_layers=n_layers)
+    w = synth.make_weights(cfg, seed, device=gen_device)
+    oracles = [O.OracleModel(synth.oracle_config(cfg), synth.oracle_views(cfg, w)) for _ in range(n_seq)]
+    wg = dict(embed=w["embed"].cuda(), final_norm=w["final_norm"].cuda(),
+              lm_head=None if w["lm_head"] is None else w["lm_head"].cuda(),
+              layers=[{k: v.cuda() for k, v in lw.items()} for lw in w["layers"]])
+    return cfg, B.Batch(cfg, wg, n_seq), oracles
+
+
+def _run(cfg, batch, oracles, lengths, steps, drop_after=None):
+    """Prefills ragged prompts, then `steps` teacher-forced batched steps (both sides follow the oracle's tokens);
+    after `drop_after` steps only the even sequences keep going."""
+    n = len(oracles)
+    worst, checked = 0.0, 0
+    toks = []
+    for s in range(n):
+        prompt = synth.make_prompt(lengths[s], cfg["vocab"], 100 + s)
+        lg_o = oracles[s].feed(prompt)
+        lg_g, tok_g = batch.prefill(s, prompt)
+        worst = max(worst, rel_err(lg_g, lg_o))
+        assert tok_g == O.argmax(lg_g)
+        toks.append(O.argmax(lg_o))
+    active = list(range(n))
+    for step in range(steps):
+        if drop_after is not None and step == drop_after:
+            active = [s for s in active if s % 2 == 0]
+        order = active[::-1] if step % 2 else active            # row order must not matter
+        lg_g, nxt = batch.decode_step(order, [toks[s] for s in order], want_logits=True)
+        for r, s in enumerate(order):
+            lg_o = oracles[s].feed([toks[s]])
+            worst = max(worst, rel_err(lg_g[r], lg_o))
+            assert nxt[r] == O.argmax(lg_g[r])                  # the kernel's arg-max of its own logits
+            if _margin(lg_o) >= MIN_MARGIN:
+                assert nxt[r] == O.argmax(lg_o)
+                checked += 1
+            toks[s] = O.argmax(lg_o)
+    for s in range(n):
+        assert batch.kv_len(s) == oracles[s].kv_len
+    print_case("worst relative logit error", worst, "greedy tokens compared", checked)
+    return worst
+
+
+def test_tiny_batch_ragged_lengths():
+    print_case("tiny model, 7 sequences of 3..60 tokens, 12 batched steps, 4 sequences leave after 5")
+    cfg, batch, oracles = _setup("tiny_small", 7, 1, max_seq=128)
+    assert _run(cfg, batch, oracles, [3, 60, 17, 33, 1, 48, 64], 12, drop_after=5) <= LOGIT_TOL
+    # a truncated sequence continues from its shorter cache, alone in the batch
+    oracles[2].truncate(10)
+    batch.truncate(2, 10)
+    lg_o = oracles[2].feed([5])
+    lg_g, nxt = batch.decode_step([2], [5], want_logits=True)
+    assert rel_err(lg_g[0], lg_o) <= LOGIT_TOL and batch.kv_len(2) == 11
+    batch.close()
+
+
+def test_batch_crosses_attention_ranges():
+    """One layer at the 1.5B shape: sequences of 30, 700 and 1030 keys decode together (1, 11 and 17 key ranges)."""
+    print_case("1.5B shape, 1 layer: 3 sequences of 30 / 700 / 1030 tokens, 3 batched steps")
+    cfg, batch, oracles = _setup("qwen1p5b", 3, 8, max_seq=1100, n_layers=1, gen_device="cuda")
+    lengths = [30, 700, 1030]
+    toks = []
+    for s in range(3):
+        prompt = synth.make_prompt(lengths[s], cfg["vocab"], 200 + s)
+        lg_o = None
+        for lo in range(0, lengths[s], 64):
+            chunk = prompt[lo:lo + 64]
+            lg_o = oracles[s].feed(chunk)
+            lg_g, _ = batch.prefill(s, chunk)
+        assert rel_err(lg_g, lg_o) <= LOGIT_TOL
+        toks.append(O.argmax(lg_o))
+    worst = 0.0
+    for step in range(3):
+        lg_g, nxt = batch.decode_step([0, 1, 2], toks, want_logits=True)
+        for s in range(3):
+            lg_o = oracles[s].feed([toks[s]])
+            worst = max(worst, rel_err(lg_g[s], lg_o))
+            toks[s] = O.argmax(lg_o)
+    print_case("worst relative logit error", worst)
+    assert worst <= LOGIT_TOL
+    batch.close()
+
+
+def test_batch_argument_errors():
+    cfg, batch, oracles = _setup("tiny_small", 3, 1, max_seq=16)
+    with pytest.raises(B.StError):
+        batch.decode_step([0, 0], [1, 2])                       # a sequence twice in one step
+    with pytest.raises(B.StError):
+        batch.decode_step([3], [1])                             # no such sequence
+    with pytest.raises(B.StError):
+        batch.decode_step([0], [cfg["vocab"]])                  # token outside the vocabulary
+    batch.prefill(1, synth.make_prompt(16, cfg["vocab"], 1), want_logits=False)
+    with pytest.raises(B.StError) as e:
+        batch.decode_step([1], [1])                             # cache full
+    assert e.value.code == B.ST_ERANGE and batch.kv_len(1) == 16 and batch.kv_len(0) == 0
+    with pytest.raises(B.StError):
+        B.Batch(cfg, batch.weights, 65)                         # more sequences than the step supports
+    batch.close()
