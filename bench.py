@@ -49,6 +49,28 @@ def cpu_baseline(cfg, w_gpu, prompt):
                       f"(kv length {n_pre}..{n_pre + n_dec}), fp32 weights"}
 
 
+def batched_decode(torch, B, synth, cost, cfg, w, n_seq=16, steps=24):
+    """16 independent sequences with prompts of 128..1024 tokens (uniform, seed 4) decoding together on one model."""
+    import numpy as np
+    cfg = dict(cfg, max_seq=1200, max_chunk=max(64, min(cfg["max_chunk"], 1024)))
+    batch = B.Batch(cfg, w, n_seq)
+    lens = np.random.default_rng(4).integers(128, 1025, n_seq)
+    for s in range(n_seq):
+        batch.prefill(s, synth.make_prompt(int(lens[s]), cfg["vocab"], 50 + s), want_logits=False)
+    seqs, toks = np.arange(n_seq, dtype=np.int32), np.ones(n_seq, np.int32)
+    for _ in range(3):
+        _, toks = batch.decode_step(seqs, toks)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        _, toks = batch.decode_step(seqs, toks)
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / steps
+    batch.close()
+    return {"n_seq": n_seq, "prompt_lengths": [int(v) for v in lens], "ms_per_step": dt * 1e3, "tok_s": n_seq / dt,
+            "weight_GB_s": cost.weight_bytes(cfg) / dt / 1e9, "hbm_frac": cost.weight_bytes(cfg) / dt / HBM_PEAK}
+
+
 def target_model_extras(torch, B, synth, cost, small, sizes=(21, 86, 256, 1024, 4096), loop=True, n_layers=None):
     """32B-shaped target: decode rate at kv ~ 4k, catch-up prefill on a 4096-token cache, and the loop."""
     cfg = synth.model_config("qwen32b", max_seq=4096 + 4096 + 64, max_chunk=4096, n_layers=n_layers)
@@ -79,10 +101,16 @@ def target_model_extras(torch, B, synth, cost, small, sizes=(21, 86, 256, 1024, 
             "ms": sec * 1e3, "tok_s": m / sec, "TFLOP_s": fl / sec / 1e12, "mfma_frac": fl / sec / MFMA_PEAK,
             "weight_GB_s": cost.weight_bytes(cfg) / sec / 1e9, "hbm_frac": cost.weight_bytes(cfg) / sec / HBM_PEAK,
             "bound": "hbm" if m < 312 else "mfma"}
+    large.close()
+    del large
+    res["batched_decode"] = {"qwen32b": batched_decode(torch, B, synth, cost, cfg, w)}
+    if loop:
+        cfg7 = synth.model_config("qwen7b", max_seq=1200, max_chunk=64)
+        res["batched_decode"]["qwen7b"] = batched_decode(torch, B, synth, cost, cfg7,
+                                                         synth.make_weights(cfg7, 4, device="cuda"))
     # the whole two-model loop at the paper's density: hand-over every 85 speculative tokens, segments of 20
     # (both models must share one vocabulary: the target is re-wrapped over the first 151936 rows of its
     # embedding and LM head, the speculative model's vocabulary size)
-    large.close()
     if not loop:
         return res
     vocab = small.cfg["vocab"]

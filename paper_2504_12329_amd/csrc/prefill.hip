@@ -479,8 +479,8 @@ __global__ __launch_bounds__(256) void k_gemm_ring(const bf16_t *__restrict__ A,
 // ---------------------------------------------------------------------------------------
 // Short chunks (at most 128 rows, two-term activations): the weight stream sets the time, so the kernel is built
 // to keep bytes in flight.  A block owns 128 weight rows and a K slice; weights and both activation terms go
-// global -> LDS directly in 128-byte row segments into a ring of NS stages of (16 + MT*8) KB (all of LDS: up to
-// 80 KB of weights in flight per CU, no staging registers), one barrier per 64-wide K step.  Wave w multiplies its
+// global -> LDS directly in 128-byte row segments into a ring of NS stages of (16 + MT*8) KB (64 KB of weights in
+// flight per CU, no staging registers), one barrier per 64-wide K step.  Wave w multiplies its
 // 32 weight rows with every 32-row activation tile (C^T = W A^T, so a lane owns an activation row) and the raw fp32
 // partial sums of the K slice go to part[z][M][N] like those of the other GEMMs.  Needs K % 64 == 0.
 // ---------------------------------------------------------------------------------------
@@ -489,7 +489,9 @@ struct SkinnyShape {
     static constexpr int kWBytes = 128 * kRingBK * 2;             // 16 KB of weights per stage
     static constexpr int kABytes = MT * 64 * kRingBK * 2;         // hi and lo rows of MT 32-row tiles
     static constexpr int kStage = kWBytes + kABytes;
-    static constexpr int kStages = (160 * 1024) / kStage;         // 6, 5, 4, 3 for MT = 1..4
+    // MT = 1: three stages, so that two blocks share a CU (measured a little faster than one block with six);
+    // otherwise all of LDS: 5, 4, 3 stages for MT = 2, 3, 4
+    static constexpr int kStages = MT == 1 ? 3 : (160 * 1024) / kStage;
     static constexpr int kLoads = 4 + 2 * MT;                     // direct loads per wave per stage
 };
 
