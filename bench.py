@@ -71,6 +71,26 @@ def batched_decode(torch, B, synth, cost, cfg, w, n_seq=16, steps=24):
             "weight_GB_s": cost.weight_bytes(cfg) / dt / 1e9, "hbm_frac": cost.weight_bytes(cfg) / dt / HBM_PEAK}
 
 
+def batched_loop(B, synth, cfg_s, w_s, cfg_l, w_l, n_seq=16, n_out=210, n_seg=20, period=85):
+    """The two-model loop for 16 sequences at once (7B-shaped speculative, 32B-shaped target), prompts of 128..1024
+    tokens (uniform, seed 4), hand-over every 85th speculative token, segments of 20."""
+    import numpy as np
+    small, large = B.Batch(cfg_s, w_s, n_seq), B.Batch(cfg_l, w_l, n_seq)
+    lens = np.random.default_rng(4).integers(128, 1025, n_seq)
+    prompts = [synth.make_prompt(int(lens[i]), cfg_s["vocab"], 50 + i) for i in range(n_seq)]
+    t0 = time.perf_counter()
+    g = B.st_generate_batch(small, large, prompts, n_out, n_seg, cfg_s["vocab"], forced_period=period)
+    dt = time.perf_counter() - t0
+    st = g["stats"]
+    small.close()
+    large.close()
+    return {"tok_s": st["n_out"] / dt, "n_seq": n_seq, "n_out": st["n_out"], "n_handoffs": st["n_handoffs"],
+            "modify_ratio": st["n_large"] / max(1, st["n_out"]), "seconds": dt,
+            "ms_small_decode": st["ms_small_decode"], "ms_large_decode": st["ms_large_decode"],
+            "ms_small_prefill": st["ms_small_prefill"], "ms_large_prefill": st["ms_large_prefill"],
+            "schedule": "forced: every 85th speculative token hands over, target writes 20; prompt prefill included"}
+
+
 def target_model_extras(torch, B, synth, cost, small, sizes=(21, 86, 256, 1024, 4096), loop=True, n_layers=None):
     """32B-shaped target: decode rate at kv ~ 4k, catch-up prefill on a 4096-token cache, and the loop."""
     cfg = synth.model_config("qwen32b", max_seq=4096 + 4096 + 64, max_chunk=4096, n_layers=n_layers)
@@ -105,9 +125,11 @@ def target_model_extras(torch, B, synth, cost, small, sizes=(21, 86, 256, 1024, 
     del large
     res["batched_decode"] = {"qwen32b": batched_decode(torch, B, synth, cost, cfg, w)}
     if loop:
-        cfg7 = synth.model_config("qwen7b", max_seq=1200, max_chunk=64)
-        res["batched_decode"]["qwen7b"] = batched_decode(torch, B, synth, cost, cfg7,
-                                                         synth.make_weights(cfg7, 4, device="cuda"))
+        cfg7 = synth.model_config("qwen7b", max_seq=1400, max_chunk=1024)
+        w7 = synth.make_weights(cfg7, 4, device="cuda")
+        res["batched_decode"]["qwen7b"] = batched_decode(torch, B, synth, cost, cfg7, w7)
+        res["loop_batched_7b_32b"] = batched_loop(B, synth, cfg7, w7, dict(cfg, max_seq=1400, max_chunk=1024), w)
+        del w7
     # the whole two-model loop at the paper's density: hand-over every 85 speculative tokens, segments of 20
     # (both models must share one vocabulary: the target is re-wrapped over the first 151936 rows of its
     # embedding and LM head, the speculative model's vocabulary size)

@@ -242,6 +242,26 @@ int st_batch_prefill(st_batch *b, int32_t seq, const int32_t *tokens, int32_t n,
 int st_batch_decode_step(st_batch *b, int32_t n_rows, const int32_t *seqs, const int32_t *tokens, float *logits,
                          int32_t *next_tokens);
 
+/* The takeover rule with HOST bitmaps (the batched loop reads every token back and evaluates it on the host);
+ * window 1 or 2 as in st_trigger_rule. */
+typedef struct {
+    const uint32_t *kw_bitmap, *delim_bitmap;
+    int32_t window, vocab;
+} st_host_rule;
+
+/* The loop of st_generate for n_seq independent sequences at once (Section 3 (1), append semantics; the batched
+ * regime of the paper's outlook): sequence i lives in slot i of both batches (empty caches), starts from
+ * prompts[i][0 .. prompt_lens[i]) and ends after n_out output tokens.  Every round runs one decode step of the
+ * speculative batch over the sequences that model is writing and one of the target batch over those inside a
+ * segment; a sequence that triggers catches the target up with its own prefill pass and joins the target's steps
+ * for n_seg tokens, then catches the speculative model up and rejoins it.  Per sequence the result is that of
+ * st_generate.  forced_period > 0 replaces the rule by "every forced_period-th speculative token fires".
+ * seqs[i] (host, capacity prompt_lens[i] + n_out) receives prompt + outputs, srcs[i] (host, n_out bytes; srcs or any
+ * entry may be NULL) 0 / 1 per output token.  stats sums over the sequences. */
+int st_generate_batch(st_batch *small, st_batch *large, const st_host_rule *rule, int32_t forced_period,
+                      int32_t n_seq, const int32_t *const *prompts, const int32_t *prompt_lens, int32_t n_out,
+                      int32_t n_seg, int32_t *const *seqs, uint8_t *const *srcs, st_gen_stats *stats);
+
 /* Measurement support: one chained greedy decode step (feeds the model's own last token) in which
  * every launch of the gate/up projection kernel -- the kernel that moves the most bytes of a step
  * (2 * intermediate * hidden bf16 weights per launch) -- carries HIP start/stop events on the

@@ -19,7 +19,7 @@ ST_TOKENS_DEVICE, ST_OUT_DEVICE, ST_TOKEN_CHAINED = 1, 2, 4
 EXPORTS = ("st_query_sizes", "st_model_create", "st_model_destroy", "st_kv_len", "st_kv_truncate", "st_prefill",
            "st_decode_step", "st_decode_step_timed", "st_decode_greedy", "st_trigger_scan", "st_handoff", "st_generate",
            "st_generate_policy", "st_batch_query_sizes", "st_batch_create", "st_batch_destroy", "st_batch_kv_len",
-           "st_batch_truncate", "st_batch_prefill", "st_batch_decode_step", "st_last_error")
+           "st_batch_truncate", "st_batch_prefill", "st_batch_decode_step", "st_generate_batch", "st_last_error")
 
 
 class StError(RuntimeError):
@@ -102,6 +102,8 @@ def lib():
         L.st_batch_truncate.argtypes = [C.c_void_p, C.c_int32, C.c_int32]
         L.st_batch_prefill.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
         L.st_batch_decode_step.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.st_generate_batch.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
+                                        C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.POINTER(st_gen_stats)]
         _lib = L
     return _lib
 
@@ -369,3 +371,25 @@ class Batch:
         _check(lib().st_batch_decode_step(self._h, s.size, _np_ptr(s), _np_ptr(t),
                                           _np_ptr(lg) if want_logits else None, _np_ptr(nxt)))
         return lg, nxt
+
+
+class st_host_rule(C.Structure):
+    _fields_ = [("kw_bitmap", C.c_void_p), ("delim_bitmap", C.c_void_p), ("window", C.c_int32), ("vocab", C.c_int32)]
+
+
+def st_generate_batch(small, large, prompts, n_out, n_seg, vocab, kw=None, delim=None, window=1, forced_period=0):
+    """The st_generate loop for len(prompts) sequences at once on two Batch objects; kw / delim are host bitmaps.
+    Returns dict(seqs, srcs, stats)."""
+    n = len(prompts)
+    ps = [np.ascontiguousarray(p, dtype=np.int32) for p in prompts]
+    lens = np.array([p.size for p in ps], dtype=np.int32)
+    seqs = [np.zeros(p.size + n_out, dtype=np.int32) for p in ps]
+    srcs = [np.zeros(max(n_out, 1), dtype=np.uint8) for _ in ps]
+    arr = lambda xs: (C.c_void_p * n)(*[x.ctypes.data for x in xs])
+    kwa = None if kw is None else np.ascontiguousarray(kw, dtype=np.uint32)
+    dla = None if delim is None else np.ascontiguousarray(delim, dtype=np.uint32)
+    rule = st_host_rule(None if kwa is None else kwa.ctypes.data, None if dla is None else dla.ctypes.data, window, vocab)
+    stats = st_gen_stats()
+    _check(lib().st_generate_batch(small._h, large._h, C.byref(rule) if kwa is not None else None, forced_period, n,
+                                   arr(ps), _np_ptr(lens), n_out, n_seg, arr(seqs), arr(srcs), C.byref(stats)))
+    return dict(seqs=seqs, srcs=srcs, stats={k: getattr(stats, k) for k, _ in st_gen_stats._fields_})

@@ -860,4 +860,120 @@ int st_batch_decode_step(st_batch *h, int32_t n_rows, const int32_t *seqs, const
     return ST_OK;
 }
 
+int st_generate_batch(st_batch *hs, st_batch *hl, const st_host_rule *rule, int32_t forced_period, int32_t n_seq,
+                      const int32_t *const *prompts, const int32_t *prompt_lens, int32_t n_out, int32_t n_seg,
+                      int32_t *const *seqs, uint8_t *const *srcs, st_gen_stats *stats) {
+    using clk = std::chrono::steady_clock;
+    auto ms_since = [](clk::time_point a) { return std::chrono::duration<double, std::milli>(clk::now() - a).count(); };
+    Batch *S = reinterpret_cast<Batch *>(hs), *L = reinterpret_cast<Batch *>(hl);
+    if (!S || !L || !prompts || !prompt_lens || !seqs) return fail(ST_EINVAL, "a batch, prompts, prompt_lens or seqs is NULL");
+    if (S == L) return fail(ST_EINVAL, "small and large must be different batches");
+    if (forced_period < 0) return fail(ST_EINVAL, "forced_period must be >= 0");
+    if (forced_period == 0) {
+        if (!rule || !rule->kw_bitmap || rule->vocab <= 0) return fail(ST_EINVAL, "a trigger rule (or forced_period > 0) is required");
+        if (rule->window != 1 && rule->window != 2) return fail(ST_EINVAL, "window must be 1 or 2");
+        if (rule->window == 2 && !rule->delim_bitmap) return fail(ST_EINVAL, "window 2 needs a delimiter bitmap");
+    }
+    if (n_seq < 1 || n_seq > S->n_seq || n_seq > L->n_seq) return fail(ST_ERANGE, "n_seq %d exceeds a batch", n_seq);
+    if (n_out < 0 || n_seg <= 0) return fail(ST_ERANGE, "n_seg must be positive and n_out non-negative");
+    for (int32_t i = 0; i < n_seq; ++i) {
+        if (!prompts[i] || !seqs[i] || prompt_lens[i] <= 0) return fail(ST_EINVAL, "bad prompt or output buffer of sequence %d", i);
+        if (S->kv_len[i] != 0 || L->kv_len[i] != 0) return fail(ST_EINVAL, "sequence %d does not start with empty caches", i);
+        if ((int64_t)prompt_lens[i] + n_out > S->base.c.max_seq || (int64_t)prompt_lens[i] + n_out > L->base.c.max_seq)
+            return fail(ST_ERANGE, "sequence %d: prompt + n_out exceeds a model's max_seq", i);
+    }
+    auto in_class = [&](const uint32_t *bm, int32_t t) {
+        return bm && t >= 0 && t < rule->vocab && ((bm[t >> 5] >> (t & 31)) & 1u);
+    };
+    enum { WRITES_SMALL, WRITES_LARGE, DONE };
+    std::vector<int> who(n_seq, WRITES_SMALL);
+    std::vector<int32_t> T(n_seq), pend(n_seq), rem(n_seq, 0), small_count(n_seq, 0);
+    st_gen_stats st = {};
+    for (int32_t i = 0; i < n_seq; ++i) {
+        memcpy(seqs[i], prompts[i], sizeof(int32_t) * prompt_lens[i]);
+        T[i] = prompt_lens[i];
+        if (n_out == 0) {
+            who[i] = DONE;
+            continue;
+        }
+        auto a = clk::now();
+        if (int rc = st_batch_prefill(hs, i, seqs[i], T[i], nullptr, &pend[i])) return rc;
+        st.ms_small_prefill += ms_since(a);
+        a = clk::now();
+        if (int rc = st_batch_prefill(hl, i, seqs[i], T[i], nullptr, nullptr)) return rc;
+        st.ms_large_prefill += ms_since(a);
+    }
+    std::vector<int32_t> rows, toks, next;
+    auto step = [&](st_batch *b, double *ms) -> int {
+        if (rows.empty()) return ST_OK;
+        next.resize(rows.size());
+        auto a = clk::now();
+        if (int rc = st_batch_decode_step(b, (int32_t)rows.size(), rows.data(), toks.data(), nullptr, next.data())) return rc;
+        *ms += ms_since(a);
+        for (size_t r = 0; r < rows.size(); ++r) pend[rows[r]] = next[r];
+        return ST_OK;
+    };
+    while (true) {
+        bool any = false;
+        // sequences the speculative model is writing: emit, test the trigger, hand over or queue the next step
+        rows.clear(), toks.clear();
+        for (int32_t i = 0; i < n_seq; ++i) {
+            if (who[i] != WRITES_SMALL) continue;
+            any = true;
+            const int32_t P = prompt_lens[i], tok = pend[i];
+            seqs[i][T[i]++] = tok;
+            if (srcs && srcs[i]) srcs[i][T[i] - 1 - P] = 0;
+            ++small_count[i];
+            if (T[i] - P == n_out) {
+                who[i] = DONE;
+                continue;
+            }
+            bool fire;
+            if (forced_period > 0)
+                fire = small_count[i] % forced_period == 0;
+            else
+                fire = in_class(rule->kw_bitmap, tok) &&
+                       (rule->window == 1 || (T[i] >= 2 && in_class(rule->delim_bitmap, seqs[i][T[i] - 2])));
+            if (fire) {
+                auto a = clk::now();
+                const int32_t lo = L->kv_len[i];
+                if (int rc = st_batch_prefill(hl, i, seqs[i] + lo, T[i] - lo, nullptr, &pend[i])) return rc;
+                st.ms_large_prefill += ms_since(a);
+                who[i] = WRITES_LARGE;
+                rem[i] = n_seg;
+                ++st.n_handoffs;
+            } else {
+                rows.push_back(i), toks.push_back(tok);
+            }
+        }
+        if (int rc = step(hs, &st.ms_small_decode)) return rc;
+        // sequences inside a target segment: emit; the segment's last token is not fed to the target
+        rows.clear(), toks.clear();
+        for (int32_t i = 0; i < n_seq; ++i) {
+            if (who[i] != WRITES_LARGE) continue;
+            any = true;
+            const int32_t P = prompt_lens[i], tok = pend[i];
+            seqs[i][T[i]++] = tok;
+            if (srcs && srcs[i]) srcs[i][T[i] - 1 - P] = 1;
+            ++st.n_large;
+            if (T[i] - P == n_out) {
+                who[i] = DONE;
+            } else if (--rem[i] == 0) {
+                auto a = clk::now();
+                const int32_t lo = S->kv_len[i];
+                if (int rc = st_batch_prefill(hs, i, seqs[i] + lo, T[i] - lo, nullptr, &pend[i])) return rc;
+                st.ms_small_prefill += ms_since(a);
+                who[i] = WRITES_SMALL;
+            } else {
+                rows.push_back(i), toks.push_back(tok);
+            }
+        }
+        if (int rc = step(hl, &st.ms_large_decode)) return rc;
+        if (!any) break;
+    }
+    for (int32_t i = 0; i < n_seq; ++i) st.n_out += T[i] - prompt_lens[i];
+    if (stats) *stats = st;
+    return ST_OK;
+}
+
 }  // extern "C"

@@ -115,3 +115,40 @@ def test_batch_argument_errors():
     with pytest.raises(B.StError):
         B.Batch(cfg, batch.weights, 65)                         # more sequences than the step supports
     batch.close()
+
+
+# (prompt seed, prompt length): searched on the CPU so that the oracle's own run of each sequence (mod-16 rule, 48
+# outputs, segments of 8) keeps every top-1/top-2 logit gap above MIN_MARGIN; re-checked below
+LOOP_PROMPTS = [(460, 28), (537, 47), (591, 25), (681, 15), (962, 22), (966, 10)]
+
+
+def test_batched_loop_matches_per_sequence_oracle():
+    """Six sequences of different prompt length run the two-model loop together; each must reproduce the schedule
+    oracle's single-sequence trace (tokens and who wrote them)."""
+    from oracle import schedule as S
+    n = len(LOOP_PROMPTS)
+    cfg, bs, o_small = _setup("tiny_small", n, 1, max_seq=128)
+    _, bl, o_large = _setup("tiny_large", n, 2, max_seq=128)
+    V = cfg["vocab"]
+    fire = S.window_rule(lambda t: t % 16 == 0)
+    prompts, traces = [], []
+    for i, (seed, plen) in enumerate(LOOP_PROMPTS):
+        prompt = synth.make_prompt(plen, V, seed)
+        a, b = S.GreedyModel(o_small[i], keep_logits=True), S.GreedyModel(o_large[i], keep_logits=True)
+        tr = S.speculative_thinking(a, b, prompt, 48, 8, fire)
+        margin = min(_margin(lg) for g in (a, b) for _, lg in g.logits)
+        assert margin >= MIN_MARGIN, f"sequence {i}: oracle run has a near-tie ({margin:.4f}); pick another seed"
+        prompts.append(prompt)
+        traces.append(tr)
+    out = B.st_generate_batch(bs, bl, prompts, 48, 8, V, kw=B.host_bitmap(V, range(0, V, 16)))
+    total_large = 0
+    for i, tr in enumerate(traces):
+        assert out["seqs"][i].tolist() == tr.seq, i
+        assert out["srcs"][i][:48].tolist() == tr.src, i
+        assert bs.kv_len(i) == o_small[i].kv_len and bl.kv_len(i) == o_large[i].kv_len
+        total_large += sum(tr.src)
+    print_case("hand-overs per sequence", [len(tr.triggers) for tr in traces])
+    assert out["stats"]["n_out"] == 48 * n and out["stats"]["n_large"] == total_large
+    assert out["stats"]["n_handoffs"] == sum(len(tr.triggers) for tr in traces)
+    bs.close()
+    bl.close()
