@@ -125,10 +125,10 @@ def target_model_extras(torch, B, synth, cost, small, sizes=(21, 86, 256, 1024, 
     del large
     res["batched_decode"] = {"qwen32b": batched_decode(torch, B, synth, cost, cfg, w)}
     if loop:
-        cfg7 = synth.model_config("qwen7b", max_seq=1400, max_chunk=1024)
+        cfg7 = synth.model_config("qwen7b", max_seq=1400, max_chunk=4096)
         w7 = synth.make_weights(cfg7, 4, device="cuda")
         res["batched_decode"]["qwen7b"] = batched_decode(torch, B, synth, cost, cfg7, w7)
-        res["loop_batched_7b_32b"] = batched_loop(B, synth, cfg7, w7, dict(cfg, max_seq=1400, max_chunk=1024), w)
+        res["loop_batched_7b_32b"] = batched_loop(B, synth, cfg7, w7, dict(cfg, max_seq=1400, max_chunk=4096), w)
         del w7
     # the whole two-model loop at the paper's density: hand-over every 85 speculative tokens, segments of 20
     # (both models must share one vocabulary: the target is re-wrapped over the first 151936 rows of its

@@ -236,6 +236,12 @@ int st_batch_truncate(st_batch *b, int32_t seq, int32_t new_len);
 /* Feeds n tokens to sequence `seq` (catch-up pass of that sequence alone); logits (fp32[vocab]) and next_tok of the
  * last position if not NULL. */
 int st_batch_prefill(st_batch *b, int32_t seq, const int32_t *tokens, int32_t n, float *logits, int32_t *next_tok);
+/* Ragged catch-up pass: feeds tokens[j][0 .. lens[j]) to the distinct sequences seqs[j], j < n, in one pass (the
+ * weights are streamed once for all of them); the lengths may differ and must not add up to more than
+ * cfg->max_chunk.  logits (fp32[n][vocab], may be NULL) and next_tokens[j] (may be NULL) are those of each
+ * sequence's last position. */
+int st_batch_prefill_many(st_batch *b, int32_t n, const int32_t *seqs, const int32_t *const *tokens,
+                          const int32_t *lens, float *logits, int32_t *next_tokens);
 /* One decode step for the n_rows distinct sequences seqs[r], feeding tokens[r] at each sequence's own position
  * (ragged lengths): logits (fp32[n_rows][vocab], may be NULL) and greedy next_tokens[r] (may be NULL); every listed
  * sequence grows by one. */

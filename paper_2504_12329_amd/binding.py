@@ -19,7 +19,8 @@ ST_TOKENS_DEVICE, ST_OUT_DEVICE, ST_TOKEN_CHAINED = 1, 2, 4
 EXPORTS = ("st_query_sizes", "st_model_create", "st_model_destroy", "st_kv_len", "st_kv_truncate", "st_prefill",
            "st_decode_step", "st_decode_step_timed", "st_decode_greedy", "st_trigger_scan", "st_handoff", "st_generate",
            "st_generate_policy", "st_batch_query_sizes", "st_batch_create", "st_batch_destroy", "st_batch_kv_len",
-           "st_batch_truncate", "st_batch_prefill", "st_batch_decode_step", "st_generate_batch", "st_last_error")
+           "st_batch_truncate", "st_batch_prefill", "st_batch_prefill_many", "st_batch_decode_step", "st_generate_batch",
+           "st_last_error")
 
 
 class StError(RuntimeError):
@@ -102,6 +103,8 @@ def lib():
         L.st_batch_truncate.argtypes = [C.c_void_p, C.c_int32, C.c_int32]
         L.st_batch_prefill.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
         L.st_batch_decode_step.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.st_batch_prefill_many.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                            C.c_void_p]
         L.st_generate_batch.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
                                         C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.POINTER(st_gen_stats)]
         _lib = L
@@ -361,6 +364,18 @@ class Batch:
         _check(lib().st_batch_prefill(self._h, seq, _np_ptr(t), t.size, _np_ptr(lg) if want_logits else None,
                                       C.byref(tok)))
         return lg, tok.value
+
+    def prefill_many(self, seqs, token_lists, want_logits=False):
+        """One ragged catch-up pass: token_lists[j] goes to sequence seqs[j].  Returns (logits [n][V] or None, next)."""
+        s = np.ascontiguousarray(seqs, dtype=np.int32)
+        ts = [np.ascontiguousarray(t, dtype=np.int32) for t in token_lists]
+        lens = np.array([t.size for t in ts], dtype=np.int32)
+        ptrs = (C.c_void_p * len(ts))(*[t.ctypes.data for t in ts])
+        lg = np.empty((s.size, self.cfg["vocab"]), dtype=np.float32) if want_logits else None
+        nxt = np.empty(s.size, dtype=np.int32)
+        _check(lib().st_batch_prefill_many(self._h, s.size, _np_ptr(s), ptrs, _np_ptr(lens),
+                                           _np_ptr(lg) if want_logits else None, _np_ptr(nxt)))
+        return lg, nxt
 
     def decode_step(self, seqs, tokens, want_logits=False):
         s = np.ascontiguousarray(seqs, dtype=np.int32)

@@ -721,7 +721,8 @@ struct Batch {
     int32_t n_seq;
     std::vector<int32_t> kv_len;
     size_t seq_stride;             // elements between consecutive sequences' caches
-    int32_t *row_ints;             // device: tok | pos | seq | next, n_seq each
+    int32_t *row_ints;             // device: tok | pos | seq (row_cap each), next (n_seq)
+    size_t row_cap;                // max(max_chunk, n_seq)
     float *q_rows, *o_rows, *part_ml, *part_acc, *logits;
 };
 constexpr int kMaxBatch = 64;
@@ -733,8 +734,10 @@ size_t batch_extra(const st_config &c, int32_t n, char *base, Batch *b) {
         off += (bytes + 255) & ~(size_t)255;
         return p;
     };
-    const size_t qd = (size_t)c.n_q_heads * c.head_dim;
-    int32_t *ri = (int32_t *)take(sizeof(int32_t) * 4 * n);
+    size_t qd = (size_t)c.n_q_heads * c.head_dim;
+    if ((size_t)c.hidden > qd) qd = c.hidden;  // o_rows also holds gathered residual rows
+    const size_t rows = c.max_chunk > n ? c.max_chunk : n;  // a ragged catch-up pass has up to max_chunk rows
+    int32_t *ri = (int32_t *)take(sizeof(int32_t) * (3 * rows + n));
     float *q = (float *)take(sizeof(float) * n * qd), *o = (float *)take(sizeof(float) * n * qd);
     float *ml = (float *)take(sizeof(float) * (size_t)n * c.n_q_heads * kAttnSplits * 2);
     float *acc = (float *)take(sizeof(float) * (size_t)n * c.n_q_heads * kAttnSplits * c.head_dim);
@@ -783,6 +786,7 @@ int st_batch_create(const st_config *cfg, const st_weights *w, int32_t n_seq, vo
     b->kv_len.assign(n_seq, 0);
     b->seq_stride = kv_bytes_of(*cfg) / sizeof(bf16_t);
     batch_extra(*cfg, n_seq, (char *)workspace + sized.bytes, b);
+    b->row_cap = cfg->max_chunk > n_seq ? cfg->max_chunk : n_seq;
     *out = reinterpret_cast<st_batch *>(b);
     return ST_OK;
 }
@@ -845,7 +849,7 @@ int st_batch_decode_step(st_batch *h, int32_t n_rows, const int32_t *seqs, const
     int32_t *dev = b->row_ints;
     ST_HIP(hipMemcpyAsync(dev, host.data(), sizeof(int32_t) * host.size(), hipMemcpyHostToDevice, b->base.stream));
     ST_HIP(hipStreamSynchronize(b->base.stream));  // `host` leaves scope before the copy would otherwise be read
-    BatchRows rows = {dev, dev + n_rows, dev + 2 * (size_t)n_rows, dev + 3 * (size_t)b->n_seq, b->seq_stride,
+    BatchRows rows = {dev, dev + n_rows, dev + 2 * (size_t)n_rows, dev + 3 * b->row_cap, b->seq_stride,
                       b->q_rows, b->o_rows, b->part_ml, b->part_acc, logits ? b->logits : nullptr};
     launch_batch_step(b->base, rows, n_rows, attn_bucket(max_pos + 1));
     if (int rc = check_launch("batched decode step")) return rc;
@@ -857,6 +861,56 @@ int st_batch_decode_step(st_batch *h, int32_t n_rows, const int32_t *seqs, const
                               b->base.stream));
     ST_HIP(hipStreamSynchronize(b->base.stream));
     for (int32_t r = 0; r < n_rows; ++r) b->kv_len[seqs[r]] += 1;
+    return ST_OK;
+}
+
+int st_batch_prefill_many(st_batch *h, int32_t n, const int32_t *seqs, const int32_t *const *tokens,
+                          const int32_t *lens, float *logits, int32_t *next_tokens) {
+    Batch *b = reinterpret_cast<Batch *>(h);
+    if (!b || !seqs || !tokens || !lens) return fail(ST_EINVAL, "batch, seqs, tokens or lens is NULL");
+    if (n < 1 || n > b->n_seq) return fail(ST_ERANGE, "n must be in [1, %d]", b->n_seq);
+    const st_config &c = b->base.c;
+    int64_t R = 0;
+    uint64_t seen = 0;
+    for (int32_t j = 0; j < n; ++j) {
+        const int32_t s = seqs[j];
+        if (s < 0 || s >= b->n_seq) return fail(ST_ERANGE, "sequence %d outside [0, %d)", s, b->n_seq);
+        if (seen >> s & 1) return fail(ST_EINVAL, "sequence %d appears twice", s);
+        seen |= (uint64_t)1 << s;
+        if (!tokens[j] || lens[j] <= 0) return fail(ST_EINVAL, "bad tokens or length of entry %d", j);
+        if ((int64_t)b->kv_len[s] + lens[j] > c.max_seq) return fail(ST_ERANGE, "KV overflow in sequence %d", s);
+        for (int32_t i = 0; i < lens[j]; ++i)
+            if (tokens[j][i] < 0 || tokens[j][i] >= c.vocab)
+                return fail(ST_ERANGE, "token id %d of entry %d is outside the vocabulary [0,%d)", tokens[j][i], j, c.vocab);
+        R += lens[j];
+    }
+    if (R > c.max_chunk) return fail(ST_ERANGE, "%lld rows in all exceed max_chunk %d", (long long)R, c.max_chunk);
+    std::vector<int32_t> host(3 * (size_t)R + n);
+    std::vector<VarlenSeg> segs(n);
+    int32_t row = 0;
+    for (int32_t j = 0; j < n; ++j) {
+        const int32_t s = seqs[j];
+        segs[j] = VarlenSeg{s, row, lens[j], b->kv_len[s]};
+        for (int32_t i = 0; i < lens[j]; ++i, ++row) {
+            host[row] = tokens[j][i];
+            host[R + row] = b->kv_len[s] + i;
+            host[2 * (size_t)R + row] = s;
+        }
+        host[3 * (size_t)R + j] = row - 1;  // the segment's last row
+    }
+    int32_t *dev = b->row_ints, *next = dev + 3 * b->row_cap;
+    hipStream_t st = b->base.stream;
+    ST_HIP(hipMemcpyAsync(dev, host.data(), sizeof(int32_t) * 3 * (size_t)R, hipMemcpyHostToDevice, st));
+    ST_HIP(hipMemcpyAsync(next, host.data() + 3 * (size_t)R, sizeof(int32_t) * n, hipMemcpyHostToDevice, st));
+    ST_HIP(hipStreamSynchronize(st));
+    BatchRows rows = {dev, dev + R, dev + 2 * (size_t)R, next, b->seq_stride, b->q_rows, b->o_rows, b->part_ml,
+                      b->part_acc, logits ? b->logits : nullptr};
+    launch_prefill_varlen(b->base, rows, segs.data(), n, (int)R);
+    if (int rc = check_launch("ragged catch-up pass")) return rc;
+    if (logits) ST_HIP(hipMemcpyAsync(logits, b->logits, sizeof(float) * (size_t)n * c.vocab, hipMemcpyDeviceToHost, st));
+    if (next_tokens) ST_HIP(hipMemcpyAsync(next_tokens, next, sizeof(int32_t) * n, hipMemcpyDeviceToHost, st));
+    ST_HIP(hipStreamSynchronize(st));
+    for (int32_t j = 0; j < n; ++j) b->kv_len[seqs[j]] += lens[j];
     return ST_OK;
 }
 
@@ -889,20 +943,51 @@ int st_generate_batch(st_batch *hs, st_batch *hl, const st_host_rule *rule, int3
     std::vector<int> who(n_seq, WRITES_SMALL);
     std::vector<int32_t> T(n_seq), pend(n_seq), rem(n_seq, 0), small_count(n_seq, 0);
     st_gen_stats st = {};
+    // catches the listed sequences of one batch up on every token they have not seen, as few ragged passes as
+    // max_chunk allows (a span longer than max_chunk goes through the chunked single-sequence pass); pend[] gets
+    // each sequence's next token
+    auto catch_up = [&](st_batch *hb, Batch *B_, const std::vector<int32_t> &list, double *ms) -> int {
+        auto a = clk::now();
+        const int32_t cap = B_->base.c.max_chunk;
+        std::vector<int32_t> ids, lens, next;
+        std::vector<const int32_t *> ptrs;
+        int64_t rows = 0;
+        auto flush = [&]() -> int {
+            if (ids.empty()) return ST_OK;
+            next.resize(ids.size());
+            if (int rc = st_batch_prefill_many(hb, (int32_t)ids.size(), ids.data(), ptrs.data(), lens.data(), nullptr, next.data()))
+                return rc;
+            for (size_t j = 0; j < ids.size(); ++j) pend[ids[j]] = next[j];
+            ids.clear(), lens.clear(), ptrs.clear();
+            rows = 0;
+            return ST_OK;
+        };
+        for (int32_t i : list) {
+            const int32_t lo = B_->kv_len[i], len = T[i] - lo;
+            if (len > cap) {
+                if (int rc = st_batch_prefill(hb, i, seqs[i] + lo, len, nullptr, &pend[i])) return rc;
+                continue;
+            }
+            if (rows + len > cap)
+                if (int rc = flush()) return rc;
+            ids.push_back(i), lens.push_back(len), ptrs.push_back(seqs[i] + lo);
+            rows += len;
+        }
+        if (int rc = flush()) return rc;
+        *ms += ms_since(a);
+        return ST_OK;
+    };
+    std::vector<int32_t> list;
     for (int32_t i = 0; i < n_seq; ++i) {
         memcpy(seqs[i], prompts[i], sizeof(int32_t) * prompt_lens[i]);
         T[i] = prompt_lens[i];
-        if (n_out == 0) {
+        if (n_out == 0)
             who[i] = DONE;
-            continue;
-        }
-        auto a = clk::now();
-        if (int rc = st_batch_prefill(hs, i, seqs[i], T[i], nullptr, &pend[i])) return rc;
-        st.ms_small_prefill += ms_since(a);
-        a = clk::now();
-        if (int rc = st_batch_prefill(hl, i, seqs[i], T[i], nullptr, nullptr)) return rc;
-        st.ms_large_prefill += ms_since(a);
+        else
+            list.push_back(i);
     }
+    if (int rc = catch_up(hl, L, list, &st.ms_large_prefill)) return rc;   // its predictions are not used
+    if (int rc = catch_up(hs, S, list, &st.ms_small_prefill)) return rc;
     std::vector<int32_t> rows, toks, next;
     auto step = [&](st_batch *b, double *ms) -> int {
         if (rows.empty()) return ST_OK;
@@ -916,7 +1001,7 @@ int st_generate_batch(st_batch *hs, st_batch *hl, const st_host_rule *rule, int3
     while (true) {
         bool any = false;
         // sequences the speculative model is writing: emit, test the trigger, hand over or queue the next step
-        rows.clear(), toks.clear();
+        rows.clear(), toks.clear(), list.clear();
         for (int32_t i = 0; i < n_seq; ++i) {
             if (who[i] != WRITES_SMALL) continue;
             any = true;
@@ -935,10 +1020,7 @@ int st_generate_batch(st_batch *hs, st_batch *hl, const st_host_rule *rule, int3
                 fire = in_class(rule->kw_bitmap, tok) &&
                        (rule->window == 1 || (T[i] >= 2 && in_class(rule->delim_bitmap, seqs[i][T[i] - 2])));
             if (fire) {
-                auto a = clk::now();
-                const int32_t lo = L->kv_len[i];
-                if (int rc = st_batch_prefill(hl, i, seqs[i] + lo, T[i] - lo, nullptr, &pend[i])) return rc;
-                st.ms_large_prefill += ms_since(a);
+                list.push_back(i);
                 who[i] = WRITES_LARGE;
                 rem[i] = n_seg;
                 ++st.n_handoffs;
@@ -947,8 +1029,9 @@ int st_generate_batch(st_batch *hs, st_batch *hl, const st_host_rule *rule, int3
             }
         }
         if (int rc = step(hs, &st.ms_small_decode)) return rc;
+        if (int rc = catch_up(hl, L, list, &st.ms_large_prefill)) return rc;  // the hand-overs of this round, together
         // sequences inside a target segment: emit; the segment's last token is not fed to the target
-        rows.clear(), toks.clear();
+        rows.clear(), toks.clear(), list.clear();
         for (int32_t i = 0; i < n_seq; ++i) {
             if (who[i] != WRITES_LARGE) continue;
             any = true;
@@ -959,16 +1042,14 @@ int st_generate_batch(st_batch *hs, st_batch *hl, const st_host_rule *rule, int3
             if (T[i] - P == n_out) {
                 who[i] = DONE;
             } else if (--rem[i] == 0) {
-                auto a = clk::now();
-                const int32_t lo = S->kv_len[i];
-                if (int rc = st_batch_prefill(hs, i, seqs[i] + lo, T[i] - lo, nullptr, &pend[i])) return rc;
-                st.ms_small_prefill += ms_since(a);
+                list.push_back(i);
                 who[i] = WRITES_SMALL;
             } else {
                 rows.push_back(i), toks.push_back(tok);
             }
         }
         if (int rc = step(hl, &st.ms_large_decode)) return rc;
+        if (int rc = catch_up(hs, S, list, &st.ms_small_prefill)) return rc;  // the segments that ended, together
         if (!any) break;
     }
     for (int32_t i = 0; i < n_seq; ++i) st.n_out += T[i] - prompt_lens[i];

@@ -1320,6 +1320,43 @@ static int gemm(const Model &m, const bf16_t *A, const bf16_t *Alo, int lda, con
     return DUAL ? 0 : splits;
 }
 
+// Causal attention of n query rows at positions pos0 .. pos0+n-1 over one sequence's cache (kc / vc of one layer).
+static void launch_flash(const Model &m, const bf16_t *qb, const bf16_t *kc, const bf16_t *vc, bf16_t *attn,
+                         bf16_t *attn_lo, int n, int pos0) {
+    const st_config &c = m.c;
+    const int d = c.head_dim, nq = c.n_q_heads, nkv = c.n_kv_heads;
+    const Workspace &w = m.ws;
+    const bool long_chunk = d == 128 && n >= kBigRows;
+    const int G = nq / nkv, rows = n * G, rpb = long_chunk ? 32 * kLongWaves : 128, rblocks = (rows + rpb - 1) / rpb;
+    const int n_tiles = (pos0 + n + kFlashKeys - 1) / kFlashKeys;
+    // key splits: enough blocks for every CU, bounded by the tiles and by the partial buffer
+    int splits = (512 + rblocks * nkv - 1) / (rblocks * nkv);
+    if (splits > n_tiles) splits = n_tiles;
+    if (splits > 32) splits = 32;
+    const size_t cap = partial_floats(c);
+    while (splits > 1 && (size_t)splits * n * nq * (d + 2) > cap) --splits;
+    float *part_o = w.qkv, *part_ml = w.qkv + (size_t)splits * n * nq * d;
+    dim3 fgrid(rblocks, nkv, splits);
+    if (long_chunk)
+        hipLaunchKernelGGL(k_flash_long<kLongWaves>, fgrid, dim3(64 * kLongWaves), 0, m.stream, qb, kc, vc, attn, part_o,
+                           part_ml, n, pos0, nq, G, c.max_seq);
+    else if (d == 128)
+        hipLaunchKernelGGL(k_flash_prefill<128>, fgrid, dim3(256), 0, m.stream, qb, kc, vc, attn, attn_lo, part_o,
+                           part_ml, n, pos0, nq, G, c.max_seq);
+    else
+        hipLaunchKernelGGL(k_flash_prefill<64>, fgrid, dim3(256), 0, m.stream, qb, kc, vc, attn, attn_lo, part_o,
+                           part_ml, n, pos0, nq, G, c.max_seq);
+    if (splits > 1) {
+        const int n_rows = n * nq;
+        if (d == 128)
+            hipLaunchKernelGGL(k_flash_combine<128>, dim3((n_rows + 1) / 2), dim3(256), 0, m.stream, part_o, part_ml,
+                               splits, n_rows, attn, attn_lo);
+        else
+            hipLaunchKernelGGL(k_flash_combine<64>, dim3((n_rows + 3) / 4), dim3(256), 0, m.stream, part_o, part_ml,
+                               splits, n_rows, attn, attn_lo);
+    }
+}
+
 void launch_prefill_layers(const Model &m, int32_t pos0, int32_t n) {
     const st_config &c = m.c;
     const int h = c.hidden, d = c.head_dim, nq = c.n_q_heads, nkv = c.n_kv_heads, I = c.intermediate;
@@ -1338,37 +1375,7 @@ void launch_prefill_layers(const Model &m, int32_t pos0, int32_t n) {
         hipLaunchKernelGGL(k_rope_append, dim3(n, nq + 2 * nkv), dim3(d / 2), 0, m.stream, w.qkv, sq,
                            (size_t)n * qkv, m.bqkv[l], w.rope, w.qb, m.kcache + lofs, m.vcache + lofs, pos0, nq, nkv,
                            d, c.max_seq);
-        {
-            const bool long_chunk = d == 128 && n >= kBigRows;
-            const int G = nq / nkv, rows = n * G, rpb = long_chunk ? 32 * kLongWaves : 128, rblocks = (rows + rpb - 1) / rpb;
-            const int n_tiles = (pos0 + n + kFlashKeys - 1) / kFlashKeys;
-            // key splits: enough blocks for every CU, bounded by the tiles and by the partial buffer
-            int splits = (512 + rblocks * nkv - 1) / (rblocks * nkv);
-            if (splits > n_tiles) splits = n_tiles;
-            if (splits > 32) splits = 32;
-            const size_t cap = partial_floats(c);
-            while (splits > 1 && (size_t)splits * n * nq * (d + 2) > cap) --splits;
-            float *part_o = w.qkv, *part_ml = w.qkv + (size_t)splits * n * nq * d;
-            dim3 fgrid(rblocks, nkv, splits);
-            if (long_chunk)
-                hipLaunchKernelGGL(k_flash_long<kLongWaves>, fgrid, dim3(64 * kLongWaves), 0, m.stream, w.qb, m.kcache + lofs, m.vcache + lofs,
-                                   w.attn, part_o, part_ml, n, pos0, nq, G, c.max_seq);
-            else if (d == 128)
-                hipLaunchKernelGGL(k_flash_prefill<128>, fgrid, dim3(256), 0, m.stream, w.qb, m.kcache + lofs,
-                                   m.vcache + lofs, w.attn, attn_lo, part_o, part_ml, n, pos0, nq, G, c.max_seq);
-            else
-                hipLaunchKernelGGL(k_flash_prefill<64>, fgrid, dim3(256), 0, m.stream, w.qb, m.kcache + lofs,
-                                   m.vcache + lofs, w.attn, attn_lo, part_o, part_ml, n, pos0, nq, G, c.max_seq);
-            if (splits > 1) {
-                const int n_rows = n * nq;
-                if (d == 128)
-                    hipLaunchKernelGGL(k_flash_combine<128>, dim3((n_rows + 1) / 2), dim3(256), 0, m.stream, part_o,
-                                       part_ml, splits, n_rows, w.attn, attn_lo);
-                else
-                    hipLaunchKernelGGL(k_flash_combine<64>, dim3((n_rows + 3) / 4), dim3(256), 0, m.stream, part_o,
-                                       part_ml, splits, n_rows, w.attn, attn_lo);
-            }
-        }
+        launch_flash(m, w.qb, m.kcache + lofs, m.vcache + lofs, w.attn, attn_lo, n, pos0);
         int so = gemm<false>(m, w.attn, attn_lo, qd, m.wo[l], n, h, qd, nullptr, nullptr, 0);
         hipLaunchKernelGGL(k_rmsnorm_rows, dim3(n), dim3(256), 0, m.stream, w.x, w.qkv, so, (size_t)n * h,
                            m.norm_mlp[l], w.xn, xn_lo, h, c.rms_eps);
@@ -1394,11 +1401,13 @@ void launch_prefill_layers(const Model &m, int32_t pos0, int32_t n) {
 // cache, attention is the split decode attention with one grid plane per row, and the LM head is one more GEMM
 // followed by a per-row arg-max.
 // ---------------------------------------------------------------------------------------
-// RoPE at each row's own position, K/V appended to each row's own cache, q kept in fp32 (as in the single step).
+// RoPE at each row's own position, K/V appended to each row's own cache; q kept in fp32 (decode rows, as in the
+// single step) or, with qb != nullptr, written as bf16 (catch-up rows).
 __global__ void k_rope_append_rows(const float *__restrict__ part, int n_part, size_t part_stride,
                                    const bf16_t *__restrict__ bias, const float2 *__restrict__ rope,
-                                   float *__restrict__ q_rows, bf16_t *__restrict__ kc, bf16_t *__restrict__ vc,
-                                   const int32_t *__restrict__ row_pos, const int32_t *__restrict__ row_seq,
+                                   float *__restrict__ q_rows, bf16_t *__restrict__ qb, bf16_t *__restrict__ kc,
+                                   bf16_t *__restrict__ vc, const int32_t *__restrict__ row_pos,
+                                   const int32_t *__restrict__ row_seq,
                                    size_t seq_stride, int nq, int nkv, int d, int max_seq) {
     const int row = blockIdx.x, head = blockIdx.y, i = threadIdx.x, half = d >> 1;
     const int pos = row_pos[row];
@@ -1422,9 +1431,15 @@ __global__ void k_rope_append_rows(const float *__restrict__ part, int n_part, s
         hi = nhi;
     }
     if (head < nq) {
-        float *dst = q_rows + (size_t)row * nq * d + head * d;
-        dst[i] = lo;
-        dst[i + half] = hi;
+        if (qb) {  // catch-up rows: bf16 queries for the flash kernels
+            bf16_t *dq = qb + (size_t)row * nq * d + head * d;
+            dq[i] = f32_to_bf16(lo);
+            dq[i + half] = f32_to_bf16(hi);
+        } else {
+            float *dst = q_rows + (size_t)row * nq * d + head * d;
+            dst[i] = lo;
+            dst[i + half] = hi;
+        }
         return;
     }
     bf16_t *dst = head < nq + nkv ? kc + cache + ((size_t)(head - nq) * max_seq + pos) * d
@@ -1487,8 +1502,8 @@ void launch_batch_step(const Model &m, const BatchRows &b, int n, int attn_block
                            m.norm_attn[l], w.xn, w.xn_lo, h, c.rms_eps);
         const int sq = gemm<false>(m, w.xn, w.xn_lo, h, m.wqkv[l], n, qkv, h, nullptr, nullptr, 0);
         hipLaunchKernelGGL(k_rope_append_rows, dim3(n, nq + 2 * nkv), dim3(d / 2), 0, m.stream, w.qkv, sq,
-                           (size_t)n * qkv, m.bqkv[l], w.rope, b.q_rows, m.kcache + lofs, m.vcache + lofs, b.row_pos,
-                           b.row_seq, b.seq_stride, nq, nkv, d, c.max_seq);
+                           (size_t)n * qkv, m.bqkv[l], w.rope, b.q_rows, (bf16_t *)nullptr, m.kcache + lofs,
+                           m.vcache + lofs, b.row_pos, b.row_seq, b.seq_stride, nq, nkv, d, c.max_seq);
         launch_attn_rows(m, l, m.stream, attn_blocks, rows, n, b.q_rows, b.part_ml, b.part_acc, b.o_rows);
         hipLaunchKernelGGL(k_rows_two_term, dim3(((size_t)n * qd + 255) / 256), dim3(256), 0, m.stream, b.o_rows,
                            w.attn, w.attn_lo, (size_t)n * qd);
@@ -1505,6 +1520,67 @@ void launch_batch_step(const Model &m, const BatchRows &b, int n, int attn_block
     const int sl = gemm<false>(m, w.xn, w.xn_lo, h, m.lm_head, n, c.vocab, h, nullptr, nullptr, 0);
     hipLaunchKernelGGL(k_argmax_rows, dim3(n), dim3(1024), 0, m.stream, w.qkv, sl, (size_t)n * c.vocab, c.vocab,
                        b.logits, b.row_next);
+}
+
+// Xg[j][:] = X[idx[j]][:] + the K slices of the last down projection for that row
+__global__ __launch_bounds__(256) void k_gather_rows(const float *__restrict__ X, const float *__restrict__ part,
+                                                     int n_part, size_t part_stride, const int32_t *__restrict__ idx,
+                                                     float *__restrict__ Xg, int h) {
+    const size_t src = (size_t)idx[blockIdx.x] * h;
+    for (int i = threadIdx.x; i < h; i += 256) {
+        float v = X[src + i];
+        for (int s = 0; s < n_part; ++s) v += part[(size_t)s * part_stride + src + i];
+        Xg[(size_t)blockIdx.x * h + i] = v;
+    }
+}
+
+// Catch-up pass over rows of several sequences at once (ragged): R rows in all, the rows of segment j are
+// contiguous (segs[j].row0 .. +len) at positions kv0 .. kv0+len-1 of sequence segs[j].seq.  Projections see one
+// R-row chunk (the weights are streamed once for all sequences); RoPE / KV append go by the per-row (sequence,
+// position) arrays; attention is launched per segment on that sequence's cache; the LM head runs on the gathered
+// last rows of the segments.
+void launch_prefill_varlen(const Model &m, const BatchRows &b, const VarlenSeg *segs, int n_seg, int R) {
+    const st_config &c = m.c;
+    const int h = c.hidden, d = c.head_dim, nq = c.n_q_heads, nkv = c.n_kv_heads, I = c.intermediate;
+    const int qd = nq * d, qkv = m.qkv_dim;
+    const Workspace &w = m.ws;
+    const bool two = R <= kSplitRows;
+    bf16_t *xn_lo = two ? w.xn_lo : nullptr, *attn_lo = two ? w.attn_lo : nullptr, *act_lo = two ? w.act_lo : nullptr;
+    hipLaunchKernelGGL(k_embed_rows, dim3(R), dim3(256), 0, m.stream, m.embed, b.row_tok, w.x, h, c.vocab);
+    int pending = 0;
+    for (int l = 0; l < c.n_layers; ++l) {
+        const size_t lofs = (size_t)l * nkv * c.max_seq * d;
+        hipLaunchKernelGGL(k_rmsnorm_rows, dim3(R), dim3(256), 0, m.stream, w.x, w.qkv, pending, (size_t)R * h,
+                           m.norm_attn[l], w.xn, xn_lo, h, c.rms_eps);
+        const int sq = gemm<false>(m, w.xn, xn_lo, h, m.wqkv[l], R, qkv, h, nullptr, nullptr, 0);
+        hipLaunchKernelGGL(k_rope_append_rows, dim3(R, nq + 2 * nkv), dim3(d / 2), 0, m.stream, w.qkv, sq,
+                           (size_t)R * qkv, m.bqkv[l], w.rope, (float *)nullptr, w.qb, m.kcache + lofs,
+                           m.vcache + lofs, b.row_pos, b.row_seq, b.seq_stride, nq, nkv, d, c.max_seq);
+        for (int j = 0; j < n_seg; ++j) {
+            const size_t cache = (size_t)segs[j].seq * b.seq_stride + lofs, q0 = (size_t)segs[j].row0 * qd;
+            launch_flash(m, w.qb + q0, m.kcache + cache, m.vcache + cache, w.attn + q0, attn_lo ? attn_lo + q0 : nullptr,
+                         segs[j].len, segs[j].kv0);
+        }
+        const int so = gemm<false>(m, w.attn, attn_lo, qd, m.wo[l], R, h, qd, nullptr, nullptr, 0);
+        hipLaunchKernelGGL(k_rmsnorm_rows, dim3(R), dim3(256), 0, m.stream, w.x, w.qkv, so, (size_t)R * h,
+                           m.norm_mlp[l], w.xn, xn_lo, h, c.rms_eps);
+        if (R <= (h % kRingBK == 0 ? kSkinnyRows : kSmallRows)) {
+            const int sg = gemm<false>(m, w.xn, xn_lo, h, m.wgu[l], R, 2 * I, h, nullptr, nullptr, 0);
+            hipLaunchKernelGGL(k_swiglu_rows, dim3((I / 4 + 255) / 256, R), dim3(256), 0, m.stream, w.qkv, sg,
+                               (size_t)R * 2 * I, I, w.act, act_lo);
+        } else {
+            gemm<true>(m, w.xn, xn_lo, h, m.wgu[l], R, I, h, w.act, act_lo, I);
+        }
+        pending = gemm<false>(m, w.act, act_lo, I, m.wdown[l], R, h, I, nullptr, nullptr, 0);
+    }
+    // head on the last row of every segment (their row indices are in b.row_next on entry)
+    hipLaunchKernelGGL(k_gather_rows, dim3(n_seg), dim3(256), 0, m.stream, w.x, w.qkv, pending, (size_t)R * h,
+                       b.row_next, b.o_rows, h);
+    hipLaunchKernelGGL(k_rmsnorm_rows, dim3(n_seg), dim3(256), 0, m.stream, b.o_rows, (const float *)nullptr, 0,
+                       (size_t)0, m.final_norm, w.xn, w.xn_lo, h, c.rms_eps);
+    const int sl = gemm<false>(m, w.xn, w.xn_lo, h, m.lm_head, n_seg, c.vocab, h, nullptr, nullptr, 0);
+    hipLaunchKernelGGL(k_argmax_rows, dim3(n_seg), dim3(1024), 0, m.stream, w.qkv, sl, (size_t)n_seg * c.vocab,
+                       c.vocab, b.logits, b.row_next);
 }
 
 }  // namespace st

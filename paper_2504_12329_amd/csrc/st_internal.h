@@ -121,6 +121,13 @@ struct BatchRows {
 };
 // All layers, LM head and arg-max for n rows (n <= 64); m.kcache / m.vcache are the caches of sequence 0.
 void launch_batch_step(const Model &m, const BatchRows &b, int n, int attn_blocks);
+// One segment of a ragged catch-up pass: rows row0 .. row0+len-1 are positions kv0 .. of sequence seq.
+struct VarlenSeg {
+    int32_t seq, row0, len, kv0;
+};
+// Ragged catch-up over R rows of n_seg sequences (R <= max_chunk); b.row_next holds the row index of every
+// segment's last row on entry and the greedy next tokens on return; b.o_rows needs n_seg * hidden floats.
+void launch_prefill_varlen(const Model &m, const BatchRows &b, const VarlenSeg *segs, int n_seg, int R);
 
 // ---- launchers (trigger.hip) ----
 void launch_trigger_scan(const st_trigger_rule &rule, const int32_t *tokens, int32_t lo, int32_t hi,

@@ -17,8 +17,8 @@ def _margin(lg):
     return float((s[-1] - s[-2]) / np.abs(lg).max())
 
 
-def _setup(name, n_seq, seed, max_seq, n_layers=None, gen_device="cpu"):
-    cfg = synth.model_config(name, max_seq=max_seq, max_chunk=64, n_layers=n_layers)
+def _setup(name, n_seq, seed, max_seq, n_layers=None, gen_device="cpu", max_chunk=64):
+    cfg = synth.model_config(name, max_seq=max_seq, max_chunk=max_chunk, n_layers=n_layers)
     w = synth.make_weights(cfg, seed, device=gen_device)
     oracles = [O.OracleModel(synth.oracle_config(cfg), synth.oracle_views(cfg, w)) for _ in range(n_seq)]
     wg = dict(embed=w["embed"].cuda(), final_norm=w["final_norm"].cuda(),
@@ -152,3 +152,32 @@ def test_batched_loop_matches_per_sequence_oracle():
     assert out["stats"]["n_handoffs"] == sum(len(tr.triggers) for tr in traces)
     bs.close()
     bl.close()
+
+
+@pytest.mark.parametrize("lens", [[5, 1, 33, 12], [70, 90, 60], [200, 150, 100]])
+def test_ragged_catch_up_pass(lens):
+    """Several sequences with different cached lengths each receive a chunk of a different length in one pass
+    (skinny / two-term / long-chunk GEMM regimes by total rows); each sequence's last-position logits must match
+    its own oracle, and a batched decode step afterwards must see the appended keys."""
+    n = len(lens)
+    print_case("tiny model, ragged catch-up of", lens, "tokens onto caches of", [7 * (j + 1) for j in range(n)])
+    cfg, batch, oracles = _setup("tiny_small", n + 1, 1, max_seq=320, max_chunk=512)
+    for j in range(n):                                    # different cached lengths first (sequence n stays empty)
+        pre = synth.make_prompt(7 * (j + 1), cfg["vocab"], 300 + j)
+        oracles[j].feed(pre)
+        batch.prefill(j, pre, want_logits=False)
+    chunks = [synth.make_prompt(lens[j], cfg["vocab"], 400 + j) for j in range(n)]
+    order = list(range(n))[::-1]                          # the order of the segments must not matter
+    lg_g, nxt = batch.prefill_many(order, [chunks[j] for j in order], want_logits=True)
+    worst, toks = 0.0, {}
+    for r, j in enumerate(order):
+        lg_o = oracles[j].feed(chunks[j])
+        worst = max(worst, rel_err(lg_g[r], lg_o))
+        assert nxt[r] == O.argmax(lg_g[r]) and batch.kv_len(j) == oracles[j].kv_len
+        toks[j] = O.argmax(lg_o)
+    lg_g, _ = batch.decode_step(list(range(n)), [toks[j] for j in range(n)], want_logits=True)
+    for j in range(n):
+        worst = max(worst, rel_err(lg_g[j], oracles[j].feed([toks[j]])))
+    print_case("worst relative logit error", worst)
+    assert worst <= LOGIT_TOL and batch.kv_len(n) == 0
+    batch.close()
