@@ -303,6 +303,13 @@ __device__ __forceinline__ void wait_loads() {  // until at most N of this wave'
 }
 template <int V>
 using ic = std::integral_constant<int, V>;
+template <int N, int I = 0, class F>
+__device__ __forceinline__ void static_for(F &&f) {  // f(ic<0>{}), ..., f(ic<N-1>{})
+    if constexpr (I < N) {
+        f(ic<I>{});
+        static_for<N, I + 1>(f);
+    }
+}
 
 template <bool DUAL>
 __global__ __launch_bounds__(256) void k_gemm_ring(const bf16_t *__restrict__ A, int lda, const bf16_t *__restrict__ B,
@@ -477,118 +484,177 @@ __global__ __launch_bounds__(256) void k_gemm_ring(const bf16_t *__restrict__ A,
 }
 
 // ---------------------------------------------------------------------------------------
-// Short chunks (at most 128 rows, two-term activations): the weight stream sets the time, so the kernel is built
-// to keep bytes in flight.  A block owns 128 weight rows and a K slice; weights and both activation terms go
-// global -> LDS directly in 128-byte row segments into a ring of NS stages of (16 + MT*8) KB (64 KB of weights in
-// flight per CU, no staging registers), one barrier per 64-wide K step.  Wave w multiplies its
-// 32 weight rows with every 32-row activation tile (C^T = W A^T, so a lane owns an activation row) and the raw fp32
-// partial sums of the K slice go to part[z][M][N] like those of the other GEMMs.  Needs K % 64 == 0.
+// Weight-streaming GEMM for chunks of at most 256 rows (two-term activations).  A block owns nt <= 8 tiles of 32
+// weight rows and a K slice; K advances BK columns per stage.  Every block re-reads the activation rows from L2,
+// and direct loads of L2-resident data cost as much load-path time as the weights from HBM do (measured: adding
+// 24 KB of activations to 16 KB of weights per stage takes the weight stream from 6.0 to 4.2 TB/s), so the block
+// is made tall -- 256 weight rows per activation fetch -- and LDS is split into two rings: weights, nw stages,
+// filled by waves 0-1, and activations, na stages, filled by waves 2-3.  The two kinds of loads sit in different
+// waves because a wave's load counter retires in order: one wave cannot wait for a recent activation load
+// without also waiting for every older weight load.  BK = 64 (128-byte row segments, which HBM streams a fifth
+// faster than 64-byte ones) up to 128 rows; BK = 32 above, where the activation stages would not leave room for
+// three weight stages.  All four waves multiply: wave w owns weight tiles w and w + 4 against every 32-row
+// activation tile (C^T = W A^T, a lane owns an activation row); raw fp32 partial sums of the K slice go to
+// part[z][M][N].  Needs K % BK == 0 and (nw - 2) * (loads per weight wave per stage) <= 63.
 // ---------------------------------------------------------------------------------------
-template <int MT>
-struct SkinnyShape {
-    static constexpr int kWBytes = 128 * kRingBK * 2;             // 16 KB of weights per stage
-    static constexpr int kABytes = MT * 64 * kRingBK * 2;         // hi and lo rows of MT 32-row tiles
-    static constexpr int kStage = kWBytes + kABytes;
-    // MT = 1: three stages, so that two blocks share a CU (measured a little faster than one block with six);
-    // otherwise all of LDS: 5, 4, 3 stages for MT = 2, 3, 4
-    static constexpr int kStages = MT == 1 ? 3 : (160 * 1024) / kStage;
-    static constexpr int kLoads = 4 + 2 * MT;                     // direct loads per wave per stage
+__device__ __forceinline__ void wait_loads_rt(int n) {  // s_waitcnt takes an immediate only
+#define ST_W1(v) case v: wait_loads<v>(); break;
+#define ST_W8(v) ST_W1(v) ST_W1(v + 1) ST_W1(v + 2) ST_W1(v + 3) ST_W1(v + 4) ST_W1(v + 5) ST_W1(v + 6) ST_W1(v + 7)
+    switch (n) {
+        ST_W8(0) ST_W8(8) ST_W8(16) ST_W8(24) ST_W8(32) ST_W8(40) ST_W8(48) ST_W8(56)
+        default: wait_loads<0>(); break;
+    }
+#undef ST_W8
+#undef ST_W1
+}
+
+template <int BK>
+struct StreamGeom {
+    static constexpr int kSeg = BK * 2;          // bytes of a row per stage
+    static constexpr int kLpr = kSeg / 16;       // lanes per row in a direct load
+    static constexpr int kRpi = 64 / kLpr;       // rows per 1 KB instruction
+    static constexpr int kWTile = 32 * kSeg;     // bytes of one 32-row weight tile per stage
+    static constexpr int kATile = 64 * kSeg;     // bytes of one activation tile (32 hi + 32 lo rows) per stage
+    // 16-byte chunk swizzle of LDS row `row` (conflict-free fragment reads)
+    __device__ static int swz(int row) { return BK == 32 ? (row >> 2) & 3 : ring_swz(row); }
 };
 
-template <int MT>
-__global__ __launch_bounds__(256) void k_gemm_skinny(const bf16_t *__restrict__ A, const bf16_t *__restrict__ Alo,
+template <int MT, int BK>
+__global__ __launch_bounds__(256) void k_gemm_stream(const bf16_t *__restrict__ A, const bf16_t *__restrict__ Alo,
                                                      int lda, const bf16_t *__restrict__ B, int M, int N, int K,
-                                                     int kps, float *__restrict__ part) {
-    using S = SkinnyShape<MT>;
-    constexpr int NS = S::kStages, DPS = S::kLoads;
+                                                     int kps, int nt, int nw, int na, float *__restrict__ part) {
+    using G = StreamGeom<BK>;
+    constexpr int kAStage = MT * G::kATile;
+    constexpr int kALoads = MT * 64 / G::kRpi / 2;   // activation instructions per stage of waves 2, 3
+    constexpr int kWLoadsMax = 8 * 32 / G::kRpi / 2; // weight instructions per stage of waves 0, 1 at nt = 8
+    constexpr int NL = kALoads > kWLoadsMax ? kALoads : kWLoadsMax;
     extern __shared__ __align__(16) unsigned char ring[];
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, kg = lane >> 5;
-    const int n0 = blockIdx.x * 128;
+    const int n0 = blockIdx.x * nt * 32;
     const int kbeg = blockIdx.y * kps;
-    const int nk = (min(K, kbeg + kps) - kbeg) / kRingBK;
+    const int nk = (min(K, kbeg + kps) - kbeg) / BK;
     const uint32_t ring0 = (uint32_t)(uintptr_t)ring;
+    const int wstage = nt * G::kWTile, a_ring = na * kAStage;
 
-    // direct loads: a 1 KB instruction fills 8 LDS rows of 128 bytes; lane -> (row lane/8, 16-byte position lane%8
-    // holding global chunk position ^ swizzle(row)).  Weights: instructions 4*wave .. +3 (rows 32*wave .. +31);
-    // activations: LDS row 64*t + 32*term + r is row 32*t + r of term (0 = high, 1 = low); rows past the edge re-read
-    // the last valid row and are never stored.
-    const bf16_t *pw[4], *pa[2 * MT];
-    int a_lds[2 * MT];
+    // direct loads: a 1 KB instruction fills kRpi LDS rows; lane -> (row lane/kLpr, 16-byte position lane%kLpr
+    // holding global chunk position ^ swz(row)).  Waves 0-1: weights; waves 2-3: activations -- LDS row
+    // 64*t + 32*term + r is row 32*t + r of term (0 = high, 1 = low); rows past the edge re-read the last valid
+    // row and are never stored.
+    const bool w_loader = wave < 2;
+    const int n_loads = w_loader ? nt * 32 / G::kRpi / 2 : kALoads;
+    const int depth = w_loader ? nw : na;
+    const uint32_t my_ring = ring0 + (w_loader ? a_ring : 0), my_stage = w_loader ? wstage : kAStage;
+    const bf16_t *pl[NL];
+    int l_off[NL];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int row = (wave * 4 + i) * 8 + (lane >> 3);
-        pw[i] = B + (size_t)min(n0 + row, N - 1) * K + kbeg + ((lane & 7) ^ ring_swz(row)) * 8;
+    for (int i = 0; i < NL; ++i) {
+        const int inst = (w_loader ? wave : wave - 2) * n_loads + i;
+        const int row = inst * G::kRpi + lane / G::kLpr;
+        const int piece = ((lane % G::kLpr) ^ G::swz(row)) * 8;
+        if (w_loader) {
+            pl[i] = B + (size_t)min(n0 + row, N - 1) * K + kbeg + piece;
+        } else {
+            const int t = min(row >> 6, MT - 1), term = (row >> 5) & 1, r = row & 31;
+            pl[i] = (term ? Alo : A) + (size_t)min(t * 32 + r, M - 1) * lda + kbeg + piece;
+        }
+        l_off[i] = inst * 1024;
     }
-#pragma unroll
-    for (int i = 0; i < 2 * MT; ++i) {
-        const int inst = wave * 2 * MT + i;                       // of 8*MT instructions, 8 rows each
-        const int row = inst * 8 + (lane >> 3);
-        const int t = row >> 6, term = (row >> 5) & 1, r = row & 31;
-        pa[i] = (term ? Alo : A) + (size_t)min(t * 32 + r, M - 1) * lda + kbeg + ((lane & 7) ^ ring_swz(row)) * 8;
-        a_lds[i] = S::kWBytes + inst * 1024;
-    }
-    auto issue = [&](int st) {
-        const uint32_t base = ring0 + (st % NS) * S::kStage;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) load_to_lds16(pw[i] + st * kRingBK, base + (wave * 4 + i) * 1024);
-#pragma unroll
-        for (int i = 0; i < 2 * MT; ++i) load_to_lds16(pa[i] + st * kRingBK, base + a_lds[i]);
+    int iss_st = 0, iss_slot = 0;  // next stage this wave loads and its ring slot
+    auto issue_one = [&](auto i_c) {
+        constexpr int i = decltype(i_c)::value;
+        if constexpr (i < NL)
+            if (i < n_loads) load_to_lds16(pl[i] + iss_st * BK, my_ring + iss_slot * my_stage + l_off[i]);
+    };
+    auto issued = [&]() {
+        ++iss_st;
+        if (++iss_slot == depth) iss_slot = 0;
     };
 
-    f32x16 acc[MT];
+    f32x16 acc[2][MT];
 #pragma unroll
-    for (int t = 0; t < MT; ++t)
+    for (int j = 0; j < 2; ++j)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
+        for (int t = 0; t < MT; ++t)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[j][t][r] = 0.f;
+    const bool second = wave + 4 < nt;  // this wave's second weight tile exists
+    // swizzles of LDS rows 32*b + l32 for even / odd b (weight tile w and w + 4 have the parity of w)
+    const int sw_even = G::swz(l32), sw_odd = G::swz(32 + l32), sw_w = (wave & 1) ? sw_odd : sw_even;
 
-    // fragment reads (see k_gemm_ring): chunk (2*ks + kg) ^ swizzle, swizzle(32*b + l32) = swizzle(l32) ^ 4*(b & 1)
-    const int ch0 = (kg ^ ring_swz(l32)) * 16;
-    const int w_off = (wave * 32 + l32) * 128, w_ch = ch0 ^ ((wave & 1) * 64);
-
-    for (int st = 0; st < NS - 1 && st < nk; ++st) issue(st);
+    for (int st = 0; st < depth - 1 && st < nk; ++st) {
+        static_for<NL>([&](auto i_c) { issue_one(i_c); });
+        issued();
+    }
+    int wslot = 0, aslot = 0;
+    constexpr int KS = BK / 16, GROUPS = 2 * KS, PER = (NL + GROUPS - 1) / GROUPS;
     for (int st = 0; st < nk; ++st) {
-        // stage st has landed once at most the stages after it are outstanding
-        switch (min(nk, st + NS - 1) - (st + 1)) {
-            case 0: wait_loads<0>(); break;
-            case 1: wait_loads<DPS>(); break;
-            case 2: wait_loads<2 * DPS>(); break;
-            case 3: wait_loads<(NS > 4 ? 3 : 0) * DPS>(); break;
-            default: wait_loads<(NS > 5 ? 4 : 0) * DPS>(); break;
-        }
+        // stage st has landed once only the stages this wave issued after it are outstanding
+        wait_loads_rt((iss_st - (st + 1)) * n_loads);
         __builtin_amdgcn_s_barrier();  // stage st complete for every wave; every wave is done with stage st-1
-        if (st + NS - 1 < nk) issue(st + NS - 1);
-        const unsigned char *base = ring + (st % NS) * S::kStage;
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            const bf16x8 wf = as_bf16x8(*reinterpret_cast<const u32x4 *>(base + w_off + (w_ch ^ (ks * 32))));
+        const bool more = iss_st < nk;
+        const unsigned char *wb = ring + a_ring + wslot * wstage, *ab = ring + aslot * kAStage;
+        // fragments of K step ks + 1 are read while the MFMAs of step ks run
+        bf16x8 wf[2][2], ah[2][MT], al[2][MT];
+        auto frags = [&](auto ks_c) {
+            constexpr int ks = decltype(ks_c)::value, b = ks & 1;
+            const int c = 2 * ks + kg;
+            wf[b][0] = as_bf16x8(*reinterpret_cast<const u32x4 *>(wb + (wave * 32 + l32) * G::kSeg + (c ^ sw_w) * 16));
+            if (second)
+                wf[b][1] = as_bf16x8(
+                    *reinterpret_cast<const u32x4 *>(wb + ((wave + 4) * 32 + l32) * G::kSeg + (c ^ sw_w) * 16));
 #pragma unroll
             for (int t = 0; t < MT; ++t) {
-                const unsigned char *ab = base + S::kWBytes + (t * 64 + l32) * 128;
-                const bf16x8 ah = as_bf16x8(*reinterpret_cast<const u32x4 *>(ab + (ch0 ^ (ks * 32))));
-                const bf16x8 al = as_bf16x8(*reinterpret_cast<const u32x4 *>(ab + 32 * 128 + (ch0 ^ 64 ^ (ks * 32))));
-                acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, ah, acc[t], 0, 0, 0);
-                acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, al, acc[t], 0, 0, 0);
+                ah[b][t] =
+                    as_bf16x8(*reinterpret_cast<const u32x4 *>(ab + (t * 64 + l32) * G::kSeg + (c ^ sw_even) * 16));
+                al[b][t] = as_bf16x8(
+                    *reinterpret_cast<const u32x4 *>(ab + (t * 64 + 32 + l32) * G::kSeg + (c ^ sw_odd) * 16));
             }
-        }
+        };
+        frags(ic<0>{});
+        static_for<KS>([&](auto ks_c) {
+            constexpr int ks = decltype(ks_c)::value, b = ks & 1;
+            if constexpr (ks + 1 < KS) frags(ic<ks + 1>{});
+            static_for<2>([&](auto j_c) {
+                constexpr int j = decltype(j_c)::value;
+                // a share of this wave's loads for the stage it fills, between the MFMA groups
+                if (more)
+                    static_for<PER>([&](auto q_c) { issue_one(ic<(2 * ks + j) * PER + decltype(q_c)::value>{}); });
+                if (j == 0 || second) {
+#pragma unroll
+                    for (int t = 0; t < MT; ++t) {
+                        acc[j][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[b][j], ah[b][t], acc[j][t], 0, 0, 0);
+                        acc[j][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[b][j], al[b][t], acc[j][t], 0, 0, 0);
+                    }
+                }
+            });
+            __builtin_amdgcn_sched_barrier(0);
+        });
+        if (more) issued();
+        if (++wslot == nw) wslot = 0;
+        if (++aslot == na) aslot = 0;
     }
     // C^T tile: lane = activation row (column of the MFMA result), register r = weight row 8*(r/4) + 4*kg + r%4
     float *pz = part + (size_t)blockIdx.y * M * N;
 #pragma unroll
-    for (int t = 0; t < MT; ++t) {
-        const int m = t * 32 + l32;
-        if (m >= M) continue;
+    for (int j = 0; j < 2; ++j) {
+        if (j == 1 && !second) break;
 #pragma unroll
-        for (int rq = 0; rq < 4; ++rq) {
-            const int n = n0 + wave * 32 + 8 * rq + 4 * kg;
-            float *dst = pz + (size_t)m * N + n;
-            if (n + 3 < N && (N & 3) == 0) {
-                *reinterpret_cast<float4 *>(dst) =
-                    make_float4(acc[t][4 * rq + 0], acc[t][4 * rq + 1], acc[t][4 * rq + 2], acc[t][4 * rq + 3]);
-            } else {
+        for (int t = 0; t < MT; ++t) {
+            const int m = t * 32 + l32;
+            if (m >= M) continue;
 #pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    if (n + e < N) dst[e] = acc[t][4 * rq + e];
+            for (int rq = 0; rq < 4; ++rq) {
+                const int n = n0 + (wave + 4 * j) * 32 + 8 * rq + 4 * kg;
+                float *dst = pz + (size_t)m * N + n;
+                if (n + 3 < N && (N & 3) == 0) {
+                    *reinterpret_cast<float4 *>(dst) = make_float4(acc[j][t][4 * rq + 0], acc[j][t][4 * rq + 1],
+                                                                   acc[j][t][4 * rq + 2], acc[j][t][4 * rq + 3]);
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (n + e < N) dst[e] = acc[j][t][4 * rq + e];
+                }
             }
         }
     }
@@ -1219,52 +1285,84 @@ static void ring_launch(const Model &m, dim3 grid, const bf16_t *A, int lda, con
     hipLaunchKernelGGL(kern, grid, dim3(256), kRingLds, m.stream, A, lda, B, M, N, K, kps, m.ws.qkv, outb, ldo, gg);
 }
 
-template <int MT>
-static void skinny_launch(const Model &m, dim3 grid, const bf16_t *A, const bf16_t *Alo, int lda, const bf16_t *B, int M,
-                          int N, int K, int kps) {
-    auto kern = k_gemm_skinny<MT>;
-    constexpr int lds = SkinnyShape<MT>::kStages * SkinnyShape<MT>::kStage;
+// Shape of a streaming GEMM launch: K columns per stage, weight tiles per block (4..8), K slices, ring depths.
+struct StreamShape {
+    int bk, nt, splits, kps, nw, na;
+};
+
+template <int MT, int BK>
+static void stream_launch(const Model &m, const StreamShape &sh, const bf16_t *A, const bf16_t *Alo, int lda,
+                          const bf16_t *B, int M, int N, int K) {
+    auto kern = k_gemm_stream<MT, BK>;
     static bool raised = false;  // more than 64 KB of dynamic LDS has to be allowed once per kernel
     if (!raised) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                  kRingLds);
         raised = true;
     }
-    hipLaunchKernelGGL(kern, grid, dim3(256), lds, m.stream, A, Alo, lda, B, M, N, K, kps, m.ws.qkv);
+    using G = StreamGeom<BK>;
+    const int lds = sh.na * MT * G::kATile + sh.nw * sh.nt * G::kWTile;
+    dim3 grid((N + 32 * sh.nt - 1) / (32 * sh.nt), sh.splits);
+    hipLaunchKernelGGL(kern, grid, dim3(256), lds, m.stream, A, Alo, lda, B, M, N, K, sh.kps, sh.nt, sh.nw, sh.na,
+                       m.ws.qkv);
 }
 
-// Chunks of at most kSmallRows rows (kSkinnyRows where the skinny kernel applies) use many K slices and an unfused
-// SwiGLU.
-constexpr int kSmallRows = 64, kSkinnyRows = 128;
+// One block per CU at a time, so the time is (rounds of 256 blocks) x (bytes a block loads, weights and activations
+// alike, + a fixed cost per block); the partial sums written and read again are charged per CU as well.
+static StreamShape stream_shape(const Model &m, int M, int N, int K) {
+    const int MT = (M + 31) / 32;
+    const int bk = MT <= 4 ? 64 : 32, seg = bk * 2, nk = K / bk;
+    const int fixed = 640 / seg;  // stages' worth of time a block spends filling its ring and storing its tile
+    const size_t cap = partial_floats(m.c);
+    StreamShape best = {bk, 8, 1, K, 2, 2};
+    double best_cost = -1;
+    for (int nt = 8; nt >= 4; --nt) {
+        const int tiles = (N + 32 * nt - 1) / (32 * nt);
+        for (int s = 1; s <= 32; ++s) {
+            const int steps = (nk + s - 1) / s;
+            if (s > 1 && (steps * bk < 256 || (size_t)s * M * N > cap)) break;
+            const int used = (nk + steps - 1) / steps;  // slices that are not empty
+            const int rounds = (tiles * used + 255) / 256;
+            const double cost = (double)rounds * (steps + fixed) * (nt * 32 + MT * 64) * seg + (double)used * M * N * 8 / 256;
+            if (best_cost < 0 || cost < best_cost) {
+                best_cost = cost;
+                best.nt = nt, best.splits = used, best.kps = steps * bk;
+            }
+        }
+    }
+    const int a_stage = MT * 64 * seg, w_stage = best.nt * 32 * seg;
+    best.na = kRingLds - 3 * a_stage >= 3 * w_stage ? 3 : 2;
+    int nw = (kRingLds - best.na * a_stage) / w_stage;
+    const int w_loads = best.nt * 32 / (64 / (seg / 16)) / 2;  // per weight wave per stage
+    if (nw > 2 + 63 / w_loads) nw = 2 + 63 / w_loads;
+    best.nw = nw;
+    return best;
+}
+
+// Two-term chunks (at most kSplitRows rows) use the streaming kernel and an unfused SwiGLU wherever K is a multiple
+// of 64; otherwise the register-staged kernel, with many K slices and an unfused SwiGLU up to kSmallRows rows.
+constexpr int kSmallRows = 64;
 
 template <bool DUAL>
 static int gemm(const Model &m, const bf16_t *A, const bf16_t *Alo, int lda, const bf16_t *B, int M, int N, int K,
                 bf16_t *outb, bf16_t *outlo, int ldo) {
     const bool big = !Alo && M >= kBigRows && K % kRingBK == 0 && K >= 2 * kRingBK;
-    if (!DUAL && Alo && M <= kSkinnyRows && K % kRingBK == 0) {
-        // short two-term chunk: 128 weight rows per block; K slices so that every CU holds a block where the tiles
-        // are few, as long as a slice keeps eight K steps and the partial sums (slices x M x N x 8 bytes written
-        // and read) stay below half the weight bytes (N x K x 2)
-        const int tiles = (N + 127) / 128, nk = K / kRingBK;
-        int splits = tiles < 256 ? 256 / tiles : 1;
-        if (splits > nk / 8) splits = nk / 8 > 1 ? nk / 8 : 1;
-        const int by_traffic = K / (8 * M) > 1 ? K / (8 * M) : 1;
-        if (splits > by_traffic) splits = by_traffic;
-        if (splits > 32) splits = 32;
-        const size_t cap = partial_floats(m.c);
-        while (splits > 1 && (size_t)splits * M * N > cap) --splits;
-        const int kps = (nk + splits - 1) / splits * kRingBK;
-        splits = (K + kps - 1) / kps;
-        dim3 grid(tiles, splits);
+    if (!DUAL && Alo && M <= kSplitRows && K % kRingBK == 0) {
+        const StreamShape sh = stream_shape(m, M, N, K);
         switch ((M + 31) / 32) {
-            case 1: skinny_launch<1>(m, grid, A, Alo, lda, B, M, N, K, kps); break;
-            case 2: skinny_launch<2>(m, grid, A, Alo, lda, B, M, N, K, kps); break;
-            case 3: skinny_launch<3>(m, grid, A, Alo, lda, B, M, N, K, kps); break;
-            default: skinny_launch<4>(m, grid, A, Alo, lda, B, M, N, K, kps); break;
+            case 1: stream_launch<1, 64>(m, sh, A, Alo, lda, B, M, N, K); break;
+            case 2: stream_launch<2, 64>(m, sh, A, Alo, lda, B, M, N, K); break;
+            case 3: stream_launch<3, 64>(m, sh, A, Alo, lda, B, M, N, K); break;
+            case 4: stream_launch<4, 64>(m, sh, A, Alo, lda, B, M, N, K); break;
+            case 5: stream_launch<5, 32>(m, sh, A, Alo, lda, B, M, N, K); break;
+            case 6: stream_launch<6, 32>(m, sh, A, Alo, lda, B, M, N, K); break;
+            case 7: stream_launch<7, 32>(m, sh, A, Alo, lda, B, M, N, K); break;
+            default: stream_launch<8, 32>(m, sh, A, Alo, lda, B, M, N, K); break;
         }
-        return splits;
+        return sh.splits;
     }
-    // two-term chunks of at most 32 / 64 rows use 32- / 64-row tiles with two waves: less LDS per block,
-    // so more blocks per CU keep more of the weight stream in flight
+    // (K not a multiple of 64) two-term chunks of at most 32 / 64 rows use 32- / 64-row tiles with two waves: less
+    // LDS per block, so more blocks per CU keep more of the weight stream in flight
     const int BM = big ? 256 : (Alo && M <= 32) ? 32 : (Alo && M <= 64) ? 64 : 128;
     const int BNO = (big ? 256 : 128) / (DUAL ? 2 : 1);
     GemmGrid gg;
@@ -1379,7 +1477,7 @@ void launch_prefill_layers(const Model &m, int32_t pos0, int32_t n) {
         int so = gemm<false>(m, w.attn, attn_lo, qd, m.wo[l], n, h, qd, nullptr, nullptr, 0);
         hipLaunchKernelGGL(k_rmsnorm_rows, dim3(n), dim3(256), 0, m.stream, w.x, w.qkv, so, (size_t)n * h,
                            m.norm_mlp[l], w.xn, xn_lo, h, c.rms_eps);
-        if (n <= (h % kRingBK == 0 ? kSkinnyRows : kSmallRows)) {  // small chunk: gate/up as a plain split-K GEMM over
+        if (n <= (h % kRingBK == 0 ? kSplitRows : kSmallRows)) {  // small chunk: gate/up as a plain split-K GEMM over
                                                                    // all 2I rows, SwiGLU in the consumer
             int sg = gemm<false>(m, w.xn, xn_lo, h, m.wgu[l], n, 2 * I, h, nullptr, nullptr, 0);
             hipLaunchKernelGGL(k_swiglu_rows, dim3((I / 4 + 255) / 256, n), dim3(256), 0, m.stream, w.qkv, sg,
@@ -1564,7 +1662,7 @@ void launch_prefill_varlen(const Model &m, const BatchRows &b, const VarlenSeg *
         const int so = gemm<false>(m, w.attn, attn_lo, qd, m.wo[l], R, h, qd, nullptr, nullptr, 0);
         hipLaunchKernelGGL(k_rmsnorm_rows, dim3(R), dim3(256), 0, m.stream, w.x, w.qkv, so, (size_t)R * h,
                            m.norm_mlp[l], w.xn, xn_lo, h, c.rms_eps);
-        if (R <= (h % kRingBK == 0 ? kSkinnyRows : kSmallRows)) {
+        if (R <= (h % kRingBK == 0 ? kSplitRows : kSmallRows)) {
             const int sg = gemm<false>(m, w.xn, xn_lo, h, m.wgu[l], R, 2 * I, h, nullptr, nullptr, 0);
             hipLaunchKernelGGL(k_swiglu_rows, dim3((I / 4 + 255) / 256, R), dim3(256), 0, m.stream, w.qkv, sg,
                                (size_t)R * 2 * I, I, w.act, act_lo);

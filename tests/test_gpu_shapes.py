@@ -102,10 +102,11 @@ def test_split_attention_matches_oracle_over_many_ranges():
     g.close()
 
 
-@pytest.mark.parametrize("m", [64, 65, 256, 257, 512, 513])
+@pytest.mark.parametrize("m", [32, 33, 64, 65, 128, 129, 200, 256, 257, 512, 513])
 def test_prefill_kernel_regime_boundaries(m):
-    """Chunk lengths on both sides of every kernel switch (32/64-row tiles, two-term activations up to
-    256 rows, 256x256 tiles from 512 rows), on top of 100 cached keys, against the oracle (2 layers)."""
+    """Chunk lengths on both sides of every kernel switch (one more 32-row activation tile, 128- to 64-byte row
+    segments above 128 rows, two-term activations up to 256 rows, 256x256 tiles above), on top of 100 cached keys,
+    against the oracle (2 layers)."""
     print_case(f"1.5B shape, 2 layers: 100 cached + chunk of {m}")
     cfg, g, o = make_pair("qwen1p5b", 11, max_seq=640, max_chunk=520, n_layers=2, gen_device="cuda")
     prompt = synth.make_prompt(100 + m, cfg["vocab"], 12)
