@@ -32,27 +32,31 @@ __global__ void k_note_fed(int32_t *state, const int32_t *tokens, int index, int
     state[kFed] = tok < 0 ? 0 : (tok >= vocab ? vocab - 1 : tok);
 }
 
+// Threads per row of k_rmsnorm_rows: with few rows a row is one block's serial walk, so the block is made wide.
+static inline int norm_threads(int rows) { return rows <= 512 ? 1024 : 256; }
+
 // x[row] += sum of the pending split-K partial results (fixed order), then y[row] = bf16(rmsnorm(x) * g).
 // part is [n_part][rows][h]; with g == nullptr only the residual update is done.  With Ylo the
 // normalised row is written as a sum of two bf16 numbers (Y + Ylo), which keeps 16 mantissa bits.
-__global__ __launch_bounds__(256) void k_rmsnorm_rows(float *__restrict__ X, const float *__restrict__ part, int n_part,
-                                                      size_t part_stride, const bf16_t *__restrict__ g,
-                                                      bf16_t *__restrict__ Y, bf16_t *__restrict__ Ylo, int h,
-                                                      float eps) {
-    __shared__ float red[4];
+__global__ __launch_bounds__(1024) void k_rmsnorm_rows(float *__restrict__ X, const float *__restrict__ part,
+                                                       int n_part, size_t part_stride, const bf16_t *__restrict__ g,
+                                                       bf16_t *__restrict__ Y, bf16_t *__restrict__ Ylo, int h,
+                                                       float eps) {
+    __shared__ float red[16];
     float4 *x = reinterpret_cast<float4 *>(X + (size_t)blockIdx.x * h);
     const float4 *p0 = reinterpret_cast<const float4 *>(part + (size_t)blockIdx.x * h);
     const size_t ps4 = part_stride / 4;
     const int n4 = h >> 2;  // h is a multiple of 8
+    const int nthr = blockDim.x;  // 256, or 1024 where the rows are few and each would be a long serial walk
     float ss = 0.f;
-    for (int i = threadIdx.x; i < n4; i += 256) {
+    for (int i = threadIdx.x; i < n4; i += nthr) {
         float4 v = x[i];
-        for (int s0 = 0; s0 < n_part; s0 += 4) {  // slices in ascending order, four loads in flight
-            float4 q[4];
+        for (int s0 = 0; s0 < n_part; s0 += 8) {  // slices in ascending order, eight loads in flight
+            float4 q[8];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) q[u] = s0 + u < n_part ? p0[(size_t)(s0 + u) * ps4 + i] : make_float4(0, 0, 0, 0);
+            for (int u = 0; u < 8; ++u) q[u] = s0 + u < n_part ? p0[(size_t)(s0 + u) * ps4 + i] : make_float4(0, 0, 0, 0);
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
+            for (int u = 0; u < 8; ++u) {
                 v.x += q[u].x;
                 v.y += q[u].y;
                 v.z += q[u].z;
@@ -63,12 +67,16 @@ __global__ __launch_bounds__(256) void k_rmsnorm_rows(float *__restrict__ X, con
         ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
     }
     if (!g) return;
-    ss = block_sum_256(ss, red);
+    ss = wave_sum(ss);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
+    __syncthreads();
+    ss = 0.f;
+    for (int w = 0; w < nthr / 64; ++w) ss += red[w];
     const float inv = 1.0f / sqrtf(ss / (float)h + eps);
     u32x2 *y = reinterpret_cast<u32x2 *>(Y + (size_t)blockIdx.x * h);
     u32x2 *ylo = Ylo ? reinterpret_cast<u32x2 *>(Ylo + (size_t)blockIdx.x * h) : nullptr;
     const u32x2 *g2 = reinterpret_cast<const u32x2 *>(g);
-    for (int i = threadIdx.x; i < n4; i += 256) {
+    for (int i = threadIdx.x; i < n4; i += nthr) {
         float4 v = x[i];
         u32x2 gg = g2[i];
         float a = v.x * inv * bf16_lo(gg.x), b = v.y * inv * bf16_hi(gg.x);
@@ -519,14 +527,16 @@ struct StreamGeom {
     __device__ static int swz(int row) { return BK == 32 ? (row >> 2) & 3 : ring_swz(row); }
 };
 
-template <int MT, int BK>
-__global__ __launch_bounds__(256) void k_gemm_stream(const bf16_t *__restrict__ A, const bf16_t *__restrict__ Alo,
-                                                     int lda, const bf16_t *__restrict__ B, int M, int N, int K,
-                                                     int kps, int nt, int nw, int na, float *__restrict__ part) {
+template <int MT, int BK, bool SPEC>
+__global__ __launch_bounds__(SPEC ? 512 : 256) void k_gemm_stream(const bf16_t *__restrict__ A,
+                                                                  const bf16_t *__restrict__ Alo, int lda,
+                                                                  const bf16_t *__restrict__ B, int M, int N, int K,
+                                                                  int kps, int nt, int nw, int na,
+                                                                  float *__restrict__ part) {
     using G = StreamGeom<BK>;
     constexpr int kAStage = MT * G::kATile;
-    constexpr int kALoads = MT * 64 / G::kRpi / 2;   // activation instructions per stage of waves 2, 3
-    constexpr int kWLoadsMax = 8 * 32 / G::kRpi / 2; // weight instructions per stage of waves 0, 1 at nt = 8
+    constexpr int kALoads = MT * 64 / G::kRpi / 2;   // activation instructions per stage of each activation wave
+    constexpr int kWLoadsMax = 8 * 32 / G::kRpi / 2; // weight instructions per stage of each weight wave at nt = 8
     constexpr int NL = kALoads > kWLoadsMax ? kALoads : kWLoadsMax;
     extern __shared__ __align__(16) unsigned char ring[];
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -536,12 +546,15 @@ __global__ __launch_bounds__(256) void k_gemm_stream(const bf16_t *__restrict__ 
     const int nk = (min(K, kbeg + kps) - kbeg) / BK;
     const uint32_t ring0 = (uint32_t)(uintptr_t)ring;
     const int wstage = nt * G::kWTile, a_ring = na * kAStage;
+    // SPEC: eight waves, 0-3 multiply and 4-7 load (a wave is held ~70 clocks at every direct load it issues, time
+    // the multiplying waves then do not lose); otherwise four waves do both.
+    const bool computes = !SPEC || wave < 4, loads = !SPEC || wave >= 4;
+    const int lw = SPEC ? (wave - 4) & 3 : wave;  // loader index: 0, 1 weights; 2, 3 activations
 
     // direct loads: a 1 KB instruction fills kRpi LDS rows; lane -> (row lane/kLpr, 16-byte position lane%kLpr
-    // holding global chunk position ^ swz(row)).  Waves 0-1: weights; waves 2-3: activations -- LDS row
-    // 64*t + 32*term + r is row 32*t + r of term (0 = high, 1 = low); rows past the edge re-read the last valid
-    // row and are never stored.
-    const bool w_loader = wave < 2;
+    // holding global chunk position ^ swz(row)).  Activations: LDS row 64*t + 32*term + r is row 32*t + r of term
+    // (0 = high, 1 = low); rows past the edge re-read the last valid row and are never stored.
+    const bool w_loader = lw < 2;
     const int n_loads = w_loader ? nt * 32 / G::kRpi / 2 : kALoads;
     const int depth = w_loader ? nw : na;
     const uint32_t my_ring = ring0 + (w_loader ? a_ring : 0), my_stage = w_loader ? wstage : kAStage;
@@ -549,7 +562,7 @@ __global__ __launch_bounds__(256) void k_gemm_stream(const bf16_t *__restrict__ 
     int l_off[NL];
 #pragma unroll
     for (int i = 0; i < NL; ++i) {
-        const int inst = (w_loader ? wave : wave - 2) * n_loads + i;
+        const int inst = (w_loader ? lw : lw - 2) * n_loads + i;
         const int row = inst * G::kRpi + lane / G::kLpr;
         const int piece = ((lane % G::kLpr) ^ G::swz(row)) * 8;
         if (w_loader) {
@@ -578,62 +591,68 @@ __global__ __launch_bounds__(256) void k_gemm_stream(const bf16_t *__restrict__ 
         for (int t = 0; t < MT; ++t)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[j][t][r] = 0.f;
-    const bool second = wave + 4 < nt;  // this wave's second weight tile exists
+    const bool second = wave + 4 < nt;  // this (multiplying) wave's second weight tile exists
     // swizzles of LDS rows 32*b + l32 for even / odd b (weight tile w and w + 4 have the parity of w)
     const int sw_even = G::swz(l32), sw_odd = G::swz(32 + l32), sw_w = (wave & 1) ? sw_odd : sw_even;
 
-    for (int st = 0; st < depth - 1 && st < nk; ++st) {
-        static_for<NL>([&](auto i_c) { issue_one(i_c); });
-        issued();
-    }
+    if (loads)
+        for (int st = 0; st < depth - 1 && st < nk; ++st) {
+            static_for<NL>([&](auto i_c) { issue_one(i_c); });
+            issued();
+        }
     int wslot = 0, aslot = 0;
     constexpr int KS = BK / 16, GROUPS = 2 * KS, PER = (NL + GROUPS - 1) / GROUPS;
     for (int st = 0; st < nk; ++st) {
         // stage st has landed once only the stages this wave issued after it are outstanding
-        wait_loads_rt((iss_st - (st + 1)) * n_loads);
+        if (loads) wait_loads_rt((iss_st - (st + 1)) * n_loads);
         __builtin_amdgcn_s_barrier();  // stage st complete for every wave; every wave is done with stage st-1
-        const bool more = iss_st < nk;
-        const unsigned char *wb = ring + a_ring + wslot * wstage, *ab = ring + aslot * kAStage;
-        // fragments of K step ks + 1 are read while the MFMAs of step ks run
-        bf16x8 wf[2][2], ah[2][MT], al[2][MT];
-        auto frags = [&](auto ks_c) {
-            constexpr int ks = decltype(ks_c)::value, b = ks & 1;
-            const int c = 2 * ks + kg;
-            wf[b][0] = as_bf16x8(*reinterpret_cast<const u32x4 *>(wb + (wave * 32 + l32) * G::kSeg + (c ^ sw_w) * 16));
-            if (second)
-                wf[b][1] = as_bf16x8(
-                    *reinterpret_cast<const u32x4 *>(wb + ((wave + 4) * 32 + l32) * G::kSeg + (c ^ sw_w) * 16));
+        const bool more = loads && iss_st < nk;
+        if (SPEC && more) static_for<NL>([&](auto i_c) { issue_one(i_c); });
+        if (computes) {
+            const unsigned char *wb = ring + a_ring + wslot * wstage, *ab = ring + aslot * kAStage;
+            // fragments of K step ks + 1 are read while the MFMAs of step ks run
+            bf16x8 wf[2][2], ah[2][MT], al[2][MT];
+            auto frags = [&](auto ks_c) {
+                constexpr int ks = decltype(ks_c)::value, b = ks & 1;
+                const int c = 2 * ks + kg;
+                wf[b][0] =
+                    as_bf16x8(*reinterpret_cast<const u32x4 *>(wb + (wave * 32 + l32) * G::kSeg + (c ^ sw_w) * 16));
+                if (second)
+                    wf[b][1] = as_bf16x8(
+                        *reinterpret_cast<const u32x4 *>(wb + ((wave + 4) * 32 + l32) * G::kSeg + (c ^ sw_w) * 16));
 #pragma unroll
-            for (int t = 0; t < MT; ++t) {
-                ah[b][t] =
-                    as_bf16x8(*reinterpret_cast<const u32x4 *>(ab + (t * 64 + l32) * G::kSeg + (c ^ sw_even) * 16));
-                al[b][t] = as_bf16x8(
-                    *reinterpret_cast<const u32x4 *>(ab + (t * 64 + 32 + l32) * G::kSeg + (c ^ sw_odd) * 16));
-            }
-        };
-        frags(ic<0>{});
-        static_for<KS>([&](auto ks_c) {
-            constexpr int ks = decltype(ks_c)::value, b = ks & 1;
-            if constexpr (ks + 1 < KS) frags(ic<ks + 1>{});
-            static_for<2>([&](auto j_c) {
-                constexpr int j = decltype(j_c)::value;
-                // a share of this wave's loads for the stage it fills, between the MFMA groups
-                if (more)
-                    static_for<PER>([&](auto q_c) { issue_one(ic<(2 * ks + j) * PER + decltype(q_c)::value>{}); });
-                if (j == 0 || second) {
-#pragma unroll
-                    for (int t = 0; t < MT; ++t) {
-                        acc[j][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[b][j], ah[b][t], acc[j][t], 0, 0, 0);
-                        acc[j][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[b][j], al[b][t], acc[j][t], 0, 0, 0);
-                    }
+                for (int t = 0; t < MT; ++t) {
+                    ah[b][t] = as_bf16x8(
+                        *reinterpret_cast<const u32x4 *>(ab + (t * 64 + l32) * G::kSeg + (c ^ sw_even) * 16));
+                    al[b][t] = as_bf16x8(
+                        *reinterpret_cast<const u32x4 *>(ab + (t * 64 + 32 + l32) * G::kSeg + (c ^ sw_odd) * 16));
                 }
+            };
+            frags(ic<0>{});
+            static_for<KS>([&](auto ks_c) {
+                constexpr int ks = decltype(ks_c)::value, b = ks & 1;
+                if constexpr (ks + 1 < KS) frags(ic<ks + 1>{});
+                static_for<2>([&](auto j_c) {
+                    constexpr int j = decltype(j_c)::value;
+                    // a share of this wave's loads for the stage it fills, between the MFMA groups
+                    if (!SPEC && more)
+                        static_for<PER>([&](auto q_c) { issue_one(ic<(2 * ks + j) * PER + decltype(q_c)::value>{}); });
+                    if (j == 0 || second) {
+#pragma unroll
+                        for (int t = 0; t < MT; ++t) {
+                            acc[j][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[b][j], ah[b][t], acc[j][t], 0, 0, 0);
+                            acc[j][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[b][j], al[b][t], acc[j][t], 0, 0, 0);
+                        }
+                    }
+                });
+                __builtin_amdgcn_sched_barrier(0);
             });
-            __builtin_amdgcn_sched_barrier(0);
-        });
+        }
         if (more) issued();
         if (++wslot == nw) wslot = 0;
         if (++aslot == na) aslot = 0;
     }
+    if (!computes) return;
     // C^T tile: lane = activation row (column of the MFMA result), register r = weight row 8*(r/4) + 4*kg + r%4
     float *pz = part + (size_t)blockIdx.y * M * N;
 #pragma unroll
@@ -1293,7 +1312,9 @@ struct StreamShape {
 template <int MT, int BK>
 static void stream_launch(const Model &m, const StreamShape &sh, const bf16_t *A, const bf16_t *Alo, int lda,
                           const bf16_t *B, int M, int N, int K) {
-    auto kern = k_gemm_stream<MT, BK>;
+    constexpr bool SPEC = MT <= 3;  // eight waves fit the register file up to three activation tiles (measured: a
+                                    // few percent faster there, slower with four)
+    auto kern = k_gemm_stream<MT, BK, SPEC>;
     static bool raised = false;  // more than 64 KB of dynamic LDS has to be allowed once per kernel
     if (!raised) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -1303,8 +1324,8 @@ static void stream_launch(const Model &m, const StreamShape &sh, const bf16_t *A
     using G = StreamGeom<BK>;
     const int lds = sh.na * MT * G::kATile + sh.nw * sh.nt * G::kWTile;
     dim3 grid((N + 32 * sh.nt - 1) / (32 * sh.nt), sh.splits);
-    hipLaunchKernelGGL(kern, grid, dim3(256), lds, m.stream, A, Alo, lda, B, M, N, K, sh.kps, sh.nt, sh.nw, sh.na,
-                       m.ws.qkv);
+    hipLaunchKernelGGL(kern, grid, dim3(SPEC ? 512 : 256), lds, m.stream, A, Alo, lda, B, M, N, K, sh.kps, sh.nt, sh.nw,
+                       sh.na, m.ws.qkv);
 }
 
 // One block per CU at a time, so the time is (rounds of 256 blocks) x (bytes a block loads, weights and activations
@@ -1467,7 +1488,7 @@ void launch_prefill_layers(const Model &m, int32_t pos0, int32_t n) {
     int pending = 0;  // K slices of the previous layer's down projection still to be added to x
     for (int l = 0; l < c.n_layers; ++l) {
         size_t lofs = (size_t)l * nkv * c.max_seq * d;
-        hipLaunchKernelGGL(k_rmsnorm_rows, dim3(n), dim3(256), 0, m.stream, w.x, w.qkv, pending, (size_t)n * h,
+        hipLaunchKernelGGL(k_rmsnorm_rows, dim3(n), dim3(norm_threads(n)), 0, m.stream, w.x, w.qkv, pending, (size_t)n * h,
                            m.norm_attn[l], w.xn, xn_lo, h, c.rms_eps);
         int sq = gemm<false>(m, w.xn, xn_lo, h, m.wqkv[l], n, qkv, h, nullptr, nullptr, 0);
         hipLaunchKernelGGL(k_rope_append, dim3(n, nq + 2 * nkv), dim3(d / 2), 0, m.stream, w.qkv, sq,
@@ -1475,7 +1496,7 @@ void launch_prefill_layers(const Model &m, int32_t pos0, int32_t n) {
                            d, c.max_seq);
         launch_flash(m, w.qb, m.kcache + lofs, m.vcache + lofs, w.attn, attn_lo, n, pos0);
         int so = gemm<false>(m, w.attn, attn_lo, qd, m.wo[l], n, h, qd, nullptr, nullptr, 0);
-        hipLaunchKernelGGL(k_rmsnorm_rows, dim3(n), dim3(256), 0, m.stream, w.x, w.qkv, so, (size_t)n * h,
+        hipLaunchKernelGGL(k_rmsnorm_rows, dim3(n), dim3(norm_threads(n)), 0, m.stream, w.x, w.qkv, so, (size_t)n * h,
                            m.norm_mlp[l], w.xn, xn_lo, h, c.rms_eps);
         if (n <= (h % kRingBK == 0 ? kSplitRows : kSmallRows)) {  // small chunk: gate/up as a plain split-K GEMM over
                                                                    // all 2I rows, SwiGLU in the consumer
@@ -1488,7 +1509,7 @@ void launch_prefill_layers(const Model &m, int32_t pos0, int32_t n) {
         pending = gemm<false>(m, w.act, act_lo, I, m.wdown[l], n, h, I, nullptr, nullptr, 0);
     }
     // the head needs the last row only: fold the last down projection into it
-    hipLaunchKernelGGL(k_rmsnorm_rows, dim3(1), dim3(256), 0, m.stream, w.x + (size_t)(n - 1) * h,
+    hipLaunchKernelGGL(k_rmsnorm_rows, dim3(1), dim3(norm_threads(1)), 0, m.stream, w.x + (size_t)(n - 1) * h,
                        w.qkv + (size_t)(n - 1) * h, pending, (size_t)n * h, nullptr, nullptr, nullptr, h, c.rms_eps);
 }
 
@@ -1596,7 +1617,7 @@ void launch_batch_step(const Model &m, const BatchRows &b, int n, int attn_block
     int pending = 0;
     for (int l = 0; l < c.n_layers; ++l) {
         const size_t lofs = (size_t)l * nkv * c.max_seq * d;
-        hipLaunchKernelGGL(k_rmsnorm_rows, dim3(n), dim3(256), 0, m.stream, w.x, w.qkv, pending, (size_t)n * h,
+        hipLaunchKernelGGL(k_rmsnorm_rows, dim3(n), dim3(norm_threads(n)), 0, m.stream, w.x, w.qkv, pending, (size_t)n * h,
                            m.norm_attn[l], w.xn, w.xn_lo, h, c.rms_eps);
         const int sq = gemm<false>(m, w.xn, w.xn_lo, h, m.wqkv[l], n, qkv, h, nullptr, nullptr, 0);
         hipLaunchKernelGGL(k_rope_append_rows, dim3(n, nq + 2 * nkv), dim3(d / 2), 0, m.stream, w.qkv, sq,
@@ -1606,14 +1627,14 @@ void launch_batch_step(const Model &m, const BatchRows &b, int n, int attn_block
         hipLaunchKernelGGL(k_rows_two_term, dim3(((size_t)n * qd + 255) / 256), dim3(256), 0, m.stream, b.o_rows,
                            w.attn, w.attn_lo, (size_t)n * qd);
         const int so = gemm<false>(m, w.attn, w.attn_lo, qd, m.wo[l], n, h, qd, nullptr, nullptr, 0);
-        hipLaunchKernelGGL(k_rmsnorm_rows, dim3(n), dim3(256), 0, m.stream, w.x, w.qkv, so, (size_t)n * h,
+        hipLaunchKernelGGL(k_rmsnorm_rows, dim3(n), dim3(norm_threads(n)), 0, m.stream, w.x, w.qkv, so, (size_t)n * h,
                            m.norm_mlp[l], w.xn, w.xn_lo, h, c.rms_eps);
         const int sg = gemm<false>(m, w.xn, w.xn_lo, h, m.wgu[l], n, 2 * I, h, nullptr, nullptr, 0);
         hipLaunchKernelGGL(k_swiglu_rows, dim3((I / 4 + 255) / 256, n), dim3(256), 0, m.stream, w.qkv, sg,
                            (size_t)n * 2 * I, I, w.act, w.act_lo);
         pending = gemm<false>(m, w.act, w.act_lo, I, m.wdown[l], n, h, I, nullptr, nullptr, 0);
     }
-    hipLaunchKernelGGL(k_rmsnorm_rows, dim3(n), dim3(256), 0, m.stream, w.x, w.qkv, pending, (size_t)n * h,
+    hipLaunchKernelGGL(k_rmsnorm_rows, dim3(n), dim3(norm_threads(n)), 0, m.stream, w.x, w.qkv, pending, (size_t)n * h,
                        m.final_norm, w.xn, w.xn_lo, h, c.rms_eps);
     const int sl = gemm<false>(m, w.xn, w.xn_lo, h, m.lm_head, n, c.vocab, h, nullptr, nullptr, 0);
     hipLaunchKernelGGL(k_argmax_rows, dim3(n), dim3(1024), 0, m.stream, w.qkv, sl, (size_t)n * c.vocab, c.vocab,
@@ -1648,7 +1669,7 @@ void launch_prefill_varlen(const Model &m, const BatchRows &b, const VarlenSeg *
     int pending = 0;
     for (int l = 0; l < c.n_layers; ++l) {
         const size_t lofs = (size_t)l * nkv * c.max_seq * d;
-        hipLaunchKernelGGL(k_rmsnorm_rows, dim3(R), dim3(256), 0, m.stream, w.x, w.qkv, pending, (size_t)R * h,
+        hipLaunchKernelGGL(k_rmsnorm_rows, dim3(R), dim3(norm_threads(R)), 0, m.stream, w.x, w.qkv, pending, (size_t)R * h,
                            m.norm_attn[l], w.xn, xn_lo, h, c.rms_eps);
         const int sq = gemm<false>(m, w.xn, xn_lo, h, m.wqkv[l], R, qkv, h, nullptr, nullptr, 0);
         hipLaunchKernelGGL(k_rope_append_rows, dim3(R, nq + 2 * nkv), dim3(d / 2), 0, m.stream, w.qkv, sq,
@@ -1660,7 +1681,7 @@ void launch_prefill_varlen(const Model &m, const BatchRows &b, const VarlenSeg *
                          segs[j].len, segs[j].kv0);
         }
         const int so = gemm<false>(m, w.attn, attn_lo, qd, m.wo[l], R, h, qd, nullptr, nullptr, 0);
-        hipLaunchKernelGGL(k_rmsnorm_rows, dim3(R), dim3(256), 0, m.stream, w.x, w.qkv, so, (size_t)R * h,
+        hipLaunchKernelGGL(k_rmsnorm_rows, dim3(R), dim3(norm_threads(R)), 0, m.stream, w.x, w.qkv, so, (size_t)R * h,
                            m.norm_mlp[l], w.xn, xn_lo, h, c.rms_eps);
         if (R <= (h % kRingBK == 0 ? kSplitRows : kSmallRows)) {
             const int sg = gemm<false>(m, w.xn, xn_lo, h, m.wgu[l], R, 2 * I, h, nullptr, nullptr, 0);
@@ -1674,7 +1695,7 @@ void launch_prefill_varlen(const Model &m, const BatchRows &b, const VarlenSeg *
     // head on the last row of every segment (their row indices are in b.row_next on entry)
     hipLaunchKernelGGL(k_gather_rows, dim3(n_seg), dim3(256), 0, m.stream, w.x, w.qkv, pending, (size_t)R * h,
                        b.row_next, b.o_rows, h);
-    hipLaunchKernelGGL(k_rmsnorm_rows, dim3(n_seg), dim3(256), 0, m.stream, b.o_rows, (const float *)nullptr, 0,
+    hipLaunchKernelGGL(k_rmsnorm_rows, dim3(n_seg), dim3(norm_threads(n_seg)), 0, m.stream, b.o_rows, (const float *)nullptr, 0,
                        (size_t)0, m.final_norm, w.xn, w.xn_lo, h, c.rms_eps);
     const int sl = gemm<false>(m, w.xn, w.xn_lo, h, m.lm_head, n_seg, c.vocab, h, nullptr, nullptr, 0);
     hipLaunchKernelGGL(k_argmax_rows, dim3(n_seg), dim3(1024), 0, m.stream, w.qkv, sl, (size_t)n_seg * c.vocab,
