@@ -157,7 +157,7 @@ def test_batched_loop_matches_per_sequence_oracle():
 @pytest.mark.parametrize("lens", [[5, 1, 33, 12], [70, 90, 60], [200, 150, 100]])
 def test_ragged_catch_up_pass(lens):
     """Several sequences with different cached lengths each receive a chunk of a different length in one pass
-    (skinny / two-term / long-chunk GEMM regimes by total rows); each sequence's last-position logits must match
+    (the short-chunk, 129..256-row and long-chunk GEMM regimes by total rows); each sequence's last-position logits must match
     its own oracle, and a batched decode step afterwards must see the appended keys."""
     n = len(lens)
     print_case("tiny model, ragged catch-up of", lens, "tokens onto caches of", [7 * (j + 1) for j in range(n)])
