@@ -991,8 +991,9 @@ __global__ __launch_bounds__(256) void k_flash_prefill(const bf16_t *__restrict_
 template <int NW>  // waves per block: 32 folded rows each
 __global__ __launch_bounds__(64 * NW, 2) void k_flash_long(const bf16_t *__restrict__ qb, const bf16_t *__restrict__ kc,
                                                     const bf16_t *__restrict__ vc, bf16_t *__restrict__ out,
-                                                    float *__restrict__ part_o, float *__restrict__ part_ml, int m,
-                                                    int kv0, int nq, int G, int max_seq) {
+                                                    bf16_t *__restrict__ outlo, float *__restrict__ part_o,
+                                                    float *__restrict__ part_ml, int m, int kv0, int nq, int G,
+                                                    int max_seq) {
     constexpr int D = 128, VS = kFlashKeys + 8;  // V^T rows of 144 bytes: 16-byte reads conflict-free
     __shared__ __align__(16) unsigned char Ks[2][kFlashKeys * D * 2];
     __shared__ __align__(16) bf16_t Vt[2][D * VS];
@@ -1190,9 +1191,15 @@ __global__ __launch_bounds__(64 * NW, 2) void k_flash_long(const bf16_t *__restr
 #pragma unroll
             for (int rq = 0; rq < 4; ++rq) {
                 const int dcol = tt * 32 + 8 * rq + 4 * kg;
-                u32x2 pk = {pack_bf16x2(o[tt][4 * rq + 0] * inv, o[tt][4 * rq + 1] * inv),
-                            pack_bf16x2(o[tt][4 * rq + 2] * inv, o[tt][4 * rq + 3] * inv)};
+                const float v0 = o[tt][4 * rq + 0] * inv, v1 = o[tt][4 * rq + 1] * inv;
+                const float v2 = o[tt][4 * rq + 2] * inv, v3 = o[tt][4 * rq + 3] * inv;
+                u32x2 pk = {pack_bf16x2(v0, v1), pack_bf16x2(v2, v3)};
                 *reinterpret_cast<u32x2 *>(orow + dcol) = pk;
+                if (outlo) {  // second bf16 term of the activation (short chunks)
+                    u32x2 lo = {pack_bf16x2(v0 - bf16_lo(pk.x), v1 - bf16_hi(pk.x)),
+                                pack_bf16x2(v2 - bf16_lo(pk.y), v3 - bf16_hi(pk.y))};
+                    *reinterpret_cast<u32x2 *>(outlo + (size_t)qtok * ldq + head * D + dcol) = lo;
+                }
             }
     } else {
         const size_t pr = (size_t)z * m * nq + (size_t)qtok * nq + head;
@@ -1445,7 +1452,7 @@ static void launch_flash(const Model &m, const bf16_t *qb, const bf16_t *kc, con
     const st_config &c = m.c;
     const int d = c.head_dim, nq = c.n_q_heads, nkv = c.n_kv_heads;
     const Workspace &w = m.ws;
-    const bool long_chunk = d == 128 && n >= kBigRows;
+    const bool long_chunk = d == 128;  // head_dim 128: the direct-to-LDS kernel at every chunk length
     const int G = nq / nkv, rows = n * G, rpb = long_chunk ? 32 * kLongWaves : 128, rblocks = (rows + rpb - 1) / rpb;
     const int n_tiles = (pos0 + n + kFlashKeys - 1) / kFlashKeys;
     // key splits: enough blocks for every CU, bounded by the tiles and by the partial buffer
@@ -1457,11 +1464,8 @@ static void launch_flash(const Model &m, const bf16_t *qb, const bf16_t *kc, con
     float *part_o = w.qkv, *part_ml = w.qkv + (size_t)splits * n * nq * d;
     dim3 fgrid(rblocks, nkv, splits);
     if (long_chunk)
-        hipLaunchKernelGGL(k_flash_long<kLongWaves>, fgrid, dim3(64 * kLongWaves), 0, m.stream, qb, kc, vc, attn, part_o,
-                           part_ml, n, pos0, nq, G, c.max_seq);
-    else if (d == 128)
-        hipLaunchKernelGGL(k_flash_prefill<128>, fgrid, dim3(256), 0, m.stream, qb, kc, vc, attn, attn_lo, part_o,
-                           part_ml, n, pos0, nq, G, c.max_seq);
+        hipLaunchKernelGGL(k_flash_long<kLongWaves>, fgrid, dim3(64 * kLongWaves), 0, m.stream, qb, kc, vc, attn, attn_lo,
+                           part_o, part_ml, n, pos0, nq, G, c.max_seq);
     else
         hipLaunchKernelGGL(k_flash_prefill<64>, fgrid, dim3(256), 0, m.stream, qb, kc, vc, attn, attn_lo, part_o,
                            part_ml, n, pos0, nq, G, c.max_seq);
