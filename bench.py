@@ -71,6 +71,26 @@ def batched_decode(torch, B, synth, cost, cfg, w, n_seq=16, steps=24):
             "weight_GB_s": cost.weight_bytes(cfg) / dt / 1e9, "hbm_frac": cost.weight_bytes(cfg) / dt / HBM_PEAK}
 
 
+def single_decode(torch, B, synth, cost, cfg, w, kv0=4096, steps=40):
+    """Greedy decode rate of one sequence at a context of about kv0 tokens (chained, captured steps)."""
+    cfg = dict(cfg, max_seq=kv0 + 128, max_chunk=min(cfg["max_chunk"], 4096))
+    model = B.Model(cfg, w)
+    toks = torch.from_numpy(synth.make_prompt(kv0, cfg["vocab"], 5)).cuda()
+    for lo in range(0, kv0, cfg["max_chunk"]):
+        model.prefill_device(toks[lo:lo + cfg["max_chunk"]])
+    out = torch.empty(64, dtype=torch.int32, device="cuda")
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    model.decode_greedy(0, 8, chained=True, out_dev=out)
+    e0.record()
+    model.decode_greedy(0, steps, chained=True, out_dev=out)
+    e1.record()
+    torch.cuda.synchronize()
+    sec = e0.elapsed_time(e1) / 1e3 / steps
+    model.close()
+    nbytes = cost.decode_bytes(cfg, kv0 + 8 + steps // 2)
+    return {"tok_s": 1 / sec, "GB_s": nbytes / sec / 1e9, "hbm_frac": nbytes / sec / HBM_PEAK}
+
+
 def batched_loop(B, synth, cfg_s, w_s, cfg_l, w_l, n_seq=16, n_out=210, n_seg=20, period=85):
     """The two-model loop for 16 sequences at once (7B-shaped speculative, 32B-shaped target), prompts of 128..1024
     tokens (uniform, seed 4), hand-over every 85th speculative token, segments of 20."""
@@ -127,6 +147,7 @@ def target_model_extras(torch, B, synth, cost, small, sizes=(21, 86, 256, 1024, 
     if loop:
         cfg7 = synth.model_config("qwen7b", max_seq=1400, max_chunk=4096)
         w7 = synth.make_weights(cfg7, 4, device="cuda")
+        res["decode_7b_kv4096"] = single_decode(torch, B, synth, cost, cfg7, w7)
         res["batched_decode"]["qwen7b"] = batched_decode(torch, B, synth, cost, cfg7, w7)
         res["loop_batched_7b_32b"] = batched_loop(B, synth, cfg7, w7, dict(cfg, max_seq=1400, max_chunk=4096), w)
         del w7

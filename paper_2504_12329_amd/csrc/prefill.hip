@@ -111,8 +111,9 @@ struct GemmGrid {
 };
 
 // BM x BNR block tile (BNR = rows of the weight tile), WGM x WGN waves, wave tile (BM/WGM) x (BNR/WGN).
-// Used as 128 x 128 with 2 x 2 waves (medium chunks, and the two-term form) and as 32- / 64-row tiles with
-// two waves (the shortest chunks); long chunks go to k_gemm_ring below.
+// The general-shape kernel (any K that is a multiple of 8): 128 x 128 with 2 x 2 waves, or 32- / 64-row tiles with
+// two waves for the shortest chunks.  Where K is a multiple of 64 -- every model shape of the paper -- chunks of
+// up to 256 rows go to k_gemm_stream and longer ones to k_gemm_ring below.
 template <int BM, int BNR, int WGM, int WGN, bool DUAL, bool SPLITA>
 __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm(const bf16_t *__restrict__ A, const bf16_t *__restrict__ Alo,
                                                          int lda, const bf16_t *__restrict__ B, int M, int N, int K,
@@ -976,7 +977,7 @@ __global__ __launch_bounds__(256) void k_flash_prefill(const bf16_t *__restrict_
     }
 }
 
-// Long chunks, head_dim 128: the same attention with at most 256 registers per lane, so that two waves
+// head_dim 128 (every chunk length): the same attention with at most 256 registers per lane, so that two waves
 // share a SIMD and one wave's softmax runs under another's MFMAs, and one barrier per 64-key tile:
 //   * K tiles go global -> LDS directly into two 16 KB slots whose 16-byte chunks are XOR-swizzled by the key
 //     row, so the S^T fragment reads need neither staging registers nor padding;
@@ -1272,7 +1273,7 @@ __global__ __launch_bounds__(256) void k_flash_combine(const float *__restrict__
 // ---------------------------------------------------------------------------------------
 // launcher
 // ---------------------------------------------------------------------------------------
-constexpr int kLongWaves = 4;  // waves per block of the long-chunk attention
+constexpr int kLongWaves = 4;  // waves per block of k_flash_long
 
 // Floats the split-K partial buffer (ws.qkv) holds; also sized in carve_workspace.
 static size_t partial_floats(const st_config &c) {
@@ -1452,7 +1453,7 @@ static void launch_flash(const Model &m, const bf16_t *qb, const bf16_t *kc, con
     const st_config &c = m.c;
     const int d = c.head_dim, nq = c.n_q_heads, nkv = c.n_kv_heads;
     const Workspace &w = m.ws;
-    const bool long_chunk = d == 128;  // head_dim 128: the direct-to-LDS kernel at every chunk length
+    const bool long_chunk = d == 128;  // head_dim 128: k_flash_long at every chunk length
     const int G = nq / nkv, rows = n * G, rpb = long_chunk ? 32 * kLongWaves : 128, rblocks = (rows + rpb - 1) / rpb;
     const int n_tiles = (pos0 + n + kFlashKeys - 1) / kFlashKeys;
     // key splits: enough blocks for every CU, bounded by the tiles and by the partial buffer
