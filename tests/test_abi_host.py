@@ -101,3 +101,14 @@ def test_model_create_checks_buffers(L):
     w3 = B.st_weights(0x10000, 0, 0x10000, arr, arr, arr, arr, arr, arr, arr)     # untied model without lm_head
     assert L.st_model_create(C.byref(cfg), C.byref(w3), 0x10000, kv, 0x20000, ws, None, C.byref(h)) == B.ST_EINVAL
     assert not h.value
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The path is a single-GPU one: the benchmark says so instead of starting ranks."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0
+    assert "one GPU" in r.stderr
