@@ -91,7 +91,8 @@ def single_decode(torch, B, synth, cost, cfg, w, kv0=4096, steps=40):
     return {"tok_s": 1 / sec, "GB_s": nbytes / sec / 1e9, "hbm_frac": nbytes / sec / HBM_PEAK}
 
 
-def batched_loop(B, synth, cfg_s, w_s, cfg_l, w_l, n_seq=16, n_out=210, n_seg=20, period=85):
+def batched_loop(B, synth, cfg_s, w_s, cfg_l, w_l, n_seq=16, n_out=210, n_seg=20, period=85, staggered=False,
+                 gather=0):
     """The two-model loop for 16 sequences at once (7B-shaped speculative, 32B-shaped target), prompts of 128..1024
     tokens (uniform, seed 4), hand-over every 85th speculative token, segments of 20."""
     import numpy as np
@@ -99,7 +100,10 @@ def batched_loop(B, synth, cfg_s, w_s, cfg_l, w_l, n_seq=16, n_out=210, n_seg=20
     lens = np.random.default_rng(4).integers(128, 1025, n_seq)
     prompts = [synth.make_prompt(int(lens[i]), cfg_s["vocab"], 50 + i) for i in range(n_seq)]
     t0 = time.perf_counter()
-    g = B.st_generate_batch(small, large, prompts, n_out, n_seg, cfg_s["vocab"], forced_period=period)
+    # staggered: hand-overs spread over the period, as sequences that trigger on their own content would be
+    phase = [(i * period) // n_seq for i in range(n_seq)] if staggered else None
+    g = B.st_generate_batch(small, large, prompts, n_out, n_seg, cfg_s["vocab"], forced_period=period,
+                            forced_phase=phase, gather=gather)
     dt = time.perf_counter() - t0
     st = g["stats"]
     small.close()
@@ -108,7 +112,10 @@ def batched_loop(B, synth, cfg_s, w_s, cfg_l, w_l, n_seq=16, n_out=210, n_seg=20
             "modify_ratio": st["n_large"] / max(1, st["n_out"]), "seconds": dt,
             "ms_small_decode": st["ms_small_decode"], "ms_large_decode": st["ms_large_decode"],
             "ms_small_prefill": st["ms_small_prefill"], "ms_large_prefill": st["ms_large_prefill"],
-            "schedule": "forced: every 85th speculative token hands over, target writes 20; prompt prefill included"}
+            "gather": gather,
+            "schedule": "forced: every 85th speculative token hands over" +
+                        (" (sequence i starts its count at 85*i/16)" if staggered else " (all sequences in step)") +
+                        ", target writes 20; prompt prefill included; the ms_* figures of the two models overlap"}
 
 
 def target_model_extras(torch, B, synth, cost, small, sizes=(21, 86, 256, 1024, 4096), loop=True, n_layers=None):
@@ -149,7 +156,13 @@ def target_model_extras(torch, B, synth, cost, small, sizes=(21, 86, 256, 1024, 
         w7 = synth.make_weights(cfg7, 4, device="cuda")
         res["decode_7b_kv4096"] = single_decode(torch, B, synth, cost, cfg7, w7)
         res["batched_decode"]["qwen7b"] = batched_decode(torch, B, synth, cost, cfg7, w7)
-        res["loop_batched_7b_32b"] = batched_loop(B, synth, cfg7, w7, dict(cfg, max_seq=1400, max_chunk=4096), w)
+        cfg_l = dict(cfg, max_seq=1400, max_chunk=4096)
+        res["loop_batched_7b_32b"] = batched_loop(B, synth, cfg7, w7, cfg_l, w)
+        # the same job with the hand-overs spread over the period: target passes held until all sequences wait
+        # (gather = n_seq), and started at once (gather = 0), which leaves the target with one or two rows per pass
+        res["loop_batched_7b_32b_staggered"] = batched_loop(B, synth, cfg7, w7, cfg_l, w, staggered=True, gather=16)
+        res["loop_batched_7b_32b_staggered"]["tok_s_without_gather"] = batched_loop(
+            B, synth, cfg7, w7, cfg_l, w, staggered=True, gather=0)["tok_s"]
         del w7
     # the whole two-model loop at the paper's density: hand-over every 85 speculative tokens, segments of 20
     # (both models must share one vocabulary: the target is re-wrapped over the first 151936 rows of its

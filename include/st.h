@@ -261,11 +261,17 @@ typedef struct {
  * speculative batch over the sequences that model is writing and one of the target batch over those inside a
  * segment; a sequence that triggers catches the target up with its own prefill pass and joins the target's steps
  * for n_seg tokens, then catches the speculative model up and rejoins it.  Per sequence the result is that of
- * st_generate.  forced_period > 0 replaces the rule by "every forced_period-th speculative token fires".
+ * st_generate.  forced_period > 0 replaces the rule by "every forced_period-th speculative token fires"; with
+ * forced_phase (host, n_seq entries >= 0, may be NULL = all zero) sequence i's count of speculative tokens starts
+ * at forced_phase[i], which staggers the hand-overs of the sequences.  The two models' passes of a round cover
+ * disjoint sequences and are issued side by side (the target's from a second host thread on a stream of its own).
+ * gather in [0, n_seq]: while the speculative model still has work, the target starts a pass only once at least
+ * `gather` sequences wait for it (a pass costs about the same for one sequence as for many); 0 or 1 = at once.
+ * Scheduling changes when a token is computed, never which token: every policy gives the same sequences.
  * seqs[i] (host, capacity prompt_lens[i] + n_out) receives prompt + outputs, srcs[i] (host, n_out bytes; srcs or any
  * entry may be NULL) 0 / 1 per output token.  stats sums over the sequences. */
 int st_generate_batch(st_batch *small, st_batch *large, const st_host_rule *rule, int32_t forced_period,
-                      int32_t n_seq, const int32_t *const *prompts, const int32_t *prompt_lens, int32_t n_out,
+                      const int32_t *forced_phase, int32_t gather, int32_t n_seq, const int32_t *const *prompts, const int32_t *prompt_lens, int32_t n_out,
                       int32_t n_seg, int32_t *const *seqs, uint8_t *const *srcs, st_gen_stats *stats);
 
 /* Measurement support: one chained greedy decode step (feeds the model's own last token) in which

@@ -105,8 +105,9 @@ def lib():
         L.st_batch_decode_step.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         L.st_batch_prefill_many.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                             C.c_void_p]
-        L.st_generate_batch.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
-                                        C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.POINTER(st_gen_stats)]
+        L.st_generate_batch.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_int32,
+                                        C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
+                                        C.POINTER(st_gen_stats)]
         _lib = L
     return _lib
 
@@ -392,9 +393,11 @@ class st_host_rule(C.Structure):
     _fields_ = [("kw_bitmap", C.c_void_p), ("delim_bitmap", C.c_void_p), ("window", C.c_int32), ("vocab", C.c_int32)]
 
 
-def st_generate_batch(small, large, prompts, n_out, n_seg, vocab, kw=None, delim=None, window=1, forced_period=0):
-    """The st_generate loop for len(prompts) sequences at once on two Batch objects; kw / delim are host bitmaps.
-    Returns dict(seqs, srcs, stats)."""
+def st_generate_batch(small, large, prompts, n_out, n_seg, vocab, kw=None, delim=None, window=1, forced_period=0,
+                      forced_phase=None, gather=0):
+    """The st_generate loop for len(prompts) sequences at once on two Batch objects; kw / delim are host bitmaps,
+    forced_phase the per-sequence start of the forced-period count, gather the number of waiting sequences the
+    target's passes are held for.  Returns dict(seqs, srcs, stats)."""
     n = len(prompts)
     ps = [np.ascontiguousarray(p, dtype=np.int32) for p in prompts]
     lens = np.array([p.size for p in ps], dtype=np.int32)
@@ -405,6 +408,8 @@ def st_generate_batch(small, large, prompts, n_out, n_seg, vocab, kw=None, delim
     dla = None if delim is None else np.ascontiguousarray(delim, dtype=np.uint32)
     rule = st_host_rule(None if kwa is None else kwa.ctypes.data, None if dla is None else dla.ctypes.data, window, vocab)
     stats = st_gen_stats()
-    _check(lib().st_generate_batch(small._h, large._h, C.byref(rule) if kwa is not None else None, forced_period, n,
+    phase = None if forced_phase is None else np.ascontiguousarray(forced_phase, dtype=np.int32)
+    _check(lib().st_generate_batch(small._h, large._h, C.byref(rule) if kwa is not None else None, forced_period,
+                                   None if phase is None else _np_ptr(phase), gather, n,
                                    arr(ps), _np_ptr(lens), n_out, n_seg, arr(seqs), arr(srcs), C.byref(stats)))
     return dict(seqs=seqs, srcs=srcs, stats={k: getattr(stats, k) for k, _ in st_gen_stats._fields_})

@@ -6,6 +6,8 @@
 #include <cstdlib>
 #include <cstring>
 #include <new>
+#include <string>
+#include <thread>
 
 #include <hip/hip_ext.h>
 
@@ -914,7 +916,8 @@ int st_batch_prefill_many(st_batch *h, int32_t n, const int32_t *seqs, const int
     return ST_OK;
 }
 
-int st_generate_batch(st_batch *hs, st_batch *hl, const st_host_rule *rule, int32_t forced_period, int32_t n_seq,
+int st_generate_batch(st_batch *hs, st_batch *hl, const st_host_rule *rule, int32_t forced_period,
+                      const int32_t *forced_phase, int32_t gather, int32_t n_seq,
                       const int32_t *const *prompts, const int32_t *prompt_lens, int32_t n_out, int32_t n_seg,
                       int32_t *const *seqs, uint8_t *const *srcs, st_gen_stats *stats) {
     using clk = std::chrono::steady_clock;
@@ -930,6 +933,7 @@ int st_generate_batch(st_batch *hs, st_batch *hl, const st_host_rule *rule, int3
     }
     if (n_seq < 1 || n_seq > S->n_seq || n_seq > L->n_seq) return fail(ST_ERANGE, "n_seq %d exceeds a batch", n_seq);
     if (n_out < 0 || n_seg <= 0) return fail(ST_ERANGE, "n_seg must be positive and n_out non-negative");
+    if (gather < 0 || gather > n_seq) return fail(ST_ERANGE, "gather must be in [0, n_seq]");
     for (int32_t i = 0; i < n_seq; ++i) {
         if (!prompts[i] || !seqs[i] || prompt_lens[i] <= 0) return fail(ST_EINVAL, "bad prompt or output buffer of sequence %d", i);
         if (S->kv_len[i] != 0 || L->kv_len[i] != 0) return fail(ST_EINVAL, "sequence %d does not start with empty caches", i);
@@ -939,9 +943,16 @@ int st_generate_batch(st_batch *hs, st_batch *hl, const st_host_rule *rule, int3
     auto in_class = [&](const uint32_t *bm, int32_t t) {
         return bm && t >= 0 && t < rule->vocab && ((bm[t >> 5] >> (t & 31)) & 1u);
     };
-    enum { WRITES_SMALL, WRITES_LARGE, DONE };
-    std::vector<int> who(n_seq, WRITES_SMALL);
+    // Per sequence: *_READY = the model's prediction (pend) is there and can be emitted; *_FEED = the emitted token
+    // waits to be fed to that model by a decode step; *_CATCH = the model has to catch up on tokens it has not seen.
+    enum { S_READY, S_FEED, S_CATCH, L_READY, L_FEED, L_CATCH, DONE };
+    std::vector<int> who(n_seq, S_READY);
     std::vector<int32_t> T(n_seq), pend(n_seq), rem(n_seq, 0), small_count(n_seq, 0);
+    if (forced_phase)
+        for (int32_t i = 0; i < n_seq; ++i) {
+            if (forced_phase[i] < 0) return fail(ST_EINVAL, "forced_phase[%d] is negative", i);
+            small_count[i] = forced_phase[i];
+        }
     st_gen_stats st = {};
     // catches the listed sequences of one batch up on every token they have not seen, as few ragged passes as
     // max_chunk allows (a span longer than max_chunk goes through the chunked single-sequence pass); pend[] gets
@@ -988,69 +999,114 @@ int st_generate_batch(st_batch *hs, st_batch *hl, const st_host_rule *rule, int3
     }
     if (int rc = catch_up(hl, L, list, &st.ms_large_prefill)) return rc;   // its predictions are not used
     if (int rc = catch_up(hs, S, list, &st.ms_small_prefill)) return rc;
-    std::vector<int32_t> rows, toks, next;
-    auto step = [&](st_batch *b, double *ms) -> int {
+    // One batched decode step of `b` for the listed rows; pend[] gets each row's next token.
+    auto step = [&](st_batch *b, const std::vector<int32_t> &rows, const std::vector<int32_t> &toks, double *ms) -> int {
         if (rows.empty()) return ST_OK;
-        next.resize(rows.size());
+        std::vector<int32_t> next(rows.size());
         auto a = clk::now();
         if (int rc = st_batch_decode_step(b, (int32_t)rows.size(), rows.data(), toks.data(), nullptr, next.data())) return rc;
         *ms += ms_since(a);
         for (size_t r = 0; r < rows.size(); ++r) pend[rows[r]] = next[r];
         return ST_OK;
     };
+    // The two models work on disjoint sets of sequences in every round, so their passes run side by side: the
+    // target's on a stream of its own (default priority) from a second host thread, the speculative model's on the
+    // calling thread.  Every call below ends with its stream idle, so the streams only have to be ordered once, here.
+    hipStream_t caller_stream = L->base.stream, side_stream = nullptr;
+    int device = 0;
+    ST_HIP(hipGetDevice(&device));
+    ST_HIP(hipStreamSynchronize(caller_stream));
+    ST_HIP(hipStreamCreateWithFlags(&side_stream, hipStreamNonBlocking));
+    L->base.stream = side_stream;
+    struct Restore {
+        Batch *L;
+        hipStream_t caller, side;
+        ~Restore() {
+            (void)hipStreamSynchronize(side);
+            L->base.stream = caller;
+            (void)hipStreamDestroy(side);
+        }
+    } restore{L, caller_stream, side_stream};
+
+    std::vector<int32_t> rows_s, toks_s, list_s, rows_l, toks_l, list_l, fed(n_seq, 0);
     while (true) {
-        bool any = false;
-        // sequences the speculative model is writing: emit, test the trigger, hand over or queue the next step
-        rows.clear(), toks.clear(), list.clear();
+        // emit what is ready and decide what each sequence needs next
         for (int32_t i = 0; i < n_seq; ++i) {
-            if (who[i] != WRITES_SMALL) continue;
-            any = true;
-            const int32_t P = prompt_lens[i], tok = pend[i];
-            seqs[i][T[i]++] = tok;
-            if (srcs && srcs[i]) srcs[i][T[i] - 1 - P] = 0;
-            ++small_count[i];
-            if (T[i] - P == n_out) {
-                who[i] = DONE;
-                continue;
-            }
-            bool fire;
-            if (forced_period > 0)
-                fire = small_count[i] % forced_period == 0;
-            else
-                fire = in_class(rule->kw_bitmap, tok) &&
-                       (rule->window == 1 || (T[i] >= 2 && in_class(rule->delim_bitmap, seqs[i][T[i] - 2])));
-            if (fire) {
-                list.push_back(i);
-                who[i] = WRITES_LARGE;
-                rem[i] = n_seg;
-                ++st.n_handoffs;
-            } else {
-                rows.push_back(i), toks.push_back(tok);
+            const int32_t P = prompt_lens[i];
+            if (who[i] == S_READY) {
+                const int32_t tok = pend[i];
+                seqs[i][T[i]++] = tok;
+                if (srcs && srcs[i]) srcs[i][T[i] - 1 - P] = 0;
+                ++small_count[i];
+                if (T[i] - P == n_out) {
+                    who[i] = DONE;
+                    continue;
+                }
+                bool fire;
+                if (forced_period > 0)
+                    fire = small_count[i] % forced_period == 0;
+                else
+                    fire = in_class(rule->kw_bitmap, tok) &&
+                           (rule->window == 1 || (T[i] >= 2 && in_class(rule->delim_bitmap, seqs[i][T[i] - 2])));
+                if (fire) {
+                    who[i] = L_CATCH;  // the target reads everything it has not seen, the trigger token included
+                    rem[i] = n_seg;
+                    ++st.n_handoffs;
+                } else {
+                    who[i] = S_FEED;
+                    fed[i] = tok;
+                }
+            } else if (who[i] == L_READY) {
+                const int32_t tok = pend[i];
+                seqs[i][T[i]++] = tok;
+                if (srcs && srcs[i]) srcs[i][T[i] - 1 - P] = 1;
+                ++st.n_large;
+                if (T[i] - P == n_out) {
+                    who[i] = DONE;
+                } else if (--rem[i] == 0) {
+                    who[i] = S_CATCH;  // the segment's last token is not fed to the target
+                } else {
+                    who[i] = L_FEED;
+                    fed[i] = tok;
+                }
             }
         }
-        if (int rc = step(hs, &st.ms_small_decode)) return rc;
-        if (int rc = catch_up(hl, L, list, &st.ms_large_prefill)) return rc;  // the hand-overs of this round, together
-        // sequences inside a target segment: emit; the segment's last token is not fed to the target
-        rows.clear(), toks.clear(), list.clear();
+        rows_s.clear(), toks_s.clear(), list_s.clear(), rows_l.clear(), toks_l.clear(), list_l.clear();
         for (int32_t i = 0; i < n_seq; ++i) {
-            if (who[i] != WRITES_LARGE) continue;
-            any = true;
-            const int32_t P = prompt_lens[i], tok = pend[i];
-            seqs[i][T[i]++] = tok;
-            if (srcs && srcs[i]) srcs[i][T[i] - 1 - P] = 1;
-            ++st.n_large;
-            if (T[i] - P == n_out) {
-                who[i] = DONE;
-            } else if (--rem[i] == 0) {
-                list.push_back(i);
-                who[i] = WRITES_SMALL;
-            } else {
-                rows.push_back(i), toks.push_back(tok);
-            }
+            if (who[i] == S_FEED) rows_s.push_back(i), toks_s.push_back(fed[i]);
+            if (who[i] == S_CATCH) list_s.push_back(i);
+            if (who[i] == L_FEED) rows_l.push_back(i), toks_l.push_back(fed[i]);
+            if (who[i] == L_CATCH) list_l.push_back(i);
         }
-        if (int rc = step(hl, &st.ms_large_decode)) return rc;
-        if (int rc = catch_up(hs, S, list, &st.ms_small_prefill)) return rc;  // the segments that ended, together
-        if (!any) break;
+        const bool small_work = !rows_s.empty() || !list_s.empty();
+        bool large_work = !rows_l.empty() || !list_l.empty();
+        if (!small_work && !large_work) break;
+        // A pass of the target costs about the same for one sequence as for sixteen (it streams the weights
+        // either way), so sequences may be held until `gather` of them wait for it -- unless nothing else can run.
+        if (large_work && small_work && (int32_t)(rows_l.size() + list_l.size()) < gather) large_work = false;
+        // target: the waiting hand-overs together, then its decode step; speculative model: its decode step, then
+        // the segments that ended, together.  (Each model's own passes share its workspace and stay in order.)
+        int rc_l = ST_OK;
+        std::string err_l;
+        std::thread side;
+        if (large_work)
+            side = std::thread([&]() {
+                (void)hipSetDevice(device);
+                rc_l = step(hl, rows_l, toks_l, &st.ms_large_decode);
+                if (rc_l == ST_OK) rc_l = catch_up(hl, L, list_l, &st.ms_large_prefill);
+                if (rc_l != ST_OK) err_l = st_last_error();
+            });
+        int rc_s = step(hs, rows_s, toks_s, &st.ms_small_decode);
+        if (rc_s == ST_OK) rc_s = catch_up(hs, S, list_s, &st.ms_small_prefill);
+        if (large_work) side.join();
+        if (rc_s != ST_OK) return rc_s;
+        if (rc_l != ST_OK) return fail(rc_l, "%s", err_l.c_str());
+        for (int32_t i : rows_s) who[i] = S_READY;
+        for (int32_t i : list_s) who[i] = S_READY;
+        if (large_work) {
+            for (int32_t i : rows_l) who[i] = L_READY;
+            for (int32_t i : list_l) who[i] = L_READY;
+        }
     }
     for (int32_t i = 0; i < n_seq; ++i) st.n_out += T[i] - prompt_lens[i];
     if (stats) *stats = st;

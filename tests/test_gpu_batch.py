@@ -154,6 +154,50 @@ def test_batched_loop_matches_per_sequence_oracle():
     bl.close()
 
 
+FORCED_PROMPTS = [(305, 23, 0), (355, 13, 2), (358, 34, 3), (408, 24, 5)]   # prompt seed, length, start of the count
+
+
+def test_batched_loop_with_staggered_forced_period():
+    """Forced hand-overs every 6th speculative token, each sequence starting its count elsewhere: the two models
+    then work on different sequences at the same time; every sequence still reproduces its own oracle trace,
+    whatever the gather threshold (scheduling changes when a token is computed, never which)."""
+    from oracle import schedule as S
+    n = len(FORCED_PROMPTS)
+    cfg, bs, o_small = _setup("tiny_small", n, 1, max_seq=128)
+    _, bl, o_large = _setup("tiny_large", n, 2, max_seq=128)
+    V = cfg["vocab"]
+    prompts, traces = [], []
+    for i, (seed, plen, phase) in enumerate(FORCED_PROMPTS):
+        prompt = synth.make_prompt(plen, V, seed)
+        a, b = S.GreedyModel(o_small[i], keep_logits=True), S.GreedyModel(o_large[i], keep_logits=True)
+        count = {"n": phase}
+
+        def fire(seq, p, count=count):
+            count["n"] += 1
+            return count["n"] % 6 == 0
+        tr = S.speculative_thinking(a, b, prompt, 40, 4, fire)
+        margin = min(_margin(lg) for g in (a, b) for _, lg in g.logits)
+        assert margin >= MIN_MARGIN, f"sequence {i}: oracle run has a near-tie ({margin:.4f}); pick another seed"
+        prompts.append(prompt)
+        traces.append(tr)
+    with pytest.raises(B.StError, match="forced_phase"):     # rejected before anything is launched
+        B.st_generate_batch(bs, bl, prompts, 40, 4, V, forced_period=6, forced_phase=[0, -1, 0, 0])
+    phases = [p for _, _, p in FORCED_PROMPTS]
+    for gather in (0, 3, n):        # at once / held until three wait / held until nothing else can run
+        for i in range(n):
+            bs.truncate(i, 0)
+            bl.truncate(i, 0)
+        out = B.st_generate_batch(bs, bl, prompts, 40, 4, V, forced_period=6, forced_phase=phases, gather=gather)
+        for i, tr in enumerate(traces):
+            assert out["seqs"][i].tolist() == tr.seq, (gather, i)
+            assert out["srcs"][i][:40].tolist() == tr.src, (gather, i)
+        assert out["stats"]["n_handoffs"] == sum(len(tr.triggers) for tr in traces)
+    with pytest.raises(B.StError, match="gather"):
+        B.st_generate_batch(bs, bl, prompts, 40, 4, V, forced_period=6, gather=n + 1)
+    bs.close()
+    bl.close()
+
+
 @pytest.mark.parametrize("lens", [[5, 1, 33, 12], [70, 90, 60], [200, 150, 100]])
 def test_ragged_catch_up_pass(lens):
     """Several sequences with different cached lengths each receive a chunk of a different length in one pass
