@@ -85,6 +85,7 @@ void carve_workspace(const st_config &c, char *base, Workspace *ws) {
     ws->xn_lo = (bf16_t *)take(sizeof(bf16_t) * sr * h);
     ws->attn_lo = (bf16_t *)take(sizeof(bf16_t) * sr * qd);
     ws->act_lo = (bf16_t *)take(sizeof(bf16_t) * sr * I);
+    ws->qb_lo = (bf16_t *)take(sizeof(bf16_t) * sr * qd);
     ws->q1 = (float *)take(sizeof(float) * qd);
     ws->o1 = (float *)take(sizeof(float) * qd);
     ws->a1 = (float *)take(sizeof(float) * I);

@@ -686,8 +686,8 @@ __global__ __launch_bounds__(SPEC ? 512 : 256) void k_gemm_stream(const bf16_t *
 // ---------------------------------------------------------------------------------------
 __global__ void k_rope_append(const float *__restrict__ part, int n_part, size_t part_stride,
                               const bf16_t *__restrict__ bias, const float2 *__restrict__ rope,
-                              bf16_t *__restrict__ qb, bf16_t *__restrict__ kc, bf16_t *__restrict__ vc, int pos0,
-                              int nq, int nkv, int d, int max_seq) {
+                              bf16_t *__restrict__ qb, bf16_t *__restrict__ qb_lo, bf16_t *__restrict__ kc,
+                              bf16_t *__restrict__ vc, int pos0, int nq, int nkv, int d, int max_seq) {
     const int row = blockIdx.x, head = blockIdx.y, i = threadIdx.x, half = d >> 1;
     const int pos = pos0 + row;
     const size_t off = (size_t)row * (nq + 2 * nkv) * d + head * d;
@@ -715,8 +715,14 @@ __global__ void k_rope_append(const float *__restrict__ part, int n_part, size_t
         dst = kc + ((size_t)(head - nq) * max_seq + pos) * d;
     else
         dst = vc + ((size_t)(head - nq - nkv) * max_seq + pos) * d;
-    dst[i] = f32_to_bf16(lo);
-    dst[i + half] = f32_to_bf16(hi);
+    const bf16_t blo = f32_to_bf16(lo), bhi = f32_to_bf16(hi);
+    dst[i] = blo;
+    dst[i + half] = bhi;
+    if (head < nq && qb_lo) {  // short chunks: the query keeps 16 mantissa bits as a second bf16 term
+        bf16_t *dl = qb_lo + (size_t)row * nq * d + head * d;
+        dl[i] = f32_to_bf16(lo - bf16_to_f32(blo));
+        dl[i + half] = f32_to_bf16(hi - bf16_to_f32(bhi));
+    }
 }
 
 // a[row][i] = silu(gate) * up from the K slices of the gate/up projection of a short chunk
@@ -989,8 +995,9 @@ __global__ __launch_bounds__(256) void k_flash_prefill(const bf16_t *__restrict_
 //     registers rare; tiles wholly below the diagonal skip the causal compare.
 // Interface and key-split partial results are those of k_flash_prefill.
 // ---------------------------------------------------------------------------------------
-template <int NW>  // waves per block: 32 folded rows each
-__global__ __launch_bounds__(64 * NW, 2) void k_flash_long(const bf16_t *__restrict__ qb, const bf16_t *__restrict__ kc,
+template <int NW, bool TWO>  // NW waves per block, 32 folded rows each; TWO: queries arrive as two bf16 terms
+__global__ __launch_bounds__(64 * NW, TWO ? 1 : 2) void k_flash_long(const bf16_t *__restrict__ qb,
+                                                    const bf16_t *__restrict__ qb_lo, const bf16_t *__restrict__ kc,
                                                     const bf16_t *__restrict__ vc, bf16_t *__restrict__ out,
                                                     bf16_t *__restrict__ outlo, float *__restrict__ part_o,
                                                     float *__restrict__ part_ml, int m, int kv0, int nq, int G,
@@ -1019,10 +1026,13 @@ __global__ __launch_bounds__(64 * NW, 2) void k_flash_long(const bf16_t *__restr
     const int t_begin = z * tps, t_end = min(n_tiles, t_begin + tps);
     const float scale = 1.4426950408889634f / sqrtf((float)D);
 
-    bf16x8 qf[D / 16];
+    bf16x8 qf[D / 16], ql[TWO ? D / 16 : 1];
 #pragma unroll
-    for (int s = 0; s < D / 16; ++s)
+    for (int s = 0; s < D / 16; ++s) {
         qf[s] = as_bf16x8(*reinterpret_cast<const u32x4 *>(qb + (size_t)qtok * ldq + head * D + 16 * s + 8 * kg));
+        if constexpr (TWO)
+            ql[s] = as_bf16x8(*reinterpret_cast<const u32x4 *>(qb_lo + (size_t)qtok * ldq + head * D + 16 * s + 8 * kg));
+    }
 
     f32x16 o[D / 32];
 #pragma unroll
@@ -1097,6 +1107,7 @@ __global__ __launch_bounds__(64 * NW, 2) void k_flash_long(const bf16_t *__restr
                 bf16x8 kf = as_bf16x8(
                     *reinterpret_cast<const u32x4 *>(kt + (u * 32 + krow) * 256 + (((2 * s + kg) ^ k_swz) * 16)));
                 sacc[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[s], sacc[u], 0, 0, 0);
+                if constexpr (TWO) sacc[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, ql[s], sacc[u], 0, 0, 0);
             }
         }
     };
@@ -1448,8 +1459,8 @@ static int gemm(const Model &m, const bf16_t *A, const bf16_t *Alo, int lda, con
 }
 
 // Causal attention of n query rows at positions pos0 .. pos0+n-1 over one sequence's cache (kc / vc of one layer).
-static void launch_flash(const Model &m, const bf16_t *qb, const bf16_t *kc, const bf16_t *vc, bf16_t *attn,
-                         bf16_t *attn_lo, int n, int pos0) {
+static void launch_flash(const Model &m, const bf16_t *qb, const bf16_t *qb_lo, const bf16_t *kc, const bf16_t *vc,
+                         bf16_t *attn, bf16_t *attn_lo, int n, int pos0) {
     const st_config &c = m.c;
     const int d = c.head_dim, nq = c.n_q_heads, nkv = c.n_kv_heads;
     const Workspace &w = m.ws;
@@ -1464,9 +1475,12 @@ static void launch_flash(const Model &m, const bf16_t *qb, const bf16_t *kc, con
     while (splits > 1 && (size_t)splits * n * nq * (d + 2) > cap) --splits;
     float *part_o = w.qkv, *part_ml = w.qkv + (size_t)splits * n * nq * d;
     dim3 fgrid(rblocks, nkv, splits);
-    if (long_chunk)
-        hipLaunchKernelGGL(k_flash_long<kLongWaves>, fgrid, dim3(64 * kLongWaves), 0, m.stream, qb, kc, vc, attn, attn_lo,
-                           part_o, part_ml, n, pos0, nq, G, c.max_seq);
+    if (long_chunk && qb_lo)
+        hipLaunchKernelGGL((k_flash_long<kLongWaves, true>), fgrid, dim3(64 * kLongWaves), 0, m.stream, qb, qb_lo, kc, vc,
+                           attn, attn_lo, part_o, part_ml, n, pos0, nq, G, c.max_seq);
+    else if (long_chunk)
+        hipLaunchKernelGGL((k_flash_long<kLongWaves, false>), fgrid, dim3(64 * kLongWaves), 0, m.stream, qb, qb_lo, kc, vc,
+                           attn, attn_lo, part_o, part_ml, n, pos0, nq, G, c.max_seq);
     else
         hipLaunchKernelGGL(k_flash_prefill<64>, fgrid, dim3(256), 0, m.stream, qb, kc, vc, attn, attn_lo, part_o,
                            part_ml, n, pos0, nq, G, c.max_seq);
@@ -1488,6 +1502,7 @@ void launch_prefill_layers(const Model &m, int32_t pos0, int32_t n) {
     const Workspace &w = m.ws;
     const bool two = n <= kSplitRows;  // short chunk: GEMM inputs carried as two bf16 terms
     bf16_t *xn_lo = two ? w.xn_lo : nullptr, *attn_lo = two ? w.attn_lo : nullptr, *act_lo = two ? w.act_lo : nullptr;
+    bf16_t *qb_lo = two && d == 128 ? w.qb_lo : nullptr;  // second term of the rotated queries (k_flash_long)
     hipLaunchKernelGGL(k_embed_rows, dim3(n), dim3(256), 0, m.stream, m.embed, w.tokens, w.x, h, c.vocab);
     hipLaunchKernelGGL(k_note_fed, dim3(1), dim3(1), 0, m.stream, w.state, w.tokens, n - 1, c.vocab);
     int pending = 0;  // K slices of the previous layer's down projection still to be added to x
@@ -1497,9 +1512,9 @@ void launch_prefill_layers(const Model &m, int32_t pos0, int32_t n) {
                            m.norm_attn[l], w.xn, xn_lo, h, c.rms_eps);
         int sq = gemm<false>(m, w.xn, xn_lo, h, m.wqkv[l], n, qkv, h, nullptr, nullptr, 0);
         hipLaunchKernelGGL(k_rope_append, dim3(n, nq + 2 * nkv), dim3(d / 2), 0, m.stream, w.qkv, sq,
-                           (size_t)n * qkv, m.bqkv[l], w.rope, w.qb, m.kcache + lofs, m.vcache + lofs, pos0, nq, nkv,
+                           (size_t)n * qkv, m.bqkv[l], w.rope, w.qb, qb_lo, m.kcache + lofs, m.vcache + lofs, pos0, nq, nkv,
                            d, c.max_seq);
-        launch_flash(m, w.qb, m.kcache + lofs, m.vcache + lofs, w.attn, attn_lo, n, pos0);
+        launch_flash(m, w.qb, qb_lo, m.kcache + lofs, m.vcache + lofs, w.attn, attn_lo, n, pos0);
         int so = gemm<false>(m, w.attn, attn_lo, qd, m.wo[l], n, h, qd, nullptr, nullptr, 0);
         hipLaunchKernelGGL(k_rmsnorm_rows, dim3(n), dim3(norm_threads(n)), 0, m.stream, w.x, w.qkv, so, (size_t)n * h,
                            m.norm_mlp[l], w.xn, xn_lo, h, c.rms_eps);
@@ -1529,7 +1544,8 @@ void launch_prefill_layers(const Model &m, int32_t pos0, int32_t n) {
 // single step) or, with qb != nullptr, written as bf16 (catch-up rows).
 __global__ void k_rope_append_rows(const float *__restrict__ part, int n_part, size_t part_stride,
                                    const bf16_t *__restrict__ bias, const float2 *__restrict__ rope,
-                                   float *__restrict__ q_rows, bf16_t *__restrict__ qb, bf16_t *__restrict__ kc,
+                                   float *__restrict__ q_rows, bf16_t *__restrict__ qb, bf16_t *__restrict__ qb_lo,
+                                   bf16_t *__restrict__ kc,
                                    bf16_t *__restrict__ vc, const int32_t *__restrict__ row_pos,
                                    const int32_t *__restrict__ row_seq,
                                    size_t seq_stride, int nq, int nkv, int d, int max_seq) {
@@ -1557,8 +1573,14 @@ __global__ void k_rope_append_rows(const float *__restrict__ part, int n_part, s
     if (head < nq) {
         if (qb) {  // catch-up rows: bf16 queries for the flash kernels
             bf16_t *dq = qb + (size_t)row * nq * d + head * d;
-            dq[i] = f32_to_bf16(lo);
-            dq[i + half] = f32_to_bf16(hi);
+            const bf16_t blo = f32_to_bf16(lo), bhi = f32_to_bf16(hi);
+            dq[i] = blo;
+            dq[i + half] = bhi;
+            if (qb_lo) {
+                bf16_t *dl = qb_lo + (size_t)row * nq * d + head * d;
+                dl[i] = f32_to_bf16(lo - bf16_to_f32(blo));
+                dl[i + half] = f32_to_bf16(hi - bf16_to_f32(bhi));
+            }
         } else {
             float *dst = q_rows + (size_t)row * nq * d + head * d;
             dst[i] = lo;
@@ -1626,8 +1648,8 @@ void launch_batch_step(const Model &m, const BatchRows &b, int n, int attn_block
                            m.norm_attn[l], w.xn, w.xn_lo, h, c.rms_eps);
         const int sq = gemm<false>(m, w.xn, w.xn_lo, h, m.wqkv[l], n, qkv, h, nullptr, nullptr, 0);
         hipLaunchKernelGGL(k_rope_append_rows, dim3(n, nq + 2 * nkv), dim3(d / 2), 0, m.stream, w.qkv, sq,
-                           (size_t)n * qkv, m.bqkv[l], w.rope, b.q_rows, (bf16_t *)nullptr, m.kcache + lofs,
-                           m.vcache + lofs, b.row_pos, b.row_seq, b.seq_stride, nq, nkv, d, c.max_seq);
+                           (size_t)n * qkv, m.bqkv[l], w.rope, b.q_rows, (bf16_t *)nullptr, (bf16_t *)nullptr,
+                           m.kcache + lofs, m.vcache + lofs, b.row_pos, b.row_seq, b.seq_stride, nq, nkv, d, c.max_seq);
         launch_attn_rows(m, l, m.stream, attn_blocks, rows, n, b.q_rows, b.part_ml, b.part_acc, b.o_rows);
         hipLaunchKernelGGL(k_rows_two_term, dim3(((size_t)n * qd + 255) / 256), dim3(256), 0, m.stream, b.o_rows,
                            w.attn, w.attn_lo, (size_t)n * qd);
@@ -1670,6 +1692,7 @@ void launch_prefill_varlen(const Model &m, const BatchRows &b, const VarlenSeg *
     const Workspace &w = m.ws;
     const bool two = R <= kSplitRows;
     bf16_t *xn_lo = two ? w.xn_lo : nullptr, *attn_lo = two ? w.attn_lo : nullptr, *act_lo = two ? w.act_lo : nullptr;
+    bf16_t *qb_lo = two && d == 128 ? w.qb_lo : nullptr;  // second term of the rotated queries (k_flash_long)
     hipLaunchKernelGGL(k_embed_rows, dim3(R), dim3(256), 0, m.stream, m.embed, b.row_tok, w.x, h, c.vocab);
     int pending = 0;
     for (int l = 0; l < c.n_layers; ++l) {
@@ -1678,11 +1701,12 @@ void launch_prefill_varlen(const Model &m, const BatchRows &b, const VarlenSeg *
                            m.norm_attn[l], w.xn, xn_lo, h, c.rms_eps);
         const int sq = gemm<false>(m, w.xn, xn_lo, h, m.wqkv[l], R, qkv, h, nullptr, nullptr, 0);
         hipLaunchKernelGGL(k_rope_append_rows, dim3(R, nq + 2 * nkv), dim3(d / 2), 0, m.stream, w.qkv, sq,
-                           (size_t)R * qkv, m.bqkv[l], w.rope, (float *)nullptr, w.qb, m.kcache + lofs,
+                           (size_t)R * qkv, m.bqkv[l], w.rope, (float *)nullptr, w.qb, qb_lo, m.kcache + lofs,
                            m.vcache + lofs, b.row_pos, b.row_seq, b.seq_stride, nq, nkv, d, c.max_seq);
         for (int j = 0; j < n_seg; ++j) {
             const size_t cache = (size_t)segs[j].seq * b.seq_stride + lofs, q0 = (size_t)segs[j].row0 * qd;
-            launch_flash(m, w.qb + q0, m.kcache + cache, m.vcache + cache, w.attn + q0, attn_lo ? attn_lo + q0 : nullptr,
+            launch_flash(m, w.qb + q0, qb_lo ? qb_lo + q0 : nullptr, m.kcache + cache, m.vcache + cache, w.attn + q0,
+                         attn_lo ? attn_lo + q0 : nullptr,
                          segs[j].len, segs[j].kv0);
         }
         const int so = gemm<false>(m, w.attn, attn_lo, qd, m.wo[l], R, h, qd, nullptr, nullptr, 0);

@@ -27,6 +27,7 @@ struct Workspace {
     bf16_t *attn;          // [max_chunk][n_q*d] attention output (GEMM input)
     bf16_t *act;           // [max_chunk][intermediate] SwiGLU output
     bf16_t *xn_lo, *attn_lo, *act_lo;  // [256][...] second bf16 terms of the three above (short chunks)
+    bf16_t *qb_lo;         // [256][n_q*d] second bf16 term of the rotated queries (short chunks)
     float *q1;             // [n_q*d] decode query
     float *o1;             // [n_q*d] decode attention output
     float *a1;             // [intermediate] decode SwiGLU output

@@ -154,8 +154,8 @@ def test_kv_capacity_edge_and_long_decode_buckets():
 def test_qwen32b_full_depth_paths_agree():
     """All 64 layers of the 32B shape (65 GB of weights, beyond the oracle's reach): the same position computed
     through the decode kernels, through a one-row catch-up and through a 21-row catch-up (three kernel sets with
-    their own bf16 roundings).  Each path is held to LOGIT_TOL against the exact result, so two paths may differ
-    by at most twice that; the greedy continuation must agree where the logit gap allows."""
+    their own bf16 roundings) must agree to the tolerance each is held to against the oracle, and so must the
+    greedy continuation where the logit gap allows."""
     print_case("32B shape, 64 layers: 200 cached tokens, position 200 through decode / 1-row / 21-row passes")
     cfg = synth.model_config("qwen32b", max_seq=256, max_chunk=128)
     w = synth.make_weights(cfg, 2, device="cuda")
@@ -170,7 +170,7 @@ def test_qwen32b_full_depth_paths_agree():
     c, tok_c = g.prefill(toks[180:201])                    # 21-row catch-up re-deriving the last 20 cache rows
     print_case("decode vs 1-row", rel_err(b, a), "decode vs 21-row", rel_err(c, a), "1-row vs 21-row", rel_err(c, b),
                "margin", _margin(a))
-    assert max(rel_err(b, a), rel_err(c, a), rel_err(c, b)) <= 2 * LOGIT_TOL
-    if _margin(a) >= 2 * MIN_MARGIN:
+    assert max(rel_err(b, a), rel_err(c, a), rel_err(c, b)) <= LOGIT_TOL
+    if _margin(a) >= MIN_MARGIN:
         assert tok_a == tok_b == tok_c
     g.close()
