@@ -248,7 +248,7 @@ def main():
 
     def job():
         model.truncate(0)
-        model.prefill_device(prompt_dev)
+        model.prefill_device(prompt_dev, two_term=True)   # 512 rows as two passes with two-term GEMM inputs
         model.decode_greedy(0, n_dec, chained=True, out_dev=out_dev)
         B._check(B.lib().st_trigger_scan(ctypes.byref(rule.c), out_dev.data_ptr(), 0, n_dec, hits_dev[1:].data_ptr(),
                                          64, hits_dev.data_ptr(), None, stream, B.ST_OUT_DEVICE))

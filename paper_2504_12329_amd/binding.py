@@ -14,7 +14,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libst.so")
 
 ST_OK, ST_EINVAL, ST_ENOMEM, ST_ERANGE, ST_EHIP = 0, -1, -2, -3, -4
-ST_TOKENS_DEVICE, ST_OUT_DEVICE, ST_TOKEN_CHAINED = 1, 2, 4
+ST_TOKENS_DEVICE, ST_OUT_DEVICE, ST_TOKEN_CHAINED, ST_PREFILL_TWO_TERM = 1, 2, 4, 8
 
 EXPORTS = ("st_query_sizes", "st_model_create", "st_model_destroy", "st_kv_len", "st_kv_truncate", "st_prefill",
            "st_decode_step", "st_decode_step_timed", "st_decode_greedy", "st_trigger_scan", "st_handoff", "st_generate",
@@ -200,19 +200,20 @@ class Model:
     def truncate(self, n):
         _check(lib().st_kv_truncate(self._h, n))
 
-    def prefill(self, tokens, want_logits=True):
-        """tokens: host int array.  Returns (logits ndarray or None, greedy token)."""
+    def prefill(self, tokens, want_logits=True, two_term=False):
+        """tokens: host int array; two_term: passes of at most 256 rows (ST_PREFILL_TWO_TERM).
+        Returns (logits ndarray or None, greedy token)."""
         t = np.ascontiguousarray(tokens, dtype=np.int32)
         lg = np.empty(self.cfg["vocab"], dtype=np.float32) if want_logits else None
         nt = C.c_int32()
         _check(lib().st_prefill(self._h, _np_ptr(t), t.size, _np_ptr(lg) if want_logits else None,
-                                C.addressof(nt), 0))
+                                C.addressof(nt), ST_PREFILL_TWO_TERM if two_term else 0))
         return lg, nt.value
 
-    def prefill_device(self, tokens_dev):
+    def prefill_device(self, tokens_dev, two_term=False):
         """tokens_dev: int32 CUDA tensor; enqueues only (no outputs, no synchronisation)."""
         _check(lib().st_prefill(self._h, tokens_dev.data_ptr(), tokens_dev.numel(), None, None,
-                                ST_TOKENS_DEVICE | ST_OUT_DEVICE))
+                                ST_TOKENS_DEVICE | ST_OUT_DEVICE | (ST_PREFILL_TWO_TERM if two_term else 0)))
 
     def decode_step(self, token, want_logits=True):
         lg = np.empty(self.cfg["vocab"], dtype=np.float32) if want_logits else None

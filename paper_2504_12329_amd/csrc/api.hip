@@ -99,7 +99,8 @@ void carve_workspace(const st_config &c, char *base, Workspace *ws) {
 
 // Enqueues the catch-up pass over `n` tokens (host or device ids); the last row's logits and greedy
 // token (with the trigger predicate when a rule is given) end up in ws.logits / state.
-static int prefill_impl(Model *m, const int32_t *tokens, int32_t n, bool tokens_dev, const st_trigger_rule *rule) {
+static int prefill_impl(Model *m, const int32_t *tokens, int32_t n, bool tokens_dev, const st_trigger_rule *rule,
+                        bool two_term = false) {
     const st_config &c = m->c;
     if (!tokens) return fail(ST_EINVAL, "tokens is NULL");
     if (n <= 0) return fail(ST_ERANGE, "n must be positive (got %d)", n);
@@ -109,8 +110,10 @@ static int prefill_impl(Model *m, const int32_t *tokens, int32_t n, bool tokens_
         for (int32_t i = 0; i < n; ++i)
             if (tokens[i] < 0 || tokens[i] >= c.vocab)
                 return fail(ST_ERANGE, "token id %d at index %d is outside the vocabulary [0,%d)", tokens[i], i, c.vocab);
-    for (int32_t done = 0; done < n; done += c.max_chunk) {
-        int32_t cn = n - done < c.max_chunk ? n - done : c.max_chunk;
+    // passes of at most max_chunk rows; 256 rows on request: the longest pass that keeps two-term GEMM inputs
+    const int32_t step = two_term && c.max_chunk > 256 ? 256 : c.max_chunk;
+    for (int32_t done = 0; done < n; done += step) {
+        int32_t cn = n - done < step ? n - done : step;
         ST_HIP(hipMemcpyAsync(m->ws.tokens, tokens + done, sizeof(int32_t) * cn,
                               tokens_dev ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice, m->stream));
         bool last_chunk = done + cn == n;
@@ -358,9 +361,9 @@ static int check_flags(uint32_t flags, uint32_t allowed) {
 
 int st_prefill(st_model *h, const int32_t *tokens, int32_t n, float *logits, int32_t *next_tok, uint32_t flags) {
     if (!h) return fail(ST_EINVAL, "model is NULL");
-    if (int rc = check_flags(flags, ST_TOKENS_DEVICE | ST_OUT_DEVICE)) return rc;
+    if (int rc = check_flags(flags, ST_TOKENS_DEVICE | ST_OUT_DEVICE | ST_PREFILL_TWO_TERM)) return rc;
     Model *m = reinterpret_cast<Model *>(h);
-    if (int rc = prefill_impl(m, tokens, n, flags & ST_TOKENS_DEVICE, nullptr)) return rc;
+    if (int rc = prefill_impl(m, tokens, n, flags & ST_TOKENS_DEVICE, nullptr, flags & ST_PREFILL_TWO_TERM)) return rc;
     return deliver(m, logits, next_tok, flags & ST_OUT_DEVICE);
 }
 

@@ -174,3 +174,24 @@ def test_qwen32b_full_depth_paths_agree():
     if _margin(a) >= MIN_MARGIN:
         assert tok_a == tok_b == tok_c
     g.close()
+
+
+def test_qwen1p5b_long_chunk_at_full_depth():
+    """A 300-token prompt through all 28 layers, against the oracle.  Fed as one pass it takes the long-chunk
+    kernels, whose GEMM inputs are single bf16 numbers: that rounding, amplified through the depth of a random-weight
+    model, is what the pass's error consists of (the decode steps that follow are unaffected).  With
+    ST_PREFILL_TWO_TERM the same prompt goes in passes of at most 256 rows and keeps the tolerance with margin."""
+    print_case("1.5B shape, 28 layers: 300-token prompt as one pass and as two-term passes, then one decode step")
+    cfg, g, o = make_pair("qwen1p5b", 1, max_seq=320, max_chunk=300, gen_device="cuda")
+    toks = synth.make_prompt(301, cfg["vocab"], 21)
+    ref = o.feed(toks[:300])
+    fast, _ = g.prefill(toks[:300])
+    dec, _ = g.decode_step(int(toks[300]))
+    ref_dec = o.feed(toks[300:301])
+    g.truncate(0)
+    two, _ = g.prefill(toks[:300], two_term=True)
+    print_case("one pass", rel_err(fast, ref), "decode after it", rel_err(dec, ref_dec), "two-term passes", rel_err(two, ref))
+    assert g.kv_len == 300
+    assert rel_err(two, ref) <= LOGIT_TOL and rel_err(dec, ref_dec) <= LOGIT_TOL
+    assert rel_err(fast, ref) <= 1.25 * LOGIT_TOL      # measured 2.1e-2: single-term inputs over 28 layers
+    g.close()
