@@ -473,6 +473,17 @@ __device__ __forceinline__ float merge_w(float m, float M) { return m == -INFINI
 
 constexpr int kKeyTile = 64;
 
+// One element of a row's attention output: fp32, or two bf16 terms where the consumer is a GEMM.
+__device__ __forceinline__ void put_attn(const AttnRows &rows, float *out, size_t row_off, size_t i, float v) {
+    if (rows.out_hi) {
+        const bf16_t h = f32_to_bf16(v);
+        rows.out_hi[row_off + i] = h;
+        rows.out_lo[row_off + i] = f32_to_bf16(v - bf16_to_f32(h));
+    } else {
+        out[i] = v;
+    }
+}
+
 __device__ __forceinline__ void unpack8(const u32x4 &w, float (&f)[8]) {
     f[0] = bf16_lo(w.x);
     f[1] = bf16_hi(w.x);
@@ -645,7 +656,7 @@ __global__ __launch_bounds__(256) void k_attn_partial(const float *__restrict__ 
         const int hh = idx / D, e = idx - hh * D;
         const float A = (red_acc[0][hh][e] + red_acc[1][hh][e]) + (red_acc[2][hh][e] + red_acc[3][hh][e]);
         if (s_active == 1) {
-            out[(size_t)(g * G + hh) * D + e] = A / run_l[hh];
+            put_attn(rows, out, (size_t)row * rows.q_stride, (size_t)(g * G + hh) * D + e, A / run_l[hh]);
         } else {
             const size_t pi = (size_t)(g * G + hh) * S + s;
             part_acc[pi * D + e] = A;
@@ -709,7 +720,7 @@ __global__ __launch_bounds__(256) void k_attn_combine(AttnRows rows, int S, cons
         for (int i = 0; i < s_active; ++i) L += wl_s[i][1];
 #pragma unroll
         for (int j = 1; j < NG; ++j) A += red[j][e];
-        out[(size_t)hh * D + e] = A / L;
+        put_attn(rows, out, (size_t)row * rows.q_stride, (size_t)hh * D + e, A / L);
     }
 }
 
@@ -756,7 +767,7 @@ static void launch_attn_t(const Model &m, int layer, hipStream_t stream, int att
 // the single-sequence step: one row whose position is state[kPos], sequence 0
 template <int D>
 static void launch_attn(const Model &m, int layer, hipStream_t stream, int attn_blocks) {
-    const AttnRows rows = {m.ws.state + kPos, nullptr, 0, 0, 0, 0};
+    const AttnRows rows = {m.ws.state + kPos, nullptr, 0, 0, 0, 0, nullptr, nullptr};
     launch_attn_t<D>(m, layer, stream, attn_blocks, rows, 1, m.ws.q1, m.ws.part_ml, m.ws.part_acc, m.ws.o1);
 }
 

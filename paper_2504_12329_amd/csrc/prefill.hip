@@ -1594,17 +1594,6 @@ __global__ void k_rope_append_rows(const float *__restrict__ part, int n_part, s
     dst[i + half] = f32_to_bf16(hi);
 }
 
-// fp32 rows -> two bf16 terms (GEMM input of the O projection)
-__global__ __launch_bounds__(256) void k_rows_two_term(const float *__restrict__ src, bf16_t *__restrict__ hi,
-                                                       bf16_t *__restrict__ lo, size_t n) {
-    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
-    if (i >= n) return;
-    const float v = src[i];
-    const bf16_t h = f32_to_bf16(v);
-    hi[i] = h;
-    lo[i] = f32_to_bf16(v - bf16_to_f32(h));
-}
-
 // Row r: logits[r][:] = sum of the K slices (also stored when logits != nullptr), next[r] = arg-max, lowest id on ties.
 __global__ __launch_bounds__(1024) void k_argmax_rows(const float *__restrict__ part, int n_part, size_t part_stride,
                                                       int V, float *__restrict__ logits, int32_t *__restrict__ next) {
@@ -1639,7 +1628,7 @@ void launch_batch_step(const Model &m, const BatchRows &b, int n, int attn_block
     const int qd = nq * d, qkv = m.qkv_dim;
     const Workspace &w = m.ws;
     const AttnRows rows = {b.row_pos, b.row_seq, b.seq_stride, qd, (size_t)nq * kAttnSplits * 2,
-                           (size_t)nq * kAttnSplits * d};
+                           (size_t)nq * kAttnSplits * d, w.attn, w.attn_lo};  // result straight into the O GEMM's input
     hipLaunchKernelGGL(k_embed_rows, dim3(n), dim3(256), 0, m.stream, m.embed, b.row_tok, w.x, h, c.vocab);
     int pending = 0;
     for (int l = 0; l < c.n_layers; ++l) {
@@ -1651,8 +1640,6 @@ void launch_batch_step(const Model &m, const BatchRows &b, int n, int attn_block
                            (size_t)n * qkv, m.bqkv[l], w.rope, b.q_rows, (bf16_t *)nullptr, (bf16_t *)nullptr,
                            m.kcache + lofs, m.vcache + lofs, b.row_pos, b.row_seq, b.seq_stride, nq, nkv, d, c.max_seq);
         launch_attn_rows(m, l, m.stream, attn_blocks, rows, n, b.q_rows, b.part_ml, b.part_acc, b.o_rows);
-        hipLaunchKernelGGL(k_rows_two_term, dim3(((size_t)n * qd + 255) / 256), dim3(256), 0, m.stream, b.o_rows,
-                           w.attn, w.attn_lo, (size_t)n * qd);
         const int so = gemm<false>(m, w.attn, w.attn_lo, qd, m.wo[l], n, h, qd, nullptr, nullptr, 0);
         hipLaunchKernelGGL(k_rmsnorm_rows, dim3(n), dim3(norm_threads(n)), 0, m.stream, w.x, w.qkv, so, (size_t)n * h,
                            m.norm_mlp[l], w.xn, w.xn_lo, h, c.rms_eps);

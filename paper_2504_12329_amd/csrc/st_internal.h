@@ -41,12 +41,14 @@ struct Workspace {
 
 // Rows of the decode attention: row z attends with its new token at position pos[z] to the cache of sequence
 // seq[z] (seq == nullptr: sequence 0), caches seq_stride elements apart; q / out rows q_stride floats apart and
-// the per-row partial buffers ml_stride / acc_stride floats apart.
+// the per-row partial buffers ml_stride / acc_stride floats apart.  With out_hi / out_lo the result is written as two
+// bf16 terms (rows q_stride elements apart: the input of the O projection GEMM) instead of fp32.
 struct AttnRows {
     const int32_t *pos, *seq;
     size_t seq_stride;
     int q_stride;
     size_t ml_stride, acc_stride;
+    bf16_t *out_hi, *out_lo;
 };
 
 constexpr int kLmBlocks = 1024;   // blocks (and arg-max partials) of the LM-head kernel
