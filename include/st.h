@@ -111,7 +111,9 @@ int st_prefill(st_model *m, const int32_t *tokens, int32_t n, float *logits, int
                uint32_t flags);
 
 /* One decode step (paper Section 4, "decode" stage): feeds one token at position kv_len,
- * kv_len += 1, same outputs as st_prefill. */
+ * kv_len += 1, same outputs as st_prefill.  The kernels of a step are captured once per trigger rule, output buffer
+ * and context-length bucket into a HIP graph (on a private stream) and replayed on the model's stream; setting the
+ * environment variable ST_NO_GRAPH before st_model_create launches them one by one instead. */
 int st_decode_step(st_model *m, int32_t token, float *logits, int32_t *next_tok, uint32_t flags);
 
 /* n chained greedy decode steps: feeds first_token (or the model's own last greedy token when
