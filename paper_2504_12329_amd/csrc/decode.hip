@@ -675,7 +675,7 @@ template <int D>
 __global__ __launch_bounds__(256) void k_attn_combine(AttnRows rows, int S, const float *__restrict__ part_ml,
                                                       const float *__restrict__ part_acc, float *__restrict__ out) {
     constexpr int NG = 256 / D;
-    __shared__ float m_s[kAttnSplits], wl_s[kAttnSplits][2];
+    __shared__ float m_s[2], wl_s[kAttnSplits][2];  // wl_s[i][0]: weight of range i; wl_s[0..1][1]: the waves' sums
     __shared__ float red[NG][D];
     const int row = blockIdx.z;
     const int t = rows.pos[row] + 1;
@@ -695,18 +695,22 @@ __global__ __launch_bounds__(256) void k_attn_combine(AttnRows rows, int S, cons
         int i = grp + NG * u;
         aa[u] = i < s_active ? part_acc[(p0 + i) * D + e] : 0.f;
     }
+    // thread i < 128 holds range i's (max, sum); the overall max and the rescaled sum are two-level reductions
+    // (wave, then the two waves that hold ranges) in a fixed order
+    static_assert(kAttnSplits == 128, "ranges live in the first two waves");
     float2 ml = make_float2(-INFINITY, 0.f);
     if (tid < s_active) ml = reinterpret_cast<const float2 *>(part_ml)[p0 + tid];
-    if (tid < kAttnSplits) m_s[tid] = ml.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const float mx = wave_max(ml.x);
+    if (lane == 0 && wave < 2) m_s[wave] = mx;
     __syncthreads();
-    float M = -INFINITY;
-    for (int i = 0; i < s_active; ++i) M = fmaxf(M, m_s[i]);
-    if (tid < kAttnSplits) {
-        float w = merge_w(ml.x, M);
-        wl_s[tid][0] = w;
-        wl_s[tid][1] = w * ml.y;
-    }
+    const float M = fmaxf(m_s[0], m_s[1]);
+    const float w = merge_w(ml.x, M);
+    if (tid < kAttnSplits) wl_s[tid][0] = w;
+    const float ls = wave_sum(w * ml.y);
+    if (lane == 0 && wave < 2) wl_s[wave][1] = ls;
     __syncthreads();
+    const float L = wl_s[0][1] + wl_s[1][1];
     float A = 0.f;
 #pragma unroll
     for (int u = 0; u < BATCH; ++u) {
@@ -716,8 +720,6 @@ __global__ __launch_bounds__(256) void k_attn_combine(AttnRows rows, int S, cons
     red[grp][e] = A;
     __syncthreads();
     if (grp == 0) {
-        float L = 0.f;
-        for (int i = 0; i < s_active; ++i) L += wl_s[i][1];
 #pragma unroll
         for (int j = 1; j < NG; ++j) A += red[j][e];
         put_attn(rows, out, (size_t)row * rows.q_stride, (size_t)hh * D + e, A / L);
