@@ -668,15 +668,15 @@ __global__ __launch_bounds__(256) void k_attn_partial(const float *__restrict__ 
     }
 }
 
-// Merges the ranges of one query head.  Block = head, 256 threads = 256/D groups x D output
-// elements; group j sums the ranges i = j (mod 256/D) in ascending order and the groups are
-// added in a fixed order.  The per-range weights exp2(m_i - M) are computed once into LDS.
+// Merges the ranges of one query head.  Block = head; 256 threads = 1024/D groups x D/4 quads of output elements:
+// group j sums the ranges i = j (mod 1024/D) in ascending order with 16-byte loads, and the groups are added in a
+// fixed order.  The per-range weights exp2(m_i - M) are computed once into LDS.
 template <int D>
 __global__ __launch_bounds__(256) void k_attn_combine(AttnRows rows, int S, const float *__restrict__ part_ml,
                                                       const float *__restrict__ part_acc, float *__restrict__ out) {
-    constexpr int NG = 256 / D;
+    constexpr int Q = D / 4, NG = 256 / Q;  // quads per row, groups of ranges
     __shared__ float m_s[2], wl_s[kAttnSplits][2];  // wl_s[i][0]: weight of range i; wl_s[0..1][1]: the waves' sums
-    __shared__ float red[NG][D];
+    __shared__ float4 red[NG][Q];
     const int row = blockIdx.z;
     const int t = rows.pos[row] + 1;
     const int chunk = attn_chunk(t, S);
@@ -685,15 +685,15 @@ __global__ __launch_bounds__(256) void k_attn_combine(AttnRows rows, int S, cons
     part_ml += (size_t)row * rows.ml_stride;
     part_acc += (size_t)row * rows.acc_stride;
     out += (size_t)row * rows.q_stride;
-    const int hh = blockIdx.x, tid = threadIdx.x, e = tid % D, grp = tid / D;
+    const int hh = blockIdx.x, tid = threadIdx.x, q = tid % Q, grp = tid / Q;
     const size_t p0 = (size_t)hh * S;
     // this thread's slice of the unnormalised outputs, issued before anything waits
     constexpr int BATCH = kAttnSplits / NG;
-    float aa[BATCH];
+    float4 aa[BATCH];
 #pragma unroll
     for (int u = 0; u < BATCH; ++u) {
-        int i = grp + NG * u;
-        aa[u] = i < s_active ? part_acc[(p0 + i) * D + e] : 0.f;
+        const int i = grp + NG * u;
+        aa[u] = i < s_active ? reinterpret_cast<const float4 *>(part_acc + (p0 + i) * D)[q] : make_float4(0.f, 0.f, 0.f, 0.f);
     }
     // thread i < 128 holds range i's (max, sum); the overall max and the rescaled sum are two-level reductions
     // (wave, then the two waves that hold ranges) in a fixed order
@@ -711,18 +711,28 @@ __global__ __launch_bounds__(256) void k_attn_combine(AttnRows rows, int S, cons
     if (lane == 0 && wave < 2) wl_s[wave][1] = ls;
     __syncthreads();
     const float L = wl_s[0][1] + wl_s[1][1];
-    float A = 0.f;
+    float4 A = make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
     for (int u = 0; u < BATCH; ++u) {
-        int i = grp + NG * u;
-        if (i < s_active) A += aa[u] * wl_s[i][0];
+        const int i = grp + NG * u;
+        if (i < s_active) {
+            const float wi = wl_s[i][0];
+            A.x += aa[u].x * wi, A.y += aa[u].y * wi, A.z += aa[u].z * wi, A.w += aa[u].w * wi;
+        }
     }
-    red[grp][e] = A;
+    red[grp][q] = A;
     __syncthreads();
     if (grp == 0) {
 #pragma unroll
-        for (int j = 1; j < NG; ++j) A += red[j][e];
-        put_attn(rows, out, (size_t)row * rows.q_stride, (size_t)hh * D + e, A / L);
+        for (int j = 1; j < NG; ++j) {
+            const float4 o = red[j][q];
+            A.x += o.x, A.y += o.y, A.z += o.z, A.w += o.w;
+        }
+        const size_t row_off = (size_t)row * rows.q_stride, i0 = (size_t)hh * D + 4 * q;
+        put_attn(rows, out, row_off, i0 + 0, A.x / L);
+        put_attn(rows, out, row_off, i0 + 1, A.y / L);
+        put_attn(rows, out, row_off, i0 + 2, A.z / L);
+        put_attn(rows, out, row_off, i0 + 3, A.w / L);
     }
 }
 
