@@ -516,7 +516,7 @@ __global__ __launch_bounds__(256) void k_attn_partial(const float *__restrict__ 
     __shared__ float sc_part[4][G][kKeyTile];
     __shared__ float p_s[G][kKeyTile];
     __shared__ float run_m[G], run_l[G], corr_s[G];
-    __shared__ float red_acc[4][G][D];
+    __shared__ __align__(16) float red_acc[4][G][D];
 
     const int row = blockIdx.z;
     const int t = rows.pos[row] + 1;  // keys 0..pos, the new one included
@@ -652,14 +652,29 @@ __global__ __launch_bounds__(256) void k_attn_partial(const float *__restrict__ 
             for (int e = 0; e < 8; ++e) red_acc[wave][hh][lane * 8 + e] = acc[hh][e];
     }
     __syncthreads();
-    for (int idx = tid; idx < G * D; idx += 256) {
-        const int hh = idx / D, e = idx - hh * D;
-        const float A = (red_acc[0][hh][e] + red_acc[1][hh][e]) + (red_acc[2][hh][e] + red_acc[3][hh][e]);
+    // four consecutive output elements per thread: 16-byte LDS reads and one 16-byte store
+    for (int idx = tid; idx < G * D / 4; idx += 256) {
+        const int hh = idx / (D / 4), e = (idx - hh * (D / 4)) * 4;
+        const float4 a0 = *reinterpret_cast<const float4 *>(&red_acc[0][hh][e]);
+        const float4 a1 = *reinterpret_cast<const float4 *>(&red_acc[1][hh][e]);
+        const float4 a2 = *reinterpret_cast<const float4 *>(&red_acc[2][hh][e]);
+        const float4 a3 = *reinterpret_cast<const float4 *>(&red_acc[3][hh][e]);
+        const float4 A = make_float4((a0.x + a1.x) + (a2.x + a3.x), (a0.y + a1.y) + (a2.y + a3.y),
+                                     (a0.z + a1.z) + (a2.z + a3.z), (a0.w + a1.w) + (a2.w + a3.w));
         if (s_active == 1) {
-            put_attn(rows, out, (size_t)row * rows.q_stride, (size_t)(g * G + hh) * D + e, A / run_l[hh]);
+            const float inv_l = 1.0f / run_l[hh];
+            const size_t row_off = (size_t)row * rows.q_stride, i0 = (size_t)(g * G + hh) * D + e;
+            if (rows.out_hi) {
+                put_attn(rows, out, row_off, i0 + 0, A.x * inv_l);
+                put_attn(rows, out, row_off, i0 + 1, A.y * inv_l);
+                put_attn(rows, out, row_off, i0 + 2, A.z * inv_l);
+                put_attn(rows, out, row_off, i0 + 3, A.w * inv_l);
+            } else {
+                *reinterpret_cast<float4 *>(out + i0) = make_float4(A.x * inv_l, A.y * inv_l, A.z * inv_l, A.w * inv_l);
+            }
         } else {
             const size_t pi = (size_t)(g * G + hh) * S + s;
-            part_acc[pi * D + e] = A;
+            *reinterpret_cast<float4 *>(part_acc + pi * D + e) = A;
             if (e == 0) {
                 part_ml[pi * 2] = run_m[hh];
                 part_ml[pi * 2 + 1] = run_l[hh];
