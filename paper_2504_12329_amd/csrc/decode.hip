@@ -182,6 +182,20 @@ __global__ __launch_bounds__(256) void k_qkv_rope(const bf16_t *__restrict__ W, 
     }
     rf.prefetch(n8, lane);
     const int pos = state[kPos];
+    // lane j finishes unit j: its bias pair and rotation are fetched now, under the weight stream
+    float b_lo = 0.f, b_hi = 0.f;
+    float2 cs = make_float2(1.f, 0.f);
+#pragma unroll
+    for (int j = 0; j < R; ++j) {
+        if (lane == j) {
+            const int r0 = row0[j], head = r0 / d, i = r0 - head * d;
+            if (bias) {
+                b_lo = bf16_to_f32(bias[r0]);
+                b_hi = bf16_to_f32(bias[r0 + half_d]);
+            }
+            if (head < nq + nkv) cs = rope[(size_t)pos * half_d + i];
+        }
+    }
     const float inv = xstage(xr, h, eps, xs, red);
     if (u0 >= n_units) return;
 
@@ -197,13 +211,8 @@ __global__ __launch_bounds__(256) void k_qkv_rope(const bf16_t *__restrict__ W, 
         if (lane == j && u0 + j < n_units) {
             int r0 = row0[j], r1 = r0 + half_d;
             int head = r0 / d, i = r0 - head * d;
-            float lo = acc[2 * j] * inv, hi = acc[2 * j + 1] * inv;
-            if (bias) {
-                lo += bf16_to_f32(bias[r0]);
-                hi += bf16_to_f32(bias[r1]);
-            }
+            float lo = acc[2 * j] * inv + b_lo, hi = acc[2 * j + 1] * inv + b_hi;
             if (head < nq + nkv) {
-                float2 cs = rope[(size_t)pos * half_d + i];
                 float nlo = lo * cs.x - hi * cs.y;
                 float nhi = hi * cs.x + lo * cs.y;
                 lo = nlo;
@@ -300,6 +309,9 @@ __global__ __launch_bounds__(256) void k_gemv_residual(const bf16_t *__restrict_
 #pragma unroll
     for (int r = 0; r < RB; ++r) wrow[r] = reinterpret_cast<const u32x4 *>(W + (size_t)min(r0 + r, N - 1) * K);
     const float4 *xv = reinterpret_cast<const float4 *>(v);
+    // the residual element this thread will add at the end: fetched now, under the weight stream
+    const bool writer = threadIdx.x < RB && r0 + (int)threadIdx.x < N;
+    const float res_v = writer ? res[r0 + threadIdx.x] : 0.f;
     float acc[RB];
 #pragma unroll
     for (int r = 0; r < RB; ++r) acc[r] = 0.f;
@@ -335,9 +347,9 @@ __global__ __launch_bounds__(256) void k_gemv_residual(const bf16_t *__restrict_
         for (int r = 0; r < RB; ++r) part[wave][r] = acc[r];
     }
     __syncthreads();
-    if (threadIdx.x < RB && r0 + (int)threadIdx.x < N) {
+    if (writer) {
         int r = threadIdx.x;
-        y[r0 + r] = res[r0 + r] + ((part[0][r] + part[1][r]) + (part[2][r] + part[3][r]));
+        y[r0 + r] = res_v + ((part[0][r] + part[1][r]) + (part[2][r] + part[3][r]));
     }
 }
 
