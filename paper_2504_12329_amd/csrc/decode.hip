@@ -650,13 +650,17 @@ __global__ __launch_bounds__(256) void k_attn_partial(const float *__restrict__ 
             }
         }
     }
-    // sum the key slots of a wave, then the four waves
+    // sum the key slots of a wave (LPK lanes apart: whole 16- / 32-lane rows), then the four waves
+    static_assert(LPK == 16 || LPK == 8, "key slots are rows of 16 lanes, or halves of them");
 #pragma unroll
-    for (int o = LPK; o < 64; o <<= 1)
+    for (int hh = 0; hh < G; ++hh)
 #pragma unroll
-        for (int hh = 0; hh < G; ++hh)
-#pragma unroll
-            for (int e = 0; e < 8; ++e) acc[hh][e] += __shfl_xor(acc[hh][e], o, kWave);
+        for (int e = 0; e < 8; ++e) {
+            float v = acc[hh][e];
+            if (LPK == 8) v += __shfl_xor(v, 8, kWave);
+            v = sum_xor16(v);
+            acc[hh][e] = sum_xor32(v);
+        }
     if (lane < LPK) {
 #pragma unroll
         for (int hh = 0; hh < G; ++hh)

@@ -902,7 +902,7 @@ __global__ __launch_bounds__(256) void k_flash_prefill(const bf16_t *__restrict_
                 sacc[u][r] = sc;
                 mx = fmaxf(mx, sc);
             }
-        mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
+        mx = max_xor32(mx);
         const float m_new = fmaxf(m_i, mx);
         const float m_use = m_new == -INFINITY ? 0.f : m_new;  // a row may see no key of this split yet
         const float corr = exp2f(m_i - m_use);                 // m_i = -inf gives 0
@@ -915,7 +915,7 @@ __global__ __launch_bounds__(256) void k_flash_prefill(const bf16_t *__restrict_
                 sacc[u][r] = p;
                 rs += p;
             }
-        rs += __shfl_xor(rs, 32, kWave);
+        rs = sum_xor32(rs);
         l_i = l_i * corr + rs;
         m_i = m_new;
 #pragma unroll
@@ -1129,7 +1129,7 @@ __global__ __launch_bounds__(64 * NW, TWO ? 1 : 2) void k_flash_long(const bf16_
         for (int u = 0; u < 2; ++u)
 #pragma unroll
             for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[u][r]);
-        mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
+        mx = max_xor32(mx);
         const float m_cand = mx * scale;
         const bool raise = m_cand > m_i + 8.0f;                    // also the first keys a row sees (m_i = -inf)
         const float m_new = raise ? m_cand : m_i;
@@ -1143,7 +1143,7 @@ __global__ __launch_bounds__(64 * NW, TWO ? 1 : 2) void k_flash_long(const bf16_
                 sacc[u][r] = p;
                 rs += p;
             }
-        rs += __shfl_xor(rs, 32, kWave);
+        rs = sum_xor32(rs);
         if (__builtin_amdgcn_ballot_w64(raise) != 0) {
             const float corr = raise ? __builtin_amdgcn_exp2f(m_i - base) : 1.0f;  // m_i = -inf gives 0
             l_i *= corr;

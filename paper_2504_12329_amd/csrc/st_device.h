@@ -32,15 +32,56 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
 }
 
+// Cross-lane reductions without the LDS crossbar (a ds_bpermute step costs ~60 clocks of latency, a DPP step ~8):
+// quad swaps, half-row and row mirrors, then the two row broadcasts leave the total in lane 63, which is read back
+// to every lane.  `old` is what a lane keeps where the pattern has no source for it (the reduction's identity).
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_move(float old, float v) {
+    return __int_as_float(
+        __builtin_amdgcn_update_dpp(__float_as_int(old), __float_as_int(v), CTRL, ROW_MASK, 0xf, false));
+}
 __device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
-    return v;
+    v += dpp_move<0xB1, 0xf>(0.f, v);   // quad_perm [1,0,3,2]
+    v += dpp_move<0x4E, 0xf>(0.f, v);   // quad_perm [2,3,0,1]
+    v += dpp_move<0x141, 0xf>(0.f, v);  // row_half_mirror
+    v += dpp_move<0x140, 0xf>(0.f, v);  // row_mirror: every lane holds its row's sum
+    v += dpp_move<0x142, 0xa>(0.f, v);  // row_bcast15 into rows 1 and 3
+    v += dpp_move<0x143, 0xc>(0.f, v);  // row_bcast31 into rows 2 and 3
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
 }
 __device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, kWave));
-    return v;
+    v = fmaxf(v, dpp_move<0xB1, 0xf>(-INFINITY, v));
+    v = fmaxf(v, dpp_move<0x4E, 0xf>(-INFINITY, v));
+    v = fmaxf(v, dpp_move<0x141, 0xf>(-INFINITY, v));
+    v = fmaxf(v, dpp_move<0x140, 0xf>(-INFINITY, v));
+    v = fmaxf(v, dpp_move<0x142, 0xa>(-INFINITY, v));
+    v = fmaxf(v, dpp_move<0x143, 0xc>(-INFINITY, v));
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
+}
+// x[lane] and x[lane ^ 16] / x[lane ^ 32], by swapping 16- / 32-lane rows of two copies of the register
+typedef unsigned int lane_pair_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ void with_xor16(float x, float &a, float &b) {
+    const lane_pair_t r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    a = __uint_as_float(r.x), b = __uint_as_float(r.y);
+}
+__device__ __forceinline__ void with_xor32(float x, float &a, float &b) {
+    const lane_pair_t r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    a = __uint_as_float(r.x), b = __uint_as_float(r.y);
+}
+__device__ __forceinline__ float sum_xor16(float x) {
+    float a, b;
+    with_xor16(x, a, b);
+    return a + b;
+}
+__device__ __forceinline__ float sum_xor32(float x) {
+    float a, b;
+    with_xor32(x, a, b);
+    return a + b;
+}
+__device__ __forceinline__ float max_xor32(float x) {
+    float a, b;
+    with_xor32(x, a, b);
+    return fmaxf(a, b);
 }
 
 // Sum over a 256-thread block (4 waves); `red` is 4 floats of LDS.  Ends with a barrier.
