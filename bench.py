@@ -25,7 +25,7 @@ PROMPT, N_DECODE = 512, 4096
 HBM_PEAK = 8.0e12          # bytes/s, MI355X HBM3E
 # HBM bytes per launch of k_gateup_swiglu<3,1,true> from rocprofv3 FETCH_SIZE (x2.00) + WRITE_SIZE (x1.00), see
 # profiles/decode_qwen1p5b_hbm_counters.md; set to None whenever that kernel changes until the counters are re-taken
-GATEUP_TRAFFIC_BYTES = 55.30e6
+GATEUP_TRAFFIC_BYTES = 55.29e6
 MFMA_PEAK = 2.5e15         # dense bf16 flop/s
 
 
