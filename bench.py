@@ -118,7 +118,8 @@ def batched_loop(B, synth, cfg_s, w_s, cfg_l, w_l, n_seq=16, n_out=210, n_seg=20
                         ", target writes 20; prompt prefill included; the ms_* figures of the two models overlap"}
 
 
-def target_model_extras(torch, B, synth, cost, small, sizes=(21, 86, 256, 1024, 4096), loop=True, n_layers=None):
+def target_model_extras(torch, B, synth, cost, small, sizes=(21, 86, 256, 1024, 4096), loop=True, n_layers=None,
+                        batched=True):
     """32B-shaped target: decode rate at kv ~ 4k, catch-up prefill on a 4096-token cache, and the loop."""
     cfg = synth.model_config("qwen32b", max_seq=4096 + 4096 + 64, max_chunk=4096, n_layers=n_layers)
     w = synth.make_weights(cfg, 2, device="cuda")
@@ -150,6 +151,8 @@ def target_model_extras(torch, B, synth, cost, small, sizes=(21, 86, 256, 1024, 
             "bound": "hbm" if m < 312 else "mfma"}
     large.close()
     del large
+    if not batched:
+        return res
     res["batched_decode"] = {"qwen32b": batched_decode(torch, B, synth, cost, cfg, w)}
     if loop:
         cfg7 = synth.model_config("qwen7b", max_seq=1400, max_chunk=4096)
@@ -217,6 +220,8 @@ def main():
                     help="catch-up chunk lengths timed on the 32B-shaped model (one size for a kernel profile)")
     ap.add_argument("--extras-layers", type=int, default=None,
                     help="profiling aid: give the 32B-shaped model this many layers (per-kernel figures are unchanged)")
+    ap.add_argument("--prefill-only", action="store_true",
+                    help="profiling aid: with --only-extras, stop after the 32B-shaped decode / catch-up timings")
     ap.add_argument("--only-extras", action="store_true",
                     help="profiling aid: run only the 32B-shaped decode / prefill measurements, no headline job")
     ap.add_argument("--no-roofline", action="store_true",
@@ -233,7 +238,8 @@ def main():
     sizes = tuple(int(v) for v in args.prefill_sizes.split(","))
     if args.only_extras:
         print(json.dumps({"target_model_32b": target_model_extras(torch, B, synth, cost, None, sizes, loop=False,
-                                                                       n_layers=args.extras_layers)}))
+                                                                       n_layers=args.extras_layers,
+                                                                       batched=not args.prefill_only)}))
         return
     n_dec = args.decode_steps
     cfg = synth.model_config("qwen1p5b", max_seq=PROMPT + N_DECODE + 64, max_chunk=PROMPT)
