@@ -879,7 +879,8 @@ void launch_head(const Model &m, const float *x_row, const st_trigger_rule *rule
 // Pairs per wave-group of the gate/up kernel and its grid: one group per wave while the whole grid
 // can be resident (3 blocks of 256 threads per CU), a balanced walk over 768 blocks otherwise.
 static void gateup_shape(int I, int k_iters, int *r_out, int *blocks_out, bool *one_out) {
-    int r = k_iters <= 4 ? 3 : (k_iters <= 8 ? 2 : 1);  // keeps the up-front loads within the register file
+    // keeps the up-front loads within the register file; from hidden 3584 on single pairs measured best
+    int r = k_iters <= 4 ? 3 : (k_iters <= 6 ? 2 : 1);
     int groups = (I + r - 1) / r;
     int blocks = (groups + 3) / 4;
     *one_out = blocks <= 768;
