@@ -173,7 +173,7 @@ def target_model_extras(torch, B, synth, cost, small, sizes=(21, 86, 256, 1024, 
     if not loop:
         return res
     vocab = small.cfg["vocab"]
-    cfg_l = dict(cfg, vocab=vocab, max_seq=2048, max_chunk=256)
+    cfg_l = dict(cfg, vocab=vocab, max_seq=5376, max_chunk=256)
     w_l = dict(w, embed=w["embed"][:vocab], lm_head=w["lm_head"][:vocab])
     large = B.Model(cfg_l, w_l)
     small.truncate(0)
@@ -188,6 +188,24 @@ def target_model_extras(torch, B, synth, cost, small, sizes=(21, 86, 256, 1024, 
                             "ms_small_decode": st["ms_small_decode"], "ms_large_decode": st["ms_large_decode"],
                             "ms_small_prefill": st["ms_small_prefill"], "ms_large_prefill": st["ms_large_prefill"],
                             "schedule": "forced: every 85th speculative token hands over, target writes 20"}
+    # the same pair under the synthetic trigger rule itself (previous id % 89 == 0 and id % 97 == 0), 5000 output
+    # tokens: on uniform ids the rule fires about once in 8600 tokens, so a run has zero or one hand-over and is in
+    # effect the speculative model's decode rate; the realised hand-overs and their catch-up lengths are reported
+    small.truncate(0)
+    large.truncate(0)
+    rule = B.TriggerRule(vocab, synth.modulo_bitmap(vocab, 97), synth.modulo_bitmap(vocab, 89), 2)
+    cfg_s = small.cfg
+    if cfg_s["max_seq"] >= 256 + 5000:
+        t0 = time.perf_counter()
+        g = B.st_generate(small, large, rule, prompt, 5000, 20)
+        dt = time.perf_counter() - t0
+        st = g["stats"]
+        res["loop_1p5b_32b_rule"] = {
+            "tok_s": st["n_out"] / dt, "n_out": st["n_out"], "n_handoffs": st["n_handoffs"],
+            "target_catch_up_lengths": [sp["large_prefill_hi"] - sp["large_prefill_lo"] for sp in g["spans"]],
+            "ms_small_decode": st["ms_small_decode"], "ms_large_decode": st["ms_large_decode"],
+            "ms_small_prefill": st["ms_small_prefill"], "ms_large_prefill": st["ms_large_prefill"],
+            "schedule": "rule: previous id % 89 == 0 and id % 97 == 0, target writes 20"}
     # the non-reasoning-speculator schedule (Section 4.3): the target writes the first 100 tokens and takes over for
     # 20 tokens after every delimiter; the delimiter class id % 24 == 0 would give a modify ratio near 44 % on
     # uniform tokens, the realised ratio is reported
@@ -242,7 +260,7 @@ def main():
                                                                        batched=not args.prefill_only)}))
         return
     n_dec = args.decode_steps
-    cfg = synth.model_config("qwen1p5b", max_seq=PROMPT + N_DECODE + 64, max_chunk=PROMPT)
+    cfg = synth.model_config("qwen1p5b", max_seq=max(PROMPT + N_DECODE + 64, 256 + 5000 + 64), max_chunk=PROMPT)
     w = synth.make_weights(cfg, 1, device="cuda")
     model = B.Model(cfg, w)
     prompt = synth.make_prompt(PROMPT, cfg["vocab"], 3)
