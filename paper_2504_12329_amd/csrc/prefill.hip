@@ -32,16 +32,28 @@ __global__ void k_note_fed(int32_t *state, const int32_t *tokens, int index, int
     state[kFed] = tok < 0 ? 0 : (tok >= vocab ? vocab - 1 : tok);
 }
 
+// Extra K slices for the last columns of a split-K result (the ring GEMM's tail): columns >= col0 have n more
+// slices, slice t of row r at part[base + t * stride + r * ld + (column - col0)]; n = 0: none.
+struct PartTail {
+    int col0, n, ld;
+    long long base, stride;
+};
+// the same for a view whose part pointer has been advanced to row `row` of an [rows][h] slice
+static inline PartTail tail_at_row(PartTail t, int row, int h) {
+    t.base += (long long)row * (t.ld - h);
+    return t;
+}
+
 // Threads per row of k_rmsnorm_rows: with few rows a row is one block's serial walk, so the block is made wide.
 static inline int norm_threads(int rows) { return rows <= 512 ? 1024 : 256; }
 
 // x[row] += sum of the pending split-K partial results (fixed order), then y[row] = bf16(rmsnorm(x) * g).
-// part is [n_part][rows][h]; with g == nullptr only the residual update is done.  With Ylo the
+// part is [n_part][rows][h] (plus the extra slices `tail` describes); with g == nullptr only the residual update is done.  With Ylo the
 // normalised row is written as a sum of two bf16 numbers (Y + Ylo), which keeps 16 mantissa bits.
 __global__ __launch_bounds__(1024) void k_rmsnorm_rows(float *__restrict__ X, const float *__restrict__ part,
                                                        int n_part, size_t part_stride, const bf16_t *__restrict__ g,
                                                        bf16_t *__restrict__ Y, bf16_t *__restrict__ Ylo, int h,
-                                                       float eps) {
+                                                       float eps, PartTail tail) {
     __shared__ float red[16];
     float4 *x = reinterpret_cast<float4 *>(X + (size_t)blockIdx.x * h);
     const float4 *p0 = reinterpret_cast<const float4 *>(part + (size_t)blockIdx.x * h);
@@ -61,6 +73,14 @@ __global__ __launch_bounds__(1024) void k_rmsnorm_rows(float *__restrict__ X, co
                 v.y += q[u].y;
                 v.z += q[u].z;
                 v.w += q[u].w;
+            }
+        }
+        if (tail.n && 4 * i >= tail.col0) {
+            const float4 *pt = reinterpret_cast<const float4 *>(part + tail.base + (long long)blockIdx.x * tail.ld +
+                                                                (4 * i - tail.col0));
+            for (int t = 0; t < tail.n; ++t) {
+                const float4 q = pt[t * (tail.stride / 4)];
+                v.x += q.x, v.y += q.y, v.z += q.z, v.w += q.w;
             }
         }
         if (n_part) x[i] = v;
@@ -108,6 +128,9 @@ constexpr int kBK = 32, kLdsStride = kBK + 8;  // 80-byte rows: conflict-free 16
 
 struct GemmGrid {
     int My, Nx, TY, TX, YB, blocks;
+    // ring kernel only: a tail of column tiles [tail_x0, ...) whose K range is cut into tail_s slices of tail_kps
+    // columns (block ids from `blocks` on; tail_tiles = 0: none)
+    int tail_x0, tail_tiles, tail_s, tail_kps;
 };
 
 // BM x BNR block tile (BNR = rows of the weight tile), WGM x WGN waves, wave tile (BM/WGM) x (BNR/WGN).
@@ -325,22 +348,50 @@ __global__ __launch_bounds__(256) void k_gemm_ring(const bf16_t *__restrict__ A,
                                                    int M, int N, int K, int kps, float *__restrict__ part,
                                                    bf16_t *__restrict__ outb, int ldo, GemmGrid gg) {
     extern __shared__ __align__(16) unsigned char ring[];
-    int x, y;
-    {
+    int x, y, kbeg, kend;
+    float *pz = nullptr;  // where this block's fp32 tile goes (plain form), row stride ldp
+    int ldp = N;
+    if ((int)blockIdx.x < gg.blocks) {
+        // XCD e owns the column tiles e, e + 8, ...; its j-th block walks them in groups of TX columns, TY x TX
+        // patches down the rows of a group (a patch = the 32 blocks its compute units run together).  A last group
+        // of fewer columns gets narrower patches, so unused ids come only at the end of the range: ids that are
+        // dealt out and return at once, interleaved with working ones, leave the blocks unevenly spread over an
+        // XCD's shader engines (measured: the O / down projections of a 4096-row chunk took 40 % longer that way).
         const int id = blockIdx.x, xcd = id & 7, j = id >> 3;
-        const int st = j >> 5, r = j & 31;
-        const int tx = r % gg.TX, ty = r / gg.TX;
-        const int yb = st % gg.YB, xb = st / gg.YB;
-        y = yb * gg.TY + ty;
-        x = (xb * gg.TX + tx) * 8 + xcd;
-        if (y >= gg.My || x >= gg.Nx) return;
+        const int nc = (gg.Nx - xcd + 7) >> 3, myp = gg.YB * gg.TY;
+        const int full = nc / gg.TX * gg.TX;
+        int cols, c0, jj;
+        if (j < full * myp) {
+            cols = gg.TX, c0 = j / (cols * myp) * cols, jj = j % (cols * myp);
+        } else {
+            cols = nc - full, c0 = full, jj = j - full * myp;
+            if (cols <= 0 || jj >= cols * myp) return;
+        }
+        const int r = jj % (cols * gg.TY);
+        y = jj / (cols * gg.TY) * gg.TY + r / cols;
+        x = (c0 + r % cols) * 8 + xcd;
+        if (y >= gg.My) return;
+        kbeg = blockIdx.y * kps, kend = min(K, kbeg + kps);
+        if (!DUAL) pz = part + (size_t)blockIdx.y * M * N;
+    } else {
+        // tail: a unit is one K slice of a patch of 32 tiles (column-major over the tail's columns); unit u runs on
+        // XCD u % 8, so the blocks that share panels at the same K positions share an L2
+        const int t = blockIdx.x - gg.blocks, xcd = t & 7, j = t >> 3;
+        const int u = (j >> 5) * 8 + xcd, q = (u / gg.tail_s) * 32 + (j & 31), sl = u % gg.tail_s;
+        if (q >= gg.tail_tiles) return;
+        x = gg.tail_x0 + q / gg.My, y = q % gg.My;
+        kbeg = sl * gg.tail_kps, kend = min(K, kbeg + gg.tail_kps);
+        const int col0 = gg.tail_x0 * 256;
+        if (sl == 0)
+            pz = part;
+        else
+            ldp = N - col0, pz = part + (size_t)M * N + (size_t)(sl - 1) * M * ldp - col0;
     }
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave >> 1, wn = wave & 1;
     const int l32 = lane & 31, kg = lane >> 5;
     const int m0 = y * 256, n0 = x * (DUAL ? 128 : 256);
-    const int kbeg = blockIdx.y * kps;
-    const int nk = (min(K, kbeg + kps) - kbeg) / kRingBK;
+    const int nk = (kend - kbeg) / kRingBK;
     const uint32_t ring0 = (uint32_t)(uintptr_t)ring;  // LDS byte offset of the ring (low half of the flat address)
 
     // direct loads: instruction i of a wave fills LDS rows [(wave*8+i)*8, +8) of a slot, lane -> (row lane/8,
@@ -465,7 +516,6 @@ __global__ __launch_bounds__(256) void k_gemm_ring(const bf16_t *__restrict__ A,
     kstep(kt++, ic<0>{});
 
     // epilogue: register r of a 32x32 tile is row 8*(r/4) + 4*(lane/32) + r%4, column lane%32
-    float *pz = DUAL ? nullptr : part + (size_t)blockIdx.y * M * N;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
 #pragma unroll
@@ -485,7 +535,7 @@ __global__ __launch_bounds__(256) void k_gemm_ring(const bf16_t *__restrict__ A,
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const int col = n0 + wn * 128 + j * 32 + l32;
-                    if (col < N) pz[(size_t)row * N + col] = acc[i][j][r];
+                    if (col < N) pz[(size_t)row * ldp + col] = acc[i][j][r];
                 }
             }
         }
@@ -687,7 +737,8 @@ __global__ __launch_bounds__(SPEC ? 512 : 256) void k_gemm_stream(const bf16_t *
 __global__ void k_rope_append(const float *__restrict__ part, int n_part, size_t part_stride,
                               const bf16_t *__restrict__ bias, const float2 *__restrict__ rope,
                               bf16_t *__restrict__ qb, bf16_t *__restrict__ qb_lo, bf16_t *__restrict__ kc,
-                              bf16_t *__restrict__ vc, int pos0, int nq, int nkv, int d, int max_seq) {
+                              bf16_t *__restrict__ vc, int pos0, int nq, int nkv, int d, int max_seq,
+                              PartTail tail) {
     const int row = blockIdx.x, head = blockIdx.y, i = threadIdx.x, half = d >> 1;
     const int pos = pos0 + row;
     const size_t off = (size_t)row * (nq + 2 * nkv) * d + head * d;
@@ -696,6 +747,13 @@ __global__ void k_rope_append(const float *__restrict__ part, int n_part, size_t
         const float *src = part + (size_t)s * part_stride + off;
         lo += src[i];
         hi += src[i + half];
+    }
+    if (tail.n && head * d >= tail.col0) {  // col0 is a multiple of 256, so a head lies on one side of it
+        const float *src = part + tail.base + (long long)row * tail.ld + (head * d - tail.col0);
+        for (int t = 0; t < tail.n; ++t, src += tail.stride) {
+            lo += src[i];
+            hi += src[i + half];
+        }
     }
     if (bias) {
         lo += bf16_to_f32(bias[head * d + i]);
@@ -1385,7 +1443,8 @@ constexpr int kSmallRows = 64;
 
 template <bool DUAL>
 static int gemm(const Model &m, const bf16_t *A, const bf16_t *Alo, int lda, const bf16_t *B, int M, int N, int K,
-                bf16_t *outb, bf16_t *outlo, int ldo) {
+                bf16_t *outb, bf16_t *outlo, int ldo, PartTail *tail = nullptr) {
+    if (tail) *tail = PartTail{};
     const bool big = !Alo && M >= kBigRows && K % kRingBK == 0 && K >= 2 * kRingBK;
     if (!DUAL && Alo && M <= kSplitRows && K % kRingBK == 0) {
         const StreamShape sh = stream_shape(m, M, N, K);
@@ -1414,6 +1473,7 @@ static int gemm(const Model &m, const bf16_t *A, const bf16_t *Alo, int lda, con
     gg.YB = (gg.My + gg.TY - 1) / gg.TY;
     const int nxl = (gg.Nx + 7) / 8, xb = (nxl + gg.TX - 1) / gg.TX;
     gg.blocks = 8 * xb * gg.YB * 32;
+    gg.tail_x0 = gg.tail_tiles = 0, gg.tail_s = 1, gg.tail_kps = K;
     int splits = 1, kps = K;
     const int tiles = gg.My * gg.Nx;
     const size_t cap = partial_floats(m.c);
@@ -1432,6 +1492,29 @@ static int gemm(const Model &m, const bf16_t *A, const bf16_t *Alo, int lda, con
         kps = (nk + splits - 1) / splits * kRingBK;
         splits = (K + kps - 1) / kps;
         if (K - (splits - 1) * kps < 2 * kRingBK) splits = 1, kps = K;  // a last slice of one step: do not split
+        // Or: whole rounds of 256 tiles at full K, and only the column tiles left over cut into K slices (a
+        // consumer that takes a PartTail adds their extra slices).  320 tiles with K = 432 steps: three rounds of
+        // half the K range each become one round at full K plus one round of quarter slices.
+        if (tail && tiles > 256 && tiles % 256 && 256 % gg.My == 0) {
+            const int nx_main = tiles / 256 * 256 / gg.My, tail_tiles = (gg.Nx - nx_main) * gg.My;
+            const int ld = N - nx_main * 256;
+            long tbest = -1;
+            int ts = 1;
+            for (int s = 1; s <= 8; ++s) {
+                const int steps = (nk + s - 1) / s;
+                if (s > 1 && (steps < 4 || nk - (s - 1) * steps < 2)) break;
+                if ((size_t)M * N + (size_t)(s - 1) * M * ld > cap) break;
+                const long cost = (long)((tail_tiles * s + 255) / 256) * (steps + 6);
+                if (tbest < 0 || cost < tbest) tbest = cost, ts = s;
+            }
+            if ((long)(tiles / 256) * (nk + 6) + tbest < best) {
+                gg.tail_x0 = nx_main, gg.tail_tiles = tail_tiles, gg.tail_s = ts;
+                gg.tail_kps = (nk + ts - 1) / ts * kRingBK;
+                gg.Nx = nx_main;  // the main part: blocks of the usual mapping over the first nx_main column tiles
+                splits = 1, kps = K;
+                *tail = PartTail{nx_main * 256, ts - 1, ld, (long long)M * N, (long long)M * ld};
+            }
+        }
     } else if (!DUAL) {
         // K slices: enough blocks to keep every CU streaming weights (the small tiles have two waves
         // each, so they need more of them), bounded by the partial-result buffer
@@ -1444,7 +1527,9 @@ static int gemm(const Model &m, const bf16_t *A, const bf16_t *Alo, int lda, con
         if (kps < 256) kps = 256;
         splits = (K + kps - 1) / kps;
     }
-    dim3 grid(gg.blocks, splits);
+    if (big) gg.blocks = 8 * ((gg.Nx + 7) / 8) * gg.YB * gg.TY;  // the ring kernel numbers its tiles without gaps
+    const int tail_units = (gg.tail_tiles + 31) / 32 * gg.tail_s;
+    dim3 grid(gg.blocks + (tail_units + 7) / 8 * 256, splits);
     if (big)
         ring_launch<DUAL>(m, grid, A, lda, B, M, N, K, kps, outb, ldo, gg);
     else if (Alo && BM == 32)
@@ -1506,18 +1591,19 @@ void launch_prefill_layers(const Model &m, int32_t pos0, int32_t n) {
     hipLaunchKernelGGL(k_embed_rows, dim3(n), dim3(256), 0, m.stream, m.embed, w.tokens, w.x, h, c.vocab);
     hipLaunchKernelGGL(k_note_fed, dim3(1), dim3(1), 0, m.stream, w.state, w.tokens, n - 1, c.vocab);
     int pending = 0;  // K slices of the previous layer's down projection still to be added to x
+    PartTail pend_tail{}, tq{}, to{};  // extra slices of the tail columns (long chunks only)
     for (int l = 0; l < c.n_layers; ++l) {
         size_t lofs = (size_t)l * nkv * c.max_seq * d;
         hipLaunchKernelGGL(k_rmsnorm_rows, dim3(n), dim3(norm_threads(n)), 0, m.stream, w.x, w.qkv, pending, (size_t)n * h,
-                           m.norm_attn[l], w.xn, xn_lo, h, c.rms_eps);
-        int sq = gemm<false>(m, w.xn, xn_lo, h, m.wqkv[l], n, qkv, h, nullptr, nullptr, 0);
+                           m.norm_attn[l], w.xn, xn_lo, h, c.rms_eps, pend_tail);
+        int sq = gemm<false>(m, w.xn, xn_lo, h, m.wqkv[l], n, qkv, h, nullptr, nullptr, 0, &tq);
         hipLaunchKernelGGL(k_rope_append, dim3(n, nq + 2 * nkv), dim3(d / 2), 0, m.stream, w.qkv, sq,
                            (size_t)n * qkv, m.bqkv[l], w.rope, w.qb, qb_lo, m.kcache + lofs, m.vcache + lofs, pos0, nq, nkv,
-                           d, c.max_seq);
+                           d, c.max_seq, tq);
         launch_flash(m, w.qb, qb_lo, m.kcache + lofs, m.vcache + lofs, w.attn, attn_lo, n, pos0);
-        int so = gemm<false>(m, w.attn, attn_lo, qd, m.wo[l], n, h, qd, nullptr, nullptr, 0);
+        int so = gemm<false>(m, w.attn, attn_lo, qd, m.wo[l], n, h, qd, nullptr, nullptr, 0, &to);
         hipLaunchKernelGGL(k_rmsnorm_rows, dim3(n), dim3(norm_threads(n)), 0, m.stream, w.x, w.qkv, so, (size_t)n * h,
-                           m.norm_mlp[l], w.xn, xn_lo, h, c.rms_eps);
+                           m.norm_mlp[l], w.xn, xn_lo, h, c.rms_eps, to);
         if (n <= (h % kRingBK == 0 ? kSplitRows : kSmallRows)) {  // small chunk: gate/up as a plain split-K GEMM over
                                                                    // all 2I rows, SwiGLU in the consumer
             int sg = gemm<false>(m, w.xn, xn_lo, h, m.wgu[l], n, 2 * I, h, nullptr, nullptr, 0);
@@ -1526,11 +1612,12 @@ void launch_prefill_layers(const Model &m, int32_t pos0, int32_t n) {
         } else {
             gemm<true>(m, w.xn, xn_lo, h, m.wgu[l], n, I, h, w.act, act_lo, I);
         }
-        pending = gemm<false>(m, w.act, act_lo, I, m.wdown[l], n, h, I, nullptr, nullptr, 0);
+        pending = gemm<false>(m, w.act, act_lo, I, m.wdown[l], n, h, I, nullptr, nullptr, 0, &pend_tail);
     }
     // the head needs the last row only: fold the last down projection into it
     hipLaunchKernelGGL(k_rmsnorm_rows, dim3(1), dim3(norm_threads(1)), 0, m.stream, w.x + (size_t)(n - 1) * h,
-                       w.qkv + (size_t)(n - 1) * h, pending, (size_t)n * h, nullptr, nullptr, nullptr, h, c.rms_eps);
+                       w.qkv + (size_t)(n - 1) * h, pending, (size_t)n * h, nullptr, nullptr, nullptr, h, c.rms_eps,
+                       tail_at_row(pend_tail, n - 1, h));
 }
 
 // ---------------------------------------------------------------------------------------
@@ -1634,7 +1721,7 @@ void launch_batch_step(const Model &m, const BatchRows &b, int n, int attn_block
     for (int l = 0; l < c.n_layers; ++l) {
         const size_t lofs = (size_t)l * nkv * c.max_seq * d;
         hipLaunchKernelGGL(k_rmsnorm_rows, dim3(n), dim3(norm_threads(n)), 0, m.stream, w.x, w.qkv, pending, (size_t)n * h,
-                           m.norm_attn[l], w.xn, w.xn_lo, h, c.rms_eps);
+                           m.norm_attn[l], w.xn, w.xn_lo, h, c.rms_eps, PartTail{});
         const int sq = gemm<false>(m, w.xn, w.xn_lo, h, m.wqkv[l], n, qkv, h, nullptr, nullptr, 0);
         hipLaunchKernelGGL(k_rope_append_rows, dim3(n, nq + 2 * nkv), dim3(d / 2), 0, m.stream, w.qkv, sq,
                            (size_t)n * qkv, m.bqkv[l], w.rope, b.q_rows, (bf16_t *)nullptr, (bf16_t *)nullptr,
@@ -1642,14 +1729,14 @@ void launch_batch_step(const Model &m, const BatchRows &b, int n, int attn_block
         launch_attn_rows(m, l, m.stream, attn_blocks, rows, n, b.q_rows, b.part_ml, b.part_acc, b.o_rows);
         const int so = gemm<false>(m, w.attn, w.attn_lo, qd, m.wo[l], n, h, qd, nullptr, nullptr, 0);
         hipLaunchKernelGGL(k_rmsnorm_rows, dim3(n), dim3(norm_threads(n)), 0, m.stream, w.x, w.qkv, so, (size_t)n * h,
-                           m.norm_mlp[l], w.xn, w.xn_lo, h, c.rms_eps);
+                           m.norm_mlp[l], w.xn, w.xn_lo, h, c.rms_eps, PartTail{});
         const int sg = gemm<false>(m, w.xn, w.xn_lo, h, m.wgu[l], n, 2 * I, h, nullptr, nullptr, 0);
         hipLaunchKernelGGL(k_swiglu_rows, dim3((I / 4 + 255) / 256, n), dim3(256), 0, m.stream, w.qkv, sg,
                            (size_t)n * 2 * I, I, w.act, w.act_lo);
         pending = gemm<false>(m, w.act, w.act_lo, I, m.wdown[l], n, h, I, nullptr, nullptr, 0);
     }
     hipLaunchKernelGGL(k_rmsnorm_rows, dim3(n), dim3(norm_threads(n)), 0, m.stream, w.x, w.qkv, pending, (size_t)n * h,
-                       m.final_norm, w.xn, w.xn_lo, h, c.rms_eps);
+                       m.final_norm, w.xn, w.xn_lo, h, c.rms_eps, PartTail{});
     const int sl = gemm<false>(m, w.xn, w.xn_lo, h, m.lm_head, n, c.vocab, h, nullptr, nullptr, 0);
     hipLaunchKernelGGL(k_argmax_rows, dim3(n), dim3(1024), 0, m.stream, w.qkv, sl, (size_t)n * c.vocab, c.vocab,
                        b.logits, b.row_next);
@@ -1685,7 +1772,7 @@ void launch_prefill_varlen(const Model &m, const BatchRows &b, const VarlenSeg *
     for (int l = 0; l < c.n_layers; ++l) {
         const size_t lofs = (size_t)l * nkv * c.max_seq * d;
         hipLaunchKernelGGL(k_rmsnorm_rows, dim3(R), dim3(norm_threads(R)), 0, m.stream, w.x, w.qkv, pending, (size_t)R * h,
-                           m.norm_attn[l], w.xn, xn_lo, h, c.rms_eps);
+                           m.norm_attn[l], w.xn, xn_lo, h, c.rms_eps, PartTail{});
         const int sq = gemm<false>(m, w.xn, xn_lo, h, m.wqkv[l], R, qkv, h, nullptr, nullptr, 0);
         hipLaunchKernelGGL(k_rope_append_rows, dim3(R, nq + 2 * nkv), dim3(d / 2), 0, m.stream, w.qkv, sq,
                            (size_t)R * qkv, m.bqkv[l], w.rope, (float *)nullptr, w.qb, qb_lo, m.kcache + lofs,
@@ -1698,7 +1785,7 @@ void launch_prefill_varlen(const Model &m, const BatchRows &b, const VarlenSeg *
         }
         const int so = gemm<false>(m, w.attn, attn_lo, qd, m.wo[l], R, h, qd, nullptr, nullptr, 0);
         hipLaunchKernelGGL(k_rmsnorm_rows, dim3(R), dim3(norm_threads(R)), 0, m.stream, w.x, w.qkv, so, (size_t)R * h,
-                           m.norm_mlp[l], w.xn, xn_lo, h, c.rms_eps);
+                           m.norm_mlp[l], w.xn, xn_lo, h, c.rms_eps, PartTail{});
         if (R <= (h % kRingBK == 0 ? kSplitRows : kSmallRows)) {
             const int sg = gemm<false>(m, w.xn, xn_lo, h, m.wgu[l], R, 2 * I, h, nullptr, nullptr, 0);
             hipLaunchKernelGGL(k_swiglu_rows, dim3((I / 4 + 255) / 256, R), dim3(256), 0, m.stream, w.qkv, sg,
@@ -1712,7 +1799,7 @@ void launch_prefill_varlen(const Model &m, const BatchRows &b, const VarlenSeg *
     hipLaunchKernelGGL(k_gather_rows, dim3(n_seg), dim3(256), 0, m.stream, w.x, w.qkv, pending, (size_t)R * h,
                        b.row_next, b.o_rows, h);
     hipLaunchKernelGGL(k_rmsnorm_rows, dim3(n_seg), dim3(norm_threads(n_seg)), 0, m.stream, b.o_rows, (const float *)nullptr, 0,
-                       (size_t)0, m.final_norm, w.xn, w.xn_lo, h, c.rms_eps);
+                       (size_t)0, m.final_norm, w.xn, w.xn_lo, h, c.rms_eps, PartTail{});
     const int sl = gemm<false>(m, w.xn, w.xn_lo, h, m.lm_head, n_seg, c.vocab, h, nullptr, nullptr, 0);
     hipLaunchKernelGGL(k_argmax_rows, dim3(n_seg), dim3(1024), 0, m.stream, w.qkv, sl, (size_t)n_seg * c.vocab,
                        c.vocab, b.logits, b.row_next);

@@ -114,6 +114,33 @@ def test_prefill_kernel_regime_boundaries(m):
     g.close()
 
 
+@pytest.mark.parametrize("name", ["qwen32b", "qwen7b"])
+def test_4096_row_chunk_agrees_with_1024_row_chunks(name):
+    """A 4096-row pass has more 256 x 256 output tiles than compute units in the O / down projections (32B shape)
+    or the QKV projection (7B shape); the columns left over after whole rounds are cut into K slices of their own,
+    which 1024-row passes never do.  Same tokens, both ways, on 300 cached keys (2 layers; the oracle is out of
+    reach at this size, the 1024-row path is checked against it in the tests above)."""
+    print_case(f"{name} shape, 2 layers: 300 cached + 4096 tokens as one chunk and as four")
+    cfg = synth.model_config(name, max_seq=4500, max_chunk=4096, n_layers=2)
+    g = B.Model(cfg, synth.make_weights(cfg, 21, device="cuda"))
+    toks = synth.make_prompt(4400, cfg["vocab"], 22)
+    g.prefill(toks[:300], want_logits=False)
+    a, ta = g.prefill(toks[300:4396])
+    g.truncate(300)
+    for lo in range(300, 4396 - 1024, 1024):
+        g.prefill(toks[lo:lo + 1024], want_logits=False)
+    b, tb = g.prefill(toks[3372:4396])
+    err = rel_err(a, b)
+    print_case("relative logit difference", err)
+    assert err <= LOGIT_TOL
+    c, _ = g.decode_step(int(toks[4396]))                 # the caches the two ways left behind agree as well
+    g.truncate(300)
+    g.prefill(toks[300:4396], want_logits=False)
+    d, _ = g.decode_step(int(toks[4396]))
+    assert rel_err(c, d) <= LOGIT_TOL
+    g.close()
+
+
 def test_prefill_is_bit_reproducible():
     """Split-K partial sums and split-key attention are merged in fixed orders: same input, same bits."""
     cfg = synth.model_config("qwen1p5b", max_seq=1400, max_chunk=1024, n_layers=2)
