@@ -128,9 +128,6 @@ constexpr int kBK = 32, kLdsStride = kBK + 8;  // 80-byte rows: conflict-free 16
 
 struct GemmGrid {
     int My, Nx, TY, TX, YB, blocks;
-    // ring kernel only: a tail of column tiles [tail_x0, ...) whose K range is cut into tail_s slices of tail_kps
-    // columns (block ids from `blocks` on; tail_tiles = 0: none)
-    int tail_x0, tail_tiles, tail_s, tail_kps;
 };
 
 // BM x BNR block tile (BNR = rows of the weight tile), WGM x WGN waves, wave tile (BM/WGM) x (BNR/WGN).
@@ -343,36 +340,47 @@ __device__ __forceinline__ void static_for(F &&f) {  // f(ic<0>{}), ..., f(ic<N-
     }
 }
 
+// Block ids -> work of the ring kernel.  Main part: S K slices of kps columns over My x Nx tiles, numbered slice by
+// slice, inside a slice by groups of TX column tiles, inside a group by TY x TX patches down the rows (narrower
+// patches at the edges, so the numbering has no gaps); XCD e (= block id % 8) takes the `per` consecutive numbers
+// from e * per on.  The 32 blocks an XCD runs together are then one patch of one K slice -- the panels they stream
+// are shared in that XCD's L2 -- and every XCD gets the same number of blocks.  Ids that are dealt out but return at
+// once must not be interleaved with working ones: the working blocks then sit unevenly on an XCD's shader engines
+// (measured: the O / down projections of a 4096-row chunk took 40 % longer that way).
+// Tail (block ids from `blocks` on): the column tiles from tail_x0 on, their K range cut into tail_s slices of
+// tail_kps columns; a unit is one slice of 32 tiles (column-major) and unit u runs on XCD u % 8.
+struct RingGrid {
+    int My, Nx, TY, TX, S, kps, per, blocks;
+    int tail_x0, tail_tiles, tail_s, tail_kps;
+};
+
 template <bool DUAL>
 __global__ __launch_bounds__(256) void k_gemm_ring(const bf16_t *__restrict__ A, int lda, const bf16_t *__restrict__ B,
-                                                   int M, int N, int K, int kps, float *__restrict__ part,
-                                                   bf16_t *__restrict__ outb, int ldo, GemmGrid gg) {
+                                                   int M, int N, int K, float *__restrict__ part,
+                                                   bf16_t *__restrict__ outb, int ldo, RingGrid gg) {
     extern __shared__ __align__(16) unsigned char ring[];
     int x, y, kbeg, kend;
     float *pz = nullptr;  // where this block's fp32 tile goes (plain form), row stride ldp
     int ldp = N;
     if ((int)blockIdx.x < gg.blocks) {
-        // XCD e owns the column tiles e, e + 8, ...; its j-th block walks them in groups of TX columns, TY x TX
-        // patches down the rows of a group (a patch = the 32 blocks its compute units run together).  A last group
-        // of fewer columns gets narrower patches, so unused ids come only at the end of the range: ids that are
-        // dealt out and return at once, interleaved with working ones, leave the blocks unevenly spread over an
-        // XCD's shader engines (measured: the O / down projections of a 4096-row chunk took 40 % longer that way).
-        const int id = blockIdx.x, xcd = id & 7, j = id >> 3;
-        const int nc = (gg.Nx - xcd + 7) >> 3, myp = gg.YB * gg.TY;
-        const int full = nc / gg.TX * gg.TX;
+        const int j = blockIdx.x >> 3, T = gg.My * gg.Nx;
+        const int f = (blockIdx.x & 7) * gg.per + j;
+        if (j >= gg.per || f >= gg.S * T) return;  // only at the end of an XCD's range
+        const int sl = f / T, fs = f % T;
+        const int full_c = gg.Nx / gg.TX * gg.TX, full_r = gg.My / gg.TY * gg.TY;
         int cols, c0, jj;
-        if (j < full * myp) {
-            cols = gg.TX, c0 = j / (cols * myp) * cols, jj = j % (cols * myp);
-        } else {
-            cols = nc - full, c0 = full, jj = j - full * myp;
-            if (cols <= 0 || jj >= cols * myp) return;
-        }
-        const int r = jj % (cols * gg.TY);
-        y = jj / (cols * gg.TY) * gg.TY + r / cols;
-        x = (c0 + r % cols) * 8 + xcd;
-        if (y >= gg.My) return;
-        kbeg = blockIdx.y * kps, kend = min(K, kbeg + kps);
-        if (!DUAL) pz = part + (size_t)blockIdx.y * M * N;
+        if (fs < full_c * gg.My)
+            cols = gg.TX, c0 = fs / (cols * gg.My) * cols, jj = fs % (cols * gg.My);
+        else
+            cols = gg.Nx - full_c, c0 = full_c, jj = fs - full_c * gg.My;
+        int r, y0;
+        if (jj < cols * full_r)
+            y0 = jj / (cols * gg.TY) * gg.TY, r = jj % (cols * gg.TY);
+        else
+            y0 = full_r, r = jj - cols * full_r;
+        y = y0 + r / cols, x = c0 + r % cols;
+        kbeg = sl * gg.kps, kend = min(K, kbeg + gg.kps);
+        if (!DUAL) pz = part + (size_t)sl * M * N;
     } else {
         // tail: a unit is one K slice of a patch of 32 tiles (column-major over the tail's columns); unit u runs on
         // XCD u % 8, so the blocks that share panels at the same K positions share an L2
@@ -1370,7 +1378,7 @@ static void gemm_launch(const Model &m, dim3 grid, const bf16_t *A, const bf16_t
 
 template <bool DUAL>
 static void ring_launch(const Model &m, dim3 grid, const bf16_t *A, int lda, const bf16_t *B, int M, int N, int K,
-                        int kps, bf16_t *outb, int ldo, const GemmGrid &gg) {
+                        bf16_t *outb, int ldo, const RingGrid &gg) {
     auto kern = k_gemm_ring<DUAL>;
     static bool raised = false;  // more than 64 KB of dynamic LDS has to be allowed once per kernel
     if (!raised) {
@@ -1378,7 +1386,7 @@ static void ring_launch(const Model &m, dim3 grid, const bf16_t *A, int lda, con
                                   kRingLds);
         raised = true;
     }
-    hipLaunchKernelGGL(kern, grid, dim3(256), kRingLds, m.stream, A, lda, B, M, N, K, kps, m.ws.qkv, outb, ldo, gg);
+    hipLaunchKernelGGL(kern, grid, dim3(256), kRingLds, m.stream, A, lda, B, M, N, K, m.ws.qkv, outb, ldo, gg);
 }
 
 // Shape of a streaming GEMM launch: K columns per stage, weight tiles per block (4..8), K slices, ring depths.
@@ -1437,6 +1445,65 @@ static StreamShape stream_shape(const Model &m, int M, int N, int K) {
     return best;
 }
 
+// The 256 x 256 ring kernel on a chunk of more than kSplitRows rows: K slices and block numbering.  Returns the
+// number of full-width K slices written to ws.qkv (0 for the fused SwiGLU form).
+template <bool DUAL>
+static int ring_gemm(const Model &m, const bf16_t *A, int lda, const bf16_t *B, int M, int N, int K, bf16_t *outb,
+                     int ldo, PartTail *tail) {
+    RingGrid gg;
+    gg.My = (M + 255) / 256;
+    gg.Nx = (N + (DUAL ? 128 : 256) - 1) / (DUAL ? 128 : 256);
+    gg.TY = 1;
+    while (gg.TY * 2 <= gg.My && gg.TY < 8) gg.TY *= 2;
+    gg.TX = 32 / gg.TY;
+    gg.S = 1, gg.kps = K;
+    gg.tail_x0 = gg.tail_tiles = 0, gg.tail_s = 1, gg.tail_kps = K;
+    const int tiles = gg.My * gg.Nx, nk = K / kRingBK;
+    if (!DUAL) {
+        // One block per CU at a time: pick the K slices that minimise (rounds of 256 blocks) x (K steps per
+        // slice + a fixed cost for filling the ring and writing the tile)
+        const size_t cap = partial_floats(m.c);
+        long best = -1;
+        for (int s = 1; s <= 8; ++s) {
+            const int steps = (nk + s - 1) / s;
+            if (steps < 4 && s > 1) break;
+            if (s > 1 && (size_t)s * M * N > cap) break;
+            const long cost = (long)((tiles * s + 255) / 256) * (steps + 6);
+            if (best < 0 || cost < best) best = cost, gg.S = s;
+        }
+        gg.kps = (nk + gg.S - 1) / gg.S * kRingBK;
+        gg.S = (K + gg.kps - 1) / gg.kps;
+        if (K - (gg.S - 1) * gg.kps < 2 * kRingBK) gg.S = 1, gg.kps = K;  // a last slice of one step: do not split
+        // Or: whole rounds of 256 tiles at full K, and only the column tiles left over cut into K slices (a
+        // consumer that takes a PartTail adds their extra slices).  320 tiles with K = 432 steps: three rounds of
+        // half the K range each become one round at full K plus one round of quarter slices.
+        if (tail && tiles > 256 && tiles % 256 && 256 % gg.My == 0) {
+            const int nx_main = tiles / 256 * 256 / gg.My, tail_tiles = (gg.Nx - nx_main) * gg.My;
+            const int ld = N - nx_main * 256;
+            long tbest = -1;
+            int ts = 1;
+            for (int s = 1; s <= 8; ++s) {
+                const int steps = (nk + s - 1) / s;
+                if (s > 1 && (steps < 4 || nk - (s - 1) * steps < 2)) break;
+                if ((size_t)M * N + (size_t)(s - 1) * M * ld > cap) break;
+                const long cost = (long)((tail_tiles * s + 255) / 256) * (steps + 6);
+                if (tbest < 0 || cost < tbest) tbest = cost, ts = s;
+            }
+            if ((long)(tiles / 256) * (nk + 6) + tbest < best) {
+                gg.tail_x0 = nx_main, gg.tail_tiles = tail_tiles, gg.tail_s = ts;
+                gg.tail_kps = (nk + ts - 1) / ts * kRingBK;
+                gg.Nx = nx_main, gg.S = 1, gg.kps = K;  // the main part: the first nx_main column tiles at full K
+                *tail = PartTail{nx_main * 256, ts - 1, ld, (long long)M * N, (long long)M * ld};
+            }
+        }
+    }
+    gg.per = (gg.S * gg.My * gg.Nx + 7) / 8;
+    gg.blocks = 8 * gg.per;
+    const int tail_units = (gg.tail_tiles + 31) / 32 * gg.tail_s;
+    ring_launch<DUAL>(m, dim3(gg.blocks + (tail_units + 7) / 8 * 256), A, lda, B, M, N, K, outb, ldo, gg);
+    return DUAL ? 0 : gg.S;
+}
+
 // Two-term chunks (at most kSplitRows rows) use the streaming kernel and an unfused SwiGLU wherever K is a multiple
 // of 64; otherwise the register-staged kernel, with many K slices and an unfused SwiGLU up to kSmallRows rows.
 constexpr int kSmallRows = 64;
@@ -1460,10 +1527,11 @@ static int gemm(const Model &m, const bf16_t *A, const bf16_t *Alo, int lda, con
         }
         return sh.splits;
     }
+    if (big) return ring_gemm<DUAL>(m, A, lda, B, M, N, K, outb, ldo, tail);
     // (K not a multiple of 64) two-term chunks of at most 32 / 64 rows use 32- / 64-row tiles with two waves: less
     // LDS per block, so more blocks per CU keep more of the weight stream in flight
-    const int BM = big ? 256 : (Alo && M <= 32) ? 32 : (Alo && M <= 64) ? 64 : 128;
-    const int BNO = (big ? 256 : 128) / (DUAL ? 2 : 1);
+    const int BM = (Alo && M <= 32) ? 32 : (Alo && M <= 64) ? 64 : 128;
+    const int BNO = 128 / (DUAL ? 2 : 1);
     GemmGrid gg;
     gg.My = (M + BM - 1) / BM;
     gg.Nx = (N + BNO - 1) / BNO;
@@ -1473,49 +1541,10 @@ static int gemm(const Model &m, const bf16_t *A, const bf16_t *Alo, int lda, con
     gg.YB = (gg.My + gg.TY - 1) / gg.TY;
     const int nxl = (gg.Nx + 7) / 8, xb = (nxl + gg.TX - 1) / gg.TX;
     gg.blocks = 8 * xb * gg.YB * 32;
-    gg.tail_x0 = gg.tail_tiles = 0, gg.tail_s = 1, gg.tail_kps = K;
     int splits = 1, kps = K;
     const int tiles = gg.My * gg.Nx;
     const size_t cap = partial_floats(m.c);
-    if (!DUAL && big) {
-        // One block per CU at a time: pick the K slices that minimise (rounds of 256 blocks) x (K steps per
-        // slice + a fixed cost for filling the ring and writing the tile)
-        const int nk = K / kRingBK;
-        long best = -1;
-        for (int s = 1; s <= 8; ++s) {
-            const int steps = (nk + s - 1) / s;
-            if (steps < 4 && s > 1) break;
-            if (s > 1 && (size_t)s * M * N > cap) break;
-            const long cost = (long)((tiles * s + 255) / 256) * (steps + 6);
-            if (best < 0 || cost < best) best = cost, splits = s;
-        }
-        kps = (nk + splits - 1) / splits * kRingBK;
-        splits = (K + kps - 1) / kps;
-        if (K - (splits - 1) * kps < 2 * kRingBK) splits = 1, kps = K;  // a last slice of one step: do not split
-        // Or: whole rounds of 256 tiles at full K, and only the column tiles left over cut into K slices (a
-        // consumer that takes a PartTail adds their extra slices).  320 tiles with K = 432 steps: three rounds of
-        // half the K range each become one round at full K plus one round of quarter slices.
-        if (tail && tiles > 256 && tiles % 256 && 256 % gg.My == 0) {
-            const int nx_main = tiles / 256 * 256 / gg.My, tail_tiles = (gg.Nx - nx_main) * gg.My;
-            const int ld = N - nx_main * 256;
-            long tbest = -1;
-            int ts = 1;
-            for (int s = 1; s <= 8; ++s) {
-                const int steps = (nk + s - 1) / s;
-                if (s > 1 && (steps < 4 || nk - (s - 1) * steps < 2)) break;
-                if ((size_t)M * N + (size_t)(s - 1) * M * ld > cap) break;
-                const long cost = (long)((tail_tiles * s + 255) / 256) * (steps + 6);
-                if (tbest < 0 || cost < tbest) tbest = cost, ts = s;
-            }
-            if ((long)(tiles / 256) * (nk + 6) + tbest < best) {
-                gg.tail_x0 = nx_main, gg.tail_tiles = tail_tiles, gg.tail_s = ts;
-                gg.tail_kps = (nk + ts - 1) / ts * kRingBK;
-                gg.Nx = nx_main;  // the main part: blocks of the usual mapping over the first nx_main column tiles
-                splits = 1, kps = K;
-                *tail = PartTail{nx_main * 256, ts - 1, ld, (long long)M * N, (long long)M * ld};
-            }
-        }
-    } else if (!DUAL) {
+    if (!DUAL) {
         // K slices: enough blocks to keep every CU streaming weights (the small tiles have two waves
         // each, so they need more of them), bounded by the partial-result buffer
         const bool small = BM <= 64;
@@ -1527,12 +1556,8 @@ static int gemm(const Model &m, const bf16_t *A, const bf16_t *Alo, int lda, con
         if (kps < 256) kps = 256;
         splits = (K + kps - 1) / kps;
     }
-    if (big) gg.blocks = 8 * ((gg.Nx + 7) / 8) * gg.YB * gg.TY;  // the ring kernel numbers its tiles without gaps
-    const int tail_units = (gg.tail_tiles + 31) / 32 * gg.tail_s;
-    dim3 grid(gg.blocks + (tail_units + 7) / 8 * 256, splits);
-    if (big)
-        ring_launch<DUAL>(m, grid, A, lda, B, M, N, K, kps, outb, ldo, gg);
-    else if (Alo && BM == 32)
+    dim3 grid(gg.blocks, splits);
+    if (Alo && BM == 32)
         gemm_launch<32, 128, 1, 2, DUAL, true>(m, grid, A, Alo, lda, B, M, N, K, kps, outb, outlo, ldo, gg);
     else if (Alo && BM == 64)
         gemm_launch<64, 128, 1, 2, DUAL, true>(m, grid, A, Alo, lda, B, M, N, K, kps, outb, outlo, ldo, gg);
