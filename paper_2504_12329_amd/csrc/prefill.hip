@@ -345,8 +345,8 @@ __device__ __forceinline__ void static_for(F &&f) {  // f(ic<0>{}), ..., f(ic<N-
 // patches at the edges, so the numbering has no gaps); XCD e (= block id % 8) takes the `per` consecutive numbers
 // from e * per on.  The 32 blocks an XCD runs together are then one patch of one K slice -- the panels they stream
 // are shared in that XCD's L2 -- and every XCD gets the same number of blocks.  Ids that are dealt out but return at
-// once must not be interleaved with working ones: the working blocks then sit unevenly on an XCD's shader engines
-// (measured: the O / down projections of a 4096-row chunk took 40 % longer that way).
+// once must not be interleaved with working ones (measured: with two of every four ids returning, the O / down
+// projections of a 4096-row chunk took 40 % longer -- as if the working blocks sat on half an XCD's shader engines).
 // Tail (block ids from `blocks` on): the column tiles from tail_x0 on, their K range cut into tail_s slices of
 // tail_kps columns; a unit is one slice of 32 tiles (column-major) and unit u runs on XCD u % 8.
 struct RingGrid {
