@@ -206,6 +206,22 @@ def target_model_extras(torch, B, synth, cost, small, sizes=(21, 86, 256, 1024, 
             "ms_small_decode": st["ms_small_decode"], "ms_large_decode": st["ms_large_decode"],
             "ms_small_prefill": st["ms_small_prefill"], "ms_large_prefill": st["ms_large_prefill"],
             "schedule": "rule: previous id % 89 == 0 and id % 97 == 0, target writes 20"}
+    # and under a rule of the paper's trigger density (previous id % 7 == 0 and id % 15 == 0: about one token in 105
+    # on uniform ids, Section 3 (1)); the density realised on this model's own greedy output is reported
+    small.truncate(0)
+    large.truncate(0)
+    rule = B.TriggerRule(vocab, synth.modulo_bitmap(vocab, 15), synth.modulo_bitmap(vocab, 7), 2)
+    t0 = time.perf_counter()
+    g = B.st_generate(small, large, rule, prompt, 1500, 20)
+    dt = time.perf_counter() - t0
+    st = g["stats"]
+    res["loop_1p5b_32b_rule_dense"] = {
+        "tok_s": st["n_out"] / dt, "n_out": st["n_out"], "n_handoffs": st["n_handoffs"],
+        "modify_ratio": st["n_large"] / max(1, st["n_out"]),
+        "target_catch_up_lengths": [sp["large_prefill_hi"] - sp["large_prefill_lo"] for sp in g["spans"]],
+        "ms_small_decode": st["ms_small_decode"], "ms_large_decode": st["ms_large_decode"],
+        "ms_small_prefill": st["ms_small_prefill"], "ms_large_prefill": st["ms_large_prefill"],
+        "schedule": "rule: previous id % 7 == 0 and id % 15 == 0, target writes 20"}
     # the non-reasoning-speculator schedule (Section 4.3): the target writes the first 100 tokens and takes over for
     # 20 tokens after every delimiter; the delimiter class id % 24 == 0 would give a modify ratio near 44 % on
     # uniform tokens, the realised ratio is reported
