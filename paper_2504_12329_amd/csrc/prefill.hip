@@ -350,11 +350,14 @@ __device__ __forceinline__ void static_for(F &&f) {  // f(ic<0>{}), ..., f(ic<N-
 // Tail (block ids from `blocks` on): the column tiles from tail_x0 on, their K range cut into tail_s slices of
 // tail_kps columns; a unit is one slice of 32 tiles (column-major) and unit u runs on XCD u % 8.
 struct RingGrid {
-    int My, Nx, TY, TX, S, kps, per, blocks;
+    int My, Nx, x0, TY, TX, S, kps, per, blocks;  // x0: column tile of the launch's first column (in its own tiles)
     int tail_x0, tail_tiles, tail_s, tail_kps;
 };
 
-template <bool DUAL>
+// HALF (fused SwiGLU form only): the block tile is 256 x (64 gate + 64 up) weight rows -- half the columns, half the
+// MFMAs per fragment of activations -- for the tiles left over after whole rounds of full tiles (one more round of
+// half the length instead of a round that leaves half the chip idle).
+template <bool DUAL, bool HALF = false>
 __global__ __launch_bounds__(256) void k_gemm_ring(const bf16_t *__restrict__ A, int lda, const bf16_t *__restrict__ B,
                                                    int M, int N, int K, float *__restrict__ part,
                                                    bf16_t *__restrict__ outb, int ldo, RingGrid gg) {
@@ -398,21 +401,31 @@ __global__ __launch_bounds__(256) void k_gemm_ring(const bf16_t *__restrict__ A,
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave >> 1, wn = wave & 1;
     const int l32 = lane & 31, kg = lane >> 5;
-    const int m0 = y * 256, n0 = x * (DUAL ? 128 : 256);
+    static_assert(DUAL || !HALF, "the half-width tile exists for the fused form only");
+    constexpr int NB = HALF ? 2 : 4;   // 32-row weight fragments per wave
+    constexpr int NLB = HALF ? 4 : 8;  // direct loads per wave for one weight slot
+    const int m0 = y * 256, n0 = (x + gg.x0) * (HALF ? 64 : DUAL ? 128 : 256);
     const int nk = (kend - kbeg) / kRingBK;
     const uint32_t ring0 = (uint32_t)(uintptr_t)ring;  // LDS byte offset of the ring (low half of the flat address)
 
     // direct loads: instruction i of a wave fills LDS rows [(wave*8+i)*8, +8) of a slot, lane -> (row lane/8,
     // 16-byte position lane%8, which holds global chunk position ^ swizzle(row)); rows past the edge re-read
     // the last valid row (their results are never stored)
-    const bf16_t *pa[8], *pb[8];
+    const bf16_t *pa[8], *pb[NLB];
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
         const int row = (wave * 8 + i) * 8 + (lane >> 3);
         const int c = (lane & 7) ^ ring_swz(row);
         pa[i] = A + (size_t)min(m0 + row, M - 1) * lda + kbeg + c * 8;
+    }
+#pragma unroll
+    for (int i = 0; i < NLB; ++i) {
+        const int row = (wave * NLB + i) * 8 + (lane >> 3);
+        const int c = (lane & 7) ^ ring_swz(row);
         int bn;
-        if (DUAL)  // rows 0..127 of the tile are gate rows, 128..255 the matching up rows (N = I)
+        if (HALF)  // rows 0..63 of the tile are gate rows, 64..127 the matching up rows
+            bn = min(n0 + (row & 63), N - 1) + (row >> 6) * N;
+        else if (DUAL)  // rows 0..127 of the tile are gate rows, 128..255 the matching up rows (N = I)
             bn = min(n0 + (row & 127), N - 1) + (row >> 7) * N;
         else
             bn = min(n0 + row, N - 1);
@@ -424,41 +437,49 @@ __global__ __launch_bounds__(256) void k_gemm_ring(const bf16_t *__restrict__ A,
     };
     auto loadB = [&](auto i_c, int slot, int kt) {
         constexpr int i = decltype(i_c)::value;
-        load_to_lds16(pb[i] + kt * kRingBK, ring0 + slot * kRingSlot + (wave * 8 + i) * 1024);
+        if constexpr (i < NLB)
+            load_to_lds16(pb[i] + kt * kRingBK, ring0 + slot * kRingSlot + (wave * NLB + i) * 1024);
     };
 
-    f32x16 acc[4][4];
+    f32x16 acc[4][NB];
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < NB; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
     // fragment reads: lane (row l32, K half kg) of 32-row block t reads chunk (2*ks + kg) ^ swizzle; the
     // swizzle of row 32*t + l32 is swizzle(l32) ^ 4*(t & 1)
     const int a_off = (wm * 128 + l32) * 128;
-    int b_off[4];
+    int b_off[NB];
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
-        b_off[j] = (DUAL ? ((j >> 1) * 128 + wn * 64 + (j & 1) * 32 + l32) : (wn * 128 + j * 32 + l32)) * 128;
+    for (int j = 0; j < NB; ++j)
+        b_off[j] = (HALF   ? (j * 64 + wn * 32 + l32)
+                    : DUAL ? ((j >> 1) * 128 + wn * 64 + (j & 1) * 32 + l32)
+                           : (wn * 128 + j * 32 + l32)) * 128;
     const int ch_even = (kg ^ ring_swz(l32)) * 16, ch_odd = ch_even ^ 64;
+    const int ch_half = wn ? ch_odd : ch_even;  // HALF: both weight fragments of a wave sit in 32-row block wn or 2 + wn
 
-    bf16x8 fa[2][4], fb[2][4];
-    // fragment q of a 16-wide step: q = 0..3 weight fragments, 4..7 activation fragments
+    bf16x8 fa[2][4], fb[2][NB];
+    // fragment q of a 16-wide step: q = 0..3 weight fragments (0..1 with HALF), 4..7 activation fragments
     auto fetch = [&](auto buf_c, auto q_c, int slotA, int slotB, int ks) {
         constexpr int buf = decltype(buf_c)::value, q = decltype(q_c)::value;
-        const int ch = ((q & 1) ? ch_odd : ch_even) ^ (ks * 32);
-        if (q < 4)
-            fb[buf][q & 3] = as_bf16x8(*reinterpret_cast<const u32x4 *>(ring + slotB * kRingSlot + b_off[q & 3] + ch));
-        else
+        if constexpr (q < 4) {
+            if constexpr (q < NB) {
+                const int ch = (HALF ? ch_half : (q & 1) ? ch_odd : ch_even) ^ (ks * 32);
+                fb[buf][q] = as_bf16x8(*reinterpret_cast<const u32x4 *>(ring + slotB * kRingSlot + b_off[q] + ch));
+            }
+        } else {
+            const int ch = ((q & 1) ? ch_odd : ch_even) ^ (ks * 32);
             fa[buf][q & 3] =
                 as_bf16x8(*reinterpret_cast<const u32x4 *>(ring + slotA * kRingSlot + a_off + (q & 3) * 4096 + ch));
+        }
     };
     auto mma_row = [&](auto buf_c, auto i_c) {
         constexpr int buf = decltype(buf_c)::value, i = decltype(i_c)::value;
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < NB; ++j)
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[buf][i], fb[buf][j], acc[i][j], 0, 0, 0);
     };
     // One 16-wide step: four groups of { one direct load (KIND 1: weight instruction D0+g, 2: activation
@@ -532,16 +553,16 @@ __global__ __launch_bounds__(256) void k_gemm_ring(const bf16_t *__restrict__ A,
             if (row >= M) continue;
             if (DUAL) {
 #pragma unroll
-                for (int j = 0; j < 2; ++j) {
-                    const int col = n0 + wn * 64 + j * 32 + l32;
+                for (int j = 0; j < NB / 2; ++j) {
+                    const int col = n0 + wn * (NB * 16) + j * 32 + l32;
                     if (col < N) {
-                        const float gt = acc[i][j][r], up = acc[i][j + 2][r];
+                        const float gt = acc[i][j][r], up = acc[i][j + NB / 2][r];
                         outb[(size_t)row * ldo + col] = f32_to_bf16(gt / (1.0f + expf(-gt)) * up);
                     }
                 }
             } else {
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
+                for (int j = 0; j < NB; ++j) {
                     const int col = n0 + wn * 128 + j * 32 + l32;
                     if (col < N) pz[(size_t)row * ldp + col] = acc[i][j][r];
                 }
@@ -1376,10 +1397,10 @@ static void gemm_launch(const Model &m, dim3 grid, const bf16_t *A, const bf16_t
                        outlo, ldo, gg);
 }
 
-template <bool DUAL>
+template <bool DUAL, bool HALF = false>
 static void ring_launch(const Model &m, dim3 grid, const bf16_t *A, int lda, const bf16_t *B, int M, int N, int K,
                         bf16_t *outb, int ldo, const RingGrid &gg) {
-    auto kern = k_gemm_ring<DUAL>;
+    auto kern = k_gemm_ring<DUAL, HALF>;
     static bool raised = false;  // more than 64 KB of dynamic LDS has to be allowed once per kernel
     if (!raised) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -1456,9 +1477,26 @@ static int ring_gemm(const Model &m, const bf16_t *A, int lda, const bf16_t *B, 
     gg.TY = 1;
     while (gg.TY * 2 <= gg.My && gg.TY < 8) gg.TY *= 2;
     gg.TX = 32 / gg.TY;
-    gg.S = 1, gg.kps = K;
+    gg.S = 1, gg.kps = K, gg.x0 = 0;
     gg.tail_x0 = gg.tail_tiles = 0, gg.tail_s = 1, gg.tail_kps = K;
     const int tiles = gg.My * gg.Nx, nk = K / kRingBK;
+    if constexpr (DUAL) {
+        // Whole rounds of 256 full tiles, then the column tiles left over as half-width tiles in a launch of their
+        // own: twice the blocks at half the length each, so the last round keeps every CU busy for half a round
+        // instead of half the CUs for a whole one.
+        if (tiles > 256 && tiles % 256 && 256 % gg.My == 0) {
+            const int nx_main = tiles / 256 * 256 / gg.My;
+            RingGrid th = gg;
+            th.Nx = 2 * (gg.Nx - nx_main), th.x0 = 2 * nx_main;
+            if (th.x0 * 64 + th.Nx * 64 > N + 63) th.Nx = (N - th.x0 * 64 + 63) / 64;  // a ragged last column tile
+            th.per = (th.My * th.Nx + 7) / 8, th.blocks = 8 * th.per;
+            gg.Nx = nx_main;
+            gg.per = (gg.My * gg.Nx + 7) / 8, gg.blocks = 8 * gg.per;
+            ring_launch<true, false>(m, dim3(gg.blocks), A, lda, B, M, N, K, outb, ldo, gg);
+            ring_launch<true, true>(m, dim3(th.blocks), A, lda, B, M, N, K, outb, ldo, th);
+            return 0;
+        }
+    }
     if (!DUAL) {
         // One block per CU at a time: pick the K slices that minimise (rounds of 256 blocks) x (K steps per
         // slice + a fixed cost for filling the ring and writing the tile)
