@@ -1620,6 +1620,26 @@ static void launch_flash(const Model &m, const bf16_t *qb, const bf16_t *qb_lo, 
     if (splits > n_tiles) splits = n_tiles;
     if (splits > 32) splits = 32;
     const size_t cap = partial_floats(c);
+    if (long_chunk) {
+        // k_flash_long: the count that minimises (rounds of resident blocks) x (tiles per block + 2 for the set-up
+        // and the store) x the time of a tile step, plus the merge pass over the partial results (its bytes at
+        // 4 TB/s + a launch).  640 blocks of 42 tiles on 512 slots are two rounds; 960 blocks of 27 are two shorter ones.
+        const int slots = qb_lo ? 256 : 512;        // one block per CU with two-term queries, else two
+        const double step_us = qb_lo ? 2.2 : 1.7;
+        double best = -1;
+        // (from two rounds of blocks on, the causal spread of their lengths, longest first, balances the CUs
+        // better than splitting does, and the merge pass would cost more than it saves: measured at 4096 rows)
+        const int sp_max = rblocks * nkv >= 2 * slots ? 1 : (n_tiles < 32 ? n_tiles : 32);
+        for (int sp = 1; sp <= sp_max; ++sp) {
+            if (sp > 1 && (size_t)sp * n * nq * (d + 2) > cap) break;
+            const int tps = (n_tiles + sp - 1) / sp, used = (n_tiles + tps - 1) / tps;
+            if (used != sp) continue;  // the same blocks as a smaller count
+            const int rounds = (rblocks * nkv * sp + slots - 1) / slots;
+            const double merge = sp > 1 ? 3.0 + (double)n * nq * d * 4 * (sp + 1) / 4e6 : 0.0;
+            const double cost = rounds * (tps + 2) * step_us + merge;
+            if (best < 0 || cost < best) best = cost, splits = sp;
+        }
+    }
     while (splits > 1 && (size_t)splits * n * nq * (d + 2) > cap) --splits;
     float *part_o = w.qkv, *part_ml = w.qkv + (size_t)splits * n * nq * d;
     dim3 fgrid(rblocks, nkv, splits);
