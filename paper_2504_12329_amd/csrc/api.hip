@@ -66,7 +66,7 @@ void carve_workspace(const st_config &c, char *base, Workspace *ws) {
         return p;
     };
     const size_t mc = c.max_chunk, h = c.hidden, qd = (size_t)c.n_q_heads * c.head_dim;
-    const size_t qkv = (size_t)(c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim, I = c.intermediate;
+    const size_t I = c.intermediate;
     ws->state = (int32_t *)take(sizeof(int32_t) * kStateInts);
     ws->counters = (int32_t *)take(sizeof(int32_t) * c.n_kv_heads);
     ws->rope = (float2 *)take(sizeof(float2) * (size_t)c.max_seq * (c.head_dim / 2));
@@ -74,10 +74,7 @@ void carve_workspace(const st_config &c, char *base, Workspace *ws) {
     ws->out_tokens = (int32_t *)take(sizeof(int32_t) * (size_t)c.max_seq);
     ws->x = (float *)take(sizeof(float) * mc * h);
     ws->xn = (bf16_t *)take(sizeof(bf16_t) * mc * h);
-    {
-        size_t a = (mc > 1024 ? mc : 1024) * (qkv > h ? qkv : h), b = (size_t)1024 * 2 * I;
-        ws->qkv = (float *)take(sizeof(float) * (a > b ? a : b));
-    }
+    ws->qkv = (float *)take(sizeof(float) * partial_floats(c));
     ws->qb = (bf16_t *)take(sizeof(bf16_t) * mc * qd);
     ws->attn = (bf16_t *)take(sizeof(bf16_t) * mc * qd);
     ws->act = (bf16_t *)take(sizeof(bf16_t) * mc * I);

@@ -1373,13 +1373,14 @@ __global__ __launch_bounds__(256) void k_flash_combine(const float *__restrict__
 // ---------------------------------------------------------------------------------------
 constexpr int kLongWaves = 4;  // waves per block of k_flash_long
 
-// Floats the split-K partial buffer (ws.qkv) holds; also sized in carve_workspace.
-static size_t partial_floats(const st_config &c) {
+// Floats the split-K partial buffer (ws.qkv) holds (the workspace is carved with the same figure).
+size_t partial_floats(const st_config &c) {
     size_t rows = c.max_chunk > 1024 ? c.max_chunk : 1024;
     size_t qkv = (size_t)(c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim;
     size_t cols = qkv > (size_t)c.hidden ? qkv : (size_t)c.hidden;
     size_t short_chunk = (size_t)1024 * 2 * c.intermediate;  // gate/up slices of chunks up to 256 rows
-    return rows * cols > short_chunk ? rows * cols : short_chunk;
+    size_t long_chunk = rows * cols + rows * cols / 4;         // one full-width slice + the extra slices of tail columns
+    return long_chunk > short_chunk ? long_chunk : short_chunk;
 }
 
 // Launches one GEMM; returns the number of K slices written to ws.qkv (0 for the fused SwiGLU form).

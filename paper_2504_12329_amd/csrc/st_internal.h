@@ -22,7 +22,7 @@ struct Workspace {
     int32_t *out_tokens;   // [max_seq] tokens produced by chained steps
     float *x;              // [max_chunk][hidden] residual stream
     bf16_t *xn;            // [max_chunk][hidden] normalised rows (GEMM input)
-    float *qkv;            // [max(max_chunk,1024)][max(qkv,hidden)] split-K partial results of the prefill GEMMs
+    float *qkv;            // partial_floats(cfg) floats: split-K partial results of the prefill GEMMs
     bf16_t *qb;            // [max_chunk][n_q*d] rotated queries
     bf16_t *attn;          // [max_chunk][n_q*d] attention output (GEMM input)
     bf16_t *act;           // [max_chunk][intermediate] SwiGLU output
@@ -111,6 +111,7 @@ void launch_head(const Model &m, const float *x_row, const st_trigger_rule *rule
 
 // ---- launchers (prefill.hip) ----
 // Feeds ws.tokens[0,n) at positions [pos0, pos0+n) through all layers; leaves the residual rows in ws.x.
+size_t partial_floats(const st_config &c);  // floats of Workspace::qkv (the split-K / split-key partial results)
 void launch_prefill_layers(const Model &m, int32_t pos0, int32_t n);
 
 // Device arrays of one batched decode step (n rows = n sequences, each at its own position).

@@ -141,6 +141,19 @@ def test_4096_row_chunk_agrees_with_1024_row_chunks(name):
     g.close()
 
 
+def test_4096_row_chunk_tail_tiles_against_oracle():
+    """A one-layer model sized so that one 4096-row pass takes every leftover-tile path of the long-chunk GEMM with
+    ragged edges, small enough for the oracle: hidden 4288 (17 column tiles of 256, the last 192 wide: one round
+    of 256 tiles + 16 tail tiles cut into K slices, in the O and the down projection) and intermediate 2240 (18
+    column tiles of 128, the last 64 wide: 256 full tiles + 3 half-width tiles in the fused gate/up GEMM)."""
+    print_case("custom shape (hidden 4288, intermediate 2240, 6 q heads per kv head), 1 layer: 40 cached + 4096-row chunk")
+    cfg, g, o = make_pair("qwen1p5b", 31, max_seq=4200, max_chunk=4096, n_layers=1, gen_device="cuda",
+                          hidden=4288, intermediate=2240, n_q_heads=6, n_kv_heads=1, vocab=2048)
+    prompt = synth.make_prompt(4136, cfg["vocab"], 32)
+    assert _teacher_forced(cfg, g, o, prompt, [40, 4096], 2) <= LOGIT_TOL
+    g.close()
+
+
 def test_prefill_is_bit_reproducible():
     """Split-K partial sums and split-key attention are merged in fixed orders: same input, same bits."""
     cfg = synth.model_config("qwen1p5b", max_seq=1400, max_chunk=1024, n_layers=2)
