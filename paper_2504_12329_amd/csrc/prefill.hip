@@ -761,14 +761,18 @@ __global__ __launch_bounds__(SPEC ? 512 : 256) void k_gemm_stream(const bf16_t *
 
 // ---------------------------------------------------------------------------------------
 // RoPE on q and k at absolute positions pos0 + row, K/V appended to the cache, q kept as bf16.
-// grid (rows, heads), block d/2 threads: one rotation pair per thread.
+// grid (rows, heads / kRopeHeads), block kRopeHeads * d/2 threads: one rotation pair per thread, kRopeHeads heads
+// per block (one head per block is a grid of 64-thread blocks that the dispatcher, not the memory, paces).
 // ---------------------------------------------------------------------------------------
+constexpr int kRopeHeads = 4;
 __global__ void k_rope_append(const float *__restrict__ part, int n_part, size_t part_stride,
                               const bf16_t *__restrict__ bias, const float2 *__restrict__ rope,
                               bf16_t *__restrict__ qb, bf16_t *__restrict__ qb_lo, bf16_t *__restrict__ kc,
                               bf16_t *__restrict__ vc, int pos0, int nq, int nkv, int d, int max_seq,
                               PartTail tail) {
-    const int row = blockIdx.x, head = blockIdx.y, i = threadIdx.x, half = d >> 1;
+    const int half = d >> 1, row = blockIdx.x;
+    const int head = blockIdx.y * kRopeHeads + threadIdx.x / half, i = threadIdx.x % half;
+    if (head >= nq + 2 * nkv) return;
     const int pos = pos0 + row;
     const size_t off = (size_t)row * (nq + 2 * nkv) * d + head * d;
     float lo = 0.f, hi = 0.f;
@@ -1681,7 +1685,8 @@ void launch_prefill_layers(const Model &m, int32_t pos0, int32_t n) {
         hipLaunchKernelGGL(k_rmsnorm_rows, dim3(n), dim3(norm_threads(n)), 0, m.stream, w.x, w.qkv, pending, (size_t)n * h,
                            m.norm_attn[l], w.xn, xn_lo, h, c.rms_eps, pend_tail);
         int sq = gemm<false>(m, w.xn, xn_lo, h, m.wqkv[l], n, qkv, h, nullptr, nullptr, 0, &tq);
-        hipLaunchKernelGGL(k_rope_append, dim3(n, nq + 2 * nkv), dim3(d / 2), 0, m.stream, w.qkv, sq,
+        hipLaunchKernelGGL(k_rope_append, dim3(n, (nq + 2 * nkv + kRopeHeads - 1) / kRopeHeads),
+                           dim3(kRopeHeads * d / 2), 0, m.stream, w.qkv, sq,
                            (size_t)n * qkv, m.bqkv[l], w.rope, w.qb, qb_lo, m.kcache + lofs, m.vcache + lofs, pos0, nq, nkv,
                            d, c.max_seq, tq);
         launch_flash(m, w.qb, qb_lo, m.kcache + lofs, m.vcache + lofs, w.attn, attn_lo, n, pos0);
