@@ -87,6 +87,15 @@ typedef struct st_model st_model;
  * Either output may be NULL.  ST_EINVAL on an unsupported shape. */
 int st_query_sizes(const st_config *cfg, size_t *kv_bytes, size_t *workspace_bytes);
 
+/* Host-only self-check of the launch plan of a catch-up pass of `rows` rows (Section 3: the target's pass over the
+ * tokens it has not seen): walks the block numbering of the four projections' GEMMs as the kernels would decode it
+ * -- K slices, leftover column tiles, half-width tiles -- and verifies that every output tile and K step is
+ * computed by exactly one block and that every partial-sum tile lies inside the workspace st_query_sizes reports.
+ * Touches no device.  launches / blocks (may be NULL) receive the GEMM launches and working blocks of one layer
+ * (0 for rows <= 256, which take the streaming kernel).  ST_EINVAL with the failing projection in
+ * st_last_error() if the plan is inconsistent, ST_ERANGE if rows is outside 1..cfg->max_chunk. */
+int st_prefill_plan_check(const st_config *cfg, int32_t rows, int32_t *launches, int32_t *blocks);
+
 /* Creates a model over caller-owned device buffers (both 256-byte aligned).  Initialises the
  * workspace (RoPE table, counters) on `stream`; the KV length starts at 0.  The weights,
  * `kv` and `workspace` are borrowed until st_model_destroy.  Two models must not share a

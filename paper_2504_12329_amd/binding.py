@@ -16,7 +16,7 @@ LIB_PATH = os.path.join(HERE, "libst.so")
 ST_OK, ST_EINVAL, ST_ENOMEM, ST_ERANGE, ST_EHIP = 0, -1, -2, -3, -4
 ST_TOKENS_DEVICE, ST_OUT_DEVICE, ST_TOKEN_CHAINED, ST_PREFILL_TWO_TERM = 1, 2, 4, 8
 
-EXPORTS = ("st_query_sizes", "st_model_create", "st_model_destroy", "st_kv_len", "st_kv_truncate", "st_prefill",
+EXPORTS = ("st_query_sizes", "st_prefill_plan_check", "st_model_create", "st_model_destroy", "st_kv_len", "st_kv_truncate", "st_prefill",
            "st_decode_step", "st_decode_step_timed", "st_decode_greedy", "st_trigger_scan", "st_handoff", "st_generate",
            "st_generate_policy", "st_batch_query_sizes", "st_batch_create", "st_batch_destroy", "st_batch_kv_len",
            "st_batch_truncate", "st_batch_prefill", "st_batch_prefill_many", "st_batch_decode_step", "st_generate_batch",
@@ -74,6 +74,7 @@ def lib():
         i32p, f32p = C.POINTER(C.c_int32), C.POINTER(C.c_float)
         L.st_last_error.restype = C.c_char_p
         L.st_query_sizes.argtypes = [C.POINTER(st_config), C.POINTER(C.c_size_t), C.POINTER(C.c_size_t)]
+        L.st_prefill_plan_check.argtypes = [C.POINTER(st_config), C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
         L.st_model_create.argtypes = [C.POINTER(st_config), C.POINTER(st_weights), C.c_void_p, C.c_size_t,
                                       C.c_void_p, C.c_size_t, C.c_void_p, C.POINTER(C.c_void_p)]
         L.st_model_destroy.argtypes = [C.c_void_p]
@@ -125,6 +126,13 @@ def st_query_sizes(cfg):
     kv, ws = C.c_size_t(), C.c_size_t()
     _check(lib().st_query_sizes(C.byref(make_config(cfg)), C.byref(kv), C.byref(ws)))
     return kv.value, ws.value
+
+
+def st_prefill_plan_check(cfg, rows):
+    """Host-only walk over the launch plan of a catch-up pass of `rows` rows; returns (launches, blocks) of a layer."""
+    nl, nb = C.c_int32(), C.c_int32()
+    _check(lib().st_prefill_plan_check(C.byref(make_config(cfg)), int(rows), C.byref(nl), C.byref(nb)))
+    return nl.value, nb.value
 
 
 def _np_ptr(a):

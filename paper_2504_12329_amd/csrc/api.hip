@@ -262,6 +262,30 @@ int st_query_sizes(const st_config *cfg, size_t *kv_bytes, size_t *workspace_byt
     return ST_OK;
 }
 
+int st_prefill_plan_check(const st_config *cfg, int32_t rows, int32_t *launches, int32_t *blocks) {
+    if (int rc = validate_config(cfg)) return rc;
+    if (rows <= 0 || rows > cfg->max_chunk) return fail(ST_ERANGE, "rows %d outside 1..max_chunk", rows);
+    if (launches) *launches = 0;
+    if (blocks) *blocks = 0;
+    if (rows <= 256) return ST_OK;  // short chunks take the streaming kernel: one tile list, no leftover handling
+    const int h = cfg->hidden, I = cfg->intermediate, qd = cfg->n_q_heads * cfg->head_dim;
+    const int qkv = (cfg->n_q_heads + 2 * cfg->n_kv_heads) * cfg->head_dim;
+    const long long cap = (long long)partial_floats(*cfg);
+    const struct {
+        const char *name;
+        int dual, N, K;
+    } g[4] = {{"QKV", 0, qkv, h}, {"O", 0, h, qd}, {"gate/up", 1, I, h}, {"down", 0, h, I}};
+    for (const auto &e : g) {
+        if (e.K % 64 || e.K < 128) continue;  // the general-shape kernel serves such a K
+        int nl = 0, nb = 0, ni = 0;
+        const int rc = ring_plan_check(e.dual, rows, e.N, e.K, cap, 1, &nl, &nb, &ni);
+        if (rc) return fail(ST_EINVAL, "block plan of the %s projection at %d rows fails check %d", e.name, rows, rc);
+        if (launches) *launches += nl;
+        if (blocks) *blocks += nb;
+    }
+    return ST_OK;
+}
+
 // Checks the weights and fills a model record over the given cache and workspace (sizes checked by the caller).
 static int build_model(const st_config *cfg, const st_weights *w, void *kv, void *workspace, void *stream, Model *m) {
     if (!w) return fail(ST_EINVAL, "weights is NULL");

@@ -3,6 +3,7 @@
 // residual / SwiGLU epilogues, RoPE + KV append, and causal flash attention with a key offset.
 #include "st_device.h"
 #include "st_internal.h"
+#include <vector>
 
 #include <type_traits>
 
@@ -353,22 +354,20 @@ struct RingGrid {
     int My, Nx, x0, TY, TX, S, kps, per, blocks;  // x0: column tile of the launch's first column (in its own tiles)
     int tail_x0, tail_tiles, tail_s, tail_kps;
 };
-
-// HALF (fused SwiGLU form only): the block tile is 256 x (64 gate + 64 up) weight rows -- half the columns, half the
-// MFMAs per fragment of activations -- for the tiles left over after whole rounds of full tiles (one more round of
-// half the length instead of a round that leaves half the chip idle).
-template <bool DUAL, bool HALF = false>
-__global__ __launch_bounds__(256) void k_gemm_ring(const bf16_t *__restrict__ A, int lda, const bf16_t *__restrict__ B,
-                                                   int M, int N, int K, float *__restrict__ part,
-                                                   bf16_t *__restrict__ outb, int ldo, RingGrid gg) {
-    extern __shared__ __align__(16) unsigned char ring[];
-    int x, y, kbeg, kend;
-    float *pz = nullptr;  // where this block's fp32 tile goes (plain form), row stride ldp
-    int ldp = N;
-    if ((int)blockIdx.x < gg.blocks) {
-        const int j = blockIdx.x >> 3, T = gg.My * gg.Nx;
-        const int f = (blockIdx.x & 7) * gg.per + j;
-        if (j >= gg.per || f >= gg.S * T) return;  // only at the end of an XCD's range
+// What block `bid` of a launch works on: tile (x, y) in the launch's own tiles (x before adding x0), K range
+// [kbeg, kend), and for the plain form where its fp32 tile goes: part + part_off, row stride ldp (the offset
+// already discounts the tail's first column).  False: the id has no work.  Shared by the kernel and the host-side
+// check of the numbering.
+struct RingBlock {
+    int x, y, kbeg, kend, ldp;
+    long long part_off;
+};
+__host__ __device__ inline bool ring_block(const RingGrid &gg, int bid, int M, int N, int K, RingBlock *o) {
+    o->ldp = N;
+    if (bid < gg.blocks) {
+        const int j = bid >> 3, T = gg.My * gg.Nx;
+        const int f = (bid & 7) * gg.per + j;
+        if (j >= gg.per || f >= gg.S * T) return false;  // only at the end of an XCD's range
         const int sl = f / T, fs = f % T;
         const int full_c = gg.Nx / gg.TX * gg.TX, full_r = gg.My / gg.TY * gg.TY;
         int cols, c0, jj;
@@ -381,23 +380,36 @@ __global__ __launch_bounds__(256) void k_gemm_ring(const bf16_t *__restrict__ A,
             y0 = jj / (cols * gg.TY) * gg.TY, r = jj % (cols * gg.TY);
         else
             y0 = full_r, r = jj - cols * full_r;
-        y = y0 + r / cols, x = c0 + r % cols;
-        kbeg = sl * gg.kps, kend = min(K, kbeg + gg.kps);
-        if (!DUAL) pz = part + (size_t)sl * M * N;
-    } else {
-        // tail: a unit is one K slice of a patch of 32 tiles (column-major over the tail's columns); unit u runs on
-        // XCD u % 8, so the blocks that share panels at the same K positions share an L2
-        const int t = blockIdx.x - gg.blocks, xcd = t & 7, j = t >> 3;
-        const int u = (j >> 5) * 8 + xcd, q = (u / gg.tail_s) * 32 + (j & 31), sl = u % gg.tail_s;
-        if (q >= gg.tail_tiles) return;
-        x = gg.tail_x0 + q / gg.My, y = q % gg.My;
-        kbeg = sl * gg.tail_kps, kend = min(K, kbeg + gg.tail_kps);
-        const int col0 = gg.tail_x0 * 256;
-        if (sl == 0)
-            pz = part;
-        else
-            ldp = N - col0, pz = part + (size_t)M * N + (size_t)(sl - 1) * M * ldp - col0;
+        o->y = y0 + r / cols, o->x = c0 + r % cols;
+        o->kbeg = sl * gg.kps, o->kend = o->kbeg + gg.kps < K ? o->kbeg + gg.kps : K;
+        o->part_off = (long long)sl * M * N;
+        return true;
     }
+    // tail: a unit is one K slice of a patch of 32 tiles (column-major over the tail's columns); unit u runs on
+    // XCD u % 8, so the blocks that share panels at the same K positions share an L2
+    const int t = bid - gg.blocks, xcd = t & 7, j = t >> 3;
+    const int u = (j >> 5) * 8 + xcd, q = (u / gg.tail_s) * 32 + (j & 31), sl = u % gg.tail_s;
+    if (q >= gg.tail_tiles) return false;
+    o->x = gg.tail_x0 + q / gg.My, o->y = q % gg.My;
+    o->kbeg = sl * gg.tail_kps, o->kend = o->kbeg + gg.tail_kps < K ? o->kbeg + gg.tail_kps : K;
+    const int col0 = gg.tail_x0 * 256;
+    o->part_off = 0;
+    if (sl > 0) o->ldp = N - col0, o->part_off = (long long)M * N + (long long)(sl - 1) * M * o->ldp - col0;
+    return true;
+}
+
+// HALF (fused SwiGLU form only): the block tile is 256 x (64 gate + 64 up) weight rows -- half the columns, half the
+// MFMAs per fragment of activations -- for the tiles left over after whole rounds of full tiles (one more round of
+// half the length instead of a round that leaves half the chip idle).
+template <bool DUAL, bool HALF = false>
+__global__ __launch_bounds__(256) void k_gemm_ring(const bf16_t *__restrict__ A, int lda, const bf16_t *__restrict__ B,
+                                                   int M, int N, int K, float *__restrict__ part,
+                                                   bf16_t *__restrict__ outb, int ldo, RingGrid gg) {
+    extern __shared__ __align__(16) unsigned char ring[];
+    RingBlock rb;
+    if (!ring_block(gg, blockIdx.x, M, N, K, &rb)) return;
+    const int x = rb.x, y = rb.y, kbeg = rb.kbeg, kend = rb.kend, ldp = rb.ldp;
+    float *pz = DUAL ? nullptr : part + rb.part_off;  // where this block's fp32 tile goes (plain form)
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave >> 1, wn = wave & 1;
     const int l32 = lane & 31, kg = lane >> 5;
@@ -1471,21 +1483,30 @@ static StreamShape stream_shape(const Model &m, int M, int N, int K) {
     return best;
 }
 
-// The 256 x 256 ring kernel on a chunk of more than kSplitRows rows: K slices and block numbering.  Returns the
-// number of full-width K slices written to ws.qkv (0 for the fused SwiGLU form).
-template <bool DUAL>
-static int ring_gemm(const Model &m, const bf16_t *A, int lda, const bf16_t *B, int M, int N, int K, bf16_t *outb,
-                     int ldo, PartTail *tail) {
+// Launches of the 256 x 256 ring kernel for one GEMM of a chunk of more than kSplitRows rows: K slices, leftover
+// tiles and block numbering.  Pure host arithmetic (ring_plan_check walks it without a GPU).
+struct RingPlan {
+    int n;             // launches: 1, or 2 for the fused form with half-width leftover tiles
+    RingGrid g[2];
+    bool half[2];
+    int grid_x[2];
+    int slices;        // full-width K slices written to the partial buffer (0 for the fused form)
+    PartTail tail;     // extra slices of the tail columns
+};
+
+static RingPlan ring_plan(bool dual, int M, int N, int K, size_t cap, bool allow_tail) {
+    RingPlan p{};
     RingGrid gg;
     gg.My = (M + 255) / 256;
-    gg.Nx = (N + (DUAL ? 128 : 256) - 1) / (DUAL ? 128 : 256);
+    gg.Nx = (N + (dual ? 128 : 256) - 1) / (dual ? 128 : 256);
     gg.TY = 1;
     while (gg.TY * 2 <= gg.My && gg.TY < 8) gg.TY *= 2;
     gg.TX = 32 / gg.TY;
     gg.S = 1, gg.kps = K, gg.x0 = 0;
     gg.tail_x0 = gg.tail_tiles = 0, gg.tail_s = 1, gg.tail_kps = K;
     const int tiles = gg.My * gg.Nx, nk = K / kRingBK;
-    if constexpr (DUAL) {
+    p.n = 1;
+    if (dual) {
         // Whole rounds of 256 full tiles, then the column tiles left over as half-width tiles in a launch of their
         // own: twice the blocks at half the length each, so the last round keeps every CU busy for half a round
         // instead of half the CUs for a whole one.
@@ -1496,16 +1517,11 @@ static int ring_gemm(const Model &m, const bf16_t *A, int lda, const bf16_t *B, 
             if (th.x0 * 64 + th.Nx * 64 > N + 63) th.Nx = (N - th.x0 * 64 + 63) / 64;  // a ragged last column tile
             th.per = (th.My * th.Nx + 7) / 8, th.blocks = 8 * th.per;
             gg.Nx = nx_main;
-            gg.per = (gg.My * gg.Nx + 7) / 8, gg.blocks = 8 * gg.per;
-            ring_launch<true, false>(m, dim3(gg.blocks), A, lda, B, M, N, K, outb, ldo, gg);
-            ring_launch<true, true>(m, dim3(th.blocks), A, lda, B, M, N, K, outb, ldo, th);
-            return 0;
+            p.n = 2, p.g[1] = th, p.half[1] = true, p.grid_x[1] = th.blocks;
         }
-    }
-    if (!DUAL) {
+    } else {
         // One block per CU at a time: pick the K slices that minimise (rounds of 256 blocks) x (K steps per
         // slice + a fixed cost for filling the ring and writing the tile)
-        const size_t cap = partial_floats(m.c);
         long best = -1;
         for (int s = 1; s <= 8; ++s) {
             const int steps = (nk + s - 1) / s;
@@ -1520,7 +1536,7 @@ static int ring_gemm(const Model &m, const bf16_t *A, int lda, const bf16_t *B, 
         // Or: whole rounds of 256 tiles at full K, and only the column tiles left over cut into K slices (a
         // consumer that takes a PartTail adds their extra slices).  320 tiles with K = 432 steps: three rounds of
         // half the K range each become one round at full K plus one round of quarter slices.
-        if (tail && tiles > 256 && tiles % 256 && 256 % gg.My == 0) {
+        if (allow_tail && tiles > 256 && tiles % 256 && 256 % gg.My == 0) {
             const int nx_main = tiles / 256 * 256 / gg.My, tail_tiles = (gg.Nx - nx_main) * gg.My;
             const int ld = N - nx_main * 256;
             long tbest = -1;
@@ -1536,15 +1552,77 @@ static int ring_gemm(const Model &m, const bf16_t *A, int lda, const bf16_t *B, 
                 gg.tail_x0 = nx_main, gg.tail_tiles = tail_tiles, gg.tail_s = ts;
                 gg.tail_kps = (nk + ts - 1) / ts * kRingBK;
                 gg.Nx = nx_main, gg.S = 1, gg.kps = K;  // the main part: the first nx_main column tiles at full K
-                *tail = PartTail{nx_main * 256, ts - 1, ld, (long long)M * N, (long long)M * ld};
+                p.tail = PartTail{nx_main * 256, ts - 1, ld, (long long)M * N, (long long)M * ld};
             }
         }
+        p.slices = gg.S;
     }
     gg.per = (gg.S * gg.My * gg.Nx + 7) / 8;
     gg.blocks = 8 * gg.per;
     const int tail_units = (gg.tail_tiles + 31) / 32 * gg.tail_s;
-    ring_launch<DUAL>(m, dim3(gg.blocks + (tail_units + 7) / 8 * 256), A, lda, B, M, N, K, outb, ldo, gg);
-    return DUAL ? 0 : gg.S;
+    p.g[0] = gg, p.half[0] = false, p.grid_x[0] = gg.blocks + (tail_units + 7) / 8 * 256;
+    return p;
+}
+
+template <bool DUAL>
+static int ring_gemm(const Model &m, const bf16_t *A, int lda, const bf16_t *B, int M, int N, int K, bf16_t *outb,
+                     int ldo, PartTail *tail) {
+    const RingPlan p = ring_plan(DUAL, M, N, K, partial_floats(m.c), tail != nullptr);
+    ring_launch<DUAL, false>(m, dim3(p.grid_x[0]), A, lda, B, M, N, K, outb, ldo, p.g[0]);
+    if constexpr (DUAL)
+        if (p.n == 2) ring_launch<true, true>(m, dim3(p.grid_x[1]), A, lda, B, M, N, K, outb, ldo, p.g[1]);
+    if (tail) *tail = p.tail;
+    return p.slices;
+}
+
+// Walks every block id of the plan on the host: 0 if each (output tile, 64-column K step) of the GEMM is covered by
+// exactly one block, every block has at least two K steps, and (plain form) every partial-sum tile lies inside
+// cap_floats; a negative code names the first failure.  blocks_out: working blocks, ids_out: ids launched.
+int ring_plan_check(int dual, int M, int N, int K, long long cap_floats, int allow_tail, int *launches_out,
+                    int *blocks_out, int *ids_out) {
+    if (M <= 0 || N <= 0 || K < 2 * kRingBK || K % kRingBK) return -1;
+    const RingPlan p = ring_plan(dual != 0, M, N, K, (size_t)cap_floats, allow_tail != 0);
+    const int nk = K / kRingBK, my = (M + 255) / 256;
+    const int out_cols = dual ? 64 : 256;  // count output columns in units every tile width is a multiple of
+    const int ncu = (N + out_cols - 1) / out_cols;
+    std::vector<unsigned char> seen((size_t)my * ncu * nk, 0);
+    int working = 0, ids = 0;
+    for (int l = 0; l < p.n; ++l) {
+        const int width = p.half[l] ? 64 : dual ? 128 : 256, per_tile = width / out_cols;
+        ids += p.grid_x[l];
+        for (int bid = 0; bid < p.grid_x[l]; ++bid) {
+            RingBlock rb;
+            if (!ring_block(p.g[l], bid, M, N, K, &rb)) continue;
+            ++working;
+            const int n0 = (rb.x + p.g[l].x0) * width;
+            if (rb.y < 0 || rb.y >= my || n0 < 0 || n0 >= N) return -2;
+            if (rb.kbeg < 0 || rb.kend > K || (rb.kend - rb.kbeg) % kRingBK || rb.kend - rb.kbeg < 2 * kRingBK) return -3;
+            for (int c = 0; c < per_tile; ++c) {
+                const int cu = n0 / out_cols + c;
+                if (cu >= ncu) break;  // the ragged part of a last tile
+                for (int ks = rb.kbeg / kRingBK; ks < rb.kend / kRingBK; ++ks) {
+                    unsigned char &cell = seen[((size_t)rb.y * ncu + cu) * nk + ks];
+                    if (cell) return -4;
+                    cell = 1;
+                }
+            }
+            if (!dual) {
+                const int rows = (rb.y * 256 + 256 < M ? rb.y * 256 + 256 : M), cols = (n0 + 256 < N ? n0 + 256 : N);
+                const long long lo = rb.part_off + (long long)rb.y * 256 * rb.ldp + n0;
+                const long long hi = rb.part_off + (long long)(rows - 1) * rb.ldp + cols - 1;
+                if (lo < 0 || hi >= cap_floats) return -5;
+                if (rb.part_off > 0 && p.tail.n > 0 && rb.ldp != N &&
+                    hi >= p.tail.base + (long long)p.tail.n * p.tail.stride)
+                    return -6;
+            }
+        }
+    }
+    for (unsigned char c : seen)
+        if (!c) return -7;
+    if (launches_out) *launches_out = p.n;
+    if (blocks_out) *blocks_out = working;
+    if (ids_out) *ids_out = ids;
+    return 0;
 }
 
 // Two-term chunks (at most kSplitRows rows) use the streaming kernel and an unfused SwiGLU wherever K is a multiple

@@ -111,6 +111,10 @@ void launch_head(const Model &m, const float *x_row, const st_trigger_rule *rule
 
 // ---- launchers (prefill.hip) ----
 // Feeds ws.tokens[0,n) at positions [pos0, pos0+n) through all layers; leaves the residual rows in ws.x.
+// Host walk over the block numbering of the long-chunk GEMM (0 = every tile and K step covered exactly once and
+// every partial-sum tile inside cap_floats; negative = which check failed).
+int ring_plan_check(int dual, int M, int N, int K, long long cap_floats, int allow_tail, int *launches_out,
+                    int *blocks_out, int *ids_out);
 size_t partial_floats(const st_config &c);  // floats of Workspace::qkv (the split-K / split-key partial results)
 void launch_prefill_layers(const Model &m, int32_t pos0, int32_t n);
 

@@ -103,6 +103,37 @@ def test_model_create_checks_buffers(L):
     assert not h.value
 
 
+def test_long_chunk_launch_plan_covers_every_tile_once(L):
+    """The block numbering of the long-chunk GEMMs (K slices, leftover column tiles cut into slices of their own,
+    half-width tiles of the fused gate/up form) walked on the host for every model shape and a spread of chunk
+    lengths: each output tile and K step computed by exactly one block, partial sums inside the workspace."""
+    from paper_2504_12329_amd import synth
+    seen_two_launches = seen_tail = False
+    for name in synth.SHAPES:
+        cfg = synth.model_config(name, max_seq=8448, max_chunk=8192)
+        h, I = cfg["hidden"], cfg["intermediate"]
+        for rows in (257, 300, 511, 512, 513, 1000, 1024, 2047, 2048, 3000, 4095, 4096, 5000, 8192):
+            launches, blocks = B.st_prefill_plan_check(cfg, rows)
+            my = (rows + 255) // 256
+            qd = cfg["n_q_heads"] * cfg["head_dim"]
+            planned = [k % 64 == 0 for k in (h, qd, h, I)]            # QKV, O, gate/up, down: K a multiple of 64
+            tiles = my * (planned[1] * ((h + 255) // 256) + planned[2] * ((I + 127) // 128))
+            assert launches >= sum(planned) and blocks >= tiles
+            seen_two_launches |= launches > sum(planned)
+    # ragged widths: a last column tile narrower than a tile in every projection
+    cfg = synth.model_config("qwen1p5b", max_seq=4200, max_chunk=4096)
+    cfg.update(hidden=4288, intermediate=2240, n_q_heads=6, n_kv_heads=1)
+    for rows in (257, 1024, 4000, 4096):
+        launches, blocks = B.st_prefill_plan_check(cfg, rows)
+        seen_tail |= rows == 4096 and launches == 5
+    assert seen_two_launches and seen_tail
+    assert B.st_prefill_plan_check(cfg, 256) == (0, 0) and B.st_prefill_plan_check(cfg, 1) == (0, 0)
+    with pytest.raises(B.StError):
+        B.st_prefill_plan_check(cfg, 4097)
+    with pytest.raises(B.StError):
+        B.st_prefill_plan_check(cfg, 0)
+
+
 def test_bench_refuses_more_than_one_gpu():
     """The path is a single-GPU one: the benchmark says so instead of starting ranks."""
     import subprocess
