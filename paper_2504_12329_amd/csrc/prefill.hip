@@ -488,10 +488,9 @@ __global__ __launch_bounds__(256) void k_gemm_ring(const bf16_t *__restrict__ A,
                 as_bf16x8(*reinterpret_cast<const u32x4 *>(ring + slotA * kRingSlot + a_off + (q & 3) * 4096 + ch));
         }
     };
-    auto mma_row = [&](auto buf_c, auto i_c) {
-        constexpr int buf = decltype(buf_c)::value, i = decltype(i_c)::value;
-#pragma unroll
-        for (int j = 0; j < NB; ++j)
+    auto mma_one = [&](auto buf_c, auto i_c, auto j_c) {
+        constexpr int buf = decltype(buf_c)::value, i = decltype(i_c)::value, j = decltype(j_c)::value;
+        if constexpr (j < NB)
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[buf][i], fb[buf][j], acc[i][j], 0, 0, 0);
     };
     // One 16-wide step: four groups of { one direct load (KIND 1: weight instruction D0+g, 2: activation
@@ -501,14 +500,22 @@ __global__ __launch_bounds__(256) void k_gemm_ring(const bf16_t *__restrict__ A,
                     int dkt) {
         constexpr int cur = decltype(cur_c)::value, kind = decltype(kind_c)::value, d0 = decltype(d0_c)::value;
         constexpr bool FETCH = decltype(fetch_c)::value != 0;
+        // the load and the two reads sit between the group's MFMAs, each issued while the MFMA before it runs
 #define ST_GEMM_GROUP(g)                                                      \
+    mma_one(ic<cur>{}, ic<g>{}, ic<0>{});                                     \
+    __builtin_amdgcn_sched_barrier(0);                                        \
     if (kind == 1) loadB(ic<d0 + g>{}, dslot, dkt);                           \
     if (kind == 2) loadA(ic<d0 + g>{}, dslot, dkt);                           \
-    if (FETCH) {                                                              \
-        fetch(ic<cur ^ 1>{}, ic<2 * g>{}, slotA, slotB, ks_next);             \
-        fetch(ic<cur ^ 1>{}, ic<2 * g + 1>{}, slotA, slotB, ks_next);         \
-    }                                                                         \
-    mma_row(ic<cur>{}, ic<g>{});                                              \
+    __builtin_amdgcn_sched_barrier(0);                                        \
+    mma_one(ic<cur>{}, ic<g>{}, ic<1>{});                                     \
+    __builtin_amdgcn_sched_barrier(0);                                        \
+    if (FETCH) fetch(ic<cur ^ 1>{}, ic<2 * g>{}, slotA, slotB, ks_next);      \
+    __builtin_amdgcn_sched_barrier(0);                                        \
+    mma_one(ic<cur>{}, ic<g>{}, ic<2>{});                                     \
+    __builtin_amdgcn_sched_barrier(0);                                        \
+    if (FETCH) fetch(ic<cur ^ 1>{}, ic<2 * g + 1>{}, slotA, slotB, ks_next);  \
+    __builtin_amdgcn_sched_barrier(0);                                        \
+    mma_one(ic<cur>{}, ic<g>{}, ic<3>{});                                     \
     __builtin_amdgcn_sched_barrier(0);
         ST_GEMM_GROUP(0) ST_GEMM_GROUP(1) ST_GEMM_GROUP(2) ST_GEMM_GROUP(3)
 #undef ST_GEMM_GROUP
