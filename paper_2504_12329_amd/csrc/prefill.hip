@@ -709,42 +709,47 @@ __global__ __launch_bounds__(SPEC ? 512 : 256) void k_gemm_stream(const bf16_t *
         if (SPEC && more) static_for<NL>([&](auto i_c) { issue_one(i_c); });
         if (computes) {
             const unsigned char *wb = ring + a_ring + wslot * wstage, *ab = ring + aslot * kAStage;
-            // fragments of K step ks + 1 are read while the MFMAs of step ks run
+            // fragments of K step ks + 1 are read while the MFMAs of step ks run: one 16-byte read behind each of the
+            // first MFMAs (read r of a step: 0 the first weight tile, 1 / 2 activation tile 0 high / low, 3 the second
+            // weight tile, then the other activation tiles), pinned there -- issued as one run ahead of the MFMAs
+            // they cost the matrix pipe their issue time
             bf16x8 wf[2][2], ah[2][MT], al[2][MT];
-            auto frags = [&](auto ks_c) {
-                constexpr int ks = decltype(ks_c)::value, b = ks & 1;
+            constexpr int NR = 2 + 2 * MT, NM = 4 * MT;  // reads and MFMAs of a 16-wide step (NR <= NM)
+            auto frag = [&](auto ks_c, auto r_c) {
+                constexpr int ks = decltype(ks_c)::value, b = ks & 1, r = decltype(r_c)::value;
                 const int c = 2 * ks + kg;
-                wf[b][0] =
-                    as_bf16x8(*reinterpret_cast<const u32x4 *>(wb + (wave * 32 + l32) * G::kSeg + (c ^ sw_w) * 16));
-                if (second)
-                    wf[b][1] = as_bf16x8(
-                        *reinterpret_cast<const u32x4 *>(wb + ((wave + 4) * 32 + l32) * G::kSeg + (c ^ sw_w) * 16));
-#pragma unroll
-                for (int t = 0; t < MT; ++t) {
-                    ah[b][t] = as_bf16x8(
-                        *reinterpret_cast<const u32x4 *>(ab + (t * 64 + l32) * G::kSeg + (c ^ sw_even) * 16));
-                    al[b][t] = as_bf16x8(
-                        *reinterpret_cast<const u32x4 *>(ab + (t * 64 + 32 + l32) * G::kSeg + (c ^ sw_odd) * 16));
+                if constexpr (r == 0) {
+                    wf[b][0] =
+                        as_bf16x8(*reinterpret_cast<const u32x4 *>(wb + (wave * 32 + l32) * G::kSeg + (c ^ sw_w) * 16));
+                } else if constexpr (r == 3) {
+                    if (second)
+                        wf[b][1] = as_bf16x8(
+                            *reinterpret_cast<const u32x4 *>(wb + ((wave + 4) * 32 + l32) * G::kSeg + (c ^ sw_w) * 16));
+                } else {
+                    constexpr int q = r < 3 ? r - 1 : r - 2, t = q >> 1;  // q: 0 / 1 = tile 0 high / low, 2 / 3 = tile 1 ...
+                    if constexpr ((q & 1) == 0)
+                        ah[b][t] = as_bf16x8(
+                            *reinterpret_cast<const u32x4 *>(ab + (t * 64 + l32) * G::kSeg + (c ^ sw_even) * 16));
+                    else
+                        al[b][t] = as_bf16x8(
+                            *reinterpret_cast<const u32x4 *>(ab + (t * 64 + 32 + l32) * G::kSeg + (c ^ sw_odd) * 16));
                 }
             };
-            frags(ic<0>{});
+            static_for<NR>([&](auto r_c) { frag(ic<0>{}, r_c); });
             static_for<KS>([&](auto ks_c) {
                 constexpr int ks = decltype(ks_c)::value, b = ks & 1;
-                if constexpr (ks + 1 < KS) frags(ic<ks + 1>{});
-                static_for<2>([&](auto j_c) {
-                    constexpr int j = decltype(j_c)::value;
-                    // a share of this wave's loads for the stage it fills, between the MFMA groups
-                    if (!SPEC && more)
-                        static_for<PER>([&](auto q_c) { issue_one(ic<(2 * ks + j) * PER + decltype(q_c)::value>{}); });
-                    if (j == 0 || second) {
-#pragma unroll
-                        for (int t = 0; t < MT; ++t) {
-                            acc[j][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[b][j], ah[b][t], acc[j][t], 0, 0, 0);
-                            acc[j][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[b][j], al[b][t], acc[j][t], 0, 0, 0);
-                        }
-                    }
+                static_for<NM>([&](auto m_c) {
+                    constexpr int m = decltype(m_c)::value, j = m / (2 * MT), t = (m % (2 * MT)) / 2;
+                    // a share of this wave's loads for the stage it fills, ahead of each weight tile's MFMAs
+                    if constexpr (m % (2 * MT) == 0)
+                        if (!SPEC && more)
+                            static_for<PER>([&](auto q_c) { issue_one(ic<(2 * ks + j) * PER + decltype(q_c)::value>{}); });
+                    if (j == 0 || second)
+                        acc[j][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[b][j], (m & 1) ? al[b][t] : ah[b][t],
+                                                                            acc[j][t], 0, 0, 0);
+                    if constexpr (ks + 1 < KS && m < NR) frag(ic<ks + 1>{}, m_c);
+                    __builtin_amdgcn_sched_barrier(0);
                 });
-                __builtin_amdgcn_sched_barrier(0);
             });
         }
         if (more) issued();
