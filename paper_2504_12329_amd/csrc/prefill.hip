@@ -1210,21 +1210,32 @@ __global__ __launch_bounds__(64 * NW, TWO ? 1 : 2) void k_flash_long(const bf16_
     bf16x8 pf[4];
     auto tile_active = [&](int t) { return wave_active && t * kFlashKeys <= wave_last_key; };
     // S^T of tile t: two 32-key sub-tiles x 32 rows
+    // (fragment reads run kAhead MFMAs ahead of their use, one read pinned behind each MFMA: an LDS read takes
+    // longer than the one or two MFMAs the compiler's own schedule leaves between a read and its use)
+    constexpr int kAhead = 4;
     auto scores = [&](int t) {
         if (!tile_active(t)) return;
         const unsigned char *kt = &Ks[t & 1][0];
 #pragma unroll
-        for (int u = 0; u < 2; ++u) {
+        for (int u = 0; u < 2; ++u)
 #pragma unroll
             for (int r = 0; r < 16; ++r) sacc[u][r] = 0.f;
-#pragma unroll
-            for (int s = 0; s < D / 16; ++s) {
-                bf16x8 kf = as_bf16x8(
-                    *reinterpret_cast<const u32x4 *>(kt + (u * 32 + krow) * 256 + (((2 * s + kg) ^ k_swz) * 16)));
-                sacc[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[s], sacc[u], 0, 0, 0);
-                if constexpr (TWO) sacc[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, ql[s], sacc[u], 0, 0, 0);
-            }
-        }
+        constexpr int NS = D / 16;  // 16-wide steps of a sub-tile; fragment i is sub-tile i / NS, step i % NS
+        bf16x8 kf[kAhead];
+        auto kread = [&](auto i_c) {
+            constexpr int i = decltype(i_c)::value, u = i / NS, s = i % NS;
+            kf[i % kAhead] = as_bf16x8(
+                *reinterpret_cast<const u32x4 *>(kt + (u * 32 + krow) * 256 + (((2 * s + kg) ^ k_swz) * 16)));
+        };
+        static_for<kAhead>([&](auto i_c) { kread(i_c); });
+        __builtin_amdgcn_sched_barrier(0);
+        static_for<2 * NS>([&](auto i_c) {
+            constexpr int i = decltype(i_c)::value, u = i / NS, s = i % NS;
+            sacc[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[i % kAhead], qf[s], sacc[u], 0, 0, 0);
+            if constexpr (TWO) sacc[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[i % kAhead], ql[s], sacc[u], 0, 0, 0);
+            if constexpr (i + kAhead < 2 * NS) kread(ic<i + kAhead>{});
+            __builtin_amdgcn_sched_barrier(0);
+        });
     };
     // online softmax of tile t: lane = query row; register r of sub-tile u is key 32u + 16*(r/8) + 8*kg + r%8
     auto softmax = [&](int t) {
@@ -1282,13 +1293,20 @@ __global__ __launch_bounds__(64 * NW, TWO ? 1 : 2) void k_flash_long(const bf16_
     auto weighted_values = [&](int t) {
         if (!tile_active(t)) return;
         const bf16_t *vt = &Vt[t & 1][0];
-#pragma unroll
-        for (int tt = 0; tt < D / 32; ++tt)
-#pragma unroll
-            for (int s2 = 0; s2 < 4; ++s2) {
-                bf16x8 vf = as_bf16x8(*reinterpret_cast<const u32x4 *>(&vt[(tt * 32 + l32) * VS + 16 * s2 + 8 * kg]));
-                o[tt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[s2], o[tt], 0, 0, 0);
-            }
+        constexpr int NV = (D / 32) * 4;  // fragment i: output tile i / 4, 16-key step i % 4
+        bf16x8 vf[kAhead];
+        auto vread = [&](auto i_c) {
+            constexpr int i = decltype(i_c)::value, tt = i / 4, s2 = i % 4;
+            vf[i % kAhead] = as_bf16x8(*reinterpret_cast<const u32x4 *>(&vt[(tt * 32 + l32) * VS + 16 * s2 + 8 * kg]));
+        };
+        static_for<kAhead>([&](auto i_c) { vread(i_c); });
+        __builtin_amdgcn_sched_barrier(0);
+        static_for<NV>([&](auto i_c) {
+            constexpr int i = decltype(i_c)::value, tt = i / 4, s2 = i % 4;
+            o[tt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[i % kAhead], pf[s2], o[tt], 0, 0, 0);
+            if constexpr (i + kAhead < NV) vread(ic<i + kAhead>{});
+            __builtin_amdgcn_sched_barrier(0);
+        });
     };
 
     // One barrier per tile: before it a wave writes its part of V^T(t) and waits for its part of K(t); after it
