@@ -576,7 +576,9 @@ __global__ __launch_bounds__(256) void k_gemm_ring(const bf16_t *__restrict__ A,
                     const int col = n0 + wn * (NB * 16) + j * 32 + l32;
                     if (col < N) {
                         const float gt = acc[i][j][r], up = acc[i][j + NB / 2][r];
-                        outb[(size_t)row * ldo + col] = f32_to_bf16(gt / (1.0f + expf(-gt)) * up);
+                        // silu through the hardware exp2 and reciprocal (1 ulp each, far below the bf16 result)
+                        const float sg = __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * gt));
+                        outb[(size_t)row * ldo + col] = f32_to_bf16(gt * sg * up);
                     }
                 }
             } else {
