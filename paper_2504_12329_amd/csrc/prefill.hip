@@ -564,31 +564,45 @@ __global__ __launch_bounds__(256) void k_gemm_ring(const bf16_t *__restrict__ A,
     kstep(kt++, ic<0>{});
 
     // epilogue: register r of a 32x32 tile is row 8*(r/4) + 4*(lane/32) + r%4, column lane%32
+    if constexpr (DUAL) {
+        // Two rows at a time: neighbouring lanes (columns c, c + 1) swap one value each, so that the even lane holds
+        // both columns of the first row and the odd lane both of the second -- one 4-byte store per lane instead of
+        // two 2-byte ones.  silu goes through the hardware exp2 and reciprocal (1 ulp each, far below bf16).
+        const bool odd = l32 & 1;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+        for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int row = m0 + wm * 128 + i * 32 + 8 * (r >> 2) + 4 * kg + (r & 3);
-            if (row >= M) continue;
-            if (DUAL) {
+            for (int j = 0; j < NB / 2; ++j)
 #pragma unroll
-                for (int j = 0; j < NB / 2; ++j) {
-                    const int col = n0 + wn * (NB * 16) + j * 32 + l32;
-                    if (col < N) {
-                        const float gt = acc[i][j][r], up = acc[i][j + NB / 2][r];
-                        // silu through the hardware exp2 and reciprocal (1 ulp each, far below the bf16 result)
-                        const float sg = __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * gt));
-                        outb[(size_t)row * ldo + col] = f32_to_bf16(gt * sg * up);
+                for (int r = 0; r < 16; r += 2) {
+                    float a[2];
+#pragma unroll
+                    for (int e = 0; e < 2; ++e) {
+                        const float gt = acc[i][j][r + e], up = acc[i][j + NB / 2][r + e];
+                        a[e] = gt * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * gt)) * up;
                     }
+                    const float other = dpp_move<0xB1, 0xf>(0.f, odd ? a[0] : a[1]);  // quad_perm [1,0,3,2]
+                    const uint32_t pk = odd ? pack_bf16x2(other, a[1]) : pack_bf16x2(a[0], other);
+                    const int row = m0 + wm * 128 + i * 32 + 8 * (r >> 2) + 4 * kg + (r & 3) + (odd ? 1 : 0);
+                    const int col = n0 + wn * (NB * 16) + j * 32 + (l32 & ~1);
+                    if (row < M && col + 1 < N)
+                        *reinterpret_cast<uint32_t *>(outb + (size_t)row * ldo + col) = pk;
+                    else if (row < M && col < N)  // an odd width: the last column alone
+                        outb[(size_t)row * ldo + col] = (bf16_t)(pk & 0xffffu);
                 }
-            } else {
+    } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int row = m0 + wm * 128 + i * 32 + 8 * (r >> 2) + 4 * kg + (r & 3);
+                if (row >= M) continue;
 #pragma unroll
                 for (int j = 0; j < NB; ++j) {
                     const int col = n0 + wn * 128 + j * 32 + l32;
                     if (col < N) pz[(size_t)row * ldp + col] = acc[i][j][r];
                 }
             }
-        }
     }
 }
 
