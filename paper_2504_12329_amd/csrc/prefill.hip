@@ -801,43 +801,46 @@ __global__ __launch_bounds__(SPEC ? 512 : 256) void k_gemm_stream(const bf16_t *
 
 // ---------------------------------------------------------------------------------------
 // RoPE on q and k at absolute positions pos0 + row, K/V appended to the cache, q kept as bf16.
-// grid (rows, heads / kRopeHeads), block kRopeHeads * d/2 threads: one rotation pair per thread, kRopeHeads heads
-// per block (one head per block is a grid of 64-thread blocks that the dispatcher, not the memory, paces).
+// A thread owns four neighbouring rotation pairs (i, i + d/2) of one head: 16-byte loads of the partial sums and
+// the rotation table, 8-byte stores; d/8 threads per head, 256 / (d/8) heads per block, grid (rows, head groups).
 // ---------------------------------------------------------------------------------------
-constexpr int kRopeHeads = 4;
-__global__ void k_rope_append(const float *__restrict__ part, int n_part, size_t part_stride,
-                              const bf16_t *__restrict__ bias, const float2 *__restrict__ rope,
-                              bf16_t *__restrict__ qb, bf16_t *__restrict__ qb_lo, bf16_t *__restrict__ kc,
-                              bf16_t *__restrict__ vc, int pos0, int nq, int nkv, int d, int max_seq,
-                              PartTail tail) {
-    const int half = d >> 1, row = blockIdx.x;
-    const int head = blockIdx.y * kRopeHeads + threadIdx.x / half, i = threadIdx.x % half;
+__global__ __launch_bounds__(256) void k_rope_append(const float *__restrict__ part, int n_part, size_t part_stride,
+                                                     const bf16_t *__restrict__ bias, const float2 *__restrict__ rope,
+                                                     bf16_t *__restrict__ qb, bf16_t *__restrict__ qb_lo,
+                                                     bf16_t *__restrict__ kc, bf16_t *__restrict__ vc, int pos0, int nq,
+                                                     int nkv, int d, int max_seq, PartTail tail) {
+    const int half = d >> 1, tph = d >> 3, row = blockIdx.x;  // tph: threads per head
+    const int head = blockIdx.y * (256 / tph) + threadIdx.x / tph, i = 4 * (threadIdx.x % tph);
     if (head >= nq + 2 * nkv) return;
     const int pos = pos0 + row;
     const size_t off = (size_t)row * (nq + 2 * nkv) * d + head * d;
-    float lo = 0.f, hi = 0.f;
-    for (int s = 0; s < n_part; ++s) {
-        const float *src = part + (size_t)s * part_stride + off;
-        lo += src[i];
-        hi += src[i + half];
-    }
+    float lo[4] = {0.f, 0.f, 0.f, 0.f}, hi[4] = {0.f, 0.f, 0.f, 0.f};
+    auto add = [&](const float *src) {
+        const float4 a = *reinterpret_cast<const float4 *>(src + i), b = *reinterpret_cast<const float4 *>(src + i + half);
+        lo[0] += a.x, lo[1] += a.y, lo[2] += a.z, lo[3] += a.w;
+        hi[0] += b.x, hi[1] += b.y, hi[2] += b.z, hi[3] += b.w;
+    };
+    for (int s = 0; s < n_part; ++s) add(part + (size_t)s * part_stride + off);
     if (tail.n && head * d >= tail.col0) {  // col0 is a multiple of 256, so a head lies on one side of it
         const float *src = part + tail.base + (long long)row * tail.ld + (head * d - tail.col0);
-        for (int t = 0; t < tail.n; ++t, src += tail.stride) {
-            lo += src[i];
-            hi += src[i + half];
-        }
+        for (int t = 0; t < tail.n; ++t, src += tail.stride) add(src);
     }
     if (bias) {
-        lo += bf16_to_f32(bias[head * d + i]);
-        hi += bf16_to_f32(bias[head * d + i + half]);
+        const u32x2 bl = *reinterpret_cast<const u32x2 *>(bias + head * d + i);
+        const u32x2 bh = *reinterpret_cast<const u32x2 *>(bias + head * d + i + half);
+        lo[0] += bf16_lo(bl.x), lo[1] += bf16_hi(bl.x), lo[2] += bf16_lo(bl.y), lo[3] += bf16_hi(bl.y);
+        hi[0] += bf16_lo(bh.x), hi[1] += bf16_hi(bh.x), hi[2] += bf16_lo(bh.y), hi[3] += bf16_hi(bh.y);
     }
     if (head < nq + nkv) {
-        float2 cs = rope[(size_t)pos * half + i];
-        float nlo = lo * cs.x - hi * cs.y;
-        float nhi = hi * cs.x + lo * cs.y;
-        lo = nlo;
-        hi = nhi;
+        const float4 *cs4 = reinterpret_cast<const float4 *>(rope + (size_t)pos * half + i);
+        const float4 c01 = cs4[0], c23 = cs4[1];  // (cos, sin) of pairs i, i+1 and i+2, i+3
+        const float cx[4] = {c01.x, c01.z, c23.x, c23.z}, sy[4] = {c01.y, c01.w, c23.y, c23.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const float nlo = lo[e] * cx[e] - hi[e] * sy[e];
+            const float nhi = hi[e] * cx[e] + lo[e] * sy[e];
+            lo[e] = nlo, hi[e] = nhi;
+        }
     }
     bf16_t *dst;
     if (head < nq)
@@ -846,13 +849,18 @@ __global__ void k_rope_append(const float *__restrict__ part, int n_part, size_t
         dst = kc + ((size_t)(head - nq) * max_seq + pos) * d;
     else
         dst = vc + ((size_t)(head - nq - nkv) * max_seq + pos) * d;
-    const bf16_t blo = f32_to_bf16(lo), bhi = f32_to_bf16(hi);
-    dst[i] = blo;
-    dst[i + half] = bhi;
+    const u32x2 plo = {pack_bf16x2(lo[0], lo[1]), pack_bf16x2(lo[2], lo[3])};
+    const u32x2 phi = {pack_bf16x2(hi[0], hi[1]), pack_bf16x2(hi[2], hi[3])};
+    *reinterpret_cast<u32x2 *>(dst + i) = plo;
+    *reinterpret_cast<u32x2 *>(dst + i + half) = phi;
     if (head < nq && qb_lo) {  // short chunks: the query keeps 16 mantissa bits as a second bf16 term
         bf16_t *dl = qb_lo + (size_t)row * nq * d + head * d;
-        dl[i] = f32_to_bf16(lo - bf16_to_f32(blo));
-        dl[i + half] = f32_to_bf16(hi - bf16_to_f32(bhi));
+        const u32x2 rlo = {pack_bf16x2(lo[0] - bf16_lo(plo.x), lo[1] - bf16_hi(plo.x)),
+                           pack_bf16x2(lo[2] - bf16_lo(plo.y), lo[3] - bf16_hi(plo.y))};
+        const u32x2 rhi = {pack_bf16x2(hi[0] - bf16_lo(phi.x), hi[1] - bf16_hi(phi.x)),
+                           pack_bf16x2(hi[2] - bf16_lo(phi.y), hi[3] - bf16_hi(phi.y))};
+        *reinterpret_cast<u32x2 *>(dl + i) = rlo;
+        *reinterpret_cast<u32x2 *>(dl + i + half) = rhi;
     }
 }
 
@@ -1809,8 +1817,8 @@ void launch_prefill_layers(const Model &m, int32_t pos0, int32_t n) {
         hipLaunchKernelGGL(k_rmsnorm_rows, dim3(n), dim3(norm_threads(n)), 0, m.stream, w.x, w.qkv, pending, (size_t)n * h,
                            m.norm_attn[l], w.xn, xn_lo, h, c.rms_eps, pend_tail);
         int sq = gemm<false>(m, w.xn, xn_lo, h, m.wqkv[l], n, qkv, h, nullptr, nullptr, 0, &tq);
-        hipLaunchKernelGGL(k_rope_append, dim3(n, (nq + 2 * nkv + kRopeHeads - 1) / kRopeHeads),
-                           dim3(kRopeHeads * d / 2), 0, m.stream, w.qkv, sq,
+        hipLaunchKernelGGL(k_rope_append, dim3(n, ((nq + 2 * nkv) * (d / 8) + 255) / 256), dim3(256), 0, m.stream,
+                           w.qkv, sq,
                            (size_t)n * qkv, m.bqkv[l], w.rope, w.qb, qb_lo, m.kcache + lofs, m.vcache + lofs, pos0, nq, nkv,
                            d, c.max_seq, tq);
         launch_flash(m, w.qb, qb_lo, m.kcache + lofs, m.vcache + lofs, w.attn, attn_lo, n, pos0);
