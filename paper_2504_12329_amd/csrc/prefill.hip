@@ -61,8 +61,12 @@ __global__ __launch_bounds__(1024) void k_rmsnorm_rows(float *__restrict__ X, co
     const size_t ps4 = part_stride / 4;
     const int n4 = h >> 2;  // h is a multiple of 8
     const int nthr = blockDim.x;  // 256, or 1024 where the rows are few and each would be a long serial walk
+    // a thread's updated residual elements stay in registers between the two passes (up to kKeep groups of four;
+    // rows longer than kKeep * 4 * blockDim.x re-read the rest from x)
+    constexpr int kKeep = 8;
+    float4 keep[kKeep];
     float ss = 0.f;
-    for (int i = threadIdx.x; i < n4; i += nthr) {
+    auto update = [&](int i) {
         float4 v = x[i];
         for (int s0 = 0; s0 < n_part; s0 += 8) {  // slices in ascending order, eight loads in flight
             float4 q[8];
@@ -86,7 +90,14 @@ __global__ __launch_bounds__(1024) void k_rmsnorm_rows(float *__restrict__ X, co
         }
         if (n_part) x[i] = v;
         ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+        return v;
+    };
+#pragma unroll
+    for (int k = 0; k < kKeep; ++k) {
+        const int i = threadIdx.x + k * nthr;
+        if (i < n4) keep[k] = update(i);
     }
+    for (int i = threadIdx.x + kKeep * nthr; i < n4; i += nthr) update(i);
     if (!g) return;
     ss = wave_sum(ss);
     if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
@@ -97,8 +108,7 @@ __global__ __launch_bounds__(1024) void k_rmsnorm_rows(float *__restrict__ X, co
     u32x2 *y = reinterpret_cast<u32x2 *>(Y + (size_t)blockIdx.x * h);
     u32x2 *ylo = Ylo ? reinterpret_cast<u32x2 *>(Ylo + (size_t)blockIdx.x * h) : nullptr;
     const u32x2 *g2 = reinterpret_cast<const u32x2 *>(g);
-    for (int i = threadIdx.x; i < n4; i += nthr) {
-        float4 v = x[i];
+    auto emit = [&](int i, const float4 &v) {
         u32x2 gg = g2[i];
         float a = v.x * inv * bf16_lo(gg.x), b = v.y * inv * bf16_hi(gg.x);
         float c = v.z * inv * bf16_lo(gg.y), d = v.w * inv * bf16_hi(gg.y);
@@ -108,7 +118,13 @@ __global__ __launch_bounds__(1024) void k_rmsnorm_rows(float *__restrict__ X, co
             u32x2 lo = {pack_bf16x2(a - bf16_lo(hi.x), b - bf16_hi(hi.x)), pack_bf16x2(c - bf16_lo(hi.y), d - bf16_hi(hi.y))};
             ylo[i] = lo;
         }
+    };
+#pragma unroll
+    for (int k = 0; k < kKeep; ++k) {
+        const int i = threadIdx.x + k * nthr;
+        if (i < n4) emit(i, keep[k]);
     }
+    for (int i = threadIdx.x + kKeep * nthr; i < n4; i += nthr) emit(i, x[i]);
 }
 
 // ---------------------------------------------------------------------------------------
