@@ -61,8 +61,9 @@ __global__ __launch_bounds__(1024) void k_rmsnorm_rows(float *__restrict__ X, co
     const size_t ps4 = part_stride / 4;
     const int n4 = h >> 2;  // h is a multiple of 8
     const int nthr = blockDim.x;  // 256, or 1024 where the rows are few and each would be a long serial walk
-    // a thread's updated residual elements stay in registers between the two passes (up to kKeep groups of four;
-    // rows longer than kKeep * 4 * blockDim.x re-read the rest from x)
+    // a thread's updated residual elements stay in registers between the two passes: kKeep groups of four cover
+    // the longest row the library accepts (hidden 8192) at 256 threads; the trailing loops would re-read anything
+    // beyond that from x
     constexpr int kKeep = 8;
     float4 keep[kKeep];
     float ss = 0.f;
