@@ -134,6 +134,21 @@ def test_long_chunk_launch_plan_covers_every_tile_once(L):
         B.st_prefill_plan_check(cfg, 0)
 
 
+def test_long_chunk_launch_plan_on_random_shapes(L):
+    """The same walk over seeded random configurations: odd widths, every group size, chunk limits from 300 to 8192."""
+    import random
+    from paper_2504_12329_amd import synth
+    rng = random.Random(5)
+    for _ in range(150):
+        d, nkv, grp = rng.choice([64, 128]), rng.choice([1, 2, 4, 8]), rng.choice([1, 2, 4, 5, 6, 7, 8])
+        mc = rng.choice([300, 512, 1000, 2048, 4096, 8192])
+        cfg = synth.model_config("qwen1p5b", max_seq=mc + 64, max_chunk=mc)
+        cfg.update(hidden=64 * rng.randint(2, 128), intermediate=8 * rng.randint(16, 3599), n_q_heads=nkv * grp,
+                   n_kv_heads=nkv, head_dim=d, vocab=1024, tie_embeddings=0)
+        for rows in {257, mc, rng.randint(257, mc)}:
+            B.st_prefill_plan_check(cfg, rows)   # raises StError naming the projection if a plan is inconsistent
+
+
 def test_bench_refuses_more_than_one_gpu():
     """The path is a single-GPU one: the benchmark says so instead of starting ranks."""
     import subprocess
