@@ -517,20 +517,20 @@ __global__ __launch_bounds__(256) void k_gemm_ring(const bf16_t *__restrict__ A,
                     int dkt) {
         constexpr int cur = decltype(cur_c)::value, kind = decltype(kind_c)::value, d0 = decltype(d0_c)::value;
         constexpr bool FETCH = decltype(fetch_c)::value != 0;
-        // the load and the two reads sit between the group's MFMAs, each issued while the MFMA before it runs
+        // the two reads and the load sit between the group's MFMAs, each issued while the MFMA before it runs
 #define ST_GEMM_GROUP(g)                                                      \
     mma_one(ic<cur>{}, ic<g>{}, ic<0>{});                                     \
     __builtin_amdgcn_sched_barrier(0);                                        \
-    if (kind == 1) loadB(ic<d0 + g>{}, dslot, dkt);                           \
-    if (kind == 2) loadA(ic<d0 + g>{}, dslot, dkt);                           \
+    if (FETCH) fetch(ic<cur ^ 1>{}, ic<2 * g>{}, slotA, slotB, ks_next);      \
     __builtin_amdgcn_sched_barrier(0);                                        \
     mma_one(ic<cur>{}, ic<g>{}, ic<1>{});                                     \
     __builtin_amdgcn_sched_barrier(0);                                        \
-    if (FETCH) fetch(ic<cur ^ 1>{}, ic<2 * g>{}, slotA, slotB, ks_next);      \
+    if (FETCH) fetch(ic<cur ^ 1>{}, ic<2 * g + 1>{}, slotA, slotB, ks_next);  \
     __builtin_amdgcn_sched_barrier(0);                                        \
     mma_one(ic<cur>{}, ic<g>{}, ic<2>{});                                     \
     __builtin_amdgcn_sched_barrier(0);                                        \
-    if (FETCH) fetch(ic<cur ^ 1>{}, ic<2 * g + 1>{}, slotA, slotB, ks_next);  \
+    if (kind == 1) loadB(ic<d0 + g>{}, dslot, dkt);                           \
+    if (kind == 2) loadA(ic<d0 + g>{}, dslot, dkt);                           \
     __builtin_amdgcn_sched_barrier(0);                                        \
     mma_one(ic<cur>{}, ic<g>{}, ic<3>{});                                     \
     __builtin_amdgcn_sched_barrier(0);
