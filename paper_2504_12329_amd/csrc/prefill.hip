@@ -344,6 +344,12 @@ __device__ __forceinline__ void load_to_lds16(const void *g, uint32_t lds_off) {
                  "s"(__builtin_amdgcn_readfirstlane(lds_off))
                  : "memory");
 }
+// the same from a wave-uniform base and a 32-bit byte offset per lane (half the address registers to read)
+__device__ __forceinline__ void load_to_lds16(const void *base, uint32_t byte_off, uint32_t lds_off) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(byte_off), "s"(base),
+                 "s"(__builtin_amdgcn_readfirstlane(lds_off))
+                 : "memory");
+}
 template <int N>
 __device__ __forceinline__ void wait_loads() {  // until at most N of this wave's direct loads are outstanding
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
@@ -440,12 +446,12 @@ __global__ __launch_bounds__(256) void k_gemm_ring(const bf16_t *__restrict__ A,
     // direct loads: instruction i of a wave fills LDS rows [(wave*8+i)*8, +8) of a slot, lane -> (row lane/8,
     // 16-byte position lane%8, which holds global chunk position ^ swizzle(row)); rows past the edge re-read
     // the last valid row (their results are never stored)
-    const bf16_t *pa[8], *pb[NLB];
+    uint32_t pa[8], pb[NLB];  // byte offsets from A / B (every operand of the library is far below 4 GB)
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
         const int row = (wave * 8 + i) * 8 + (lane >> 3);
         const int c = (lane & 7) ^ ring_swz(row);
-        pa[i] = A + (size_t)min(m0 + row, M - 1) * lda + kbeg + c * 8;
+        pa[i] = (uint32_t)(((size_t)min(m0 + row, M - 1) * lda + kbeg + c * 8) * sizeof(bf16_t));
     }
 #pragma unroll
     for (int i = 0; i < NLB; ++i) {
@@ -458,16 +464,16 @@ __global__ __launch_bounds__(256) void k_gemm_ring(const bf16_t *__restrict__ A,
             bn = min(n0 + (row & 127), N - 1) + (row >> 7) * N;
         else
             bn = min(n0 + row, N - 1);
-        pb[i] = B + (size_t)bn * K + kbeg + c * 8;
+        pb[i] = (uint32_t)(((size_t)bn * K + kbeg + c * 8) * sizeof(bf16_t));
     }
     auto loadA = [&](auto i_c, int slot, int kt) {
         constexpr int i = decltype(i_c)::value;
-        load_to_lds16(pa[i] + kt * kRingBK, ring0 + slot * kRingSlot + (wave * 8 + i) * 1024);
+        load_to_lds16(A, pa[i] + kt * (kRingBK * 2), ring0 + slot * kRingSlot + (wave * 8 + i) * 1024);
     };
     auto loadB = [&](auto i_c, int slot, int kt) {
         constexpr int i = decltype(i_c)::value;
         if constexpr (i < NLB)
-            load_to_lds16(pb[i] + kt * kRingBK, ring0 + slot * kRingSlot + (wave * NLB + i) * 1024);
+            load_to_lds16(B, pb[i] + kt * (kRingBK * 2), ring0 + slot * kRingSlot + (wave * NLB + i) * 1024);
     };
 
     f32x16 acc[4][NB];
@@ -1704,7 +1710,10 @@ template <bool DUAL>
 static int gemm(const Model &m, const bf16_t *A, const bf16_t *Alo, int lda, const bf16_t *B, int M, int N, int K,
                 bf16_t *outb, bf16_t *outlo, int ldo, PartTail *tail = nullptr) {
     if (tail) *tail = PartTail{};
-    const bool big = !Alo && M >= kBigRows && K % kRingBK == 0 && K >= 2 * kRingBK;
+    // (the ring kernel addresses its operands with 32-bit byte offsets)
+    const bool fits32 = (size_t)M * lda * sizeof(bf16_t) < ((size_t)1 << 32) &&
+                        (size_t)(DUAL ? 2 : 1) * N * K * sizeof(bf16_t) < ((size_t)1 << 32);
+    const bool big = !Alo && M >= kBigRows && K % kRingBK == 0 && K >= 2 * kRingBK && fits32;
     if (!DUAL && Alo && M <= kSplitRows && K % kRingBK == 0) {
         const StreamShape sh = stream_shape(m, M, N, K);
         switch ((M + 31) / 32) {
