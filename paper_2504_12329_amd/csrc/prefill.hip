@@ -1929,31 +1929,65 @@ __global__ void k_rope_append_rows(const float *__restrict__ part, int n_part, s
 }
 
 // Row r: logits[r][:] = sum of the K slices (also stored when logits != nullptr), next[r] = arg-max, lowest id on ties.
-__global__ __launch_bounds__(1024) void k_argmax_rows(const float *__restrict__ part, int n_part, size_t part_stride,
-                                                      int V, float *__restrict__ logits, int32_t *__restrict__ next) {
-    __shared__ float bv[16];
-    __shared__ int bi[16];
-    const int row = blockIdx.x, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+// Two passes: grid (rows, kArgSegs) blocks each reduce one segment of a row to a (value, id) pair, then one wave per
+// row picks among the pairs (one 1024-thread block per row walked 152064 columns in 148 dependent steps: 127 us).
+constexpr int kArgSegs = 16;  // rows * kArgSegs pairs must fit the kLmBlocks-entry scratch arrays (rows <= 64)
+static_assert(64 * kArgSegs <= kLmBlocks, "the per-segment arg-max pairs use the LM head's scratch arrays");
+__device__ __forceinline__ void argmax_take(float &best, int &arg, float v, int id) {
+    if (v > best || (v == best && id < arg)) best = v, arg = id;
+}
+__global__ __launch_bounds__(256) void k_argmax_rows_part(const float *__restrict__ part, int n_part, size_t part_stride,
+                                                          int V, bool vec4, float *__restrict__ logits,
+                                                          float *__restrict__ pv, int32_t *__restrict__ pi) {
+    __shared__ float bv[4];
+    __shared__ int bi[4];
+    const int row = blockIdx.x, seg = blockIdx.y, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int per = ((V + kArgSegs - 1) / kArgSegs + 3) & ~3;  // columns per segment, a multiple of four
+    const int v0 = seg * per, v1 = min(V, v0 + per);
+    const float *p = part + (size_t)row * V;
     float best = -INFINITY;
     int arg = 0x7fffffff;
-    for (int v = threadIdx.x; v < V; v += 1024) {
-        float a = 0.f;
-        for (int s = 0; s < n_part; ++s) a += part[(size_t)s * part_stride + (size_t)row * V + v];
-        if (logits) logits[(size_t)row * V + v] = a;
-        if (a > best) best = a, arg = v;  // ascending v per thread: the first maximum is kept
+    if (vec4) {
+        for (int v = v0 + 4 * threadIdx.x; v < v1; v += 1024) {
+            float4 a = *reinterpret_cast<const float4 *>(p + v);
+            for (int s = 1; s < n_part; ++s) {
+                const float4 q = *reinterpret_cast<const float4 *>(p + (size_t)s * part_stride + v);
+                a.x += q.x, a.y += q.y, a.z += q.z, a.w += q.w;
+            }
+            if (logits) *reinterpret_cast<float4 *>(logits + (size_t)row * V + v) = a;
+            argmax_take(best, arg, a.x, v), argmax_take(best, arg, a.y, v + 1);
+            argmax_take(best, arg, a.z, v + 2), argmax_take(best, arg, a.w, v + 3);
+        }
+    } else {
+        for (int v = v0 + threadIdx.x; v < v1; v += 256) {
+            float a = 0.f;
+            for (int s = 0; s < n_part; ++s) a += p[(size_t)s * part_stride + v];
+            if (logits) logits[(size_t)row * V + v] = a;
+            argmax_take(best, arg, a, v);
+        }
     }
-    for (int o = 32; o > 0; o >>= 1) {
-        const float ob = __shfl_xor(best, o, kWave);
-        const int oa = __shfl_xor(arg, o, kWave);
-        if (ob > best || (ob == best && oa < arg)) best = ob, arg = oa;
-    }
+    for (int o = 32; o > 0; o >>= 1) argmax_take(best, arg, __shfl_xor(best, o, kWave), __shfl_xor(arg, o, kWave));
     if (lane == 0) bv[wave] = best, bi[wave] = arg;
     __syncthreads();
     if (threadIdx.x == 0) {
-        for (int w = 1; w < 16; ++w)
-            if (bv[w] > best || (bv[w] == best && bi[w] < arg)) best = bv[w], arg = bi[w];
-        next[row] = arg;
+        for (int w = 1; w < 4; ++w) argmax_take(best, arg, bv[w], bi[w]);
+        pv[row * kArgSegs + seg] = best, pi[row * kArgSegs + seg] = arg;
     }
+}
+__global__ __launch_bounds__(64) void k_argmax_rows_final(const float *__restrict__ pv, const int32_t *__restrict__ pi,
+                                                          int V, int32_t *__restrict__ next) {
+    const int row = blockIdx.x, lane = threadIdx.x;
+    float best = lane < kArgSegs ? pv[row * kArgSegs + lane] : -INFINITY;
+    int arg = lane < kArgSegs ? pi[row * kArgSegs + lane] : 0x7fffffff;
+    for (int o = 32; o > 0; o >>= 1) argmax_take(best, arg, __shfl_xor(best, o, kWave), __shfl_xor(arg, o, kWave));
+    if (lane == 0) next[row] = arg < V ? arg : 0;  // a row of NaNs compares false everywhere: keep the id in range
+}
+static void launch_argmax_rows(const Model &m, int rows, int n_part, float *logits, int32_t *next) {
+    const int V = m.c.vocab;
+    const bool vec4 = (V & 3) == 0 && ((uintptr_t)logits & 15) == 0;  // 16-byte accesses need both
+    hipLaunchKernelGGL(k_argmax_rows_part, dim3(rows, kArgSegs), dim3(256), 0, m.stream, m.ws.qkv, n_part,
+                       (size_t)rows * V, V, vec4, logits, m.ws.amax_val, m.ws.amax_idx);
+    hipLaunchKernelGGL(k_argmax_rows_final, dim3(rows), dim3(64), 0, m.stream, m.ws.amax_val, m.ws.amax_idx, V, next);
 }
 
 void launch_batch_step(const Model &m, const BatchRows &b, int n, int attn_blocks) {
@@ -1985,8 +2019,7 @@ void launch_batch_step(const Model &m, const BatchRows &b, int n, int attn_block
     hipLaunchKernelGGL(k_rmsnorm_rows, dim3(n), dim3(norm_threads(n)), 0, m.stream, w.x, w.qkv, pending, (size_t)n * h,
                        m.final_norm, w.xn, w.xn_lo, h, c.rms_eps, PartTail{});
     const int sl = gemm<false>(m, w.xn, w.xn_lo, h, m.lm_head, n, c.vocab, h, nullptr, nullptr, 0);
-    hipLaunchKernelGGL(k_argmax_rows, dim3(n), dim3(1024), 0, m.stream, w.qkv, sl, (size_t)n * c.vocab, c.vocab,
-                       b.logits, b.row_next);
+    launch_argmax_rows(m, n, sl, b.logits, b.row_next);
 }
 
 // Xg[j][:] = X[idx[j]][:] + the K slices of the last down projection for that row
@@ -2048,8 +2081,7 @@ void launch_prefill_varlen(const Model &m, const BatchRows &b, const VarlenSeg *
     hipLaunchKernelGGL(k_rmsnorm_rows, dim3(n_seg), dim3(norm_threads(n_seg)), 0, m.stream, b.o_rows, (const float *)nullptr, 0,
                        (size_t)0, m.final_norm, w.xn, w.xn_lo, h, c.rms_eps, PartTail{});
     const int sl = gemm<false>(m, w.xn, w.xn_lo, h, m.lm_head, n_seg, c.vocab, h, nullptr, nullptr, 0);
-    hipLaunchKernelGGL(k_argmax_rows, dim3(n_seg), dim3(1024), 0, m.stream, w.qkv, sl, (size_t)n_seg * c.vocab,
-                       c.vocab, b.logits, b.row_next);
+    launch_argmax_rows(m, n_seg, sl, b.logits, b.row_next);
 }
 
 }  // namespace st

@@ -17,8 +17,10 @@ def _margin(lg):
     return float((s[-1] - s[-2]) / np.abs(lg).max())
 
 
-def _setup(name, n_seq, seed, max_seq, n_layers=None, gen_device="cpu", max_chunk=64):
+def _setup(name, n_seq, seed, max_seq, n_layers=None, gen_device="cpu", max_chunk=64, vocab=None):
     cfg = synth.model_config(name, max_seq=max_seq, max_chunk=max_chunk, n_layers=n_layers)
+    if vocab is not None:
+        cfg["vocab"] = vocab
     w = synth.make_weights(cfg, seed, device=gen_device)
     oracles = [O.OracleModel(synth.oracle_config(cfg), synth.oracle_views(cfg, w)) for _ in range(n_seq)]
     wg = dict(embed=w["embed"].cuda(), final_norm=w["final_norm"].cuda(),
@@ -70,6 +72,15 @@ def test_tiny_batch_ragged_lengths():
     lg_o = oracles[2].feed([5])
     lg_g, nxt = batch.decode_step([2], [5], want_logits=True)
     assert rel_err(lg_g[0], lg_o) <= LOGIT_TOL and batch.kv_len(2) == 11
+    batch.close()
+
+
+def test_tiny_batch_vocabulary_not_a_multiple_of_four():
+    """1022 logits per row: the batched arg-max and the LM-head partials take their element-by-element paths, and
+    the last arg-max segment is ragged."""
+    print_case("tiny model, vocabulary 1022, 5 sequences, 6 batched steps")
+    cfg, batch, oracles = _setup("tiny_small", 5, 3, max_seq=128, vocab=1022)
+    assert _run(cfg, batch, oracles, [9, 40, 2, 64, 21], 6) <= LOGIT_TOL
     batch.close()
 
 
