@@ -1530,26 +1530,44 @@ static void stream_launch(const Model &m, const StreamShape &sh, const bf16_t *A
 
 // One block per CU at a time, so the time is (rounds of 256 blocks) x (bytes a block loads, weights and activations
 // alike, + a fixed cost per block); the partial sums written and read again are charged per CU as well.
+// Up to kInvariantRows rows (the most a batched decode step holds) the K slices are those of a 16-row launch whatever
+// M is, and only the tile count per block follows M: a row's sums are then formed in the same order in every batch,
+// so its logits do not depend on which or how many other rows share the step.
+constexpr int kInvariantRows = 64;
 static StreamShape stream_shape(const Model &m, int M, int N, int K) {
     const int MT = (M + 31) / 32;
     const int bk = MT <= 4 ? 64 : 32, seg = bk * 2, nk = K / bk;
     const int fixed = 640 / seg;  // stages' worth of time a block spends filling its ring and storing its tile
     const size_t cap = partial_floats(m.c);
-    StreamShape best = {bk, 8, 1, K, 2, 2};
-    double best_cost = -1;
-    for (int nt = 8; nt >= 4; --nt) {
-        const int tiles = (N + 32 * nt - 1) / (32 * nt);
-        for (int s = 1; s <= 32; ++s) {
-            const int steps = (nk + s - 1) / s;
-            if (s > 1 && (steps * bk < 256 || (size_t)s * M * N > cap)) break;
-            const int used = (nk + steps - 1) / steps;  // slices that are not empty
-            const int rounds = (tiles * used + 255) / 256;
-            const double cost = (double)rounds * (steps + fixed) * (nt * 32 + MT * 64) * seg + (double)used * M * N * 8 / 256;
-            if (best_cost < 0 || cost < best_cost) {
-                best_cost = cost;
-                best.nt = nt, best.splits = used, best.kps = steps * bk;
+    // cheapest (tiles per block, K slices) for cost_rows rows in mt activation tiles; cap_rows rows must fit the
+    // partial buffer; only_steps > 0 admits only slices of that many stages
+    auto search = [&](int cost_rows, int mt, int cap_rows, int only_steps) {
+        StreamShape best = {bk, 8, 1, K, 2, 2};
+        double best_cost = -1;
+        for (int nt = 8; nt >= 4; --nt) {
+            const int tiles = (N + 32 * nt - 1) / (32 * nt);
+            for (int s = 1; s <= 32; ++s) {
+                const int steps = (nk + s - 1) / s;
+                if (s > 1 && (steps * bk < 256 || (size_t)s * cap_rows * N > cap)) break;
+                if (only_steps > 0 && steps != only_steps) continue;
+                const int used = (nk + steps - 1) / steps;  // slices that are not empty
+                const int rounds = (tiles * used + 255) / 256;
+                const double cost = (double)rounds * (steps + fixed) * (nt * 32 + mt * 64) * seg +
+                                    (double)used * cost_rows * N * 8 / 256;
+                if (best_cost < 0 || cost < best_cost) {
+                    best_cost = cost;
+                    best.nt = nt, best.splits = used, best.kps = steps * bk;
+                }
             }
         }
+        return best;
+    };
+    StreamShape best;
+    if (M <= kInvariantRows) {
+        const StreamShape canon = search(16, 1, kInvariantRows, 0);
+        best = search(M, MT, kInvariantRows, canon.kps / bk);
+    } else {
+        best = search(M, MT, M, 0);
     }
     const int a_stage = MT * 64 * seg, w_stage = best.nt * 32 * seg;
     best.na = kRingLds - 3 * a_stage >= 3 * w_stage ? 3 : 2;

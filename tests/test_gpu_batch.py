@@ -84,6 +84,33 @@ def test_tiny_batch_vocabulary_not_a_multiple_of_four():
     batch.close()
 
 
+@pytest.mark.parametrize("name,layers,lens", [
+    ("tiny_small", None, [1 + (7 * i) % 60 for i in range(40)]),
+    ("qwen1p5b", 1, [5 + (97 * i) % 700 for i in range(40)])])
+def test_row_bits_do_not_depend_on_the_batch(name, layers, lens):
+    """A sequence's logits of a batched step are the same bits whether it decodes alone, with two others, with 16,
+    32 or 39 others, and wherever its row sits: the K slices of the step's GEMMs do not follow the row count."""
+    n = len(lens)
+    cfg, batch, _ = _setup(name, n, 5, max_seq=800, n_layers=layers, gen_device="cuda" if layers else "cpu")
+    toks = []
+    for s in range(n):
+        prompt = synth.make_prompt(lens[s], cfg["vocab"], 700 + s)
+        for lo in range(0, lens[s], 64):
+            batch.prefill(s, prompt[lo:lo + 64], want_logits=False)
+        toks.append(int(prompt[-1]))
+    full, nxt_full = batch.decode_step(list(range(n)), toks, want_logits=True)
+    full = np.array(full, copy=True)
+    for group in ([3], [5, 3, 1], list(range(17)), list(range(4, 37)), list(range(n))[::-1]):
+        for s in group:
+            batch.truncate(s, lens[s])
+        lg, nxt = batch.decode_step(group, [toks[s] for s in group], want_logits=True)
+        for r, s in enumerate(group):
+            assert np.array_equal(np.asarray(lg[r]).view(np.uint32), full[s].view(np.uint32)), (len(group), s)
+            assert nxt[r] == nxt_full[s]
+    print_case(name, "rows per step compared", [1, 3, 17, 33, n])
+    batch.close()
+
+
 def test_batch_crosses_attention_ranges():
     """One layer at the 1.5B shape: sequences of 30, 700 and 1030 keys decode together (1, 11 and 17 key ranges)."""
     print_case("1.5B shape, 1 layer: 3 sequences of 30 / 700 / 1030 tokens, 3 batched steps")
