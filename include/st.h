@@ -261,7 +261,8 @@ int st_batch_prefill_many(st_batch *b, int32_t n, const int32_t *seqs, const int
                           const int32_t *lens, float *logits, int32_t *next_tokens);
 /* One decode step for the n_rows distinct sequences seqs[r], feeding tokens[r] at each sequence's own position
  * (ragged lengths): logits (fp32[n_rows][vocab], may be NULL) and greedy next_tokens[r] (may be NULL); every listed
- * sequence grows by one. */
+ * sequence grows by one.  A row's logits do not depend on the other rows, their number or the row order (the sums are
+ * formed in one order for every n_rows); they differ in rounding from st_decode_step's, which uses other kernels. */
 int st_batch_decode_step(st_batch *b, int32_t n_rows, const int32_t *seqs, const int32_t *tokens, float *logits,
                          int32_t *next_tokens);
 
