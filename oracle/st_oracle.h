@@ -83,9 +83,11 @@ int32_t orc_argmax(const float *v, int32_t n);
  * q [nq][d]; K, V [t][nkv][d]; out [nq][d].  Query head h uses kv head h/(nq/nkv). */
 void orc_attention(const float *q, const float *K, const float *V, int32_t t,
                    int32_t nq, int32_t nkv, int32_t d, float *out);
-/* Positions p in [lo,hi) where kw[tokens[p]] holds and (window==1, or p>=1 and
- * delim[tokens[p-1]] holds).  Bitmaps: bit (id&31) of word id>>5.  Writes the first
- * min(count,cap) positions ascending; returns the total count, or -1 on a bad id. */
+/* Positions p in [lo,hi) where the token-level takeover rule holds (Section 3 (1)).  window == 1: tokens[p] is in
+ * the keyword set.  window == w + 1 >= 2: the w tokens ending at p are the sentence that follows a delimiter
+ * (tokens[p-w] is in the delimiter set, none of tokens[p-w+1 .. p-1] is) and at least one of them is a keyword; the
+ * look-back may reach before lo but not before position 0.  Bitmaps: bit (id&31) of word id>>5.  Writes the first
+ * min(count,cap) positions ascending; returns the total count, or -1 on a token id outside [0, vocab). */
 int32_t orc_trigger_scan(const int32_t *tokens, int32_t lo, int32_t hi, int32_t vocab,
                          const uint32_t *kw, const uint32_t *delim, int32_t window,
                          int32_t *positions, int32_t cap);

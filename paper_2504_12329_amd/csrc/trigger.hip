@@ -1,6 +1,14 @@
 // Token-level takeover trigger (paper Section 3 (1), keyword sets of Appendix C as id bitmaps; window > 2
-// is the n1-token sentence after a delimiter): an ordered, exact scan of a token range.  One 1024-thread block walks the range in tiles and
-// compacts the firing positions in ascending order with wave ballots.
+// is the n1-token sentence after a delimiter): an ordered, exact scan of a token range.
+//
+// The rule is evaluated as two running maxima instead of a look-back loop per position.  With w = window - 1,
+//   lastD(q) = largest index j <= q whose token is a delimiter (-1: none),
+//   lastK(q) = largest index j <= q whose token is a keyword   (-1: none),
+// position p fires exactly when  p - w >= 0,  lastD(p - 1) == p - w  (a delimiter right before the sentence and none
+// inside it before its last token)  and  lastK(p) > p - w  (a keyword inside it).  Both maxima are prefix scans, so
+// a position costs O(1) whatever the window; the scan starts w tokens before `lo`, which is as far back as any
+// position of the range looks.  One 1024-thread block walks the tokens in tiles, carries the two maxima from tile
+// to tile and compacts the firing positions in ascending order with wave ballots.
 #include "st_device.h"
 #include "st_internal.h"
 
@@ -10,49 +18,52 @@ __device__ __forceinline__ bool in_set(const uint32_t *bm, int id, int vocab) {
     return id >= 0 && id < vocab && ((bm[id >> 5] >> (id & 31)) & 1u);
 }
 
+// inclusive running maximum over the lanes of a wave
+__device__ __forceinline__ int wave_running_max(int v, int lane) {
+#pragma unroll
+    for (int o = 1; o < kWave; o <<= 1) {
+        const int u = __shfl_up(v, o, kWave);
+        if (lane >= o) v = max(v, u);
+    }
+    return v;
+}
+
 __global__ __launch_bounds__(1024) void k_trigger_scan(const int32_t *__restrict__ tokens, int lo, int hi,
                                                        const uint32_t *__restrict__ kw,
                                                        const uint32_t *__restrict__ delim, int window, int vocab,
                                                        int32_t *__restrict__ positions, int cap,
                                                        int32_t *__restrict__ n_found) {
-    __shared__ int wave_total[16];
-    __shared__ int base;
+    __shared__ int wave_d[16], wave_k[16], wave_n[16];
+    __shared__ int carry_d, carry_k, base;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    if (threadIdx.x == 0) base = 0;
+    const int w = window - 1;
+    const int scan_from = w == 0 ? lo : max(0, lo - w);
+    if (threadIdx.x == 0) carry_d = carry_k = -1, base = 0;
     __syncthreads();
-    for (int start = lo; start < hi; start += 1024) {
-        int p = start + (int)threadIdx.x;
-        bool fire = false;
-        if (p < hi) {
-            if (window == 1) {
-                fire = in_set(kw, tokens[p], vocab);
-            } else {
-                // the sentence of window - 1 tokens ending at p: delimiter right before it, none inside it
-                // before its last token, a keyword somewhere in it
-                const int first = p - (window - 1) + 1;
-                if (first >= 1 && in_set(delim, tokens[first - 1], vocab)) {
-                    bool ok = true, any = false;
-                    for (int q = first; q <= p; ++q) {
-                        const int t = tokens[q];
-                        if (q < p && in_set(delim, t, vocab)) ok = false;
-                        any |= in_set(kw, t, vocab);
-                    }
-                    fire = ok && any;
-                }
-            }
-        }
-        unsigned long long mask = __ballot(fire);
-        int before = __popcll(mask & ((1ull << lane) - 1ull));
-        if (lane == 0) wave_total[wave] = __popcll(mask);
+    for (int start = scan_from; start < hi; start += 1024) {
+        const int p = start + (int)threadIdx.x;
+        const int id = p < hi ? tokens[p] : -1;  // -1 belongs to no set
+        const bool is_k = in_set(kw, id, vocab), is_d = w > 0 && in_set(delim, id, vocab);
+        const int run_d = wave_running_max(is_d ? p : -1, lane), run_k = wave_running_max(is_k ? p : -1, lane);
+        int before_d = __shfl_up(run_d, 1, kWave);  // lastD(p - 1) within this wave
+        if (lane == 0) before_d = -1;
+        if (lane == kWave - 1) wave_d[wave] = run_d, wave_k[wave] = run_k;
         __syncthreads();
-        int off = base + before;
-        for (int w = 0; w < wave; ++w) off += wave_total[w];
+        int pre_d = carry_d, pre_k = carry_k;  // maxima over everything before this wave
+        for (int v = 0; v < wave; ++v) pre_d = max(pre_d, wave_d[v]), pre_k = max(pre_k, wave_k[v]);
+        const int last_d = max(pre_d, before_d), last_k = max(pre_k, run_k);
+        const bool fire = p >= lo && p < hi && (w == 0 ? is_k : (p - w >= 0 && last_d == p - w && last_k > p - w));
+        const unsigned long long mask = __ballot(fire);
+        if (lane == 0) wave_n[wave] = __popcll(mask);
+        __syncthreads();
+        int off = base + __popcll(mask & ((1ull << lane) - 1ull));
+        for (int v = 0; v < wave; ++v) off += wave_n[v];
         if (fire && off < cap) positions[off] = p;
         __syncthreads();
         if (threadIdx.x == 0) {
-            int tot = 0;
-            for (int w = 0; w < 16; ++w) tot += wave_total[w];
-            base += tot;
+            int tot = 0, md = carry_d, mk = carry_k;
+            for (int v = 0; v < 16; ++v) tot += wave_n[v], md = max(md, wave_d[v]), mk = max(mk, wave_k[v]);
+            base += tot, carry_d = md, carry_k = mk;
         }
         __syncthreads();
     }

@@ -54,6 +54,46 @@ def test_trigger_scan_bruteforce(oracle_lib, window):
         assert cnt == len(want) and pos.tolist() == want[:2]
 
 
+def _running_maxima(tokens, lo, hi, kwset, delimset, window):
+    """The form the GPU scan evaluates (host arithmetic of k_trigger_scan): with w = window - 1, lastD(q) / lastK(q)
+    the largest index <= q holding a delimiter / keyword, p fires when p - w >= 0, lastD(p - 1) == p - w and
+    lastK(p) > p - w; the running maxima start w tokens before lo."""
+    if window == 1:
+        return [p for p in range(lo, hi) if tokens[p] in kwset]
+    w, out = window - 1, []
+    last_d = last_k = -1
+    for p in range(max(0, lo - w), hi):
+        before_d = last_d
+        if tokens[p] in delimset:
+            last_d = p
+        if tokens[p] in kwset:
+            last_k = p
+        if p >= lo and p - w >= 0 and before_d == p - w and last_k > p - w:
+            out.append(p)
+    return out
+
+
+@pytest.mark.parametrize("window", [2, 3, 4, 9, 40, 257])
+def test_running_maxima_form_of_the_rule(oracle_lib, window):
+    """The prefix-scan form of the sentence rule gives the positions of the brute-force replay and of the oracle."""
+    rng = np.random.default_rng(100 + window)
+    V = 120
+    kw, dl = synth.modulo_bitmap(V, 7), synth.modulo_bitmap(V, 3)
+    kwset, dlset = set(range(0, V, 7)), set(range(0, V, 3))
+    for trial in range(40):
+        n = int(rng.integers(0, 700))
+        toks = rng.integers(0, V, n).astype(np.int32)
+        if n:                                 # delimiters about one sentence apart, so that long windows fire too
+            toks[toks % 3 == 0] += 1
+            k = max(1, n // window)
+            toks[rng.integers(0, n, k)] = 3 * rng.integers(0, V // 3, k)
+        lo = int(rng.integers(0, n + 1))
+        hi = int(rng.integers(lo, n + 1))
+        got = _running_maxima(toks, lo, hi, kwset, dlset, window)
+        assert got == _brute(toks, lo, hi, kwset, dlset, window)
+        assert got == oracle_lib.trigger_scan(toks, lo, hi, V, kw, dl, window, cap=1000)[1].tolist()
+
+
 def test_trigger_scan_hand_cases(oracle_lib):
     V = 64
     kw, dl = synth.modulo_bitmap(V, 5), synth.modulo_bitmap(V, 3)
