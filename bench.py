@@ -30,23 +30,38 @@ MFMA_PEAK = 2.5e15         # dense bf16 flop/s
 
 
 def cpu_baseline(cfg, w_gpu, prompt):
-    """The oracle as it stands, timed on this machine's host cores on a bounded sample of the same workload."""
+    """The oracle as it stands, timed on this machine's host cores on a bounded sample of the same workload: a 64-token
+    prompt pass and 16 greedy decode steps at all cores, then 6 more decode steps on one core."""
+    import ctypes
     from oracle import oracle as O
     from paper_2504_12329_amd import synth
-    ocfg = synth.oracle_config(dict(cfg, max_seq=64))
+    ocfg = synth.oracle_config(dict(cfg, max_seq=128))
     orc = O.OracleModel(ocfg, synth.oracle_views(cfg, w_gpu))
-    n_pre, n_dec = 8, 24
-    lg = orc.feed(prompt[:n_pre])
-    tok = O.argmax(lg)
+    n_pre, n_dec, n_one = 64, 16, 6
+    cores = int(O.lib().orc_threads())
+    t0 = time.perf_counter()
+    tok = O.argmax(orc.feed(prompt[:n_pre]))
+    t_pre = time.perf_counter() - t0
     t0 = time.perf_counter()
     for _ in range(n_dec):
         tok = O.argmax(orc.feed([tok]))
-    dt = time.perf_counter() - t0
-    cores = O.lib().orc_threads()
+    t_dec = time.perf_counter() - t0
+    # one core: the oracle's loops are OpenMP, so the thread count is set through the OpenMP runtime it links
+    omp = ctypes.CDLL("libgomp.so.1")
+    omp.omp_set_num_threads(1)
+    t0 = time.perf_counter()
+    for _ in range(n_one):
+        tok = O.argmax(orc.feed([tok]))
+    t_one = time.perf_counter() - t0
+    omp.omp_set_num_threads(cores)
     orc.close()
-    return {"value": n_dec / dt, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
-            "sample": f"{n_dec} greedy decode steps of the same 1.5B-shaped model after an {n_pre}-token prompt "
-                      f"(kv length {n_pre}..{n_pre + n_dec}), fp32 weights"}
+    return {"value": n_dec / t_dec, "unit": "tokens/s", "cores": cores, "kind": "oracle",
+            "prefill_tok_s": n_pre / t_pre, "one_core": {"value": n_one / t_one, "unit": "tokens/s", "cores": 1},
+            "sample": f"the same 1.5B-shaped model in fp32: {n_pre}-token prompt pass, then {n_dec} greedy decode "
+                      f"steps on {cores} cores (kv length {n_pre}..{n_pre + n_dec}), then {n_one} more on one core.  "
+                      "The GPU figure is quoted at kv 1k..4k; the oracle cannot reach that context inside the sample "
+                      "(it would feed 1k tokens one by one), and at kv 1k its attention would add 0.5 % to the bytes "
+                      "a token reads"}
 
 
 def batched_decode(torch, B, synth, cost, cfg, w, n_seq=16, steps=24):
@@ -136,19 +151,25 @@ def target_model_extras(torch, B, synth, cost, small, sizes=(21, 86, 256, 1024, 
     sec = e0.elapsed_time(e1) / 1e3 / 20
     res = {"decode_kv4096": {"tok_s": 1 / sec, "GB_s": cost.decode_bytes(cfg, 4110) / sec / 1e9,
                              "hbm_frac": cost.decode_bytes(cfg, 4110) / sec / HBM_PEAK}, "prefill_on_kv4096": {}}
-    for m in sizes:
+    def timed_pass(m, fast):
         for _ in range(2):
             large.truncate(4096)
             e0.record()
-            large.prefill_device(toks[4096:4096 + m])
+            large.prefill_device(toks[4096:4096 + m], fast=fast)
             e1.record()
             torch.cuda.synchronize()
         sec = e0.elapsed_time(e1) / 1e3
         fl = cost.prefill_flops(cfg, m, 4096)
-        res["prefill_on_kv4096"][str(m)] = {
-            "ms": sec * 1e3, "tok_s": m / sec, "TFLOP_s": fl / sec / 1e12, "mfma_frac": fl / sec / MFMA_PEAK,
-            "weight_GB_s": cost.weight_bytes(cfg) / sec / 1e9, "hbm_frac": cost.weight_bytes(cfg) / sec / HBM_PEAK,
-            "bound": "hbm" if m < 312 else "mfma"}
+        return {"ms": sec * 1e3, "tok_s": m / sec, "TFLOP_s": fl / sec / 1e12, "mfma_frac": fl / sec / MFMA_PEAK,
+                "weight_GB_s": cost.weight_bytes(cfg) / sec / 1e9, "hbm_frac": cost.weight_bytes(cfg) / sec / HBM_PEAK,
+                "bound": "hbm" if m < 312 else "mfma"}
+
+    for m in sizes:
+        # the pass as every entry point runs it by default (it meets the logit tolerance against the oracle at
+        # every depth tested); above 256 rows also the opt-in pass with single-bf16 GEMM inputs (ST_PREFILL_FAST)
+        res["prefill_on_kv4096"][str(m)] = timed_pass(m, False)
+        if m > 256:
+            res["prefill_on_kv4096"][str(m)]["fast_single_term"] = timed_pass(m, True)
     large.close()
     del large
     if not batched:
@@ -333,7 +354,14 @@ def main():
     gu_us = float(np.mean(gu[8:]))
     bytes_per_launch = 2 * cfg["intermediate"] * cfg["hidden"] * 2
     achieved = bytes_per_launch / (gu_us * 1e-6)
-    roofline = {"bound": "hbm", "kernel": "k_gateup_swiglu", "achieved": achieved / 1e9, "peak": HBM_PEAK / 1e9,
+    # the whole decode step first (all kernels of a token: algorithmic bytes of the token over the step time in the
+    # kv window where it is lowest), then the kernel that moves the most bytes
+    worst = min(windows, key=lambda k: windows[k]["hbm_frac"]) if windows else None
+    whole = None if worst is None else {
+        "bound": "hbm", "scope": f"whole decode step, 128-step window at kv {worst}",
+        "achieved": windows[worst]["GB_s"], "peak": HBM_PEAK / 1e9, "unit": "GB/s", "frac": windows[worst]["hbm_frac"]}
+    roofline = {"whole_step": whole,
+                "bound": "hbm", "kernel": "k_gateup_swiglu", "achieved": achieved / 1e9, "peak": HBM_PEAK / 1e9,
                 "unit": "GB/s", "frac": achieved / HBM_PEAK, "traffic": GATEUP_TRAFFIC_BYTES,
                 "bytes_per_launch": bytes_per_launch, "avg_launch_us": gu_us,
                 "launches_timed": len(gu[8:]) * cfg["n_layers"]}

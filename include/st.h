@@ -47,11 +47,16 @@ enum {
     ST_OUT_DEVICE = 2u,    /* output pointers are device memory; the call does not synchronise */
     ST_TOKEN_CHAINED = 4u, /* st_decode_step: ignore `token`, feed the model's own last greedy token
                               (kept on the device), so steps can be queued without a host round trip */
-    ST_PREFILL_TWO_TERM = 8u /* st_prefill: feed a long run of tokens in passes of at most 256 rows, the length up to
-                              which every GEMM and attention input is carried as two bf16 terms (16 mantissa
-                              bits).  Longer passes round those inputs to one bf16 and run up to twice as fast where
-                              the MFMA rate, not the weight stream, sets the time; over 28 layers that rounding
-                              about doubles the logit error of the pass (measured 2.1e-2 against 1.0e-2) */
+    ST_PREFILL_TWO_TERM = 8u, /* st_prefill: feed a long run of tokens in passes of at most 256 rows (the length up
+                              to which the second bf16 term of the GEMM inputs costs no time) */
+    ST_PREFILL_FAST = 16u    /* st_prefill: in passes of more than 256 rows round every GEMM and attention input to
+                              one bf16.  By default every pass carries those inputs as two bf16 terms (16 mantissa
+                              bits), which leaves the bf16 K/V cache as its only rounding: its logits are then as
+                              close to an fp32 evaluation as the decode step's.  Passes of more than 256 rows are
+                              bound by the MFMA rate and pay twice the MFMA work for that; with this flag they run
+                              about 1.8x faster and their logit error about doubles (measured against the CPU
+                              oracle: 1.7e-2 against 0.8e-2 through 28 layers of the 1.5B shape).  Excludes
+                              ST_PREFILL_TWO_TERM. */
 };
 
 /* Shape of a Qwen-2.5-architecture decoder (pre-norm, RMSNorm, rotate-half RoPE, GQA, SwiGLU). */
@@ -113,7 +118,8 @@ int st_kv_truncate(st_model *m, int32_t new_len);
  * tokens[0,n) at positions [kv_len, kv_len+n), appends their keys and values to the cache,
  * kv_len += n.  logits (fp32[vocab]) and next_tok (the greedy arg-max, lowest index on ties)
  * of the LAST fed position are written when the pointers are non-NULL.
- * Runs of more than max_chunk tokens (256 with ST_PREFILL_TWO_TERM) are fed as consecutive passes.
+ * Runs of more than max_chunk tokens (256 with ST_PREFILL_TWO_TERM) are fed as consecutive passes; see
+ * ST_PREFILL_FAST for the precision of passes of more than 256 rows.
  * ST_ERANGE if n <= 0, kv_len + n > max_seq, or (host tokens only) an id is outside the vocabulary;
  * ids in device memory that are out of range are clamped into the vocabulary by the kernel. */
 int st_prefill(st_model *m, const int32_t *tokens, int32_t n, float *logits, int32_t *next_tok,
@@ -124,6 +130,12 @@ int st_prefill(st_model *m, const int32_t *tokens, int32_t n, float *logits, int
  * and context-length bucket into a HIP graph (on a private stream) and replayed on the model's stream; setting the
  * environment variable ST_NO_GRAPH before st_model_create launches them one by one instead. */
 int st_decode_step(st_model *m, int32_t token, float *logits, int32_t *next_tok, uint32_t flags);
+
+/* How st_decode_step runs its kernels.  *graphs (may be NULL): step graphs captured so far.  *mode (may be NULL):
+ * 0 = captured graphs are replayed; 1 = graphs were switched off with ST_NO_GRAPH; 2 = a capture or instantiation
+ * failed -- the HIP message was left in st_last_error() by the call that hit it -- and every step since has been
+ * launched kernel by kernel (same results, about a tenth slower).  ST_EINVAL if m is NULL. */
+int st_decode_graph_state(const st_model *m, int32_t *graphs, int32_t *mode);
 
 /* n chained greedy decode steps: feeds first_token (or the model's own last greedy token when
  * ST_TOKEN_CHAINED is set), then each step's arg-max, writing the n produced tokens to

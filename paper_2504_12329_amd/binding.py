@@ -14,10 +14,10 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libst.so")
 
 ST_OK, ST_EINVAL, ST_ENOMEM, ST_ERANGE, ST_EHIP = 0, -1, -2, -3, -4
-ST_TOKENS_DEVICE, ST_OUT_DEVICE, ST_TOKEN_CHAINED, ST_PREFILL_TWO_TERM = 1, 2, 4, 8
+ST_TOKENS_DEVICE, ST_OUT_DEVICE, ST_TOKEN_CHAINED, ST_PREFILL_TWO_TERM, ST_PREFILL_FAST = 1, 2, 4, 8, 16
 
 EXPORTS = ("st_query_sizes", "st_prefill_plan_check", "st_model_create", "st_model_destroy", "st_kv_len", "st_kv_truncate", "st_prefill",
-           "st_decode_step", "st_decode_step_timed", "st_decode_greedy", "st_trigger_scan", "st_handoff", "st_generate",
+           "st_decode_step", "st_decode_graph_state", "st_decode_step_timed", "st_decode_greedy", "st_trigger_scan", "st_handoff", "st_generate",
            "st_generate_policy", "st_batch_query_sizes", "st_batch_create", "st_batch_destroy", "st_batch_kv_len",
            "st_batch_truncate", "st_batch_prefill", "st_batch_prefill_many", "st_batch_decode_step", "st_generate_batch",
            "st_last_error")
@@ -84,6 +84,7 @@ def lib():
         L.st_prefill.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_uint32]
         L.st_decode_step.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_uint32]
         L.st_decode_step_timed.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_double)]
+        L.st_decode_graph_state.argtypes = [C.c_void_p, i32p, i32p]
         L.st_decode_greedy.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_uint32]
         L.st_trigger_scan.argtypes = [C.POINTER(st_trigger_rule), C.c_void_p, C.c_int32, C.c_int32, C.c_void_p,
                                       C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32]
@@ -160,6 +161,10 @@ def st_trigger_scan(rule, tokens_dev, lo, hi, cap, stream=None):
     return n.value, pos[:min(n.value, cap)].copy()
 
 
+def _pass_flags(two_term, fast):
+    return (ST_PREFILL_TWO_TERM if two_term else 0) | (ST_PREFILL_FAST if fast else 0)
+
+
 class Model:
     """st_model over torch-owned device buffers.  `weights` is the dict made by synth.make_weights on the GPU."""
 
@@ -208,26 +213,32 @@ class Model:
     def truncate(self, n):
         _check(lib().st_kv_truncate(self._h, n))
 
-    def prefill(self, tokens, want_logits=True, two_term=False):
-        """tokens: host int array; two_term: passes of at most 256 rows (ST_PREFILL_TWO_TERM).
-        Returns (logits ndarray or None, greedy token)."""
+    def prefill(self, tokens, want_logits=True, two_term=False, fast=False):
+        """tokens: host int array; two_term: passes of at most 256 rows (ST_PREFILL_TWO_TERM); fast: single-bf16 GEMM
+        inputs in passes of more than 256 rows (ST_PREFILL_FAST).  Returns (logits ndarray or None, greedy token)."""
         t = np.ascontiguousarray(tokens, dtype=np.int32)
         lg = np.empty(self.cfg["vocab"], dtype=np.float32) if want_logits else None
         nt = C.c_int32()
         _check(lib().st_prefill(self._h, _np_ptr(t), t.size, _np_ptr(lg) if want_logits else None,
-                                C.addressof(nt), ST_PREFILL_TWO_TERM if two_term else 0))
+                                C.addressof(nt), _pass_flags(two_term, fast)))
         return lg, nt.value
 
-    def prefill_device(self, tokens_dev, two_term=False):
+    def prefill_device(self, tokens_dev, two_term=False, fast=False):
         """tokens_dev: int32 CUDA tensor; enqueues only (no outputs, no synchronisation)."""
         _check(lib().st_prefill(self._h, tokens_dev.data_ptr(), tokens_dev.numel(), None, None,
-                                ST_TOKENS_DEVICE | ST_OUT_DEVICE | (ST_PREFILL_TWO_TERM if two_term else 0)))
+                                ST_TOKENS_DEVICE | ST_OUT_DEVICE | _pass_flags(two_term, fast)))
 
     def decode_step(self, token, want_logits=True):
         lg = np.empty(self.cfg["vocab"], dtype=np.float32) if want_logits else None
         nt = C.c_int32()
         _check(lib().st_decode_step(self._h, int(token), _np_ptr(lg) if want_logits else None, C.addressof(nt), 0))
         return lg, nt.value
+
+    def graph_state(self):
+        """(step graphs captured so far, mode): mode 0 = graphs replayed, 1 = off by ST_NO_GRAPH, 2 = capture failed."""
+        n, mode = C.c_int32(), C.c_int32()
+        _check(lib().st_decode_graph_state(self._h, C.byref(n), C.byref(mode)))
+        return n.value, mode.value
 
     def decode_step_timed(self):
         """One chained step with per-launch events; returns (mean gate/up kernel us, whole step us)."""

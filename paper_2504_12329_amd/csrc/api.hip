@@ -5,6 +5,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <thread>
@@ -18,7 +19,7 @@ namespace st {
 
 static thread_local char g_err[512] = "";
 
-static int fail(int code, const char *fmt, ...) {
+int fail(int code, const char *fmt, ...) {
     va_list ap;
     va_start(ap, fmt);
     vsnprintf(g_err, sizeof(g_err), fmt, ap);
@@ -78,11 +79,10 @@ void carve_workspace(const st_config &c, char *base, Workspace *ws) {
     ws->qb = (bf16_t *)take(sizeof(bf16_t) * mc * qd);
     ws->attn = (bf16_t *)take(sizeof(bf16_t) * mc * qd);
     ws->act = (bf16_t *)take(sizeof(bf16_t) * mc * I);
-    const size_t sr = mc < 256 ? mc : 256;  // rows of the two-term activation buffers
-    ws->xn_lo = (bf16_t *)take(sizeof(bf16_t) * sr * h);
-    ws->attn_lo = (bf16_t *)take(sizeof(bf16_t) * sr * qd);
-    ws->act_lo = (bf16_t *)take(sizeof(bf16_t) * sr * I);
-    ws->qb_lo = (bf16_t *)take(sizeof(bf16_t) * sr * qd);
+    ws->xn_lo = (bf16_t *)take(sizeof(bf16_t) * mc * h);
+    ws->attn_lo = (bf16_t *)take(sizeof(bf16_t) * mc * qd);
+    ws->act_lo = (bf16_t *)take(sizeof(bf16_t) * mc * I);
+    ws->qb_lo = (bf16_t *)take(sizeof(bf16_t) * mc * qd);
     ws->q1 = (float *)take(sizeof(float) * qd);
     ws->o1 = (float *)take(sizeof(float) * qd);
     ws->a1 = (float *)take(sizeof(float) * I);
@@ -96,8 +96,9 @@ void carve_workspace(const st_config &c, char *base, Workspace *ws) {
 
 // Enqueues the catch-up pass over `n` tokens (host or device ids); the last row's logits and greedy
 // token (with the trigger predicate when a rule is given) end up in ws.logits / state.
+enum PrefillMode { kPassDefault, kPassTwoTerm, kPassFast };
 static int prefill_impl(Model *m, const int32_t *tokens, int32_t n, bool tokens_dev, const st_trigger_rule *rule,
-                        bool two_term = false) {
+                        PrefillMode mode = kPassDefault) {
     const st_config &c = m->c;
     if (!tokens) return fail(ST_EINVAL, "tokens is NULL");
     if (n <= 0) return fail(ST_ERANGE, "n must be positive (got %d)", n);
@@ -107,8 +108,9 @@ static int prefill_impl(Model *m, const int32_t *tokens, int32_t n, bool tokens_
         for (int32_t i = 0; i < n; ++i)
             if (tokens[i] < 0 || tokens[i] >= c.vocab)
                 return fail(ST_ERANGE, "token id %d at index %d is outside the vocabulary [0,%d)", tokens[i], i, c.vocab);
-    // passes of at most max_chunk rows; 256 rows on request: the longest pass that keeps two-term GEMM inputs
-    const int32_t step = two_term && c.max_chunk > 256 ? 256 : c.max_chunk;
+    // passes of at most max_chunk rows; 256 rows on request: the longest pass that keeps every GEMM input in two terms
+    const int32_t step = mode == kPassTwoTerm && c.max_chunk > 256 ? 256 : c.max_chunk;
+    m->long_terms = mode == kPassFast ? 0 : kDefaultLongTerms;
     for (int32_t done = 0; done < n; done += step) {
         int32_t cn = n - done < step ? n - done : step;
         ST_HIP(hipMemcpyAsync(m->ws.tokens, tokens + done, sizeof(int32_t) * cn,
@@ -137,25 +139,36 @@ static hipGraphExec_t step_graph(Model *m, const st_trigger_rule *rule, int32_t 
             g.attn_blocks == bucket)
             return g.exec;
     if (m->graphs.size() >= 64) return nullptr;  // unusual caller: many distinct rules; launch directly
-    if (!m->capture_stream && hipStreamCreateWithFlags(&m->capture_stream, hipStreamNonBlocking) != hipSuccess) {
+    // A failure here is not fatal -- the step is launched kernel by kernel instead, about a tenth slower -- but it is
+    // not silent either: the HIP message goes to st_last_error() and st_decode_graph_state() reports mode 2.
+    auto give_up = [&](const char *what, hipError_t e) -> hipGraphExec_t {
         m->graphs_off = true;
+        m->graph_failed = true;
+        (void)fail(ST_EHIP, "decode-step graph: %s failed (%s); steps are launched kernel by kernel from now on", what,
+                   hipGetErrorString(e));
         (void)hipGetLastError();
         return nullptr;
+    };
+    if (!m->capture_stream) {
+        hipError_t e = hipStreamCreateWithFlags(&m->capture_stream, hipStreamNonBlocking);
+        if (e != hipSuccess) {
+            m->capture_stream = nullptr;
+            return give_up("hipStreamCreateWithFlags", e);
+        }
     }
     hipGraph_t graph = nullptr;
     hipGraphExec_t exec = nullptr;
-    bool ok = hipStreamBeginCapture(m->capture_stream, hipStreamCaptureModeRelaxed) == hipSuccess;
-    if (ok) {
-        launch_decode_step(*m, rule, out_seq_dev, m->capture_stream, bucket);
-        ok = hipStreamEndCapture(m->capture_stream, &graph) == hipSuccess && graph != nullptr;
+    hipError_t e = hipStreamBeginCapture(m->capture_stream, hipStreamCaptureModeRelaxed);
+    if (e != hipSuccess) return give_up("hipStreamBeginCapture", e);
+    launch_decode_step(*m, rule, out_seq_dev, m->capture_stream, bucket);
+    e = hipStreamEndCapture(m->capture_stream, &graph);
+    if (e != hipSuccess || !graph) {
+        if (graph) (void)hipGraphDestroy(graph);
+        return give_up("hipStreamEndCapture", e);
     }
-    if (ok) ok = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0) == hipSuccess;
-    if (graph) (void)hipGraphDestroy(graph);
-    if (!ok) {
-        m->graphs_off = true;
-        (void)hipGetLastError();
-        return nullptr;
-    }
+    e = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
+    (void)hipGraphDestroy(graph);
+    if (e != hipSuccess) return give_up("hipGraphInstantiate", e);
     m->graphs.push_back(StepGraph{kw, dl, out_seq_dev, window, vocab, bucket, exec});
     return exec;
 }
@@ -274,14 +287,25 @@ int st_prefill_plan_check(const st_config *cfg, int32_t rows, int32_t *launches,
     const struct {
         const char *name;
         int dual, N, K;
-    } g[4] = {{"QKV", 0, qkv, h}, {"O", 0, h, qd}, {"gate/up", 1, I, h}, {"down", 0, h, I}};
+        bool def_two;
+    } g[4] = {{"QKV", 0, qkv, h, (kDefaultLongTerms & kTermQKV) != 0},
+              {"O", 0, h, qd, (kDefaultLongTerms & kTermO) != 0},
+              {"gate/up", 1, I, h, (kDefaultLongTerms & kTermGateUp) != 0},
+              {"down", 0, h, I, (kDefaultLongTerms & kTermDown) != 0}};
     for (const auto &e : g) {
         if (e.K % 64 || e.K < 128) continue;  // the general-shape kernel serves such a K
-        int nl = 0, nb = 0, ni = 0;
-        const int rc = ring_plan_check(e.dual, rows, e.N, e.K, cap, 1, &nl, &nb, &ni);
-        if (rc) return fail(ST_EINVAL, "block plan of the %s projection at %d rows fails check %d", e.name, rows, rc);
-        if (launches) *launches += nl;
-        if (blocks) *blocks += nb;
+        // a projection whose input carries two bf16 terms runs the doubled contraction [A | Alo] x [B | B]: the
+        // plans of both forms are walked
+        for (int terms = 1; terms <= 2; ++terms) {
+            int nl = 0, nb = 0, ni = 0;
+            const int rc = ring_plan_check(e.dual, rows, e.N, terms * e.K, cap, 1, &nl, &nb, &ni);
+            if (rc)
+                return fail(ST_EINVAL, "block plan of the %s projection at %d rows (%d-term input) fails check %d",
+                            e.name, rows, terms, rc);
+            if (terms != (e.def_two ? 2 : 1)) continue;  // the counts reported are the default pass's
+            if (launches) *launches += nl;
+            if (blocks) *blocks += nb;
+        }
     }
     return ST_OK;
 }
@@ -325,6 +349,12 @@ static int build_model(const st_config *cfg, const st_weights *w, void *kv, void
     m->timers = nullptr;
     m->capture_stream = nullptr;
     m->graphs_off = getenv("ST_NO_GRAPH") != nullptr;
+    m->graph_failed = false;
+    m->long_terms = kDefaultLongTerms;
+    static std::once_flag lds_once;
+    static hipError_t lds_rc = hipSuccess;
+    std::call_once(lds_once, [] { lds_rc = raise_lds_limits(); });
+    if (lds_rc != hipSuccess) return fail(ST_EHIP, "raising the kernels' LDS limit: %s", hipGetErrorString(lds_rc));
     launch_init(*m);
     return check_launch("workspace initialisation");
 }
@@ -364,6 +394,14 @@ int st_kv_len(const st_model *h, int32_t *out) {
     return ST_OK;
 }
 
+int st_decode_graph_state(const st_model *h, int32_t *graphs, int32_t *mode) {
+    if (!h) return fail(ST_EINVAL, "model is NULL");
+    const Model *m = reinterpret_cast<const Model *>(h);
+    if (graphs) *graphs = (int32_t)m->graphs.size();
+    if (mode) *mode = m->graph_failed ? 2 : (m->graphs_off ? 1 : 0);
+    return ST_OK;
+}
+
 int st_kv_truncate(st_model *h, int32_t new_len) {
     if (!h) return fail(ST_EINVAL, "model is NULL");
     Model *m = reinterpret_cast<Model *>(h);
@@ -382,9 +420,12 @@ static int check_flags(uint32_t flags, uint32_t allowed) {
 
 int st_prefill(st_model *h, const int32_t *tokens, int32_t n, float *logits, int32_t *next_tok, uint32_t flags) {
     if (!h) return fail(ST_EINVAL, "model is NULL");
-    if (int rc = check_flags(flags, ST_TOKENS_DEVICE | ST_OUT_DEVICE | ST_PREFILL_TWO_TERM)) return rc;
+    if (int rc = check_flags(flags, ST_TOKENS_DEVICE | ST_OUT_DEVICE | ST_PREFILL_TWO_TERM | ST_PREFILL_FAST)) return rc;
+    if ((flags & ST_PREFILL_TWO_TERM) && (flags & ST_PREFILL_FAST))
+        return fail(ST_EINVAL, "ST_PREFILL_TWO_TERM and ST_PREFILL_FAST exclude each other");
     Model *m = reinterpret_cast<Model *>(h);
-    if (int rc = prefill_impl(m, tokens, n, flags & ST_TOKENS_DEVICE, nullptr, flags & ST_PREFILL_TWO_TERM)) return rc;
+    const PrefillMode mode = (flags & ST_PREFILL_TWO_TERM) ? kPassTwoTerm : (flags & ST_PREFILL_FAST) ? kPassFast : kPassDefault;
+    if (int rc = prefill_impl(m, tokens, n, flags & ST_TOKENS_DEVICE, nullptr, mode)) return rc;
     return deliver(m, logits, next_tok, flags & ST_OUT_DEVICE);
 }
 

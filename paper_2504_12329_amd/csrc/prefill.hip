@@ -305,7 +305,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void k_gemm(const bf16_t *__restric
                     float a = gt / (1.0f + expf(-gt)) * up;
                     bf16_t hi = f32_to_bf16(a);
                     outb[(size_t)row * ldo + col] = hi;
-                    if (SPLITA) outlo[(size_t)row * ldo + col] = f32_to_bf16(a - bf16_to_f32(hi));
+                    if (outlo) outlo[(size_t)row * ldo + col] = f32_to_bf16(a - bf16_to_f32(hi));
                 }
             } else {
 #pragma unroll
@@ -425,12 +425,15 @@ __host__ __device__ inline bool ring_block(const RingGrid &gg, int bid, int M, i
 // MFMAs per fragment of activations -- for the tiles left over after whole rounds of full tiles (one more round of
 // half the length instead of a round that leaves half the chip idle).
 template <bool DUAL, bool HALF = false>
-__global__ __launch_bounds__(256) void k_gemm_ring(const bf16_t *__restrict__ A, int lda, const bf16_t *__restrict__ B,
-                                                   int M, int N, int K, float *__restrict__ part,
-                                                   bf16_t *__restrict__ outb, int ldo, RingGrid gg) {
+__global__ __launch_bounds__(256) void k_gemm_ring(const bf16_t *__restrict__ A, const bf16_t *__restrict__ Alo, int lda,
+                                                   const bf16_t *__restrict__ B, int M, int N, int K,
+                                                   float *__restrict__ part, bf16_t *__restrict__ outb,
+                                                   bf16_t *__restrict__ outlo, int ldo, RingGrid gg) {
     extern __shared__ __align__(16) unsigned char ring[];
     RingBlock rb;
-    if (!ring_block(gg, blockIdx.x, M, N, K, &rb)) return;
+    // Two-term activations (Alo != nullptr): the contraction runs over 2K columns, [A | Alo] against [B | B]; K step
+    // ka >= K / 64 takes its activations from Alo and wraps round in the weights.
+    if (!ring_block(gg, blockIdx.x, M, N, Alo ? 2 * K : K, &rb)) return;
     const int x = rb.x, y = rb.y, kbeg = rb.kbeg, kend = rb.kend, ldp = rb.ldp;
     float *pz = DUAL ? nullptr : part + rb.part_off;  // where this block's fp32 tile goes (plain form)
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -451,7 +454,7 @@ __global__ __launch_bounds__(256) void k_gemm_ring(const bf16_t *__restrict__ A,
     for (int i = 0; i < 8; ++i) {
         const int row = (wave * 8 + i) * 8 + (lane >> 3);
         const int c = (lane & 7) ^ ring_swz(row);
-        pa[i] = (uint32_t)(((size_t)min(m0 + row, M - 1) * lda + kbeg + c * 8) * sizeof(bf16_t));
+        pa[i] = (uint32_t)(((size_t)min(m0 + row, M - 1) * lda + c * 8) * sizeof(bf16_t));
     }
 #pragma unroll
     for (int i = 0; i < NLB; ++i) {
@@ -464,16 +467,25 @@ __global__ __launch_bounds__(256) void k_gemm_ring(const bf16_t *__restrict__ A,
             bn = min(n0 + (row & 127), N - 1) + (row >> 7) * N;
         else
             bn = min(n0 + row, N - 1);
-        pb[i] = (uint32_t)(((size_t)bn * K + kbeg + c * 8) * sizeof(bf16_t));
+        pb[i] = (uint32_t)(((size_t)bn * K + c * 8) * sizeof(bf16_t));
     }
-    auto loadA = [&](auto i_c, int slot, int kt) {
-        constexpr int i = decltype(i_c)::value;
-        load_to_lds16(A, pa[i] + kt * (kRingBK * 2), ring0 + slot * kRingSlot + (wave * 8 + i) * 1024);
+    // the K position of a step is a wave-uniform base (scalar registers), the lane offsets above never change
+    const int nkw = K / kRingBK, k0 = kbeg / kRingBK;  // K steps of the weights; first step of this block
+    auto baseA = [&](int kt) {
+        const int ka = k0 + kt;
+        return ka < nkw ? A + (size_t)ka * kRingBK : Alo + (size_t)(ka - nkw) * kRingBK;
     };
-    auto loadB = [&](auto i_c, int slot, int kt) {
+    auto baseB = [&](int kt) {
+        const int ka = k0 + kt;
+        return B + (size_t)(ka < nkw ? ka : ka - nkw) * kRingBK;
+    };
+    auto loadA = [&](auto i_c, int slot, const bf16_t *base) {
         constexpr int i = decltype(i_c)::value;
-        if constexpr (i < NLB)
-            load_to_lds16(B, pb[i] + kt * (kRingBK * 2), ring0 + slot * kRingSlot + (wave * NLB + i) * 1024);
+        load_to_lds16(base, pa[i], ring0 + slot * kRingSlot + (wave * 8 + i) * 1024);
+    };
+    auto loadB = [&](auto i_c, int slot, const bf16_t *base) {
+        constexpr int i = decltype(i_c)::value;
+        if constexpr (i < NLB) load_to_lds16(base, pb[i], ring0 + slot * kRingSlot + (wave * NLB + i) * 1024);
     };
 
     f32x16 acc[4][NB];
@@ -520,7 +532,7 @@ __global__ __launch_bounds__(256) void k_gemm_ring(const bf16_t *__restrict__ A,
     // instruction D0+g, 0: none), two fragment reads for the following step, four MFMAs }; the scheduling
     // fences keep that interleave.
     auto step = [&](auto cur_c, auto fetch_c, int slotA, int slotB, int ks_next, auto kind_c, auto d0_c, int dslot,
-                    int dkt) {
+                    const bf16_t *dbase) {
         constexpr int cur = decltype(cur_c)::value, kind = decltype(kind_c)::value, d0 = decltype(d0_c)::value;
         constexpr bool FETCH = decltype(fetch_c)::value != 0;
         // the two reads and the load sit between the group's MFMAs, each issued while the MFMA before it runs
@@ -535,8 +547,8 @@ __global__ __launch_bounds__(256) void k_gemm_ring(const bf16_t *__restrict__ A,
     __builtin_amdgcn_sched_barrier(0);                                        \
     mma_one(ic<cur>{}, ic<g>{}, ic<2>{});                                     \
     __builtin_amdgcn_sched_barrier(0);                                        \
-    if (kind == 1) loadB(ic<d0 + g>{}, dslot, dkt);                           \
-    if (kind == 2) loadA(ic<d0 + g>{}, dslot, dkt);                           \
+    if (kind == 1) loadB(ic<d0 + g>{}, dslot, dbase);                         \
+    if (kind == 2) loadA(ic<d0 + g>{}, dslot, dbase);                         \
     __builtin_amdgcn_sched_barrier(0);                                        \
     mma_one(ic<cur>{}, ic<g>{}, ic<3>{});                                     \
     __builtin_amdgcn_sched_barrier(0);
@@ -545,13 +557,16 @@ __global__ __launch_bounds__(256) void k_gemm_ring(const bf16_t *__restrict__ A,
     };
 
     // prologue: A0 B0 A1 whole and the first half of B1 (nk >= 2)
-    loadA(ic<0>{}, 0, 0), loadA(ic<1>{}, 0, 0), loadA(ic<2>{}, 0, 0), loadA(ic<3>{}, 0, 0);
-    loadA(ic<4>{}, 0, 0), loadA(ic<5>{}, 0, 0), loadA(ic<6>{}, 0, 0), loadA(ic<7>{}, 0, 0);
-    loadB(ic<0>{}, 1, 0), loadB(ic<1>{}, 1, 0), loadB(ic<2>{}, 1, 0), loadB(ic<3>{}, 1, 0);
-    loadB(ic<4>{}, 1, 0), loadB(ic<5>{}, 1, 0), loadB(ic<6>{}, 1, 0), loadB(ic<7>{}, 1, 0);
-    loadA(ic<0>{}, 2, 1), loadA(ic<1>{}, 2, 1), loadA(ic<2>{}, 2, 1), loadA(ic<3>{}, 2, 1);
-    loadA(ic<4>{}, 2, 1), loadA(ic<5>{}, 2, 1), loadA(ic<6>{}, 2, 1), loadA(ic<7>{}, 2, 1);
-    loadB(ic<0>{}, 3, 1), loadB(ic<1>{}, 3, 1), loadB(ic<2>{}, 3, 1), loadB(ic<3>{}, 3, 1);
+    {
+        const bf16_t *a0 = baseA(0), *b0 = baseB(0), *a1 = baseA(1), *b1 = baseB(1);
+        loadA(ic<0>{}, 0, a0), loadA(ic<1>{}, 0, a0), loadA(ic<2>{}, 0, a0), loadA(ic<3>{}, 0, a0);
+        loadA(ic<4>{}, 0, a0), loadA(ic<5>{}, 0, a0), loadA(ic<6>{}, 0, a0), loadA(ic<7>{}, 0, a0);
+        loadB(ic<0>{}, 1, b0), loadB(ic<1>{}, 1, b0), loadB(ic<2>{}, 1, b0), loadB(ic<3>{}, 1, b0);
+        loadB(ic<4>{}, 1, b0), loadB(ic<5>{}, 1, b0), loadB(ic<6>{}, 1, b0), loadB(ic<7>{}, 1, b0);
+        loadA(ic<0>{}, 2, a1), loadA(ic<1>{}, 2, a1), loadA(ic<2>{}, 2, a1), loadA(ic<3>{}, 2, a1);
+        loadA(ic<4>{}, 2, a1), loadA(ic<5>{}, 2, a1), loadA(ic<6>{}, 2, a1), loadA(ic<7>{}, 2, a1);
+        loadB(ic<0>{}, 3, b1), loadB(ic<1>{}, 3, b1), loadB(ic<2>{}, 3, b1), loadB(ic<3>{}, 3, b1);
+    }
     wait_loads<12>();  // A0 and B0 are in
     __builtin_amdgcn_s_barrier();
     fetch(ic<0>{}, ic<0>{}, 0, 1, 0), fetch(ic<0>{}, ic<1>{}, 0, 1, 0), fetch(ic<0>{}, ic<2>{}, 0, 1, 0);
@@ -559,15 +574,17 @@ __global__ __launch_bounds__(256) void k_gemm_ring(const bf16_t *__restrict__ A,
     fetch(ic<0>{}, ic<6>{}, 0, 1, 0), fetch(ic<0>{}, ic<7>{}, 0, 1, 0);
     __builtin_amdgcn_sched_barrier(0);
 
+    const bf16_t *bn1 = baseB(1), *an2 = baseA(2), *bn2 = baseB(2);  // bases of B(kt+1), A(kt+2), B(kt+2)
+    int wrap_in = nkw - (k0 + 2);  // K steps until A(kt+2) crosses into the low term (<= 0: never in this block)
     int sA = 0;  // ring slot of this K step's activations; its weights sit in the next slot, and so on round
     auto fwd = [](int s, int d) { return s + d >= kRingSlots ? s + d - kRingSlots : s + d; };
     // AHEAD: 2 = K steps kt+1 and kt+2 exist, 1 = only kt+1, 0 = this is the last
-    auto kstep = [&](int kt, auto ahead_c) {
+    auto kstep = [&](int, auto ahead_c) {
         constexpr int AHEAD = decltype(ahead_c)::value;
         const int sB = fwd(sA, 1), sA1 = fwd(sA, 2), sB1 = fwd(sA, 3), sA2 = fwd(sA, 4);
-        step(ic<0>{}, ic<1>{}, sA, sB, 1, ic<(AHEAD >= 1 ? 1 : 0)>{}, ic<4>{}, sB1, kt + 1);  // rest of B(kt+1)
-        step(ic<1>{}, ic<1>{}, sA, sB, 2, ic<(AHEAD >= 2 ? 2 : 0)>{}, ic<0>{}, sA2, kt + 2);  // A(kt+2), first half
-        step(ic<0>{}, ic<1>{}, sA, sB, 3, ic<(AHEAD >= 2 ? 2 : 0)>{}, ic<4>{}, sA2, kt + 2);  // A(kt+2), second half
+        step(ic<0>{}, ic<1>{}, sA, sB, 1, ic<(AHEAD >= 1 ? 1 : 0)>{}, ic<4>{}, sB1, bn1);  // rest of B(kt+1)
+        step(ic<1>{}, ic<1>{}, sA, sB, 2, ic<(AHEAD >= 2 ? 2 : 0)>{}, ic<0>{}, sA2, an2);  // A(kt+2), first half
+        step(ic<0>{}, ic<1>{}, sA, sB, 3, ic<(AHEAD >= 2 ? 2 : 0)>{}, ic<4>{}, sA2, an2);  // A(kt+2), second half
         if (AHEAD >= 1) {
             // all fragments of this K step are in registers and K step kt+1 has landed (only A(kt+2) may
             // still be in flight); after the barrier that holds for every wave, so both slots are free
@@ -575,11 +592,15 @@ __global__ __launch_bounds__(256) void k_gemm_ring(const bf16_t *__restrict__ A,
             if (AHEAD >= 2) wait_loads<8>(); else wait_loads<0>();
             __builtin_amdgcn_s_barrier();
             __builtin_amdgcn_sched_barrier(0);
-            step(ic<1>{}, ic<1>{}, sA1, sB1, 0, ic<(AHEAD >= 2 ? 1 : 0)>{}, ic<0>{}, sA, kt + 2);  // B(kt+2), first half
+            step(ic<1>{}, ic<1>{}, sA1, sB1, 0, ic<(AHEAD >= 2 ? 1 : 0)>{}, ic<0>{}, sA, bn2);  // B(kt+2), first half
         } else {
-            step(ic<1>{}, ic<0>{}, sA1, sB1, 0, ic<0>{}, ic<0>{}, sA, kt + 2);
+            step(ic<1>{}, ic<0>{}, sA1, sB1, 0, ic<0>{}, ic<0>{}, sA, bn2);
         }
         sA = sA1;
+        // bases of the next step's loads: B(kt+2) becomes B(kt+1), the other two move on by one K step and cross
+        // from the high to the low term (and back to the weights' first column) at most once in a block's range
+        bn1 = bn2, an2 += kRingBK, bn2 += kRingBK;
+        if (--wrap_in == 0) an2 = Alo, bn2 = B;
     };
     int kt = 0;
     for (; kt + 2 < nk; ++kt) kstep(kt, ic<2>{});
@@ -605,13 +626,21 @@ __global__ __launch_bounds__(256) void k_gemm_ring(const bf16_t *__restrict__ A,
                         a[e] = gt * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * gt)) * up;
                     }
                     const float other = dpp_move<0xB1, 0xf>(0.f, odd ? a[0] : a[1]);  // quad_perm [1,0,3,2]
-                    const uint32_t pk = odd ? pack_bf16x2(other, a[1]) : pack_bf16x2(a[0], other);
+                    const float x0 = odd ? other : a[0], x1 = odd ? a[1] : other;
+                    const uint32_t pk = pack_bf16x2(x0, x1);
                     const int row = m0 + wm * 128 + i * 32 + 8 * (r >> 2) + 4 * kg + (r & 3) + (odd ? 1 : 0);
                     const int col = n0 + wn * (NB * 16) + j * 32 + (l32 & ~1);
                     if (row < M && col + 1 < N)
                         *reinterpret_cast<uint32_t *>(outb + (size_t)row * ldo + col) = pk;
                     else if (row < M && col < N)  // an odd width: the last column alone
                         outb[(size_t)row * ldo + col] = (bf16_t)(pk & 0xffffu);
+                    if (outlo) {  // second bf16 term of the activation (feeds a two-term down projection)
+                        const uint32_t lo = pack_bf16x2(x0 - bf16_lo(pk), x1 - bf16_hi(pk));
+                        if (row < M && col + 1 < N)
+                            *reinterpret_cast<uint32_t *>(outlo + (size_t)row * ldo + col) = lo;
+                        else if (row < M && col < N)
+                            outlo[(size_t)row * ldo + col] = (bf16_t)(lo & 0xffffu);
+                    }
                 }
     } else {
 #pragma unroll
@@ -1492,16 +1521,32 @@ static void gemm_launch(const Model &m, dim3 grid, const bf16_t *A, const bf16_t
 }
 
 template <bool DUAL, bool HALF = false>
-static void ring_launch(const Model &m, dim3 grid, const bf16_t *A, int lda, const bf16_t *B, int M, int N, int K,
-                        bf16_t *outb, int ldo, const RingGrid &gg) {
-    auto kern = k_gemm_ring<DUAL, HALF>;
-    static bool raised = false;  // more than 64 KB of dynamic LDS has to be allowed once per kernel
-    if (!raised) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                  kRingLds);
-        raised = true;
-    }
-    hipLaunchKernelGGL(kern, grid, dim3(256), kRingLds, m.stream, A, lda, B, M, N, K, m.ws.qkv, outb, ldo, gg);
+static void ring_launch(const Model &m, dim3 grid, const bf16_t *A, const bf16_t *Alo, int lda, const bf16_t *B, int M,
+                        int N, int K, bf16_t *outb, bf16_t *outlo, int ldo, const RingGrid &gg) {
+    hipLaunchKernelGGL((k_gemm_ring<DUAL, HALF>), grid, dim3(256), kRingLds, m.stream, A, Alo, lda, B, M, N, K,
+                       m.ws.qkv, outb, outlo, ldo, gg);
+}
+
+// The ring and streaming kernels use more dynamic LDS than a kernel gets by default; the limit is raised once per
+// process for every instantiation (called under std::call_once when the first model is created, so the launchers,
+// which may run on several host threads, never touch it).
+template <class K>
+static hipError_t raise_one(K kern) {
+    return hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                               kRingLds);
+}
+hipError_t raise_lds_limits() {
+    hipError_t e = hipSuccess;
+    auto take = [&](hipError_t r) {
+        if (e == hipSuccess) e = r;
+    };
+    take(raise_one(k_gemm_ring<false, false>)), take(raise_one(k_gemm_ring<true, false>));
+    take(raise_one(k_gemm_ring<true, true>));
+    take(raise_one(k_gemm_stream<1, 64, true>)), take(raise_one(k_gemm_stream<2, 64, true>));
+    take(raise_one(k_gemm_stream<3, 64, true>)), take(raise_one(k_gemm_stream<4, 64, false>));
+    take(raise_one(k_gemm_stream<5, 32, false>)), take(raise_one(k_gemm_stream<6, 32, false>));
+    take(raise_one(k_gemm_stream<7, 32, false>)), take(raise_one(k_gemm_stream<8, 32, false>));
+    return e;
 }
 
 // Shape of a streaming GEMM launch: K columns per stage, weight tiles per block (4..8), K slices, ring depths.
@@ -1515,12 +1560,6 @@ static void stream_launch(const Model &m, const StreamShape &sh, const bf16_t *A
     constexpr bool SPEC = MT <= 3;  // eight waves fit the register file up to three activation tiles (measured: a
                                     // few percent faster there, slower with four)
     auto kern = k_gemm_stream<MT, BK, SPEC>;
-    static bool raised = false;  // more than 64 KB of dynamic LDS has to be allowed once per kernel
-    if (!raised) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                  kRingLds);
-        raised = true;
-    }
     using G = StreamGeom<BK>;
     const int lds = sh.na * MT * G::kATile + sh.nw * sh.nt * G::kWTile;
     dim3 grid((N + 32 * sh.nt - 1) / (32 * sh.nt), sh.splits);
@@ -1659,13 +1698,15 @@ static RingPlan ring_plan(bool dual, int M, int N, int K, size_t cap, bool allow
     return p;
 }
 
+// Alo != nullptr: two-term activations, the plan covers the doubled contraction [A | Alo] x [B | B].
 template <bool DUAL>
-static int ring_gemm(const Model &m, const bf16_t *A, int lda, const bf16_t *B, int M, int N, int K, bf16_t *outb,
-                     int ldo, PartTail *tail) {
-    const RingPlan p = ring_plan(DUAL, M, N, K, partial_floats(m.c), tail != nullptr);
-    ring_launch<DUAL, false>(m, dim3(p.grid_x[0]), A, lda, B, M, N, K, outb, ldo, p.g[0]);
+static int ring_gemm(const Model &m, const bf16_t *A, const bf16_t *Alo, int lda, const bf16_t *B, int M, int N, int K,
+                     bf16_t *outb, bf16_t *outlo, int ldo, PartTail *tail) {
+    const RingPlan p = ring_plan(DUAL, M, N, Alo ? 2 * K : K, partial_floats(m.c), tail != nullptr);
+    ring_launch<DUAL, false>(m, dim3(p.grid_x[0]), A, Alo, lda, B, M, N, K, outb, outlo, ldo, p.g[0]);
     if constexpr (DUAL)
-        if (p.n == 2) ring_launch<true, true>(m, dim3(p.grid_x[1]), A, lda, B, M, N, K, outb, ldo, p.g[1]);
+        if (p.n == 2)
+            ring_launch<true, true>(m, dim3(p.grid_x[1]), A, Alo, lda, B, M, N, K, outb, outlo, ldo, p.g[1]);
     if (tail) *tail = p.tail;
     return p.slices;
 }
@@ -1731,7 +1772,7 @@ static int gemm(const Model &m, const bf16_t *A, const bf16_t *Alo, int lda, con
     // (the ring kernel addresses its operands with 32-bit byte offsets)
     const bool fits32 = (size_t)M * lda * sizeof(bf16_t) < ((size_t)1 << 32) &&
                         (size_t)(DUAL ? 2 : 1) * N * K * sizeof(bf16_t) < ((size_t)1 << 32);
-    const bool big = !Alo && M >= kBigRows && K % kRingBK == 0 && K >= 2 * kRingBK && fits32;
+    const bool big = M >= kBigRows && K % kRingBK == 0 && K >= 2 * kRingBK && fits32;
     if (!DUAL && Alo && M <= kSplitRows && K % kRingBK == 0) {
         const StreamShape sh = stream_shape(m, M, N, K);
         switch ((M + 31) / 32) {
@@ -1746,7 +1787,7 @@ static int gemm(const Model &m, const bf16_t *A, const bf16_t *Alo, int lda, con
         }
         return sh.splits;
     }
-    if (big) return ring_gemm<DUAL>(m, A, lda, B, M, N, K, outb, ldo, tail);
+    if (big) return ring_gemm<DUAL>(m, A, Alo, lda, B, M, N, K, outb, outlo, ldo, tail);
     // (K not a multiple of 64) two-term chunks of at most 32 / 64 rows use 32- / 64-row tiles with two waves: less
     // LDS per block, so more blocks per CU keep more of the weight stream in flight
     const int BM = (Alo && M <= 32) ? 32 : (Alo && M <= 64) ? 64 : 128;
@@ -1785,6 +1826,28 @@ static int gemm(const Model &m, const bf16_t *A, const bf16_t *Alo, int lda, con
     else
         gemm_launch<128, 128, 2, 2, DUAL, false>(m, grid, A, Alo, lda, B, M, N, K, kps, outb, outlo, ldo, gg);
     return DUAL ? 0 : splits;
+}
+
+// Which GEMM and attention inputs of a pass over n rows carry a second bf16 term (x = hi + lo, 16 mantissa bits).
+// By default all of them, at every pass length: the pass then rounds nothing the decode step does not round either
+// (only the bf16 K/V cache is left), and measured against the CPU oracle its logit error is the decode step's at
+// every depth tried.  Up to kSplitRows rows the second term is free (the weight stream sets the time); longer
+// passes are MFMA-bound and pay twice the MFMA work.  m.long_terms == 0 (ST_PREFILL_FAST) drops the second terms
+// of those longer passes: single bf16 inputs, about 1.8x faster, about twice the logit error.
+struct PassTerms {
+    bf16_t *xn_lo, *attn_lo, *act_lo, *qb_lo;  // where the producers write the low terms (nullptr: not needed)
+    bool qkv_two, gu_two;                      // xn_lo feeds the QKV / the gate-up projection
+};
+static PassTerms pass_terms(const Model &m, int n) {
+    const Workspace &w = m.ws;
+    const int terms = n <= kSplitRows ? kTermAll : m.long_terms;
+    PassTerms t;
+    t.qkv_two = terms & kTermQKV, t.gu_two = terms & kTermGateUp;
+    t.xn_lo = (t.qkv_two || t.gu_two) ? w.xn_lo : nullptr;
+    t.attn_lo = terms & kTermO ? w.attn_lo : nullptr;
+    t.act_lo = terms & kTermDown ? w.act_lo : nullptr;
+    t.qb_lo = (terms & kTermQuery) && m.c.head_dim == 128 ? w.qb_lo : nullptr;  // rotated queries (k_flash_long)
+    return t;
 }
 
 // Causal attention of n query rows at positions pos0 .. pos0+n-1 over one sequence's cache (kc / vc of one layer).
@@ -1849,9 +1912,8 @@ void launch_prefill_layers(const Model &m, int32_t pos0, int32_t n) {
     const int h = c.hidden, d = c.head_dim, nq = c.n_q_heads, nkv = c.n_kv_heads, I = c.intermediate;
     const int qd = nq * d, qkv = m.qkv_dim;
     const Workspace &w = m.ws;
-    const bool two = n <= kSplitRows;  // short chunk: GEMM inputs carried as two bf16 terms
-    bf16_t *xn_lo = two ? w.xn_lo : nullptr, *attn_lo = two ? w.attn_lo : nullptr, *act_lo = two ? w.act_lo : nullptr;
-    bf16_t *qb_lo = two && d == 128 ? w.qb_lo : nullptr;  // second term of the rotated queries (k_flash_long)
+    const PassTerms t = pass_terms(m, n);
+    bf16_t *xn_lo = t.xn_lo, *attn_lo = t.attn_lo, *act_lo = t.act_lo, *qb_lo = t.qb_lo;
     hipLaunchKernelGGL(k_embed_rows, dim3(n), dim3(256), 0, m.stream, m.embed, w.tokens, w.x, h, c.vocab);
     hipLaunchKernelGGL(k_note_fed, dim3(1), dim3(1), 0, m.stream, w.state, w.tokens, n - 1, c.vocab);
     int pending = 0;  // K slices of the previous layer's down projection still to be added to x
@@ -1860,7 +1922,7 @@ void launch_prefill_layers(const Model &m, int32_t pos0, int32_t n) {
         size_t lofs = (size_t)l * nkv * c.max_seq * d;
         hipLaunchKernelGGL(k_rmsnorm_rows, dim3(n), dim3(norm_threads(n)), 0, m.stream, w.x, w.qkv, pending, (size_t)n * h,
                            m.norm_attn[l], w.xn, xn_lo, h, c.rms_eps, pend_tail);
-        int sq = gemm<false>(m, w.xn, xn_lo, h, m.wqkv[l], n, qkv, h, nullptr, nullptr, 0, &tq);
+        int sq = gemm<false>(m, w.xn, t.qkv_two ? xn_lo : nullptr, h, m.wqkv[l], n, qkv, h, nullptr, nullptr, 0, &tq);
         hipLaunchKernelGGL(k_rope_append, dim3(n, ((nq + 2 * nkv) * (d / 8) + 255) / 256), dim3(256), 0, m.stream,
                            w.qkv, sq,
                            (size_t)n * qkv, m.bqkv[l], w.rope, w.qb, qb_lo, m.kcache + lofs, m.vcache + lofs, pos0, nq, nkv,
@@ -1873,9 +1935,9 @@ void launch_prefill_layers(const Model &m, int32_t pos0, int32_t n) {
                                                                    // all 2I rows, SwiGLU in the consumer
             int sg = gemm<false>(m, w.xn, xn_lo, h, m.wgu[l], n, 2 * I, h, nullptr, nullptr, 0);
             hipLaunchKernelGGL(k_swiglu_rows, dim3((I / 4 + 255) / 256, n), dim3(256), 0, m.stream, w.qkv, sg,
-                               (size_t)n * 2 * I, I, w.act, act_lo);
+                               (size_t)n * 2 * I, I, w.act, w.act_lo);
         } else {
-            gemm<true>(m, w.xn, xn_lo, h, m.wgu[l], n, I, h, w.act, act_lo, I);
+            gemm<true>(m, w.xn, t.gu_two ? xn_lo : nullptr, h, m.wgu[l], n, I, h, w.act, act_lo, I);
         }
         pending = gemm<false>(m, w.act, act_lo, I, m.wdown[l], n, h, I, nullptr, nullptr, 0, &pend_tail);
     }
@@ -2062,16 +2124,15 @@ void launch_prefill_varlen(const Model &m, const BatchRows &b, const VarlenSeg *
     const int h = c.hidden, d = c.head_dim, nq = c.n_q_heads, nkv = c.n_kv_heads, I = c.intermediate;
     const int qd = nq * d, qkv = m.qkv_dim;
     const Workspace &w = m.ws;
-    const bool two = R <= kSplitRows;
-    bf16_t *xn_lo = two ? w.xn_lo : nullptr, *attn_lo = two ? w.attn_lo : nullptr, *act_lo = two ? w.act_lo : nullptr;
-    bf16_t *qb_lo = two && d == 128 ? w.qb_lo : nullptr;  // second term of the rotated queries (k_flash_long)
+    const PassTerms t = pass_terms(m, R);
+    bf16_t *xn_lo = t.xn_lo, *attn_lo = t.attn_lo, *act_lo = t.act_lo, *qb_lo = t.qb_lo;
     hipLaunchKernelGGL(k_embed_rows, dim3(R), dim3(256), 0, m.stream, m.embed, b.row_tok, w.x, h, c.vocab);
     int pending = 0;
     for (int l = 0; l < c.n_layers; ++l) {
         const size_t lofs = (size_t)l * nkv * c.max_seq * d;
         hipLaunchKernelGGL(k_rmsnorm_rows, dim3(R), dim3(norm_threads(R)), 0, m.stream, w.x, w.qkv, pending, (size_t)R * h,
                            m.norm_attn[l], w.xn, xn_lo, h, c.rms_eps, PartTail{});
-        const int sq = gemm<false>(m, w.xn, xn_lo, h, m.wqkv[l], R, qkv, h, nullptr, nullptr, 0);
+        const int sq = gemm<false>(m, w.xn, t.qkv_two ? xn_lo : nullptr, h, m.wqkv[l], R, qkv, h, nullptr, nullptr, 0);
         hipLaunchKernelGGL(k_rope_append_rows, dim3(R, nq + 2 * nkv), dim3(d / 2), 0, m.stream, w.qkv, sq,
                            (size_t)R * qkv, m.bqkv[l], w.rope, (float *)nullptr, w.qb, qb_lo, m.kcache + lofs,
                            m.vcache + lofs, b.row_pos, b.row_seq, b.seq_stride, nq, nkv, d, c.max_seq);
@@ -2087,9 +2148,9 @@ void launch_prefill_varlen(const Model &m, const BatchRows &b, const VarlenSeg *
         if (R <= (h % kRingBK == 0 ? kSplitRows : kSmallRows)) {
             const int sg = gemm<false>(m, w.xn, xn_lo, h, m.wgu[l], R, 2 * I, h, nullptr, nullptr, 0);
             hipLaunchKernelGGL(k_swiglu_rows, dim3((I / 4 + 255) / 256, R), dim3(256), 0, m.stream, w.qkv, sg,
-                               (size_t)R * 2 * I, I, w.act, act_lo);
+                               (size_t)R * 2 * I, I, w.act, w.act_lo);
         } else {
-            gemm<true>(m, w.xn, xn_lo, h, m.wgu[l], R, I, h, w.act, act_lo, I);
+            gemm<true>(m, w.xn, t.gu_two ? xn_lo : nullptr, h, m.wgu[l], R, I, h, w.act, act_lo, I);
         }
         pending = gemm<false>(m, w.act, act_lo, I, m.wdown[l], R, h, I, nullptr, nullptr, 0);
     }

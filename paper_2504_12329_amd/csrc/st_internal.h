@@ -26,8 +26,8 @@ struct Workspace {
     bf16_t *qb;            // [max_chunk][n_q*d] rotated queries
     bf16_t *attn;          // [max_chunk][n_q*d] attention output (GEMM input)
     bf16_t *act;           // [max_chunk][intermediate] SwiGLU output
-    bf16_t *xn_lo, *attn_lo, *act_lo;  // [256][...] second bf16 terms of the three above (short chunks)
-    bf16_t *qb_lo;         // [256][n_q*d] second bf16 term of the rotated queries (short chunks)
+    bf16_t *xn_lo, *attn_lo, *act_lo;  // [max_chunk][...] second bf16 terms of the three above
+    bf16_t *qb_lo;         // [max_chunk][n_q*d] second bf16 term of the rotated queries
     float *q1;             // [n_q*d] decode query
     float *o1;             // [n_q*d] decode attention output
     float *a1;             // [intermediate] decode SwiGLU output
@@ -50,6 +50,11 @@ struct AttnRows {
     size_t ml_stride, acc_stride;
     bf16_t *out_hi, *out_lo;
 };
+
+// Inputs that may carry a second bf16 term in a pass of more than 256 rows (Model::long_terms): the activations of
+// the four projections and the rotated queries of the attention
+enum LongTerms { kTermQKV = 1, kTermO = 2, kTermGateUp = 4, kTermDown = 8, kTermQuery = 16, kTermAll = 31 };
+constexpr int kDefaultLongTerms = kTermAll;
 
 constexpr int kLmBlocks = 1024;   // blocks (and arg-max partials) of the LM-head kernel
 constexpr int kAttnSplits = 128;  // most key ranges one kv head is split into at decode
@@ -80,7 +85,12 @@ struct Model {
     hipStream_t capture_stream;      // private stream the step graphs are captured on (lazily created)
     std::vector<StepGraph> graphs;
     bool graphs_off;                 // capture failed or was disabled: steps are launched kernel by kernel
+    bool graph_failed;               // graphs_off because a capture or instantiation failed (reported, not silent)
+    int long_terms;                  // LongTerms mask of the pass being enqueued (see pass_terms in prefill.hip)
 };
+
+// Records the thread's error message (st_last_error) and returns `code`.
+int fail(int code, const char *fmt, ...) __attribute__((format(printf, 2, 3)));
 
 // Carves the workspace; with base == nullptr only sizes it.
 void carve_workspace(const st_config &c, char *base, Workspace *ws);
@@ -116,6 +126,7 @@ void launch_head(const Model &m, const float *x_row, const st_trigger_rule *rule
 int ring_plan_check(int dual, int M, int N, int K, long long cap_floats, int allow_tail, int *launches_out,
                     int *blocks_out, int *ids_out);
 size_t partial_floats(const st_config &c);  // floats of Workspace::qkv (the split-K / split-key partial results)
+hipError_t raise_lds_limits();              // once per process, before the first ring / streaming GEMM launch
 void launch_prefill_layers(const Model &m, int32_t pos0, int32_t n);
 
 // Device arrays of one batched decode step (n rows = n sequences, each at its own position).

@@ -18,13 +18,13 @@ def _margin(lg):
     return float((s[-1] - s[-2]) / np.abs(lg).max())
 
 
-def _teacher_forced(cfg, g, o, prompt, splits, n_decode):
+def _teacher_forced(cfg, g, o, prompt, splits, n_decode, fast=False):
     """Feeds `prompt` in the given chunk sizes, then n_decode oracle-chosen tokens one by one."""
     worst = 0.0
     lo = hi = 0
     for n in splits:
         hi = lo + n
-        lg_g, tok_g = g.prefill(prompt[lo:hi])
+        lg_g, tok_g = g.prefill(prompt[lo:hi], fast=fast)
         lo = hi
     assert hi == len(prompt)
     lg_o = o.feed(prompt)
@@ -44,10 +44,13 @@ def _teacher_forced(cfg, g, o, prompt, splits, n_decode):
 
 
 def test_qwen1p5b_whole_model():
-    print_case("1.5B shape, 28 layers: prefill 33+7 tokens, 6 decode steps")
-    cfg, g, o = make_pair("qwen1p5b", 1, max_seq=64, max_chunk=48, gen_device="cuda")
+    """The whole 28-layer model: logits within the tolerance at the prompt's end and at each of 32 teacher-forced
+    decode steps, and the GPU's greedy token equal to the oracle's at every step whose top-two logit gap in the
+    oracle exceeds MIN_MARGIN (a bf16 path may legitimately break a nearer tie the other way)."""
+    print_case("1.5B shape, 28 layers: prefill 33+7 tokens, 32 decode steps")
+    cfg, g, o = make_pair("qwen1p5b", 1, max_seq=80, max_chunk=48, gen_device="cuda")
     prompt = synth.make_prompt(40, cfg["vocab"], 3)
-    assert _teacher_forced(cfg, g, o, prompt, [33, 7], 6) <= LOGIT_TOL
+    assert _teacher_forced(cfg, g, o, prompt, [33, 7], 32) <= LOGIT_TOL
     g.close()
 
 
@@ -102,55 +105,61 @@ def test_split_attention_matches_oracle_over_many_ranges():
     g.close()
 
 
-@pytest.mark.parametrize("m", [32, 33, 64, 65, 128, 129, 200, 256, 257, 512, 513])
-def test_prefill_kernel_regime_boundaries(m):
+@pytest.mark.parametrize("m,fast", [(32, False), (33, False), (64, False), (65, False), (128, False), (129, False),
+                                    (200, False), (256, False), (257, False), (512, False), (513, False),
+                                    (257, True), (513, True)])
+def test_prefill_kernel_regime_boundaries(m, fast):
     """Chunk lengths on both sides of every kernel switch (one more 32-row activation tile, 128- to 64-byte row
-    segments above 128 rows, two-term activations up to 256 rows, 256x256 tiles above), on top of 100 cached keys,
-    against the oracle (2 layers)."""
-    print_case(f"1.5B shape, 2 layers: 100 cached + chunk of {m}")
+    segments above 128 rows, the streaming kernel up to 256 rows, 256x256 tiles above -- with two-term inputs by
+    default and with single bf16 inputs on request), on top of 100 cached keys, against the oracle (2 layers)."""
+    print_case(f"1.5B shape, 2 layers: 100 cached + chunk of {m}" + (" (single-term inputs)" if fast else ""))
     cfg, g, o = make_pair("qwen1p5b", 11, max_seq=640, max_chunk=520, n_layers=2, gen_device="cuda")
     prompt = synth.make_prompt(100 + m, cfg["vocab"], 12)
-    assert _teacher_forced(cfg, g, o, prompt, [100, m], 1) <= LOGIT_TOL
+    assert _teacher_forced(cfg, g, o, prompt, [100, m], 1, fast=fast) <= LOGIT_TOL
     g.close()
 
 
+@pytest.mark.parametrize("fast", [False, True])
 @pytest.mark.parametrize("name", ["qwen32b", "qwen7b"])
-def test_4096_row_chunk_agrees_with_1024_row_chunks(name):
+def test_4096_row_chunk_agrees_with_1024_row_chunks(name, fast):
     """A 4096-row pass has more 256 x 256 output tiles than compute units in the O / down projections (32B shape)
     or the QKV projection (7B shape); the columns left over after whole rounds are cut into K slices of their own,
     which 1024-row passes never do.  Same tokens, both ways, on 300 cached keys (2 layers; the oracle is out of
     reach at this size, the 1024-row path is checked against it in the tests above)."""
-    print_case(f"{name} shape, 2 layers: 300 cached + 4096 tokens as one chunk and as four")
+    print_case(f"{name} shape, 2 layers: 300 cached + 4096 tokens as one chunk and as four" +
+               (" (single-term inputs)" if fast else ""))
     cfg = synth.model_config(name, max_seq=4500, max_chunk=4096, n_layers=2)
     g = B.Model(cfg, synth.make_weights(cfg, 21, device="cuda"))
     toks = synth.make_prompt(4400, cfg["vocab"], 22)
     g.prefill(toks[:300], want_logits=False)
-    a, ta = g.prefill(toks[300:4396])
+    a, ta = g.prefill(toks[300:4396], fast=fast)
     g.truncate(300)
     for lo in range(300, 4396 - 1024, 1024):
-        g.prefill(toks[lo:lo + 1024], want_logits=False)
-    b, tb = g.prefill(toks[3372:4396])
+        g.prefill(toks[lo:lo + 1024], want_logits=False, fast=fast)
+    b, tb = g.prefill(toks[3372:4396], fast=fast)
     err = rel_err(a, b)
     print_case("relative logit difference", err)
     assert err <= LOGIT_TOL
     c, _ = g.decode_step(int(toks[4396]))                 # the caches the two ways left behind agree as well
     g.truncate(300)
-    g.prefill(toks[300:4396], want_logits=False)
+    g.prefill(toks[300:4396], want_logits=False, fast=fast)
     d, _ = g.decode_step(int(toks[4396]))
     assert rel_err(c, d) <= LOGIT_TOL
     g.close()
 
 
-def test_4096_row_chunk_tail_tiles_against_oracle():
+@pytest.mark.parametrize("fast", [False, True])
+def test_4096_row_chunk_tail_tiles_against_oracle(fast):
     """A one-layer model sized so that one 4096-row pass takes every leftover-tile path of the long-chunk GEMM with
     ragged edges, small enough for the oracle: hidden 4288 (17 column tiles of 256, the last 192 wide: one round
     of 256 tiles + 16 tail tiles cut into K slices, in the O and the down projection) and intermediate 2240 (18
     column tiles of 128, the last 64 wide: 256 full tiles + 3 half-width tiles in the fused gate/up GEMM)."""
-    print_case("custom shape (hidden 4288, intermediate 2240, 6 q heads per kv head), 1 layer: 40 cached + 4096-row chunk")
+    print_case("custom shape (hidden 4288, intermediate 2240, 6 q heads per kv head), 1 layer: 40 cached + 4096-row chunk" +
+               (" (single-term inputs)" if fast else ""))
     cfg, g, o = make_pair("qwen1p5b", 31, max_seq=4200, max_chunk=4096, n_layers=1, gen_device="cuda",
                           hidden=4288, intermediate=2240, n_q_heads=6, n_kv_heads=1, vocab=2048)
     prompt = synth.make_prompt(4136, cfg["vocab"], 32)
-    assert _teacher_forced(cfg, g, o, prompt, [40, 4096], 2) <= LOGIT_TOL
+    assert _teacher_forced(cfg, g, o, prompt, [40, 4096], 2, fast=fast) <= LOGIT_TOL
     g.close()
 
 
@@ -216,22 +225,57 @@ def test_qwen32b_full_depth_paths_agree():
     g.close()
 
 
+FAST_TOL = 2 * LOGIT_TOL   # opt-in passes with single-bf16 inputs (ST_PREFILL_FAST): about twice the default error
+
+
 def test_qwen1p5b_long_chunk_at_full_depth():
     """A 300-token prompt through all 28 layers, against the oracle.  Fed as one pass it takes the long-chunk
-    kernels, whose GEMM inputs are single bf16 numbers: that rounding, amplified through the depth of a random-weight
-    model, is what the pass's error consists of (the decode steps that follow are unaffected).  With
-    ST_PREFILL_TWO_TERM the same prompt goes in passes of at most 256 rows and keeps the tolerance with margin."""
-    print_case("1.5B shape, 28 layers: 300-token prompt as one pass and as two-term passes, then one decode step")
+    kernels; by default their GEMM and attention inputs are two bf16 terms, which leaves the bf16 K/V cache as the
+    pass's only rounding, and the pass is held to the same tolerance as everything else -- as are the same prompt in
+    passes of at most 256 rows (ST_PREFILL_TWO_TERM) and the decode step that follows.  With ST_PREFILL_FAST the
+    inputs are single bf16 numbers: that rounding, amplified through the depth of a random-weight model, about
+    doubles the error; it is bounded here so that a regression of the opt-in path still shows."""
+    print_case("1.5B shape, 28 layers: 300-token prompt as one pass (default and single-term), as <=256-row passes, then one decode step")
     cfg, g, o = make_pair("qwen1p5b", 1, max_seq=320, max_chunk=300, gen_device="cuda")
     toks = synth.make_prompt(301, cfg["vocab"], 21)
     ref = o.feed(toks[:300])
-    fast, _ = g.prefill(toks[:300])
+    one, _ = g.prefill(toks[:300])
     dec, _ = g.decode_step(int(toks[300]))
     ref_dec = o.feed(toks[300:301])
     g.truncate(0)
     two, _ = g.prefill(toks[:300], two_term=True)
-    print_case("one pass", rel_err(fast, ref), "decode after it", rel_err(dec, ref_dec), "two-term passes", rel_err(two, ref))
+    g.truncate(0)
+    fast, _ = g.prefill(toks[:300], fast=True)
+    print_case("one pass", rel_err(one, ref), "decode after it", rel_err(dec, ref_dec), "<=256-row passes",
+               rel_err(two, ref), "one pass, single-term inputs", rel_err(fast, ref))
     assert g.kv_len == 300
-    assert rel_err(two, ref) <= LOGIT_TOL and rel_err(dec, ref_dec) <= LOGIT_TOL
-    assert rel_err(fast, ref) <= 1.25 * LOGIT_TOL      # measured 2.1e-2: single-term inputs over 28 layers
+    assert rel_err(one, ref) <= LOGIT_TOL and rel_err(two, ref) <= LOGIT_TOL and rel_err(dec, ref_dec) <= LOGIT_TOL
+    assert rel_err(fast, ref) <= FAST_TOL
+    with pytest.raises(B.StError):
+        g.prefill(toks[:4], two_term=True, fast=True)      # the two flags exclude each other
+    g.close()
+
+
+def test_long_pass_through_64_layers_of_a_narrow_model():
+    """Depth pin: a model as deep as the 32B one (64 layers) but narrow enough for the oracle (hidden 1024, 8 query /
+    2 kv heads of 128, intermediate 2816, vocab 4096).  A 300-row pass, the same rows in passes of at most 256, and
+    the decode step at the same position all stay within the tolerance of the oracle through the full depth, and
+    the default pass is no further from it than 1.5 times the decode step -- whose only rounding is the bf16 K/V
+    cache -- so what error a long pass has is the cache's, not its own.  The opt-in single-term pass is bounded too."""
+    print_case("narrow 64-layer model: 300-row pass (default, single-term, <=256-row passes) and decode at row 300")
+    cfg, g, o = make_pair("qwen1p5b", 5, max_seq=340, max_chunk=320, n_layers=64, gen_device="cuda",
+                          hidden=1024, n_q_heads=8, n_kv_heads=2, intermediate=2816, vocab=4096, tie_embeddings=0)
+    toks = synth.make_prompt(300, cfg["vocab"], 21)
+    ref = o.feed(toks)
+    errs = {}
+    for name, kw in (("default", {}), ("single-term", {"fast": True}), ("<=256 rows", {"two_term": True})):
+        g.truncate(0)
+        errs[name] = rel_err(g.prefill(toks, **kw)[0], ref)
+    g.truncate(0)
+    g.prefill(toks[:299], want_logits=False)
+    errs["decode"] = rel_err(g.decode_step(int(toks[299]))[0], ref)
+    print_case(errs)
+    assert max(errs["default"], errs["<=256 rows"], errs["decode"]) <= LOGIT_TOL
+    assert errs["default"] <= 1.5 * errs["decode"]
+    assert errs["single-term"] <= FAST_TOL
     g.close()
