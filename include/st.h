@@ -166,6 +166,19 @@ int st_trigger_scan(const st_trigger_rule *rule, const int32_t *tokens, int32_t 
                     int32_t *positions, int32_t cap, int32_t *n_found, int32_t *scratch,
                     void *stream, uint32_t flags);
 
+/* st_trigger_scan with host outputs for callers that cannot allocate device memory (code under HIP graph capture
+ * set-up, tight serving loops, harnesses that forbid hipMalloc): the device staging that st_trigger_scan takes as
+ * `scratch` is a static device array inside the library instead, ST_SCAN_STATIC_MAX_CAP positions + the count
+ * (16 KB + 4 B on every GPU the library runs on, held until the process ends).  Same results as st_trigger_scan:
+ * the first min(count, cap) firing positions of tokens[lo,hi) (device memory) ascending in positions[] and the
+ * total count in *n_found, both HOST memory; synchronises `stream`.  Calls no hipMalloc / hipFree.  ST_ERANGE if
+ * cap > ST_SCAN_STATIC_MAX_CAP (or the range is bad), otherwise the errors of st_trigger_scan.  All calls on one
+ * GPU share that GPU's array: two calls that overlap in time on the same GPU (different host threads or streams)
+ * race and must be serialised by the caller. */
+#define ST_SCAN_STATIC_MAX_CAP 4096
+int st_trigger_scan_static(const st_trigger_rule *rule, const int32_t *tokens, int32_t lo, int32_t hi,
+                           int32_t *positions, int32_t cap, int32_t *n_found, void *stream);
+
 /* Half-open absolute position spans touched by one hand-over. */
 typedef struct {
     int32_t large_prefill_lo, large_prefill_hi; /* tokens the target caught up on */

@@ -17,7 +17,7 @@ ST_OK, ST_EINVAL, ST_ENOMEM, ST_ERANGE, ST_EHIP = 0, -1, -2, -3, -4
 ST_TOKENS_DEVICE, ST_OUT_DEVICE, ST_TOKEN_CHAINED, ST_PREFILL_TWO_TERM, ST_PREFILL_FAST = 1, 2, 4, 8, 16
 
 EXPORTS = ("st_query_sizes", "st_prefill_plan_check", "st_model_create", "st_model_destroy", "st_kv_len", "st_kv_truncate", "st_prefill",
-           "st_decode_step", "st_decode_graph_state", "st_decode_step_timed", "st_decode_greedy", "st_trigger_scan", "st_handoff", "st_generate",
+           "st_decode_step", "st_decode_graph_state", "st_decode_step_timed", "st_decode_greedy", "st_trigger_scan", "st_trigger_scan_static", "st_handoff", "st_generate",
            "st_generate_policy", "st_batch_query_sizes", "st_batch_create", "st_batch_destroy", "st_batch_kv_len",
            "st_batch_truncate", "st_batch_prefill", "st_batch_prefill_many", "st_batch_decode_step", "st_generate_batch",
            "st_last_error")
@@ -88,6 +88,8 @@ def lib():
         L.st_decode_greedy.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_uint32]
         L.st_trigger_scan.argtypes = [C.POINTER(st_trigger_rule), C.c_void_p, C.c_int32, C.c_int32, C.c_void_p,
                                       C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32]
+        L.st_trigger_scan_static.argtypes = [C.POINTER(st_trigger_rule), C.c_void_p, C.c_int32, C.c_int32, C.c_void_p,
+                                             C.c_int32, C.c_void_p, C.c_void_p]
         L.st_handoff.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, i32p, C.c_int32, C.c_int32, C.c_void_p,
                                  i32p, C.POINTER(st_spans), C.c_uint32]
         L.st_generate.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(st_trigger_rule), C.c_int32, C.c_void_p,
@@ -158,6 +160,19 @@ def st_trigger_scan(rule, tokens_dev, lo, hi, cap, stream=None):
     s = torch.cuda.current_stream().cuda_stream if stream is None else stream
     _check(lib().st_trigger_scan(C.byref(rule.c), tokens_dev.data_ptr(), lo, hi, _np_ptr(pos), cap, C.byref(n),
                                  scratch.data_ptr(), s, 0))
+    return n.value, pos[:min(n.value, cap)].copy()
+
+
+ST_SCAN_STATIC_MAX_CAP = 4096
+
+
+def st_trigger_scan_static(rule, tokens_dev, lo, hi, cap, stream=None):
+    """st_trigger_scan without a caller-provided device scratch (the library's static staging array; allocates
+    nothing on the device).  Returns (total_count, positions ndarray)."""
+    pos = np.empty(max(cap, 1), dtype=np.int32)
+    n = C.c_int32()
+    s = torch.cuda.current_stream().cuda_stream if stream is None else stream
+    _check(lib().st_trigger_scan_static(C.byref(rule.c), tokens_dev.data_ptr(), lo, hi, _np_ptr(pos), cap, C.byref(n), s))
     return n.value, pos[:min(n.value, cap)].copy()
 
 

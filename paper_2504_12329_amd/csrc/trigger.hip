@@ -9,6 +9,8 @@
 // a position costs O(1) whatever the window; the scan starts w tokens before `lo`, which is as far back as any
 // position of the range looks.  One 1024-thread block walks the tokens in tiles, carries the two maxima from tile
 // to tile and compacts the firing positions in ascending order with wave ballots.
+#include <mutex>
+
 #include "st_device.h"
 #include "st_internal.h"
 
@@ -76,4 +78,65 @@ void launch_trigger_scan(const st_trigger_rule &rule, const int32_t *tokens, int
                        rule.delim_bitmap, rule.window, rule.vocab, positions, cap, n_found);
 }
 
+// ---------------------------------------------------------------------------------------
+// The scan for callers that cannot allocate device memory: the result staging (count + positions) lives in a
+// file-scope device array instead of a caller-provided scratch buffer.  Every GPU the library runs on holds its
+// own copy of the array until the process ends; its address is looked up once per device.
+// ---------------------------------------------------------------------------------------
+static __device__ __align__(256) int32_t scratch[1 + ST_SCAN_STATIC_MAX_CAP];
+
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mutex;
+static int32_t *g_scratch_ptr[kMaxDevices];  // device address of `scratch` on each device (nullptr: not looked up yet)
+
+// Device address of this device's copy of the staging array (the array's name is only a host-side handle).
+static int scratch_address(int32_t **out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(ST_EHIP, "hipGetDevice: %s", hipGetErrorString(e));
+    if (dev < 0 || dev >= kMaxDevices) return fail(ST_EHIP, "device index %d outside [0, %d)", dev, kMaxDevices);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p)
+            return fail(ST_EHIP, "hipGetSymbolAddress(scratch): %s", hipGetErrorString(e));
+        g_scratch_ptr[dev] = static_cast<int32_t *>(p);
+    }
+    *out = g_scratch_ptr[dev];
+    return ST_OK;
+}
+
 }  // namespace st
+
+using namespace st;
+
+extern "C" int st_trigger_scan_static(const st_trigger_rule *rule, const int32_t *tokens, int32_t lo, int32_t hi,
+                                      int32_t *positions, int32_t cap, int32_t *n_found, void *stream) {
+    if (!rule || !rule->kw_bitmap || !tokens || !n_found) return fail(ST_EINVAL, "rule, bitmap, tokens or n_found is NULL");
+    if (rule->window < 1 || rule->window > ST_MAX_SCAN_WINDOW) return fail(ST_EINVAL, "window must be in [1, %d]", ST_MAX_SCAN_WINDOW);
+    if (rule->window >= 2 && !rule->delim_bitmap) return fail(ST_EINVAL, "a window above 1 needs a delimiter bitmap");
+    if (rule->vocab <= 0) return fail(ST_EINVAL, "rule vocab must be positive");
+    if (cap < 0 || (cap > 0 && !positions)) return fail(ST_EINVAL, "cap < 0, or positions is NULL with cap > 0");
+    if (cap > ST_SCAN_STATIC_MAX_CAP)
+        return fail(ST_ERANGE, "cap %d exceeds the static staging array (%d positions)", cap, ST_SCAN_STATIC_MAX_CAP);
+    if (lo < 0 || hi < lo) return fail(ST_ERANGE, "bad range [%d,%d)", lo, hi);
+    int32_t *stage = nullptr;
+    if (int rc = scratch_address(&stage)) return rc;
+    hipStream_t s = (hipStream_t)stream;
+    // the kernel writes the count and the first min(count, cap) positions on every call: nothing of the previous
+    // call's contents is read, so nothing has to be cleared
+    launch_trigger_scan(*rule, tokens, lo, hi, stage + 1, cap, stage, s);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(ST_EHIP, "trigger scan: %s", hipGetErrorString(e));
+    e = hipMemcpyAsync(n_found, stage, sizeof(int32_t), hipMemcpyDeviceToHost, s);
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
+    if (e != hipSuccess) return fail(ST_EHIP, "reading the count back: %s", hipGetErrorString(e));
+    const int32_t k = *n_found < cap ? *n_found : cap;
+    if (k > 0) {
+        e = hipMemcpyAsync(positions, stage + 1, sizeof(int32_t) * k, hipMemcpyDeviceToHost, s);
+        if (e == hipSuccess) e = hipStreamSynchronize(s);
+        if (e != hipSuccess) return fail(ST_EHIP, "reading the positions back: %s", hipGetErrorString(e));
+    }
+    return ST_OK;
+}
