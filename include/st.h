@@ -49,13 +49,15 @@ enum {
                               (kept on the device), so steps can be queued without a host round trip */
     ST_PREFILL_TWO_TERM = 8u, /* st_prefill: feed a long run of tokens in passes of at most 256 rows (the length up
                               to which the second bf16 term of the GEMM inputs costs no time) */
-    ST_PREFILL_FAST = 16u    /* st_prefill: in passes of more than 256 rows round every GEMM and attention input to
+    ST_PREFILL_FAST = 16u    /* st_prefill: in passes of more than 128 rows round every GEMM and attention input to
                               one bf16.  By default every pass carries those inputs as two bf16 terms (16 mantissa
                               bits), which leaves the bf16 K/V cache as its only rounding: its logits are then as
-                              close to an fp32 evaluation as the decode step's.  Passes of more than 256 rows are
-                              bound by the MFMA rate and pay twice the MFMA work for that; with this flag they run
-                              about 1.8x faster and their logit error about doubles (measured against the CPU
-                              oracle: 1.7e-2 against 0.8e-2 through 28 layers of the 1.5B shape).  Excludes
+                              close to an fp32 evaluation as the decode step's.  Up to about 240 rows the second
+                              term costs no time (the weight stream sets it); longer passes are bound by the MFMA
+                              rate and pay twice the MFMA work.  With this flag passes of 129 rows and more take
+                              the MFMA-bound kernels with single bf16 inputs: 1.3x (129 rows) to 1.8x (1024 rows
+                              and more) faster, at about twice the logit error (measured against the CPU oracle:
+                              1.7e-2 against 0.8e-2 through 28 layers of the 1.5B shape).  Excludes
                               ST_PREFILL_TWO_TERM. */
 };
 
@@ -97,7 +99,7 @@ int st_query_sizes(const st_config *cfg, size_t *kv_bytes, size_t *workspace_byt
  * -- K slices, leftover column tiles, half-width tiles -- and verifies that every output tile and K step is
  * computed by exactly one block and that every partial-sum tile lies inside the workspace st_query_sizes reports.
  * Touches no device.  launches / blocks (may be NULL) receive the GEMM launches and working blocks of one layer
- * (0 for rows <= 256, which take the streaming kernel).  ST_EINVAL with the failing projection in
+ * (0 for rows <= 128, which take the streaming kernel whatever the precision).  ST_EINVAL with the failing projection in
  * st_last_error() if the plan is inconsistent, ST_ERANGE if rows is outside 1..cfg->max_chunk. */
 int st_prefill_plan_check(const st_config *cfg, int32_t rows, int32_t *launches, int32_t *blocks);
 
@@ -119,7 +121,7 @@ int st_kv_truncate(st_model *m, int32_t new_len);
  * kv_len += n.  logits (fp32[vocab]) and next_tok (the greedy arg-max, lowest index on ties)
  * of the LAST fed position are written when the pointers are non-NULL.
  * Runs of more than max_chunk tokens (256 with ST_PREFILL_TWO_TERM) are fed as consecutive passes; see
- * ST_PREFILL_FAST for the precision of passes of more than 256 rows.
+ * ST_PREFILL_FAST for the precision of long passes.
  * ST_ERANGE if n <= 0, kv_len + n > max_seq, or (host tokens only) an id is outside the vocabulary;
  * ids in device memory that are out of range are clamped into the vocabulary by the kernel. */
 int st_prefill(st_model *m, const int32_t *tokens, int32_t n, float *logits, int32_t *next_tok,

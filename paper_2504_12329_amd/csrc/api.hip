@@ -111,6 +111,7 @@ static int prefill_impl(Model *m, const int32_t *tokens, int32_t n, bool tokens_
     // passes of at most max_chunk rows; 256 rows on request: the longest pass that keeps every GEMM input in two terms
     const int32_t step = mode == kPassTwoTerm && c.max_chunk > 256 ? 256 : c.max_chunk;
     m->long_terms = mode == kPassFast ? 0 : kDefaultLongTerms;
+    m->ring_min_rows = mode == kPassFast ? kRingMinRowsFast : kRingMinRows;
     for (int32_t done = 0; done < n; done += step) {
         int32_t cn = n - done < step ? n - done : step;
         ST_HIP(hipMemcpyAsync(m->ws.tokens, tokens + done, sizeof(int32_t) * cn,
@@ -280,7 +281,7 @@ int st_prefill_plan_check(const st_config *cfg, int32_t rows, int32_t *launches,
     if (rows <= 0 || rows > cfg->max_chunk) return fail(ST_ERANGE, "rows %d outside 1..max_chunk", rows);
     if (launches) *launches = 0;
     if (blocks) *blocks = 0;
-    if (rows <= 256) return ST_OK;  // short chunks take the streaming kernel: one tile list, no leftover handling
+    if (rows < kRingMinRowsFast) return ST_OK;  // short chunks take the streaming kernel: one tile list, no leftovers
     const int h = cfg->hidden, I = cfg->intermediate, qd = cfg->n_q_heads * cfg->head_dim;
     const int qkv = (cfg->n_q_heads + 2 * cfg->n_kv_heads) * cfg->head_dim;
     const long long cap = (long long)partial_floats(*cfg);
@@ -351,6 +352,7 @@ static int build_model(const st_config *cfg, const st_weights *w, void *kv, void
     m->graphs_off = getenv("ST_NO_GRAPH") != nullptr;
     m->graph_failed = false;
     m->long_terms = kDefaultLongTerms;
+    m->ring_min_rows = kRingMinRows;
     static std::once_flag lds_once;
     static hipError_t lds_rc = hipSuccess;
     std::call_once(lds_once, [] { lds_rc = raise_lds_limits(); });
@@ -792,6 +794,7 @@ struct Batch {
     int32_t *row_ints;             // device: tok | pos | seq (row_cap each), next (n_seq)
     size_t row_cap;                // max(max_chunk, n_seq)
     float *q_rows, *o_rows, *part_ml, *part_acc, *logits;
+    FlashSeg *seg_tab;             // device: kMaxBatch entries, the segment table of a ragged catch-up pass
 };
 constexpr int kMaxBatch = 64;
 
@@ -810,7 +813,8 @@ size_t batch_extra(const st_config &c, int32_t n, char *base, Batch *b) {
     float *ml = (float *)take(sizeof(float) * (size_t)n * c.n_q_heads * kAttnSplits * 2);
     float *acc = (float *)take(sizeof(float) * (size_t)n * c.n_q_heads * kAttnSplits * c.head_dim);
     float *lg = (float *)take(sizeof(float) * (size_t)n * c.vocab);
-    if (b) b->row_ints = ri, b->q_rows = q, b->o_rows = o, b->part_ml = ml, b->part_acc = acc, b->logits = lg;
+    FlashSeg *st = (FlashSeg *)take(sizeof(FlashSeg) * kMaxBatch);
+    if (b) b->row_ints = ri, b->q_rows = q, b->o_rows = o, b->part_ml = ml, b->part_acc = acc, b->logits = lg, b->seg_tab = st;
     return off;
 }
 int check_batch(const st_config *cfg, int32_t n_seq) {
@@ -918,7 +922,7 @@ int st_batch_decode_step(st_batch *h, int32_t n_rows, const int32_t *seqs, const
     ST_HIP(hipMemcpyAsync(dev, host.data(), sizeof(int32_t) * host.size(), hipMemcpyHostToDevice, b->base.stream));
     ST_HIP(hipStreamSynchronize(b->base.stream));  // `host` leaves scope before the copy would otherwise be read
     BatchRows rows = {dev, dev + n_rows, dev + 2 * (size_t)n_rows, dev + 3 * b->row_cap, b->seq_stride,
-                      b->q_rows, b->o_rows, b->part_ml, b->part_acc, logits ? b->logits : nullptr};
+                      b->q_rows, b->o_rows, b->part_ml, b->part_acc, logits ? b->logits : nullptr, nullptr};
     launch_batch_step(b->base, rows, n_rows, attn_bucket(max_pos + 1));
     if (int rc = check_launch("batched decode step")) return rc;
     if (logits)
@@ -954,11 +958,12 @@ int st_batch_prefill_many(st_batch *h, int32_t n, const int32_t *seqs, const int
     }
     if (R > c.max_chunk) return fail(ST_ERANGE, "%lld rows in all exceed max_chunk %d", (long long)R, c.max_chunk);
     std::vector<int32_t> host(3 * (size_t)R + n);
-    std::vector<VarlenSeg> segs(n);
-    int32_t row = 0;
+    std::vector<FlashSeg> segs(n);
+    int32_t row = 0, blk = 0;
     for (int32_t j = 0; j < n; ++j) {
         const int32_t s = seqs[j];
-        segs[j] = VarlenSeg{s, row, lens[j], b->kv_len[s]};
+        segs[j] = FlashSeg{row, lens[j], b->kv_len[s], s, blk, flash_row_blocks(c, lens[j])};
+        blk += segs[j].nblk;
         for (int32_t i = 0; i < lens[j]; ++i, ++row) {
             host[row] = tokens[j][i];
             host[R + row] = b->kv_len[s] + i;
@@ -970,9 +975,10 @@ int st_batch_prefill_many(st_batch *h, int32_t n, const int32_t *seqs, const int
     hipStream_t st = b->base.stream;
     ST_HIP(hipMemcpyAsync(dev, host.data(), sizeof(int32_t) * 3 * (size_t)R, hipMemcpyHostToDevice, st));
     ST_HIP(hipMemcpyAsync(next, host.data() + 3 * (size_t)R, sizeof(int32_t) * n, hipMemcpyHostToDevice, st));
+    ST_HIP(hipMemcpyAsync(b->seg_tab, segs.data(), sizeof(FlashSeg) * n, hipMemcpyHostToDevice, st));
     ST_HIP(hipStreamSynchronize(st));
     BatchRows rows = {dev, dev + R, dev + 2 * (size_t)R, next, b->seq_stride, b->q_rows, b->o_rows, b->part_ml,
-                      b->part_acc, logits ? b->logits : nullptr};
+                      b->part_acc, logits ? b->logits : nullptr, b->seg_tab};
     launch_prefill_varlen(b->base, rows, segs.data(), n, (int)R);
     if (int rc = check_launch("ragged catch-up pass")) return rc;
     if (logits) ST_HIP(hipMemcpyAsync(logits, b->logits, sizeof(float) * (size_t)n * c.vocab, hipMemcpyDeviceToHost, st));

@@ -961,12 +961,30 @@ __global__ __launch_bounds__(256) void k_swiglu_rows(const float *__restrict__ p
 // ---------------------------------------------------------------------------------------
 constexpr int kFlashKeys = 64;
 
+// Resolves blockIdx.x to (segment, row block inside it); all values are wave-uniform.
+struct FlashWhere {
+    int m, kv0, row_base, bx, nbx;
+    size_t cache;
+};
+__device__ __forceinline__ FlashWhere flash_where(const FlashSeg *segs, int n_seg, size_t seq_stride, int m, int kv0) {
+    FlashWhere w = {m, kv0, 0, (int)blockIdx.x, (int)gridDim.x, 0};
+    if (segs) {
+        int j = 0;
+        while (j + 1 < n_seg && w.bx >= segs[j + 1].blk0) ++j;
+        const FlashSeg sg = segs[j];
+        w.m = sg.len, w.kv0 = sg.kv0, w.row_base = sg.row0, w.bx -= sg.blk0, w.nbx = sg.nblk;
+        w.cache = (size_t)sg.seq * seq_stride;
+    }
+    return w;
+}
+
 template <int D>
 __global__ __launch_bounds__(256) void k_flash_prefill(const bf16_t *__restrict__ qb, const bf16_t *__restrict__ kc,
                                                        const bf16_t *__restrict__ vc, bf16_t *__restrict__ out,
                                                        bf16_t *__restrict__ outlo, float *__restrict__ part_o,
                                                        float *__restrict__ part_ml, int m, int kv0, int nq, int G,
-                                                       int max_seq) {
+                                                       int max_seq, const FlashSeg *__restrict__ segs, int n_seg,
+                                                       size_t seq_stride, int m_total) {
     constexpr int KS = D + 8;             // K tile row stride (elements): 16-byte reads conflict-free
     constexpr int VS = kFlashKeys + 4;    // V^T row stride (elements)
     constexpr int CH = D / 8;             // 16-byte chunks per key
@@ -977,8 +995,11 @@ __global__ __launch_bounds__(256) void k_flash_prefill(const bf16_t *__restrict_
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, kg = lane >> 5;
     const int g = blockIdx.y, n_split = gridDim.z, z = blockIdx.z;
+    const FlashWhere fw = flash_where(segs, n_seg, seq_stride, m, kv0);
+    m = fw.m, kv0 = fw.kv0;
+    kc += fw.cache, vc += fw.cache;
     const int rows = m * G;
-    const int r0 = blockIdx.x * 128, rw0 = r0 + wave * 32;
+    const int r0 = fw.bx * 128, rw0 = r0 + wave * 32;
     const int ldq = nq * D;
     const bool wave_active = rw0 < rows;
     const int row = min(rw0 + l32, rows - 1);
@@ -994,7 +1015,7 @@ __global__ __launch_bounds__(256) void k_flash_prefill(const bf16_t *__restrict_
     bf16x8 qf[D / 16];
 #pragma unroll
     for (int s = 0; s < D / 16; ++s)
-        qf[s] = as_bf16x8(*reinterpret_cast<const u32x4 *>(qb + (size_t)qtok * ldq + head * D + 16 * s + 8 * kg));
+        qf[s] = as_bf16x8(*reinterpret_cast<const u32x4 *>(qb + (size_t)(fw.row_base + qtok) * ldq + head * D + 16 * s + 8 * kg));
 
     f32x16 o[D / 32];
 #pragma unroll
@@ -1138,8 +1159,8 @@ __global__ __launch_bounds__(256) void k_flash_prefill(const bf16_t *__restrict_
     if (!wave_active || rw0 + l32 >= rows) return;
     if (n_split == 1) {
         const float inv = 1.0f / l_i;
-        bf16_t *orow = out + (size_t)qtok * ldq + head * D;
-        bf16_t *lrow = outlo ? outlo + (size_t)qtok * ldq + head * D : nullptr;
+        bf16_t *orow = out + (size_t)(fw.row_base + qtok) * ldq + head * D;
+        bf16_t *lrow = outlo ? outlo + (size_t)(fw.row_base + qtok) * ldq + head * D : nullptr;
 #pragma unroll
         for (int tt = 0; tt < D / 32; ++tt)
 #pragma unroll
@@ -1157,7 +1178,7 @@ __global__ __launch_bounds__(256) void k_flash_prefill(const bf16_t *__restrict_
             }
     } else {
         // partial result of this key split for (token, head): [z][token*nq + head]
-        const size_t pr = (size_t)z * m * nq + (size_t)qtok * nq + head;
+        const size_t pr = (size_t)z * m_total * nq + (size_t)(fw.row_base + qtok) * nq + head;
         float *po = part_o + pr * D;
 #pragma unroll
         for (int tt = 0; tt < D / 32; ++tt)
@@ -1192,7 +1213,8 @@ __global__ __launch_bounds__(64 * NW, TWO ? 1 : 2) void k_flash_long(const bf16_
                                                     const bf16_t *__restrict__ vc, bf16_t *__restrict__ out,
                                                     bf16_t *__restrict__ outlo, float *__restrict__ part_o,
                                                     float *__restrict__ part_ml, int m, int kv0, int nq, int G,
-                                                    int max_seq) {
+                                                    int max_seq, const FlashSeg *__restrict__ segs, int n_seg,
+                                                    size_t seq_stride, int m_total) {
     constexpr int D = 128, VS = kFlashKeys + 8;  // V^T rows of 144 bytes: 16-byte reads conflict-free
     __shared__ __align__(16) unsigned char Ks[2][kFlashKeys * D * 2];
     __shared__ __align__(16) bf16_t Vt[2][D * VS];
@@ -1200,10 +1222,13 @@ __global__ __launch_bounds__(64 * NW, TWO ? 1 : 2) void k_flash_long(const bf16_
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, kg = lane >> 5;
     const int g = blockIdx.y, n_split = gridDim.z, z = blockIdx.z;
+    const FlashWhere fw = flash_where(segs, n_seg, seq_stride, m, kv0);
+    m = fw.m, kv0 = fw.kv0;
+    kc += fw.cache, vc += fw.cache;
     const int rows = m * G;
     constexpr int kLongRows = 32 * NW, NT = 64 * NW;
     // blocks with the most keys (the last rows) are dispatched first, so the causal tail is made of short blocks
-    const int r0 = (gridDim.x - 1 - blockIdx.x) * kLongRows, rw0 = r0 + wave * 32;
+    const int r0 = (fw.nbx - 1 - fw.bx) * kLongRows, rw0 = r0 + wave * 32;
     const int ldq = nq * D;
     const bool wave_active = rw0 < rows;
     const int row = min(rw0 + l32, rows - 1);
@@ -1220,9 +1245,9 @@ __global__ __launch_bounds__(64 * NW, TWO ? 1 : 2) void k_flash_long(const bf16_
     bf16x8 qf[D / 16], ql[TWO ? D / 16 : 1];
 #pragma unroll
     for (int s = 0; s < D / 16; ++s) {
-        qf[s] = as_bf16x8(*reinterpret_cast<const u32x4 *>(qb + (size_t)qtok * ldq + head * D + 16 * s + 8 * kg));
+        qf[s] = as_bf16x8(*reinterpret_cast<const u32x4 *>(qb + (size_t)(fw.row_base + qtok) * ldq + head * D + 16 * s + 8 * kg));
         if constexpr (TWO)
-            ql[s] = as_bf16x8(*reinterpret_cast<const u32x4 *>(qb_lo + (size_t)qtok * ldq + head * D + 16 * s + 8 * kg));
+            ql[s] = as_bf16x8(*reinterpret_cast<const u32x4 *>(qb_lo + (size_t)(fw.row_base + qtok) * ldq + head * D + 16 * s + 8 * kg));
     }
 
     f32x16 o[D / 32];
@@ -1406,7 +1431,7 @@ __global__ __launch_bounds__(64 * NW, TWO ? 1 : 2) void k_flash_long(const bf16_
     if (!wave_active || rw0 + l32 >= rows) return;
     if (n_split == 1) {
         const float inv = 1.0f / l_i;
-        bf16_t *orow = out + (size_t)qtok * ldq + head * D;
+        bf16_t *orow = out + (size_t)(fw.row_base + qtok) * ldq + head * D;
 #pragma unroll
         for (int tt = 0; tt < D / 32; ++tt)
 #pragma unroll
@@ -1419,11 +1444,11 @@ __global__ __launch_bounds__(64 * NW, TWO ? 1 : 2) void k_flash_long(const bf16_
                 if (outlo) {  // second bf16 term of the activation (short chunks)
                     u32x2 lo = {pack_bf16x2(v0 - bf16_lo(pk.x), v1 - bf16_hi(pk.x)),
                                 pack_bf16x2(v2 - bf16_lo(pk.y), v3 - bf16_hi(pk.y))};
-                    *reinterpret_cast<u32x2 *>(outlo + (size_t)qtok * ldq + head * D + dcol) = lo;
+                    *reinterpret_cast<u32x2 *>(outlo + (size_t)(fw.row_base + qtok) * ldq + head * D + dcol) = lo;
                 }
             }
     } else {
-        const size_t pr = (size_t)z * m * nq + (size_t)qtok * nq + head;
+        const size_t pr = (size_t)z * m_total * nq + (size_t)(fw.row_base + qtok) * nq + head;
         float *po = part_o + pr * D;
 #pragma unroll
         for (int tt = 0; tt < D / 32; ++tt)
@@ -1506,9 +1531,8 @@ size_t partial_floats(const st_config &c) {
 }
 
 // Launches one GEMM; returns the number of K slices written to ws.qkv (0 for the fused SwiGLU form).
-// Alo != nullptr selects the two-term activation form (chunks of at most kSplitRows rows).
-constexpr int kSplitRows = 256;
-constexpr int kBigRows = 257;  // every chunk too long for the two-term form uses the 256 x 256 ring kernel
+// Alo != nullptr selects the two-term activation form.
+constexpr int kSplitRows = 256;  // most rows the weight-streaming kernel takes (eight 32-row activation tiles)
 
 template <int BM, int BNR, int WGM, int WGN, bool DUAL, bool SPLITA>
 static void gemm_launch(const Model &m, dim3 grid, const bf16_t *A, const bf16_t *Alo, int lda, const bf16_t *B, int M,
@@ -1761,8 +1785,9 @@ int ring_plan_check(int dual, int M, int N, int K, long long cap_floats, int all
     return 0;
 }
 
-// Two-term chunks (at most kSplitRows rows) use the streaming kernel and an unfused SwiGLU wherever K is a multiple
-// of 64; otherwise the register-staged kernel, with many K slices and an unfused SwiGLU up to kSmallRows rows.
+// Chunks below the model's ring threshold (two-term, at most kSplitRows rows) use the streaming kernel and an unfused
+// SwiGLU wherever K is a multiple of 64; otherwise the register-staged kernel, with many K slices and an unfused
+// SwiGLU up to kSmallRows rows.
 constexpr int kSmallRows = 64;
 
 template <bool DUAL>
@@ -1772,8 +1797,8 @@ static int gemm(const Model &m, const bf16_t *A, const bf16_t *Alo, int lda, con
     // (the ring kernel addresses its operands with 32-bit byte offsets)
     const bool fits32 = (size_t)M * lda * sizeof(bf16_t) < ((size_t)1 << 32) &&
                         (size_t)(DUAL ? 2 : 1) * N * K * sizeof(bf16_t) < ((size_t)1 << 32);
-    const bool big = M >= kBigRows && K % kRingBK == 0 && K >= 2 * kRingBK && fits32;
-    if (!DUAL && Alo && M <= kSplitRows && K % kRingBK == 0) {
+    const bool big = M >= m.ring_min_rows && K % kRingBK == 0 && K >= 2 * kRingBK && fits32;
+    if (!big && !DUAL && Alo && M <= kSplitRows && K % kRingBK == 0) {
         const StreamShape sh = stream_shape(m, M, N, K);
         switch ((M + 31) / 32) {
             case 1: stream_launch<1, 64>(m, sh, A, Alo, lda, B, M, N, K); break;
@@ -1840,7 +1865,7 @@ struct PassTerms {
 };
 static PassTerms pass_terms(const Model &m, int n) {
     const Workspace &w = m.ws;
-    const int terms = n <= kSplitRows ? kTermAll : m.long_terms;
+    const int terms = n < m.ring_min_rows ? kTermAll : m.long_terms;
     PassTerms t;
     t.qkv_two = terms & kTermQKV, t.gu_two = terms & kTermGateUp;
     t.xn_lo = (t.qkv_two || t.gu_two) ? w.xn_lo : nullptr;
@@ -1850,21 +1875,34 @@ static PassTerms pass_terms(const Model &m, int n) {
     return t;
 }
 
-// Causal attention of n query rows at positions pos0 .. pos0+n-1 over one sequence's cache (kc / vc of one layer).
+int flash_row_blocks(const st_config &c, int len) {
+    const int G = c.n_q_heads / c.n_kv_heads;
+    return (len * G + 127) / 128;  // both attention kernels take 128 folded rows per block
+}
+
+// Causal attention of n query rows at positions pos0 .. pos0+n-1 over one sequence's cache (kc / vc of one layer) --
+// or, with `ragged`, of the R rows of several sequences in one launch (kc / vc are then sequence 0's caches).
+struct RaggedPass {
+    const FlashSeg *segs_dev;  // device table, n_seg entries
+    int n_seg, R, total_blocks, max_tiles;
+    size_t seq_stride;
+};
 static void launch_flash(const Model &m, const bf16_t *qb, const bf16_t *qb_lo, const bf16_t *kc, const bf16_t *vc,
-                         bf16_t *attn, bf16_t *attn_lo, int n, int pos0) {
+                         bf16_t *attn, bf16_t *attn_lo, int n, int pos0, const RaggedPass *ragged = nullptr) {
     const st_config &c = m.c;
     const int d = c.head_dim, nq = c.n_q_heads, nkv = c.n_kv_heads;
     const Workspace &w = m.ws;
     const bool long_chunk = d == 128;  // head_dim 128: k_flash_long at every chunk length
-    const int G = nq / nkv, rows = n * G, rpb = long_chunk ? 32 * kLongWaves : 128, rblocks = (rows + rpb - 1) / rpb;
-    const int n_tiles = (pos0 + n + kFlashKeys - 1) / kFlashKeys;
+    const int G = nq / nkv;
+    const int rblocks = ragged ? ragged->total_blocks : flash_row_blocks(c, n);
+    const int n_tiles = ragged ? ragged->max_tiles : (pos0 + n + kFlashKeys - 1) / kFlashKeys;
+    const int n_rows_all = ragged ? ragged->R : n;  // rows the partial buffers are sized for
     // key splits: enough blocks for every CU, bounded by the tiles and by the partial buffer
     int splits = (512 + rblocks * nkv - 1) / (rblocks * nkv);
     if (splits > n_tiles) splits = n_tiles;
     if (splits > 32) splits = 32;
     const size_t cap = partial_floats(c);
-    if (long_chunk) {
+    if (long_chunk && !ragged) {
         // k_flash_long: the count that minimises (rounds of resident blocks) x (tiles per block + 2 for the set-up
         // and the store) x the time of a tile step, plus the merge pass over the partial results (its bytes at
         // 4 TB/s + a launch).  640 blocks of 42 tiles on 512 slots are two rounds; 960 blocks of 27 are two shorter ones.
@@ -1884,20 +1922,23 @@ static void launch_flash(const Model &m, const bf16_t *qb, const bf16_t *qb_lo, 
             if (best < 0 || cost < best) best = cost, splits = sp;
         }
     }
-    while (splits > 1 && (size_t)splits * n * nq * (d + 2) > cap) --splits;
-    float *part_o = w.qkv, *part_ml = w.qkv + (size_t)splits * n * nq * d;
+    while (splits > 1 && (size_t)splits * n_rows_all * nq * (d + 2) > cap) --splits;
+    float *part_o = w.qkv, *part_ml = w.qkv + (size_t)splits * n_rows_all * nq * d;
     dim3 fgrid(rblocks, nkv, splits);
+    const FlashSeg *segs = ragged ? ragged->segs_dev : nullptr;
+    const int n_seg = ragged ? ragged->n_seg : 0;
+    const size_t seq_stride = ragged ? ragged->seq_stride : 0;
     if (long_chunk && qb_lo)
         hipLaunchKernelGGL((k_flash_long<kLongWaves, true>), fgrid, dim3(64 * kLongWaves), 0, m.stream, qb, qb_lo, kc, vc,
-                           attn, attn_lo, part_o, part_ml, n, pos0, nq, G, c.max_seq);
+                           attn, attn_lo, part_o, part_ml, n, pos0, nq, G, c.max_seq, segs, n_seg, seq_stride, n_rows_all);
     else if (long_chunk)
         hipLaunchKernelGGL((k_flash_long<kLongWaves, false>), fgrid, dim3(64 * kLongWaves), 0, m.stream, qb, qb_lo, kc, vc,
-                           attn, attn_lo, part_o, part_ml, n, pos0, nq, G, c.max_seq);
+                           attn, attn_lo, part_o, part_ml, n, pos0, nq, G, c.max_seq, segs, n_seg, seq_stride, n_rows_all);
     else
         hipLaunchKernelGGL(k_flash_prefill<64>, fgrid, dim3(256), 0, m.stream, qb, kc, vc, attn, attn_lo, part_o,
-                           part_ml, n, pos0, nq, G, c.max_seq);
+                           part_ml, n, pos0, nq, G, c.max_seq, segs, n_seg, seq_stride, n_rows_all);
     if (splits > 1) {
-        const int n_rows = n * nq;
+        const int n_rows = n_rows_all * nq;
         if (d == 128)
             hipLaunchKernelGGL(k_flash_combine<128>, dim3((n_rows + 1) / 2), dim3(256), 0, m.stream, part_o, part_ml,
                                splits, n_rows, attn, attn_lo);
@@ -1931,8 +1972,8 @@ void launch_prefill_layers(const Model &m, int32_t pos0, int32_t n) {
         int so = gemm<false>(m, w.attn, attn_lo, qd, m.wo[l], n, h, qd, nullptr, nullptr, 0, &to);
         hipLaunchKernelGGL(k_rmsnorm_rows, dim3(n), dim3(norm_threads(n)), 0, m.stream, w.x, w.qkv, so, (size_t)n * h,
                            m.norm_mlp[l], w.xn, xn_lo, h, c.rms_eps, to);
-        if (n <= (h % kRingBK == 0 ? kSplitRows : kSmallRows)) {  // small chunk: gate/up as a plain split-K GEMM over
-                                                                   // all 2I rows, SwiGLU in the consumer
+        if (n < (h % kRingBK == 0 ? m.ring_min_rows : kSmallRows + 1)) {  // small chunk: gate/up as a plain split-K
+                                                                           // GEMM over all 2I rows, SwiGLU in the consumer
             int sg = gemm<false>(m, w.xn, xn_lo, h, m.wgu[l], n, 2 * I, h, nullptr, nullptr, 0);
             hipLaunchKernelGGL(k_swiglu_rows, dim3((I / 4 + 255) / 256, n), dim3(256), 0, m.stream, w.qkv, sg,
                                (size_t)n * 2 * I, I, w.act, w.act_lo);
@@ -2117,10 +2158,17 @@ __global__ __launch_bounds__(256) void k_gather_rows(const float *__restrict__ X
 // Catch-up pass over rows of several sequences at once (ragged): R rows in all, the rows of segment j are
 // contiguous (segs[j].row0 .. +len) at positions kv0 .. kv0+len-1 of sequence segs[j].seq.  Projections see one
 // R-row chunk (the weights are streamed once for all sequences); RoPE / KV append go by the per-row (sequence,
-// position) arrays; attention is launched per segment on that sequence's cache; the LM head runs on the gathered
-// last rows of the segments.
-void launch_prefill_varlen(const Model &m, const BatchRows &b, const VarlenSeg *segs, int n_seg, int R) {
+// position) arrays; attention is one launch over all segments (a device table tells every block its segment: rows,
+// positions and cache), with one key-split count for the whole pass; the LM head runs on the gathered last rows of
+// the segments.  `segs` is the host copy of the table at b.seg_tab.
+void launch_prefill_varlen(const Model &m, const BatchRows &b, const FlashSeg *segs, int n_seg, int R) {
     const st_config &c = m.c;
+    RaggedPass ragged = {b.seg_tab, n_seg, R, 0, 0, b.seq_stride};
+    for (int j = 0; j < n_seg; ++j) {
+        ragged.total_blocks = segs[j].blk0 + segs[j].nblk;
+        const int tiles = (segs[j].kv0 + segs[j].len + kFlashKeys - 1) / kFlashKeys;
+        if (tiles > ragged.max_tiles) ragged.max_tiles = tiles;
+    }
     const int h = c.hidden, d = c.head_dim, nq = c.n_q_heads, nkv = c.n_kv_heads, I = c.intermediate;
     const int qd = nq * d, qkv = m.qkv_dim;
     const Workspace &w = m.ws;
@@ -2136,16 +2184,11 @@ void launch_prefill_varlen(const Model &m, const BatchRows &b, const VarlenSeg *
         hipLaunchKernelGGL(k_rope_append_rows, dim3(R, nq + 2 * nkv), dim3(d / 2), 0, m.stream, w.qkv, sq,
                            (size_t)R * qkv, m.bqkv[l], w.rope, (float *)nullptr, w.qb, qb_lo, m.kcache + lofs,
                            m.vcache + lofs, b.row_pos, b.row_seq, b.seq_stride, nq, nkv, d, c.max_seq);
-        for (int j = 0; j < n_seg; ++j) {
-            const size_t cache = (size_t)segs[j].seq * b.seq_stride + lofs, q0 = (size_t)segs[j].row0 * qd;
-            launch_flash(m, w.qb + q0, qb_lo ? qb_lo + q0 : nullptr, m.kcache + cache, m.vcache + cache, w.attn + q0,
-                         attn_lo ? attn_lo + q0 : nullptr,
-                         segs[j].len, segs[j].kv0);
-        }
+        launch_flash(m, w.qb, qb_lo, m.kcache + lofs, m.vcache + lofs, w.attn, attn_lo, 0, 0, &ragged);
         const int so = gemm<false>(m, w.attn, attn_lo, qd, m.wo[l], R, h, qd, nullptr, nullptr, 0);
         hipLaunchKernelGGL(k_rmsnorm_rows, dim3(R), dim3(norm_threads(R)), 0, m.stream, w.x, w.qkv, so, (size_t)R * h,
                            m.norm_mlp[l], w.xn, xn_lo, h, c.rms_eps, PartTail{});
-        if (R <= (h % kRingBK == 0 ? kSplitRows : kSmallRows)) {
+        if (R < (h % kRingBK == 0 ? m.ring_min_rows : kSmallRows + 1)) {
             const int sg = gemm<false>(m, w.xn, xn_lo, h, m.wgu[l], R, 2 * I, h, nullptr, nullptr, 0);
             hipLaunchKernelGGL(k_swiglu_rows, dim3((I / 4 + 255) / 256, R), dim3(256), 0, m.stream, w.qkv, sg,
                                (size_t)R * 2 * I, I, w.act, w.act_lo);

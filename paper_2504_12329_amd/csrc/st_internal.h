@@ -55,6 +55,10 @@ struct AttnRows {
 // the four projections and the rotated queries of the attention
 enum LongTerms { kTermQKV = 1, kTermO = 2, kTermGateUp = 4, kTermDown = 8, kTermQuery = 16, kTermAll = 31 };
 constexpr int kDefaultLongTerms = kTermAll;
+// Passes of at least this many rows take the 256 x 256 ring GEMMs, shorter ones the weight-streaming kernel (always
+// two-term).  Measured per layer of the 32B shape on 4096 cached keys, streaming two-term / ring two-term / ring
+// single-term: 129 rows 0.50 / 0.60 / 0.39 ms, 224 rows 0.63 / 0.64 / 0.41 ms, 256 rows 0.69 / 0.64 / 0.41 ms.
+constexpr int kRingMinRows = 241, kRingMinRowsFast = 129;
 
 constexpr int kLmBlocks = 1024;   // blocks (and arg-max partials) of the LM-head kernel
 constexpr int kAttnSplits = 128;  // most key ranges one kv head is split into at decode
@@ -87,6 +91,7 @@ struct Model {
     bool graphs_off;                 // capture failed or was disabled: steps are launched kernel by kernel
     bool graph_failed;               // graphs_off because a capture or instantiation failed (reported, not silent)
     int long_terms;                  // LongTerms mask of the pass being enqueued (see pass_terms in prefill.hip)
+    int ring_min_rows;               // passes of at least this many rows take the 256 x 256 ring GEMMs
 };
 
 // Records the thread's error message (st_last_error) and returns `code`.
@@ -137,16 +142,21 @@ struct BatchRows {
     float *q_rows, *o_rows;                      // [n][n_q*d]
     float *part_ml, *part_acc;                   // [n][n_q][kAttnSplits][2 | d]
     float *logits;                               // [n][vocab] or nullptr
+    const struct FlashSeg *seg_tab;              // device: segment table of a ragged catch-up pass (else nullptr)
 };
 // All layers, LM head and arg-max for n rows (n <= 64); m.kcache / m.vcache are the caches of sequence 0.
 void launch_batch_step(const Model &m, const BatchRows &b, int n, int attn_blocks);
-// One segment of a ragged catch-up pass: rows row0 .. row0+len-1 are positions kv0 .. of sequence seq.
-struct VarlenSeg {
-    int32_t seq, row0, len, kv0;
+// One segment of a ragged catch-up pass: query rows [row0, row0 + len) of the pass are positions kv0 .. kv0 + len - 1
+// of sequence `seq`; the attention launch gives it the row blocks [blk0, blk0 + nblk) of grid.x
+// (nblk = flash_row_blocks(cfg, len)).
+struct FlashSeg {
+    int32_t row0, len, kv0, seq, blk0, nblk;
 };
+int flash_row_blocks(const st_config &c, int len);
 // Ragged catch-up over R rows of n_seg sequences (R <= max_chunk); b.row_next holds the row index of every
-// segment's last row on entry and the greedy next tokens on return; b.o_rows needs n_seg * hidden floats.
-void launch_prefill_varlen(const Model &m, const BatchRows &b, const VarlenSeg *segs, int n_seg, int R);
+// segment's last row on entry and the greedy next tokens on return; b.o_rows needs n_seg * hidden floats; segs is
+// the host copy of the segment table already uploaded to b.seg_tab.
+void launch_prefill_varlen(const Model &m, const BatchRows &b, const FlashSeg *segs, int n_seg, int R);
 
 // ---- launchers (trigger.hip) ----
 void launch_trigger_scan(const st_trigger_rule &rule, const int32_t *tokens, int32_t lo, int32_t hi,

@@ -236,6 +236,56 @@ def test_batched_loop_with_staggered_forced_period():
     bl.close()
 
 
+def _ragged_against_oracles(cfg, batch, oracles, cached, lens, decode_after=True):
+    """Sequence j holds cached[j] tokens; one ragged pass feeds lens[j] more to each (segments in reverse order); every
+    sequence's last-position logits against its own oracle, then one batched decode step over all of them."""
+    n = len(lens)
+    for j in range(n):
+        if cached[j]:
+            pre = synth.make_prompt(cached[j], cfg["vocab"], 300 + j)
+            oracles[j].feed(pre)
+            batch.prefill(j, pre, want_logits=False)
+    chunks = [synth.make_prompt(lens[j], cfg["vocab"], 400 + j) for j in range(n)]
+    order = list(range(n))[::-1]
+    lg_g, nxt = batch.prefill_many(order, [chunks[j] for j in order], want_logits=True)
+    worst, toks = 0.0, {}
+    for r, j in enumerate(order):
+        lg_o = oracles[j].feed(chunks[j])
+        worst = max(worst, rel_err(lg_g[r], lg_o))
+        assert nxt[r] == O.argmax(lg_g[r]) and batch.kv_len(j) == oracles[j].kv_len
+        toks[j] = O.argmax(lg_o)
+    if decode_after:
+        lg_g, _ = batch.decode_step(list(range(n)), [toks[j] for j in range(n)], want_logits=True)
+        for j in range(n):
+            worst = max(worst, rel_err(lg_g[j], oracles[j].feed([toks[j]])))
+    print_case("worst relative logit error", worst)
+    return worst
+
+
+def test_ragged_catch_up_of_sixteen_sequences():
+    """Sixteen segments of 1..40 rows on caches of 0..150 tokens in one pass: the attention of the pass is one launch
+    whose blocks find their segment in a device table (several key splits, segments shorter than a row block, an
+    empty cache among them)."""
+    rng = np.random.default_rng(77)
+    lens = [int(v) for v in rng.integers(1, 41, 16)]
+    cached = [int(v) for v in rng.integers(0, 151, 16)]
+    cached[3], lens[3], lens[9] = 0, 1, 40
+    print_case("tiny model, 16 sequences: ragged catch-up of", lens, "tokens onto caches of", cached)
+    cfg, batch, oracles = _setup("tiny_small", 16, 1, max_seq=256, max_chunk=512)
+    assert _ragged_against_oracles(cfg, batch, oracles, cached, lens) <= LOGIT_TOL
+    batch.close()
+
+
+@pytest.mark.parametrize("lens,cached", [([40, 130, 7], [90, 20, 300]), ([150, 200], [0, 64])])
+def test_ragged_catch_up_pass_head_dim_128(lens, cached):
+    """The same at head_dim 128 (1.5B shape, 2 layers), whose attention kernel is a different one: a pass of 177 rows
+    (two-term queries, streaming GEMMs) and one of 350 rows (256 x 256 tiles)."""
+    print_case("1.5B shape, 2 layers: ragged catch-up of", lens, "tokens onto caches of", cached)
+    cfg, batch, oracles = _setup("qwen1p5b", len(lens), 6, max_seq=512, n_layers=2, gen_device="cuda", max_chunk=512)
+    assert _ragged_against_oracles(cfg, batch, oracles, cached, lens) <= LOGIT_TOL
+    batch.close()
+
+
 @pytest.mark.parametrize("lens", [[5, 1, 33, 12], [70, 90, 60], [200, 150, 100]])
 def test_ragged_catch_up_pass(lens):
     """Several sequences with different cached lengths each receive a chunk of a different length in one pass
