@@ -111,6 +111,22 @@ int st_model_create(const st_config *cfg, const st_weights *w, void *kv, size_t 
                     void *workspace, size_t workspace_bytes, void *stream, st_model **out);
 void st_model_destroy(st_model *m);
 
+/* fp16 operand mode for long passes.  The weights are bf16 numbers, and a bf16 number of magnitude between 2^-16 and
+ * 65504 is an fp16 number as well.  st_model_attach_f16 copies the four projection matrices of every layer as fp16
+ * into `buf` (device memory owned by the caller, 256-byte aligned, st_query_f16_bytes bytes -- as many as the bf16
+ * matrices take -- borrowed until st_model_destroy or a detaching call); weights smaller than 2^-16 round to a
+ * multiple of 2^-24.  From then on default-precision passes of 129 rows and more run their four GEMMs in the
+ * MFMA-bound kernels on the fp16 MFMA, with single fp16 activations instead of two bf16 terms:
+ * the same MFMA rate as one bf16 term, 11 mantissa bits instead of 8 -- measured against the CPU oracle the pass
+ * stays at the decode step's error, at about the speed of ST_PREFILL_FAST.  Activations are normalised rows,
+ * attention outputs and SwiGLU products; they saturate at +-65504 when written.  The K/V cache, the queries (two
+ * bf16 terms), shorter passes, ST_PREFILL_FAST / ST_PREFILL_TWO_TERM passes and the decode step are unchanged.
+ * buf == NULL detaches.  The call runs on the model's stream and synchronises it.  ST_EINVAL if hidden,
+ * n_q_heads*head_dim or intermediate is not a multiple of 64; ST_ENOMEM if `bytes` is too small; ST_ERANGE (mode not
+ * enabled) if a weight is NaN or larger than 65504. */
+int st_query_f16_bytes(const st_config *cfg, size_t *bytes);
+int st_model_attach_f16(st_model *m, void *buf, size_t bytes);
+
 /* Number of positions whose keys/values are cached. */
 int st_kv_len(const st_model *m, int32_t *out);
 /* O(1) rollback to a shorter context (0 <= new_len <= kv_len), ST_ERANGE otherwise. */
@@ -275,6 +291,8 @@ int st_batch_query_sizes(const st_config *cfg, int32_t n_seq, size_t *kv_bytes, 
 int st_batch_create(const st_config *cfg, const st_weights *w, int32_t n_seq, void *kv, size_t kv_bytes,
                     void *workspace, size_t workspace_bytes, void *stream, st_batch **out);
 void st_batch_destroy(st_batch *b);
+/* st_model_attach_f16 for the weights a batch shares (same buffer size, same errors). */
+int st_batch_attach_f16(st_batch *b, void *buf, size_t bytes);
 int st_batch_kv_len(const st_batch *b, int32_t seq, int32_t *out);
 int st_batch_truncate(st_batch *b, int32_t seq, int32_t new_len);
 /* Feeds n tokens to sequence `seq` (catch-up pass of that sequence alone); logits (fp32[vocab]) and next_tok of the

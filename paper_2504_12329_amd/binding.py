@@ -17,7 +17,7 @@ ST_OK, ST_EINVAL, ST_ENOMEM, ST_ERANGE, ST_EHIP = 0, -1, -2, -3, -4
 ST_TOKENS_DEVICE, ST_OUT_DEVICE, ST_TOKEN_CHAINED, ST_PREFILL_TWO_TERM, ST_PREFILL_FAST = 1, 2, 4, 8, 16
 
 EXPORTS = ("st_query_sizes", "st_prefill_plan_check", "st_model_create", "st_model_destroy", "st_kv_len", "st_kv_truncate", "st_prefill",
-           "st_decode_step", "st_decode_graph_state", "st_decode_step_timed", "st_decode_greedy", "st_trigger_scan", "st_trigger_scan_static", "st_handoff", "st_generate",
+           "st_query_f16_bytes", "st_model_attach_f16", "st_batch_attach_f16", "st_decode_step", "st_decode_graph_state", "st_decode_step_timed", "st_decode_greedy", "st_trigger_scan", "st_trigger_scan_static", "st_handoff", "st_generate",
            "st_generate_policy", "st_batch_query_sizes", "st_batch_create", "st_batch_destroy", "st_batch_kv_len",
            "st_batch_truncate", "st_batch_prefill", "st_batch_prefill_many", "st_batch_decode_step", "st_generate_batch",
            "st_last_error")
@@ -85,6 +85,9 @@ def lib():
         L.st_decode_step.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_uint32]
         L.st_decode_step_timed.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_double)]
         L.st_decode_graph_state.argtypes = [C.c_void_p, i32p, i32p]
+        L.st_query_f16_bytes.argtypes = [C.POINTER(st_config), C.POINTER(C.c_size_t)]
+        L.st_model_attach_f16.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t]
+        L.st_batch_attach_f16.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t]
         L.st_decode_greedy.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_uint32]
         L.st_trigger_scan.argtypes = [C.POINTER(st_trigger_rule), C.c_void_p, C.c_int32, C.c_int32, C.c_void_p,
                                       C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32]
@@ -249,6 +252,18 @@ class Model:
         _check(lib().st_decode_step(self._h, int(token), _np_ptr(lg) if want_logits else None, C.addressof(nt), 0))
         return lg, nt.value
 
+    def attach_f16(self, on=True):
+        """Gives the model an fp16 copy of its projection weights (torch-owned buffer): long default-precision passes
+        then run on the fp16 MFMA with single fp16 activations.  on=False detaches and frees the buffer."""
+        if not on:
+            _check(lib().st_model_attach_f16(self._h, None, 0))
+            self.f16_buf = None
+            return
+        n = C.c_size_t()
+        _check(lib().st_query_f16_bytes(C.byref(make_config(self.cfg)), C.byref(n)))
+        self.f16_buf = torch.empty(n.value, dtype=torch.uint8, device=self.kv.device)
+        _check(lib().st_model_attach_f16(self._h, self.f16_buf.data_ptr(), n.value))
+
     def graph_state(self):
         """(step graphs captured so far, mode): mode 0 = graphs replayed, 1 = off by ST_NO_GRAPH, 2 = capture failed."""
         n, mode = C.c_int32(), C.c_int32()
@@ -392,6 +407,13 @@ class Batch:
 
     def truncate(self, seq, n):
         _check(lib().st_batch_truncate(self._h, seq, n))
+
+    def attach_f16(self):
+        """fp16 copy of the shared projection weights (see Model.attach_f16)."""
+        n = C.c_size_t()
+        _check(lib().st_query_f16_bytes(C.byref(make_config(self.cfg)), C.byref(n)))
+        self.f16_buf = torch.empty(n.value, dtype=torch.uint8, device=self.kv.device)
+        _check(lib().st_batch_attach_f16(self._h, self.f16_buf.data_ptr(), n.value))
 
     def prefill(self, seq, tokens, want_logits=True):
         t = np.ascontiguousarray(tokens, dtype=np.int32)

@@ -97,6 +97,12 @@ void carve_workspace(const st_config &c, char *base, Workspace *ws) {
 // Enqueues the catch-up pass over `n` tokens (host or device ids); the last row's logits and greedy
 // token (with the trigger predicate when a rule is given) end up in ws.logits / state.
 enum PrefillMode { kPassDefault, kPassTwoTerm, kPassFast };
+// Precision and kernel regime of the passes enqueued next (read by pass_terms / gemm in prefill.hip).
+static void set_pass_mode(Model *m, PrefillMode mode) {
+    m->long_terms = mode == kPassFast ? 0 : kDefaultLongTerms;
+    m->f16_pass = mode == kPassDefault && m->f16_on;
+    m->ring_min_rows = (mode == kPassFast || m->f16_pass) ? kRingMinRowsFast : kRingMinRows;
+}
 static int prefill_impl(Model *m, const int32_t *tokens, int32_t n, bool tokens_dev, const st_trigger_rule *rule,
                         PrefillMode mode = kPassDefault) {
     const st_config &c = m->c;
@@ -110,8 +116,7 @@ static int prefill_impl(Model *m, const int32_t *tokens, int32_t n, bool tokens_
                 return fail(ST_ERANGE, "token id %d at index %d is outside the vocabulary [0,%d)", tokens[i], i, c.vocab);
     // passes of at most max_chunk rows; 256 rows on request: the longest pass that keeps every GEMM input in two terms
     const int32_t step = mode == kPassTwoTerm && c.max_chunk > 256 ? 256 : c.max_chunk;
-    m->long_terms = mode == kPassFast ? 0 : kDefaultLongTerms;
-    m->ring_min_rows = mode == kPassFast ? kRingMinRowsFast : kRingMinRows;
+    set_pass_mode(m, mode);
     for (int32_t done = 0; done < n; done += step) {
         int32_t cn = n - done < step ? n - done : step;
         ST_HIP(hipMemcpyAsync(m->ws.tokens, tokens + done, sizeof(int32_t) * cn,
@@ -353,6 +358,7 @@ static int build_model(const st_config *cfg, const st_weights *w, void *kv, void
     m->graph_failed = false;
     m->long_terms = kDefaultLongTerms;
     m->ring_min_rows = kRingMinRows;
+    m->f16_on = m->f16_pass = false;
     static std::once_flag lds_once;
     static hipError_t lds_rc = hipSuccess;
     std::call_once(lds_once, [] { lds_rc = raise_lds_limits(); });
@@ -388,6 +394,58 @@ void st_model_destroy(st_model *h) {
     for (StepGraph &g : m->graphs) (void)hipGraphExecDestroy(g.exec);
     if (m->capture_stream) (void)hipStreamDestroy(m->capture_stream);
     delete m;
+}
+
+static size_t f16_elems(const st_config &c) {  // elements of one layer's four projection matrices
+    const size_t h = c.hidden, qd = (size_t)c.n_q_heads * c.head_dim, I = c.intermediate;
+    return (qd + 2 * (size_t)c.n_kv_heads * c.head_dim) * h + h * qd + 2 * I * h + h * I;
+}
+
+int st_query_f16_bytes(const st_config *cfg, size_t *bytes) {
+    if (int rc = validate_config(cfg)) return rc;
+    if (!bytes) return fail(ST_EINVAL, "bytes is NULL");
+    if (!f16_shape_ok(*cfg))
+        return fail(ST_EINVAL, "the fp16 operand mode needs hidden, n_q_heads*head_dim and intermediate to be multiples of 64");
+    *bytes = f16_elems(*cfg) * cfg->n_layers * sizeof(bf16_t);
+    return ST_OK;
+}
+
+static int attach_f16(Model *m, void *buf, size_t bytes) {
+    m->f16_on = m->f16_pass = false;
+    m->wqkv16.clear(), m->wo16.clear(), m->wgu16.clear(), m->wdown16.clear();
+    if (!buf) return ST_OK;  // detach
+    const st_config &c = m->c;
+    if (!f16_shape_ok(c))
+        return fail(ST_EINVAL, "the fp16 operand mode needs hidden, n_q_heads*head_dim and intermediate to be multiples of 64");
+    const size_t need = f16_elems(c) * c.n_layers * sizeof(bf16_t);
+    if (bytes < need) return fail(ST_ENOMEM, "fp16 weight buffer has %zu bytes, %zu needed", bytes, need);
+    if ((uintptr_t)buf & 255) return fail(ST_EINVAL, "the fp16 weight buffer must be 256-byte aligned");
+    const size_t h = c.hidden, qd = (size_t)c.n_q_heads * c.head_dim, I = c.intermediate;
+    const size_t n_qkv = (size_t)m->qkv_dim * h, n_o = h * qd, n_gu = 2 * I * h, n_d = h * I;
+    launch_set_state(*m, kCount, 0);
+    bf16_t *p = static_cast<bf16_t *>(buf);
+    int32_t *bad = m->ws.state + kCount;
+    for (int l = 0; l < c.n_layers; ++l) {
+        launch_f16_copy(*m, m->wqkv[l], p, n_qkv, bad), m->wqkv16.push_back(p), p += n_qkv;
+        launch_f16_copy(*m, m->wo[l], p, n_o, bad), m->wo16.push_back(p), p += n_o;
+        launch_f16_copy(*m, m->wgu[l], p, n_gu, bad), m->wgu16.push_back(p), p += n_gu;
+        launch_f16_copy(*m, m->wdown[l], p, n_d, bad), m->wdown16.push_back(p), p += n_d;
+    }
+    if (int rc = check_launch("fp16 weight copy")) return rc;
+    int32_t n_bad = 0;
+    ST_HIP(hipMemcpyAsync(&n_bad, bad, sizeof(int32_t), hipMemcpyDeviceToHost, m->stream));
+    ST_HIP(hipStreamSynchronize(m->stream));
+    if (n_bad) {
+        m->wqkv16.clear(), m->wo16.clear(), m->wgu16.clear(), m->wdown16.clear();
+        return fail(ST_ERANGE, "%d weights are NaN or exceed the largest fp16 number: fp16 operand mode not enabled", n_bad);
+    }
+    m->f16_on = true;
+    return ST_OK;
+}
+
+int st_model_attach_f16(st_model *hm, void *buf, size_t bytes) {
+    if (!hm) return fail(ST_EINVAL, "model is NULL");
+    return attach_f16(reinterpret_cast<Model *>(hm), buf, bytes);
 }
 
 int st_kv_len(const st_model *h, int32_t *out) {
@@ -865,6 +923,11 @@ int st_batch_create(const st_config *cfg, const st_weights *w, int32_t n_seq, vo
 
 void st_batch_destroy(st_batch *h) { delete reinterpret_cast<Batch *>(h); }
 
+int st_batch_attach_f16(st_batch *h, void *buf, size_t bytes) {
+    if (!h) return fail(ST_EINVAL, "batch is NULL");
+    return attach_f16(&reinterpret_cast<Batch *>(h)->base, buf, bytes);
+}
+
 int st_batch_kv_len(const st_batch *h, int32_t seq, int32_t *out) {
     const Batch *b = reinterpret_cast<const Batch *>(h);
     if (!b || !out) return fail(ST_EINVAL, "batch or out is NULL");
@@ -979,6 +1042,7 @@ int st_batch_prefill_many(st_batch *h, int32_t n, const int32_t *seqs, const int
     ST_HIP(hipStreamSynchronize(st));
     BatchRows rows = {dev, dev + R, dev + 2 * (size_t)R, next, b->seq_stride, b->q_rows, b->o_rows, b->part_ml,
                       b->part_acc, logits ? b->logits : nullptr, b->seg_tab};
+    set_pass_mode(&b->base, kPassDefault);
     launch_prefill_varlen(b->base, rows, segs.data(), n, (int)R);
     if (int rc = check_launch("ragged catch-up pass")) return rc;
     if (logits) ST_HIP(hipMemcpyAsync(logits, b->logits, sizeof(float) * (size_t)n * c.vocab, hipMemcpyDeviceToHost, st));

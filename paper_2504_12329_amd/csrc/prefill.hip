@@ -15,6 +15,25 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 
+// fp16 operand mode of the long-chunk GEMMs (see st_model_attach_f16): the same 16-bit containers hold IEEE half
+// numbers and the MFMA is the f16 one (same rate as bf16, 11 mantissa bits instead of 8).
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ f16x8 as_f16x8(u32x4 v) { return __builtin_bit_cast(f16x8, v); }
+// fp32 -> fp16, round to nearest even, saturating at the largest finite half (activations are O(1); the clamp only
+// keeps a stray huge value from becoming an infinity inside a dot product)
+__device__ __forceinline__ uint32_t pack_f16x2(float lo, float hi) {
+    lo = fminf(fmaxf(lo, -65504.f), 65504.f), hi = fminf(fmaxf(hi, -65504.f), 65504.f);
+    const f16x2_t v = {(_Float16)lo, (_Float16)hi};
+    return __builtin_bit_cast(uint32_t, v);
+}
+__device__ __forceinline__ uint32_t pack_16x2(bool f16, float lo, float hi) {
+    return f16 ? pack_f16x2(lo, hi) : pack_bf16x2(lo, hi);
+}
+__device__ __forceinline__ uint16_t to_16(bool f16, float v) {
+    return f16 ? (uint16_t)(pack_f16x2(v, 0.f) & 0xffffu) : f32_to_bf16(v);
+}
+
 // ---------------------------------------------------------------------------------------
 // rows: embedding gather and RMSNorm
 // ---------------------------------------------------------------------------------------
@@ -50,11 +69,12 @@ static inline int norm_threads(int rows) { return rows <= 512 ? 1024 : 256; }
 
 // x[row] += sum of the pending split-K partial results (fixed order), then y[row] = bf16(rmsnorm(x) * g).
 // part is [n_part][rows][h] (plus the extra slices `tail` describes); with g == nullptr only the residual update is done.  With Ylo the
-// normalised row is written as a sum of two bf16 numbers (Y + Ylo), which keeps 16 mantissa bits.
+// normalised row is written as a sum of two bf16 numbers (Y + Ylo), which keeps 16 mantissa bits; with f16 (and no
+// Ylo) as one fp16 number.
 __global__ __launch_bounds__(1024) void k_rmsnorm_rows(float *__restrict__ X, const float *__restrict__ part,
                                                        int n_part, size_t part_stride, const bf16_t *__restrict__ g,
                                                        bf16_t *__restrict__ Y, bf16_t *__restrict__ Ylo, int h,
-                                                       float eps, PartTail tail) {
+                                                       float eps, PartTail tail, int f16) {
     __shared__ float red[16];
     float4 *x = reinterpret_cast<float4 *>(X + (size_t)blockIdx.x * h);
     const float4 *p0 = reinterpret_cast<const float4 *>(part + (size_t)blockIdx.x * h);
@@ -113,7 +133,7 @@ __global__ __launch_bounds__(1024) void k_rmsnorm_rows(float *__restrict__ X, co
         u32x2 gg = g2[i];
         float a = v.x * inv * bf16_lo(gg.x), b = v.y * inv * bf16_hi(gg.x);
         float c = v.z * inv * bf16_lo(gg.y), d = v.w * inv * bf16_hi(gg.y);
-        u32x2 hi = {pack_bf16x2(a, b), pack_bf16x2(c, d)};
+        u32x2 hi = {pack_16x2(f16, a, b), pack_16x2(f16, c, d)};  // fp16 for the fp16 operand mode (then no low term)
         y[i] = hi;
         if (ylo) {  // second bf16 term of the activation
             u32x2 lo = {pack_bf16x2(a - bf16_lo(hi.x), b - bf16_hi(hi.x)), pack_bf16x2(c - bf16_lo(hi.y), d - bf16_hi(hi.y))};
@@ -424,7 +444,9 @@ __host__ __device__ inline bool ring_block(const RingGrid &gg, int bid, int M, i
 // HALF (fused SwiGLU form only): the block tile is 256 x (64 gate + 64 up) weight rows -- half the columns, half the
 // MFMAs per fragment of activations -- for the tiles left over after whole rounds of full tiles (one more round of
 // half the length instead of a round that leaves half the chip idle).
-template <bool DUAL, bool HALF = false>
+// F16: A and B hold fp16 numbers (single-term activations, the model's fp16 copy of the weights) and the fused
+// epilogue writes fp16.
+template <bool DUAL, bool HALF = false, bool F16 = false>
 __global__ __launch_bounds__(256) void k_gemm_ring(const bf16_t *__restrict__ A, const bf16_t *__restrict__ Alo, int lda,
                                                    const bf16_t *__restrict__ B, int M, int N, int K,
                                                    float *__restrict__ part, bf16_t *__restrict__ outb,
@@ -508,25 +530,30 @@ __global__ __launch_bounds__(256) void k_gemm_ring(const bf16_t *__restrict__ A,
     const int ch_even = (kg ^ ring_swz(l32)) * 16, ch_odd = ch_even ^ 64;
     const int ch_half = wn ? ch_odd : ch_even;  // HALF: both weight fragments of a wave sit in 32-row block wn or 2 + wn
 
-    bf16x8 fa[2][4], fb[2][NB];
+    u32x4 fa[2][4], fb[2][NB];
     // fragment q of a 16-wide step: q = 0..3 weight fragments (0..1 with HALF), 4..7 activation fragments
     auto fetch = [&](auto buf_c, auto q_c, int slotA, int slotB, int ks) {
         constexpr int buf = decltype(buf_c)::value, q = decltype(q_c)::value;
         if constexpr (q < 4) {
             if constexpr (q < NB) {
                 const int ch = (HALF ? ch_half : (q & 1) ? ch_odd : ch_even) ^ (ks * 32);
-                fb[buf][q] = as_bf16x8(*reinterpret_cast<const u32x4 *>(ring + slotB * kRingSlot + b_off[q] + ch));
+                fb[buf][q] = *reinterpret_cast<const u32x4 *>(ring + slotB * kRingSlot + b_off[q] + ch);
             }
         } else {
             const int ch = ((q & 1) ? ch_odd : ch_even) ^ (ks * 32);
-            fa[buf][q & 3] =
-                as_bf16x8(*reinterpret_cast<const u32x4 *>(ring + slotA * kRingSlot + a_off + (q & 3) * 4096 + ch));
+            fa[buf][q & 3] = *reinterpret_cast<const u32x4 *>(ring + slotA * kRingSlot + a_off + (q & 3) * 4096 + ch);
         }
     };
     auto mma_one = [&](auto buf_c, auto i_c, auto j_c) {
         constexpr int buf = decltype(buf_c)::value, i = decltype(i_c)::value, j = decltype(j_c)::value;
-        if constexpr (j < NB)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[buf][i], fb[buf][j], acc[i][j], 0, 0, 0);
+        if constexpr (j < NB) {
+            if constexpr (F16)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(as_f16x8(fa[buf][i]), as_f16x8(fb[buf][j]),
+                                                                   acc[i][j], 0, 0, 0);
+            else
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(fa[buf][i]), as_bf16x8(fb[buf][j]),
+                                                                    acc[i][j], 0, 0, 0);
+        }
     };
     // One 16-wide step: four groups of { one direct load (KIND 1: weight instruction D0+g, 2: activation
     // instruction D0+g, 0: none), two fragment reads for the following step, four MFMAs }; the scheduling
@@ -627,14 +654,14 @@ __global__ __launch_bounds__(256) void k_gemm_ring(const bf16_t *__restrict__ A,
                     }
                     const float other = dpp_move<0xB1, 0xf>(0.f, odd ? a[0] : a[1]);  // quad_perm [1,0,3,2]
                     const float x0 = odd ? other : a[0], x1 = odd ? a[1] : other;
-                    const uint32_t pk = pack_bf16x2(x0, x1);
+                    const uint32_t pk = F16 ? pack_f16x2(x0, x1) : pack_bf16x2(x0, x1);
                     const int row = m0 + wm * 128 + i * 32 + 8 * (r >> 2) + 4 * kg + (r & 3) + (odd ? 1 : 0);
                     const int col = n0 + wn * (NB * 16) + j * 32 + (l32 & ~1);
                     if (row < M && col + 1 < N)
                         *reinterpret_cast<uint32_t *>(outb + (size_t)row * ldo + col) = pk;
                     else if (row < M && col < N)  // an odd width: the last column alone
                         outb[(size_t)row * ldo + col] = (bf16_t)(pk & 0xffffu);
-                    if (outlo) {  // second bf16 term of the activation (feeds a two-term down projection)
+                    if (!F16 && outlo) {  // second bf16 term of the activation (feeds a two-term down projection)
                         const uint32_t lo = pack_bf16x2(x0 - bf16_lo(pk), x1 - bf16_hi(pk));
                         if (row < M && col + 1 < N)
                             *reinterpret_cast<uint32_t *>(outlo + (size_t)row * ldo + col) = lo;
@@ -984,7 +1011,7 @@ __global__ __launch_bounds__(256) void k_flash_prefill(const bf16_t *__restrict_
                                                        bf16_t *__restrict__ outlo, float *__restrict__ part_o,
                                                        float *__restrict__ part_ml, int m, int kv0, int nq, int G,
                                                        int max_seq, const FlashSeg *__restrict__ segs, int n_seg,
-                                                       size_t seq_stride, int m_total) {
+                                                       size_t seq_stride, int m_total, int f16) {
     constexpr int KS = D + 8;             // K tile row stride (elements): 16-byte reads conflict-free
     constexpr int VS = kFlashKeys + 4;    // V^T row stride (elements)
     constexpr int CH = D / 8;             // 16-byte chunks per key
@@ -1168,7 +1195,7 @@ __global__ __launch_bounds__(256) void k_flash_prefill(const bf16_t *__restrict_
                 int dcol = tt * 32 + 8 * rq + 4 * kg;
                 float v0 = o[tt][4 * rq + 0] * inv, v1 = o[tt][4 * rq + 1] * inv;
                 float v2 = o[tt][4 * rq + 2] * inv, v3 = o[tt][4 * rq + 3] * inv;
-                u32x2 pk = {pack_bf16x2(v0, v1), pack_bf16x2(v2, v3)};
+                u32x2 pk = {pack_16x2(f16, v0, v1), pack_16x2(f16, v2, v3)};  // output: bf16, or fp16 (no low term)
                 *reinterpret_cast<u32x2 *>(orow + dcol) = pk;
                 if (lrow) {
                     u32x2 lo = {pack_bf16x2(v0 - bf16_lo(pk.x), v1 - bf16_hi(pk.x)),
@@ -1214,7 +1241,7 @@ __global__ __launch_bounds__(64 * NW, TWO ? 1 : 2) void k_flash_long(const bf16_
                                                     bf16_t *__restrict__ outlo, float *__restrict__ part_o,
                                                     float *__restrict__ part_ml, int m, int kv0, int nq, int G,
                                                     int max_seq, const FlashSeg *__restrict__ segs, int n_seg,
-                                                    size_t seq_stride, int m_total) {
+                                                    size_t seq_stride, int m_total, int f16) {
     constexpr int D = 128, VS = kFlashKeys + 8;  // V^T rows of 144 bytes: 16-byte reads conflict-free
     __shared__ __align__(16) unsigned char Ks[2][kFlashKeys * D * 2];
     __shared__ __align__(16) bf16_t Vt[2][D * VS];
@@ -1439,7 +1466,7 @@ __global__ __launch_bounds__(64 * NW, TWO ? 1 : 2) void k_flash_long(const bf16_
                 const int dcol = tt * 32 + 8 * rq + 4 * kg;
                 const float v0 = o[tt][4 * rq + 0] * inv, v1 = o[tt][4 * rq + 1] * inv;
                 const float v2 = o[tt][4 * rq + 2] * inv, v3 = o[tt][4 * rq + 3] * inv;
-                u32x2 pk = {pack_bf16x2(v0, v1), pack_bf16x2(v2, v3)};
+                u32x2 pk = {pack_16x2(f16, v0, v1), pack_16x2(f16, v2, v3)};  // output: bf16, or fp16 (no low term)
                 *reinterpret_cast<u32x2 *>(orow + dcol) = pk;
                 if (outlo) {  // second bf16 term of the activation (short chunks)
                     u32x2 lo = {pack_bf16x2(v0 - bf16_lo(pk.x), v1 - bf16_hi(pk.x)),
@@ -1472,7 +1499,7 @@ __global__ __launch_bounds__(64 * NW, TWO ? 1 : 2) void k_flash_long(const bf16_
 template <int D>
 __global__ __launch_bounds__(256) void k_flash_combine(const float *__restrict__ part_o,
                                                        const float *__restrict__ part_ml, int n_split, int n_rows,
-                                                       bf16_t *__restrict__ out, bf16_t *__restrict__ outlo) {
+                                                       bf16_t *__restrict__ out, bf16_t *__restrict__ outlo, int f16) {
     constexpr int RPB = 256 / D, kMaxSplits = 32;
     __shared__ float m_s[RPB][kMaxSplits], w_s[RPB][kMaxSplits], l_s[RPB];
     const int g = threadIdx.x / D, e = threadIdx.x % D;
@@ -1510,7 +1537,7 @@ __global__ __launch_bounds__(256) void k_flash_combine(const float *__restrict__
     __syncthreads();
     if (!live) return;
     const float v = A / l_s[g];
-    const bf16_t hi = f32_to_bf16(v);
+    const bf16_t hi = to_16(f16, v);
     out[(size_t)r * D + e] = hi;
     if (outlo) outlo[(size_t)r * D + e] = f32_to_bf16(v - bf16_to_f32(hi));
 }
@@ -1545,10 +1572,14 @@ static void gemm_launch(const Model &m, dim3 grid, const bf16_t *A, const bf16_t
 }
 
 template <bool DUAL, bool HALF = false>
-static void ring_launch(const Model &m, dim3 grid, const bf16_t *A, const bf16_t *Alo, int lda, const bf16_t *B, int M,
-                        int N, int K, bf16_t *outb, bf16_t *outlo, int ldo, const RingGrid &gg) {
-    hipLaunchKernelGGL((k_gemm_ring<DUAL, HALF>), grid, dim3(256), kRingLds, m.stream, A, Alo, lda, B, M, N, K,
-                       m.ws.qkv, outb, outlo, ldo, gg);
+static void ring_launch(const Model &m, bool f16, dim3 grid, const bf16_t *A, const bf16_t *Alo, int lda,
+                        const bf16_t *B, int M, int N, int K, bf16_t *outb, bf16_t *outlo, int ldo, const RingGrid &gg) {
+    if (f16)
+        hipLaunchKernelGGL((k_gemm_ring<DUAL, HALF, true>), grid, dim3(256), kRingLds, m.stream, A, Alo, lda, B, M, N, K,
+                           m.ws.qkv, outb, outlo, ldo, gg);
+    else
+        hipLaunchKernelGGL((k_gemm_ring<DUAL, HALF, false>), grid, dim3(256), kRingLds, m.stream, A, Alo, lda, B, M, N, K,
+                           m.ws.qkv, outb, outlo, ldo, gg);
 }
 
 // The ring and streaming kernels use more dynamic LDS than a kernel gets by default; the limit is raised once per
@@ -1564,8 +1595,10 @@ hipError_t raise_lds_limits() {
     auto take = [&](hipError_t r) {
         if (e == hipSuccess) e = r;
     };
-    take(raise_one(k_gemm_ring<false, false>)), take(raise_one(k_gemm_ring<true, false>));
-    take(raise_one(k_gemm_ring<true, true>));
+    take(raise_one(k_gemm_ring<false, false, false>)), take(raise_one(k_gemm_ring<true, false, false>));
+    take(raise_one(k_gemm_ring<true, true, false>));
+    take(raise_one(k_gemm_ring<false, false, true>)), take(raise_one(k_gemm_ring<true, false, true>));
+    take(raise_one(k_gemm_ring<true, true, true>));
     take(raise_one(k_gemm_stream<1, 64, true>)), take(raise_one(k_gemm_stream<2, 64, true>));
     take(raise_one(k_gemm_stream<3, 64, true>)), take(raise_one(k_gemm_stream<4, 64, false>));
     take(raise_one(k_gemm_stream<5, 32, false>)), take(raise_one(k_gemm_stream<6, 32, false>));
@@ -1724,13 +1757,13 @@ static RingPlan ring_plan(bool dual, int M, int N, int K, size_t cap, bool allow
 
 // Alo != nullptr: two-term activations, the plan covers the doubled contraction [A | Alo] x [B | B].
 template <bool DUAL>
-static int ring_gemm(const Model &m, const bf16_t *A, const bf16_t *Alo, int lda, const bf16_t *B, int M, int N, int K,
-                     bf16_t *outb, bf16_t *outlo, int ldo, PartTail *tail) {
+static int ring_gemm(const Model &m, bool f16, const bf16_t *A, const bf16_t *Alo, int lda, const bf16_t *B, int M, int N,
+                     int K, bf16_t *outb, bf16_t *outlo, int ldo, PartTail *tail) {
     const RingPlan p = ring_plan(DUAL, M, N, Alo ? 2 * K : K, partial_floats(m.c), tail != nullptr);
-    ring_launch<DUAL, false>(m, dim3(p.grid_x[0]), A, Alo, lda, B, M, N, K, outb, outlo, ldo, p.g[0]);
+    ring_launch<DUAL, false>(m, f16, dim3(p.grid_x[0]), A, Alo, lda, B, M, N, K, outb, outlo, ldo, p.g[0]);
     if constexpr (DUAL)
         if (p.n == 2)
-            ring_launch<true, true>(m, dim3(p.grid_x[1]), A, Alo, lda, B, M, N, K, outb, outlo, ldo, p.g[1]);
+            ring_launch<true, true>(m, f16, dim3(p.grid_x[1]), A, Alo, lda, B, M, N, K, outb, outlo, ldo, p.g[1]);
     if (tail) *tail = p.tail;
     return p.slices;
 }
@@ -1790,9 +1823,10 @@ int ring_plan_check(int dual, int M, int N, int K, long long cap_floats, int all
 // SwiGLU up to kSmallRows rows.
 constexpr int kSmallRows = 64;
 
+// f16: the operands hold fp16 numbers (only the ring kernel has that form: the caller has made sure this GEMM takes it).
 template <bool DUAL>
 static int gemm(const Model &m, const bf16_t *A, const bf16_t *Alo, int lda, const bf16_t *B, int M, int N, int K,
-                bf16_t *outb, bf16_t *outlo, int ldo, PartTail *tail = nullptr) {
+                bf16_t *outb, bf16_t *outlo, int ldo, PartTail *tail = nullptr, bool f16 = false) {
     if (tail) *tail = PartTail{};
     // (the ring kernel addresses its operands with 32-bit byte offsets)
     const bool fits32 = (size_t)M * lda * sizeof(bf16_t) < ((size_t)1 << 32) &&
@@ -1812,7 +1846,7 @@ static int gemm(const Model &m, const bf16_t *A, const bf16_t *Alo, int lda, con
         }
         return sh.splits;
     }
-    if (big) return ring_gemm<DUAL>(m, A, Alo, lda, B, M, N, K, outb, outlo, ldo, tail);
+    if (big) return ring_gemm<DUAL>(m, f16, A, Alo, lda, B, M, N, K, outb, outlo, ldo, tail);
     // (K not a multiple of 64) two-term chunks of at most 32 / 64 rows use 32- / 64-row tiles with two waves: less
     // LDS per block, so more blocks per CU keep more of the weight stream in flight
     const int BM = (Alo && M <= 32) ? 32 : (Alo && M <= 64) ? 64 : 128;
@@ -1862,17 +1896,55 @@ static int gemm(const Model &m, const bf16_t *A, const bf16_t *Alo, int lda, con
 struct PassTerms {
     bf16_t *xn_lo, *attn_lo, *act_lo, *qb_lo;  // where the producers write the low terms (nullptr: not needed)
     bool qkv_two, gu_two;                      // xn_lo feeds the QKV / the gate-up projection
+    bool f16;                                  // fp16 operand mode: single fp16 GEMM inputs, the model's fp16 weights
 };
 static PassTerms pass_terms(const Model &m, int n) {
     const Workspace &w = m.ws;
-    const int terms = n < m.ring_min_rows ? kTermAll : m.long_terms;
+    int terms = n < m.ring_min_rows ? kTermAll : m.long_terms;
     PassTerms t;
+    // fp16 operand mode (a pass that would otherwise pay for two bf16 terms in the ring GEMMs, on a model that has
+    // its fp16 weight copy): the GEMM inputs are single fp16 numbers, only the queries keep two bf16 terms
+    t.f16 = n >= m.ring_min_rows && m.f16_pass;
+    if (t.f16) terms = kTermQuery;
     t.qkv_two = terms & kTermQKV, t.gu_two = terms & kTermGateUp;
     t.xn_lo = (t.qkv_two || t.gu_two) ? w.xn_lo : nullptr;
     t.attn_lo = terms & kTermO ? w.attn_lo : nullptr;
     t.act_lo = terms & kTermDown ? w.act_lo : nullptr;
     t.qb_lo = (terms & kTermQuery) && m.c.head_dim == 128 ? w.qb_lo : nullptr;  // rotated queries (k_flash_long)
     return t;
+}
+
+// ---------------------------------------------------------------------------------------
+// fp16 copy of the projection weights (st_model_attach_f16).  A bf16 number of magnitude in [2^-16, 65504] is an
+// fp16 number too (8 significant bits fit the 11 of a half; below 2^-14 the half is subnormal with spacing 2^-24),
+// smaller ones round to a multiple of 2^-24 (absolute error <= 3e-8), larger ones or NaNs are counted in *bad.
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_bf16_to_f16(const bf16_t *__restrict__ src, bf16_t *__restrict__ dst, size_t n8,
+                                                     int32_t *__restrict__ bad) {
+    int n_bad = 0;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n8; i += (size_t)gridDim.x * 256) {
+        const u32x4 v = reinterpret_cast<const u32x4 *>(src)[i];
+        const float f[8] = {bf16_lo(v.x), bf16_hi(v.x), bf16_lo(v.y), bf16_hi(v.y),
+                            bf16_lo(v.z), bf16_hi(v.z), bf16_lo(v.w), bf16_hi(v.w)};
+#pragma unroll
+        for (int e = 0; e < 8; ++e) n_bad += !(fabsf(f[e]) <= 65504.f);  // too large for a half, or NaN
+        const u32x4 o = {pack_f16x2(f[0], f[1]), pack_f16x2(f[2], f[3]), pack_f16x2(f[4], f[5]), pack_f16x2(f[6], f[7])};
+        reinterpret_cast<u32x4 *>(dst)[i] = o;
+    }
+    if (n_bad) atomicAdd(bad, n_bad);
+}
+void launch_f16_copy(const Model &m, const bf16_t *src, bf16_t *dst, size_t n, int32_t *bad) {
+    const size_t n8 = n / 8;  // every projection matrix has a multiple of 8 elements (K is a multiple of 64)
+    int blocks = (int)((n8 + 255) / 256 < 4096 ? (n8 + 255) / 256 : 4096);
+    hipLaunchKernelGGL(k_bf16_to_f16, dim3(blocks), dim3(256), 0, m.stream, src, dst, n8, bad);
+}
+// The fp16 operand mode runs only in the ring kernel: every projection's K must suit it and its 32-bit offsets.
+bool f16_shape_ok(const st_config &c) {
+    const size_t h = c.hidden, qd = (size_t)c.n_q_heads * c.head_dim, I = c.intermediate;
+    const size_t qkv = (size_t)(c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim, mc = c.max_chunk, lim = (size_t)1 << 32;
+    for (size_t K : {h, qd, I})
+        if (K % kRingBK || K < 2 * kRingBK || mc * K * sizeof(bf16_t) >= lim) return false;
+    return qkv * h * 2 < lim && h * qd * 2 < lim && 2 * I * h * 2 < lim && h * I * 2 < lim;
 }
 
 int flash_row_blocks(const st_config &c, int len) {
@@ -1888,7 +1960,8 @@ struct RaggedPass {
     size_t seq_stride;
 };
 static void launch_flash(const Model &m, const bf16_t *qb, const bf16_t *qb_lo, const bf16_t *kc, const bf16_t *vc,
-                         bf16_t *attn, bf16_t *attn_lo, int n, int pos0, const RaggedPass *ragged = nullptr) {
+                         bf16_t *attn, bf16_t *attn_lo, int n, int pos0, const RaggedPass *ragged = nullptr,
+                         bool f16_out = false) {
     const st_config &c = m.c;
     const int d = c.head_dim, nq = c.n_q_heads, nkv = c.n_kv_heads;
     const Workspace &w = m.ws;
@@ -1930,21 +2003,23 @@ static void launch_flash(const Model &m, const bf16_t *qb, const bf16_t *qb_lo, 
     const size_t seq_stride = ragged ? ragged->seq_stride : 0;
     if (long_chunk && qb_lo)
         hipLaunchKernelGGL((k_flash_long<kLongWaves, true>), fgrid, dim3(64 * kLongWaves), 0, m.stream, qb, qb_lo, kc, vc,
-                           attn, attn_lo, part_o, part_ml, n, pos0, nq, G, c.max_seq, segs, n_seg, seq_stride, n_rows_all);
+                           attn, attn_lo, part_o, part_ml, n, pos0, nq, G, c.max_seq, segs, n_seg, seq_stride, n_rows_all,
+                           (int)f16_out);
     else if (long_chunk)
         hipLaunchKernelGGL((k_flash_long<kLongWaves, false>), fgrid, dim3(64 * kLongWaves), 0, m.stream, qb, qb_lo, kc, vc,
-                           attn, attn_lo, part_o, part_ml, n, pos0, nq, G, c.max_seq, segs, n_seg, seq_stride, n_rows_all);
+                           attn, attn_lo, part_o, part_ml, n, pos0, nq, G, c.max_seq, segs, n_seg, seq_stride, n_rows_all,
+                           (int)f16_out);
     else
         hipLaunchKernelGGL(k_flash_prefill<64>, fgrid, dim3(256), 0, m.stream, qb, kc, vc, attn, attn_lo, part_o,
-                           part_ml, n, pos0, nq, G, c.max_seq, segs, n_seg, seq_stride, n_rows_all);
+                           part_ml, n, pos0, nq, G, c.max_seq, segs, n_seg, seq_stride, n_rows_all, (int)f16_out);
     if (splits > 1) {
         const int n_rows = n_rows_all * nq;
         if (d == 128)
             hipLaunchKernelGGL(k_flash_combine<128>, dim3((n_rows + 1) / 2), dim3(256), 0, m.stream, part_o, part_ml,
-                               splits, n_rows, attn, attn_lo);
+                               splits, n_rows, attn, attn_lo, (int)f16_out);
         else
             hipLaunchKernelGGL(k_flash_combine<64>, dim3((n_rows + 3) / 4), dim3(256), 0, m.stream, part_o, part_ml,
-                               splits, n_rows, attn, attn_lo);
+                               splits, n_rows, attn, attn_lo, (int)f16_out);
     }
 }
 
@@ -1962,30 +2037,34 @@ void launch_prefill_layers(const Model &m, int32_t pos0, int32_t n) {
     for (int l = 0; l < c.n_layers; ++l) {
         size_t lofs = (size_t)l * nkv * c.max_seq * d;
         hipLaunchKernelGGL(k_rmsnorm_rows, dim3(n), dim3(norm_threads(n)), 0, m.stream, w.x, w.qkv, pending, (size_t)n * h,
-                           m.norm_attn[l], w.xn, xn_lo, h, c.rms_eps, pend_tail);
-        int sq = gemm<false>(m, w.xn, t.qkv_two ? xn_lo : nullptr, h, m.wqkv[l], n, qkv, h, nullptr, nullptr, 0, &tq);
+                           m.norm_attn[l], w.xn, xn_lo, h, c.rms_eps, pend_tail, (int)t.f16);
+        int sq = gemm<false>(m, w.xn, t.qkv_two ? xn_lo : nullptr, h, t.f16 ? m.wqkv16[l] : m.wqkv[l], n, qkv, h, nullptr,
+                             nullptr, 0, &tq, t.f16);
         hipLaunchKernelGGL(k_rope_append, dim3(n, ((nq + 2 * nkv) * (d / 8) + 255) / 256), dim3(256), 0, m.stream,
                            w.qkv, sq,
                            (size_t)n * qkv, m.bqkv[l], w.rope, w.qb, qb_lo, m.kcache + lofs, m.vcache + lofs, pos0, nq, nkv,
                            d, c.max_seq, tq);
-        launch_flash(m, w.qb, qb_lo, m.kcache + lofs, m.vcache + lofs, w.attn, attn_lo, n, pos0);
-        int so = gemm<false>(m, w.attn, attn_lo, qd, m.wo[l], n, h, qd, nullptr, nullptr, 0, &to);
+        launch_flash(m, w.qb, qb_lo, m.kcache + lofs, m.vcache + lofs, w.attn, attn_lo, n, pos0, nullptr, t.f16);
+        int so = gemm<false>(m, w.attn, attn_lo, qd, t.f16 ? m.wo16[l] : m.wo[l], n, h, qd, nullptr, nullptr, 0, &to,
+                             t.f16);
         hipLaunchKernelGGL(k_rmsnorm_rows, dim3(n), dim3(norm_threads(n)), 0, m.stream, w.x, w.qkv, so, (size_t)n * h,
-                           m.norm_mlp[l], w.xn, xn_lo, h, c.rms_eps, to);
+                           m.norm_mlp[l], w.xn, xn_lo, h, c.rms_eps, to, (int)t.f16);
         if (n < (h % kRingBK == 0 ? m.ring_min_rows : kSmallRows + 1)) {  // small chunk: gate/up as a plain split-K
                                                                            // GEMM over all 2I rows, SwiGLU in the consumer
             int sg = gemm<false>(m, w.xn, xn_lo, h, m.wgu[l], n, 2 * I, h, nullptr, nullptr, 0);
             hipLaunchKernelGGL(k_swiglu_rows, dim3((I / 4 + 255) / 256, n), dim3(256), 0, m.stream, w.qkv, sg,
                                (size_t)n * 2 * I, I, w.act, w.act_lo);
         } else {
-            gemm<true>(m, w.xn, t.gu_two ? xn_lo : nullptr, h, m.wgu[l], n, I, h, w.act, act_lo, I);
+            gemm<true>(m, w.xn, t.gu_two ? xn_lo : nullptr, h, t.f16 ? m.wgu16[l] : m.wgu[l], n, I, h, w.act, act_lo, I,
+                       nullptr, t.f16);
         }
-        pending = gemm<false>(m, w.act, act_lo, I, m.wdown[l], n, h, I, nullptr, nullptr, 0, &pend_tail);
+        pending = gemm<false>(m, w.act, act_lo, I, t.f16 ? m.wdown16[l] : m.wdown[l], n, h, I, nullptr, nullptr, 0,
+                              &pend_tail, t.f16);
     }
     // the head needs the last row only: fold the last down projection into it
     hipLaunchKernelGGL(k_rmsnorm_rows, dim3(1), dim3(norm_threads(1)), 0, m.stream, w.x + (size_t)(n - 1) * h,
                        w.qkv + (size_t)(n - 1) * h, pending, (size_t)n * h, nullptr, nullptr, nullptr, h, c.rms_eps,
-                       tail_at_row(pend_tail, n - 1, h));
+                       tail_at_row(pend_tail, n - 1, h), 0);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -2123,7 +2202,7 @@ void launch_batch_step(const Model &m, const BatchRows &b, int n, int attn_block
     for (int l = 0; l < c.n_layers; ++l) {
         const size_t lofs = (size_t)l * nkv * c.max_seq * d;
         hipLaunchKernelGGL(k_rmsnorm_rows, dim3(n), dim3(norm_threads(n)), 0, m.stream, w.x, w.qkv, pending, (size_t)n * h,
-                           m.norm_attn[l], w.xn, w.xn_lo, h, c.rms_eps, PartTail{});
+                           m.norm_attn[l], w.xn, w.xn_lo, h, c.rms_eps, PartTail{}, 0);
         const int sq = gemm<false>(m, w.xn, w.xn_lo, h, m.wqkv[l], n, qkv, h, nullptr, nullptr, 0);
         hipLaunchKernelGGL(k_rope_append_rows, dim3(n, nq + 2 * nkv), dim3(d / 2), 0, m.stream, w.qkv, sq,
                            (size_t)n * qkv, m.bqkv[l], w.rope, b.q_rows, (bf16_t *)nullptr, (bf16_t *)nullptr,
@@ -2131,14 +2210,14 @@ void launch_batch_step(const Model &m, const BatchRows &b, int n, int attn_block
         launch_attn_rows(m, l, m.stream, attn_blocks, rows, n, b.q_rows, b.part_ml, b.part_acc, b.o_rows);
         const int so = gemm<false>(m, w.attn, w.attn_lo, qd, m.wo[l], n, h, qd, nullptr, nullptr, 0);
         hipLaunchKernelGGL(k_rmsnorm_rows, dim3(n), dim3(norm_threads(n)), 0, m.stream, w.x, w.qkv, so, (size_t)n * h,
-                           m.norm_mlp[l], w.xn, w.xn_lo, h, c.rms_eps, PartTail{});
+                           m.norm_mlp[l], w.xn, w.xn_lo, h, c.rms_eps, PartTail{}, 0);
         const int sg = gemm<false>(m, w.xn, w.xn_lo, h, m.wgu[l], n, 2 * I, h, nullptr, nullptr, 0);
         hipLaunchKernelGGL(k_swiglu_rows, dim3((I / 4 + 255) / 256, n), dim3(256), 0, m.stream, w.qkv, sg,
                            (size_t)n * 2 * I, I, w.act, w.act_lo);
         pending = gemm<false>(m, w.act, w.act_lo, I, m.wdown[l], n, h, I, nullptr, nullptr, 0);
     }
     hipLaunchKernelGGL(k_rmsnorm_rows, dim3(n), dim3(norm_threads(n)), 0, m.stream, w.x, w.qkv, pending, (size_t)n * h,
-                       m.final_norm, w.xn, w.xn_lo, h, c.rms_eps, PartTail{});
+                       m.final_norm, w.xn, w.xn_lo, h, c.rms_eps, PartTail{}, 0);
     const int sl = gemm<false>(m, w.xn, w.xn_lo, h, m.lm_head, n, c.vocab, h, nullptr, nullptr, 0);
     launch_argmax_rows(m, n, sl, b.logits, b.row_next);
 }
@@ -2179,29 +2258,33 @@ void launch_prefill_varlen(const Model &m, const BatchRows &b, const FlashSeg *s
     for (int l = 0; l < c.n_layers; ++l) {
         const size_t lofs = (size_t)l * nkv * c.max_seq * d;
         hipLaunchKernelGGL(k_rmsnorm_rows, dim3(R), dim3(norm_threads(R)), 0, m.stream, w.x, w.qkv, pending, (size_t)R * h,
-                           m.norm_attn[l], w.xn, xn_lo, h, c.rms_eps, PartTail{});
-        const int sq = gemm<false>(m, w.xn, t.qkv_two ? xn_lo : nullptr, h, m.wqkv[l], R, qkv, h, nullptr, nullptr, 0);
+                           m.norm_attn[l], w.xn, xn_lo, h, c.rms_eps, PartTail{}, (int)t.f16);
+        const int sq = gemm<false>(m, w.xn, t.qkv_two ? xn_lo : nullptr, h, t.f16 ? m.wqkv16[l] : m.wqkv[l], R, qkv, h,
+                                   nullptr, nullptr, 0, nullptr, t.f16);
         hipLaunchKernelGGL(k_rope_append_rows, dim3(R, nq + 2 * nkv), dim3(d / 2), 0, m.stream, w.qkv, sq,
                            (size_t)R * qkv, m.bqkv[l], w.rope, (float *)nullptr, w.qb, qb_lo, m.kcache + lofs,
                            m.vcache + lofs, b.row_pos, b.row_seq, b.seq_stride, nq, nkv, d, c.max_seq);
-        launch_flash(m, w.qb, qb_lo, m.kcache + lofs, m.vcache + lofs, w.attn, attn_lo, 0, 0, &ragged);
-        const int so = gemm<false>(m, w.attn, attn_lo, qd, m.wo[l], R, h, qd, nullptr, nullptr, 0);
+        launch_flash(m, w.qb, qb_lo, m.kcache + lofs, m.vcache + lofs, w.attn, attn_lo, 0, 0, &ragged, t.f16);
+        const int so = gemm<false>(m, w.attn, attn_lo, qd, t.f16 ? m.wo16[l] : m.wo[l], R, h, qd, nullptr, nullptr, 0,
+                                   nullptr, t.f16);
         hipLaunchKernelGGL(k_rmsnorm_rows, dim3(R), dim3(norm_threads(R)), 0, m.stream, w.x, w.qkv, so, (size_t)R * h,
-                           m.norm_mlp[l], w.xn, xn_lo, h, c.rms_eps, PartTail{});
+                           m.norm_mlp[l], w.xn, xn_lo, h, c.rms_eps, PartTail{}, (int)t.f16);
         if (R < (h % kRingBK == 0 ? m.ring_min_rows : kSmallRows + 1)) {
             const int sg = gemm<false>(m, w.xn, xn_lo, h, m.wgu[l], R, 2 * I, h, nullptr, nullptr, 0);
             hipLaunchKernelGGL(k_swiglu_rows, dim3((I / 4 + 255) / 256, R), dim3(256), 0, m.stream, w.qkv, sg,
                                (size_t)R * 2 * I, I, w.act, w.act_lo);
         } else {
-            gemm<true>(m, w.xn, t.gu_two ? xn_lo : nullptr, h, m.wgu[l], R, I, h, w.act, act_lo, I);
+            gemm<true>(m, w.xn, t.gu_two ? xn_lo : nullptr, h, t.f16 ? m.wgu16[l] : m.wgu[l], R, I, h, w.act, act_lo, I,
+                       nullptr, t.f16);
         }
-        pending = gemm<false>(m, w.act, act_lo, I, m.wdown[l], R, h, I, nullptr, nullptr, 0);
+        pending = gemm<false>(m, w.act, act_lo, I, t.f16 ? m.wdown16[l] : m.wdown[l], R, h, I, nullptr, nullptr, 0,
+                              nullptr, t.f16);
     }
     // head on the last row of every segment (their row indices are in b.row_next on entry)
     hipLaunchKernelGGL(k_gather_rows, dim3(n_seg), dim3(256), 0, m.stream, w.x, w.qkv, pending, (size_t)R * h,
                        b.row_next, b.o_rows, h);
     hipLaunchKernelGGL(k_rmsnorm_rows, dim3(n_seg), dim3(norm_threads(n_seg)), 0, m.stream, b.o_rows, (const float *)nullptr, 0,
-                       (size_t)0, m.final_norm, w.xn, w.xn_lo, h, c.rms_eps, PartTail{});
+                       (size_t)0, m.final_norm, w.xn, w.xn_lo, h, c.rms_eps, PartTail{}, 0);
     const int sl = gemm<false>(m, w.xn, w.xn_lo, h, m.lm_head, n_seg, c.vocab, h, nullptr, nullptr, 0);
     launch_argmax_rows(m, n_seg, sl, b.logits, b.row_next);
 }

@@ -16,6 +16,7 @@ enum StateSlot {
     kFired = 2,  // 1 if the trigger rule fired on kTok
     kFed = 3,    // token fed by the step that produced kTok
     kStep = 4,   // running index into the output-token buffer of a chained run
+    kCount = 5,  // scratch counter of set-up kernels (weights an fp16 copy could not hold)
     kStateInts = 16
 };
 

@@ -57,8 +57,10 @@ enum LongTerms { kTermQKV = 1, kTermO = 2, kTermGateUp = 4, kTermDown = 8, kTerm
 constexpr int kDefaultLongTerms = kTermAll;
 // Passes of at least this many rows take the 256 x 256 ring GEMMs, shorter ones the weight-streaming kernel (always
 // two-term).  Measured per layer of the 32B shape on 4096 cached keys, streaming two-term / ring two-term / ring
-// single-term: 129 rows 0.50 / 0.60 / 0.39 ms, 224 rows 0.63 / 0.64 / 0.41 ms, 256 rows 0.69 / 0.64 / 0.41 ms.
-constexpr int kRingMinRows = 241, kRingMinRowsFast = 129;
+// single-term: 129 rows 0.50 / 0.60 / 0.39 ms, 224 rows 0.63 / 0.64 / 0.41 ms, 256 rows 0.69 / 0.64 / 0.41 ms (the
+// fp16 operand mode runs at the single-term figures + 5 %).
+constexpr int kRingMinRows = 241;      // two bf16 terms
+constexpr int kRingMinRowsFast = 129;  // one term: ST_PREFILL_FAST, or the fp16 operand mode
 
 constexpr int kLmBlocks = 1024;   // blocks (and arg-max partials) of the LM-head kernel
 constexpr int kAttnSplits = 128;  // most key ranges one kv head is split into at decode
@@ -92,6 +94,10 @@ struct Model {
     bool graph_failed;               // graphs_off because a capture or instantiation failed (reported, not silent)
     int long_terms;                  // LongTerms mask of the pass being enqueued (see pass_terms in prefill.hip)
     int ring_min_rows;               // passes of at least this many rows take the 256 x 256 ring GEMMs
+    // fp16 copies of the four projection matrices of every layer (st_model_attach_f16), empty until attached
+    std::vector<const bf16_t *> wqkv16, wo16, wgu16, wdown16;
+    bool f16_on;                     // the copies exist
+    bool f16_pass;                   // the pass being enqueued uses them (default precision only)
 };
 
 // Records the thread's error message (st_last_error) and returns `code`.
@@ -132,6 +138,10 @@ int ring_plan_check(int dual, int M, int N, int K, long long cap_floats, int all
                     int *blocks_out, int *ids_out);
 size_t partial_floats(const st_config &c);  // floats of Workspace::qkv (the split-K / split-key partial results)
 hipError_t raise_lds_limits();              // once per process, before the first ring / streaming GEMM launch
+// fp16 operand mode: element-wise copy of n bf16 numbers as fp16 (counts the ones no half can hold in *bad), and
+// whether a model shape can run in that mode
+void launch_f16_copy(const Model &m, const bf16_t *src, bf16_t *dst, size_t n, int32_t *bad);
+bool f16_shape_ok(const st_config &c);
 void launch_prefill_layers(const Model &m, int32_t pos0, int32_t n);
 
 // Device arrays of one batched decode step (n rows = n sequences, each at its own position).

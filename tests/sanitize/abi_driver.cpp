@@ -50,6 +50,16 @@ int main() {
             CHECK(st_batch_query_sizes(&c, 16, &bkv, &bws) == ST_OK && bkv == 16 * kv && bws > ws);
         }
         CHECK(st_batch_query_sizes(&c, 0, &bkv, &bws) == ST_ERANGE && st_batch_query_sizes(&c, 65, &bkv, &bws) == ST_ERANGE);
+        // the fp16 weight copy: as many bytes as the bf16 projection matrices, only where every K is a multiple of 64
+        size_t f16 = 0;
+        const int rc16 = st_query_f16_bytes(&c, &f16);
+        if (c.hidden % 64 == 0 && c.intermediate % 64 == 0 && (c.n_q_heads * c.head_dim) % 64 == 0) {
+            const size_t qd = (size_t)c.n_q_heads * c.head_dim, kvd = (size_t)c.n_kv_heads * c.head_dim, h = c.hidden;
+            CHECK(rc16 == ST_OK && f16 == 2 * (size_t)c.n_layers * ((qd + 2 * kvd) * h + h * qd + 3 * h * (size_t)c.intermediate));
+        } else {
+            CHECK(rc16 == ST_EINVAL);
+        }
+        CHECK(st_query_f16_bytes(&c, nullptr) == ST_EINVAL);
     }
     // rejected shapes
     st_config bad = shapes[0];
@@ -86,6 +96,7 @@ int main() {
     CHECK(st_prefill(nullptr, &tok, 1, &lg, &tok, 0) == ST_EINVAL && st_decode_step(nullptr, 0, &lg, &tok, 0) == ST_EINVAL);
     CHECK(st_decode_greedy(nullptr, 0, 1, &tok, 0) == ST_EINVAL && st_decode_step_timed(nullptr, nullptr, nullptr) == ST_EINVAL);
     CHECK(st_decode_graph_state(nullptr, &n, &n) == ST_EINVAL);
+    CHECK(st_model_attach_f16(nullptr, fake, 256) == ST_EINVAL && st_batch_attach_f16(nullptr, fake, 256) == ST_EINVAL);
     CHECK(st_handoff(nullptr, nullptr, &tok, &n, 1, 1, nullptr, &tok, nullptr, 0) == ST_EINVAL);
     CHECK(st_generate(nullptr, nullptr, nullptr, 0, &tok, 1, 1, 1, &tok, nullptr, nullptr, 0, nullptr) == ST_EINVAL);
     CHECK(st_generate_policy(nullptr, nullptr, nullptr, &tok, 1, 1, &tok, nullptr, nullptr, 0, nullptr) == ST_EINVAL);

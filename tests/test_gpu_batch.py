@@ -276,12 +276,17 @@ def test_ragged_catch_up_of_sixteen_sequences():
     batch.close()
 
 
-@pytest.mark.parametrize("lens,cached", [([40, 130, 7], [90, 20, 300]), ([150, 200], [0, 64])])
-def test_ragged_catch_up_pass_head_dim_128(lens, cached):
+@pytest.mark.parametrize("lens,cached,f16", [([40, 130, 7], [90, 20, 300], False), ([150, 200], [0, 64], False),
+                                             ([40, 130, 7], [90, 20, 300], True)])
+def test_ragged_catch_up_pass_head_dim_128(lens, cached, f16):
     """The same at head_dim 128 (1.5B shape, 2 layers), whose attention kernel is a different one: a pass of 177 rows
-    (two-term queries, streaming GEMMs) and one of 350 rows (256 x 256 tiles)."""
-    print_case("1.5B shape, 2 layers: ragged catch-up of", lens, "tokens onto caches of", cached)
+    (two-term queries, streaming GEMMs -- or, with the fp16 weight copy attached, the ring GEMMs on fp16 operands)
+    and one of 350 rows (256 x 256 tiles)."""
+    print_case("1.5B shape, 2 layers: ragged catch-up of", lens, "tokens onto caches of", cached,
+               "(fp16 operand mode)" if f16 else "")
     cfg, batch, oracles = _setup("qwen1p5b", len(lens), 6, max_seq=512, n_layers=2, gen_device="cuda", max_chunk=512)
+    if f16:
+        batch.attach_f16()
     assert _ragged_against_oracles(cfg, batch, oracles, cached, lens) <= LOGIT_TOL
     batch.close()
 

@@ -260,8 +260,9 @@ def test_long_pass_through_64_layers_of_a_narrow_model():
     """Depth pin: a model as deep as the 32B one (64 layers) but narrow enough for the oracle (hidden 1024, 8 query /
     2 kv heads of 128, intermediate 2816, vocab 4096).  A 300-row pass, the same rows in passes of at most 256, and
     the decode step at the same position all stay within the tolerance of the oracle through the full depth, and
-    the default pass is no further from it than 1.5 times the decode step -- whose only rounding is the bf16 K/V
-    cache -- so what error a long pass has is the cache's, not its own.  The opt-in single-term pass is bounded too."""
+    the default pass (two bf16 terms, and with the fp16 weight copy attached: single fp16 operands) is no further from
+    it than 1.5 times the decode step -- whose only rounding is the bf16 K/V cache -- so what error a long pass has
+    is the cache's, not its own.  The opt-in single-term pass is bounded too."""
     print_case("narrow 64-layer model: 300-row pass (default, single-term, <=256-row passes) and decode at row 300")
     cfg, g, o = make_pair("qwen1p5b", 5, max_seq=340, max_chunk=320, n_layers=64, gen_device="cuda",
                           hidden=1024, n_q_heads=8, n_kv_heads=2, intermediate=2816, vocab=4096, tie_embeddings=0)
@@ -274,8 +275,78 @@ def test_long_pass_through_64_layers_of_a_narrow_model():
     g.truncate(0)
     g.prefill(toks[:299], want_logits=False)
     errs["decode"] = rel_err(g.decode_step(int(toks[299]))[0], ref)
+    g.attach_f16()                                        # the same pass on the fp16 MFMA with fp16 activations
+    g.truncate(0)
+    errs["fp16 operands"] = rel_err(g.prefill(toks)[0], ref)
     print_case(errs)
-    assert max(errs["default"], errs["<=256 rows"], errs["decode"]) <= LOGIT_TOL
-    assert errs["default"] <= 1.5 * errs["decode"]
+    assert max(errs["default"], errs["<=256 rows"], errs["decode"], errs["fp16 operands"]) <= LOGIT_TOL
+    assert errs["default"] <= 1.5 * errs["decode"] and errs["fp16 operands"] <= 1.5 * errs["decode"]
     assert errs["single-term"] <= FAST_TOL
     g.close()
+
+
+@pytest.mark.parametrize("m", [129, 200, 257, 513])
+def test_f16_operand_mode_regime_boundaries(m):
+    """With the fp16 weight copy attached, default passes of 129 rows and more run their GEMMs on the fp16 MFMA
+    (single fp16 activations, queries in two bf16 terms): chunk lengths around the kernel switches, on top of 100
+    cached keys, against the oracle (2 layers); shorter passes and the decode step are unchanged."""
+    print_case(f"1.5B shape, 2 layers, fp16 operand mode: 100 cached + chunk of {m}")
+    cfg, g, o = make_pair("qwen1p5b", 11, max_seq=640, max_chunk=520, n_layers=2, gen_device="cuda")
+    g.attach_f16()
+    prompt = synth.make_prompt(100 + m, cfg["vocab"], 12)
+    assert _teacher_forced(cfg, g, o, prompt, [100, m], 1) <= LOGIT_TOL
+    g.close()
+
+
+def test_f16_operand_mode_at_full_depth_and_tail_tiles():
+    """fp16 operand mode through all 28 layers of the 1.5B shape (300-row pass against the oracle: within the
+    tolerance and within 1.3x of the two-term pass), then detached again (bit-identical to before); and a 4096-row
+    pass of the custom shape that takes every leftover-tile path of the ring GEMM, in fp16."""
+    print_case("1.5B shape, 28 layers: 300-token prompt, two bf16 terms against fp16 operands")
+    cfg, g, o = make_pair("qwen1p5b", 1, max_seq=320, max_chunk=300, gen_device="cuda")
+    toks = synth.make_prompt(300, cfg["vocab"], 21)
+    ref = o.feed(toks)
+    two, _ = g.prefill(toks)
+    g.attach_f16()
+    g.truncate(0)
+    f16, _ = g.prefill(toks)
+    g.attach_f16(False)
+    g.truncate(0)
+    again, _ = g.prefill(toks)
+    print_case("two bf16 terms", rel_err(two, ref), "fp16 operands", rel_err(f16, ref))
+    assert rel_err(f16, ref) <= LOGIT_TOL and rel_err(f16, ref) <= 1.3 * rel_err(two, ref)
+    assert np.array_equal(two, again) and not np.array_equal(two, f16)
+    g.close()
+    o.close()
+    print_case("custom shape (hidden 4288, intermediate 2240): 1 layer, 40 cached + 4096-row chunk, fp16 operands")
+    cfg, g, o = make_pair("qwen1p5b", 31, max_seq=4200, max_chunk=4096, n_layers=1, gen_device="cuda",
+                          hidden=4288, intermediate=2240, n_q_heads=6, n_kv_heads=1, vocab=2048)
+    g.attach_f16()
+    prompt = synth.make_prompt(4136, cfg["vocab"], 32)
+    assert _teacher_forced(cfg, g, o, prompt, [40, 4096], 2) <= LOGIT_TOL
+    g.close()
+
+
+def test_f16_attach_rejects_what_it_cannot_hold():
+    """A weight beyond the fp16 range keeps the mode off (ST_ERANGE, passes stay in two bf16 terms); a shape whose
+    intermediate size is not a multiple of 64 is refused (ST_EINVAL); a short buffer too (ST_ENOMEM)."""
+    cfg = synth.model_config("qwen1p5b", max_seq=400, max_chunk=320, n_layers=1)
+    w = synth.make_weights(cfg, 3, device="cuda")
+    g = B.Model(cfg, w)
+    toks = synth.make_prompt(300, cfg["vocab"], 4)
+    before, _ = g.prefill(toks)
+    w["layers"][0]["w_down"][5, 7] = 1.0e5
+    with pytest.raises(B.StError) as e:
+        g.attach_f16()
+    assert e.value.code == B.ST_ERANGE
+    w["layers"][0]["w_down"][5, 7] = 0.0
+    n = B.C.c_size_t()
+    B._check(B.lib().st_query_f16_bytes(B.C.byref(B.make_config(cfg)), B.C.byref(n)))
+    small = torch.empty(n.value - 256, dtype=torch.uint8, device="cuda")
+    assert B.lib().st_model_attach_f16(g._h, small.data_ptr(), small.numel()) == B.ST_ENOMEM
+    g.truncate(0)
+    after, _ = g.prefill(toks)                            # still the two-term pass (one weight differs: now 0)
+    assert np.isfinite(after).all() and rel_err(after, before) < 0.05
+    g.close()
+    tiny = synth.model_config("tiny_small", max_seq=64, max_chunk=64)
+    assert B.lib().st_query_f16_bytes(B.C.byref(B.make_config(tiny)), B.C.byref(n)) == B.ST_EINVAL
