@@ -142,15 +142,19 @@ def batched_loop(B, synth, cfg_s, w_s, cfg_l, w_l, n_seq=16, n_out=210, n_seg=20
 
 
 def target_model_extras(torch, B, synth, cost, small, sizes=(21, 86, 256, 1024, 4096), loop=True, n_layers=None,
-                        batched=True):
-    """32B-shaped target: decode rate at kv ~ 4k, catch-up prefill on a 4096-token cache, and the loop."""
+                        batched=True, forms=("f16", "two_term", "fast")):
+    """32B-shaped target: decode rate at kv ~ 4k, catch-up prefill on a 4096-token cache, and the loop.  `forms`:
+    which forms of the passes of 129 rows and more are timed (a kernel profile takes one)."""
     cfg = synth.model_config("qwen32b", max_seq=4096 + 4096 + 64, max_chunk=4096, n_layers=n_layers)
     w = synth.make_weights(cfg, 2, device="cuda")
     large = B.Model(cfg, w)
     toks = torch.from_numpy(synth.make_prompt(8192, cfg["vocab"], 5)).cuda()
     out = torch.empty(64, dtype=torch.int32, device="cuda")
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    large.prefill_device(toks[:4096])
+    if forms[0] == "f16":
+        large.attach_f16()
+    large.prefill_device(toks[:4096], fast=(forms[0] == "fast"))   # the cached context, in the first form asked for
+    large.attach_f16(False)
     large.decode_greedy(0, 8, chained=True, out_dev=out)
     e0.record()
     large.decode_greedy(0, 20, chained=True, out_dev=out)
@@ -179,13 +183,20 @@ def target_model_extras(torch, B, synth, cost, small, sizes=(21, 86, 256, 1024, 
     # the logit tolerance against the oracle at every depth tested.
     side = {}
     for m in sizes:
-        if m > 128:
-            side[m] = {"two_term_bf16": timed_pass(m, False), "fast_single_term": timed_pass(m, True)}
-    large.attach_f16()
-    for m in sizes:
-        res["prefill_on_kv4096"][str(m)] = dict(timed_pass(m, False), **side.get(m, {}))
-        res["prefill_on_kv4096"][str(m)]["form"] = "fp16 operands" if m > 128 else "two bf16 terms (streaming kernel)"
-    large.attach_f16(False)
+        side[m] = {}
+        if m > 128 and "two_term" in forms:
+            side[m]["two_term_bf16"] = timed_pass(m, False)
+        if m > 128 and "fast" in forms:
+            side[m]["fast_single_term"] = timed_pass(m, True)
+    if "f16" in forms:
+        large.attach_f16()
+        for m in sizes:
+            res["prefill_on_kv4096"][str(m)] = dict(timed_pass(m, False), **side[m])
+            res["prefill_on_kv4096"][str(m)]["form"] = "fp16 operands" if m > 128 else "two bf16 terms (streaming kernel)"
+        large.attach_f16(False)
+    else:
+        for m in sizes:
+            res["prefill_on_kv4096"][str(m)] = side[m] if m > 128 else dict(timed_pass(m, False))
     large.close()
     del large
     if not batched:
@@ -295,6 +306,8 @@ def main():
     ap.add_argument("--no-extras", action="store_true", help="skip the 32B-shaped model and the two-model loop")
     ap.add_argument("--prefill-sizes", default="21,86,256,1024,4096",
                     help="catch-up chunk lengths timed on the 32B-shaped model (one size for a kernel profile)")
+    ap.add_argument("--prefill-forms", default="f16,two_term,fast",
+                    help="profiling aid: forms of the long passes to time (f16, two_term, fast); the first also fills the cache")
     ap.add_argument("--extras-layers", type=int, default=None,
                     help="profiling aid: give the 32B-shaped model this many layers (per-kernel figures are unchanged)")
     ap.add_argument("--prefill-only", action="store_true",
@@ -316,7 +329,8 @@ def main():
     if args.only_extras:
         print(json.dumps({"target_model_32b": target_model_extras(torch, B, synth, cost, None, sizes, loop=False,
                                                                        n_layers=args.extras_layers,
-                                                                       batched=not args.prefill_only)}))
+                                                                       batched=not args.prefill_only,
+                                                                       forms=tuple(args.prefill_forms.split(",")))}))
         return
     n_dec = args.decode_steps
     cfg = synth.model_config("qwen1p5b", max_seq=max(PROMPT + N_DECODE + 64, 256 + 5000 + 64), max_chunk=PROMPT)

@@ -115,12 +115,12 @@ void st_model_destroy(st_model *m);
  * 65504 is an fp16 number as well.  st_model_attach_f16 copies the four projection matrices of every layer as fp16
  * into `buf` (device memory owned by the caller, 256-byte aligned, st_query_f16_bytes bytes -- as many as the bf16
  * matrices take -- borrowed until st_model_destroy or a detaching call); weights smaller than 2^-16 round to a
- * multiple of 2^-24.  From then on default-precision passes of 129 rows and more run their four GEMMs in the
- * MFMA-bound kernels on the fp16 MFMA, with single fp16 activations instead of two bf16 terms:
+ * multiple of 2^-24.  From then on default-precision passes of every length run their four GEMMs per layer on the
+ * fp16 MFMA, with single fp16 activations instead of two bf16 terms (from 129 rows on in the MFMA-bound kernels):
  * the same MFMA rate as one bf16 term, 11 mantissa bits instead of 8 -- measured against the CPU oracle the pass
  * stays at the decode step's error, at about the speed of ST_PREFILL_FAST.  Activations are normalised rows,
  * attention outputs and SwiGLU products; they saturate at +-65504 when written.  The K/V cache, the queries (two
- * bf16 terms), shorter passes, ST_PREFILL_FAST / ST_PREFILL_TWO_TERM passes and the decode step are unchanged.
+ * bf16 terms), ST_PREFILL_FAST / ST_PREFILL_TWO_TERM passes, the LM head and the decode step are unchanged.
  * buf == NULL detaches.  The call runs on the model's stream and synchronises it.  ST_EINVAL if hidden,
  * n_q_heads*head_dim or intermediate is not a multiple of 64; ST_ENOMEM if `bytes` is too small; ST_ERANGE (mode not
  * enabled) if a weight is NaN or larger than 65504. */

@@ -716,20 +716,25 @@ struct StreamGeom {
     static constexpr int kLpr = kSeg / 16;       // lanes per row in a direct load
     static constexpr int kRpi = 64 / kLpr;       // rows per 1 KB instruction
     static constexpr int kWTile = 32 * kSeg;     // bytes of one 32-row weight tile per stage
-    static constexpr int kATile = 64 * kSeg;     // bytes of one activation tile (32 hi + 32 lo rows) per stage
+    static constexpr int kARows = 32 * kSeg;     // bytes of 32 activation rows per stage (a tile holds one such block
+                                                 // per term: high, low)
     // 16-byte chunk swizzle of LDS row `row` (conflict-free fragment reads)
     __device__ static int swz(int row) { return BK == 32 ? (row >> 2) & 3 : ring_swz(row); }
 };
 
-template <int MT, int BK, bool SPEC>
+// TERMS = 2: activations as two bf16 terms (A + Alo).  TERMS = 1 with F16: single fp16 activations against the
+// model's fp16 copy of the weights on the f16 MFMA (half the activation traffic and half the MFMAs per weight byte).
+template <int MT, int BK, bool SPEC, int TERMS = 2, bool F16 = false>
 __global__ __launch_bounds__(SPEC ? 512 : 256) void k_gemm_stream(const bf16_t *__restrict__ A,
                                                                   const bf16_t *__restrict__ Alo, int lda,
                                                                   const bf16_t *__restrict__ B, int M, int N, int K,
                                                                   int kps, int nt, int nw, int na,
                                                                   float *__restrict__ part) {
     using G = StreamGeom<BK>;
-    constexpr int kAStage = MT * G::kATile;
-    constexpr int kALoads = MT * 64 / G::kRpi / 2;   // activation instructions per stage of each activation wave
+    static_assert(TERMS == 1 || TERMS == 2, "one or two activation terms");
+    constexpr int RT = 32 * TERMS;                   // LDS rows of one activation tile
+    constexpr int kAStage = MT * TERMS * G::kARows;
+    constexpr int kALoads = MT * RT / G::kRpi / 2;   // activation instructions per stage of each activation wave
     constexpr int kWLoadsMax = 8 * 32 / G::kRpi / 2; // weight instructions per stage of each weight wave at nt = 8
     constexpr int NL = kALoads > kWLoadsMax ? kALoads : kWLoadsMax;
     extern __shared__ __align__(16) unsigned char ring[];
@@ -746,7 +751,7 @@ __global__ __launch_bounds__(SPEC ? 512 : 256) void k_gemm_stream(const bf16_t *
     const int lw = SPEC ? (wave - 4) & 3 : wave;  // loader index: 0, 1 weights; 2, 3 activations
 
     // direct loads: a 1 KB instruction fills kRpi LDS rows; lane -> (row lane/kLpr, 16-byte position lane%kLpr
-    // holding global chunk position ^ swz(row)).  Activations: LDS row 64*t + 32*term + r is row 32*t + r of term
+    // holding global chunk position ^ swz(row)).  Activations: LDS row RT*t + 32*term + r is row 32*t + r of term
     // (0 = high, 1 = low); rows past the edge re-read the last valid row and are never stored.
     const bool w_loader = lw < 2;
     const int n_loads = w_loader ? nt * 32 / G::kRpi / 2 : kALoads;
@@ -762,7 +767,7 @@ __global__ __launch_bounds__(SPEC ? 512 : 256) void k_gemm_stream(const bf16_t *
         if (w_loader) {
             pl[i] = B + (size_t)min(n0 + row, N - 1) * K + kbeg + piece;
         } else {
-            const int t = min(row >> 6, MT - 1), term = (row >> 5) & 1, r = row & 31;
+            const int t = min(row / RT, MT - 1), term = (row >> 5) % TERMS, r = row & 31;
             pl[i] = (term ? Alo : A) + (size_t)min(t * 32 + r, M - 1) * lda + kbeg + piece;
         }
         l_off[i] = inst * 1024;
@@ -805,46 +810,52 @@ __global__ __launch_bounds__(SPEC ? 512 : 256) void k_gemm_stream(const bf16_t *
         if (computes) {
             const unsigned char *wb = ring + a_ring + wslot * wstage, *ab = ring + aslot * kAStage;
             // fragments of K step ks + 1 are read while the MFMAs of step ks run: one 16-byte read behind each of the
-            // first MFMAs (read r of a step: 0 the first weight tile, 1 / 2 activation tile 0 high / low, 3 the second
-            // weight tile, then the other activation tiles), pinned there -- issued as one run ahead of the MFMAs
-            // they cost the matrix pipe their issue time
-            bf16x8 wf[2][2], ah[2][MT], al[2][MT];
-            constexpr int NR = 2 + 2 * MT, NM = 4 * MT;  // reads and MFMAs of a 16-wide step (NR <= NM)
+            // first MFMAs, pinned there -- issued as one run ahead of the MFMAs they cost the matrix pipe their issue
+            // time
+            u32x4 wf[2][2], af[2][TERMS][MT];
+            constexpr int NR = 2 + TERMS * MT, NM = 2 * TERMS * MT;  // reads and MFMAs of a 16-wide step
+            // read r of a step: 0 = the first weight tile, 1 .. TERMS = activation tile 0 (high, low), TERMS + 1 = the
+            // second weight tile, then the other activation tiles
             auto frag = [&](auto ks_c, auto r_c) {
                 constexpr int ks = decltype(ks_c)::value, b = ks & 1, r = decltype(r_c)::value;
                 const int c = 2 * ks + kg;
                 if constexpr (r == 0) {
-                    wf[b][0] =
-                        as_bf16x8(*reinterpret_cast<const u32x4 *>(wb + (wave * 32 + l32) * G::kSeg + (c ^ sw_w) * 16));
-                } else if constexpr (r == 3) {
+                    wf[b][0] = *reinterpret_cast<const u32x4 *>(wb + (wave * 32 + l32) * G::kSeg + (c ^ sw_w) * 16);
+                } else if constexpr (r == TERMS + 1) {
                     if (second)
-                        wf[b][1] = as_bf16x8(
-                            *reinterpret_cast<const u32x4 *>(wb + ((wave + 4) * 32 + l32) * G::kSeg + (c ^ sw_w) * 16));
+                        wf[b][1] =
+                            *reinterpret_cast<const u32x4 *>(wb + ((wave + 4) * 32 + l32) * G::kSeg + (c ^ sw_w) * 16);
                 } else {
-                    constexpr int q = r < 3 ? r - 1 : r - 2, t = q >> 1;  // q: 0 / 1 = tile 0 high / low, 2 / 3 = tile 1 ...
-                    if constexpr ((q & 1) == 0)
-                        ah[b][t] = as_bf16x8(
-                            *reinterpret_cast<const u32x4 *>(ab + (t * 64 + l32) * G::kSeg + (c ^ sw_even) * 16));
-                    else
-                        al[b][t] = as_bf16x8(
-                            *reinterpret_cast<const u32x4 *>(ab + (t * 64 + 32 + l32) * G::kSeg + (c ^ sw_odd) * 16));
+                    constexpr int q = r <= TERMS ? r - 1 : r - 2, t = q / TERMS, term = q % TERMS;
+                    constexpr int blk = t * TERMS + term;  // 32-row block of the activation stage
+                    af[b][term][t] = *reinterpret_cast<const u32x4 *>(
+                        ab + (blk * 32 + l32) * G::kSeg + (c ^ ((blk & 1) ? sw_odd : sw_even)) * 16);
                 }
             };
             static_for<NR>([&](auto r_c) { frag(ic<0>{}, r_c); });
             static_for<KS>([&](auto ks_c) {
                 constexpr int ks = decltype(ks_c)::value, b = ks & 1;
                 static_for<NM>([&](auto m_c) {
-                    constexpr int m = decltype(m_c)::value, j = m / (2 * MT), t = (m % (2 * MT)) / 2;
+                    constexpr int m = decltype(m_c)::value, j = m / (TERMS * MT), t = (m % (TERMS * MT)) / TERMS;
+                    constexpr int term = m % TERMS;
                     // a share of this wave's loads for the stage it fills, ahead of each weight tile's MFMAs
-                    if constexpr (m % (2 * MT) == 0)
+                    if constexpr (m % (TERMS * MT) == 0)
                         if (!SPEC && more)
                             static_for<PER>([&](auto q_c) { issue_one(ic<(2 * ks + j) * PER + decltype(q_c)::value>{}); });
-                    if (j == 0 || second)
-                        acc[j][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[b][j], (m & 1) ? al[b][t] : ah[b][t],
-                                                                            acc[j][t], 0, 0, 0);
+                    if (j == 0 || second) {
+                        if constexpr (F16)
+                            acc[j][t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(as_f16x8(wf[b][j]), as_f16x8(af[b][term][t]),
+                                                                               acc[j][t], 0, 0, 0);
+                        else
+                            acc[j][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                                as_bf16x8(wf[b][j]), as_bf16x8(af[b][term][t]), acc[j][t], 0, 0, 0);
+                    }
                     if constexpr (ks + 1 < KS && m < NR) frag(ic<ks + 1>{}, m_c);
                     __builtin_amdgcn_sched_barrier(0);
                 });
+                // (one activation tile in one term has more reads than MFMAs: the rest follow the last MFMA)
+                if constexpr (ks + 1 < KS && NR > NM)
+                    static_for<NR - NM>([&](auto e_c) { frag(ic<ks + 1>{}, ic<NM + decltype(e_c)::value>{}); });
             });
         }
         if (more) issued();
@@ -946,7 +957,8 @@ __global__ __launch_bounds__(256) void k_rope_append(const float *__restrict__ p
 // a[row][i] = silu(gate) * up from the K slices of the gate/up projection of a short chunk
 // (part is [n_part][rows][2I]: gate columns [0,I), up columns [I,2I)), written as two bf16 terms.
 __global__ __launch_bounds__(256) void k_swiglu_rows(const float *__restrict__ part, int n_part, size_t part_stride,
-                                                     int I, bf16_t *__restrict__ act, bf16_t *__restrict__ act_lo) {
+                                                     int I, bf16_t *__restrict__ act, bf16_t *__restrict__ act_lo,
+                                                     int f16) {
     const int row = blockIdx.y;
     const int i4 = blockIdx.x * 256 + threadIdx.x;  // group of four columns
     if (i4 * 4 >= I) return;
@@ -969,6 +981,11 @@ __global__ __launch_bounds__(256) void k_swiglu_rows(const float *__restrict__ p
     }
     const float v0 = gt.x / (1.0f + expf(-gt.x)) * up.x, v1 = gt.y / (1.0f + expf(-gt.y)) * up.y;
     const float v2 = gt.z / (1.0f + expf(-gt.z)) * up.z, v3 = gt.w / (1.0f + expf(-gt.w)) * up.w;
+    if (f16) {  // fp16 operand mode: one fp16 number, no low term
+        const u32x2 h16 = {pack_f16x2(v0, v1), pack_f16x2(v2, v3)};
+        reinterpret_cast<u32x2 *>(act + (size_t)row * I)[i4] = h16;
+        return;
+    }
     u32x2 hi = {pack_bf16x2(v0, v1), pack_bf16x2(v2, v3)};
     u32x2 lo = {pack_bf16x2(v0 - bf16_lo(hi.x), v1 - bf16_hi(hi.x)), pack_bf16x2(v2 - bf16_lo(hi.y), v3 - bf16_hi(hi.y))};
     reinterpret_cast<u32x2 *>(act + (size_t)row * I)[i4] = hi;
@@ -1235,7 +1252,7 @@ __global__ __launch_bounds__(256) void k_flash_prefill(const bf16_t *__restrict_
 // Interface and key-split partial results are those of k_flash_prefill.
 // ---------------------------------------------------------------------------------------
 template <int NW, bool TWO>  // NW waves per block, 32 folded rows each; TWO: queries arrive as two bf16 terms
-__global__ __launch_bounds__(64 * NW, TWO ? 1 : 2) void k_flash_long(const bf16_t *__restrict__ qb,
+__global__ __launch_bounds__(64 * NW, 2) void k_flash_long(const bf16_t *__restrict__ qb,
                                                     const bf16_t *__restrict__ qb_lo, const bf16_t *__restrict__ kc,
                                                     const bf16_t *__restrict__ vc, bf16_t *__restrict__ out,
                                                     bf16_t *__restrict__ outlo, float *__restrict__ part_o,
@@ -1599,6 +1616,8 @@ hipError_t raise_lds_limits() {
     take(raise_one(k_gemm_ring<true, true, false>));
     take(raise_one(k_gemm_ring<false, false, true>)), take(raise_one(k_gemm_ring<true, false, true>));
     take(raise_one(k_gemm_ring<true, true, true>));
+    take(raise_one(k_gemm_stream<1, 64, true, 1, true>)), take(raise_one(k_gemm_stream<2, 64, true, 1, true>));
+    take(raise_one(k_gemm_stream<3, 64, true, 1, true>)), take(raise_one(k_gemm_stream<4, 64, false, 1, true>));
     take(raise_one(k_gemm_stream<1, 64, true>)), take(raise_one(k_gemm_stream<2, 64, true>));
     take(raise_one(k_gemm_stream<3, 64, true>)), take(raise_one(k_gemm_stream<4, 64, false>));
     take(raise_one(k_gemm_stream<5, 32, false>)), take(raise_one(k_gemm_stream<6, 32, false>));
@@ -1611,14 +1630,14 @@ struct StreamShape {
     int bk, nt, splits, kps, nw, na;
 };
 
-template <int MT, int BK>
+template <int MT, int BK, int TERMS = 2, bool F16 = false>
 static void stream_launch(const Model &m, const StreamShape &sh, const bf16_t *A, const bf16_t *Alo, int lda,
                           const bf16_t *B, int M, int N, int K) {
     constexpr bool SPEC = MT <= 3;  // eight waves fit the register file up to three activation tiles (measured: a
                                     // few percent faster there, slower with four)
-    auto kern = k_gemm_stream<MT, BK, SPEC>;
+    auto kern = k_gemm_stream<MT, BK, SPEC, TERMS, F16>;
     using G = StreamGeom<BK>;
-    const int lds = sh.na * MT * G::kATile + sh.nw * sh.nt * G::kWTile;
+    const int lds = sh.na * MT * TERMS * G::kARows + sh.nw * sh.nt * G::kWTile;
     dim3 grid((N + 32 * sh.nt - 1) / (32 * sh.nt), sh.splits);
     hipLaunchKernelGGL(kern, grid, dim3(SPEC ? 512 : 256), lds, m.stream, A, Alo, lda, B, M, N, K, sh.kps, sh.nt, sh.nw,
                        sh.na, m.ws.qkv);
@@ -1630,7 +1649,7 @@ static void stream_launch(const Model &m, const StreamShape &sh, const bf16_t *A
 // M is, and only the tile count per block follows M: a row's sums are then formed in the same order in every batch,
 // so its logits do not depend on which or how many other rows share the step.
 constexpr int kInvariantRows = 64;
-static StreamShape stream_shape(const Model &m, int M, int N, int K) {
+static StreamShape stream_shape(const Model &m, int M, int N, int K, int terms = 2) {
     const int MT = (M + 31) / 32;
     const int bk = MT <= 4 ? 64 : 32, seg = bk * 2, nk = K / bk;
     const int fixed = 640 / seg;  // stages' worth of time a block spends filling its ring and storing its tile
@@ -1648,7 +1667,7 @@ static StreamShape stream_shape(const Model &m, int M, int N, int K) {
                 if (only_steps > 0 && steps != only_steps) continue;
                 const int used = (nk + steps - 1) / steps;  // slices that are not empty
                 const int rounds = (tiles * used + 255) / 256;
-                const double cost = (double)rounds * (steps + fixed) * (nt * 32 + mt * 64) * seg +
+                const double cost = (double)rounds * (steps + fixed) * (nt * 32 + mt * 32 * terms) * seg +
                                     (double)used * cost_rows * N * 8 / 256;
                 if (best_cost < 0 || cost < best_cost) {
                     best_cost = cost;
@@ -1665,7 +1684,7 @@ static StreamShape stream_shape(const Model &m, int M, int N, int K) {
     } else {
         best = search(M, MT, M, 0);
     }
-    const int a_stage = MT * 64 * seg, w_stage = best.nt * 32 * seg;
+    const int a_stage = MT * 32 * terms * seg, w_stage = best.nt * 32 * seg;
     best.na = kRingLds - 3 * a_stage >= 3 * w_stage ? 3 : 2;
     int nw = (kRingLds - best.na * a_stage) / w_stage;
     const int w_loads = best.nt * 32 / (64 / (seg / 16)) / 2;  // per weight wave per stage
@@ -1832,6 +1851,16 @@ static int gemm(const Model &m, const bf16_t *A, const bf16_t *Alo, int lda, con
     const bool fits32 = (size_t)M * lda * sizeof(bf16_t) < ((size_t)1 << 32) &&
                         (size_t)(DUAL ? 2 : 1) * N * K * sizeof(bf16_t) < ((size_t)1 << 32);
     const bool big = M >= m.ring_min_rows && K % kRingBK == 0 && K >= 2 * kRingBK && fits32;
+    if (!big && !DUAL && f16 && M <= 128 && K % kRingBK == 0) {  // fp16 operand mode below the ring threshold
+        const StreamShape sh = stream_shape(m, M, N, K, 1);
+        switch ((M + 31) / 32) {
+            case 1: stream_launch<1, 64, 1, true>(m, sh, A, nullptr, lda, B, M, N, K); break;
+            case 2: stream_launch<2, 64, 1, true>(m, sh, A, nullptr, lda, B, M, N, K); break;
+            case 3: stream_launch<3, 64, 1, true>(m, sh, A, nullptr, lda, B, M, N, K); break;
+            default: stream_launch<4, 64, 1, true>(m, sh, A, nullptr, lda, B, M, N, K); break;
+        }
+        return sh.splits;
+    }
     if (!big && !DUAL && Alo && M <= kSplitRows && K % kRingBK == 0) {
         const StreamShape sh = stream_shape(m, M, N, K);
         switch ((M + 31) / 32) {
@@ -1902,9 +1931,9 @@ static PassTerms pass_terms(const Model &m, int n) {
     const Workspace &w = m.ws;
     int terms = n < m.ring_min_rows ? kTermAll : m.long_terms;
     PassTerms t;
-    // fp16 operand mode (a pass that would otherwise pay for two bf16 terms in the ring GEMMs, on a model that has
-    // its fp16 weight copy): the GEMM inputs are single fp16 numbers, only the queries keep two bf16 terms
-    t.f16 = n >= m.ring_min_rows && m.f16_pass;
+    // fp16 operand mode (default-precision passes of a model that has its fp16 weight copy): the GEMM inputs are
+    // single fp16 numbers at every pass length, only the queries keep two bf16 terms
+    t.f16 = m.f16_pass;
     if (t.f16) terms = kTermQuery;
     t.qkv_two = terms & kTermQKV, t.gu_two = terms & kTermGateUp;
     t.xn_lo = (t.qkv_two || t.gu_two) ? w.xn_lo : nullptr;
@@ -1979,8 +2008,8 @@ static void launch_flash(const Model &m, const bf16_t *qb, const bf16_t *qb_lo, 
         // k_flash_long: the count that minimises (rounds of resident blocks) x (tiles per block + 2 for the set-up
         // and the store) x the time of a tile step, plus the merge pass over the partial results (its bytes at
         // 4 TB/s + a launch).  640 blocks of 42 tiles on 512 slots are two rounds; 960 blocks of 27 are two shorter ones.
-        const int slots = qb_lo ? 256 : 512;        // one block per CU with two-term queries, else two
-        const double step_us = qb_lo ? 2.2 : 1.7;
+        const int slots = 512;                      // two blocks per CU
+        const double step_us = qb_lo ? 2.2 : 1.7;   // a tile step with / without the second term of the queries
         double best = -1;
         // (from two rounds of blocks on, the causal spread of their lengths, longest first, balances the CUs
         // better than splitting does, and the merge pass would cost more than it saves: measured at 4096 rows)
@@ -2051,9 +2080,10 @@ void launch_prefill_layers(const Model &m, int32_t pos0, int32_t n) {
                            m.norm_mlp[l], w.xn, xn_lo, h, c.rms_eps, to, (int)t.f16);
         if (n < (h % kRingBK == 0 ? m.ring_min_rows : kSmallRows + 1)) {  // small chunk: gate/up as a plain split-K
                                                                            // GEMM over all 2I rows, SwiGLU in the consumer
-            int sg = gemm<false>(m, w.xn, xn_lo, h, m.wgu[l], n, 2 * I, h, nullptr, nullptr, 0);
+            int sg = gemm<false>(m, w.xn, xn_lo, h, t.f16 ? m.wgu16[l] : m.wgu[l], n, 2 * I, h, nullptr, nullptr, 0, nullptr,
+                                 t.f16);
             hipLaunchKernelGGL(k_swiglu_rows, dim3((I / 4 + 255) / 256, n), dim3(256), 0, m.stream, w.qkv, sg,
-                               (size_t)n * 2 * I, I, w.act, w.act_lo);
+                               (size_t)n * 2 * I, I, w.act, w.act_lo, (int)t.f16);
         } else {
             gemm<true>(m, w.xn, t.gu_two ? xn_lo : nullptr, h, t.f16 ? m.wgu16[l] : m.wgu[l], n, I, h, w.act, act_lo, I,
                        nullptr, t.f16);
@@ -2213,7 +2243,7 @@ void launch_batch_step(const Model &m, const BatchRows &b, int n, int attn_block
                            m.norm_mlp[l], w.xn, w.xn_lo, h, c.rms_eps, PartTail{}, 0);
         const int sg = gemm<false>(m, w.xn, w.xn_lo, h, m.wgu[l], n, 2 * I, h, nullptr, nullptr, 0);
         hipLaunchKernelGGL(k_swiglu_rows, dim3((I / 4 + 255) / 256, n), dim3(256), 0, m.stream, w.qkv, sg,
-                           (size_t)n * 2 * I, I, w.act, w.act_lo);
+                           (size_t)n * 2 * I, I, w.act, w.act_lo, 0);
         pending = gemm<false>(m, w.act, w.act_lo, I, m.wdown[l], n, h, I, nullptr, nullptr, 0);
     }
     hipLaunchKernelGGL(k_rmsnorm_rows, dim3(n), dim3(norm_threads(n)), 0, m.stream, w.x, w.qkv, pending, (size_t)n * h,
@@ -2270,9 +2300,10 @@ void launch_prefill_varlen(const Model &m, const BatchRows &b, const FlashSeg *s
         hipLaunchKernelGGL(k_rmsnorm_rows, dim3(R), dim3(norm_threads(R)), 0, m.stream, w.x, w.qkv, so, (size_t)R * h,
                            m.norm_mlp[l], w.xn, xn_lo, h, c.rms_eps, PartTail{}, (int)t.f16);
         if (R < (h % kRingBK == 0 ? m.ring_min_rows : kSmallRows + 1)) {
-            const int sg = gemm<false>(m, w.xn, xn_lo, h, m.wgu[l], R, 2 * I, h, nullptr, nullptr, 0);
+            const int sg = gemm<false>(m, w.xn, xn_lo, h, t.f16 ? m.wgu16[l] : m.wgu[l], R, 2 * I, h, nullptr, nullptr, 0,
+                                       nullptr, t.f16);
             hipLaunchKernelGGL(k_swiglu_rows, dim3((I / 4 + 255) / 256, R), dim3(256), 0, m.stream, w.qkv, sg,
-                               (size_t)R * 2 * I, I, w.act, w.act_lo);
+                               (size_t)R * 2 * I, I, w.act, w.act_lo, (int)t.f16);
         } else {
             gemm<true>(m, w.xn, t.gu_two ? xn_lo : nullptr, h, t.f16 ? m.wgu16[l] : m.wgu[l], R, I, h, w.act, act_lo, I,
                        nullptr, t.f16);

@@ -285,11 +285,12 @@ def test_long_pass_through_64_layers_of_a_narrow_model():
     g.close()
 
 
-@pytest.mark.parametrize("m", [129, 200, 257, 513])
+@pytest.mark.parametrize("m", [1, 21, 32, 33, 86, 128, 129, 200, 257, 513])
 def test_f16_operand_mode_regime_boundaries(m):
-    """With the fp16 weight copy attached, default passes of 129 rows and more run their GEMMs on the fp16 MFMA
-    (single fp16 activations, queries in two bf16 terms): chunk lengths around the kernel switches, on top of 100
-    cached keys, against the oracle (2 layers); shorter passes and the decode step are unchanged."""
+    """With the fp16 weight copy attached, default passes run their GEMMs on the fp16 MFMA (single fp16 activations,
+    queries in two bf16 terms) -- in the streaming kernel up to 128 rows, in the ring kernel above: chunk lengths
+    around the kernel switches, on top of 100 cached keys, against the oracle (2 layers); the decode step is
+    unchanged."""
     print_case(f"1.5B shape, 2 layers, fp16 operand mode: 100 cached + chunk of {m}")
     cfg, g, o = make_pair("qwen1p5b", 11, max_seq=640, max_chunk=520, n_layers=2, gen_device="cuda")
     g.attach_f16()
