@@ -114,6 +114,8 @@ def batched_loop(B, synth, cfg_s, w_s, cfg_l, w_l, n_seq=16, n_out=210, n_seg=20
     id % keyword == 0."""
     import numpy as np
     small, large = B.Batch(cfg_s, w_s, n_seq), B.Batch(cfg_l, w_l, n_seq)
+    small.attach_f16()      # catch-up passes on fp16 operands (the decode steps are unchanged)
+    large.attach_f16()
     lens = np.random.default_rng(4).integers(128, 1025, n_seq)
     vocab = cfg_s["vocab"]
     prompts = [synth.make_prompt(int(lens[i]), vocab, 50 + i) for i in range(n_seq)]
@@ -176,27 +178,27 @@ def target_model_extras(torch, B, synth, cost, small, sizes=(21, 86, 256, 1024, 
                 "weight_GB_s": cost.weight_bytes(cfg) / sec / 1e9, "hbm_frac": cost.weight_bytes(cfg) / sec / HBM_PEAK,
                 "bound": "hbm" if m < 312 else "mfma"}
 
-    # Three forms of a pass of 129 rows and more.  The headline entry is the default-precision pass of a model that
-    # has been given the fp16 copy of its projection weights (st_model_attach_f16: fp16 MFMA, single fp16
-    # activations); "two_term_bf16" is the same precision without that copy (two bf16 terms, twice the MFMA work);
-    # "fast_single_term" is ST_PREFILL_FAST (single bf16 inputs, about twice the logit error).  The first two meet
-    # the logit tolerance against the oracle at every depth tested.
+    # Forms of a pass.  The headline entry of every size is the default-precision pass of a model that has been
+    # given the fp16 copy of its projection weights (st_model_attach_f16: fp16 MFMA, single fp16 activations);
+    # "two_term_bf16" is the same precision without that copy (two bf16 terms: twice the MFMA work, which is free
+    # while the weight stream sets the time); "fast_single_term" (129 rows and more) is ST_PREFILL_FAST (single bf16
+    # inputs, about twice the logit error).  The first two meet the logit tolerance against the oracle at every depth
+    # tested.
     side = {}
     for m in sizes:
         side[m] = {}
-        if m > 128 and "two_term" in forms:
+        if "two_term" in forms:
             side[m]["two_term_bf16"] = timed_pass(m, False)
         if m > 128 and "fast" in forms:
             side[m]["fast_single_term"] = timed_pass(m, True)
     if "f16" in forms:
         large.attach_f16()
         for m in sizes:
-            res["prefill_on_kv4096"][str(m)] = dict(timed_pass(m, False), **side[m])
-            res["prefill_on_kv4096"][str(m)]["form"] = "fp16 operands" if m > 128 else "two bf16 terms (streaming kernel)"
+            res["prefill_on_kv4096"][str(m)] = dict(timed_pass(m, False), form="fp16 operands", **side[m])
         large.attach_f16(False)
     else:
         for m in sizes:
-            res["prefill_on_kv4096"][str(m)] = side[m] if m > 128 else dict(timed_pass(m, False))
+            res["prefill_on_kv4096"][str(m)] = side[m]
     large.close()
     del large
     if not batched:
@@ -230,6 +232,7 @@ def target_model_extras(torch, B, synth, cost, small, sizes=(21, 86, 256, 1024, 
     cfg_l = dict(cfg, vocab=vocab, max_seq=5376, max_chunk=256)
     w_l = dict(w, embed=w["embed"][:vocab], lm_head=w["lm_head"][:vocab])
     large = B.Model(cfg_l, w_l)
+    large.attach_f16()      # catch-up passes on fp16 operands (the speculative model got its copy in main())
     small.truncate(0)
     prompt = synth.make_prompt(256, vocab, 7)
     n_out = 1050
@@ -336,6 +339,7 @@ def main():
     cfg = synth.model_config("qwen1p5b", max_seq=max(PROMPT + N_DECODE + 64, 256 + 5000 + 64), max_chunk=PROMPT)
     w = synth.make_weights(cfg, 1, device="cuda")
     model = B.Model(cfg, w)
+    model.attach_f16()      # the prompt pass runs on fp16 operands (default precision); decode is unaffected
     prompt = synth.make_prompt(PROMPT, cfg["vocab"], 3)
     prompt_dev = torch.from_numpy(prompt).cuda()
     out_dev = torch.empty(N_DECODE, dtype=torch.int32, device="cuda")
@@ -345,7 +349,7 @@ def main():
 
     def job():
         model.truncate(0)
-        model.prefill_device(prompt_dev, two_term=True)   # 512 rows as two passes with two-term GEMM inputs
+        model.prefill_device(prompt_dev)                  # one 512-row pass, default precision
         model.decode_greedy(0, n_dec, chained=True, out_dev=out_dev)
         B._check(B.lib().st_trigger_scan(ctypes.byref(rule.c), out_dev.data_ptr(), 0, n_dec, hits_dev[1:].data_ptr(),
                                          64, hits_dev.data_ptr(), None, stream, B.ST_OUT_DEVICE))
@@ -409,7 +413,8 @@ def main():
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "qwen2.5-1.5B-shaped greedy decode: 512-token random prompt prefill + 4096 decode "
                                "steps + trigger scan, batch 1, contiguous bf16 KV cache, seeded random bf16 weights",
-                   "prompt_tokens": PROMPT, "decode_steps": n_dec},
+                   "prompt_tokens": PROMPT, "decode_steps": n_dec,
+                   "prefill_operands": "fp16 MFMA on an fp16 copy of the bf16 projection weights (st_model_attach_f16)"},
         "decode_windows": windows,
         "whole_step_us_ungraphed": float(np.mean(st[8:])),
         "algorithmic_bytes_per_token": {k: cost.decode_bytes(cfg, int(k)) for k in windows},

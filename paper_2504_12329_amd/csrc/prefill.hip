@@ -1732,12 +1732,17 @@ static RingPlan ring_plan(bool dual, int M, int N, int K, size_t cap, bool allow
     } else {
         // One block per CU at a time: pick the K slices that minimise (rounds of 256 blocks) x (K steps per
         // slice + a fixed cost for filling the ring and writing the tile)
+        // Short passes (one or two row tiles) have few tiles, so they may take up to 16 slices; there the partial
+        // sums every slice writes and the consumer reads again (8 bytes per element at ~4 TB/s, in units of a
+        // 1.4 us K step) are part of the price.
         long best = -1;
-        for (int s = 1; s <= 8; ++s) {
+        const int max_s = M <= 512 ? 16 : 8;
+        const double slice_steps = M <= 512 ? (double)M * N * 8 / 4e12 / 1.4e-6 : 0.0;
+        for (int s = 1; s <= max_s; ++s) {
             const int steps = (nk + s - 1) / s;
             if (steps < 4 && s > 1) break;
             if (s > 1 && (size_t)s * M * N > cap) break;
-            const long cost = (long)((tiles * s + 255) / 256) * (steps + 6);
+            const long cost = (long)((tiles * s + 255) / 256) * (steps + 6) + (long)(s * slice_steps);
             if (best < 0 || cost < best) best = cost, gg.S = s;
         }
         gg.kps = (nk + gg.S - 1) / gg.S * kRingBK;
