@@ -12,7 +12,10 @@
  * Conventions
  *  - Every call returns ST_OK (0) or a negative st_status; st_last_error() gives a
  *    thread-local message for the last failure.  All arguments are validated before any
- *    kernel is launched; a failed call leaves the model's KV length unchanged.
+ *    kernel is launched: a call rejected with ST_EINVAL / ST_ENOMEM / ST_ERANGE has changed nothing.  ST_EHIP
+ *    (the HIP runtime failed in the middle of a call) leaves the models involved in an undefined state: destroy them.
+ *    The two-model calls (st_handoff, st_generate*) can also return an error after the first model has already
+ *    advanced; st_kv_len tells where each model stands.
  *  - The library never allocates device memory.  Weights, the KV cache and the workspace
  *    are device buffers owned by the caller and must outlive the model; st_query_sizes
  *    tells how large the KV cache and workspace must be.  Handles are host memory owned by

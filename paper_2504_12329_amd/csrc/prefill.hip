@@ -1564,6 +1564,8 @@ __global__ __launch_bounds__(256) void k_flash_combine(const float *__restrict__
 // ---------------------------------------------------------------------------------------
 constexpr int kLongWaves = 4;  // waves per block of k_flash_long
 
+constexpr int kInvariantRows = 64;  // most rows of a batched decode step (see stream_shape)
+
 // Floats the split-K partial buffer (ws.qkv) holds (the workspace is carved with the same figure).
 size_t partial_floats(const st_config &c) {
     size_t rows = c.max_chunk > 1024 ? c.max_chunk : 1024;
@@ -1571,7 +1573,9 @@ size_t partial_floats(const st_config &c) {
     size_t cols = qkv > (size_t)c.hidden ? qkv : (size_t)c.hidden;
     size_t short_chunk = (size_t)1024 * 2 * c.intermediate;  // gate/up slices of chunks up to 256 rows
     size_t long_chunk = rows * cols + rows * cols / 4;         // one full-width slice + the extra slices of tail columns
-    return long_chunk > short_chunk ? long_chunk : short_chunk;
+    size_t head_rows = (size_t)kInvariantRows * c.vocab;       // LM-head GEMM of a batched step / ragged pass (one slice)
+    size_t need = long_chunk > short_chunk ? long_chunk : short_chunk;
+    return need > head_rows ? need : head_rows;
 }
 
 // Launches one GEMM; returns the number of K slices written to ws.qkv (0 for the fused SwiGLU form).
@@ -1648,7 +1652,6 @@ static void stream_launch(const Model &m, const StreamShape &sh, const bf16_t *A
 // Up to kInvariantRows rows (the most a batched decode step holds) the K slices are those of a 16-row launch whatever
 // M is, and only the tile count per block follows M: a row's sums are then formed in the same order in every batch,
 // so its logits do not depend on which or how many other rows share the step.
-constexpr int kInvariantRows = 64;
 static StreamShape stream_shape(const Model &m, int M, int N, int K, int terms = 2) {
     const int MT = (M + 31) / 32;
     const int bk = MT <= 4 ? 64 : 32, seg = bk * 2, nk = K / bk;
