@@ -114,16 +114,19 @@ int st_model_create(const st_config *cfg, const st_weights *w, void *kv, size_t 
                     void *workspace, size_t workspace_bytes, void *stream, st_model **out);
 void st_model_destroy(st_model *m);
 
-/* fp16 operand mode for long passes.  The weights are bf16 numbers, and a bf16 number of magnitude between 2^-16 and
- * 65504 is an fp16 number as well.  st_model_attach_f16 copies the four projection matrices of every layer as fp16
- * into `buf` (device memory owned by the caller, 256-byte aligned, st_query_f16_bytes bytes -- as many as the bf16
- * matrices take -- borrowed until st_model_destroy or a detaching call); weights smaller than 2^-16 round to a
- * multiple of 2^-24.  From then on default-precision passes of every length run their four GEMMs per layer on the
- * fp16 MFMA, with single fp16 activations instead of two bf16 terms (from 129 rows on in the MFMA-bound kernels):
- * the same MFMA rate as one bf16 term, 11 mantissa bits instead of 8 -- measured against the CPU oracle the pass
- * stays at the decode step's error, at about the speed of ST_PREFILL_FAST.  Activations are normalised rows,
- * attention outputs and SwiGLU products; they saturate at +-65504 when written.  The K/V cache, the queries (two
- * bf16 terms), ST_PREFILL_FAST / ST_PREFILL_TWO_TERM passes, the LM head and the decode step are unchanged.
+/* fp16 operand mode for catch-up passes.  The weights are bf16 numbers, and a bf16 number of magnitude between 2^-16
+ * and 65504 is an fp16 number as well.  st_model_attach_f16 copies the O, gate/up and down projection matrices of
+ * every layer as fp16 into `buf` (device memory owned by the caller, 256-byte aligned, st_query_f16_bytes bytes -- as
+ * many as those bf16 matrices take -- borrowed until st_model_destroy or a detaching call); weights smaller than 2^-16
+ * round to a multiple of 2^-24.  From then on default-precision passes of every length run those three GEMMs per
+ * layer on the fp16 MFMA, with single fp16 activations instead of two bf16 terms (from 129 rows on in the MFMA-bound
+ * kernels): the same MFMA rate as one bf16 term, 11 mantissa bits instead of 8.  The QKV projection keeps its input
+ * in two bf16 terms and the attention its queries: what reaches the attention logits is the one place where 11 bits
+ * showed (through all 64 layers of the 32B shape).  Measured against the CPU oracle, and against the decode step
+ * where the oracle cannot reach, the pass is as close as the two-term pass, at about 1.1x the time of
+ * ST_PREFILL_FAST.  The fp16 activations are normalised rows, attention outputs and SwiGLU products; they saturate
+ * at +-65504 when written.  The K/V cache, ST_PREFILL_FAST / ST_PREFILL_TWO_TERM passes, the LM head and the decode
+ * step are unchanged.
  * buf == NULL detaches.  The call runs on the model's stream and synchronises it.  ST_EINVAL if hidden,
  * n_q_heads*head_dim or intermediate is not a multiple of 64; ST_ENOMEM if `bytes` is too small; ST_ERANGE (mode not
  * enabled) if a weight is NaN or larger than 65504. */

@@ -396,9 +396,9 @@ void st_model_destroy(st_model *h) {
     delete m;
 }
 
-static size_t f16_elems(const st_config &c) {  // elements of one layer's four projection matrices
+static size_t f16_elems(const st_config &c) {  // elements of one layer's O, gate/up and down projection matrices
     const size_t h = c.hidden, qd = (size_t)c.n_q_heads * c.head_dim, I = c.intermediate;
-    return (qd + 2 * (size_t)c.n_kv_heads * c.head_dim) * h + h * qd + 2 * I * h + h * I;
+    return h * qd + 2 * I * h + h * I;
 }
 
 int st_query_f16_bytes(const st_config *cfg, size_t *bytes) {
@@ -412,7 +412,7 @@ int st_query_f16_bytes(const st_config *cfg, size_t *bytes) {
 
 static int attach_f16(Model *m, void *buf, size_t bytes) {
     m->f16_on = m->f16_pass = false;
-    m->wqkv16.clear(), m->wo16.clear(), m->wgu16.clear(), m->wdown16.clear();
+    m->wo16.clear(), m->wgu16.clear(), m->wdown16.clear();
     if (!buf) return ST_OK;  // detach
     const st_config &c = m->c;
     if (!f16_shape_ok(c))
@@ -421,12 +421,11 @@ static int attach_f16(Model *m, void *buf, size_t bytes) {
     if (bytes < need) return fail(ST_ENOMEM, "fp16 weight buffer has %zu bytes, %zu needed", bytes, need);
     if ((uintptr_t)buf & 255) return fail(ST_EINVAL, "the fp16 weight buffer must be 256-byte aligned");
     const size_t h = c.hidden, qd = (size_t)c.n_q_heads * c.head_dim, I = c.intermediate;
-    const size_t n_qkv = (size_t)m->qkv_dim * h, n_o = h * qd, n_gu = 2 * I * h, n_d = h * I;
+    const size_t n_o = h * qd, n_gu = 2 * I * h, n_d = h * I;
     launch_set_state(*m, kCount, 0);
     bf16_t *p = static_cast<bf16_t *>(buf);
     int32_t *bad = m->ws.state + kCount;
     for (int l = 0; l < c.n_layers; ++l) {
-        launch_f16_copy(*m, m->wqkv[l], p, n_qkv, bad), m->wqkv16.push_back(p), p += n_qkv;
         launch_f16_copy(*m, m->wo[l], p, n_o, bad), m->wo16.push_back(p), p += n_o;
         launch_f16_copy(*m, m->wgu[l], p, n_gu, bad), m->wgu16.push_back(p), p += n_gu;
         launch_f16_copy(*m, m->wdown[l], p, n_d, bad), m->wdown16.push_back(p), p += n_d;
@@ -436,7 +435,7 @@ static int attach_f16(Model *m, void *buf, size_t bytes) {
     ST_HIP(hipMemcpyAsync(&n_bad, bad, sizeof(int32_t), hipMemcpyDeviceToHost, m->stream));
     ST_HIP(hipStreamSynchronize(m->stream));
     if (n_bad) {
-        m->wqkv16.clear(), m->wo16.clear(), m->wgu16.clear(), m->wdown16.clear();
+        m->wo16.clear(), m->wgu16.clear(), m->wdown16.clear();
         return fail(ST_ERANGE, "%d weights are NaN or exceed the largest fp16 number: fp16 operand mode not enabled", n_bad);
     }
     m->f16_on = true;

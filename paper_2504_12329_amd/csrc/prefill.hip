@@ -21,9 +21,10 @@ typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef _Float16 f16x2_t __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ f16x8 as_f16x8(u32x4 v) { return __builtin_bit_cast(f16x8, v); }
 // fp32 -> fp16, round to nearest even, saturating at the largest finite half (activations are O(1); the clamp only
-// keeps a stray huge value from becoming an infinity inside a dot product)
+// keeps a stray huge value from becoming an infinity inside a dot product); a NaN stays a NaN
+__device__ __forceinline__ float clamp_f16(float v) { return v != v ? v : fminf(fmaxf(v, -65504.f), 65504.f); }
 __device__ __forceinline__ uint32_t pack_f16x2(float lo, float hi) {
-    lo = fminf(fmaxf(lo, -65504.f), 65504.f), hi = fminf(fmaxf(hi, -65504.f), 65504.f);
+    lo = clamp_f16(lo), hi = clamp_f16(hi);
     const f16x2_t v = {(_Float16)lo, (_Float16)hi};
     return __builtin_bit_cast(uint32_t, v);
 }
@@ -444,13 +445,13 @@ __host__ __device__ inline bool ring_block(const RingGrid &gg, int bid, int M, i
 // HALF (fused SwiGLU form only): the block tile is 256 x (64 gate + 64 up) weight rows -- half the columns, half the
 // MFMAs per fragment of activations -- for the tiles left over after whole rounds of full tiles (one more round of
 // half the length instead of a round that leaves half the chip idle).
-// F16: A and B hold fp16 numbers (single-term activations, the model's fp16 copy of the weights) and the fused
-// epilogue writes fp16.
+// F16: A and B hold fp16 numbers (single-term activations, the model's fp16 copy of the weights).  out_f16: the
+// fused epilogue writes fp16 (one term) instead of bf16 (+ its low term).
 template <bool DUAL, bool HALF = false, bool F16 = false>
 __global__ __launch_bounds__(256) void k_gemm_ring(const bf16_t *__restrict__ A, const bf16_t *__restrict__ Alo, int lda,
                                                    const bf16_t *__restrict__ B, int M, int N, int K,
                                                    float *__restrict__ part, bf16_t *__restrict__ outb,
-                                                   bf16_t *__restrict__ outlo, int ldo, RingGrid gg) {
+                                                   bf16_t *__restrict__ outlo, int ldo, RingGrid gg, int out_f16) {
     extern __shared__ __align__(16) unsigned char ring[];
     RingBlock rb;
     // Two-term activations (Alo != nullptr): the contraction runs over 2K columns, [A | Alo] against [B | B]; K step
@@ -654,14 +655,14 @@ __global__ __launch_bounds__(256) void k_gemm_ring(const bf16_t *__restrict__ A,
                     }
                     const float other = dpp_move<0xB1, 0xf>(0.f, odd ? a[0] : a[1]);  // quad_perm [1,0,3,2]
                     const float x0 = odd ? other : a[0], x1 = odd ? a[1] : other;
-                    const uint32_t pk = F16 ? pack_f16x2(x0, x1) : pack_bf16x2(x0, x1);
+                    const uint32_t pk = out_f16 ? pack_f16x2(x0, x1) : pack_bf16x2(x0, x1);
                     const int row = m0 + wm * 128 + i * 32 + 8 * (r >> 2) + 4 * kg + (r & 3) + (odd ? 1 : 0);
                     const int col = n0 + wn * (NB * 16) + j * 32 + (l32 & ~1);
                     if (row < M && col + 1 < N)
                         *reinterpret_cast<uint32_t *>(outb + (size_t)row * ldo + col) = pk;
                     else if (row < M && col < N)  // an odd width: the last column alone
                         outb[(size_t)row * ldo + col] = (bf16_t)(pk & 0xffffu);
-                    if (!F16 && outlo) {  // second bf16 term of the activation (feeds a two-term down projection)
+                    if (!out_f16 && outlo) {  // second bf16 term of the activation (feeds a two-term down projection)
                         const uint32_t lo = pack_bf16x2(x0 - bf16_lo(pk), x1 - bf16_hi(pk));
                         if (row < M && col + 1 < N)
                             *reinterpret_cast<uint32_t *>(outlo + (size_t)row * ldo + col) = lo;
@@ -1593,14 +1594,14 @@ static void gemm_launch(const Model &m, dim3 grid, const bf16_t *A, const bf16_t
 }
 
 template <bool DUAL, bool HALF = false>
-static void ring_launch(const Model &m, bool f16, dim3 grid, const bf16_t *A, const bf16_t *Alo, int lda,
+static void ring_launch(const Model &m, bool f16, bool out_f16, dim3 grid, const bf16_t *A, const bf16_t *Alo, int lda,
                         const bf16_t *B, int M, int N, int K, bf16_t *outb, bf16_t *outlo, int ldo, const RingGrid &gg) {
     if (f16)
         hipLaunchKernelGGL((k_gemm_ring<DUAL, HALF, true>), grid, dim3(256), kRingLds, m.stream, A, Alo, lda, B, M, N, K,
-                           m.ws.qkv, outb, outlo, ldo, gg);
+                           m.ws.qkv, outb, outlo, ldo, gg, (int)out_f16);
     else
         hipLaunchKernelGGL((k_gemm_ring<DUAL, HALF, false>), grid, dim3(256), kRingLds, m.stream, A, Alo, lda, B, M, N, K,
-                           m.ws.qkv, outb, outlo, ldo, gg);
+                           m.ws.qkv, outb, outlo, ldo, gg, (int)out_f16);
 }
 
 // The ring and streaming kernels use more dynamic LDS than a kernel gets by default; the limit is raised once per
@@ -1784,13 +1785,14 @@ static RingPlan ring_plan(bool dual, int M, int N, int K, size_t cap, bool allow
 
 // Alo != nullptr: two-term activations, the plan covers the doubled contraction [A | Alo] x [B | B].
 template <bool DUAL>
-static int ring_gemm(const Model &m, bool f16, const bf16_t *A, const bf16_t *Alo, int lda, const bf16_t *B, int M, int N,
-                     int K, bf16_t *outb, bf16_t *outlo, int ldo, PartTail *tail) {
+static int ring_gemm(const Model &m, bool f16, bool out_f16, const bf16_t *A, const bf16_t *Alo, int lda, const bf16_t *B,
+                     int M, int N, int K, bf16_t *outb, bf16_t *outlo, int ldo, PartTail *tail) {
     const RingPlan p = ring_plan(DUAL, M, N, Alo ? 2 * K : K, partial_floats(m.c), tail != nullptr);
-    ring_launch<DUAL, false>(m, f16, dim3(p.grid_x[0]), A, Alo, lda, B, M, N, K, outb, outlo, ldo, p.g[0]);
+    ring_launch<DUAL, false>(m, f16, out_f16, dim3(p.grid_x[0]), A, Alo, lda, B, M, N, K, outb, outlo, ldo, p.g[0]);
     if constexpr (DUAL)
         if (p.n == 2)
-            ring_launch<true, true>(m, f16, dim3(p.grid_x[1]), A, Alo, lda, B, M, N, K, outb, outlo, ldo, p.g[1]);
+            ring_launch<true, true>(m, f16, out_f16, dim3(p.grid_x[1]), A, Alo, lda, B, M, N, K, outb, outlo, ldo,
+                                    p.g[1]);
     if (tail) *tail = p.tail;
     return p.slices;
 }
@@ -1853,7 +1855,7 @@ constexpr int kSmallRows = 64;
 // f16: the operands hold fp16 numbers (only the ring kernel has that form: the caller has made sure this GEMM takes it).
 template <bool DUAL>
 static int gemm(const Model &m, const bf16_t *A, const bf16_t *Alo, int lda, const bf16_t *B, int M, int N, int K,
-                bf16_t *outb, bf16_t *outlo, int ldo, PartTail *tail = nullptr, bool f16 = false) {
+                bf16_t *outb, bf16_t *outlo, int ldo, PartTail *tail = nullptr, bool f16 = false, bool out_f16 = false) {
     if (tail) *tail = PartTail{};
     // (the ring kernel addresses its operands with 32-bit byte offsets)
     const bool fits32 = (size_t)M * lda * sizeof(bf16_t) < ((size_t)1 << 32) &&
@@ -1883,7 +1885,7 @@ static int gemm(const Model &m, const bf16_t *A, const bf16_t *Alo, int lda, con
         }
         return sh.splits;
     }
-    if (big) return ring_gemm<DUAL>(m, f16, A, Alo, lda, B, M, N, K, outb, outlo, ldo, tail);
+    if (big) return ring_gemm<DUAL>(m, f16, out_f16, A, Alo, lda, B, M, N, K, outb, outlo, ldo, tail);
     // (K not a multiple of 64) two-term chunks of at most 32 / 64 rows use 32- / 64-row tiles with two waves: less
     // LDS per block, so more blocks per CU keep more of the weight stream in flight
     const int BM = (Alo && M <= 32) ? 32 : (Alo && M <= 64) ? 64 : 128;
@@ -1933,16 +1935,23 @@ static int gemm(const Model &m, const bf16_t *A, const bf16_t *Alo, int lda, con
 struct PassTerms {
     bf16_t *xn_lo, *attn_lo, *act_lo, *qb_lo;  // where the producers write the low terms (nullptr: not needed)
     bool qkv_two, gu_two;                      // xn_lo feeds the QKV / the gate-up projection
-    bool f16;                                  // fp16 operand mode: single fp16 GEMM inputs, the model's fp16 weights
+    // fp16 operand mode: the inputs of the gate/up, O and down projections (normalised rows of the MLP block,
+    // attention output, SwiGLU output) are single fp16 numbers multiplied with the model's fp16 weights
+    bool f16_xg, f16_attn, f16_act;
 };
 static PassTerms pass_terms(const Model &m, int n) {
     const Workspace &w = m.ws;
     int terms = n < m.ring_min_rows ? kTermAll : m.long_terms;
     PassTerms t;
-    // fp16 operand mode (default-precision passes of a model that has its fp16 weight copy): the GEMM inputs are
-    // single fp16 numbers at every pass length, only the queries keep two bf16 terms
-    t.f16 = m.f16_pass;
-    if (t.f16) terms = kTermQuery;
+    // Default-precision passes of a model that has its fp16 weight copy: at every pass length the inputs of the
+    // gate/up, O and down projections are single fp16 numbers.  The input of the QKV projection and the queries keep
+    // two bf16 terms: what reaches the attention logits is exponentiated, and through 64 layers of the 32B shape a
+    // pass with fp16 QKV inputs ended 2.1-2.5e-2 from the decode step where this form ends 1.3-1.6e-2, the same as
+    // two bf16 terms everywhere (fp16 in any of the other three inputs made no difference), for 5 % of the time.
+    t.f16_xg = t.f16_attn = t.f16_act = m.f16_pass;
+    if (t.f16_xg) terms &= ~kTermGateUp;
+    if (t.f16_attn) terms &= ~kTermO;
+    if (t.f16_act) terms &= ~kTermDown;
     t.qkv_two = terms & kTermQKV, t.gu_two = terms & kTermGateUp;
     t.xn_lo = (t.qkv_two || t.gu_two) ? w.xn_lo : nullptr;
     t.attn_lo = terms & kTermO ? w.attn_lo : nullptr;
@@ -2074,30 +2083,29 @@ void launch_prefill_layers(const Model &m, int32_t pos0, int32_t n) {
     for (int l = 0; l < c.n_layers; ++l) {
         size_t lofs = (size_t)l * nkv * c.max_seq * d;
         hipLaunchKernelGGL(k_rmsnorm_rows, dim3(n), dim3(norm_threads(n)), 0, m.stream, w.x, w.qkv, pending, (size_t)n * h,
-                           m.norm_attn[l], w.xn, xn_lo, h, c.rms_eps, pend_tail, (int)t.f16);
-        int sq = gemm<false>(m, w.xn, t.qkv_two ? xn_lo : nullptr, h, t.f16 ? m.wqkv16[l] : m.wqkv[l], n, qkv, h, nullptr,
-                             nullptr, 0, &tq, t.f16);
+                           m.norm_attn[l], w.xn, t.qkv_two ? xn_lo : nullptr, h, c.rms_eps, pend_tail, 0);
+        int sq = gemm<false>(m, w.xn, t.qkv_two ? xn_lo : nullptr, h, m.wqkv[l], n, qkv, h, nullptr, nullptr, 0, &tq);
         hipLaunchKernelGGL(k_rope_append, dim3(n, ((nq + 2 * nkv) * (d / 8) + 255) / 256), dim3(256), 0, m.stream,
                            w.qkv, sq,
                            (size_t)n * qkv, m.bqkv[l], w.rope, w.qb, qb_lo, m.kcache + lofs, m.vcache + lofs, pos0, nq, nkv,
                            d, c.max_seq, tq);
-        launch_flash(m, w.qb, qb_lo, m.kcache + lofs, m.vcache + lofs, w.attn, attn_lo, n, pos0, nullptr, t.f16);
-        int so = gemm<false>(m, w.attn, attn_lo, qd, t.f16 ? m.wo16[l] : m.wo[l], n, h, qd, nullptr, nullptr, 0, &to,
-                             t.f16);
+        launch_flash(m, w.qb, qb_lo, m.kcache + lofs, m.vcache + lofs, w.attn, attn_lo, n, pos0, nullptr, t.f16_attn);
+        int so = gemm<false>(m, w.attn, attn_lo, qd, t.f16_attn ? m.wo16[l] : m.wo[l], n, h, qd, nullptr, nullptr, 0, &to,
+                             t.f16_attn);
         hipLaunchKernelGGL(k_rmsnorm_rows, dim3(n), dim3(norm_threads(n)), 0, m.stream, w.x, w.qkv, so, (size_t)n * h,
-                           m.norm_mlp[l], w.xn, xn_lo, h, c.rms_eps, to, (int)t.f16);
+                           m.norm_mlp[l], w.xn, t.f16_xg ? nullptr : xn_lo, h, c.rms_eps, to, (int)t.f16_xg);
         if (n < (h % kRingBK == 0 ? m.ring_min_rows : kSmallRows + 1)) {  // small chunk: gate/up as a plain split-K
                                                                            // GEMM over all 2I rows, SwiGLU in the consumer
-            int sg = gemm<false>(m, w.xn, xn_lo, h, t.f16 ? m.wgu16[l] : m.wgu[l], n, 2 * I, h, nullptr, nullptr, 0, nullptr,
-                                 t.f16);
+            int sg = gemm<false>(m, w.xn, t.f16_xg ? nullptr : xn_lo, h, t.f16_xg ? m.wgu16[l] : m.wgu[l], n, 2 * I, h,
+                                 nullptr, nullptr, 0, nullptr, t.f16_xg);
             hipLaunchKernelGGL(k_swiglu_rows, dim3((I / 4 + 255) / 256, n), dim3(256), 0, m.stream, w.qkv, sg,
-                               (size_t)n * 2 * I, I, w.act, w.act_lo, (int)t.f16);
+                               (size_t)n * 2 * I, I, w.act, w.act_lo, (int)t.f16_act);
         } else {
-            gemm<true>(m, w.xn, t.gu_two ? xn_lo : nullptr, h, t.f16 ? m.wgu16[l] : m.wgu[l], n, I, h, w.act, act_lo, I,
-                       nullptr, t.f16);
+            gemm<true>(m, w.xn, t.gu_two ? xn_lo : nullptr, h, t.f16_xg ? m.wgu16[l] : m.wgu[l], n, I, h, w.act, act_lo, I,
+                       nullptr, t.f16_xg, t.f16_act);
         }
-        pending = gemm<false>(m, w.act, act_lo, I, t.f16 ? m.wdown16[l] : m.wdown[l], n, h, I, nullptr, nullptr, 0,
-                              &pend_tail, t.f16);
+        pending = gemm<false>(m, w.act, act_lo, I, t.f16_act ? m.wdown16[l] : m.wdown[l], n, h, I, nullptr, nullptr, 0,
+                              &pend_tail, t.f16_act);
     }
     // the head needs the last row only: fold the last down projection into it
     hipLaunchKernelGGL(k_rmsnorm_rows, dim3(1), dim3(norm_threads(1)), 0, m.stream, w.x + (size_t)(n - 1) * h,
@@ -2296,28 +2304,27 @@ void launch_prefill_varlen(const Model &m, const BatchRows &b, const FlashSeg *s
     for (int l = 0; l < c.n_layers; ++l) {
         const size_t lofs = (size_t)l * nkv * c.max_seq * d;
         hipLaunchKernelGGL(k_rmsnorm_rows, dim3(R), dim3(norm_threads(R)), 0, m.stream, w.x, w.qkv, pending, (size_t)R * h,
-                           m.norm_attn[l], w.xn, xn_lo, h, c.rms_eps, PartTail{}, (int)t.f16);
-        const int sq = gemm<false>(m, w.xn, t.qkv_two ? xn_lo : nullptr, h, t.f16 ? m.wqkv16[l] : m.wqkv[l], R, qkv, h,
-                                   nullptr, nullptr, 0, nullptr, t.f16);
+                           m.norm_attn[l], w.xn, t.qkv_two ? xn_lo : nullptr, h, c.rms_eps, PartTail{}, 0);
+        const int sq = gemm<false>(m, w.xn, t.qkv_two ? xn_lo : nullptr, h, m.wqkv[l], R, qkv, h, nullptr, nullptr, 0);
         hipLaunchKernelGGL(k_rope_append_rows, dim3(R, nq + 2 * nkv), dim3(d / 2), 0, m.stream, w.qkv, sq,
                            (size_t)R * qkv, m.bqkv[l], w.rope, (float *)nullptr, w.qb, qb_lo, m.kcache + lofs,
                            m.vcache + lofs, b.row_pos, b.row_seq, b.seq_stride, nq, nkv, d, c.max_seq);
-        launch_flash(m, w.qb, qb_lo, m.kcache + lofs, m.vcache + lofs, w.attn, attn_lo, 0, 0, &ragged, t.f16);
-        const int so = gemm<false>(m, w.attn, attn_lo, qd, t.f16 ? m.wo16[l] : m.wo[l], R, h, qd, nullptr, nullptr, 0,
-                                   nullptr, t.f16);
+        launch_flash(m, w.qb, qb_lo, m.kcache + lofs, m.vcache + lofs, w.attn, attn_lo, 0, 0, &ragged, t.f16_attn);
+        const int so = gemm<false>(m, w.attn, attn_lo, qd, t.f16_attn ? m.wo16[l] : m.wo[l], R, h, qd, nullptr, nullptr, 0,
+                                   nullptr, t.f16_attn);
         hipLaunchKernelGGL(k_rmsnorm_rows, dim3(R), dim3(norm_threads(R)), 0, m.stream, w.x, w.qkv, so, (size_t)R * h,
-                           m.norm_mlp[l], w.xn, xn_lo, h, c.rms_eps, PartTail{}, (int)t.f16);
+                           m.norm_mlp[l], w.xn, t.f16_xg ? nullptr : xn_lo, h, c.rms_eps, PartTail{}, (int)t.f16_xg);
         if (R < (h % kRingBK == 0 ? m.ring_min_rows : kSmallRows + 1)) {
-            const int sg = gemm<false>(m, w.xn, xn_lo, h, t.f16 ? m.wgu16[l] : m.wgu[l], R, 2 * I, h, nullptr, nullptr, 0,
-                                       nullptr, t.f16);
+            const int sg = gemm<false>(m, w.xn, t.f16_xg ? nullptr : xn_lo, h, t.f16_xg ? m.wgu16[l] : m.wgu[l], R, 2 * I, h,
+                                       nullptr, nullptr, 0, nullptr, t.f16_xg);
             hipLaunchKernelGGL(k_swiglu_rows, dim3((I / 4 + 255) / 256, R), dim3(256), 0, m.stream, w.qkv, sg,
-                               (size_t)R * 2 * I, I, w.act, w.act_lo, (int)t.f16);
+                               (size_t)R * 2 * I, I, w.act, w.act_lo, (int)t.f16_act);
         } else {
-            gemm<true>(m, w.xn, t.gu_two ? xn_lo : nullptr, h, t.f16 ? m.wgu16[l] : m.wgu[l], R, I, h, w.act, act_lo, I,
-                       nullptr, t.f16);
+            gemm<true>(m, w.xn, t.gu_two ? xn_lo : nullptr, h, t.f16_xg ? m.wgu16[l] : m.wgu[l], R, I, h, w.act, act_lo, I,
+                       nullptr, t.f16_xg, t.f16_act);
         }
-        pending = gemm<false>(m, w.act, act_lo, I, t.f16 ? m.wdown16[l] : m.wdown[l], R, h, I, nullptr, nullptr, 0,
-                              nullptr, t.f16);
+        pending = gemm<false>(m, w.act, act_lo, I, t.f16_act ? m.wdown16[l] : m.wdown[l], R, h, I, nullptr, nullptr, 0,
+                              nullptr, t.f16_act);
     }
     // head on the last row of every segment (their row indices are in b.row_next on entry)
     hipLaunchKernelGGL(k_gather_rows, dim3(n_seg), dim3(256), 0, m.stream, w.x, w.qkv, pending, (size_t)R * h,

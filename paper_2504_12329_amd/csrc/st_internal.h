@@ -94,8 +94,9 @@ struct Model {
     bool graph_failed;               // graphs_off because a capture or instantiation failed (reported, not silent)
     int long_terms;                  // LongTerms mask of the pass being enqueued (see pass_terms in prefill.hip)
     int ring_min_rows;               // passes of at least this many rows take the 256 x 256 ring GEMMs
-    // fp16 copies of the four projection matrices of every layer (st_model_attach_f16), empty until attached
-    std::vector<const bf16_t *> wqkv16, wo16, wgu16, wdown16;
+    // fp16 copies of the O, gate/up and down projection matrices of every layer (st_model_attach_f16), empty until
+    // attached
+    std::vector<const bf16_t *> wo16, wgu16, wdown16;
     bool f16_on;                     // the copies exist
     bool f16_pass;                   // the pass being enqueued uses them (default precision only)
 };

@@ -50,12 +50,12 @@ int main() {
             CHECK(st_batch_query_sizes(&c, 16, &bkv, &bws) == ST_OK && bkv == 16 * kv && bws > ws);
         }
         CHECK(st_batch_query_sizes(&c, 0, &bkv, &bws) == ST_ERANGE && st_batch_query_sizes(&c, 65, &bkv, &bws) == ST_ERANGE);
-        // the fp16 weight copy: as many bytes as the bf16 projection matrices, only where every K is a multiple of 64
+        // the fp16 weight copy: as many bytes as the bf16 O, gate/up and down matrices, only where every K is a multiple of 64
         size_t f16 = 0;
         const int rc16 = st_query_f16_bytes(&c, &f16);
         if (c.hidden % 64 == 0 && c.intermediate % 64 == 0 && (c.n_q_heads * c.head_dim) % 64 == 0) {
-            const size_t qd = (size_t)c.n_q_heads * c.head_dim, kvd = (size_t)c.n_kv_heads * c.head_dim, h = c.hidden;
-            CHECK(rc16 == ST_OK && f16 == 2 * (size_t)c.n_layers * ((qd + 2 * kvd) * h + h * qd + 3 * h * (size_t)c.intermediate));
+            const size_t qd = (size_t)c.n_q_heads * c.head_dim, h = c.hidden;
+            CHECK(rc16 == ST_OK && f16 == 2 * (size_t)c.n_layers * (h * qd + 3 * h * (size_t)c.intermediate));
         } else {
             CHECK(rc16 == ST_EINVAL);
         }

@@ -279,3 +279,24 @@ def test_trigger_scan_bit_exact(window):
     toks = np.array([3, 64, -1, 5, 1 << 30], np.int32)
     n_, pos = B.st_trigger_scan(small_rule, torch.from_numpy(toks).cuda(), 0, 5, cap=8)
     assert n_ == 2 and pos.tolist() == [0, 3]
+
+
+def test_decode_steps_replay_captured_graphs():
+    """st_decode_graph_state: after a few decode steps the model reports captured step graphs in use (mode 0); the
+    count grows when the context crosses into the next attention-grid bucket."""
+    cfg = synth.model_config("tiny_small", max_seq=256, max_chunk=64)
+    w = synth.make_weights(cfg, 1)
+    wg = dict(embed=w["embed"].cuda(), final_norm=w["final_norm"].cuda(), lm_head=w["lm_head"].cuda(),
+              layers=[{k: v.cuda() for k, v in lw.items()} for lw in w["layers"]])
+    g = B.Model(cfg, wg)
+    assert g.graph_state() == (0, 0)
+    g.prefill(synth.make_prompt(60, cfg["vocab"], 3), want_logits=False)
+    for t in range(3):
+        g.decode_step(t + 1, want_logits=False)            # 61..63 keys: one range
+    n1, mode = g.graph_state()
+    assert mode == 0 and n1 >= 1
+    for t in range(4):
+        g.decode_step(t + 5, want_logits=False)            # 64..67 keys: two ranges, another graph
+    n2, mode = g.graph_state()
+    assert mode == 0 and n2 > n1
+    g.close()
