@@ -58,9 +58,10 @@ enum {
                               close to an fp32 evaluation as the decode step's.  Up to about 240 rows the second
                               term costs no time (the weight stream sets it); longer passes are bound by the MFMA
                               rate and pay twice the MFMA work.  With this flag passes of 129 rows and more take
-                              the MFMA-bound kernels with single bf16 inputs: 1.3x (129 rows) to 1.8x (1024 rows
-                              and more) faster, at about twice the logit error (measured against the CPU oracle:
-                              1.7e-2 against 0.8e-2 through 28 layers of the 1.5B shape).  Excludes
+                              single bf16 inputs: 1.3x (129 rows) to 1.8x (1024 rows and more) faster, at about
+                              twice the logit error at the depths the CPU oracle reaches (1.7e-2 against 0.8e-2
+                              through 28 layers of the 1.5B shape) and more beyond (6.8e-2 from the decode step
+                              through 64 layers of the 32B shape, where the default pass is at 1.3e-2).  Excludes
                               ST_PREFILL_TWO_TERM. */
 };
 
@@ -102,7 +103,7 @@ int st_query_sizes(const st_config *cfg, size_t *kv_bytes, size_t *workspace_byt
  * -- K slices, leftover column tiles, half-width tiles -- and verifies that every output tile and K step is
  * computed by exactly one block and that every partial-sum tile lies inside the workspace st_query_sizes reports.
  * Touches no device.  launches / blocks (may be NULL) receive the GEMM launches and working blocks of one layer
- * (0 for rows <= 128, which take the streaming kernel whatever the precision).  ST_EINVAL with the failing projection in
+ * (0 for rows <= 192, which take the streaming kernel whatever the precision).  ST_EINVAL with the failing projection in
  * st_last_error() if the plan is inconsistent, ST_ERANGE if rows is outside 1..cfg->max_chunk. */
 int st_prefill_plan_check(const st_config *cfg, int32_t rows, int32_t *launches, int32_t *blocks);
 
@@ -119,7 +120,7 @@ void st_model_destroy(st_model *m);
  * every layer as fp16 into `buf` (device memory owned by the caller, 256-byte aligned, st_query_f16_bytes bytes -- as
  * many as those bf16 matrices take -- borrowed until st_model_destroy or a detaching call); weights smaller than 2^-16
  * round to a multiple of 2^-24.  From then on default-precision passes of every length run those three GEMMs per
- * layer on the fp16 MFMA, with single fp16 activations instead of two bf16 terms (from 129 rows on in the MFMA-bound
+ * layer on the fp16 MFMA, with single fp16 activations instead of two bf16 terms (from 193 rows on in the MFMA-bound
  * kernels): the same MFMA rate as one bf16 term, 11 mantissa bits instead of 8.  The QKV projection keeps its input
  * in two bf16 terms and the attention its queries: what reaches the attention logits is the one place where 11 bits
  * showed (through all 64 layers of the 32B shape).  Measured against the CPU oracle, and against the decode step

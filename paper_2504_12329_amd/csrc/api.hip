@@ -286,7 +286,7 @@ int st_prefill_plan_check(const st_config *cfg, int32_t rows, int32_t *launches,
     if (rows <= 0 || rows > cfg->max_chunk) return fail(ST_ERANGE, "rows %d outside 1..max_chunk", rows);
     if (launches) *launches = 0;
     if (blocks) *blocks = 0;
-    if (rows < kRingMinRowsFast) return ST_OK;  // short chunks take the streaming kernel: one tile list, no leftovers
+    if (rows < kRingMinRowsFast) return ST_OK;  // shorter chunks take the streaming kernel: one tile list, no leftovers
     const int h = cfg->hidden, I = cfg->intermediate, qd = cfg->n_q_heads * cfg->head_dim;
     const int qkv = (cfg->n_q_heads + 2 * cfg->n_kv_heads) * cfg->head_dim;
     const long long cap = (long long)partial_floats(*cfg);

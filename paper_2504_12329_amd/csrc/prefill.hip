@@ -1623,6 +1623,12 @@ hipError_t raise_lds_limits() {
     take(raise_one(k_gemm_ring<true, true, true>));
     take(raise_one(k_gemm_stream<1, 64, true, 1, true>)), take(raise_one(k_gemm_stream<2, 64, true, 1, true>));
     take(raise_one(k_gemm_stream<3, 64, true, 1, true>)), take(raise_one(k_gemm_stream<4, 64, false, 1, true>));
+    take(raise_one(k_gemm_stream<5, 64, false, 1, true>)), take(raise_one(k_gemm_stream<6, 64, false, 1, true>));
+    take(raise_one(k_gemm_stream<7, 64, false, 1, true>)), take(raise_one(k_gemm_stream<8, 64, false, 1, true>));
+    take(raise_one(k_gemm_stream<1, 64, true, 1, false>)), take(raise_one(k_gemm_stream<2, 64, true, 1, false>));
+    take(raise_one(k_gemm_stream<3, 64, true, 1, false>)), take(raise_one(k_gemm_stream<4, 64, false, 1, false>));
+    take(raise_one(k_gemm_stream<5, 64, false, 1, false>)), take(raise_one(k_gemm_stream<6, 64, false, 1, false>));
+    take(raise_one(k_gemm_stream<7, 64, false, 1, false>)), take(raise_one(k_gemm_stream<8, 64, false, 1, false>));
     take(raise_one(k_gemm_stream<1, 64, true>)), take(raise_one(k_gemm_stream<2, 64, true>));
     take(raise_one(k_gemm_stream<3, 64, true>)), take(raise_one(k_gemm_stream<4, 64, false>));
     take(raise_one(k_gemm_stream<5, 32, false>)), take(raise_one(k_gemm_stream<6, 32, false>));
@@ -1655,7 +1661,7 @@ static void stream_launch(const Model &m, const StreamShape &sh, const bf16_t *A
 // so its logits do not depend on which or how many other rows share the step.
 static StreamShape stream_shape(const Model &m, int M, int N, int K, int terms = 2) {
     const int MT = (M + 31) / 32;
-    const int bk = MT <= 4 ? 64 : 32, seg = bk * 2, nk = K / bk;
+    const int bk = MT * terms <= 8 ? 64 : 32, seg = bk * 2, nk = K / bk;  // 128-byte row segments while the tiles fit
     const int fixed = 640 / seg;  // stages' worth of time a block spends filling its ring and storing its tile
     const size_t cap = partial_floats(m.c);
     // cheapest (tiles per block, K slices) for cost_rows rows in mt activation tiles; cap_rows rows must fit the
@@ -1861,14 +1867,21 @@ static int gemm(const Model &m, const bf16_t *A, const bf16_t *Alo, int lda, con
     const bool fits32 = (size_t)M * lda * sizeof(bf16_t) < ((size_t)1 << 32) &&
                         (size_t)(DUAL ? 2 : 1) * N * K * sizeof(bf16_t) < ((size_t)1 << 32);
     const bool big = M >= m.ring_min_rows && K % kRingBK == 0 && K >= 2 * kRingBK && fits32;
-    if (!big && !DUAL && f16 && M <= 128 && K % kRingBK == 0) {  // fp16 operand mode below the ring threshold
+    if (!big && !DUAL && !Alo && M <= kSplitRows && K % kRingBK == 0) {
+        // one activation term below the ring threshold: fp16 operands, or single bf16 (ST_PREFILL_FAST)
         const StreamShape sh = stream_shape(m, M, N, K, 1);
+#define ST_STREAM1(MTV)                                                                   \
+    case MTV:                                                                             \
+        if (f16)                                                                          \
+            stream_launch<MTV, 64, 1, true>(m, sh, A, nullptr, lda, B, M, N, K);          \
+        else                                                                              \
+            stream_launch<MTV, 64, 1, false>(m, sh, A, nullptr, lda, B, M, N, K);         \
+        break;
         switch ((M + 31) / 32) {
-            case 1: stream_launch<1, 64, 1, true>(m, sh, A, nullptr, lda, B, M, N, K); break;
-            case 2: stream_launch<2, 64, 1, true>(m, sh, A, nullptr, lda, B, M, N, K); break;
-            case 3: stream_launch<3, 64, 1, true>(m, sh, A, nullptr, lda, B, M, N, K); break;
-            default: stream_launch<4, 64, 1, true>(m, sh, A, nullptr, lda, B, M, N, K); break;
+            ST_STREAM1(1) ST_STREAM1(2) ST_STREAM1(3) ST_STREAM1(4) ST_STREAM1(5) ST_STREAM1(6) ST_STREAM1(7)
+            default: ST_STREAM1(8)
         }
+#undef ST_STREAM1
         return sh.splits;
     }
     if (!big && !DUAL && Alo && M <= kSplitRows && K % kRingBK == 0) {
@@ -1941,7 +1954,7 @@ struct PassTerms {
 };
 static PassTerms pass_terms(const Model &m, int n) {
     const Workspace &w = m.ws;
-    int terms = n < m.ring_min_rows ? kTermAll : m.long_terms;
+    int terms = n <= 128 ? kTermAll : m.long_terms;  // up to 128 rows the second term is free in every mode
     PassTerms t;
     // Default-precision passes of a model that has its fp16 weight copy: at every pass length the inputs of the
     // gate/up, O and down projections are single fp16 numbers.  The input of the QKV projection and the queries keep

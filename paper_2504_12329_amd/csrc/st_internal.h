@@ -55,12 +55,12 @@ struct AttnRows {
 // the four projections and the rotated queries of the attention
 enum LongTerms { kTermQKV = 1, kTermO = 2, kTermGateUp = 4, kTermDown = 8, kTermQuery = 16, kTermAll = 31 };
 constexpr int kDefaultLongTerms = kTermAll;
-// Passes of at least this many rows take the 256 x 256 ring GEMMs, shorter ones the weight-streaming kernel (always
-// two-term).  Measured per layer of the 32B shape on 4096 cached keys, streaming two-term / ring two-term / ring
-// single-term: 129 rows 0.50 / 0.60 / 0.39 ms, 224 rows 0.63 / 0.64 / 0.41 ms, 256 rows 0.69 / 0.64 / 0.41 ms (the
-// fp16 operand mode runs at the single-term figures + 5 %).
+// Passes of at least this many rows take the 256 x 256 ring GEMMs, shorter ones the weight-streaming kernel.  Measured
+// per layer of the 32B shape on 4096 cached keys, streaming against ring kernel -- two bf16 terms: 129 rows 0.50 / 0.60,
+// 224 rows 0.63 / 0.64, 256 rows 0.69 / 0.64 ms; one term (fp16 operands): 129 rows 0.36 / 0.40, 160 rows 0.38 / 0.41,
+// 192 rows 0.41 / 0.42, 224 rows 0.47 / 0.43, 256 rows 0.50 / 0.44 ms (single bf16: 0.02-0.03 ms less on both sides).
 constexpr int kRingMinRows = 241;      // two bf16 terms
-constexpr int kRingMinRowsFast = 129;  // one term: ST_PREFILL_FAST, or the fp16 operand mode
+constexpr int kRingMinRowsFast = 193;  // one term: ST_PREFILL_FAST, or the fp16 operand mode
 
 constexpr int kLmBlocks = 1024;   // blocks (and arg-max partials) of the LM-head kernel
 constexpr int kAttnSplits = 128;  // most key ranges one kv head is split into at decode

@@ -112,7 +112,7 @@ def test_long_chunk_launch_plan_covers_every_tile_once(L):
     for name in synth.SHAPES:
         cfg = synth.model_config(name, max_seq=8448, max_chunk=8192)
         h, I = cfg["hidden"], cfg["intermediate"]
-        for rows in (129, 200, 256, 257, 300, 511, 512, 513, 1000, 1024, 2047, 2048, 3000, 4095, 4096, 5000, 8192):
+        for rows in (193, 200, 256, 257, 300, 511, 512, 513, 1000, 1024, 2047, 2048, 3000, 4095, 4096, 5000, 8192):
             launches, blocks = B.st_prefill_plan_check(cfg, rows)
             my = (rows + 255) // 256
             qd = cfg["n_q_heads"] * cfg["head_dim"]
@@ -127,7 +127,7 @@ def test_long_chunk_launch_plan_covers_every_tile_once(L):
         launches, blocks = B.st_prefill_plan_check(cfg, rows)
         seen_tail |= rows == 4096 and launches == 5
     assert seen_two_launches and seen_tail
-    assert B.st_prefill_plan_check(cfg, 128) == (0, 0) and B.st_prefill_plan_check(cfg, 1) == (0, 0)
+    assert B.st_prefill_plan_check(cfg, 192) == (0, 0) and B.st_prefill_plan_check(cfg, 1) == (0, 0)
     with pytest.raises(B.StError):
         B.st_prefill_plan_check(cfg, 4097)
     with pytest.raises(B.StError):
@@ -145,7 +145,7 @@ def test_long_chunk_launch_plan_on_random_shapes(L):
         cfg = synth.model_config("qwen1p5b", max_seq=mc + 64, max_chunk=mc)
         cfg.update(hidden=64 * rng.randint(2, 128), intermediate=8 * rng.randint(16, 3599), n_q_heads=nkv * grp,
                    n_kv_heads=nkv, head_dim=d, vocab=1024, tie_embeddings=0)
-        for rows in {129, 257, mc, rng.randint(129, mc)}:
+        for rows in {193, 257, mc, rng.randint(193, mc)}:
             B.st_prefill_plan_check(cfg, rows)   # raises StError naming the projection if a plan is inconsistent
 
 

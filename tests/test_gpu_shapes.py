@@ -108,11 +108,12 @@ def test_split_attention_matches_oracle_over_many_ranges():
 
 @pytest.mark.parametrize("m,fast", [(32, False), (33, False), (64, False), (65, False), (128, False), (129, False),
                                     (200, False), (256, False), (257, False), (512, False), (513, False),
-                                    (257, True), (513, True)])
+                                    (129, True), (192, True), (193, True), (257, True), (513, True)])
 def test_prefill_kernel_regime_boundaries(m, fast):
     """Chunk lengths on both sides of every kernel switch (one more 32-row activation tile, 128- to 64-byte row
-    segments above 128 rows, the streaming kernel up to 256 rows, 256x256 tiles above -- with two-term inputs by
-    default and with single bf16 inputs on request), on top of 100 cached keys, against the oracle (2 layers)."""
+    segments above 128 rows, the streaming kernel up to 240 rows, 256x256 tiles above -- with two-term inputs by
+    default; with single bf16 inputs on request: one-term streaming kernel from 129 rows, tiles from 193), on top of
+    100 cached keys, against the oracle (2 layers)."""
     print_case(f"1.5B shape, 2 layers: 100 cached + chunk of {m}" + (" (single-term inputs)" if fast else ""))
     cfg, g, o = make_pair("qwen1p5b", 11, max_seq=640, max_chunk=520, n_layers=2, gen_device="cuda")
     prompt = synth.make_prompt(100 + m, cfg["vocab"], 12)
@@ -308,7 +309,7 @@ def test_long_pass_through_64_layers_of_a_narrow_model():
     g.close()
 
 
-@pytest.mark.parametrize("m", [1, 21, 32, 33, 86, 128, 129, 200, 257, 513])
+@pytest.mark.parametrize("m", [1, 21, 32, 33, 86, 128, 129, 160, 192, 193, 257, 513])
 def test_f16_operand_mode_regime_boundaries(m):
     """With the fp16 weight copy attached, default passes run their O, gate/up and down GEMMs on the fp16 MFMA (single
     fp16 activations; the QKV input and the queries stay in two bf16 terms) -- in the streaming kernel up to 128 rows,
