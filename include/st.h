@@ -136,7 +136,8 @@ int st_model_attach_f16(st_model *m, void *buf, size_t bytes);
 
 /* Number of positions whose keys/values are cached. */
 int st_kv_len(const st_model *m, int32_t *out);
-/* O(1) rollback to a shorter context (0 <= new_len <= kv_len), ST_ERANGE otherwise. */
+/* O(1) rollback to a shorter context (0 <= new_len <= kv_len), ST_ERANGE otherwise.  Also clears the condition left
+ * by a single-kernel decode step that gave up waiting (st_decode_step_kind). */
 int st_kv_truncate(st_model *m, int32_t new_len);
 
 /* The prefix / catch-up pass (paper Section 4, "prefix" stage of Table 3 and Eq. 1): feeds
@@ -161,6 +162,18 @@ int st_decode_step(st_model *m, int32_t token, float *logits, int32_t *next_tok,
  * failed -- the HIP message was left in st_last_error() by the call that hit it -- and every step since has been
  * launched kernel by kernel (same results, about a tenth slower).  ST_EINVAL if m is NULL. */
 int st_decode_graph_state(const st_model *m, int32_t *graphs, int32_t *mode);
+
+/* Which form of the decode step (paper Section 4, "decode" stage) the model runs.  *kind: 0 = one kernel per stage
+ * (the default); 1 = the whole step is one persistent kernel, one block per compute unit, whose stages hand their
+ * vectors over through {value, epoch} words in the workspace.  The persistent form is chosen at st_model_create when
+ * ST_DECODE_PERSIST=1 is in the environment and the shape fits it (every row length at least 256, its LDS plan within
+ * 160 KB); it is kept as a measured alternative -- 5-10 % slower than the default on the 1.5B / 7B / 32B shapes.
+ * Both forms meet the same tolerance; their sums are ordered differently, so logits differ in the last bits.  The
+ * persistent form needs all its blocks resident at once: while a step runs, other work on the GPU that occupies
+ * compute units for long delays it, and if a wait inside it exceeds its limit (ST_PERSIST_SPIN polling rounds,
+ * default 2^20, about a second) the step gives up and the next call that reads results back returns ST_EHIP.
+ * ST_EINVAL if m or kind is NULL. */
+int st_decode_step_kind(const st_model *m, int32_t *kind);
 
 /* n chained greedy decode steps: feeds first_token (or the model's own last greedy token when
  * ST_TOKEN_CHAINED is set), then each step's arg-max, writing the n produced tokens to

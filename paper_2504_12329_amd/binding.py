@@ -17,7 +17,7 @@ ST_OK, ST_EINVAL, ST_ENOMEM, ST_ERANGE, ST_EHIP = 0, -1, -2, -3, -4
 ST_TOKENS_DEVICE, ST_OUT_DEVICE, ST_TOKEN_CHAINED, ST_PREFILL_TWO_TERM, ST_PREFILL_FAST = 1, 2, 4, 8, 16
 
 EXPORTS = ("st_query_sizes", "st_prefill_plan_check", "st_model_create", "st_model_destroy", "st_kv_len", "st_kv_truncate", "st_prefill",
-           "st_query_f16_bytes", "st_model_attach_f16", "st_batch_attach_f16", "st_decode_step", "st_decode_graph_state", "st_decode_step_timed", "st_decode_greedy", "st_trigger_scan", "st_trigger_scan_static", "st_handoff", "st_generate",
+           "st_query_f16_bytes", "st_model_attach_f16", "st_batch_attach_f16", "st_decode_step", "st_decode_graph_state", "st_decode_step_kind", "st_decode_step_timed", "st_decode_greedy", "st_trigger_scan", "st_trigger_scan_static", "st_handoff", "st_generate",
            "st_generate_policy", "st_batch_query_sizes", "st_batch_create", "st_batch_destroy", "st_batch_kv_len",
            "st_batch_truncate", "st_batch_prefill", "st_batch_prefill_many", "st_batch_decode_step", "st_generate_batch",
            "st_last_error")
@@ -85,6 +85,7 @@ def lib():
         L.st_decode_step.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_uint32]
         L.st_decode_step_timed.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_double)]
         L.st_decode_graph_state.argtypes = [C.c_void_p, i32p, i32p]
+        L.st_decode_step_kind.argtypes = [C.c_void_p, i32p]
         L.st_query_f16_bytes.argtypes = [C.POINTER(st_config), C.POINTER(C.c_size_t)]
         L.st_model_attach_f16.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t]
         L.st_batch_attach_f16.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t]
@@ -269,6 +270,12 @@ class Model:
         n, mode = C.c_int32(), C.c_int32()
         _check(lib().st_decode_graph_state(self._h, C.byref(n), C.byref(mode)))
         return n.value, mode.value
+
+    def step_kind(self):
+        """1 = the decode step is one persistent kernel, 0 = one kernel per stage."""
+        k = C.c_int32()
+        _check(lib().st_decode_step_kind(self._h, C.byref(k)))
+        return k.value
 
     def decode_step_timed(self):
         """One chained step with per-launch events; returns (mean gate/up kernel us, whole step us)."""

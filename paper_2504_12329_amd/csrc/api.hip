@@ -59,6 +59,20 @@ static size_t kv_bytes_of(const st_config &c) {
     return (size_t)2 * c.n_layers * c.n_kv_heads * (size_t)c.max_seq * c.head_dim * sizeof(bf16_t);
 }
 
+int persist_cu_count() {
+    static std::once_flag once;
+    static int n_cu = 0;
+    std::call_once(once, [] {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess)
+            n_cu = n;
+        else
+            (void)hipGetLastError();
+    });
+    return n_cu;
+}
+
 void carve_workspace(const st_config &c, char *base, Workspace *ws) {
     size_t off = 0;
     auto take = [&](size_t bytes) {
@@ -91,6 +105,11 @@ void carve_workspace(const st_config &c, char *base, Workspace *ws) {
     ws->logits = (float *)take(sizeof(float) * (size_t)c.vocab);
     ws->amax_val = (float *)take(sizeof(float) * kLmBlocks);
     ws->amax_idx = (int32_t *)take(sizeof(int32_t) * kLmBlocks);
+    PersistPlan plan;
+    const bool planned = persist_plan(c, persist_cu_count(), &plan);
+    ws->ll = (unsigned long long *)take(planned ? sizeof(unsigned long long) * plan.ll_words : 0);
+    ws->ptab = (PersistLayer *)take(planned ? sizeof(PersistLayer) * (size_t)c.n_layers : 0);
+    ws->pargs = (PersistArgs *)take(planned ? sizeof(PersistArgs) : 0);
     ws->bytes = off;
 }
 
@@ -139,7 +158,8 @@ static hipGraphExec_t step_graph(Model *m, const st_trigger_rule *rule, int32_t 
     if (m->graphs_off || m->timers) return nullptr;
     const void *kw = rule ? rule->kw_bitmap : nullptr, *dl = rule ? rule->delim_bitmap : nullptr;
     int window = rule ? rule->window : 0, vocab = rule ? rule->vocab : 0;
-    const int bucket = attn_bucket(m->kv_len + 1);
+    // the single-kernel step sizes its attention split on the device: one graph serves every context length
+    const int bucket = m->persist_on ? 0 : attn_bucket(m->kv_len + 1);
     for (const StepGraph &g : m->graphs)
         if (g.kw == kw && g.delim == dl && g.out_seq == out_seq_dev && g.window == window && g.vocab == vocab &&
             g.attn_blocks == bucket)
@@ -182,6 +202,10 @@ static hipGraphExec_t step_graph(Model *m, const st_trigger_rule *rule, int32_t 
 static int decode_impl(Model *m, const st_trigger_rule *rule, int32_t *out_seq_dev) {
     if (m->kv_len + 1 > m->c.max_seq)
         return fail(ST_ERANGE, "KV overflow: kv_len %d + 1 > max_seq %d", m->kv_len, m->c.max_seq);
+    if (m->persist_on && ++m->persist_launches >= (1L << 24)) {  // long before the 32-bit epochs could repeat
+        launch_persist_reset(*m);
+        m->persist_launches = 0;
+    }
     if (hipGraphExec_t exec = step_graph(m, rule, out_seq_dev)) {
         ST_HIP(hipGraphLaunch(exec, m->stream));
     } else {
@@ -192,22 +216,35 @@ static int decode_impl(Model *m, const st_trigger_rule *rule, int32_t *out_seq_d
     return ST_OK;
 }
 
+static int persist_failed() {
+    return fail(ST_EHIP, "a wait inside the single-kernel decode step timed out (another kernel holding compute units "
+                         "for too long, or a lost block); results since the last successful call are invalid");
+}
+
 // Copies logits / greedy token out; host destinations synchronise the stream.
 static int deliver(Model *m, float *logits, int32_t *next_tok, bool out_dev) {
     hipMemcpyKind kind = out_dev ? hipMemcpyDeviceToDevice : hipMemcpyDeviceToHost;
     if (logits) ST_HIP(hipMemcpyAsync(logits, m->ws.logits, sizeof(float) * (size_t)m->c.vocab, kind, m->stream));
     if (next_tok) ST_HIP(hipMemcpyAsync(next_tok, m->ws.state + kTok, sizeof(int32_t), kind, m->stream));
-    if (!out_dev) ST_HIP(hipStreamSynchronize(m->stream));
+    if (!out_dev) {
+        int32_t perr = 0;
+        if (m->persist_on)
+            ST_HIP(hipMemcpyAsync(&perr, m->ws.state + kPersistErr, sizeof(int32_t), hipMemcpyDeviceToHost, m->stream));
+        ST_HIP(hipStreamSynchronize(m->stream));
+        if (perr) return persist_failed();
+    }
     return ST_OK;
 }
 
 // Reads (greedy token, fired) back to the host.
 static int fetch_token(Model *m, int32_t *tok, int32_t *fired) {
-    int32_t two[2];
-    ST_HIP(hipMemcpyAsync(two, m->ws.state + kTok, sizeof(two), hipMemcpyDeviceToHost, m->stream));
+    int32_t st[kPersistErr + 1];
+    static_assert(kTok == 1 && kFired == 2, "slots read back together");
+    ST_HIP(hipMemcpyAsync(st, m->ws.state, sizeof(st), hipMemcpyDeviceToHost, m->stream));
     ST_HIP(hipStreamSynchronize(m->stream));
-    *tok = two[0];
-    if (fired) *fired = two[1];
+    if (m->persist_on && st[kPersistErr]) return persist_failed();
+    *tok = st[kTok];
+    if (fired) *fired = st[kFired];
     return ST_OK;
 }
 
@@ -364,7 +401,30 @@ static int build_model(const st_config *cfg, const st_weights *w, void *kv, void
     std::call_once(lds_once, [] { lds_rc = raise_lds_limits(); });
     if (lds_rc != hipSuccess) return fail(ST_EHIP, "raising the kernels' LDS limit: %s", hipGetErrorString(lds_rc));
     launch_init(*m);
-    return check_launch("workspace initialisation");
+    if (int rc = check_launch("workspace initialisation")) return rc;
+    // the single-kernel decode step: on request (ST_DECODE_PERSIST=1), where the shape fits it.  Measured on the
+    // 1.5B / 7B / 32B shapes it is 5-10 % slower than the kernel-per-stage step, so it is not the default.
+    m->persist_on = false;
+    m->persist_launches = 0;
+    const char *pe = getenv("ST_DECODE_PERSIST");
+    if (pe && pe[0] == '1' && persist_plan(*cfg, persist_cu_count(), &m->persist)) {
+        const char *sl = getenv("ST_PERSIST_SPIN");
+        m->persist_spin_limit = sl ? atoi(sl) : (1 << 20);
+        if (m->persist_spin_limit < 1) m->persist_spin_limit = 1;
+        m->ptab_host.resize(cfg->n_layers);
+        for (int l = 0; l < cfg->n_layers; ++l)
+            m->ptab_host[l] = PersistLayer{m->wqkv[l], m->bqkv[l], m->wo[l], m->wgu[l], m->wdown[l], m->norm_attn[l],
+                                           m->norm_mlp[l], nullptr};
+        ST_HIP(hipMemcpyAsync(m->ws.ptab, m->ptab_host.data(), sizeof(PersistLayer) * (size_t)cfg->n_layers,
+                              hipMemcpyHostToDevice, m->stream));
+        m->pargs_host = persist_args(*m);
+        ST_HIP(hipMemcpyAsync(m->ws.pargs, &m->pargs_host, sizeof(PersistArgs), hipMemcpyHostToDevice, m->stream));
+        ST_HIP(persist_prepare(*m));
+        launch_persist_reset(*m);
+        if (int rc = check_launch("hand-over words")) return rc;
+        m->persist_on = true;
+    }
+    return ST_OK;
 }
 
 int st_model_create(const st_config *cfg, const st_weights *w, void *kv, size_t kv_bytes, void *workspace,
@@ -461,12 +521,22 @@ int st_decode_graph_state(const st_model *h, int32_t *graphs, int32_t *mode) {
     return ST_OK;
 }
 
+int st_decode_step_kind(const st_model *h, int32_t *kind) {
+    if (!h || !kind) return fail(ST_EINVAL, "model or kind is NULL");
+    *kind = reinterpret_cast<const Model *>(h)->persist_on ? 1 : 0;
+    return ST_OK;
+}
+
 int st_kv_truncate(st_model *h, int32_t new_len) {
     if (!h) return fail(ST_EINVAL, "model is NULL");
     Model *m = reinterpret_cast<Model *>(h);
     if (new_len < 0 || new_len > m->kv_len)
         return fail(ST_ERANGE, "new_len %d outside [0, %d]", new_len, m->kv_len);
     launch_set_state(*m, kPos, new_len);
+    if (m->persist_on) {  // also the way back from a step that gave up waiting: clears its error flag
+        launch_persist_reset(*m);
+        m->persist_launches = 0;
+    }
     if (int rc = check_launch("truncate")) return rc;
     m->kv_len = new_len;
     return ST_OK;
@@ -911,6 +981,7 @@ int st_batch_create(const st_config *cfg, const st_weights *w, int32_t n_seq, vo
         return rc;
     }
     b->base.graphs_off = true;  // the batched step is launched kernel by kernel
+    b->base.persist_on = false;
     b->n_seq = n_seq;
     b->kv_len.assign(n_seq, 0);
     b->seq_stride = kv_bytes_of(*cfg) / sizeof(bf16_t);

@@ -964,6 +964,10 @@ void launch_decode_layers(const Model &m, float *x, hipStream_t stream, int attn
 
 void launch_decode_step(const Model &m, const st_trigger_rule *rule, int32_t *out_seq_dev, hipStream_t stream,
                         int attn_blocks) {
+    if (m.persist_on && !m.timers) {
+        launch_decode_persist(m, rule, out_seq_dev, stream);
+        return;
+    }
     launch_decode_layers(m, m.ws.x, stream, attn_blocks);
     launch_head(m, m.ws.x, rule, 1, out_seq_dev, stream);
 }

@@ -17,6 +17,8 @@ enum StateSlot {
     kFed = 3,    // token fed by the step that produced kTok
     kStep = 4,   // running index into the output-token buffer of a chained run
     kCount = 5,  // scratch counter of set-up kernels (weights an fp16 copy could not hold)
+    kEpoch = 6,  // launches of the persistent decode step so far (its hand-over words carry epochs derived from it)
+    kPersistErr = 7,  // 1 once a wait inside the persistent decode step has timed out
     kStateInts = 16
 };
 

@@ -14,6 +14,45 @@ namespace st {
 
 typedef uint16_t bf16_t;
 
+// ---- the persistent single-kernel decode step (persist.hip) ----
+constexpr int kPersistThreads = 512;  // threads of its blocks (one block per compute unit)
+struct PersistLayer {                 // device table: weights of one layer
+    const bf16_t *wqkv, *bqkv, *wo, *wgu, *wdown, *norm_attn, *norm_mlp, *pad;
+};
+// Geometry of the step for a model shape on a device with nb compute units: regions of the hand-over words (offsets
+// in 8-byte words), attention split, LDS size.
+struct PersistPlan {
+    int nb;        // blocks
+    int s_cap;     // most key ranges per kv head
+    int dsl;       // output elements per work item of the range merge
+    int kmax;      // longest GEMV input (floats of LDS for it)
+    int lp_qkv, lp_o, lp_gu, lp_dn, lp_lm;  // log2 of the K parts a row is cut into, per stage
+    size_t lds_bytes;
+    int off_x, off_qkv, off_part, off_attn, off_x2, off_act, off_cand;
+    size_t ll_words;
+};
+struct PersistArgs {
+    const PersistLayer *layers;
+    const bf16_t *embed, *lm_head, *final_norm;
+    bf16_t *kc, *vc;
+    int32_t *state;
+    const float2 *rope;
+    unsigned long long *ll;
+    float *logits;
+    int L, h, nq, nkv, I, V, max_seq;
+    float eps;
+    int s_cap, dsl, kmax;
+    int lp_qkv, lp_o, lp_gu, lp_dn, lp_lm;
+    int off_x, off_qkv, off_part, off_attn, off_x2, off_act, off_cand;
+    int spin_limit;
+};
+
+struct PersistRule {  // what changes from launch to launch: trigger rule and output buffer
+    const uint32_t *kw, *delim;
+    int32_t *out_seq;
+    int window, rule_vocab;
+};
+
 struct Workspace {
     int32_t *state;        // kStateInts
     int32_t *counters;     // n_kv_heads arrival counters of the split attention
@@ -36,6 +75,9 @@ struct Workspace {
     float *logits;         // [vocab]
     float *amax_val;       // [kLmBlocks]
     int32_t *amax_idx;     // [kLmBlocks]
+    unsigned long long *ll;  // hand-over words of the persistent decode step (PersistPlan::ll_words; may be empty)
+    PersistLayer *ptab;      // [n_layers] its table of weight pointers
+    PersistArgs *pargs;      // its per-model arguments
     size_t bytes;
 };
 
@@ -99,6 +141,13 @@ struct Model {
     std::vector<const bf16_t *> wo16, wgu16, wdown16;
     bool f16_on;                     // the copies exist
     bool f16_pass;                   // the pass being enqueued uses them (default precision only)
+    // persistent single-kernel decode step: on when the shape fits (persist_plan) and ST_DECODE_PERSIST is not 0
+    bool persist_on;
+    PersistPlan persist;
+    int persist_spin_limit;          // polling rounds a wait may take before the step gives up
+    long persist_launches;           // since the hand-over words were last cleared
+    std::vector<PersistLayer> ptab_host;
+    PersistArgs pargs_host;
 };
 
 // Records the thread's error message (st_last_error) and returns `code`.
@@ -106,6 +155,8 @@ int fail(int code, const char *fmt, ...) __attribute__((format(printf, 2, 3)));
 
 // Carves the workspace; with base == nullptr only sizes it.
 void carve_workspace(const st_config &c, char *base, Workspace *ws);
+// Compute units the persistent decode step is planned for (those of the current device; 0 if it cannot be read).
+int persist_cu_count();
 
 // ---- launchers (decode.hip) ----
 void launch_init(const Model &m);
@@ -130,6 +181,15 @@ void launch_decode_layers(const Model &m, float *x, hipStream_t stream, int attn
 // LM head + arg-max over the residual row x_row (fp32[hidden]); advances state[kPos] by `advance`.
 void launch_head(const Model &m, const float *x_row, const st_trigger_rule *rule, int32_t advance,
                  int32_t *out_seq_dev, hipStream_t stream);
+
+// ---- launchers (persist.hip) ----
+// Plans the persistent step for a shape on n_cu compute units; false if the shape does not fit it.
+bool persist_plan(const st_config &c, int n_cu, PersistPlan *out);
+hipError_t persist_prepare(const Model &m);  // raises the kernel's LDS limit (once per model)
+void launch_persist_reset(const Model &m);   // clears the hand-over words, the launch counter and the error flag
+PersistArgs persist_args(const Model &m);    // the per-model arguments (to be copied to Workspace::pargs)
+// The whole single-token step as one kernel: same contract as launch_decode_step.
+void launch_decode_persist(const Model &m, const st_trigger_rule *rule, int32_t *out_seq_dev, hipStream_t stream);
 
 // ---- launchers (prefill.hip) ----
 // Feeds ws.tokens[0,n) at positions [pos0, pos0+n) through all layers; leaves the residual rows in ws.x.

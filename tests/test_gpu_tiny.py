@@ -282,8 +282,9 @@ def test_trigger_scan_bit_exact(window):
 
 
 def test_decode_steps_replay_captured_graphs():
-    """st_decode_graph_state: after a few decode steps the model reports captured step graphs in use (mode 0); the
-    count grows when the context crosses into the next attention-grid bucket."""
+    """st_decode_graph_state: after a few decode steps the model reports captured step graphs in use (mode 0); with one
+    kernel per stage the count grows when the context crosses into the next attention-grid bucket, the single-kernel
+    step needs one graph for every length."""
     cfg = synth.model_config("tiny_small", max_seq=256, max_chunk=64)
     w = synth.make_weights(cfg, 1)
     wg = dict(embed=w["embed"].cuda(), final_norm=w["final_norm"].cuda(), lm_head=w["lm_head"].cuda(),
@@ -298,5 +299,5 @@ def test_decode_steps_replay_captured_graphs():
     for t in range(4):
         g.decode_step(t + 5, want_logits=False)            # 64..67 keys: two ranges, another graph
     n2, mode = g.graph_state()
-    assert mode == 0 and n2 > n1
+    assert mode == 0 and (n2 == n1 if g.step_kind() == 1 else n2 > n1)
     g.close()

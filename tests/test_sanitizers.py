@@ -34,7 +34,8 @@ def test_library_host_code_under_address_and_ub_sanitizers(tmp_path):
     flags = ["--offload-arch=gfx950", "-O1", "-g", "-std=c++17", "-fsanitize=address,undefined", "-fno-gpu-sanitize",
              "-fno-sanitize-recover=all", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
     csrc = os.path.join(ROOT, "paper_2504_12329_amd", "csrc")
-    srcs = [os.path.join(csrc, f) for f in ("api.hip", "decode.hip", "prefill.hip", "trigger.hip")]
+    from paper_2504_12329_amd import build as lib_build
+    srcs = [os.path.join(csrc, f) for f in lib_build.SOURCES]
     srcs.append(os.path.join(SAN, "abi_driver.cpp"))
 
     def compile_one(src):
@@ -42,7 +43,7 @@ def test_library_host_code_under_address_and_ub_sanitizers(tmp_path):
         subprocess.run(["hipcc", *flags, "-x", "hip", "-c", src, "-o", obj], check=True, capture_output=True)
         return obj
 
-    with ThreadPoolExecutor(max_workers=5) as ex:
+    with ThreadPoolExecutor(max_workers=6) as ex:
         objs = list(ex.map(compile_one, srcs))
     exe = str(tmp_path / "abi_san")
     subprocess.run(["hipcc", "--offload-arch=gfx950", "-fsanitize=address,undefined", "-fno-gpu-sanitize", "-o", exe, *objs],
