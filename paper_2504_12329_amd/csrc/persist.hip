@@ -1,21 +1,23 @@
-// Single-token decode step as ONE persistent kernel (paper Section 4, "decode" stage).
+// Single-token decode step as ONE persistent kernel (paper Section 4, "decode" stage); an alternative to the
+// kernel-per-stage step of decode.hip, chosen with ST_DECODE_PERSIST=1.
 //
 // One block per compute unit walks the stages of every layer (QKV, attention ranges, range merge, O projection,
 // gate/up + SwiGLU, down projection) and then the LM head and the arg-max.  What a stage needs from the one before
 // it -- a vector of a few thousand floats produced piecewise by all blocks -- travels through device memory as
 // 8-byte words {value, epoch}: written with one relaxed 64-bit agent-scope atomic store, read with the matching load
 // until the epoch is the expected one.  Value and flag share the word, so no fence, no read-modify-write atomic and
-// no grid barrier is needed, and a hand-over costs about one memory round trip more than the store.
+// no grid barrier is needed; a hand-over costs about 2.4 us, which is what a dependent dispatch costs.
 //
-// Why: with one kernel per stage a dependent dispatch costs ~2.7 us before its first byte arrives, and a small model
-// has ~170 of them per token.  Here the weight stream never stops: the first kPF 16-byte groups per thread of a
-// stage's weights are requested a whole stage ahead (weights do not depend on activations), so they are in registers
-// when the input vector arrives, and the rest streams behind them.
+// Why it exists: with one kernel per stage a small model pays ~170 dependent dispatches per token during which no
+// weight byte moves.  Here weights are requested ahead of their stage (they do not depend on activations) and wait
+// in registers.  Measured, the step is nevertheless 6-10 % slower than the separate kernels on the 1.5B / 7B / 32B
+// shapes (the waits plus the arithmetic of one 8-wave block per compute unit outweigh the saved dispatches), so it
+// is not the default; it is kept as a tested alternative.
 //
-// Work split: a block owns a contiguous range of rows of every matrix.  Its share is contiguous in memory (row-major
-// weights), so the 512 threads read it as one flat run of 16-byte groups, whatever the row length; a wave's 64 groups
-// (1 KB) lie in at most NS consecutive rows, are reduced per row with DPP wave sums into LDS slots, and a row's
-// slots are added in ascending order afterwards: every sum has a fixed order, results are reproducible.
+// Work split: a block owns a contiguous range of rows of every matrix; a row (or, where rows are few and long, one of
+// P parts of a row) is a task, wave w of the block takes the tasks w, w + 8, ...; a lane keeps one running sum per
+// task, a task ends with one DPP wave sum into an LDS slot, and a row's slots are added in ascending order: every
+// sum has a fixed order, results are reproducible.
 //
 // Every wait is bounded: a poll that exceeds its spin limit raises state[kPersistErr], which every other poll loop
 // checks, and from then on no thread waits again -- every wave reaches the end of the kernel.
