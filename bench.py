@@ -86,10 +86,20 @@ def batched_decode(torch, B, synth, cost, cfg, w, n_seq=16, steps=24):
             "weight_GB_s": cost.weight_bytes(cfg) / dt / 1e9, "hbm_frac": cost.weight_bytes(cfg) / dt / HBM_PEAK}
 
 
-def single_decode(torch, B, synth, cost, cfg, w, kv0=4096, steps=40):
-    """Greedy decode rate of one sequence at a context of about kv0 tokens (chained, captured steps)."""
+def single_decode(torch, B, synth, cost, cfg, w, kv0=4096, steps=40, single_kernel=False):
+    """Greedy decode rate of one sequence at a context of about kv0 tokens (chained, captured steps); with
+    single_kernel the step is the persistent kernel the library offers as an alternative (ST_DECODE_PERSIST=1)."""
     cfg = dict(cfg, max_seq=kv0 + 128, max_chunk=min(cfg["max_chunk"], 4096))
-    model = B.Model(cfg, w)
+    old = os.environ.get("ST_DECODE_PERSIST")
+    os.environ["ST_DECODE_PERSIST"] = "1" if single_kernel else "0"
+    try:
+        model = B.Model(cfg, w)
+    finally:
+        if old is None:
+            del os.environ["ST_DECODE_PERSIST"]
+        else:
+            os.environ["ST_DECODE_PERSIST"] = old
+    assert model.step_kind() == (1 if single_kernel else 0)
     toks = torch.from_numpy(synth.make_prompt(kv0, cfg["vocab"], 5)).cuda()
     for lo in range(0, kv0, cfg["max_chunk"]):
         model.prefill_device(toks[lo:lo + cfg["max_chunk"]])
@@ -417,6 +427,9 @@ def main():
                    "prefill_operands": "fp16 MFMA on an fp16 copy of the bf16 projection weights (st_model_attach_f16)"},
         "decode_windows": windows,
         "whole_step_us_ungraphed": float(np.mean(st[8:])),
+        # the same step as one persistent kernel (opt-in alternative), beside the default at the same context
+        "single_kernel_step_kv4096": {"single_kernel": single_decode(torch, B, synth, cost, cfg, w, single_kernel=True),
+                                      "kernel_per_stage": single_decode(torch, B, synth, cost, cfg, w)},
         "algorithmic_bytes_per_token": {k: cost.decode_bytes(cfg, int(k)) for k in windows},
         "roofline": roofline,
     }

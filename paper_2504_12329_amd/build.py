@@ -28,5 +28,18 @@ def build(verbose=False):
     return LIB
 
 
+def build_stage_profiling():
+    """The library with stage timestamps compiled into the persistent decode kernel (-DST_PERSIST_PROF), as
+    _build/libst_prof.so; for persist_stages.py.  The other objects are those of the last build()."""
+    os.makedirs(OBJ, exist_ok=True)
+    obj = os.path.join(OBJ, "persist_prof.o")
+    subprocess.run(["hipcc", *FLAGS, "-DST_PERSIST_PROF", "-DST_PERSIST_PROF_IN", "-c", os.path.join(CSRC, "persist.hip"),
+                    "-o", obj], check=True)
+    others = [os.path.join(OBJ, src.replace(".hip", ".o")) for src in SOURCES if src != "persist.hip"]
+    lib = os.path.join(OBJ, "libst_prof.so")
+    subprocess.run(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib, *others, obj], check=True)
+    return lib
+
+
 if __name__ == "__main__":
     build(verbose=True)
