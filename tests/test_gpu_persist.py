@@ -130,3 +130,24 @@ def test_a_wait_that_runs_out_is_reported_and_truncate_recovers():
         g.truncate(40)
     print_case("steps that gave up:", failed, "of 8")
     g.close()
+
+
+def test_two_model_loop_on_the_single_kernel_step_matches_the_oracle_schedule():
+    """The whole takeover loop (st_generate: speculative model, trigger rule, target segments, catch-up passes) with
+    both tiny models on the single-kernel step: token sequence, sources and trigger positions equal the schedule
+    oracle's (same prompt seed, margin-checked, as the kernel-per-stage test of the tiny pair)."""
+    from oracle import schedule as S
+    cfg, gs, os_ = _persist_pair("tiny_small", 1, max_seq=256, max_chunk=64)
+    _, gl, ol = _persist_pair("tiny_large", 2, max_seq=256, max_chunk=64)
+    assert gs.step_kind() == 1 and gl.step_kind() == 1
+    prompt = synth.make_prompt(32, cfg["vocab"], 319)
+    a, b = S.GreedyModel(os_, keep_logits=True), S.GreedyModel(ol, keep_logits=True)
+    tr = S.speculative_thinking(a, b, prompt, 64, 8, S.window_rule(lambda t: t % 16 == 0))
+    margin = min((np.sort(lg)[-1] - np.sort(lg)[-2]) / np.abs(lg).max() for g in (a, b) for _, lg in g.logits)
+    assert margin >= 0.008 and len(tr.triggers) >= 2
+    rule = B.TriggerRule(cfg["vocab"], synth.modulo_bitmap(cfg["vocab"], 16))
+    print_case("tiny pair, single-kernel step: 64 outputs, segments of 8, triggers", tr.triggers)
+    out = B.st_generate(gs, gl, rule, prompt, 64, 8)
+    assert out["seq"].tolist() == tr.seq and out["src"].tolist() == tr.src
+    assert [s["large_prefill_hi"] - 1 for s in out["spans"]] == tr.triggers
+    gs.close(), gl.close()
