@@ -175,6 +175,17 @@ int st_decode_graph_state(const st_model *m, int32_t *graphs, int32_t *mode);
  * ST_EINVAL if m or kind is NULL. */
 int st_decode_step_kind(const st_model *m, int32_t *kind);
 
+/* Host-only: the plan of the single-kernel decode step for a model shape on a GPU with n_cu compute units (one block
+ * per unit), without touching a device.  On success *lds_bytes is the LDS one block asks for (at most 160 KB, and
+ * more than half of it so that a compute unit holds exactly one block), *handover_words the 8-byte {value, epoch}
+ * words st_query_sizes adds to the workspace, regions[7] the word offsets of the seven hand-over regions (x, q/k/v,
+ * range records, attention vector, x after attention, SwiGLU vector, arg-max candidates; ascending, non-overlapping)
+ * and parts[5] the K parts a weight row is cut into in the QKV, O, gate/up, down and LM-head stages (1, 2, 4 or 8).
+ * Any output pointer may be NULL.  ST_EINVAL if the shape does not fit the step (a row shorter than 256 elements, the
+ * LDS plan above 160 KB, fewer than 8 or more than 1024 compute units, fewer units than kv heads). */
+int st_decode_persist_plan(const st_config *cfg, int32_t n_cu, size_t *lds_bytes, size_t *handover_words,
+                           int32_t *regions, int32_t *parts);
+
 /* n chained greedy decode steps: feeds first_token (or the model's own last greedy token when
  * ST_TOKEN_CHAINED is set), then each step's arg-max, writing the n produced tokens to
  * out_tokens (host, or device with ST_OUT_DEVICE).  kv_len += n.  Nothing returns to the

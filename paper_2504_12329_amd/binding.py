@@ -17,7 +17,7 @@ ST_OK, ST_EINVAL, ST_ENOMEM, ST_ERANGE, ST_EHIP = 0, -1, -2, -3, -4
 ST_TOKENS_DEVICE, ST_OUT_DEVICE, ST_TOKEN_CHAINED, ST_PREFILL_TWO_TERM, ST_PREFILL_FAST = 1, 2, 4, 8, 16
 
 EXPORTS = ("st_query_sizes", "st_prefill_plan_check", "st_model_create", "st_model_destroy", "st_kv_len", "st_kv_truncate", "st_prefill",
-           "st_query_f16_bytes", "st_model_attach_f16", "st_batch_attach_f16", "st_decode_step", "st_decode_graph_state", "st_decode_step_kind", "st_decode_step_timed", "st_decode_greedy", "st_trigger_scan", "st_trigger_scan_static", "st_handoff", "st_generate",
+           "st_query_f16_bytes", "st_model_attach_f16", "st_batch_attach_f16", "st_decode_step", "st_decode_graph_state", "st_decode_step_kind", "st_decode_persist_plan", "st_decode_step_timed", "st_decode_greedy", "st_trigger_scan", "st_trigger_scan_static", "st_handoff", "st_generate",
            "st_generate_policy", "st_batch_query_sizes", "st_batch_create", "st_batch_destroy", "st_batch_kv_len",
            "st_batch_truncate", "st_batch_prefill", "st_batch_prefill_many", "st_batch_decode_step", "st_generate_batch",
            "st_last_error")
@@ -86,6 +86,8 @@ def lib():
         L.st_decode_step_timed.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_double)]
         L.st_decode_graph_state.argtypes = [C.c_void_p, i32p, i32p]
         L.st_decode_step_kind.argtypes = [C.c_void_p, i32p]
+        L.st_decode_persist_plan.argtypes = [C.POINTER(st_config), C.c_int32, C.POINTER(C.c_size_t),
+                                             C.POINTER(C.c_size_t), i32p, i32p]
         L.st_query_f16_bytes.argtypes = [C.POINTER(st_config), C.POINTER(C.c_size_t)]
         L.st_model_attach_f16.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t]
         L.st_batch_attach_f16.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t]
@@ -140,6 +142,14 @@ def st_prefill_plan_check(cfg, rows):
     nl, nb = C.c_int32(), C.c_int32()
     _check(lib().st_prefill_plan_check(C.byref(make_config(cfg)), int(rows), C.byref(nl), C.byref(nb)))
     return nl.value, nb.value
+
+
+def st_decode_persist_plan(cfg, n_cu):
+    """Host-only plan of the single-kernel decode step: dict(lds_bytes, handover_words, regions[7], parts[5])."""
+    lds, words = C.c_size_t(), C.c_size_t()
+    regions, parts = (C.c_int32 * 7)(), (C.c_int32 * 5)()
+    _check(lib().st_decode_persist_plan(C.byref(make_config(cfg)), int(n_cu), C.byref(lds), C.byref(words), regions, parts))
+    return dict(lds_bytes=lds.value, handover_words=words.value, regions=list(regions), parts=list(parts))
 
 
 def _np_ptr(a):

@@ -527,6 +527,25 @@ int st_decode_step_kind(const st_model *h, int32_t *kind) {
     return ST_OK;
 }
 
+int st_decode_persist_plan(const st_config *cfg, int32_t n_cu, size_t *lds_bytes, size_t *handover_words,
+                           int32_t *regions, int32_t *parts) {
+    if (int rc = validate_config(cfg)) return rc;
+    PersistPlan p;
+    if (!persist_plan(*cfg, n_cu, &p))
+        return fail(ST_EINVAL, "the shape does not fit the single-kernel decode step on %d compute units", n_cu);
+    if (lds_bytes) *lds_bytes = p.lds_bytes;
+    if (handover_words) *handover_words = p.ll_words;
+    if (regions) {
+        const int r[7] = {p.off_x, p.off_qkv, p.off_part, p.off_attn, p.off_x2, p.off_act, p.off_cand};
+        for (int i = 0; i < 7; ++i) regions[i] = r[i];
+    }
+    if (parts) {
+        const int lp[5] = {p.lp_qkv, p.lp_o, p.lp_gu, p.lp_dn, p.lp_lm};
+        for (int i = 0; i < 5; ++i) parts[i] = 1 << lp[i];
+    }
+    return ST_OK;
+}
+
 int st_kv_truncate(st_model *h, int32_t new_len) {
     if (!h) return fail(ST_EINVAL, "model is NULL");
     Model *m = reinterpret_cast<Model *>(h);

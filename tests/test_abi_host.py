@@ -158,3 +158,31 @@ def test_bench_refuses_more_than_one_gpu():
                        timeout=120)
     assert r.returncode != 0
     assert "one GPU" in r.stderr
+
+
+def test_single_kernel_decode_plan_on_the_host(L):
+    """st_decode_persist_plan for every model shape on 256 compute units: the block's LDS request is above half and
+    within all of a compute unit's 160 KB, the seven hand-over regions ascend without overlap and hold what their
+    stage writes, rows are cut into 1, 2, 4 or 8 parts (few long rows into several: the down projection of the 1.5B
+    shape has 6 rows of 8960 per block), and shapes the step cannot take are refused."""
+    from paper_2504_12329_amd import synth
+    for name in synth.SHAPES:
+        cfg = synth.model_config(name, max_seq=4096, max_chunk=512)
+        p = B.st_decode_persist_plan(cfg, 256)
+        assert 80 * 1024 < p["lds_bytes"] <= 160 * 1024, (name, p)
+        r = p["regions"] + [p["handover_words"]]
+        h, d, nq, nkv = cfg["hidden"], cfg["head_dim"], cfg["n_q_heads"], cfg["n_kv_heads"]
+        ranges = min(128, 256 // nkv)
+        need = [h, (nq + 2 * nkv) * d, nq * ranges * (d + 2), nq * d, h, cfg["intermediate"], 2 * 256]
+        for i in range(7):
+            assert r[i + 1] - r[i] >= need[i], (name, i, r, need)
+        assert all(q in (1, 2, 4, 8) for q in p["parts"]), p
+    p = B.st_decode_persist_plan(synth.model_config("qwen1p5b", max_seq=4096, max_chunk=512), 256)
+    assert p["parts"][0] == 1 and p["parts"][3] > 1        # QKV: 8 rows of 1536; down: 6 rows of 8960
+    small = synth.model_config("tiny_small", max_seq=256, max_chunk=64)
+    with pytest.raises(B.StError):
+        B.st_decode_persist_plan(dict(small, hidden=64, n_q_heads=1, n_kv_heads=1), 256)   # rows of 64 elements
+    with pytest.raises(B.StError):
+        B.st_decode_persist_plan(small, 4)                 # fewer than 8 compute units
+    with pytest.raises(B.StError):
+        B.st_decode_persist_plan(dict(small, n_q_heads=16, n_kv_heads=16, hidden=1024), 8)  # 16 kv heads on 8 units
