@@ -151,3 +151,31 @@ def test_two_model_loop_on_the_single_kernel_step_matches_the_oracle_schedule():
     assert out["seq"].tolist() == tr.seq and out["src"].tolist() == tr.src
     assert [s["large_prefill_hi"] - 1 for s in out["spans"]] == tr.triggers
     gs.close(), gl.close()
+
+
+def test_full_depth_1p5b_both_step_kinds_agree():
+    """All 28 layers of the 1.5B shape at 600 .. 616 keys: the single-kernel step against the kernel-per-stage step
+    (each pinned to the oracle elsewhere: the whole-model test of the default step, the few-layer test above), logits
+    within 1e-3 of each other at every one of 16 chained steps' starting points and the same greedy tokens."""
+    name, kv0 = "qwen1p5b", 600
+    cfg = synth.model_config(name, max_seq=kv0 + 32, max_chunk=kv0)
+    w = synth.make_weights(cfg, 4, device="cuda")
+    g1 = _with_env("ST_DECODE_PERSIST", "1", lambda: B.Model(cfg, w))
+    g0 = B.Model(cfg, w)
+    assert g1.step_kind() == 1 and g0.step_kind() == 0
+    prompt = synth.make_prompt(kv0, cfg["vocab"], 21)
+    print_case("1.5B shape, 28 layers:", kv0, "prompt tokens, 16 steps on both step kinds")
+    _, t1 = g1.prefill(prompt, want_logits=False)
+    _, t0 = g0.prefill(prompt, want_logits=False)
+    assert t1 == t0
+    tok, apart = t0, 0.0
+    for _ in range(16):
+        lg1, n1 = g1.decode_step(tok)
+        lg0, n0 = g0.decode_step(tok)
+        apart = max(apart, rel_err(lg1, lg0))
+        margin = (np.sort(lg0)[-1] - np.sort(lg0)[-2]) / np.abs(lg0).max()
+        assert n1 == n0 or margin < 1e-3, (n1, n0, margin)
+        tok = n0
+    print_case("largest distance between the two step kinds", apart)
+    assert apart <= 1e-3
+    g1.close(), g0.close()
