@@ -179,3 +179,28 @@ def test_full_depth_1p5b_both_step_kinds_agree():
     print_case("largest distance between the two step kinds", apart)
     assert apart <= 1e-3
     g1.close(), g0.close()
+
+
+@pytest.mark.parametrize("d,nq,nkv", [(64, 4, 4), (128, 3, 1), (64, 8, 2), (128, 8, 1), (128, 16, 16)])
+def test_every_head_grouping_on_both_step_kinds(d, nq, nkv):
+    """Query heads per kv head G = 1, 3, 4, 8 (and 16 kv heads of one query head each) at both head sizes, on a narrow
+    two-layer model (hidden 512, intermediate 1032 -- rows of 129 sixteen-byte groups, not a multiple of a wave --
+    vocabulary 2000): 70-token prompt, then 6 teacher-forced steps across the 64-key range boundary, both step kinds
+    against the oracle."""
+    over = dict(head_dim=d, n_q_heads=nq, n_kv_heads=nkv, hidden=512, intermediate=1032, vocab=2000)
+    cfg, g1, o = _persist_pair("tiny_small", 9, max_seq=128, max_chunk=80, **over)
+    _, g0, _ = make_pair("tiny_small", 9, max_seq=128, max_chunk=80, **over)
+    assert g1.step_kind() == 1 and g0.step_kind() == 0
+    prompt = synth.make_prompt(60, cfg["vocab"], 17)
+    print_case("head_dim", d, "q heads", nq, "kv heads", nkv, ": 60-token prompt, 8 steps")
+    tok = O.argmax(o.feed(prompt))
+    g1.prefill(prompt, want_logits=False)
+    g0.prefill(prompt, want_logits=False)
+    for _ in range(8):
+        lg_o = o.feed([tok])
+        lg1, t1 = g1.decode_step(tok)
+        lg0, t0 = g0.decode_step(tok)
+        assert t1 == O.argmax(lg1) and t0 == O.argmax(lg0)
+        assert rel_err(lg1, lg_o) <= LOGIT_TOL and rel_err(lg0, lg_o) <= LOGIT_TOL and rel_err(lg1, lg0) <= 1e-4
+        tok = O.argmax(lg_o)
+    g1.close(), g0.close()
